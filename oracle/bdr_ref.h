@@ -1,0 +1,126 @@
+/*
+ * bdr_ref.h -- CPU oracle for the Block Data Representation (BDR) quantizer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, scalar implementation of
+ * what the two-level shared-microexponent quantizer computes, written from the
+ * paper's definitions (arXiv 2302.08007).  It exists so that the GPU library
+ * can be checked against something that can be verified by eye.  It shares no
+ * code with the GPU library and must never be called from the product path.
+ *
+ * Every pointer here is a HOST pointer.  Nothing is allocated on behalf of the
+ * caller except short-lived scratch that is freed before return.
+ *
+ * Passages followed (all from the paper):
+ *   - format tuple (k1, k2, d1, d2, m) and bits/element:
+ *       Sec. III, "Block Data Representations"
+ *   - MX9 / MX6 / MX4 instances: Table II
+ *   - shared exponent E, m-bit rounded magnitude, per-element error bound,
+ *     sub-block shift tau <= beta = 2^d2 - 1:
+ *       Sec. IX (proof of Theorem 1), Eq. "max_exp", "max_exp_round",
+ *       "q_error_max", "q_error_max-1" and the paragraph after "q_error_all"
+ *   - QSNR: Sec. IV-A, Eq. 3
+ *   - quantize along the reduction axis; transpose before quantizing:
+ *       Sec. V, "Training"
+ *
+ * Readings taken where the paper is silent are stated beside the code that
+ * implements them in bdr_ref.c.
+ */
+#ifndef BDR_REF_H
+#define BDR_REF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* A BDR format, Sec. III: block size k1, sub-block size k2, d1 bits of shared
+ * exponent per block, d2 bits of microexponent per sub-block, m magnitude bits
+ * (plus one sign bit) per element, and the rounding rule for the magnitude. */
+typedef struct {
+    int32_t k1, d1, k2, d2, m, rounding;
+} bdr_ref_format;
+
+enum { BDR_REF_RNE = 0, BDR_REF_RNA = 1, BDR_REF_RTZ = 2 };
+enum { BDR_REF_F32 = 0, BDR_REF_BF16 = 1 };
+enum { BDR_REF_AXIS_ROW = 0, BDR_REF_AXIS_COL = 1 };
+enum {
+    BDR_REF_OK = 0,
+    BDR_REF_ERR_NULL = 1,
+    BDR_REF_ERR_FORMAT = 2,
+    BDR_REF_ERR_SHAPE = 3,
+    BDR_REF_ERR_DTYPE = 5
+};
+
+/* 0 when the tuple is a format this oracle implements:
+ * k1, k2 powers of two, k2 divides k1, 1 <= k1 <= 4096, d1 == 8,
+ * 0 <= d2 <= 3, 1 <= m <= 8, rounding in {RNE, RNA, RTZ}. */
+int bdr_ref_format_validate(const bdr_ref_format *f);
+
+/* Bits per element of the format, Sec. III: (m+1) + d1/k1 + d2/k2. */
+double bdr_ref_bits_per_element(const bdr_ref_format *f);
+
+/* Byte sizes of the three packed planes for a [rows x cols] tensor quantized
+ * along `axis`.  A row (of the transposed tensor when axis is COL) whose
+ * length is not a multiple of k1 is padded with zeros to the next multiple. */
+int bdr_ref_packed_sizes(const bdr_ref_format *f, int64_t rows, int64_t cols, int axis,
+                         size_t *codes_bytes, size_t *sexp_bytes, size_t *mexp_bytes);
+
+/* Quantize one block of n <= k1 elements given as FP32 bit patterns.
+ * Outputs are unpacked: the shared exponent code (biased, 8 bit), one shift
+ * tau per sub-block (k1/k2 of them) and one (m+1)-bit sign|magnitude code per
+ * element (k1 of them; positions >= n are the codes of +0). */
+void bdr_ref_quantize_block(const bdr_ref_format *f, const uint32_t *xbits, int n,
+                            uint8_t *sexp, uint8_t *tau, uint16_t *code);
+
+/* Value of one code: (-1)^s * M * 2^(sexp - 127 - tau - (m-1)), as a double
+ * (exact).  The caller narrows it. */
+double bdr_ref_decode(const bdr_ref_format *f, uint8_t sexp, uint8_t tau, uint16_t code);
+
+/* Quantize x ([rows x cols], leading dimension ld elements, dtype F32 or BF16)
+ * into the three planes (sizes from bdr_ref_packed_sizes; mexp may be NULL when
+ * d2 == 0).  AXIS_COL gives exactly what AXIS_ROW gives on the transpose. */
+int bdr_ref_quantize(const bdr_ref_format *f, const void *x, int dtype, int64_t rows,
+                     int64_t cols, int64_t ld, int axis, uint8_t *codes, uint8_t *sexp,
+                     uint8_t *mexp);
+
+/* Inverse of the packing: rebuild y ([rows x cols], leading dimension ld) from
+ * the planes.  BF16 output requires m + (2^d2 - 1) <= 8, for which it is exact. */
+int bdr_ref_dequantize(const bdr_ref_format *f, const uint8_t *codes, const uint8_t *sexp,
+                       const uint8_t *mexp, int64_t rows, int64_t cols, int axis, void *y,
+                       int dtype, int64_t ld);
+
+/* y = dequantize(quantize(x)); same dtype and leading dimension on both sides. */
+int bdr_ref_quantize_dequantize(const bdr_ref_format *f, const void *x, void *y, int dtype,
+                                int64_t rows, int64_t cols, int64_t ld, int axis);
+
+/* Eq. 3 over the whole tensor, one value per format, quantizing along rows.
+ * sums (n_fmts + 1 doubles) receives S_err[f] = sum (Q(x)-x)^2 per format and
+ * then S_sig = sum x^2; qsnr_db[f] = 10 log10(S_sig / S_err[f]) (+inf when
+ * S_err is 0). */
+int bdr_ref_qsnr_sweep(const bdr_ref_format *fmts, int32_t n_fmts, const void *x, int dtype,
+                       int64_t rows, int64_t cols, int64_t ld, double *qsnr_db, double *sums);
+
+/* C[i,j] = sum_k Ahat[i,k] * Bhat[j,k] in fp64, rounded once to fp32, where
+ * Ahat ([M x K]) and Bhat ([N x K]) are the dequantized operands, both packed
+ * row-wise (blocks along K).  Evaluates only the n_samples entries
+ * (idx_i[s], idx_j[s]); out[s] gets the value and, when absdot is not NULL,
+ * absdot[s] = sum_k |Ahat[i,k] * Bhat[j,k]|. */
+int bdr_ref_mx_gemm_sampled(const bdr_ref_format *fa, const bdr_ref_format *fb,
+                            const uint8_t *a_codes, const uint8_t *a_sexp, const uint8_t *a_mexp,
+                            const uint8_t *b_codes, const uint8_t *b_sexp, const uint8_t *b_mexp,
+                            int64_t M, int64_t N, int64_t K, int64_t n_samples,
+                            const int64_t *idx_i, const int64_t *idx_j, float *out,
+                            double *absdot);
+
+/* The full [M x N] product of the same definition (row-major, ldc elements). */
+int bdr_ref_mx_gemm(const bdr_ref_format *fa, const bdr_ref_format *fb, const uint8_t *a_codes,
+                    const uint8_t *a_sexp, const uint8_t *a_mexp, const uint8_t *b_codes,
+                    const uint8_t *b_sexp, const uint8_t *b_mexp, int64_t M, int64_t N, int64_t K,
+                    float *C, int64_t ldc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BDR_REF_H */

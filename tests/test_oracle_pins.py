@@ -1,0 +1,501 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something other than
+itself -- hand-worked examples, the paper's closed forms, invariants its definitions fix,
+special cases that reduce to a textbook routine, and brute-force enumeration of every
+representable value on small blocks.  No GPU is involved.
+"""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as O
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+# --------------------------------------------------------------------------- helpers
+
+def f32(x):
+    return np.asarray(x, dtype=np.float32)
+
+
+def true_exponent(v):
+    """floor(log2|v|) of a finite float via frexp, with subnormals and zero at -126 and the
+    top binade capped -- the exponent an FP32 value 'privately' carries (Sec. IX, Eq. max_exp)."""
+    v = abs(float(v))
+    if v < 2.0 ** -126:
+        return -126
+    return min(math.frexp(v)[1] - 1, 127)
+
+
+def brute_block(x, f):
+    """Quantize one block by enumeration: every representable magnitude M * 2^q, M in
+    [0, 2^m), is listed and the nearest one to |x_i| picked in exact rational arithmetic."""
+    k1, k2, m = f.k1, f.k2, f.m
+    beta = (1 << f.d2) - 1
+    xs = [float(v) for v in x] + [0.0] * (k1 - len(x))
+    E = max(true_exponent(v) for v in xs)
+    taus, codes, vals = [], [], []
+    for j in range(k1 // k2):
+        sub = xs[j * k2:(j + 1) * k2]
+        tau = min(beta, E - max(true_exponent(v) for v in sub))
+        taus.append(tau)
+        step = Fraction(2) ** (E - tau - (m - 1))
+        cands = [M * step for M in range(1 << m)]
+        for v in sub:
+            t = Fraction(abs(v))
+            if f.rounding == O.RTZ:
+                M = max(i for i, c in enumerate(cands) if c <= t)
+            else:
+                best = min(abs(c - t) for c in cands)
+                near = [i for i, c in enumerate(cands) if abs(c - t) == best]
+                if len(near) == 1:
+                    M = near[0]
+                elif f.rounding == O.RNE:
+                    M = [i for i in near if i % 2 == 0][0]
+                else:
+                    M = max(near)
+            sign = 1 if math.copysign(1.0, v) < 0 else 0
+            codes.append((sign << m) | M)
+            vals.append((-1.0 if sign else 1.0) * float(cands[M]))
+    return E + 127, taus, codes, vals
+
+
+def unpack_stream(buf, width, count):
+    """Independent reader of a little-endian bit stream: numpy unpackbits, then weights."""
+    if width == 0:
+        return np.zeros(count, np.int64)
+    bits = np.unpackbits(np.asarray(buf, np.uint8), bitorder="little")[:width * count]
+    return bits.reshape(count, width).astype(np.int64) @ (1 << np.arange(width, dtype=np.int64))
+
+
+def rand_wide(rng, n, spread=6.0):
+    """Values whose exponents spread over many binades, with exact zeros and signs mixed in."""
+    x = rng.standard_normal(n) * np.exp2(rng.integers(-int(spread), int(spread) + 1, n))
+    x[rng.random(n) < 0.05] = 0.0
+    x[rng.random(n) < 0.02] = -0.0
+    return f32(x)
+
+
+SWEEP = [O.fmt(k1, k1 if k2 == 0 else k2, d2, m)
+         for k1 in (8, 16, 32, 64) for k2 in (1, 2, 4, 0) for d2 in (0, 1) for m in (2, 4)]
+SMALL = [O.fmt(k1, k2, d2, m, rounding=r)
+         for k1 in (1, 2, 4, 8) for k2 in (1, 2, 4, 8) if k2 <= k1
+         for d2 in (0, 1, 2) for m in (1, 2, 3) for r in (O.RNE, O.RNA, O.RTZ)]
+
+
+# ------------------------------------------------------------------ format and sizes
+
+def test_table2_bits_per_element():
+    # Table II, last row: 9, 6 and 4 average bits per element
+    assert O.bits_per_element(O.MX9) == 9.0
+    assert O.bits_per_element(O.MX6) == 6.0
+    assert O.bits_per_element(O.MX4) == 4.0
+
+
+@pytest.mark.parametrize("f", SWEEP + [O.MX9, O.MX6, O.MX4], ids=repr)
+def test_packed_bytes_equal_bits_formula(f):
+    # Sec. III: (m+1) + d1/k1 + d2/k2 bits per element -- the three planes together hold
+    # exactly that many bits when the planes are whole bytes
+    rows, cols = 6, 512
+    nc, ns, nm = O.packed_sizes(f, rows, cols)
+    n = rows * cols
+    assert nc * 8 == n * (f.m + 1)
+    assert ns * 8 == n * 8 // f.k1
+    assert nm * 8 == n * f.d2 // f.k2
+    assert (nc + ns + nm) * 8 == n * ((f.m + 1) + Fraction(8, f.k1) + Fraction(f.d2, f.k2))
+
+
+def test_validate_rejects_bad_tuples():
+    assert O.validate(O.MX6) == O.OK
+    for bad in (O.fmt(12, 2, 1, 4), O.fmt(16, 3, 1, 4), O.fmt(16, 32, 1, 4), O.fmt(16, 2, 4, 4),
+                O.fmt(16, 2, -1, 4), O.fmt(16, 2, 1, 0), O.fmt(16, 2, 1, 9),
+                O.fmt(16, 2, 1, 4, d1=5), O.fmt(16, 2, 1, 4, rounding=7), O.fmt(0, 1, 0, 4)):
+        assert O.validate(bad) == O.ERR_FORMAT
+
+
+# --------------------------------------------------------------- hand-worked examples
+
+def _golden_lines():
+    with open(os.path.join(HERE, "golden", "worked_examples.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                yield line
+
+
+@pytest.mark.parametrize("line", list(_golden_lines()))
+def test_worked_examples(line):
+    head, xs, se, taus, codes, xhat = [p.split() for p in line.split("|")]
+    k1, k2, d2, m, rnd = map(int, head)
+    f = O.fmt(k1, k2, d2, m, rounding=rnd)
+    x = f32([float(v) for v in xs])
+    got_se, got_tau, got_code = O.quantize_block(f, x)
+    assert got_se == int(se[0])
+    assert got_tau.tolist() == [int(t) for t in taus]
+    assert got_code.tolist() == [int(c) for c in codes]
+    want = f32([float(v) for v in xhat])
+    got = f32([O.decode(f, got_se, got_tau[i // k2], got_code[i]) for i in range(k1)])
+    assert got.tobytes() == want.tobytes()  # bitwise, so the sign of zero counts
+    # and the whole-tensor path (pack, then unpack) says the same
+    y = O.quantize_dequantize(f, x.reshape(1, -1))
+    assert y.tobytes() == want.tobytes()
+
+
+# ------------------------------------------------------ brute force on small blocks
+
+@pytest.mark.parametrize("f", SMALL, ids=repr)
+def test_brute_force_small_blocks(f):
+    rng = np.random.default_rng(1234 + f.k1 * 97 + f.k2 * 13 + f.d2 * 7 + f.m)
+    for trial in range(40):
+        x = rand_wide(rng, f.k1, spread=4)
+        if trial % 5 == 0:  # plant exact ties and values just beside them
+            E = max(true_exponent(v) for v in x)
+            step = 2.0 ** (E - (f.m - 1))
+            x[rng.integers(f.k1)] = np.float32((rng.integers(0, 1 << f.m) + 0.5) * step / 2)
+        se, tau, code = O.quantize_block(f, x)
+        bse, btau, bcode, bval = brute_block(x, f)
+        assert se == bse, x
+        assert tau.tolist() == btau, x
+        assert code.tolist() == bcode, x
+        got = [O.decode(f, se, tau[i // f.k2], code[i]) for i in range(f.k1)]
+        assert f32(got).tobytes() == f32(bval).tobytes()
+
+
+@pytest.mark.parametrize("f", [O.MX9, O.MX6, O.MX4, O.fmt(64, 4, 1, 4), O.fmt(32, 1, 1, 2),
+                               O.fmt(16, 8, 2, 5), O.fmt(8, 2, 3, 8)], ids=repr)
+def test_brute_force_real_formats(f):
+    rng = np.random.default_rng(99 + f.m)
+    for _ in range(25):
+        x = rand_wide(rng, f.k1, spread=5)
+        se, tau, code = O.quantize_block(f, x)
+        bse, btau, bcode, _ = brute_block(x, f)
+        assert (se, tau.tolist(), code.tolist()) == (bse, btau, bcode)
+
+
+def test_short_block_is_zero_padded():
+    # end of Sec. IX: a vector shorter than k1 behaves as a block of that size
+    f = O.MX6
+    x = f32([0.3, -1.7, 0.02])
+    se, tau, code = O.quantize_block(f, x)
+    se2, tau2, code2 = O.quantize_block(f, np.concatenate([x, np.zeros(13, np.float32)]))
+    assert (se, tau.tolist(), code.tolist()) == (se2, tau2.tolist(), code2.tolist())
+    y = O.quantize_dequantize(f, x.reshape(1, 3))
+    assert y.shape == (1, 3)
+    assert y.tobytes() == f32(brute_block(x, f)[3][:3]).tobytes()
+
+
+# ------------------------------------------------------- properties of each step
+
+def test_shared_exponent_is_floor_log2_of_block_max():
+    rng = np.random.default_rng(5)
+    f = O.MX9
+    for _ in range(200):
+        x = rand_wide(rng, 16, spread=20)
+        if not np.any(x):
+            continue
+        se, _, _ = O.quantize_block(f, x)
+        assert se - 127 == max(math.floor(math.log2(abs(float(v)))) for v in x if v != 0)
+
+
+def test_tau_property_of_the_proof():
+    # Sec. IX: a sub-block with shift tau < beta holds an element whose exponent is exactly
+    # E - tau; in a sub-block with shift beta every exponent is at most E - beta
+    rng = np.random.default_rng(6)
+    for f in (O.MX6, O.fmt(32, 4, 2, 3), O.fmt(16, 1, 3, 2)):
+        beta = (1 << f.d2) - 1
+        for _ in range(100):
+            x = rand_wide(rng, f.k1, spread=4)
+            se, tau, _ = O.quantize_block(f, x)
+            E = se - 127
+            for j, t in enumerate(tau.tolist()):
+                exps = [true_exponent(v) for v in x[j * f.k2:(j + 1) * f.k2]]
+                if t < beta:
+                    assert max(exps) == E - t
+                else:
+                    assert max(exps) <= E - beta
+
+
+@pytest.mark.parametrize("f", [O.MX9, O.MX6, O.MX4, O.fmt(64, 64, 0, 4), O.fmt(8, 1, 2, 3)], ids=repr)
+def test_per_element_error_bound(f):
+    # Sec. IX, Eq. "q_error_max-1": |Q(x) - x| <= 2^(E - tau - m) -- for every element that was
+    # not held at the top code (the bound's premise is that rounding stays inside m bits)
+    rng = np.random.default_rng(7)
+    top = (1 << f.m) - 1
+    for _ in range(100):
+        x = rand_wide(rng, f.k1, spread=3)
+        se, tau, code = O.quantize_block(f, x)
+        for i in range(f.k1):
+            t = int(tau[i // f.k2])
+            xh = O.decode(f, se, t, code[i])
+            err = abs(Fraction(xh) - Fraction(float(x[i])))
+            held = (code[i] & top) == top and abs(float(x[i])) > abs(xh)
+            if not held:
+                assert err <= Fraction(2) ** (se - 127 - t - f.m)
+            else:
+                assert err <= Fraction(2) ** (se - 127 - t - f.m + 1)
+
+
+@pytest.mark.parametrize("f", [O.MX9, O.MX6, O.MX4, O.fmt(8, 4, 2, 3, rounding=O.RNA),
+                               O.fmt(32, 32, 0, 5, rounding=O.RTZ)], ids=repr)
+def test_idempotent_symmetric_scale_equivariant(f):
+    rng = np.random.default_rng(8)
+    x = rand_wide(rng, 64 * 128, spread=6).reshape(64, 128)
+    c, s, mx = O.quantize(f, x)
+    y = O.dequantize(f, c, s, mx, *x.shape)
+    # representable inputs are unchanged, codes included: Q(Q(x)) = Q(x)
+    c2, s2, m2 = O.quantize(f, y)
+    assert np.array_equal(c, c2) and np.array_equal(s, s2) and np.array_equal(mx, m2)
+    assert O.dequantize(f, c2, s2, m2, *x.shape).tobytes() == y.tobytes()
+    # Q(-x) = -Q(x), bit for bit (sign of zero included)
+    yn = O.quantize_dequantize(f, -x)
+    assert yn.tobytes() == (-y).tobytes()
+    # end of Sec. IX: Q(2^j x) = 2^j Q(x); exponent codes move by j, the rest stays
+    for j in (-40, -3, 5, 60):
+        xs = f32(np.ldexp(x, j))
+        cj, sj, mj = O.quantize(f, xs)
+        assert np.array_equal(cj, c) and np.array_equal(mj, mx)
+        assert np.array_equal(sj.astype(int), s.astype(int) + j)
+        assert O.dequantize(f, cj, sj, mj, *x.shape).tobytes() == f32(np.ldexp(y, j)).tobytes()
+
+
+def test_every_code_tuple_is_a_fixed_point():
+    # decode every (exponent, tau, code) of a tiny format; whatever the values are, quantizing
+    # them gives the same values back
+    # (exponent code 1 is left out: values below 2^-126 all carry the exponent -126, so a shift
+    # under the lowest exponent is a tuple the quantizer never emits)
+    f = O.fmt(4, 2, 1, 2)
+    seen = 0
+    for se in (2, 3, 126, 127, 200, 254):
+        for taus in itertools.product((0, 1), repeat=2):
+            for codes in itertools.product(range(8), repeat=4):
+                v = f32([O.decode(f, se, taus[i // 2], codes[i]) for i in range(4)])
+                y = O.quantize_dequantize(f, v.reshape(1, 4))
+                assert y.tobytes() == v.tobytes()
+                seen += 1
+    assert seen == 6 * 4 * 4096
+
+
+def test_bfp_reduction_against_textbook():
+    # d2 = 0 is block floating point (Fig. 5 caption): shared exponent from frexp of the
+    # block maximum, integers from rint, clip, ldexp back
+    rng = np.random.default_rng(9)
+    x = f32(rng.standard_normal((32, 256)) * np.exp2(rng.integers(-8, 8, (32, 1))))
+    for k1, m in ((16, 7), (8, 4), (64, 2), (32, 3)):
+        xb = x.reshape(-1, k1).astype(np.float64)
+        _, e = np.frexp(np.abs(xb).max(axis=1, keepdims=True))
+        step = np.ldexp(1.0, (e - 1) - (m - 1))
+        want = f32(np.sign(xb) * np.minimum(np.rint(np.abs(xb) / step), 2 ** m - 1) * step)
+        for k2 in (1, 2, k1):  # with d2 = 0 the sub-block size cannot matter
+            got = O.quantize_dequantize(O.fmt(k1, k2, 0, m), x)
+            assert np.array_equal(got.reshape(-1, k1), want)
+        # one sub-block per block has tau = 0 whatever d2 says
+        got = O.quantize_dequantize(O.fmt(k1, k1, 1, m), x)
+        assert np.array_equal(got.reshape(-1, k1), want)
+
+
+def test_columnwise_is_rowwise_on_the_transpose():
+    # Sec. V: quantization follows the reduction axis; transpose first, then quantize
+    rng = np.random.default_rng(10)
+    x = rand_wide(rng, 48 * 40, spread=3).reshape(48, 40)
+    xt = np.ascontiguousarray(x.T)
+    for f in (O.MX9, O.MX4, O.fmt(8, 4, 2, 3)):
+        pc = O.quantize(f, x, axis=O.AXIS_COL)
+        pr = O.quantize(f, xt, axis=O.AXIS_ROW)
+        for a, b in zip(pc, pr):
+            assert np.array_equal(a, b)
+        yc = O.dequantize(f, *pc, 48, 40, axis=O.AXIS_COL)
+        yr = O.dequantize(f, *pr, 40, 48, axis=O.AXIS_ROW)
+        assert yc.tobytes() == np.ascontiguousarray(yr.T).tobytes()
+        assert O.quantize_dequantize(f, x, axis=O.AXIS_COL).tobytes() == yc.tobytes()
+    # and it is not the same as quantizing along rows
+    assert not np.array_equal(O.quantize_dequantize(O.MX4, x, axis=O.AXIS_COL),
+                              O.quantize_dequantize(O.MX4, x, axis=O.AXIS_ROW))
+
+
+# --------------------------------------------------------------------- packed image
+
+@pytest.mark.parametrize("f", [O.MX9, O.MX6, O.MX4, O.fmt(8, 1, 2, 2), O.fmt(64, 4, 1, 4),
+                               O.fmt(4, 2, 3, 8), O.fmt(2, 1, 1, 1)], ids=repr)
+def test_plane_layout(f):
+    # element t sits at bits [t(m+1), (t+1)(m+1)), one exponent byte per block, sub-block u at
+    # bits [u d2, (u+1) d2): read the planes back with an independent bit reader
+    rng = np.random.default_rng(11)
+    rows, cols = 5, 192
+    x = rand_wide(rng, rows * cols, spread=4).reshape(rows, cols)
+    codes, sexp, mexp = O.quantize(f, x)
+    n = rows * cols
+    got_codes = unpack_stream(codes, f.m + 1, n)
+    got_tau = unpack_stream(mexp, f.d2, n // f.k2)
+    for b in range(n // f.k1):
+        se, tau, code = O.quantize_block(f, x.reshape(-1)[b * f.k1:(b + 1) * f.k1])
+        assert sexp[b] == se
+        assert got_codes[b * f.k1:(b + 1) * f.k1].tolist() == code.tolist()
+        assert got_tau[b * (f.k1 // f.k2):(b + 1) * (f.k1 // f.k2)].tolist() == tau.tolist()
+
+
+def test_ragged_rows_are_padded_per_row():
+    f = O.fmt(8, 2, 1, 3)
+    rng = np.random.default_rng(12)
+    x = rand_wide(rng, 3 * 13, spread=3).reshape(3, 13)
+    xp = np.zeros((3, 16), np.float32)
+    xp[:, :13] = x
+    for a, b in zip(O.quantize(f, x), O.quantize(f, xp)):
+        assert np.array_equal(a, b)
+    assert np.array_equal(O.quantize_dequantize(f, x), O.quantize_dequantize(f, xp)[:, :13])
+
+
+# ------------------------------------------------------------------------ edge values
+
+def test_zero_subnormal_inf_nan():
+    f = O.MX6
+    # an all-zero block: exponent code 1, zero magnitudes, signs kept
+    x = np.zeros(16, np.float32)
+    x[3] = -0.0
+    se, tau, code = O.quantize_block(f, x)
+    assert se == 1 and tau.tolist() == [0] * 8
+    assert code.tolist() == [0, 0, 0, 16] + [0] * 12
+    # subnormals carry exponent -126 and no implicit one: 3 * 2^-149 on a step of 2^-129 rounds to
+    # 0, on its own in a k1 = 1 block with m = 8 it keeps ... 2^-126-7 = 2^-133 steps: 3*2^-149/2^-133 -> 0
+    tiny = np.float32(3 * 2.0 ** -149)
+    big_sub = np.float32(2.0 ** -127 + 2.0 ** -130)  # subnormal, 0.5625 * 2^-126
+    g = O.fmt(2, 1, 0, 4)
+    se, tau, code = O.quantize_block(g, f32([big_sub, tiny]))
+    assert se == 1
+    # step = 2^(-126-3) = 2^-129: 2^-127 + 2^-130 = 4.5 steps -> tie -> 4 ; tiny -> 0
+    assert code.tolist() == [4, 0]
+    # Inf and NaN are outside the domain; they are held at the largest finite code
+    se, tau, code = O.quantize_block(f, f32([np.inf, -np.inf, np.nan, 1.0] + [0.0] * 12))
+    assert se == 254
+    assert code[0] == 15 and code[1] == 31 and (code[2] & 15) == 15
+    assert math.isfinite(O.decode(f, se, tau[0], code[0]))
+
+
+def test_bf16_input_and_output():
+    rng = np.random.default_rng(13)
+    x = rand_wide(rng, 16 * 64, spread=5).reshape(16, 64)
+    xb = (x.view(np.uint32) >> 16).astype(np.uint16)          # bf16 bit patterns (truncated)
+    xw = (xb.astype(np.uint32) << 16).view(np.float32)        # the same values, widened
+    for f in (O.MX9, O.MX6, O.MX4):
+        pb, pw = O.quantize(f, xb), O.quantize(f, xw)
+        for a, b in zip(pb, pw):
+            assert np.array_equal(a, b)
+        y32 = O.dequantize(f, *pw, 16, 64)
+        y16 = O.dequantize(f, *pb, 16, 64, out_dtype=np.uint16)
+        assert np.array_equal(y16, (y32.view(np.uint32) >> 16).astype(np.uint16))
+        assert not np.any(y32.view(np.uint32) & 0xFFFF)       # nothing was cut off
+    with pytest.raises(O.OracleError):
+        O.dequantize(O.fmt(16, 2, 2, 7), *O.quantize(O.fmt(16, 2, 2, 7), xw), 16, 64,
+                     out_dtype=np.uint16)
+
+
+# ------------------------------------------------------------------------------ QSNR
+
+def theorem1_bound(f, n):
+    # Theorem 1: 6.02 m + 10 log10( 2^(2 beta) / (min(N, k1) + (2^(2 beta) - 1) k2) )
+    beta = (1 << f.d2) - 1
+    return 6.02 * f.m + 10 * math.log10(4.0 ** beta / (min(n, f.k1) + (4.0 ** beta - 1) * f.k2))
+
+
+def test_theorem1_values_for_table2_formats():
+    # beta = 1, k1 = 16, k2 = 2: 10 log10(4 / (16 + 3*2)) = -7.4036 dB below 6.02 m
+    assert theorem1_bound(O.MX9, 1 << 20) == pytest.approx(42.14 - 7.4036, abs=1e-3)
+    assert theorem1_bound(O.MX6, 1 << 20) == pytest.approx(24.08 - 7.4036, abs=1e-3)
+    assert theorem1_bound(O.MX4, 1 << 20) == pytest.approx(12.04 - 7.4036, abs=1e-3)
+    # plain BFP (beta = 0): 6.02 m - 10 log10(k1)
+    assert theorem1_bound(O.fmt(16, 16, 0, 7), 1 << 20) == pytest.approx(42.14 - 12.0412, abs=1e-3)
+    # a vector shorter than the block counts as a block of its own length
+    assert theorem1_bound(O.fmt(64, 64, 0, 4), 8) == pytest.approx(24.08 - 9.0309, abs=1e-3)
+
+
+def test_qsnr_closed_form():
+    # every element 1.25 * 2^j, m = 2, plain BFP: step 2^(j-1), 2.5 steps is a tie -> 2, error
+    # 0.25 * 2^j each, so QSNR = 10 log10(1.5625 / 0.0625) = 10 log10(25)
+    x = f32(np.ldexp(1.25, np.arange(-20, 12))).repeat(16).reshape(-1, 64)
+    x[::2] *= -1
+    q, s = O.qsnr_sweep([O.fmt(16, 16, 0, 2), O.fmt(16, 2, 1, 2)], x)
+    assert q[0] == pytest.approx(10 * math.log10(25.0), rel=1e-12)
+    assert q[1] == pytest.approx(10 * math.log10(25.0), rel=1e-12)
+    assert s[2] == pytest.approx(float(np.sum(x.astype(np.float64) ** 2)), rel=1e-14)
+    # exactly representable data has no noise at all
+    q, s = O.qsnr_sweep([O.MX9], f32(np.arange(-64, 64)).reshape(8, 16))
+    assert q[0] == math.inf and s[0] == 0.0
+
+
+def _distributions():
+    rng = np.random.default_rng(14)
+    n = 256 * 256
+    yield "normal", f32(rng.standard_normal(n))
+    yield "variable_variance", f32(rng.standard_normal(n) * np.abs(rng.standard_normal(n)))
+    yield "student_t3", f32(0.02 * rng.standard_t(3, n))
+    z = rng.standard_normal(n)
+    z[rng.random(n) < 0.001] *= 100
+    yield "outliers", f32(z)
+    yield "uniform", f32(rng.uniform(-3, 3, n))
+
+
+@pytest.mark.parametrize("name,x", list(_distributions()))
+def test_qsnr_sweep_matches_its_definition_and_theorem1(name, x):
+    x = x.reshape(256, 256)
+    fmts = SWEEP + [O.MX9, O.MX6, O.MX4]
+    q, s = O.qsnr_sweep(fmts, x)
+    sig = math.fsum(float(v) ** 2 for v in x.reshape(-1))
+    assert s[-1] == pytest.approx(sig, rel=1e-12)
+    for i, f in enumerate(fmts):
+        # Eq. 3 with numpy on the oracle's own dequantized tensor
+        y = O.quantize_dequantize(f, x)
+        err = math.fsum((float(a) - float(b)) ** 2 for a, b in zip(y.reshape(-1), x.reshape(-1)))
+        assert s[i] == pytest.approx(err, rel=1e-12)
+        assert q[i] == pytest.approx(-10 * math.log10(err / sig), rel=1e-12)
+        # Theorem 1 holds for any distribution
+        assert q[i] >= theorem1_bound(f, x.size) - 1e-9, (name, f)
+    # the 64-format sweep holds only 32 different quantizers: d2 = 0 ignores k2, and k2 = k1
+    # leaves tau at 0
+    by = {(f.k1, f.k2, f.d2, f.m): q[i] for i, f in enumerate(SWEEP)}
+    for (k1, k2, d2, m), v in by.items():
+        if d2 == 0 or k2 == k1:
+            assert v == by[(k1, k1, 0, m)]
+
+
+def test_six_db_per_mantissa_bit():
+    # Theorem 1 discussion: QSNR is linear in m at 6.02 dB per bit (soft check on smooth data)
+    rng = np.random.default_rng(15)
+    x = f32(rng.standard_normal((128, 256)))
+    q, _ = O.qsnr_sweep([O.fmt(16, 2, 1, m) for m in (3, 4, 5, 6, 7)], x)
+    assert np.allclose(np.diff(q), 6.02, atol=0.25)
+
+
+# ---------------------------------------------------------------------------- mx_gemm
+
+def test_mx_gemm_exact_on_small_integers():
+    # integers below 2^m with one exponent are exact in MX, so the product is an integer matrix
+    rng = np.random.default_rng(16)
+    M, N, K = 24, 20, 64
+    A = f32(rng.integers(-7, 8, (M, K)))
+    B = f32(rng.integers(-7, 8, (N, K)))
+    A[:, ::16] = 8.0  # pins every block's exponent, so all entries sit on the integer grid
+    B[:, ::16] = -8.0
+    f = O.MX6
+    pa, pb = O.quantize(f, A), O.quantize(f, B)
+    assert np.array_equal(O.dequantize(f, *pa, M, K), A)
+    C = O.mx_gemm(f, f, pa, pb, M, N, K)
+    assert np.array_equal(C, f32(A.astype(np.int64) @ B.astype(np.int64).T))
+
+
+def test_mx_gemm_against_numpy_and_sampling():
+    rng = np.random.default_rng(17)
+    M, N, K = 40, 36, 128
+    A, B = f32(rng.standard_normal((M, K))), f32(rng.standard_normal((N, K)))
+    for fa, fb in ((O.MX6, O.MX6), (O.MX9, O.MX4)):
+        pa, pb = O.quantize(fa, A), O.quantize(fb, B)
+        Ah = O.dequantize(fa, *pa, M, K).astype(np.float64)
+        Bh = O.dequantize(fb, *pb, N, K).astype(np.float64)
+        C = O.mx_gemm(fa, fb, pa, pb, M, N, K)
+        assert np.allclose(C, Ah @ Bh.T, rtol=1e-6, atol=1e-6)
+        ii, jj = rng.integers(0, M, 50), rng.integers(0, N, 50)
+        out, absdot = O.mx_gemm_sampled(fa, fb, pa, pb, M, N, K, ii, jj)
+        assert np.array_equal(out, C[ii, jj])
+        assert np.allclose(absdot, (np.abs(Ah[ii]) * np.abs(Bh[jj])).sum(axis=1), rtol=1e-12)
