@@ -1,0 +1,141 @@
+/*
+ * bdr_mx.h -- C ABI of the MI355X (gfx950) library for Block Data Representations
+ * and shared microexponents (arXiv 2302.08007).
+ *
+ * The library holds the data-parallel hot path of the two-level quantizer: shared
+ * exponent per k1-block, microexponent per k2-sub-block, m-bit sign-magnitude
+ * elements; bit-packing; dequantization; the QSNR reduction over a sweep of
+ * formats; and a GEMM on MX-quantized operands.
+ *
+ * Conventions that hold for every entry point unless it says otherwise:
+ *   - `const bdr_format *` arguments point to HOST memory and are read before the
+ *     call returns.  Every other pointer is a DEVICE pointer owned by the caller.
+ *   - The library allocates nothing, frees nothing and never synchronizes: work is
+ *     enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and the call returns at once.
+ *   - Every function returns a bdr_status.  On any status other than BDR_OK nothing
+ *     was launched and no output was touched.  Nothing throws or aborts.
+ *   - A tensor is [rows x cols], row-major, with `ld` elements between the starts
+ *     of consecutive rows (ld >= cols).
+ *
+ * Packed image (three planes, each a little-endian bit stream: bit b of a stream
+ * is bit b % 8 of byte b / 8).  For blocks along the rows of an [R x C] tensor:
+ *   codes : element t = r * C + c holds bits [t (m+1), (t+1)(m+1)): the magnitude
+ *           M in the low m bits, the sign above it;
+ *   sexp  : one byte per k1-block, block index r * (C / k1) + c / k1: the biased
+ *           FP32 exponent of the block maximum (d1 = 8);
+ *   mexp  : sub-block u = r * (C / k2) + c / k2 holds bits [u d2, (u+1) d2): the
+ *           shift tau of that sub-block.  Absent (may be NULL) when d2 = 0.
+ * The value of an element is (-1)^sign * M * 2^(sexp - 127 - tau - (m - 1)).
+ * BDR_AXIS_COL means: exactly what BDR_AXIS_ROW gives on the transposed tensor
+ * ([cols x rows]), plane indices included.
+ */
+#ifndef BDR_MX_H
+#define BDR_MX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* A BDR format (Sec. III, "Block Data Representations"): k1 elements share one
+ * d1-bit exponent, every k2 of them share one d2-bit microexponent, each element
+ * has m magnitude bits and a sign; bits/element = (m+1) + d1/k1 + d2/k2.
+ * `rounding` says how the magnitude is rounded (Sec. IX says "nearest"). */
+typedef struct {
+    int32_t k1, d1, k2, d2, m, rounding;
+} bdr_format;
+
+enum bdr_rounding { BDR_RNE = 0 /* nearest, ties to even */, BDR_RNA = 1 /* ties away */, BDR_RTZ = 2 /* truncate */ };
+enum bdr_dtype { BDR_F32 = 0, BDR_BF16 = 1 };
+enum bdr_axis { BDR_AXIS_ROW = 0 /* blocks along the contiguous axis */, BDR_AXIS_COL = 1 /* blocks down the columns */ };
+enum bdr_status {
+    BDR_OK = 0,
+    BDR_ERR_NULL = 1,   /* a required pointer is NULL */
+    BDR_ERR_FORMAT = 2, /* the format tuple is not one this library implements */
+    BDR_ERR_SHAPE = 3,  /* negative size, ld < cols, or the blocked axis is not a multiple of what the kernels need */
+    BDR_ERR_ALIGN = 4,  /* a pointer or row pitch is not 16-byte aligned */
+    BDR_ERR_DTYPE = 5,  /* unknown dtype, or BF16 output asked for a format it cannot hold exactly */
+    BDR_ERR_LAUNCH = 6, /* the HIP runtime refused a launch (hipGetLastError was consumed) */
+    BDR_ERR_WORKSPACE = 7 /* workspace missing or too small */
+};
+
+/* Table II: MX9, MX6 and MX4 are (k1 16, d1 8, k2 2, d2 1, m 7 / 4 / 2). */
+#define BDR_FORMAT_MX9 { 16, 8, 2, 1, 7, BDR_RNE }
+#define BDR_FORMAT_MX6 { 16, 8, 2, 1, 4, BDR_RNE }
+#define BDR_FORMAT_MX4 { 16, 8, 2, 1, 2, BDR_RNE }
+
+/* Human-readable name of a status.  Never NULL; static storage. */
+const char *bdr_status_string(int status);
+
+/* Host only.  BDR_OK when the tuple is implemented: k1 and k2 powers of two,
+ * k2 divides k1, 1 <= k1 <= 512, d1 = 8 (Theorem 1 fixes d1 = 8), 0 <= d2 <= 3,
+ * 1 <= m <= 8, rounding one of bdr_rounding.  (Sec. III.) */
+int bdr_format_validate(const bdr_format *fmt);
+
+/* Host only.  Byte sizes of the three planes of a [rows x cols] tensor blocked
+ * along `axis`; the three together hold (m+1) + d1/k1 + d2/k2 bits per element
+ * (Sec. III).  The blocked axis must be a multiple of max(k1, 8).  Any of the
+ * three outputs may be NULL. */
+int bdr_packed_sizes(const bdr_format *fmt, int64_t rows, int64_t cols, int axis,
+                     size_t *codes_bytes, size_t *sexp_bytes, size_t *mexp_bytes);
+
+/* Quantize x into the packed image (Sec. IX: shared exponent from the block
+ * maximum, Eq. "max_exp"; sub-block shift tau <= 2^d2 - 1, Eq. "q_error_max-1";
+ * magnitude rounded to m bits, Eq. "max_exp_round"; Sec. V for the axis).
+ *   x      device, [rows x cols] of `dtype`, pitch ld elements, 16-byte aligned,
+ *          ld * sizeof(element) a multiple of 16
+ *   codes, sexp, mexp   device, sizes from bdr_packed_sizes, 16-byte aligned,
+ *          fully overwritten; mexp may be NULL when d2 = 0
+ * The blocked axis must be a multiple of max(k1, 8); for BDR_AXIS_COL cols must
+ * also be a multiple of 8.  rows = 0 or cols = 0 is BDR_OK and launches nothing. */
+int bdr_quantize(const bdr_format *fmt, const void *x, int dtype, int64_t rows, int64_t cols,
+                 int64_t ld, int axis, void *codes, void *sexp, void *mexp, void *hip_stream);
+
+/* Rebuild y from the packed image: y = (-1)^sign * M * 2^(sexp-127-tau-(m-1))
+ * (the descaling step of Sec. II / Fig. 4).  Exact in FP32 for every format; BF16
+ * output needs m + 2^d2 - 1 <= 8 (then it is exact too), else BDR_ERR_DTYPE.
+ * Same shape and alignment rules as bdr_quantize; y is fully overwritten. */
+int bdr_dequantize(const bdr_format *fmt, const void *codes, const void *sexp, const void *mexp,
+                   int64_t rows, int64_t cols, int axis, void *y, int dtype, int64_t ld,
+                   void *hip_stream);
+
+/* y = dequantize(quantize(x)) in one pass, without the packed image -- what an
+ * emulation library does around every tensor operation (Sec. VI, "Experimental
+ * Setup").  x and y have the same dtype, shape and pitch; y may alias x. */
+int bdr_quantize_dequantize(const bdr_format *fmt, const void *x, void *y, int dtype,
+                            int64_t rows, int64_t cols, int64_t ld, int axis, void *hip_stream);
+
+/* Bytes of device workspace bdr_qsnr_sweep needs for n_fmts formats. */
+size_t bdr_qsnr_sweep_workspace_bytes(int32_t n_fmts);
+
+/* QSNR (Sec. IV-A, Eq. 3) of every format in fmts[0..n_fmts) on one tensor, blocks
+ * along rows, reading x once:
+ *   sums[f]      = sum over the tensor of (Q_f(x) - x)^2      (f < n_fmts)
+ *   sums[n_fmts] = sum over the tensor of x^2
+ *   qsnr_db[f]   = 10 log10(sums[n_fmts] / sums[f]), +inf when sums[f] = 0
+ * fmts is a host array; qsnr_db (n_fmts doubles), sums (n_fmts + 1 doubles) and
+ * workspace are device memory; workspace need not be cleared by the caller.
+ * cols must be a multiple of max(8, every k1).  1 <= n_fmts <= 1024. */
+int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+                   int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
+                   size_t workspace_bytes, void *hip_stream);
+
+/* C = Ahat * Bhat^T in FP32, where Ahat [M x K] and Bhat [N x K] are the values of
+ * two packed images blocked along K (Sec. V: both inputs of a tensor operation are
+ * MX-quantized, along the reduction dimension).  Operands are expanded exactly to
+ * BF16 on chip and accumulated in FP32.
+ *   fa, fb : formats of A and B; both need k1 = 16, k2 = 2, d2 = 1, m <= 7 ... see
+ *            the status returned; MX9, MX6 and MX4 are accepted
+ *   C      : device, [M x N] floats, pitch ldc, fully overwritten
+ * M and N must be multiples of 128 ... K a multiple of 64. */
+int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
+            const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BDR_MX_H */

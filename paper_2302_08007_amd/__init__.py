@@ -1,0 +1,178 @@
+"""MI355X (gfx950) library for Block Data Representations / shared microexponents (MX).
+
+This package is a thin ctypes binding over ``libbdr_mx.so`` (C ABI in ``include/bdr_mx.h``).
+It only marshals arguments: tensors must already live on the GPU, every step of the path runs
+in the library's HIP kernels, and work is enqueued on torch's current stream.  There is no CPU
+fallback -- if the library has not been built, importing fails.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbdr_mx.so")
+
+RNE, RNA, RTZ = 0, 1, 2
+F32, BF16 = 0, 1
+AXIS_ROW, AXIS_COL = 0, 1
+OK = 0
+
+EXPORTS = (
+    "bdr_status_string", "bdr_format_validate", "bdr_packed_sizes", "bdr_quantize",
+    "bdr_dequantize", "bdr_quantize_dequantize", "bdr_qsnr_sweep_workspace_bytes",
+    "bdr_qsnr_sweep", "mx_gemm",
+)
+
+
+class Format(ctypes.Structure):
+    """BDR format tuple (Sec. III of the paper): k1, d1, k2, d2, m and the rounding rule."""
+
+    _fields_ = [(n, ctypes.c_int32) for n in ("k1", "d1", "k2", "d2", "m", "rounding")]
+
+    def __repr__(self):
+        return "Format(k1=%d,d1=%d,k2=%d,d2=%d,m=%d,rnd=%d)" % (
+            self.k1, self.d1, self.k2, self.d2, self.m, self.rounding)
+
+
+def fmt(k1, k2, d2, m, d1=8, rounding=RNE):
+    return Format(k1, d1, k2, d2, m, rounding)
+
+
+# Table II
+MX9 = fmt(16, 2, 1, 7)
+MX6 = fmt(16, 2, 1, 4)
+MX4 = fmt(16, 2, 1, 2)
+
+
+class BdrError(RuntimeError):
+    def __init__(self, status):
+        super().__init__("libbdr_mx: %s (status %d)" % (status_string(status), status))
+        self.status = status
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_2302_08007_amd.build` "
+            "(there is no fallback path)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    P, I32, I64, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    FP = ctypes.POINTER(Format)
+    L.bdr_status_string.argtypes = [ctypes.c_int]
+    L.bdr_status_string.restype = ctypes.c_char_p
+    L.bdr_format_validate.argtypes = [FP]
+    L.bdr_packed_sizes.argtypes = [FP, I64, I64, I32, P, P, P]
+    L.bdr_quantize.argtypes = [FP, P, I32, I64, I64, I64, I32, P, P, P, P]
+    L.bdr_dequantize.argtypes = [FP, P, P, P, I64, I64, I32, P, I32, I64, P]
+    L.bdr_quantize_dequantize.argtypes = [FP, P, P, I32, I64, I64, I64, I32, P]
+    L.bdr_qsnr_sweep_workspace_bytes.argtypes = [I32]
+    L.bdr_qsnr_sweep_workspace_bytes.restype = SZ
+    L.bdr_qsnr_sweep.argtypes = [FP, I32, P, I32, I64, I64, I64, P, P, P, SZ, P]
+    L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P]
+    return L
+
+
+lib = _load()
+
+
+def status_string(status):
+    return lib.bdr_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != OK:
+        raise BdrError(status)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("expected a float32 or bfloat16 tensor, got %s" % t.dtype)
+
+
+def _dev2d(t):
+    if not (t.is_cuda and t.dim() == 2 and t.stride(1) == 1):
+        raise ValueError("expected a 2-D GPU tensor with unit column stride")
+    return t.shape[0], t.shape[1], t.stride(0)
+
+
+def _p(t):
+    return ctypes.c_void_p(0 if t is None or t.numel() == 0 else t.data_ptr())
+
+
+def bdr_format_validate(f):
+    return lib.bdr_format_validate(ctypes.byref(f))
+
+
+def bdr_packed_sizes(f, rows, cols, axis=AXIS_ROW):
+    c, s, m = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.bdr_packed_sizes(ctypes.byref(f), rows, cols, axis, ctypes.byref(c),
+                                ctypes.byref(s), ctypes.byref(m)))
+    return c.value, s.value, m.value
+
+
+def alloc_planes(f, rows, cols, axis=AXIS_ROW, device="cuda"):
+    """Uninitialised uint8 tensors for the codes, shared-exponent and microexponent planes."""
+    nc, ns, nm = bdr_packed_sizes(f, rows, cols, axis)
+    return tuple(torch.empty(n, dtype=torch.uint8, device=device) for n in (nc, ns, nm))
+
+
+def bdr_quantize(f, x, axis=AXIS_ROW, out=None):
+    """Quantize a 2-D GPU tensor into (codes, sexp, mexp) uint8 planes."""
+    rows, cols, ld = _dev2d(x)
+    planes = out if out is not None else alloc_planes(f, rows, cols, axis, x.device)
+    _check(lib.bdr_quantize(ctypes.byref(f), _p(x), _dtype_code(x), rows, cols, ld, axis,
+                            _p(planes[0]), _p(planes[1]), _p(planes[2]), _stream()))
+    return planes
+
+
+def bdr_dequantize(f, planes, rows, cols, axis=AXIS_ROW, dtype=torch.float32, out=None):
+    y = out if out is not None else torch.empty((rows, cols), dtype=dtype, device=planes[0].device)
+    r, c, ld = _dev2d(y)
+    assert (r, c) == (rows, cols)
+    _check(lib.bdr_dequantize(ctypes.byref(f), _p(planes[0]), _p(planes[1]), _p(planes[2]), rows,
+                              cols, axis, _p(y), _dtype_code(y), ld, _stream()))
+    return y
+
+
+def bdr_quantize_dequantize(f, x, axis=AXIS_ROW, out=None):
+    rows, cols, ld = _dev2d(x)
+    y = out if out is not None else torch.empty_like(x)
+    if _dev2d(y) != (rows, cols, ld) or y.dtype != x.dtype:
+        raise ValueError("output must match the input's shape, pitch and dtype")
+    _check(lib.bdr_quantize_dequantize(ctypes.byref(f), _p(x), _p(y), _dtype_code(x), rows, cols,
+                                       ld, axis, _stream()))
+    return y
+
+
+def bdr_qsnr_sweep(fmts, x, workspace=None, out=None):
+    """QSNR (dB) of every format on a 2-D GPU tensor.  Returns (qsnr_db[n], sums[n+1]) float64."""
+    rows, cols, ld = _dev2d(x)
+    n = len(fmts)
+    arr = (Format * max(n, 1))(*fmts)
+    need = lib.bdr_qsnr_sweep_workspace_bytes(n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = (torch.empty(n, dtype=torch.float64, device=x.device),
+               torch.empty(n + 1, dtype=torch.float64, device=x.device))
+    _check(lib.bdr_qsnr_sweep(arr, n, _p(x), _dtype_code(x), rows, cols, ld, _p(out[0]),
+                              _p(out[1]), _p(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None):
+    """C[M, N] = Ahat @ Bhat^T for two packed operands blocked along K."""
+    C = out if out is not None else torch.empty((M, N), dtype=torch.float32,
+                                                device=a_planes[0].device)
+    _check(lib.mx_gemm(ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]),
+                       _p(a_planes[2]), _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]), M, N, K,
+                       _p(C), C.stride(0), _stream()))
+    return C

@@ -1,0 +1,207 @@
+// C ABI of libbdr_mx.so: argument checking and dispatch.  No kernel lives here.
+//
+// Every entry point validates on the host first and returns a status; nothing is
+// launched unless every check passed, because a kernel that is handed a shape it
+// does not expect can fault the GPU.
+#include "bdr_internal.hpp"
+
+namespace {
+
+inline bool is_pow2(int32_t v) { return v > 0 && (v & (v - 1)) == 0; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_size(int dtype) { return dtype == BDR_F32 ? 4 : 2; }
+
+int check_format(const bdr_format *f)
+{
+    if (!f) return BDR_ERR_NULL;
+    if (!is_pow2(f->k1) || f->k1 > 256) return BDR_ERR_FORMAT;
+    if (!is_pow2(f->k2) || f->k2 > f->k1) return BDR_ERR_FORMAT;
+    if (f->d1 != 8) return BDR_ERR_FORMAT;
+    if (f->d2 < 0 || f->d2 > 3) return BDR_ERR_FORMAT;
+    if (f->m < 1 || f->m > 8) return BDR_ERR_FORMAT;
+    if (f->rounding != BDR_RNE && f->rounding != BDR_RNA && f->rounding != BDR_RTZ)
+        return BDR_ERR_FORMAT;
+    return BDR_OK;
+}
+
+// Shape rules common to quantize / dequantize / fused: the blocked axis is a
+// multiple of max(k1, 8) (a lane owns 8 consecutive elements of a block row),
+// and for column blocks the contiguous axis is a multiple of 8 as well.
+int check_shape(const bdr_format *f, int dtype, int64_t rows, int64_t cols, int64_t ld, int axis)
+{
+    if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
+    if (axis != BDR_AXIS_ROW && axis != BDR_AXIS_COL) return BDR_ERR_SHAPE;
+    if (rows < 0 || cols < 0 || ld < cols) return BDR_ERR_SHAPE;
+    if (rows > 0 && cols > 0 && rows > ((int64_t)1 << 40) / cols) return BDR_ERR_SHAPE;
+    const int64_t unit = f->k1 > 8 ? f->k1 : 8;
+    const int64_t blocked = axis == BDR_AXIS_ROW ? cols : rows;
+    if (blocked % unit != 0) return BDR_ERR_SHAPE;
+    if (axis == BDR_AXIS_COL && cols % 8 != 0) return BDR_ERR_SHAPE;
+    return BDR_OK;
+}
+
+int check_tensor_ptr(const void *p, int dtype, int64_t ld)
+{
+    if (!p) return BDR_ERR_NULL;
+    if (!aligned16(p) || (ld * (int64_t)elem_size(dtype)) % 16 != 0) return BDR_ERR_ALIGN;
+    return BDR_OK;
+}
+
+int check_planes(const bdr_format *f, const void *codes, const void *sexp, const void *mexp)
+{
+    if (!codes || !sexp || (f->d2 > 0 && !mexp)) return BDR_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(sexp) || (f->d2 > 0 && !aligned16(mexp)))
+        return BDR_ERR_ALIGN;
+    return BDR_OK;
+}
+
+inline bool bf16_exact(const bdr_format *f) { return f->m + ((1 << f->d2) - 1) <= 8; }
+
+}  // namespace
+
+extern "C" {
+
+const char *bdr_status_string(int status)
+{
+    switch (status) {
+    case BDR_OK: return "ok";
+    case BDR_ERR_NULL: return "a required pointer is NULL";
+    case BDR_ERR_FORMAT: return "BDR format not implemented";
+    case BDR_ERR_SHAPE: return "bad shape for this format";
+    case BDR_ERR_ALIGN: return "pointer or pitch not 16-byte aligned";
+    case BDR_ERR_DTYPE: return "bad dtype for this call";
+    case BDR_ERR_LAUNCH: return "HIP launch failed";
+    case BDR_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+    }
+}
+
+int bdr_format_validate(const bdr_format *fmt) { return check_format(fmt); }
+
+int bdr_packed_sizes(const bdr_format *fmt, int64_t rows, int64_t cols, int axis,
+                     size_t *codes_bytes, size_t *sexp_bytes, size_t *mexp_bytes)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    st = check_shape(fmt, BDR_F32, rows, cols, cols, axis);
+    if (st) return st;
+    const uint64_t n = (uint64_t)rows * (uint64_t)cols;
+    if (codes_bytes) *codes_bytes = (size_t)(n * (uint64_t)(fmt->m + 1) / 8u);  // n % 8 == 0
+    if (sexp_bytes) *sexp_bytes = (size_t)(n / (uint64_t)fmt->k1);
+    if (mexp_bytes) *mexp_bytes = (size_t)((n / (uint64_t)fmt->k2 * (uint64_t)fmt->d2 + 7u) / 8u);
+    return BDR_OK;
+}
+
+int bdr_quantize(const bdr_format *fmt, const void *x, int dtype, int64_t rows, int64_t cols,
+                 int64_t ld, int axis, void *codes, void *sexp, void *mexp, void *hip_stream)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    st = check_shape(fmt, dtype, rows, cols, ld, axis);
+    if (st) return st;
+    if (rows == 0 || cols == 0) return BDR_OK;
+    st = check_tensor_ptr(x, dtype, ld);
+    if (st) return st;
+    st = check_planes(fmt, codes, sexp, mexp);
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (axis == BDR_AXIS_ROW)
+        return bdr::quantize_row(*fmt, x, dtype, rows, cols, ld, codes, sexp, mexp, s);
+    return bdr::quantize_col(*fmt, x, dtype, rows, cols, ld, codes, sexp, mexp, s);
+}
+
+int bdr_dequantize(const bdr_format *fmt, const void *codes, const void *sexp, const void *mexp,
+                   int64_t rows, int64_t cols, int axis, void *y, int dtype, int64_t ld,
+                   void *hip_stream)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    st = check_shape(fmt, dtype, rows, cols, ld, axis);
+    if (st) return st;
+    if (dtype == BDR_BF16 && !bf16_exact(fmt)) return BDR_ERR_DTYPE;
+    if (rows == 0 || cols == 0) return BDR_OK;
+    st = check_tensor_ptr(y, dtype, ld);
+    if (st) return st;
+    st = check_planes(fmt, codes, sexp, mexp);
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (axis == BDR_AXIS_ROW)
+        return bdr::dequantize_row(*fmt, codes, sexp, mexp, rows, cols, y, dtype, ld, s);
+    return bdr::dequantize_col(*fmt, codes, sexp, mexp, rows, cols, y, dtype, ld, s);
+}
+
+int bdr_quantize_dequantize(const bdr_format *fmt, const void *x, void *y, int dtype,
+                            int64_t rows, int64_t cols, int64_t ld, int axis, void *hip_stream)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    st = check_shape(fmt, dtype, rows, cols, ld, axis);
+    if (st) return st;
+    if (dtype == BDR_BF16 && !bf16_exact(fmt)) return BDR_ERR_DTYPE;
+    if (rows == 0 || cols == 0) return BDR_OK;
+    st = check_tensor_ptr(x, dtype, ld);
+    if (st) return st;
+    st = check_tensor_ptr(y, dtype, ld);
+    if (st) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (axis == BDR_AXIS_ROW) return bdr::qdq_row(*fmt, x, y, dtype, rows, cols, ld, s);
+    return bdr::qdq_col(*fmt, x, y, dtype, rows, cols, ld, s);
+}
+
+size_t bdr_qsnr_sweep_workspace_bytes(int32_t n_fmts)
+{
+    if (n_fmts < 1 || n_fmts > 1024) return 0;
+    return bdr::sweep_workspace_bytes(n_fmts);
+}
+
+int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+                   int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
+                   size_t workspace_bytes, void *hip_stream)
+{
+    if (!fmts) return BDR_ERR_NULL;
+    if (n_fmts < 1 || n_fmts > 1024) return BDR_ERR_SHAPE;
+    for (int32_t k = 0; k < n_fmts; ++k) {
+        int st = check_format(&fmts[k]);
+        if (st) return st;
+        st = check_shape(&fmts[k], dtype, rows, cols, ld, BDR_AXIS_ROW);
+        if (st) return st;
+    }
+    if (!qsnr_db || !sums) return BDR_ERR_NULL;
+    if (!workspace || workspace_bytes < bdr::sweep_workspace_bytes(n_fmts)) return BDR_ERR_WORKSPACE;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(qsnr_db) & 7u) ||
+        (reinterpret_cast<uintptr_t>(sums) & 7u))
+        return BDR_ERR_ALIGN;
+    if (rows > 0 && cols > 0) {
+        int st = check_tensor_ptr(x, dtype, ld);
+        if (st) return st;
+    }
+    return bdr::qsnr_sweep(fmts, n_fmts, x, dtype, rows, cols, ld, qsnr_db, sums, workspace,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
+int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
+            const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream)
+{
+    int st = check_format(fa);
+    if (st) return st;
+    st = check_format(fb);
+    if (st) return st;
+    if (!bdr::is_mx(*fa) || !bdr::is_mx(*fb)) return BDR_ERR_FORMAT;
+    if (M < 0 || N < 0 || K < 0 || ldc < N) return BDR_ERR_SHAPE;
+    if (M % 128 != 0 || N % 128 != 0 || K % 64 != 0) return BDR_ERR_SHAPE;
+    if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
+    if (M == 0 || N == 0) return BDR_OK;
+    if (!C) return BDR_ERR_NULL;
+    if (!aligned16(C) || (ldc * 4) % 16 != 0) return BDR_ERR_ALIGN;
+    if (K > 0) {
+        st = check_planes(fa, a_codes, a_sexp, a_mexp);
+        if (st) return st;
+        st = check_planes(fb, b_codes, b_sexp, b_mexp);
+        if (st) return st;
+    }
+    return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc,
+                     static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

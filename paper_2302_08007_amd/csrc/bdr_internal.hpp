@@ -1,0 +1,48 @@
+// Host-side declarations shared by the translation units of libbdr_mx.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bdr_mx.h"
+
+namespace bdr {
+
+inline bool is_mx(const bdr_format &f)
+{
+    // Table II family: k1 16, k2 2, d1 8, d2 1, nearest-even; m 7, 4 or 2.
+    return f.k1 == 16 && f.k2 == 2 && f.d1 == 8 && f.d2 == 1 && f.rounding == BDR_RNE &&
+           (f.m == 7 || f.m == 4 || f.m == 2);
+}
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? BDR_OK : BDR_ERR_LAUNCH;
+}
+
+// Blocks along the contiguous axis.  All arguments were validated by the caller.
+int quantize_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,
+                 int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s);
+int dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+                   int64_t rows, int64_t cols, void *y, int dtype, int64_t ld, hipStream_t s);
+int qdq_row(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
+            int64_t ld, hipStream_t s);
+
+// Blocks down the columns (planes indexed as for the transposed tensor).
+int quantize_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,
+                 int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s);
+int dequantize_col(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+                   int64_t rows, int64_t cols, void *y, int dtype, int64_t ld, hipStream_t s);
+int qdq_col(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
+            int64_t ld, hipStream_t s);
+
+size_t sweep_workspace_bytes(int32_t n_fmts);
+int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+               int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
+               hipStream_t s);
+
+int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,
+         const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+         int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
+
+}  // namespace bdr

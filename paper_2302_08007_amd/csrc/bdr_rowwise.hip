@@ -1,0 +1,515 @@
+// Row-wise (blocks along the contiguous axis) quantize, dequantize and fused
+// round trip.
+//
+// Two families of kernels:
+//   mx_*      the Table II formats (k1 16, k2 2, d2 1, nearest-even), m in {7,4,2}.
+//             One lane owns 8 consecutive elements (four sub-blocks, half a
+//             block); the two lanes of a block meet through one DPP quad
+//             permute.  HBM bound: every byte is read once and written once.
+//   generic_* any format the library accepts, parameters at run time.
+//
+// Quantization follows Sec. IX of the paper: the shared exponent is the exponent
+// of the block maximum (Eq. "max_exp"), a sub-block is shifted down by
+// tau = min(2^d2 - 1, E - E_sub) (Eq. "q_error_max-1" and the text after
+// "q_error_all"), and the magnitude is rounded to m bits whose top bit has weight
+// 2^(E - tau) (Eq. "max_exp_round").  All scaling is by powers of two through
+// ldexp, which is exact, so codes match an integer implementation bit for bit.
+#include "bdr_device.hpp"
+#include "bdr_internal.hpp"
+
+namespace bdr {
+
+constexpr int kThreads = 256;
+constexpr int kTileElems = kThreads * 8;
+
+// ---------------------------------------------------------------- MX fast path
+
+// Quantize the 8 elements of one lane.  lo/hi: the 8 codes packed little-endian,
+// (MB+1) bits each.  se: biased shared exponent of the lane's block.  tau4: one
+// shift bit per sub-block.  yb (only when DEQ): the dequantized bit patterns.
+template <int MB, bool DEQ>
+__device__ __forceinline__ void mx_quant8(const uint32_t (&xb)[8], uint32_t &lo, uint32_t &hi,
+                                          uint32_t &se, uint32_t &tau4, uint32_t (&yb)[8])
+{
+    constexpr int CB = MB + 1;
+    constexpr uint32_t MMASK = (1u << MB) - 1u;
+    constexpr float TOP = (float)MMASK;
+
+    uint32_t p[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        p[j] = clamp_mag(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask));
+    const uint32_t lm = umax(umax(p[0], p[1]), umax(p[2], p[3]));
+    const uint32_t bm = umax(lm, dpp<kQuadXor1>(lm));  // the other half of the block
+    const uint32_t thr = bm & kExpMask;
+    se = bm >> 23;
+    const int c0 = (MB - 1) + 127 - (int)se;  // x * 2^c0 puts the block maximum in [2^(m-1), 2^m)
+
+    lo = 0;
+    hi = 0;
+    tau4 = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t t = p[j] < thr ? 1u : 0u;  // sub-block exponent below the shared one
+        tau4 |= t << j;
+        const int sh = c0 + (int)t;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i = 2 * j + k;
+            float y = __builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh);
+            y = __builtin_fminf(y, TOP);  // a magnitude that would round to 2^m stays at 2^m - 1
+            const uint32_t zb = as_u(y + kMagic);
+            const uint32_t code = bfi(MMASK, zb, xb[i] >> (31 - MB));
+            const int off = i * CB;
+            if (off < 32) lo |= code << off;
+            if (off >= 32)
+                hi |= code << (off - 32);
+            else if (off + CB > 32)
+                hi |= code >> (32 - off);
+            if (DEQ) {
+                const float v = __builtin_ldexpf(as_f(zb) - kMagic, -sh);
+                yb[i] = bfi(kAbsMask, as_u(v), xb[i]);
+            }
+        }
+    }
+}
+
+template <int MB, typename T>
+__global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
+    const T *__restrict__ x, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
+    uint8_t *__restrict__ mexp, int64_t n_groups)
+{
+    constexpr int CB = MB + 1;
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= n_groups) return;  // whole quads leave together (n_groups % 4 == 0)
+
+    uint32_t xb[8], yb[8];
+    load8(x + 8 * g, xb);
+    uint32_t lo, hi, se, tau4;
+    mx_quant8<MB, false>(xb, lo, hi, se, tau4, yb);
+
+    const uint32_t i = threadIdx.x & 3u;
+    const int64_t quad = g >> 2;
+
+    if (CB == 8) {
+        u32x2 v = {lo, hi};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(codes + 8 * g));
+    } else if (CB == 5) {
+        // A quad holds 4 x 40 bits = 5 dwords.  Lane 0 writes dwords 0-1, lane i
+        // writes dword i + 1; each needs the low word of the next lane.
+        const uint32_t nlo = dpp<kQuadNext>(lo);
+        const uint32_t whi = hi | (nlo << 8);
+        uint8_t *qb = codes + 20 * quad;
+        if (i == 0) {
+            u32x2_a4 v = {lo, whi};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x2_a4 *>(qb));
+        } else {
+            __builtin_nontemporal_store(funnel_r(whi, lo, 32u - 8u * i),
+                                        reinterpret_cast<uint32_t *>(qb + 4 * (i + 1)));
+        }
+    } else {
+        // CB == 3: a quad holds 4 x 24 bits = 3 dwords, written by lanes 0-2.
+        const uint32_t nlo = dpp<kQuadNext>(lo);
+        if (i < 3)
+            __builtin_nontemporal_store((lo >> (8u * i)) | (nlo << (24u - 8u * i)),
+                                        reinterpret_cast<uint32_t *>(codes + 12 * quad + 4 * i));
+    }
+
+    // The quad's two exponent bytes and two microexponent bytes, gathered with
+    // two DPP ORs; lane 0 writes the exponents, lane 2 the microexponents.
+    uint32_t r = (tau4 << (4u * i)) | (se << (16u + 8u * (i >> 1)));
+    r |= dpp<kQuadXor1>(r);
+    r |= dpp<kQuadXor2>(r);
+    if ((i & 1u) == 0) {
+        uint8_t *dst = i == 0 ? sexp : mexp;
+        const uint16_t val = i == 0 ? (uint16_t)(r >> 16) : (uint16_t)(r & 0xffffu);
+        *reinterpret_cast<uint16_t *>(dst + 2 * quad) = val;
+    }
+}
+
+template <int MB, typename T>
+__global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
+    const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups)
+{
+    constexpr int CB = MB + 1;
+    constexpr uint32_t CMASK = (1u << CB) - 1u;
+    constexpr uint32_t MMASK = (1u << MB) - 1u;
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= n_groups) return;
+    const uint32_t i = threadIdx.x & 3u;
+    const int64_t quad = g >> 2;
+
+    uint32_t lo, hi = 0;
+    if (CB == 8) {
+        u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes + 8 * g));
+        lo = v.x;
+        hi = v.y;
+    } else if (CB == 5) {
+        // lane i's 40 bits start 8 i bits into dword i of the quad's 5 dwords
+        u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(codes + 20 * quad + 4 * i);
+        lo = funnel_r(v.y, v.x, 8u * i);
+        hi = (v.y >> (8u * i)) & 0xffu;
+    } else {
+        // lane i's 24 bits start at bit 24 i of the quad's 3 dwords
+        const uint32_t j = i >> 1;
+        u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(codes + 12 * quad + 4 * j);
+        const uint64_t w = ((uint64_t)v.y << 32) | v.x;
+        lo = (uint32_t)(w >> (24u * i - 32u * j)) & 0xffffffu;
+    }
+    const uint32_t se = sexp[g >> 1];
+    const uint32_t tau4 = ((uint32_t)mexp[g >> 1] >> (4u * (i & 1u))) & 0xfu;
+
+    uint32_t yb[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int off = e * CB;
+        uint32_t c;
+        if (off >= 32)
+            c = hi >> (off - 32);
+        else if (off + CB > 32)
+            c = (lo >> off) | (hi << (32 - off));
+        else
+            c = lo >> off;
+        c &= CMASK;
+        const int q = (int)se - 127 - (int)((tau4 >> (e >> 1)) & 1u) - (MB - 1);
+        const float v = __builtin_ldexpf((float)(c & MMASK), q);
+        yb[e] = as_u(v) | ((c >> MB) << 31);
+    }
+    store8(y + 8 * g, yb);
+}
+
+template <int MB, typename T>
+__global__ __launch_bounds__(kThreads) void mx_qdq_row_kernel(const T *x, T *y, int64_t n_groups)
+{
+    // no __restrict__: y may be x (each lane reads its 8 elements before it writes them)
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= n_groups) return;  // whole blocks leave together (n_groups % 2 == 0)
+    uint32_t xb[8], yb[8];
+    load8(x + 8 * g, xb);
+    uint32_t lo, hi, se, tau4;
+    mx_quant8<MB, true>(xb, lo, hi, se, tau4, yb);
+    store8(y + 8 * g, yb);
+}
+
+// ------------------------------------------------------------- generic kernels
+
+struct GenFmt {
+    int k1, k2, d2, m, rounding;
+};
+
+// Sub-block and block maxima (exponent-clamped magnitudes) for the 8 elements
+// of a lane; the block or sub-block may be smaller than the lane's run, or span
+// up to 32 lanes.
+__device__ __forceinline__ void gen_maxima(const GenFmt &f, const uint32_t (&xb)[8],
+                                           uint32_t (&pe)[8], uint32_t (&be)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pe[i] = clamp_mag(xb[i] & kAbsMask);
+#pragma unroll
+    for (int w = 1; w < 8; w <<= 1) {
+        if (f.k2 > w) {
+            uint32_t t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t[i] = umax(pe[i], pe[i ^ w]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pe[i] = t[i];
+        }
+    }
+    if (f.k2 > 8) {
+        uint32_t v = pe[0];
+        for (int w = 1; w < f.k2 / 8; w <<= 1) v = umax(v, (uint32_t)__shfl_xor((int)v, w));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pe[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) be[i] = pe[i];
+#pragma unroll
+    for (int w = 1; w < 8; w <<= 1) {
+        if (f.k1 > w) {
+            uint32_t t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t[i] = umax(be[i], be[i ^ w]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) be[i] = t[i];
+        }
+    }
+    if (f.k1 > 8) {
+        uint32_t v = be[0];
+        for (int w = 1; w < f.k1 / 8; w <<= 1) v = umax(v, (uint32_t)__shfl_xor((int)v, w));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) be[i] = v;
+    }
+}
+
+// |x| * 2^sh rounded to an integer in [0, top] by the format's rule.
+__device__ __forceinline__ float gen_round(float ax, int sh, float top, int rounding)
+{
+    float y = __builtin_fminf(__builtin_ldexpf(ax, sh), top);
+    if (rounding == BDR_RNE) return __builtin_rintf(y);
+    const float t = __builtin_truncf(y);
+    if (rounding == BDR_RNA) return (y - t) >= 0.5f ? t + 1.0f : t;
+    return t;
+}
+
+// MODE 0: write the packed planes.  MODE 1: write the dequantized tensor.
+template <typename T, int MODE>
+__global__ __launch_bounds__(kThreads) void generic_quantize_row_kernel(
+    GenFmt f, const T *x, T *y, uint8_t *__restrict__ codes,
+    uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp, int64_t cols, int64_t ld,
+    int64_t n_groups)
+{
+    __shared__ uint32_t s_mexp[kTileElems * 3 / 32 + 1];
+    if (MODE == 0 && f.d2 > 0) {
+        for (int t = threadIdx.x; t < kTileElems * 3 / 32 + 1; t += kThreads) s_mexp[t] = 0;
+        __syncthreads();
+    }
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool active = g < n_groups;
+    uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int64_t addr = 0;
+    if (active) {
+        const int64_t t0 = 8 * g;
+        const int64_t r = t0 / cols;
+        addr = r * ld + (t0 - r * cols);
+        load8(x + addr, xb);
+    }
+    uint32_t pe[8], be[8];
+    gen_maxima(f, xb, pe, be);
+
+    const int beta = (1 << f.d2) - 1;
+    const int cb = f.m + 1;
+    const float top = (float)((1u << f.m) - 1u);
+    uint32_t code[8], tau[8], yb[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int se = (int)(be[i] >> 23);
+        int t = se - (int)(pe[i] >> 23);
+        t = t < beta ? t : beta;
+        tau[i] = (uint32_t)t;
+        const int sh = (f.m - 1) + 127 - se + t;
+        const float mf = gen_round(__builtin_fabsf(as_f(xb[i])), sh, top, f.rounding);
+        code[i] = (uint32_t)mf | ((xb[i] >> 31) << f.m);
+        if (MODE == 1) yb[i] = as_u(__builtin_ldexpf(mf, -sh)) | (xb[i] & 0x80000000u);
+    }
+    if (MODE == 1) {
+        if (active) store8(y + addr, yb);
+        return;
+    }
+
+    if (active) {
+        // 8 codes of cb <= 9 bits: 64 bits plus, for cb = 9, one more byte
+        uint64_t w = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w |= (uint64_t)code[i] << (i * cb);
+        const uint32_t extra = code[7] >> 1;
+        uint8_t *cp = codes + (int64_t)cb * g;
+        for (int b = 0; b < cb; ++b) cp[b] = b < 8 ? (uint8_t)(w >> (8 * b)) : (uint8_t)extra;
+
+        if (f.k1 >= 8) {
+            const int lanes = f.k1 / 8;
+            if ((g & (lanes - 1)) == 0) sexp[g / lanes] = (uint8_t)(be[0] >> 23);
+        } else {
+            const int lk1 = __builtin_ctz(f.k1);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if ((i & (f.k1 - 1)) == 0) sexp[((8 * g) >> lk1) + (i >> lk1)] = (uint8_t)(be[i] >> 23);
+        }
+    }
+    if (f.d2 == 0) return;
+
+    // Microexponents: each lane ORs its bits into the tile's bit stream in LDS,
+    // then the tile is written out byte by byte.  A tile's stream starts on a
+    // byte boundary because kTileElems / k2 is a multiple of 8.
+    const int64_t tile_sub0 = (int64_t)blockIdx.x * (kTileElems / f.k2);
+    if (active) {
+        uint32_t field = 0;
+        int width = 0;
+        int64_t u0;
+        if (f.k2 <= 8) {
+            const int lk2 = __builtin_ctz(f.k2);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if ((i & (f.k2 - 1)) == 0) field |= tau[i] << ((i >> lk2) * f.d2);
+            width = (8 >> lk2) * f.d2;
+            u0 = (8 * g) >> lk2;
+        } else {
+            const int lanes = f.k2 / 8;
+            if ((g & (lanes - 1)) == 0) {
+                field = tau[0];
+                width = f.d2;
+            }
+            u0 = g / lanes;
+        }
+        if (width > 0) {
+            const uint32_t bit = (uint32_t)((u0 - tile_sub0) * f.d2);
+            const uint32_t s = bit & 31u;
+            atomicOr(&s_mexp[bit >> 5], field << s);
+            if (s + (uint32_t)width > 32u) atomicOr(&s_mexp[(bit >> 5) + 1], field >> (32u - s));
+        }
+    }
+    __syncthreads();
+    const int64_t n_sub = n_groups * 8 / f.k2;
+    int64_t tile_subs = n_sub - tile_sub0;
+    if (tile_subs > kTileElems / f.k2) tile_subs = kTileElems / f.k2;
+    const int nbytes = (int)((tile_subs * f.d2 + 7) / 8);
+    uint8_t *mp = mexp + tile_sub0 * f.d2 / 8;
+    for (int b = threadIdx.x; b < nbytes; b += kThreads)
+        mp[b] = (uint8_t)(s_mexp[b >> 2] >> (8 * (b & 3)));
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void generic_dequantize_row_kernel(
+    GenFmt f, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
+    const uint8_t *__restrict__ mexp, int64_t mexp_bytes, T *__restrict__ y, int64_t cols,
+    int64_t ld, int64_t n_groups)
+{
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= n_groups) return;
+    const int cb = f.m + 1;
+    const uint32_t cmask = (1u << cb) - 1u, mmask = (1u << f.m) - 1u;
+    const uint32_t beta = (1u << f.d2) - 1u;
+
+    const int lk1 = __builtin_ctz(f.k1), lk2 = __builtin_ctz(f.k2);
+    const uint8_t *cp = codes + (int64_t)cb * g;
+    uint64_t w = 0;
+    uint32_t extra = 0;
+    for (int b = 0; b < cb; ++b) {
+        if (b < 8)
+            w |= (uint64_t)cp[b] << (8 * b);
+        else
+            extra = cp[b];
+    }
+    uint32_t yb[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t c = (uint32_t)(w >> (i * cb));
+        if (i == 7 && cb == 9) c |= extra << 1;
+        c &= cmask;
+        const int64_t t = 8 * g + i;
+        const int se = sexp[t >> lk1];
+        uint32_t tau = 0;
+        if (f.d2 > 0) {
+            const int64_t bit = (t >> lk2) * f.d2;
+            const int64_t byte = bit >> 3;
+            uint32_t v = mexp[byte];
+            if (byte + 1 < mexp_bytes) v |= (uint32_t)mexp[byte + 1] << 8;
+            tau = (v >> (bit & 7)) & beta;
+        }
+        const int q = se - 127 - (int)tau - (f.m - 1);
+        yb[i] = as_u(__builtin_ldexpf((float)(c & mmask), q)) | ((c >> f.m) << 31);
+    }
+    const int64_t t0 = 8 * g;
+    const int64_t r = t0 / cols;
+    store8(y + r * ld + (t0 - r * cols), yb);
+}
+
+// -------------------------------------------------------------------- launchers
+
+static inline unsigned blocks_for(int64_t n_groups)
+{
+    return (unsigned)((n_groups + kThreads - 1) / kThreads);
+}
+
+static inline GenFmt gen_of(const bdr_format &f)
+{
+    GenFmt g = {f.k1, f.k2, f.d2, f.m, f.rounding};
+    return g;
+}
+
+// The fast kernels see the tensor as one flat run of whole quads of lanes.
+static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, int64_t ld)
+{
+    return is_mx(f) && ld == cols && (rows * cols) % 32 == 0;
+}
+
+template <typename T>
+static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
+                          uint8_t *codes, uint8_t *sexp, uint8_t *mexp, hipStream_t s)
+{
+    const int64_t ng = rows * cols / 8;
+    const dim3 grid(blocks_for(ng)), block(kThreads);
+    if (mx_fast_ok(f, rows, cols, ld)) {
+        if (f.m == 7)
+            hipLaunchKernelGGL((mx_quantize_row_kernel<7, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
+        else if (f.m == 4)
+            hipLaunchKernelGGL((mx_quantize_row_kernel<4, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
+        else
+            hipLaunchKernelGGL((mx_quantize_row_kernel<2, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
+    } else {
+        hipLaunchKernelGGL((generic_quantize_row_kernel<T, 0>), grid, block, 0, s, gen_of(f), x,
+                           (T *)nullptr, codes, sexp, mexp, cols, ld, ng);
+    }
+    return launch_status();
+}
+
+int quantize_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,
+                 int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
+{
+    if (dtype == BDR_F32)
+        return quantize_row_t(f, (const float *)x, rows, cols, ld, (uint8_t *)codes,
+                              (uint8_t *)sexp, (uint8_t *)mexp, s);
+    return quantize_row_t(f, (const uint16_t *)x, rows, cols, ld, (uint8_t *)codes,
+                          (uint8_t *)sexp, (uint8_t *)mexp, s);
+}
+
+template <typename T>
+static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t *sexp,
+                            const uint8_t *mexp, int64_t rows, int64_t cols, T *y, int64_t ld,
+                            hipStream_t s)
+{
+    const int64_t ng = rows * cols / 8;
+    const dim3 grid(blocks_for(ng)), block(kThreads);
+    if (mx_fast_ok(f, rows, cols, ld)) {
+        if (f.m == 7)
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
+        else if (f.m == 4)
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
+        else
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
+    } else {
+        const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
+        hipLaunchKernelGGL((generic_dequantize_row_kernel<T>), grid, block, 0, s, gen_of(f), codes,
+                           sexp, mexp, mexp_bytes, y, cols, ld, ng);
+    }
+    return launch_status();
+}
+
+int dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+                   int64_t rows, int64_t cols, void *y, int dtype, int64_t ld, hipStream_t s)
+{
+    if (dtype == BDR_F32)
+        return dequantize_row_t(f, (const uint8_t *)codes, (const uint8_t *)sexp,
+                                (const uint8_t *)mexp, rows, cols, (float *)y, ld, s);
+    return dequantize_row_t(f, (const uint8_t *)codes, (const uint8_t *)sexp,
+                            (const uint8_t *)mexp, rows, cols, (uint16_t *)y, ld, s);
+}
+
+template <typename T>
+static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_t cols, int64_t ld,
+                     hipStream_t s)
+{
+    const int64_t ng = rows * cols / 8;
+    const dim3 grid(blocks_for(ng)), block(kThreads);
+    if (is_mx(f) && ld == cols) {
+        if (f.m == 7)
+            hipLaunchKernelGGL((mx_qdq_row_kernel<7, T>), grid, block, 0, s, x, y, ng);
+        else if (f.m == 4)
+            hipLaunchKernelGGL((mx_qdq_row_kernel<4, T>), grid, block, 0, s, x, y, ng);
+        else
+            hipLaunchKernelGGL((mx_qdq_row_kernel<2, T>), grid, block, 0, s, x, y, ng);
+    } else {
+        hipLaunchKernelGGL((generic_quantize_row_kernel<T, 1>), grid, block, 0, s, gen_of(f), x, y,
+                           (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols, ld, ng);
+    }
+    return launch_status();
+}
+
+int qdq_row(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
+            int64_t ld, hipStream_t s)
+{
+    if (dtype == BDR_F32) return qdq_row_t(f, (const float *)x, (float *)y, rows, cols, ld, s);
+    return qdq_row_t(f, (const uint16_t *)x, (uint16_t *)y, rows, cols, ld, s);
+}
+
+}  // namespace bdr
