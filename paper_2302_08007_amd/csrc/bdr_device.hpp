@@ -58,19 +58,66 @@ __device__ __forceinline__ uint32_t funnel_r(uint32_t hi, uint32_t lo, uint32_t 
 __device__ __forceinline__ float as_f(uint32_t b) { return __uint_as_float(b); }
 __device__ __forceinline__ uint32_t as_u(float f) { return __float_as_uint(f); }
 
-// Load 8 consecutive elements as FP32 bit patterns (streaming, not kept in cache).
+// Cache hints, chosen by measurement on MI355X (1 GiB tensors):
+//  - a lane's two adjacent 16-byte FP32 loads do best as plain loads (with the
+//    streaming hint the second one is fetched again);
+//  - one 16-byte load per lane (BF16) is the same either way;
+//  - FP32 output written as two 16-byte stores per lane must be plain stores
+//    (streaming partial-line stores halve the write rate);
+//  - the small packed planes do best with the streaming hint.
+#ifndef BDR_EXP_NT_LOAD
+#define BDR_EXP_NT_LOAD 0
+#endif
+#ifndef BDR_EXP_NT_CODES
+#define BDR_EXP_NT_CODES 1
+#endif
+#ifndef BDR_EXP_NT_OUT
+#define BDR_EXP_NT_OUT 0
+#endif
+template <bool NT, typename V>
+__device__ __forceinline__ V ldg(const V *p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void stg(V v, V *p)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// Two dwords at a dword-aligned (not 8-byte-aligned) address, as one access.
+__device__ __forceinline__ void store_pair_a4(uint32_t a, uint32_t b, void *p)
+{
+    u32x2_a4 v = {a, b};
+    if (BDR_EXP_NT_CODES)
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2_a4 *>(p));
+    else
+        *reinterpret_cast<u32x2_a4 *>(p) = v;
+}
+__device__ __forceinline__ void load_pair_a4(const void *p, uint32_t &a, uint32_t &b)
+{
+    u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(p);
+    a = v.x;
+    b = v.y;
+}
+
+// Load 8 consecutive elements as FP32 bit patterns.
 __device__ __forceinline__ void load8(const float *p, uint32_t (&xb)[8])
 {
     const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
-    u32x4 a = __builtin_nontemporal_load(q);
-    u32x4 b = __builtin_nontemporal_load(q + 1);
+    u32x4 a = ldg<BDR_EXP_NT_LOAD>(q);
+    u32x4 b = ldg<BDR_EXP_NT_LOAD>(q + 1);
     xb[0] = a.x; xb[1] = a.y; xb[2] = a.z; xb[3] = a.w;
     xb[4] = b.x; xb[5] = b.y; xb[6] = b.z; xb[7] = b.w;
 }
 
 __device__ __forceinline__ void load8(const uint16_t *p, uint32_t (&xb)[8])
 {
-    u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    u32x4 a = ldg<true>(reinterpret_cast<const u32x4 *>(p));
     xb[0] = a.x << 16; xb[1] = a.x & 0xffff0000u;
     xb[2] = a.y << 16; xb[3] = a.y & 0xffff0000u;
     xb[4] = a.z << 16; xb[5] = a.z & 0xffff0000u;
@@ -84,8 +131,8 @@ __device__ __forceinline__ void store8(float *p, const uint32_t (&yb)[8])
     u32x4 *q = reinterpret_cast<u32x4 *>(p);
     u32x4 a = {yb[0], yb[1], yb[2], yb[3]};
     u32x4 b = {yb[4], yb[5], yb[6], yb[7]};
-    __builtin_nontemporal_store(a, q);
-    __builtin_nontemporal_store(b, q + 1);
+    stg<BDR_EXP_NT_OUT>(a, q);
+    stg<BDR_EXP_NT_OUT>(b, q + 1);
 }
 
 __device__ __forceinline__ void store8(uint16_t *p, const uint32_t (&yb)[8])

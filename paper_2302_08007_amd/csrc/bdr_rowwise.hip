@@ -19,7 +19,10 @@
 
 namespace bdr {
 
-constexpr int kThreads = 256;
+#ifndef BDR_EXP_THREADS
+#define BDR_EXP_THREADS 256
+#endif
+constexpr int kThreads = BDR_EXP_THREADS;
 constexpr int kTileElems = kThreads * 8;
 
 // ---------------------------------------------------------------- MX fast path
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
 
     if (CB == 8) {
         u32x2 v = {lo, hi};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(codes + 8 * g));
+        stg<BDR_EXP_NT_CODES>(v, reinterpret_cast<u32x2 *>(codes + 8 * g));
     } else if (CB == 5) {
         // A quad holds 4 x 40 bits = 5 dwords.  Lane 0 writes dwords 0-1, lane i
         // writes dword i + 1; each needs the low word of the next lane.
@@ -101,18 +104,17 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
         const uint32_t whi = hi | (nlo << 8);
         uint8_t *qb = codes + 20 * quad;
         if (i == 0) {
-            u32x2_a4 v = {lo, whi};
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x2_a4 *>(qb));
+            store_pair_a4(lo, whi, qb);
         } else {
-            __builtin_nontemporal_store(funnel_r(whi, lo, 32u - 8u * i),
-                                        reinterpret_cast<uint32_t *>(qb + 4 * (i + 1)));
+            stg<BDR_EXP_NT_CODES>(funnel_r(whi, lo, 32u - 8u * i),
+                                  reinterpret_cast<uint32_t *>(qb + 4 * (i + 1)));
         }
     } else {
         // CB == 3: a quad holds 4 x 24 bits = 3 dwords, written by lanes 0-2.
         const uint32_t nlo = dpp<kQuadNext>(lo);
         if (i < 3)
-            __builtin_nontemporal_store((lo >> (8u * i)) | (nlo << (24u - 8u * i)),
-                                        reinterpret_cast<uint32_t *>(codes + 12 * quad + 4 * i));
+            stg<BDR_EXP_NT_CODES>((lo >> (8u * i)) | (nlo << (24u - 8u * i)),
+                                  reinterpret_cast<uint32_t *>(codes + 12 * quad + 4 * i));
     }
 
     // The quad's two exponent bytes and two microexponent bytes, gathered with
@@ -147,14 +149,16 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
         hi = v.y;
     } else if (CB == 5) {
         // lane i's 40 bits start 8 i bits into dword i of the quad's 5 dwords
-        u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(codes + 20 * quad + 4 * i);
-        lo = funnel_r(v.y, v.x, 8u * i);
-        hi = (v.y >> (8u * i)) & 0xffu;
+        uint32_t v0, v1;
+        load_pair_a4(codes + 20 * quad + 4 * i, v0, v1);
+        lo = funnel_r(v1, v0, 8u * i);
+        hi = (v1 >> (8u * i)) & 0xffu;
     } else {
         // lane i's 24 bits start at bit 24 i of the quad's 3 dwords
         const uint32_t j = i >> 1;
-        u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(codes + 12 * quad + 4 * j);
-        const uint64_t w = ((uint64_t)v.y << 32) | v.x;
+        uint32_t v0, v1;
+        load_pair_a4(codes + 12 * quad + 4 * j, v0, v1);
+        const uint64_t w = ((uint64_t)v1 << 32) | v0;
         lo = (uint32_t)(w >> (24u * i - 32u * j)) & 0xffffffu;
     }
     const uint32_t se = sexp[g >> 1];

@@ -1,5 +1,411 @@
+// QSNR of many BDR formats on one tensor, reading the tensor once.
+//
+// QSNR is the ratio of signal power to quantization-noise power in decibels
+// (Sec. IV-A, Eq. 3); the design-space study of the paper evaluates it for
+// hundreds of format tuples (Sec. IV).  This file does the noise half of that
+// study on the GPU: per format f, S_err[f] = sum (Q_f(x) - x)^2, plus one
+// S_sig = sum x^2, then 10 log10(S_sig / S_err[f]).
+//
+// How the work is shared between formats:
+//   - The exponent of the maximum over every aligned power-of-two group of
+//     1 .. 256 elements is computed once per load (in-lane for groups up to 8,
+//     DPP / one shuffle across lanes above that).
+//   - Formats are grouped on the host into "classes" (k1, k2, d2): within a
+//     class every element has the same effective exponent
+//         eps = max(E_block - beta, E_subblock)      (Sec. IX: tau <= beta)
+//     so it is computed once per class.  d2 = 0 and k2 = k1 both mean tau = 0
+//     and share a class; identical tuples share one accumulator.
+//   - A quantizer (class, m, rounding) then costs six VALU operations per
+//     element: scale, clamp, round, subtract, unscale, square-accumulate.
+//
+// Range: squares of FP32 numbers underflow for small tensors, so the kernel works
+// on x * 2^s with s chosen from the tensor's largest exponent (a tiny pre-pass)
+// and undoes the scale in FP64 at the end.  Scaling by a power of two commutes
+// with the quantizer (end of Sec. IX), so nothing changes except for values more
+// than 126 binades below the tensor maximum, whose contribution is below 2^-250
+// of either sum.
+//
+// Sums: FP32 inside a lane over at most 32 elements, FP64 from there on;
+// per-block partials are combined in a fixed order, so results are reproducible.
+#include "bdr_device.hpp"
 #include "bdr_internal.hpp"
+
 namespace bdr {
-size_t sweep_workspace_bytes(int32_t n) { return 16 * (size_t)(n + 1); }
-int qsnr_sweep(const bdr_format *, int32_t, const void *, int, int64_t, int64_t, int64_t, double *, double *, void *, hipStream_t) { return BDR_ERR_LAUNCH; }
+
+namespace {
+
+constexpr int kSweepThreads = 256;
+constexpr int kWaves = kSweepThreads / 64;
+constexpr int kG = 4;  // groups of 8 elements per lane per iteration
+constexpr int kMaxBlocks = 2048;
+constexpr int kChunk = 256;  // formats per launch: keeps the kernel arguments under 4 KiB
+constexpr int kMaxClasses = kChunk;
+constexpr int kMaxQuant = kChunk;
+constexpr size_t kHeaderBytes = 256;
+
+struct ClassDesc {
+    uint8_t lk1, lk2, beta, nq;  // log2 k1, log2 k2, 2^d2 - 1, quantizers in the class
+    uint16_t first;              // index of its first quantizer
+};
+struct QuantDesc {
+    uint8_t m, rounding;
+};
+struct SweepPlan {
+    int32_t n_class, n_quant;
+    ClassDesc cls[kMaxClasses];
+    QuantDesc q[kMaxQuant];
+};
+struct FormatMap {
+    uint16_t idx[kChunk];  // format -> quantizer
+};
+
+struct Header {
+    uint32_t absmax_bits;
+};
+
+__global__ void sweep_clear_kernel(Header *h) { h->absmax_bits = 0; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void sweep_absmax_kernel(const T *__restrict__ x, int64_t cols,
+                                                           int64_t ld, int64_t n_groups, Header *h)
+{
+    uint32_t m = 0;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < n_groups;
+         g += (int64_t)gridDim.x * 256) {
+        const int64_t t0 = 8 * g;
+        const int64_t r = ld == cols ? 0 : t0 / cols;
+        uint32_t xb[8];
+        load8(x + r * ld + (t0 - r * cols), xb);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = umax(m, xb[i] & kAbsMask);
+    }
+    for (int w = 32; w > 0; w >>= 1) m = umax(m, (uint32_t)__shfl_xor((int)m, w));
+    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(&h->absmax_bits, m);
 }
+
+// Exponent fields of the maxima over aligned groups, for one run of 8 elements.
+struct Levels {
+    uint32_t e0[8];  // per element
+    uint32_t e1[4];  // per pair
+    uint32_t e2[2];  // per 4
+    uint32_t eL[6];  // per 8, 16, 32, 64, 128, 256 (lane and across lanes)
+};
+
+__device__ __forceinline__ void build_levels(const uint32_t (&ab)[8], uint32_t mag_lo, Levels &L)
+{
+    uint32_t p0[8], p1[4], p2[2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p0[i] = umin(umax(ab[i], mag_lo), kMagHi);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p1[i] = umax(p0[2 * i], p0[2 * i + 1]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) p2[i] = umax(p1[2 * i], p1[2 * i + 1]);
+    uint32_t v = umax(p2[0], p2[1]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) L.e0[i] = p0[i] >> 23;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) L.e1[i] = p1[i] >> 23;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) L.e2[i] = p2[i] >> 23;
+    L.eL[0] = v >> 23;
+    v = umax(v, dpp<kQuadXor1>(v));
+    L.eL[1] = v >> 23;
+    v = umax(v, dpp<kQuadXor2>(v));
+    L.eL[2] = v >> 23;
+    v = umax(v, dpp<kRowHalfMirror>(v));
+    L.eL[3] = v >> 23;
+    v = umax(v, dpp<kRowMirror>(v));
+    L.eL[4] = v >> 23;
+    v = umax(v, (uint32_t)__shfl_xor((int)v, 16));
+    L.eL[5] = v >> 23;
+}
+
+// Exponent of the level-`lk` group that element i of the run belongs to.
+__device__ __forceinline__ void level_exps(const Levels &L, int lk, int (&out)[8])
+{
+    if (lk == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (int)L.e0[i];
+    } else if (lk == 1) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (int)L.e1[i >> 1];
+    } else if (lk == 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (int)L.e2[i >> 2];
+    } else {
+        uint32_t v = L.eL[0];
+#pragma unroll
+        for (int l = 1; l < 6; ++l) v = (lk - 3 == l) ? L.eL[l] : v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (int)v;
+    }
+}
+
+template <int ROUNDING>
+__device__ __forceinline__ float round_mode(float y)
+{
+    if (ROUNDING == BDR_RNE) return __builtin_rintf(y);
+    const float t = __builtin_truncf(y);
+    if (ROUNDING == BDR_RNA) return (y - t) >= 0.5f ? t + 1.0f : t;
+    return t;
+}
+
+// Sum over the lane's kG*8 elements of the squared quantization error of one
+// quantizer, given the per-element scaling exponents of its class.
+template <int ROUNDING>
+__device__ __forceinline__ float quant_err2(const float (&ax)[kG][8], const int (&shb)[kG][8],
+                                            int m)
+{
+    const float top = (float)((1u << m) - 1u);
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < kG; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int sh = shb[j][i] + (m - 1);
+            const float y = __builtin_fminf(__builtin_ldexpf(ax[j][i], sh), top);
+            // scaled |x| minus its rounded (or held) magnitude: exact
+            const float yy = __builtin_ldexpf(ax[j][i], sh);
+            const float d = __builtin_ldexpf(yy - round_mode<ROUNDING>(y), -sh);
+            acc = __builtin_fmaf(d, d, acc);
+        }
+    return acc;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += as_f(dpp<kQuadXor1>(as_u(v)));
+    v += as_f(dpp<kQuadXor2>(as_u(v)));
+    v += as_f(dpp<kRowHalfMirror>(as_u(v)));
+    v += as_f(dpp<kRowMirror>(as_u(v)));
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
+    SweepPlan plan, const T *__restrict__ x, int64_t cols, int64_t ld, int64_t n_groups,
+    const Header *__restrict__ hdr, double *__restrict__ partials)
+{
+    extern __shared__ double s_acc[];  // [kWaves][n_quant + 1]
+    const int nq = plan.n_quant;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int t = threadIdx.x; t < kWaves * (nq + 1); t += kSweepThreads) s_acc[t] = 0.0;
+    __syncthreads();
+    double *wacc = s_acc + wave * (nq + 1);
+
+    // Work on x * 2^sref so that the tensor maximum lands in [1, 2).
+    const int eref = (int)(umin(umax(hdr->absmax_bits, kMagLo), kMagHi) >> 23);
+    const int sref = 127 - eref;
+    // the lowest exponent an element can carry (code 1 before scaling)
+    const uint32_t mag_lo = (uint32_t)(1 + (sref > 0 ? sref : 0)) << 23;
+
+    const int64_t per_iter = (int64_t)gridDim.x * kSweepThreads * kG;
+    for (int64_t base = (int64_t)blockIdx.x * kSweepThreads * kG; base < n_groups;
+         base += per_iter) {
+        float ax[kG][8];
+        Levels L[kG];
+        float sig = 0.f;
+#pragma unroll
+        for (int j = 0; j < kG; ++j) {
+            const int64_t g = base + (int64_t)wave * (64 * kG) + j * 64 + lane;
+            uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (g < n_groups) {
+                const int64_t t0 = 8 * g;
+                const int64_t r = ld == cols ? 0 : t0 / cols;
+                load8(x + r * ld + (t0 - r * cols), xb);
+            }
+            uint32_t ab[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                ax[j][i] = __builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sref);
+                ab[i] = as_u(ax[j][i]);
+                sig = __builtin_fmaf(ax[j][i], ax[j][i], sig);
+            }
+            build_levels(ab, mag_lo, L[j]);
+        }
+        sig = wave_sum(sig);
+        if (lane == 0) wacc[nq] += (double)sig;
+
+        for (int c = 0; c < plan.n_class; ++c) {
+            const ClassDesc cd = plan.cls[c];
+            int shb[kG][8];
+#pragma unroll
+            for (int j = 0; j < kG; ++j) {
+                int eb[8], es[8];
+                level_exps(L[j], cd.lk1, eb);
+                level_exps(L[j], cd.lk2, es);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int eps = max(eb[i] - (int)cd.beta, es[i]);
+                    shb[j][i] = 127 - eps;
+                }
+            }
+            for (int k = 0; k < cd.nq; ++k) {
+                const QuantDesc qd = plan.q[cd.first + k];
+                float e2;
+                if (qd.rounding == BDR_RNE)
+                    e2 = quant_err2<BDR_RNE>(ax, shb, qd.m);
+                else if (qd.rounding == BDR_RNA)
+                    e2 = quant_err2<BDR_RNA>(ax, shb, qd.m);
+                else
+                    e2 = quant_err2<BDR_RTZ>(ax, shb, qd.m);
+                e2 = wave_sum(e2);
+                if (lane == 0) wacc[cd.first + k] += (double)e2;
+            }
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t <= nq; t += kSweepThreads) {
+        double v = 0.0;
+        for (int w = 0; w < kWaves; ++w) v += s_acc[w * (nq + 1) + t];
+        partials[(int64_t)blockIdx.x * (nq + 1) + t] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void sweep_finalize_kernel(
+    FormatMap map, int32_t n_fmts, int32_t n_quant, int32_t n_blocks,
+    const Header *__restrict__ hdr, const double *__restrict__ partials,
+    double *__restrict__ qsnr_db, double *__restrict__ sums, double *sig_out)
+{
+    extern __shared__ double s_tot[];  // [n_quant + 1], in the tensor's own scale
+    const int eref = (int)(umin(umax(hdr->absmax_bits, kMagLo), kMagHi) >> 23);
+    const double unscale = __builtin_ldexp(1.0, -2 * (127 - eref));
+    for (int t = threadIdx.x; t <= n_quant; t += blockDim.x) {
+        double v = 0.0;
+        for (int b = 0; b < n_blocks; ++b) v += partials[(int64_t)b * (n_quant + 1) + t];
+        s_tot[t] = v * unscale;
+    }
+    __syncthreads();
+    const double sig = s_tot[n_quant];
+    for (int f = threadIdx.x; f <= n_fmts; f += blockDim.x) {
+        if (f == n_fmts) {
+            *sig_out = sig;
+        } else {
+            const double err = s_tot[map.idx[f]];
+            sums[f] = err;
+            qsnr_db[f] = err > 0.0 ? 10.0 * log10(sig / err) : __builtin_inf();
+        }
+    }
+}
+
+inline int ilog2(int v) { return __builtin_ctz((unsigned)v); }
+
+}  // namespace
+
+size_t sweep_workspace_bytes(int32_t n_fmts)
+{
+    const int per_launch = n_fmts < kChunk ? n_fmts : kChunk;
+    return kHeaderBytes + (size_t)kMaxBlocks * (size_t)(per_launch + 1) * sizeof(double);
+}
+
+namespace {
+
+// Host plan for up to kChunk formats: classes of (k1, k2, beta) with the tau = 0
+// formats merged, and within a class one quantizer per distinct (m, rounding).
+void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &map)
+{
+    struct Key {
+        int lk1, lk2, beta, m, rnd;
+    };
+    Key keys[kMaxQuant];
+    int order[kChunk];
+    int nq = 0;
+    for (int f = 0; f < n_fmts; ++f) {
+        Key k = {ilog2(fmts[f].k1), ilog2(fmts[f].k2), (1 << fmts[f].d2) - 1, fmts[f].m,
+                 fmts[f].rounding};
+        if (k.beta == 0 || k.lk2 == k.lk1) {  // no sub-block shift: plain block floating point
+            k.beta = 0;
+            k.lk2 = k.lk1;
+        }
+        int found = -1;
+        for (int j = 0; j < nq && found < 0; ++j)
+            if (keys[j].lk1 == k.lk1 && keys[j].lk2 == k.lk2 && keys[j].beta == k.beta &&
+                keys[j].m == k.m && keys[j].rnd == k.rnd)
+                found = j;
+        if (found < 0) {
+            keys[nq] = k;
+            found = nq++;
+        }
+        order[f] = found;
+    }
+    int newidx[kMaxQuant];
+    bool placed[kMaxQuant] = {false};
+    int nc = 0, pos = 0;
+    for (int j = 0; j < nq; ++j) {
+        if (placed[j]) continue;
+        ClassDesc &cd = plan.cls[nc++];
+        cd.lk1 = (uint8_t)keys[j].lk1;
+        cd.lk2 = (uint8_t)keys[j].lk2;
+        cd.beta = (uint8_t)keys[j].beta;
+        cd.first = (uint16_t)pos;
+        int cnt = 0;
+        for (int i = j; i < nq; ++i) {
+            if (placed[i] || keys[i].lk1 != keys[j].lk1 || keys[i].lk2 != keys[j].lk2 ||
+                keys[i].beta != keys[j].beta)
+                continue;
+            placed[i] = true;
+            newidx[i] = pos;
+            plan.q[pos].m = (uint8_t)keys[i].m;
+            plan.q[pos].rounding = (uint8_t)keys[i].rnd;
+            ++pos;
+            ++cnt;
+        }
+        cd.nq = (uint8_t)cnt;  // at most 8 values of m x 3 roundings
+    }
+    plan.n_class = nc;
+    plan.n_quant = nq;
+    for (int f = 0; f < n_fmts; ++f) map.idx[f] = (uint16_t)newidx[order[f]];
+}
+
+}  // namespace
+
+int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+               int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
+               hipStream_t s)
+{
+    static_assert(sizeof(SweepPlan) + 64 < 4096, "kernel arguments must stay under 4 KiB");
+    Header *hdr = reinterpret_cast<Header *>(workspace);
+    double *partials = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes);
+    const int64_t n_groups = rows * cols / 8;
+    const int64_t per_block = (int64_t)kSweepThreads * kG;
+    int64_t nb = (n_groups + per_block - 1) / per_block;
+    if (nb > kMaxBlocks) nb = kMaxBlocks;
+    if (nb < 1) nb = 1;
+
+    hipLaunchKernelGGL(sweep_clear_kernel, dim3(1), dim3(1), 0, s, hdr);
+    if (n_groups > 0) {
+        const int64_t want = (n_groups + 255) / 256;
+        const unsigned ab = (unsigned)(want < 4096 ? want : 4096);
+        if (dtype == BDR_F32)
+            hipLaunchKernelGGL(sweep_absmax_kernel<float>, dim3(ab), dim3(256), 0, s,
+                               (const float *)x, cols, ld, n_groups, hdr);
+        else
+            hipLaunchKernelGGL(sweep_absmax_kernel<uint16_t>, dim3(ab), dim3(256), 0, s,
+                               (const uint16_t *)x, cols, ld, n_groups, hdr);
+    }
+    // Chunks of formats run one after the other on the stream and reuse the
+    // partial-sum area; each launch gets its own copy of the plan by value.
+    for (int32_t f0 = 0; f0 < n_fmts; f0 += kChunk) {
+        const int nf = n_fmts - f0 < kChunk ? n_fmts - f0 : kChunk;
+        SweepPlan plan;
+        FormatMap map;
+        make_plan(fmts + f0, nf, plan, map);
+        const int nq = plan.n_quant;
+        const size_t lds = (size_t)kWaves * (size_t)(nq + 1) * sizeof(double);
+        if (dtype == BDR_F32)
+            hipLaunchKernelGGL(sweep_kernel<float>, dim3((unsigned)nb), dim3(kSweepThreads), lds,
+                               s, plan, (const float *)x, cols, ld, n_groups, hdr, partials);
+        else
+            hipLaunchKernelGGL(sweep_kernel<uint16_t>, dim3((unsigned)nb), dim3(kSweepThreads),
+                               lds, s, plan, (const uint16_t *)x, cols, ld, n_groups, hdr,
+                               partials);
+        hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(256),
+                           (size_t)(nq + 1) * sizeof(double), s, map, nf, nq, (int32_t)nb, hdr,
+                           partials, qsnr_db + f0, sums + f0, sums + n_fmts);
+    }
+    return launch_status();
+}
+
+}  // namespace bdr

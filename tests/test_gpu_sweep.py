@@ -1,0 +1,119 @@
+"""GPU parity: the fused QSNR sweep against the CPU oracle (1e-4 relative on dB and on sums)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2302_08007_amd as B
+import synth_inputs as S
+from gpu_util import ofmt, to_np
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-4  # tolerance on QSNR in dB, relative
+
+
+def sweep64():
+    return [B.fmt(k1, k1 if k2 == 0 else k2, d2, m)
+            for k1 in (8, 16, 32, 64) for k2 in (1, 2, 4, 0) for d2 in (0, 1) for m in (2, 4)]
+
+
+def check(fmts, x, what=""):
+    q, s = B.bdr_qsnr_sweep(fmts, x)
+    torch.cuda.synchronize()
+    q, s = q.cpu().numpy(), s.cpu().numpy()
+    xn = to_np(x)
+    qw, sw = O.qsnr_sweep([ofmt(f) for f in fmts], xn)
+    for i, f in enumerate(fmts):
+        if math.isinf(qw[i]):
+            assert math.isinf(q[i]) and s[i] == 0.0, (what, f)
+        else:
+            assert q[i] == pytest.approx(qw[i], rel=RTOL), (what, f, q[i], qw[i])
+            assert s[i] == pytest.approx(sw[i], rel=2e-5), (what, f)
+    assert s[-1] == pytest.approx(sw[-1], rel=2e-5)
+    return q
+
+
+def test_tiny_config_qsnr():
+    x = S.tiny(device="cuda")
+    q = check([B.MX9, B.MX6, B.MX4], x, "tiny")
+    assert q[0] > q[1] > q[2]
+
+
+def test_sweep_64_formats_reduced_size():
+    x = S.sweep(1 << 18, device="cuda")
+    q = check(sweep64(), x, "sweep64")
+    # formats without a sub-block shift are the same quantizer and must report the same number
+    by = {(f.k1, f.k2, f.d2, f.m): q[i] for i, f in enumerate(sweep64())}
+    for (k1, k2, d2, m), v in by.items():
+        if d2 == 0 or k2 == k1:
+            assert v == by[(k1, k1, 0, m)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_other_formats_and_roundings(dtype):
+    fmts = [B.fmt(1, 1, 0, 4), B.fmt(2, 1, 1, 3), B.fmt(4, 2, 2, 5), B.fmt(8, 8, 0, 8),
+            B.fmt(16, 2, 1, 7, rounding=B.RNA), B.fmt(16, 2, 1, 7, rounding=B.RTZ),
+            B.fmt(16, 4, 3, 1), B.fmt(32, 16, 2, 6), B.fmt(64, 8, 1, 3, rounding=B.RNA),
+            B.fmt(128, 2, 1, 4), B.fmt(128, 64, 2, 2), B.fmt(256, 1, 3, 5), B.fmt(256, 256, 0, 7),
+            B.fmt(256, 32, 1, 4, rounding=B.RTZ), B.MX6, B.MX6]
+    x = S.wide_range(96, 1024 + 256, device="cuda", seed=3, spread=5, dtype=dtype)
+    check(fmts, x, "mixed %s" % dtype)
+
+
+@pytest.mark.parametrize("shift", [-110, -60, 40, 100])
+def test_tensor_scale_does_not_matter(shift):
+    # squares of very small or very large FP32 values leave the FP32 range; QSNR must not care
+    x = torch.ldexp(S.tiny(128, 512, device="cuda", seed=9), torch.tensor(shift, device="cuda"))
+    q = check([B.MX9, B.MX6, B.MX4, B.fmt(64, 64, 0, 4)], x, "shift %d" % shift)
+    q0, _ = B.bdr_qsnr_sweep([B.MX9, B.MX6, B.MX4, B.fmt(64, 64, 0, 4)],
+                             S.tiny(128, 512, device="cuda", seed=9))
+    assert np.allclose(q, q0.cpu().numpy(), rtol=1e-6)
+
+
+def test_strided_ragged_and_exact():
+    big = S.tiny(77, 1024, device="cuda", seed=4)
+    check([B.MX6, B.fmt(64, 4, 1, 4)], big[:, 128:128 + 320], "strided")       # ld > cols
+    check([B.MX4], S.tiny(1, 16, device="cuda", seed=5), "one block")
+    ints = torch.arange(-64, 64, device="cuda", dtype=torch.float32).reshape(8, 16)
+    q, s = B.bdr_qsnr_sweep([B.MX9], ints)
+    assert math.isinf(q.item() if q.numel() == 1 else q[0].item()) and s[0].item() == 0.0
+    z, sz = B.bdr_qsnr_sweep([B.MX9], torch.zeros(4, 64, device="cuda"))
+    assert sz[1].item() == 0.0 and sz[0].item() == 0.0
+
+
+def test_more_formats_than_one_launch_holds():
+    fmts = [B.fmt(k1, k2, d2, m, rounding=r) for k1 in (16, 64) for k2 in (1, 2, 8)
+            for d2 in (0, 1, 2, 3) for m in range(1, 9) for r in (0, 1)]
+    assert len(fmts) > 256
+    x = S.tiny(64, 256, device="cuda", seed=6)
+    check(fmts, x, "384 formats")
+
+
+def test_full_size_sweep_properties_and_sampled_formats():
+    # 16,777,216 values, the bench configuration.  The oracle runs four of the 64 formats in
+    # full; the rest are checked through properties that hold at any size.
+    x = S.sweep(device="cuda")
+    fmts = sweep64()
+    q, s = B.bdr_qsnr_sweep(fmts, x)
+    q, s = q.cpu().numpy(), s.cpu().numpy()
+    xn = to_np(x)
+    idx = [0, 21, 42, 63]
+    qw, sw = O.qsnr_sweep([ofmt(fmts[i]) for i in idx], xn)
+    for j, i in enumerate(idx):
+        assert q[i] == pytest.approx(qw[j], rel=RTOL), fmts[i]
+    assert s[-1] == pytest.approx(sw[-1], rel=2e-5)
+    # additivity: the sums over the two halves add up to the sums over the whole
+    h = x.shape[0] // 2
+    _, s1 = B.bdr_qsnr_sweep(fmts, x[:h])
+    _, s2 = B.bdr_qsnr_sweep(fmts, x[h:])
+    assert np.allclose(s1.cpu().numpy() + s2.cpu().numpy(), s, rtol=1e-6)
+    for i, f in enumerate(fmts):
+        beta = (1 << f.d2) - 1
+        bound = 6.02 * f.m + 10 * math.log10(4.0 ** beta / (f.k1 + (4.0 ** beta - 1) * f.k2))
+        assert q[i] >= bound, f          # Theorem 1
+    # run twice: bit-identical (fixed-order reduction)
+    q2, s2b = B.bdr_qsnr_sweep(fmts, x)
+    assert np.array_equal(q2.cpu().numpy(), q) and np.array_equal(s2b.cpu().numpy(), s)
