@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Bench of the BDR/MX hot path on one MI355X.
+
+Workload ("bandwidth" configuration): a 268,435,456-element FP32 tensor (1 GiB), 0.02 x
+Student-t(3), seed 1, already resident in HBM.  One step is one pass of the row-wise hot path
+over it for each of MX9, MX6 and MX4: quantize to the packed planes, then dequantize back to
+FP32 (six kernels).  The headline value is the algorithmic traffic of a step divided by its
+wall time: 2 * n * (4 + bits/8) bytes per format.
+
+Prints ONE JSON line.  Besides the contract keys it carries
+  roofline      HBM roofline of the dominant kernel (the MX6 quantize), timed with device
+                events around each of its launches inside the timed region;
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload;
+  other         separately timed legs: fused round trip, QSNR sweep, column-wise quantize,
+                mx_gemm (whatever the library implements), not part of `value`.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
+N_ELEMS = 1 << 28
+COLS = 4096
+FORMATS = ("MX9", "MX6", "MX4")
+
+
+def alg_bytes(n, bits, elem_bytes=4):
+    """Algorithmic bytes of one direction: the tensor once plus its packed image once."""
+    return n * (elem_bytes + bits / 8.0)
+
+
+def cpu_baseline(sample_elems, threads):
+    """The oracle as it stands, on the first `sample_elems` of the same tensor recipe, the same
+    step (quantize + dequantize for MX9, MX6, MX4), rows split over `threads` host threads."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle as O
+    import synth_inputs as S
+
+    x = S.bandwidth(sample_elems, COLS, device="cpu").numpy()
+    rows = x.shape[0]
+    parts = [x[i * rows // threads:(i + 1) * rows // threads] for i in range(threads)]
+    parts = [np.ascontiguousarray(p) for p in parts if p.shape[0]]
+    fmts = (O.MX9, O.MX6, O.MX4)
+
+    def work(p):
+        for f in fmts:
+            planes = O.quantize(f, p)
+            O.dequantize(f, *planes, *p.shape)
+
+    O.lib()
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=len(parts)) as ex:
+        list(ex.map(work, parts))
+    dt = time.perf_counter() - t0
+    nbytes = sum(2 * alg_bytes(sample_elems, b) for b in (9, 6, 4))
+    return {
+        "value": nbytes / dt / 1e9, "unit": "GB/s", "cores": len(parts), "kind": "oracle",
+        "sample": "first %d elements of the same tensor recipe, same step (MX9+MX6+MX4 quantize"
+                  " and dequantize), %.1f s wall" % (sample_elems, dt),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other", action="store_true", help="skip the separately timed legs")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 25)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (every shard of the path is "
+                 "independent; see DESIGN.md); run with --gpus 1")
+
+    import torch
+
+    import paper_2302_08007_amd as B
+    import synth_inputs as S
+
+    torch.cuda.set_device(0)
+    x = S.bandwidth(N_ELEMS, COLS, device="cuda")
+    rows, cols = x.shape
+    y = torch.empty_like(x)
+    planes = {n: B.alloc_planes(getattr(B, n), rows, cols) for n in FORMATS}
+    fm = {n: getattr(B, n) for n in FORMATS}
+    bits = {"MX9": 9, "MX6": 6, "MX4": 4}
+    q6_events = []
+
+    def step(record):
+        # all three quantizes, then all three dequantizes: alternating a read-heavy and a
+        # write-heavy kernel makes each wait for the other's write-back
+        for n in FORMATS:
+            if record and n == "MX6":
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                B.bdr_quantize(fm[n], x, out=planes[n])
+                b.record()
+                q6_events.append((a, b))
+            else:
+                B.bdr_quantize(fm[n], x, out=planes[n])
+        for n in FORMATS:
+            B.bdr_dequantize(fm[n], planes[n], rows, cols, out=y)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    step_bytes = sum(2 * alg_bytes(N_ELEMS, bits[n]) for n in FORMATS)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    q6_ms = sorted(a.elapsed_time(b) for a, b in q6_events)
+    q6_avg = sum(q6_ms) / len(q6_ms)
+    q6_bytes = alg_bytes(N_ELEMS, 6)
+    achieved = q6_bytes / (q6_avg * 1e-3) / 1e9
+    roofline = {
+        "kernel": "mx_quantize_row_kernel<4, float> (MX6 quantize, fp32 in)",
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "algorithmic_bytes_per_launch": q6_bytes, "avg_launch_us": round(q6_avg * 1e3, 2),
+        "traffic": measured_traffic(),
+    }
+
+    def timed(fn, reps=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            b.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sum(ts) / len(ts)
+
+    other = {}
+    if not args.no_other:
+        per = {}
+        for n in FORMATS:
+            tq = timed(lambda: B.bdr_quantize(fm[n], x, out=planes[n]))
+            td = timed(lambda: B.bdr_dequantize(fm[n], planes[n], rows, cols, out=y))
+            tf = timed(lambda: B.bdr_quantize_dequantize(fm[n], x, out=y))
+            ab = alg_bytes(N_ELEMS, bits[n])
+            per[n] = {
+                "quantize_GBps": round(ab / tq / 1e6, 1), "quantize_frac": round(ab / tq / 1e6 / HBM_PEAK_GBS, 4),
+                "dequantize_GBps": round(ab / td / 1e6, 1), "dequantize_frac": round(ab / td / 1e6 / HBM_PEAK_GBS, 4),
+                "fused_roundtrip_GBps": round(8.0 * N_ELEMS / tf / 1e6, 1),
+                "fused_roundtrip_frac": round(8.0 * N_ELEMS / tf / 1e6 / HBM_PEAK_GBS, 4),
+                "quantize_Gelem_s": round(N_ELEMS / tq / 1e6, 1),
+            }
+        other["rowwise_fp32_1GiB"] = per
+        del y
+        other.update(other_legs(B, S, torch, timed))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        cpu = cpu_baseline(args.cpu_sample, threads)
+
+    print(json.dumps({
+        "metric": "MX9/MX6/MX4 quantize+dequantize algorithmic GB/s (fp32, row-wise)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "bandwidth: 268,435,456 fp32 (1 GiB), 0.02*Student-t(3), seed 1; "
+                               "step = quantize+dequantize for MX9, MX6, MX4",
+                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+        "roofline": roofline, "cpu_baseline": cpu, "other": other,
+    }))
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/), or None when no such summary has been recorded."""
+    path = os.path.join(ROOT, "profiles", "mx6_quantize_f32_1GiB_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def other_legs(B, S, torch, timed):
+    """QSNR sweep (configs/s), activation-shaped bf16 row/column quantize, mx_gemm (TFLOP/s)."""
+    out = {}
+    try:
+        xs = S.sweep(device="cuda")
+        fmts = [B.fmt(k1, k1 if k2 == 0 else k2, d2, m) for k1 in (8, 16, 32, 64)
+                for k2 in (1, 2, 4, 0) for d2 in (0, 1) for m in (2, 4)]
+        ws = torch.empty(B.lib.bdr_qsnr_sweep_workspace_bytes(len(fmts)), dtype=torch.uint8, device="cuda")
+        res = (torch.empty(64, dtype=torch.float64, device="cuda"),
+               torch.empty(65, dtype=torch.float64, device="cuda"))
+        t = timed(lambda: B.bdr_qsnr_sweep(fmts, xs, workspace=ws, out=res))
+        out["qsnr_sweep_64fmt_16Mi"] = {
+            "ms": round(t, 4), "configs_per_s": round(64 / (t * 1e-3), 1),
+            "Gelem_configs_per_s": round(64 * xs.numel() / (t * 1e-3) / 1e9, 1),
+            "distinct_quantizers": 32}
+        del xs
+    except B.BdrError as e:
+        out["qsnr_sweep_64fmt_16Mi"] = {"error": str(e)}
+    try:
+        # three buffers in rotation so the 192 MiB input is not served from the 256 MB cache
+        xa = [S.activation(device="cuda", seed=3 + i) for i in range(3)]
+        r, c = xa[0].shape
+        ab = alg_bytes(r * c, 9, 2)
+        leg = {}
+        for axis, name in ((B.AXIS_ROW, "row"), (B.AXIS_COL, "col")):
+            pl = B.alloc_planes(B.MX9, r, c, axis)
+            k = [0]
+
+            def run():
+                B.bdr_quantize(B.MX9, xa[k[0] % 3], axis=axis, out=pl)
+                k[0] += 1
+            t = timed(run, reps=12)
+            leg[name] = {"us": round(t * 1e3, 1), "GBps": round(ab / t / 1e6, 1),
+                         "frac": round(ab / t / 1e6 / HBM_PEAK_GBS, 4)}
+        out["activation_bf16_8192x12288_MX9"] = leg
+        del xa
+    except B.BdrError as e:
+        out["activation_bf16_8192x12288_MX9"] = {"error": str(e)}
+    try:
+        M = N = K = 8192
+        A, Bm = S.gemm_operands(M, N, K, device="cuda")
+        pa, pb = B.bdr_quantize(B.MX6, A), B.bdr_quantize(B.MX6, Bm)
+        C = torch.empty(M, N, device="cuda")
+        t = timed(lambda: B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C), reps=5)
+        tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
+        out["mx_gemm_8192_MX6"] = {"ms": round(t, 3), "TFLOPs": round(tf, 1),
+                                   "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4)}
+    except B.BdrError as e:
+        out["mx_gemm_8192_MX6"] = {"error": str(e)}
+    return out
+
+
+if __name__ == "__main__":
+    main()

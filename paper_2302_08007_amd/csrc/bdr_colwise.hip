@@ -1,6 +1,330 @@
+// Column-wise (blocks down the columns) quantize, dequantize and fused round
+// trip for the Table II formats, staged through LDS.
+//
+// MX is a directional format: a tensor must be quantized along the reduction
+// axis, and quantizing does not commute with transposing (Sec. V, "Training").
+// The result here is defined as the row-wise result on the transposed tensor,
+// plane indices included, but the transpose is never materialized: a workgroup
+// brings a 128-row x 64-column tile into LDS with row-contiguous 16-byte loads,
+// each lane then reads one 16-row block of one column out of LDS, quantizes it
+// entirely in registers (the block is in one lane, so no cross-lane reduction is
+// needed), and the eight lanes that hold the eight consecutive blocks of one
+// column write a contiguous run of the packed planes.
+//
+// LDS layout: row-major 16-byte chunks, chunk k of row r stored at position
+// k ^ swz(r) where swz depends only on the block index r / 16.  Lanes of a wave
+// read the same row offset of eight different blocks; the XOR puts those on
+// different banks.
+#include "bdr_device.hpp"
 #include "bdr_internal.hpp"
+
 namespace bdr {
-int quantize_col(const bdr_format &, const void *, int, int64_t, int64_t, int64_t, void *, void *, void *, hipStream_t) { return BDR_ERR_LAUNCH; }
-int dequantize_col(const bdr_format &, const void *, const void *, const void *, int64_t, int64_t, void *, int, int64_t, hipStream_t) { return BDR_ERR_LAUNCH; }
-int qdq_col(const bdr_format &, const void *, void *, int, int64_t, int64_t, int64_t, hipStream_t) { return BDR_ERR_LAUNCH; }
+
+namespace {
+
+constexpr int kTR = 128;       // tile rows = 8 blocks of 16
+constexpr int kTC = 64;        // tile columns
+constexpr int kColThreads = 256;
+
+typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
+
+template <typename T>
+struct TileGeom;
+template <>
+struct TileGeom<uint16_t> {
+    static constexpr int kEPC = 8;               // elements per 16-byte chunk
+    static constexpr int kChunks = kTC / kEPC;   // chunks per tile row
+    __device__ static int swz(int r) { return (r >> 4) & 7; }
+};
+template <>
+struct TileGeom<float> {
+    static constexpr int kEPC = 4;
+    static constexpr int kChunks = kTC / kEPC;
+    __device__ static int swz(int r) { return ((r >> 4) & 7) << 1; }
+};
+
+// byte offset of element (r, c) of the tile in LDS
+template <typename T>
+__device__ __forceinline__ int lds_off(int r, int c)
+{
+    typedef TileGeom<T> G;
+    const int k = c / G::kEPC, e = c % G::kEPC;
+    return (r * G::kChunks + (k ^ G::swz(r))) * 16 + e * (int)sizeof(T);
 }
+
+template <typename T>
+__device__ __forceinline__ void tile_load(const T *__restrict__ x, int64_t ld, int64_t r0,
+                                          int64_t c0, uint8_t *tile)
+{
+    typedef TileGeom<T> G;
+    constexpr int kTotal = kTR * G::kChunks;
+#pragma unroll
+    for (int j = 0; j < kTotal / kColThreads; ++j) {
+        const int q = threadIdx.x + j * kColThreads;
+        const int r = q / G::kChunks, k = q % G::kChunks;
+        const u32x4 v = ldg<true>(
+            reinterpret_cast<const u32x4 *>(x + (r0 + r) * ld + c0 + k * G::kEPC));
+        *reinterpret_cast<u32x4 *>(tile + (r * G::kChunks + (k ^ G::swz(r))) * 16) = v;
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void tile_store(T *__restrict__ y, int64_t ld, int64_t r0, int64_t c0,
+                                           const uint8_t *tile)
+{
+    typedef TileGeom<T> G;
+    constexpr int kTotal = kTR * G::kChunks;
+#pragma unroll
+    for (int j = 0; j < kTotal / kColThreads; ++j) {
+        const int q = threadIdx.x + j * kColThreads;
+        const int r = q / G::kChunks, k = q % G::kChunks;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(tile + (r * G::kChunks + (k ^ G::swz(r))) * 16);
+        stg<true>(v, reinterpret_cast<u32x4 *>(y + (r0 + r) * ld + c0 + k * G::kEPC));
+    }
+}
+
+__device__ __forceinline__ uint32_t lds_get(const uint8_t *tile, int off, float)
+{
+    return *reinterpret_cast<const uint32_t *>(tile + off);
+}
+__device__ __forceinline__ uint32_t lds_get(const uint8_t *tile, int off, uint16_t)
+{
+    return (uint32_t)*reinterpret_cast<const uint16_t *>(tile + off) << 16;
+}
+__device__ __forceinline__ void lds_put(uint8_t *tile, int off, uint32_t bits, float)
+{
+    *reinterpret_cast<uint32_t *>(tile + off) = bits;
+}
+__device__ __forceinline__ void lds_put(uint8_t *tile, int off, uint32_t bits, uint16_t)
+{
+    *reinterpret_cast<uint16_t *>(tile + off) = (uint16_t)(bits >> 16);
+}
+
+// Quantize one whole block held by one lane (Sec. IX: shared exponent from the
+// block maximum, one shift bit per pair, m-bit nearest-even magnitudes).
+// w: the 16 codes packed little-endian, (MB+1) bits each.  yb only when DEQ.
+template <int MB, bool DEQ>
+__device__ __forceinline__ void mx_quant16(const uint32_t (&xb)[16], uint32_t (&w)[4],
+                                           uint32_t &se, uint32_t &tau8, uint32_t (&yb)[16])
+{
+    constexpr int CB = MB + 1;
+    constexpr uint32_t MMASK = (1u << MB) - 1u;
+    constexpr float TOP = (float)MMASK;
+    uint32_t p[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        p[j] = clamp_mag(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask));
+    uint32_t bm = p[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) bm = umax(bm, p[j]);
+    const uint32_t thr = bm & kExpMask;
+    se = bm >> 23;
+    const int c0 = (MB - 1) + 127 - (int)se;
+    w[0] = w[1] = w[2] = w[3] = 0;
+    tau8 = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t t = p[j] < thr ? 1u : 0u;
+        tau8 |= t << j;
+        const int sh = c0 + (int)t;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int i = 2 * j + k;
+            float y = __builtin_fminf(__builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh), TOP);
+            const uint32_t zb = as_u(y + kMagic);
+            const uint32_t code = bfi(MMASK, zb, xb[i] >> (31 - MB));
+            const int off = i * CB;
+            w[off >> 5] |= code << (off & 31);
+            if ((off & 31) + CB > 32) w[(off >> 5) + 1] |= code >> (32 - (off & 31));
+            if (DEQ) {
+                const float v = __builtin_ldexpf(as_f(zb) - kMagic, -sh);
+                yb[i] = bfi(kAbsMask, as_u(v), xb[i]);
+            }
+        }
+    }
+}
+
+template <int MB>
+__device__ __forceinline__ void mx_dequant16(const uint32_t (&w)[4], uint32_t se, uint32_t tau8,
+                                             uint32_t (&yb)[16])
+{
+    constexpr int CB = MB + 1;
+    constexpr uint32_t CMASK = (1u << CB) - 1u, MMASK = (1u << MB) - 1u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int off = i * CB;
+        uint32_t c = w[off >> 5] >> (off & 31);
+        if ((off & 31) + CB > 32) c |= w[(off >> 5) + 1] << (32 - (off & 31));
+        c &= CMASK;
+        const int q = (int)se - 127 - (int)((tau8 >> (i >> 1)) & 1u) - (MB - 1);
+        yb[i] = as_u(__builtin_ldexpf((float)(c & MMASK), q)) | ((c >> MB) << 31);
+    }
+}
+
+// Packed codes of one block <-> global memory.  blk: block index in the codes
+// plane.  Lanes 2p and 2p+1 hold blocks 2p and 2p+1 (blk parity = lane parity);
+// for 5- and 3-bit codes a block is 10 or 6 bytes, so a pair of lanes shares its
+// middle dword and exchanges 16 bits through DPP.
+template <int MB>
+__device__ __forceinline__ void codes_store(uint8_t *codes, int64_t blk, const uint32_t (&w)[4])
+{
+    constexpr int CB = MB + 1;
+    const bool odd = blk & 1;
+    if (CB == 8) {
+        u32x4 v = {w[0], w[1], w[2], w[3]};
+        stg<true>(v, reinterpret_cast<u32x4 *>(codes + 16 * blk));
+    } else if (CB == 5) {
+        const uint32_t ow0 = dpp<kQuadXor1>(w[0]);
+        uint8_t *pb = codes + 20 * (blk >> 1);
+        if (!odd) {
+            u32x3_a4 v = {w[0], w[1], w[2] | (ow0 << 16)};
+            *reinterpret_cast<u32x3_a4 *>(pb) = v;
+        } else {
+            store_pair_a4((w[0] >> 16) | (w[1] << 16), (w[1] >> 16) | (w[2] << 16), pb + 12);
+        }
+    } else {
+        const uint32_t ow0 = dpp<kQuadXor1>(w[0]);
+        uint8_t *pb = codes + 12 * (blk >> 1);
+        if (!odd)
+            store_pair_a4(w[0], w[1] | (ow0 << 16), pb);
+        else
+            *reinterpret_cast<uint32_t *>(pb + 8) = (w[0] >> 16) | (w[1] << 16);
+    }
+}
+
+template <int MB>
+__device__ __forceinline__ void codes_load(const uint8_t *codes, int64_t blk, uint32_t (&w)[4])
+{
+    constexpr int CB = MB + 1;
+    const uint32_t s = 16u * (uint32_t)(blk & 1);
+    w[0] = w[1] = w[2] = w[3] = 0;
+    if (CB == 8) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(codes + 16 * blk);
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else if (CB == 5) {
+        // even block: dwords 0-2 of the pair's five; odd block: dwords 2-4, 16 bits in
+        const u32x3_a4 v = *reinterpret_cast<const u32x3_a4 *>(codes + 20 * (blk >> 1) + 8 * (blk & 1));
+        w[0] = funnel_r(v.y, v.x, s);
+        w[1] = funnel_r(v.z, v.y, s);
+        w[2] = (v.z >> s) & 0xffffu;
+    } else {
+        uint32_t v0, v1;
+        load_pair_a4(codes + 12 * (blk >> 1) + 4 * (blk & 1), v0, v1);
+        w[0] = funnel_r(v1, v0, s);
+        w[1] = (v1 >> s) & 0xffffu;
+    }
+}
+
+// MODE 0 quantize (x -> planes), 1 dequantize (planes -> y), 2 fused (x -> y).
+template <int MB, typename T, int MODE>
+__global__ __launch_bounds__(kColThreads) void mx_col_kernel(
+    const T *x, T *y, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
+    uint8_t *__restrict__ mexp, int64_t rows, int64_t ld)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
+    const int64_t r0 = (int64_t)blockIdx.x * kTR;  // consecutive workgroups walk down the rows:
+    const int64_t c0 = (int64_t)blockIdx.y * kTC;  // their plane writes are adjacent
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = lane & 7, cl = lane >> 3;
+    const int64_t blocks_per_col = rows >> 4;
+
+    if (MODE != 1) {
+        tile_load(x, ld, r0, c0, tile);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int it = 0; it < kTC / 32; ++it) {
+        const int c = 8 * (wave + 4 * it) + cl;  // column inside the tile
+        const int64_t blk = (c0 + c) * blocks_per_col + (r0 >> 4) + b;
+        uint32_t xb[16], yb[16], w[4], se, tau8;
+        if (MODE != 1) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) xb[i] = lds_get(tile, lds_off<T>(16 * b + i, c), T());
+            mx_quant16<MB, MODE == 2>(xb, w, se, tau8, yb);
+        }
+        if (MODE == 0) {
+            codes_store<MB>(codes, blk, w);
+            sexp[blk] = (uint8_t)se;
+            mexp[blk] = (uint8_t)tau8;
+        }
+        if (MODE == 1) {
+            codes_load<MB>(codes, blk, w);
+            mx_dequant16<MB>(w, sexp[blk], mexp[blk], yb);
+        }
+        if (MODE != 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) lds_put(tile, lds_off<T>(16 * b + i, c), yb[i], T());
+        }
+    }
+    if (MODE != 0) {
+        __syncthreads();
+        tile_store(y, ld, r0, c0, tile);
+    }
+}
+
+template <int MB, typename T>
+void launch_col(int mode, const T *x, T *y, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
+                int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
+{
+    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / kTC)), block(kColThreads);
+    if (mode == 0)
+        hipLaunchKernelGGL((mx_col_kernel<MB, T, 0>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
+    else if (mode == 1)
+        hipLaunchKernelGGL((mx_col_kernel<MB, T, 1>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
+    else
+        hipLaunchKernelGGL((mx_col_kernel<MB, T, 2>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
+}
+
+template <typename T>
+int col_dispatch(int mode, const bdr_format &f, const T *x, T *y, uint8_t *codes, uint8_t *sexp,
+                 uint8_t *mexp, int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
+{
+    if (f.m == 7)
+        launch_col<7, T>(mode, x, y, codes, sexp, mexp, rows, cols, ld, s);
+    else if (f.m == 4)
+        launch_col<4, T>(mode, x, y, codes, sexp, mexp, rows, cols, ld, s);
+    else
+        launch_col<2, T>(mode, x, y, codes, sexp, mexp, rows, cols, ld, s);
+    return launch_status();
+}
+
+// The tiled kernels need whole tiles and a grid the hardware accepts.
+bool tiled_ok(const bdr_format &f, int64_t rows, int64_t cols)
+{
+    return is_mx(f) && rows % kTR == 0 && cols % kTC == 0 && cols / kTC <= 65535;
+}
+
+int col_any(int mode, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
+            int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
+{
+    if (!tiled_ok(f, rows, cols))
+        return generic_col(mode, f, x, y, dtype, rows, cols, ld, codes, sexp, mexp, s);
+    if (dtype == BDR_F32)
+        return col_dispatch(mode, f, (const float *)x, (float *)y, (uint8_t *)codes,
+                            (uint8_t *)sexp, (uint8_t *)mexp, rows, cols, ld, s);
+    return col_dispatch(mode, f, (const uint16_t *)x, (uint16_t *)y, (uint8_t *)codes,
+                        (uint8_t *)sexp, (uint8_t *)mexp, rows, cols, ld, s);
+}
+
+}  // namespace
+
+int quantize_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,
+                 int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
+{
+    return col_any(0, f, x, nullptr, dtype, rows, cols, ld, codes, sexp, mexp, s);
+}
+
+int dequantize_col(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+                   int64_t rows, int64_t cols, void *y, int dtype, int64_t ld, hipStream_t s)
+{
+    return col_any(1, f, nullptr, y, dtype, rows, cols, ld, const_cast<void *>(codes),
+                   const_cast<void *>(sexp), const_cast<void *>(mexp), s);
+}
+
+int qdq_col(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
+            int64_t ld, hipStream_t s)
+{
+    return col_any(2, f, x, y, dtype, rows, cols, ld, nullptr, nullptr, nullptr, s);
+}
+
+}  // namespace bdr

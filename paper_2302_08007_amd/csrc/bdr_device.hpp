@@ -100,9 +100,18 @@ __device__ __forceinline__ void store_pair_a4(uint32_t a, uint32_t b, void *p)
 }
 __device__ __forceinline__ void load_pair_a4(const void *p, uint32_t &a, uint32_t &b)
 {
+#if defined(BDR_EXP_DEQ_TWO)
+    a = reinterpret_cast<const uint32_t *>(p)[0];
+    b = reinterpret_cast<const uint32_t *>(p)[1];
+#elif defined(BDR_EXP_DEQ_NT)
+    u32x2_a4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_a4 *>(p));
+    a = v.x;
+    b = v.y;
+#else
     u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(p);
     a = v.x;
     b = v.y;
+#endif
 }
 
 // Load 8 consecutive elements as FP32 bit patterns.

@@ -36,6 +36,11 @@ int dequantize_col(const bdr_format &f, const void *codes, const void *sexp, con
 int qdq_col(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
             int64_t ld, hipStream_t s);
 
+// Column blocks through the general (one element at a time) kernels.
+// what: 0 quantize (x -> planes), 1 dequantize (planes -> y), 2 fused (x -> y).
+int generic_col(int what, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
+                int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s);
+
 size_t sweep_workspace_bytes(int32_t n_fmts);
 int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
                int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,

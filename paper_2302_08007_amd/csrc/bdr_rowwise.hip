@@ -197,6 +197,17 @@ __global__ __launch_bounds__(kThreads) void mx_qdq_row_kernel(const T *x, T *y, 
 }
 
 // ------------------------------------------------------------- generic kernels
+//
+// These see the tensor as a logical [R x C] array with blocks along C, element
+// (r, c) at r * sr + c * sc.  Row blocks: sr = ld, sc = 1 (vector loads).  Column
+// blocks: the transposed view, sr = 1, sc = ld (STRIDED: one element at a time;
+// this is the slow general path, the tiled kernels in bdr_colwise.hip are the
+// fast one).
+
+__device__ __forceinline__ uint32_t load1(const float *p) { return as_u(*p); }
+__device__ __forceinline__ uint32_t load1(const uint16_t *p) { return (uint32_t)*p << 16; }
+__device__ __forceinline__ void store1(float *p, uint32_t b) { *p = as_f(b); }
+__device__ __forceinline__ void store1(uint16_t *p, uint32_t b) { *p = (uint16_t)(b >> 16); }
 
 struct GenFmt {
     int k1, k2, d2, m, rounding;
@@ -257,10 +268,10 @@ __device__ __forceinline__ float gen_round(float ax, int sh, float top, int roun
 }
 
 // MODE 0: write the packed planes.  MODE 1: write the dequantized tensor.
-template <typename T, int MODE>
-__global__ __launch_bounds__(kThreads) void generic_quantize_row_kernel(
+template <typename T, int MODE, bool STRIDED>
+__global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     GenFmt f, const T *x, T *y, uint8_t *__restrict__ codes,
-    uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp, int64_t cols, int64_t ld,
+    uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp, int64_t cols, int64_t sr, int64_t sc,
     int64_t n_groups)
 {
     __shared__ uint32_t s_mexp[kTileElems * 3 / 32 + 1];
@@ -275,8 +286,13 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_row_kernel(
     if (active) {
         const int64_t t0 = 8 * g;
         const int64_t r = t0 / cols;
-        addr = r * ld + (t0 - r * cols);
-        load8(x + addr, xb);
+        addr = r * sr + (t0 - r * cols) * sc;
+        if (STRIDED) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xb[i] = load1(x + addr + i * sc);
+        } else {
+            load8(x + addr, xb);
+        }
     }
     uint32_t pe[8], be[8];
     gen_maxima(f, xb, pe, be);
@@ -297,7 +313,14 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_row_kernel(
         if (MODE == 1) yb[i] = as_u(__builtin_ldexpf(mf, -sh)) | (xb[i] & 0x80000000u);
     }
     if (MODE == 1) {
-        if (active) store8(y + addr, yb);
+        if (active) {
+            if (STRIDED) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) store1(y + addr + i * sc, yb[i]);
+            } else {
+                store8(y + addr, yb);
+            }
+        }
         return;
     }
 
@@ -362,11 +385,11 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_row_kernel(
         mp[b] = (uint8_t)(s_mexp[b >> 2] >> (8 * (b & 3)));
 }
 
-template <typename T>
-__global__ __launch_bounds__(kThreads) void generic_dequantize_row_kernel(
+template <typename T, bool STRIDED>
+__global__ __launch_bounds__(kThreads) void generic_dequantize_kernel(
     GenFmt f, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, int64_t mexp_bytes, T *__restrict__ y, int64_t cols,
-    int64_t ld, int64_t n_groups)
+    int64_t sr, int64_t sc, int64_t n_groups)
 {
     const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (g >= n_groups) return;
@@ -405,7 +428,13 @@ __global__ __launch_bounds__(kThreads) void generic_dequantize_row_kernel(
     }
     const int64_t t0 = 8 * g;
     const int64_t r = t0 / cols;
-    store8(y + r * ld + (t0 - r * cols), yb);
+    const int64_t addr = r * sr + (t0 - r * cols) * sc;
+    if (STRIDED) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store1(y + addr + i * sc, yb[i]);
+    } else {
+        store8(y + addr, yb);
+    }
 }
 
 // -------------------------------------------------------------------- launchers
@@ -441,8 +470,8 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
         else
             hipLaunchKernelGGL((mx_quantize_row_kernel<2, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
     } else {
-        hipLaunchKernelGGL((generic_quantize_row_kernel<T, 0>), grid, block, 0, s, gen_of(f), x,
-                           (T *)nullptr, codes, sexp, mexp, cols, ld, ng);
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false>), grid, block, 0, s, gen_of(f), x,
+                           (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
     }
     return launch_status();
 }
@@ -473,8 +502,8 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
             hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
     } else {
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
-        hipLaunchKernelGGL((generic_dequantize_row_kernel<T>), grid, block, 0, s, gen_of(f), codes,
-                           sexp, mexp, mexp_bytes, y, cols, ld, ng);
+        hipLaunchKernelGGL((generic_dequantize_kernel<T, false>), grid, block, 0, s, gen_of(f),
+                           codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
     }
     return launch_status();
 }
@@ -503,8 +532,9 @@ static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_
         else
             hipLaunchKernelGGL((mx_qdq_row_kernel<2, T>), grid, block, 0, s, x, y, ng);
     } else {
-        hipLaunchKernelGGL((generic_quantize_row_kernel<T, 1>), grid, block, 0, s, gen_of(f), x, y,
-                           (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols, ld, ng);
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false>), grid, block, 0, s, gen_of(f), x,
+                           y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols, ld,
+                           (int64_t)1, ng);
     }
     return launch_status();
 }
@@ -514,6 +544,38 @@ int qdq_row(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows
 {
     if (dtype == BDR_F32) return qdq_row_t(f, (const float *)x, (float *)y, rows, cols, ld, s);
     return qdq_row_t(f, (const uint16_t *)x, (uint16_t *)y, rows, cols, ld, s);
+}
+
+// Column blocks through the generic kernels: the transposed view [cols x rows].
+template <typename T>
+static int generic_col_t(int what, const bdr_format &f, const T *x, T *y, int64_t rows,
+                         int64_t cols, int64_t ld, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
+                         hipStream_t s)
+{
+    const int64_t ng = rows * cols / 8;
+    const dim3 grid(blocks_for(ng)), block(kThreads);
+    if (what == 0)
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 0, true>), grid, block, 0, s, gen_of(f), x,
+                           (T *)nullptr, codes, sexp, mexp, rows, (int64_t)1, ld, ng);
+    else if (what == 1)
+        hipLaunchKernelGGL((generic_dequantize_kernel<T, true>), grid, block, 0, s, gen_of(f),
+                           codes, sexp, mexp, (rows * cols / f.k2 * f.d2 + 7) / 8, y, rows,
+                           (int64_t)1, ld, ng);
+    else
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 1, true>), grid, block, 0, s, gen_of(f), x,
+                           y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, rows,
+                           (int64_t)1, ld, ng);
+    return launch_status();
+}
+
+int generic_col(int what, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
+                int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
+{
+    if (dtype == BDR_F32)
+        return generic_col_t(what, f, (const float *)x, (float *)y, rows, cols, ld,
+                             (uint8_t *)codes, (uint8_t *)sexp, (uint8_t *)mexp, s);
+    return generic_col_t(what, f, (const uint16_t *)x, (uint16_t *)y, rows, cols, ld,
+                         (uint8_t *)codes, (uint8_t *)sexp, (uint8_t *)mexp, s);
 }
 
 }  // namespace bdr

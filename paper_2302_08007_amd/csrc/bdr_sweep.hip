@@ -41,7 +41,8 @@ constexpr int kMaxBlocks = 2048;
 constexpr int kChunk = 256;  // formats per launch: keeps the kernel arguments under 4 KiB
 constexpr int kMaxClasses = kChunk;
 constexpr int kMaxQuant = kChunk;
-constexpr size_t kHeaderBytes = 256;
+constexpr size_t kHeaderBytes = 256;                            // Header
+constexpr size_t kTotalsBytes = 4096 - 256;                     // kChunk + 1 doubles fit
 
 struct ClassDesc {
     uint8_t lk1, lk2, beta, nq;  // log2 k1, log2 k2, 2^d2 - 1, quantizers in the class
@@ -65,10 +66,13 @@ struct Header {
 
 __global__ void sweep_clear_kernel(Header *h) { h->absmax_bits = 0; }
 
+// Largest magnitude of the tensor.  Only its exponent is used, so a block whose
+// maximum does not raise the exponent already recorded skips the atomic.
 template <typename T>
 __global__ __launch_bounds__(256) void sweep_absmax_kernel(const T *__restrict__ x, int64_t cols,
                                                            int64_t ld, int64_t n_groups, Header *h)
 {
+    __shared__ uint32_t s_m[4];
     uint32_t m = 0;
     for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < n_groups;
          g += (int64_t)gridDim.x * 256) {
@@ -80,20 +84,34 @@ __global__ __launch_bounds__(256) void sweep_absmax_kernel(const T *__restrict__
         for (int i = 0; i < 8; ++i) m = umax(m, xb[i] & kAbsMask);
     }
     for (int w = 32; w > 0; w >>= 1) m = umax(m, (uint32_t)__shfl_xor((int)m, w));
-    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(&h->absmax_bits, m);
+    if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = umax(umax(s_m[0], s_m[1]), umax(s_m[2], s_m[3]));
+        const uint32_t seen = __atomic_load_n(&h->absmax_bits, __ATOMIC_RELAXED);
+        if ((m >> 23) > (seen >> 23)) atomicMax(&h->absmax_bits, m);
+    }
 }
 
-// Exponent fields of the maxima over aligned groups, for one run of 8 elements.
+// Scaling exponents 127 - e of the maxima over aligned groups, for one run of 8
+// elements, as signed bytes (127 - e lies in [-127, 126]):
+//   w[0], w[1]  per element            w[2]  per pair
+//   w[3]        per 4 (bytes 0-1), per 8 and per 16 (bytes 2-3)
+//   w[4]        per 32, 64, 128, 256
 struct Levels {
-    uint32_t e0[8];  // per element
-    uint32_t e1[4];  // per pair
-    uint32_t e2[2];  // per 4
-    uint32_t eL[6];  // per 8, 16, 32, 64, 128, 256 (lane and across lanes)
+    uint32_t w[5];
 };
+
+__device__ __forceinline__ uint32_t neg_exp_byte(uint32_t mag) { return (127u - (mag >> 23)) & 0xffu; }
+
+__device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    return a | (b << 8) | (c << 16) | (d << 24);
+}
 
 __device__ __forceinline__ void build_levels(const uint32_t (&ab)[8], uint32_t mag_lo, Levels &L)
 {
-    uint32_t p0[8], p1[4], p2[2];
+    uint32_t p0[8], p1[4], p2[2], pl[6];
 #pragma unroll
     for (int i = 0; i < 8; ++i) p0[i] = umin(umax(ab[i], mag_lo), kMagHi);
 #pragma unroll
@@ -101,72 +119,82 @@ __device__ __forceinline__ void build_levels(const uint32_t (&ab)[8], uint32_t m
 #pragma unroll
     for (int i = 0; i < 2; ++i) p2[i] = umax(p1[2 * i], p1[2 * i + 1]);
     uint32_t v = umax(p2[0], p2[1]);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) L.e0[i] = p0[i] >> 23;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) L.e1[i] = p1[i] >> 23;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) L.e2[i] = p2[i] >> 23;
-    L.eL[0] = v >> 23;
+    pl[0] = v;
     v = umax(v, dpp<kQuadXor1>(v));
-    L.eL[1] = v >> 23;
+    pl[1] = v;
     v = umax(v, dpp<kQuadXor2>(v));
-    L.eL[2] = v >> 23;
+    pl[2] = v;
     v = umax(v, dpp<kRowHalfMirror>(v));
-    L.eL[3] = v >> 23;
+    pl[3] = v;
     v = umax(v, dpp<kRowMirror>(v));
-    L.eL[4] = v >> 23;
+    pl[4] = v;
     v = umax(v, (uint32_t)__shfl_xor((int)v, 16));
-    L.eL[5] = v >> 23;
+    pl[5] = v;
+    L.w[0] = pack4(neg_exp_byte(p0[0]), neg_exp_byte(p0[1]), neg_exp_byte(p0[2]), neg_exp_byte(p0[3]));
+    L.w[1] = pack4(neg_exp_byte(p0[4]), neg_exp_byte(p0[5]), neg_exp_byte(p0[6]), neg_exp_byte(p0[7]));
+    L.w[2] = pack4(neg_exp_byte(p1[0]), neg_exp_byte(p1[1]), neg_exp_byte(p1[2]), neg_exp_byte(p1[3]));
+    L.w[3] = pack4(neg_exp_byte(p2[0]), neg_exp_byte(p2[1]), neg_exp_byte(pl[0]), neg_exp_byte(pl[1]));
+    L.w[4] = pack4(neg_exp_byte(pl[2]), neg_exp_byte(pl[3]), neg_exp_byte(pl[4]), neg_exp_byte(pl[5]));
 }
 
-// Exponent of the level-`lk` group that element i of the run belongs to.
+__device__ __forceinline__ int sbyte(uint32_t w, int idx)
+{
+    return __builtin_amdgcn_sbfe((int)w, 8 * idx, 8);
+}
+
+// 127 - e for a group of 8 or more elements (lk >= 3): one value per lane.
+__device__ __forceinline__ int lane_level(const Levels &L, int lk)
+{
+    const uint64_t both = ((uint64_t)L.w[4] << 32) | L.w[3];
+    return (int)(int8_t)(both >> (8 * (lk - 1)));  // lk = 3 is byte 2 of w[3]
+}
+
+// 127 - e of the level-lk group each of the 8 elements belongs to.
 __device__ __forceinline__ void level_exps(const Levels &L, int lk, int (&out)[8])
 {
     if (lk == 0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = (int)L.e0[i];
+        for (int i = 0; i < 8; ++i) out[i] = sbyte(L.w[i >> 2], i & 3);
     } else if (lk == 1) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = (int)L.e1[i >> 1];
+        for (int i = 0; i < 8; ++i) out[i] = sbyte(L.w[2], i >> 1);
     } else if (lk == 2) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = (int)L.e2[i >> 2];
+        for (int i = 0; i < 8; ++i) out[i] = sbyte(L.w[3], i >> 2);
     } else {
-        uint32_t v = L.eL[0];
+        const int v = lane_level(L, lk);
 #pragma unroll
-        for (int l = 1; l < 6; ++l) v = (lk - 3 == l) ? L.eL[l] : v;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = (int)v;
+        for (int i = 0; i < 8; ++i) out[i] = v;
     }
 }
 
+// Squared error of one quantizer summed over the lane's kG*8 elements, in the
+// tensor's (pre-scaled) units.  yp = |x| * 2^sh lies in [0, 2) with the top
+// magnitude bit at weight 2^0; nsh = -sh.
+//   nearest-even: adding 2^(24-m) to a value in [0, 2) rounds it to a multiple
+//   of 2^-(m-1), which is the step of an m-bit magnitude at that weight.
 template <int ROUNDING>
-__device__ __forceinline__ float round_mode(float y)
+__device__ __forceinline__ float quant_err2(const float (&yp)[kG][8], const int (&nsh)[kG][8], int m)
 {
-    if (ROUNDING == BDR_RNE) return __builtin_rintf(y);
-    const float t = __builtin_truncf(y);
-    if (ROUNDING == BDR_RNA) return (y - t) >= 0.5f ? t + 1.0f : t;
-    return t;
-}
-
-// Sum over the lane's kG*8 elements of the squared quantization error of one
-// quantizer, given the per-element scaling exponents of its class.
-template <int ROUNDING>
-__device__ __forceinline__ float quant_err2(const float (&ax)[kG][8], const int (&shb)[kG][8],
-                                            int m)
-{
-    const float top = (float)((1u << m) - 1u);
+    const float step = __builtin_ldexpf(1.0f, 1 - m);
+    const float top = 2.0f - step;
+    const float magic = __builtin_ldexpf(1.0f, 24 - m);
     float acc = 0.f;
 #pragma unroll
     for (int j = 0; j < kG; ++j)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int sh = shb[j][i] + (m - 1);
-            const float y = __builtin_fminf(__builtin_ldexpf(ax[j][i], sh), top);
-            // scaled |x| minus its rounded (or held) magnitude: exact
-            const float yy = __builtin_ldexpf(ax[j][i], sh);
-            const float d = __builtin_ldexpf(yy - round_mode<ROUNDING>(y), -sh);
+            const float y = __builtin_fminf(yp[j][i], top);  // held at the top code
+            float r;
+            if (ROUNDING == BDR_RNE) {
+                r = (y + magic) - magic;
+            } else {
+                const float sc = __builtin_ldexpf(y, m - 1);
+                const float t = __builtin_truncf(sc);
+                const float up = (ROUNDING == BDR_RNA && (sc - t) >= 0.5f) ? 1.0f : 0.0f;
+                r = __builtin_ldexpf(t + up, 1 - m);
+            }
+            const float d = __builtin_ldexpf(yp[j][i] - r, nsh[j][i]);  // difference is exact
             acc = __builtin_fmaf(d, d, acc);
         }
     return acc;
@@ -230,27 +258,30 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
 
         for (int c = 0; c < plan.n_class; ++c) {
             const ClassDesc cd = plan.cls[c];
-            int shb[kG][8];
+            // sh = 127 - max(E_block - beta, E_sub) = min(127 - E_block + beta, 127 - E_sub)
+            float yp[kG][8];
+            int nsh[kG][8];
 #pragma unroll
             for (int j = 0; j < kG; ++j) {
-                int eb[8], es[8];
-                level_exps(L[j], cd.lk1, eb);
-                level_exps(L[j], cd.lk2, es);
+                int cb[8], cs[8];
+                level_exps(L[j], cd.lk1, cb);
+                level_exps(L[j], cd.lk2, cs);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int eps = max(eb[i] - (int)cd.beta, es[i]);
-                    shb[j][i] = 127 - eps;
+                    const int sh = min(cb[i] + (int)cd.beta, cs[i]);
+                    yp[j][i] = __builtin_ldexpf(ax[j][i], sh);
+                    nsh[j][i] = -sh;
                 }
             }
             for (int k = 0; k < cd.nq; ++k) {
                 const QuantDesc qd = plan.q[cd.first + k];
                 float e2;
                 if (qd.rounding == BDR_RNE)
-                    e2 = quant_err2<BDR_RNE>(ax, shb, qd.m);
+                    e2 = quant_err2<BDR_RNE>(yp, nsh, qd.m);
                 else if (qd.rounding == BDR_RNA)
-                    e2 = quant_err2<BDR_RNA>(ax, shb, qd.m);
+                    e2 = quant_err2<BDR_RNA>(yp, nsh, qd.m);
                 else
-                    e2 = quant_err2<BDR_RTZ>(ax, shb, qd.m);
+                    e2 = quant_err2<BDR_RTZ>(yp, nsh, qd.m);
                 e2 = wave_sum(e2);
                 if (lane == 0) wacc[cd.first + k] += (double)e2;
             }
@@ -264,26 +295,39 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
     }
 }
 
-__global__ __launch_bounds__(256) void sweep_finalize_kernel(
-    FormatMap map, int32_t n_fmts, int32_t n_quant, int32_t n_blocks,
-    const Header *__restrict__ hdr, const double *__restrict__ partials,
-    double *__restrict__ qsnr_db, double *__restrict__ sums, double *sig_out)
+// Column t of the per-block partial sums, added up in a fixed order: lane i takes
+// blocks i, i + 256, ... and the 256 lane sums go through a fixed tree.
+__global__ __launch_bounds__(256) void sweep_reduce_kernel(int32_t n_quant, int32_t n_blocks,
+                                                           const double *__restrict__ partials,
+                                                           double *__restrict__ totals)
 {
-    extern __shared__ double s_tot[];  // [n_quant + 1], in the tensor's own scale
+    __shared__ double s_v[256];
+    const int t = blockIdx.x;
+    double v = 0.0;
+    for (int b = threadIdx.x; b < n_blocks; b += 256) v += partials[(int64_t)b * (n_quant + 1) + t];
+    s_v[threadIdx.x] = v;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) s_v[threadIdx.x] += s_v[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) totals[t] = s_v[0];
+}
+
+__global__ __launch_bounds__(256) void sweep_finalize_kernel(
+    FormatMap map, int32_t n_fmts, int32_t n_quant, const Header *__restrict__ hdr,
+    const double *__restrict__ totals, double *__restrict__ qsnr_db, double *__restrict__ sums,
+    double *sig_out)
+{
+    // undo the pre-scale: sums were taken on x * 2^(127 - eref)
     const int eref = (int)(umin(umax(hdr->absmax_bits, kMagLo), kMagHi) >> 23);
     const double unscale = __builtin_ldexp(1.0, -2 * (127 - eref));
-    for (int t = threadIdx.x; t <= n_quant; t += blockDim.x) {
-        double v = 0.0;
-        for (int b = 0; b < n_blocks; ++b) v += partials[(int64_t)b * (n_quant + 1) + t];
-        s_tot[t] = v * unscale;
-    }
-    __syncthreads();
-    const double sig = s_tot[n_quant];
+    const double sig = totals[n_quant] * unscale;
     for (int f = threadIdx.x; f <= n_fmts; f += blockDim.x) {
         if (f == n_fmts) {
             *sig_out = sig;
         } else {
-            const double err = s_tot[map.idx[f]];
+            const double err = totals[map.idx[f]] * unscale;
             sums[f] = err;
             qsnr_db[f] = err > 0.0 ? 10.0 * log10(sig / err) : __builtin_inf();
         }
@@ -297,7 +341,7 @@ inline int ilog2(int v) { return __builtin_ctz((unsigned)v); }
 size_t sweep_workspace_bytes(int32_t n_fmts)
 {
     const int per_launch = n_fmts < kChunk ? n_fmts : kChunk;
-    return kHeaderBytes + (size_t)kMaxBlocks * (size_t)(per_launch + 1) * sizeof(double);
+    return kHeaderBytes + kTotalsBytes + (size_t)kMaxBlocks * (size_t)(per_launch + 1) * sizeof(double);
 }
 
 namespace {
@@ -367,7 +411,10 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
 {
     static_assert(sizeof(SweepPlan) + 64 < 4096, "kernel arguments must stay under 4 KiB");
     Header *hdr = reinterpret_cast<Header *>(workspace);
-    double *partials = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes);
+    static_assert((kChunk + 1) * sizeof(double) <= kTotalsBytes, "totals area too small");
+    double *totals = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes);
+    double *partials = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes +
+                                                  kTotalsBytes);
     const int64_t n_groups = rows * cols / 8;
     const int64_t per_block = (int64_t)kSweepThreads * kG;
     int64_t nb = (n_groups + per_block - 1) / per_block;
@@ -377,7 +424,7 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
     hipLaunchKernelGGL(sweep_clear_kernel, dim3(1), dim3(1), 0, s, hdr);
     if (n_groups > 0) {
         const int64_t want = (n_groups + 255) / 256;
-        const unsigned ab = (unsigned)(want < 4096 ? want : 4096);
+        const unsigned ab = (unsigned)(want < 1024 ? want : 1024);
         if (dtype == BDR_F32)
             hipLaunchKernelGGL(sweep_absmax_kernel<float>, dim3(ab), dim3(256), 0, s,
                                (const float *)x, cols, ld, n_groups, hdr);
@@ -401,9 +448,10 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
             hipLaunchKernelGGL(sweep_kernel<uint16_t>, dim3((unsigned)nb), dim3(kSweepThreads),
                                lds, s, plan, (const uint16_t *)x, cols, ld, n_groups, hdr,
                                partials);
-        hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(256),
-                           (size_t)(nq + 1) * sizeof(double), s, map, nf, nq, (int32_t)nb, hdr,
-                           partials, qsnr_db + f0, sums + f0, sums + n_fmts);
+        hipLaunchKernelGGL(sweep_reduce_kernel, dim3((unsigned)(nq + 1)), dim3(256), 0, s, nq,
+                           (int32_t)nb, partials, totals);
+        hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(256), 0, s, map, nf, nq, hdr,
+                           totals, qsnr_db + f0, sums + f0, sums + n_fmts);
     }
     return launch_status();
 }

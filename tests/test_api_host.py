@@ -1,0 +1,139 @@
+"""Host-side tests of the C ABI: the library loads, exports what include/bdr_mx.h declares, and
+every argument check answers with the right status before anything is launched (no GPU needed:
+none of these calls reaches a kernel)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle as O
+import paper_2302_08007_amd as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x10000)       # 16-byte aligned, never dereferenced on the host
+FAKE_ODD = ctypes.c_void_p(0x10004)
+NULL = ctypes.c_void_p(0)
+OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_LAUNCH, ERR_WS = range(8)
+
+
+def test_exports_match_header():
+    text = open(os.path.join(ROOT, "include", "bdr_mx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(bdr_\w+|mx_gemm)\s*\(", text))
+    names -= {"bdr_format"}
+    assert names == set(B.EXPORTS)
+    for n in names:
+        assert getattr(B.lib, n) is not None
+
+
+def test_status_strings():
+    seen = {B.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and B.status_string(99) == "unknown status"
+
+
+def test_format_validate():
+    assert B.bdr_format_validate(B.MX9) == OK
+    assert B.lib.bdr_format_validate(None) == ERR_NULL
+    for bad in (B.fmt(12, 2, 1, 4), B.fmt(16, 3, 1, 4), B.fmt(16, 32, 1, 4), B.fmt(16, 2, 4, 4),
+                B.fmt(16, 2, -1, 4), B.fmt(16, 2, 1, 0), B.fmt(16, 2, 1, 9), B.fmt(512, 2, 1, 4),
+                B.fmt(16, 2, 1, 4, d1=7), B.fmt(16, 2, 1, 4, rounding=3)):
+        assert B.bdr_format_validate(bad) == ERR_FORMAT, bad
+    for good in (B.fmt(1, 1, 0, 1), B.fmt(256, 256, 3, 8, rounding=B.RTZ), B.fmt(64, 1, 2, 5)):
+        assert B.bdr_format_validate(good) == OK, good
+
+
+@pytest.mark.parametrize("f", [B.MX9, B.MX6, B.MX4, B.fmt(64, 4, 1, 4), B.fmt(8, 1, 3, 2),
+                               B.fmt(256, 128, 1, 8), B.fmt(2, 1, 1, 3)], ids=repr)
+def test_packed_sizes_formula_and_oracle(f):
+    rows, cols = 256, 1024
+    nc, ns, nm = B.bdr_packed_sizes(f, rows, cols)
+    n = rows * cols
+    # Sec. III: (m + 1) + d1 / k1 + d2 / k2 bits per element
+    assert 8 * nc == n * (f.m + 1) and 8 * ns == n * 8 // f.k1 and 8 * nm == n * f.d2 // f.k2
+    assert (nc, ns, nm) == O.packed_sizes(O.Format(f.k1, f.d1, f.k2, f.d2, f.m, f.rounding), rows, cols)
+    assert B.bdr_packed_sizes(f, rows, cols, B.AXIS_COL) == B.bdr_packed_sizes(f, cols, rows)
+    # Table II: 9, 6 and 4 bits per element
+    if f.k1 == 16 and f.k2 == 2 and f.d2 == 1:
+        assert 8 * (nc + ns + nm) == n * (f.m + 2)
+
+
+def test_packed_sizes_errors():
+    with pytest.raises(B.BdrError) as e:
+        B.bdr_packed_sizes(B.MX6, 4, 24)           # not a multiple of k1
+    assert e.value.status == ERR_SHAPE
+    with pytest.raises(B.BdrError):
+        B.bdr_packed_sizes(B.fmt(4, 2, 1, 3), 4, 12)   # not a multiple of 8
+    with pytest.raises(B.BdrError):
+        B.bdr_packed_sizes(B.MX6, -1, 16)
+    with pytest.raises(B.BdrError):
+        B.bdr_packed_sizes(B.MX6, 16, 16, 2)
+    assert B.bdr_packed_sizes(B.MX6, 0, 16) == (0, 0, 0)
+
+
+def _q(f, x=FAKE, dtype=0, rows=4, cols=64, ld=64, axis=0, codes=FAKE, sexp=FAKE, mexp=FAKE):
+    return B.lib.bdr_quantize(ctypes.byref(f), x, dtype, rows, cols, ld, axis, codes, sexp, mexp, NULL)
+
+
+def test_quantize_argument_checks():
+    f = B.MX6
+    assert B.lib.bdr_quantize(None, FAKE, 0, 4, 64, 64, 0, FAKE, FAKE, FAKE, NULL) == ERR_NULL
+    assert _q(B.fmt(16, 2, 1, 12)) == ERR_FORMAT
+    assert _q(f, dtype=2) == ERR_DTYPE
+    assert _q(f, axis=5) == ERR_SHAPE
+    assert _q(f, cols=40, ld=40) == ERR_SHAPE            # 40 % 16 != 0
+    assert _q(f, ld=32) == ERR_SHAPE                     # ld < cols
+    assert _q(f, rows=-1) == ERR_SHAPE
+    assert _q(f, rows=6, axis=1) == ERR_SHAPE            # blocked axis = rows
+    assert _q(f, rows=1 << 30, cols=1 << 20, ld=1 << 20) == ERR_SHAPE   # too large
+    assert _q(f, x=NULL) == ERR_NULL
+    assert _q(f, codes=NULL) == ERR_NULL
+    assert _q(f, mexp=NULL) == ERR_NULL
+    assert _q(B.fmt(16, 16, 0, 4), mexp=NULL, x=FAKE_ODD) == ERR_ALIGN    # mexp may be NULL for d2 = 0
+    assert _q(f, x=FAKE_ODD) == ERR_ALIGN
+    assert _q(f, ld=66) == ERR_ALIGN                     # pitch not a multiple of 16 bytes
+    assert _q(f, sexp=FAKE_ODD) == ERR_ALIGN
+    assert _q(f, rows=0) == OK                           # empty: nothing to launch
+    assert _q(f, rows=0, x=NULL, codes=NULL, sexp=NULL, mexp=NULL) == OK
+
+
+def test_dequantize_and_fused_argument_checks():
+    L, f = B.lib, B.MX6
+    deq = lambda f, y=FAKE, dtype=0, rows=4, cols=64, ld=64: L.bdr_dequantize(
+        ctypes.byref(f), FAKE, FAKE, FAKE, rows, cols, 0, y, dtype, ld, NULL)
+    assert deq(f, y=NULL) == ERR_NULL
+    assert deq(f, y=FAKE_ODD) == ERR_ALIGN
+    assert deq(f, cols=8, ld=8) == ERR_SHAPE
+    assert deq(B.fmt(16, 2, 2, 7), dtype=1) == ERR_DTYPE         # m + beta = 10 > 8: not exact in bf16
+    assert deq(B.fmt(16, 2, 3, 2), dtype=1) == ERR_DTYPE
+    assert deq(f, rows=0) == OK
+    qdq = lambda f, x=FAKE, y=FAKE, dtype=0: L.bdr_quantize_dequantize(
+        ctypes.byref(f), x, y, dtype, 4, 64, 64, 0, NULL)
+    assert qdq(f, x=NULL) == ERR_NULL and qdq(f, y=NULL) == ERR_NULL
+    assert qdq(B.fmt(8, 2, 3, 8), dtype=1) == ERR_DTYPE
+    assert qdq(f, dtype=7) == ERR_DTYPE
+
+
+def test_sweep_and_gemm_argument_checks():
+    L = B.lib
+    arr = (B.Format * 2)(B.MX6, B.fmt(64, 4, 1, 4))
+    need = L.bdr_qsnr_sweep_workspace_bytes(2)
+    assert need > 0 and L.bdr_qsnr_sweep_workspace_bytes(0) == 0
+    assert L.bdr_qsnr_sweep_workspace_bytes(2000) == 0
+    sw = lambda n=2, x=FAKE, cols=64, q=FAKE, s=FAKE, ws=FAKE, wsb=need: L.bdr_qsnr_sweep(
+        arr, n, x, 0, 4, cols, cols, q, s, ws, wsb, NULL)
+    assert L.bdr_qsnr_sweep(None, 2, FAKE, 0, 4, 64, 64, FAKE, FAKE, FAKE, need, NULL) == ERR_NULL
+    assert sw(n=0) == ERR_SHAPE
+    assert sw(cols=32) == ERR_SHAPE                      # 32 % 64 != 0 for the second format
+    assert sw(q=NULL) == ERR_NULL
+    assert sw(ws=NULL) == ERR_WS and sw(wsb=need - 1) == ERR_WS
+    assert sw(x=NULL) == ERR_NULL
+    assert sw(s=FAKE_ODD) == ERR_ALIGN
+    f = B.MX6
+    gm = lambda fa=f, fb=f, M=128, N=128, K=64, C=FAKE, ldc=128, a=FAKE: L.mx_gemm(
+        ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, C, ldc, NULL)
+    assert gm(fa=B.fmt(32, 2, 1, 4)) == ERR_FORMAT
+    assert gm(M=100) == ERR_SHAPE and gm(K=48) == ERR_SHAPE and gm(ldc=64) == ERR_SHAPE
+    assert gm(C=NULL) == ERR_NULL and gm(a=NULL) == ERR_NULL
+    assert gm(C=FAKE_ODD) == ERR_ALIGN
+    assert gm(M=0) == OK

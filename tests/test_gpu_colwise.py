@@ -1,0 +1,121 @@
+"""GPU parity: column-wise (strided-axis) quantize / dequantize / fused against the oracle,
+bit for bit.  Column blocks are defined as row blocks of the transposed tensor (Sec. V)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2302_08007_amd as B
+import synth_inputs as S
+from gpu_util import assert_bits_equal, assert_planes_equal, ofmt, to_np
+
+pytestmark = pytest.mark.gpu
+MX = ["MX9", "MX6", "MX4"]
+
+
+def _check_col(f, x, what):
+    rows, cols = x.shape
+    xn = to_np(x)
+    want = O.quantize(ofmt(f), xn, axis=O.AXIS_COL)
+    planes = B.bdr_quantize(f, x, axis=B.AXIS_COL)
+    torch.cuda.synchronize()
+    assert_planes_equal(planes, want, what + " quantize")
+    out_dtype = np.float32 if x.dtype == torch.float32 else np.uint16
+    ywant = O.dequantize(ofmt(f), *want, rows, cols, axis=O.AXIS_COL, out_dtype=out_dtype)
+    y = B.bdr_dequantize(f, planes, rows, cols, axis=B.AXIS_COL, dtype=x.dtype)
+    assert_bits_equal(y, ywant, what + " dequantize")
+    y2 = B.bdr_quantize_dequantize(f, x, axis=B.AXIS_COL)
+    assert_bits_equal(y2, ywant, what + " fused")
+    return planes
+
+
+@pytest.mark.parametrize("name", MX)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(128, 64), (256, 192), (384, 64), (1024, 320)])
+def test_tiled_path(name, dtype, shape):
+    x = S.wide_range(*shape, device="cuda", seed=shape[0] + shape[1], dtype=dtype)
+    _check_col(getattr(B, name), x, "%s %s %s" % (name, dtype, shape))
+
+
+@pytest.mark.parametrize("name", MX)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(16, 8), (48, 24), (144, 64), (128, 72), (272, 200)])
+def test_shapes_that_take_the_general_path(name, dtype, shape):
+    # rows not a multiple of 128 or columns not a multiple of 64
+    x = S.wide_range(*shape, device="cuda", seed=shape[0] * 7 + shape[1], dtype=dtype)
+    _check_col(getattr(B, name), x, "%s %s %s" % (name, dtype, shape))
+
+
+@pytest.mark.parametrize("kw", [dict(k1=8, k2=1, d2=1, m=2), dict(k1=32, k2=4, d2=2, m=3),
+                                dict(k1=64, k2=64, d2=0, m=4), dict(k1=4, k2=2, d2=1, m=6),
+                                dict(k1=128, k2=16, d2=3, m=5), dict(k1=16, k2=2, d2=1, m=4, rounding=1)],
+                         ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+def test_other_formats_column_wise(kw):
+    f = B.fmt(**kw)
+    x = S.wide_range(256, 40, device="cuda", seed=11)
+    _check_col(f, x, repr(f))
+
+
+@pytest.mark.parametrize("name", MX)
+def test_column_blocks_equal_row_blocks_of_the_transpose(name):
+    f = getattr(B, name)
+    x = S.wide_range(256, 128, device="cuda", seed=21)
+    pc = B.bdr_quantize(f, x, axis=B.AXIS_COL)
+    pr = B.bdr_quantize(f, x.t().contiguous(), axis=B.AXIS_ROW)
+    for a, b in zip(pc, pr):
+        assert torch.equal(a, b)
+    # and differs from quantizing along rows
+    pr2 = B.bdr_quantize(f, x, axis=B.AXIS_ROW)
+    assert not torch.equal(pc[0], pr2[0])
+
+
+def test_strided_and_in_place():
+    big = S.wide_range(256, 512, device="cuda", seed=31)
+    x = big[:, 128:128 + 192]                      # ld > cols
+    xn = np.ascontiguousarray(to_np(big)[:, 128:128 + 192])
+    for f in (B.MX9, B.MX6):
+        want = O.quantize(ofmt(f), xn, axis=O.AXIS_COL)
+        assert_planes_equal(B.bdr_quantize(f, x, axis=B.AXIS_COL), want, "strided")
+        ywant = O.quantize_dequantize(ofmt(f), xn, axis=O.AXIS_COL)
+        z = x.clone()
+        B.bdr_quantize_dequantize(f, z, axis=B.AXIS_COL, out=z)
+        assert_bits_equal(z, ywant, "in place")
+
+
+def test_special_values_column_wise():
+    x = torch.zeros(128, 64, device="cuda")
+    x[3, 0] = -0.0
+    x[:16, 1] = 2.0 ** -140
+    x[5, 1] = -3 * 2.0 ** -149
+    x[:16, 2] = 2.0 ** -126
+    x[1, 2] = 2.0 ** -127
+    x[0, 3], x[1, 3], x[2, 3] = 3.4e38, -1.7e38, 1e-30
+    x[0, 4], x[1, 4], x[2, 4], x[3, 4] = float("inf"), -float("inf"), float("nan"), 1.0
+    x[:64, 5] = torch.tensor([(-1.0) ** i * (i + 0.5) for i in range(64)], device="cuda")
+    x[:, 6] = 1.9999999
+    for name in MX:
+        _check_col(getattr(B, name), x, name + " special")
+        _check_col(getattr(B, name), x.to(torch.bfloat16), name + " special bf16")
+
+
+def test_activation_config_full_size_sampled_columns():
+    # 8192 x 12288 bf16, MX9, the bench configuration: the oracle checks whole column tiles
+    # sampled across the tensor (each column's planes are a contiguous slice of the full planes)
+    x = S.activation(device="cuda")
+    rows, cols = x.shape
+    f = B.MX9
+    planes = B.bdr_quantize(f, x, axis=B.AXIS_COL)
+    y = B.bdr_quantize_dequantize(f, x, axis=B.AXIS_COL)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    for c0 in sorted(set([0, cols - 64] + [int(v) * 64 for v in rng.integers(0, cols // 64, 4)])):
+        sub = x[:, c0:c0 + 64].contiguous()
+        want = O.quantize(ofmt(f), to_np(sub), axis=O.AXIS_COL)
+        per_col = [rows * 8 // 8, rows // 16, rows // 16]
+        got = [p[c0 * n:(c0 + 64) * n] for p, n in zip(planes, per_col)]
+        assert_planes_equal(got, want, "columns %d.." % c0)
+        ywant = O.dequantize(ofmt(f), *want, rows, 64, axis=O.AXIS_COL, out_dtype=np.uint16)
+        assert_bits_equal(y[:, c0:c0 + 64].contiguous(), ywant, "fused columns %d.." % c0)
+    # the outlier columns really are there, and row-wise quantization of the same tensor differs
+    pr = B.bdr_quantize(f, x, axis=B.AXIS_ROW)
+    assert not torch.equal(pr[1][:4096], planes[1][:4096])
