@@ -1,0 +1,97 @@
+"""GPU parity: mx_gemm against the fp64 oracle.  Tolerance: |C - C_ref| <= 1e-4 * sum_k |a b|
+(norm-relative, because entries of C can be near zero)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2302_08007_amd as B
+import synth_inputs as S
+from gpu_util import ofmt, to_np
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-4
+
+
+def _planes_np(planes):
+    return [p.cpu().numpy() for p in planes]
+
+
+def _check(fa, fb, A, Bm, what):
+    M, K = A.shape
+    N = Bm.shape[0]
+    pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
+    C = B.mx_gemm(fa, fb, pa, pb, M, N, K)
+    torch.cuda.synchronize()
+    pan, pbn = _planes_np(pa), _planes_np(pb)
+    Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
+    Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
+    Cref = O.mx_gemm(ofmt(fa), ofmt(fb), pan, pbn, M, N, K)
+    assert np.allclose(Cref, Ah @ Bh.T, rtol=1e-6, atol=1e-30)       # the oracle is a plain GEMM
+    bound = RTOL * (np.abs(Ah) @ np.abs(Bh).T)
+    err = np.abs(C.cpu().numpy().astype(np.float64) - Cref)
+    assert np.all(err <= bound + 1e-30), (what, float((err / (bound + 1e-30)).max()))
+    return C
+
+
+@pytest.mark.parametrize("shape", [(128, 128, 64), (128, 256, 128), (384, 128, 192), (256, 256, 512)])
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX9", "MX9"), ("MX4", "MX4"),
+                                   ("MX9", "MX4"), ("MX4", "MX6"), ("MX6", "MX9")])
+def test_small_full_matrix(shape, names):
+    M, N, K = shape
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=M + N + K)
+    _check(getattr(B, names[0]), getattr(B, names[1]), A, Bm, "%s %s" % (shape, names))
+
+
+def test_exact_on_small_integers():
+    # integers below 2^m sharing one exponent are exact in MX: the product is an integer matrix
+    g = torch.Generator(device="cuda").manual_seed(5)
+    M, N, K = 128, 128, 256
+    A = torch.randint(-7, 8, (M, K), generator=g, device="cuda").float()
+    Bm = torch.randint(-7, 8, (N, K), generator=g, device="cuda").float()
+    A[:, ::16] = 8.0
+    Bm[:, ::16] = -8.0
+    f = B.MX6
+    C = B.mx_gemm(f, f, B.bdr_quantize(f, A), B.bdr_quantize(f, Bm), M, N, K)
+    want = (A.double() @ Bm.double().t()).float()
+    assert torch.equal(C, want)
+
+
+def test_wide_exponent_range_and_signs():
+    A = S.wide_range(128, 256, device="cuda", seed=41, spread=8)
+    Bm = S.wide_range(256, 256, device="cuda", seed=42, spread=8)
+    _check(B.MX6, B.MX9, A, Bm, "wide")
+
+
+def test_strided_output_and_empty_k():
+    M, N, K = 128, 128, 64
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=8)
+    pa, pb = B.bdr_quantize(B.MX6, A), B.bdr_quantize(B.MX6, Bm)
+    big = torch.full((M, 2 * N), 3.0, device="cuda")
+    B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=big[:, :N])
+    ref = B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K)
+    assert torch.equal(big[:, :N], ref) and torch.all(big[:, N:] == 3.0)
+    z = B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, 0)
+    assert torch.count_nonzero(z) == 0
+
+
+def test_full_size_sampled_entries():
+    # 8192^3, MX6 x MX6, the bench configuration: 64 x 64 sampled entries against the oracle
+    M = N = K = 8192
+    A, Bm = S.gemm_operands(M, N, K, device="cuda")
+    f = B.MX6
+    pa, pb = B.bdr_quantize(f, A), B.bdr_quantize(f, Bm)
+    C = B.mx_gemm(f, f, pa, pb, M, N, K)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    ri = np.sort(rng.choice(M, 64, replace=False))
+    ci = np.sort(rng.choice(N, 64, replace=False))
+    ii, jj = [a.reshape(-1) for a in np.meshgrid(ri, ci, indexing="ij")]
+    want, absdot = O.mx_gemm_sampled(ofmt(f), ofmt(f), _planes_np(pa), _planes_np(pb), M, N, K, ii, jj)
+    got = C[torch.as_tensor(ii, device="cuda"), torch.as_tensor(jj, device="cuda")].cpu().numpy()
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= RTOL * absdot), float((err / absdot).max())
+    # fidelity against the unquantized FP32 product (library GEMM): finite and in a sane band
+    Cfp = A @ Bm.t()
+    q = 10 * torch.log10(Cfp.double().square().sum() / (C.double() - Cfp.double()).square().sum())
+    assert 10.0 < q.item() < 40.0
