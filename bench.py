@@ -78,7 +78,7 @@ def main():
     ap.add_argument("--no-other", action="store_true", help="skip the separately timed legs")
     ap.add_argument("--cpu-sample", type=int, default=1 << 25)
     ap.add_argument("--pmc-probe", action="store_true",
-                    help="run a 1 GiB tensor copy and one launch of each row-wise MX6 kernel, "
+                    help="run a 1 GiB tensor copy and one launch of each row-wise MX kernel, "
                          "three times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -118,11 +118,12 @@ def main():
         # the copy reads 1 GiB and writes 1 GiB: it calibrates the counters' units
         for _ in range(3):
             y.copy_(x)
-            B.bdr_quantize(fm["MX6"], x, out=planes["MX6"])
-            B.bdr_dequantize(fm["MX6"], planes["MX6"], rows, cols, out=y)
-            B.bdr_quantize_dequantize(fm["MX6"], x, out=y)
+            for n in ("MX6", "MX9", "MX4"):
+                B.bdr_quantize(fm[n], x, out=planes[n])
+                B.bdr_dequantize(fm[n], planes[n], rows, cols, out=y)
+                B.bdr_quantize_dequantize(fm[n], x, out=y)
         torch.cuda.synchronize()
-        print(json.dumps({"pmc_probe": "copy, mx6 quantize, mx6 dequantize, mx6 fused x3"}))
+        print(json.dumps({"pmc_probe": "3 x (copy, then quantize, dequantize, fused for MX6, MX9, MX4)"}))
         return
 
     for _ in range(args.warmup):

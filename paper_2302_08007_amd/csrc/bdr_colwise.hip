@@ -100,48 +100,17 @@ __device__ __forceinline__ void lds_put(uint8_t *tile, int off, uint32_t bits, u
     *reinterpret_cast<uint16_t *>(tile + off) = (uint16_t)(bits >> 16);
 }
 
-// Quantize one whole block held by one lane (Sec. IX: shared exponent from the
-// block maximum, one shift bit per pair, m-bit nearest-even magnitudes).
+// Quantize one whole block held by one lane (no cross-lane step).
 // w: the 16 codes packed little-endian, (MB+1) bits each.  yb only when DEQ.
 template <int MB, bool DEQ>
 __device__ __forceinline__ void mx_quant16(const uint32_t (&xb)[16], uint32_t (&w)[4],
                                            uint32_t &se, uint32_t &tau8, uint32_t (&yb)[16])
 {
-    constexpr int CB = MB + 1;
-    constexpr uint32_t MMASK = (1u << MB) - 1u;
-    constexpr float TOP = (float)MMASK;
-    uint32_t p[8];
+    constexpr int NW = MxWords<MB, 8>::kN;
+    uint32_t ww[NW];
+    mx_quant_lane<MB, 8, 0, DEQ>(xb, ww, se, tau8, yb);
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-        p[j] = clamp_mag(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask));
-    uint32_t bm = p[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) bm = umax(bm, p[j]);
-    const uint32_t thr = bm & kExpMask;
-    se = bm >> 23;
-    const int c0 = (MB - 1) + 127 - (int)se;
-    w[0] = w[1] = w[2] = w[3] = 0;
-    tau8 = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t t = p[j] < thr ? 1u : 0u;
-        tau8 |= t << j;
-        const int sh = c0 + (int)t;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int i = 2 * j + k;
-            float y = __builtin_fminf(__builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh), TOP);
-            const uint32_t zb = as_u(y + kMagic);
-            const uint32_t code = bfi(MMASK, zb, xb[i] >> (31 - MB));
-            const int off = i * CB;
-            w[off >> 5] |= code << (off & 31);
-            if ((off & 31) + CB > 32) w[(off >> 5) + 1] |= code >> (32 - (off & 31));
-            if (DEQ) {
-                const float v = __builtin_ldexpf(as_f(zb) - kMagic, -sh);
-                yb[i] = bfi(kAbsMask, as_u(v), xb[i]);
-            }
-        }
-    }
+    for (int k = 0; k < 4; ++k) w[k] = k < NW ? ww[k < NW ? k : 0] : 0u;
 }
 
 template <int MB>

@@ -61,19 +61,15 @@ __device__ __forceinline__ uint32_t as_u(float f) { return __float_as_uint(f); }
 // Cache hints, chosen by measurement on MI355X (1 GiB tensors):
 //  - a lane's two adjacent 16-byte FP32 loads do best as plain loads (with the
 //    streaming hint the second one is fetched again);
-//  - one 16-byte load per lane (BF16) is the same either way;
+//  - one 16-byte access per lane (BF16 rows, FP32 with 4 elements per lane) is
+//    best with the streaming hint;
 //  - FP32 output written as two 16-byte stores per lane must be plain stores
 //    (streaming partial-line stores halve the write rate);
 //  - the small packed planes do best with the streaming hint.
-#ifndef BDR_EXP_NT_LOAD
-#define BDR_EXP_NT_LOAD 0
-#endif
-#ifndef BDR_EXP_NT_CODES
-#define BDR_EXP_NT_CODES 1
-#endif
-#ifndef BDR_EXP_NT_OUT
-#define BDR_EXP_NT_OUT 0
-#endif
+constexpr bool kNtPairLoad = false;
+constexpr bool kNtPairStore = false;
+constexpr bool kNtPlanes = true;
+
 template <bool NT, typename V>
 __device__ __forceinline__ V ldg(const V *p)
 {
@@ -89,37 +85,142 @@ __device__ __forceinline__ void stg(V v, V *p)
         *p = v;
 }
 
+// ------------------------------------------------------------------ MX core
+//
+// Quantize the 2*NP consecutive elements one lane holds of a Table II block
+// (k1 16, k2 2, d2 1, nearest-even, MB magnitude bits).  The block spans
+// 16 / (2*NP) adjacent lanes (XL = log2 of that: 0, 1 or 2); its maximum is
+// combined across them with DPP quad permutes.
+//
+//   w     the lane's 2*NP codes packed little-endian, MB+1 bits each
+//   se    biased shared exponent of the block (Sec. IX: exponent of the maximum)
+//   tau   one bit per pair: 1 when the pair's largest exponent is below se
+//   yb    (DEQ only) bit patterns of the dequantized values
+//
+// Instruction economy, because these kernels are only ~2x away from VALU-bound:
+//   - pair maximum and the lower exponent clamp are one v_max3_u32;
+//   - |x| * 2^sh, min with 2^m - 1 and + 2^23 (round to nearest-even integer)
+//     are three VALU ops; the 2^23 bias in every term is removed once per word by
+//     starting the word at minus the sum of the biases, so a magnitude is packed
+//     with a single shift-add;
+//   - sign bits are OR-ed into a second accumulator (shift, and-or); for 8-bit
+//     codes they are instead gathered four at a time with byte permutes.
+template <int MB, int NP>
+struct MxWords {
+    static constexpr int kCB = MB + 1;
+    static constexpr int kN = (2 * NP * kCB + 31) / 32;
+};
+
+constexpr uint32_t kMagicBits = 0x4B000000u;  // bit pattern of 2^23
+
+// sum over the non-straddling elements of word k of (2^23 bits << shift), mod 2^32
+template <int MB, int NP>
+__device__ __forceinline__ constexpr uint32_t mx_bias(int k)
+{
+    uint32_t b = 0;
+    for (int i = 0; i < 2 * NP; ++i) {
+        const int off = i * (MB + 1);
+        if ((off >> 5) == k && (off & 31) + (MB + 1) <= 32) b += kMagicBits << (off & 31);
+    }
+    return b;
+}
+
+template <int MB, int NP, int XL, bool DEQ>
+__device__ __forceinline__ void mx_quant_lane(const uint32_t (&xb)[2 * NP],
+                                              uint32_t (&w)[MxWords<MB, NP>::kN], uint32_t &se,
+                                              uint32_t &tau, uint32_t (&yb)[2 * NP])
+{
+    constexpr int CB = MB + 1;
+    constexpr int NW = MxWords<MB, NP>::kN;
+    constexpr uint32_t MMASK = (1u << MB) - 1u;
+    constexpr float TOP = (float)MMASK;
+
+    // pair maxima, clamped below at 2^-126 (exponent code 1 for zero / subnormal)
+    uint32_t p[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j)
+        p[j] = umax(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask), kMagLo);
+    uint32_t bm = p[0];
+#pragma unroll
+    for (int j = 1; j < NP; ++j) bm = umax(bm, p[j]);
+    if (XL >= 1) bm = umax(bm, dpp<kQuadXor1>(bm));
+    if (XL >= 2) bm = umax(bm, dpp<kQuadXor2>(bm));
+    bm = umin(bm, kMagHi);  // Inf / NaN count as exponent code 254
+    const uint32_t thr = bm & kExpMask;
+    se = bm >> 23;
+    const int c0 = (MB - 1) + 127 - (int)se;  // x * 2^c0 puts the block maximum in [2^(m-1), 2^m)
+    const int c1 = c0 + 1;
+
+    uint32_t mag[NW], sgn[NW];
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        mag[k] = 0u - mx_bias<MB, NP>(k);
+        sgn[k] = 0;
+    }
+    tau = 0;
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        const bool below = p[j] < thr;  // pair exponent below the shared one: shift by one
+        const int sh = below ? c1 : c0;
+        tau |= (below ? 1u : 0u) << j;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = 2 * j + e;
+            const float y =
+                __builtin_fminf(__builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh), TOP);
+            const uint32_t zb = as_u(y + kMagic);  // 2^23 bits + nearest-even integer
+            const int off = i * CB, k = off >> 5, s = off & 31;
+            if (s + CB <= 32) {
+                mag[k] += zb << s;
+                if (CB != 8) sgn[k] |= (xb[i] >> (31 - s - MB)) & (1u << (s + MB));
+            } else {  // code straddles two words: place a clean copy in both
+                const uint32_t c = (zb & MMASK) | ((xb[i] >> 31) << MB);
+                sgn[k] |= c << s;
+                sgn[k + 1] |= c >> (32 - s);
+            }
+            if (DEQ) {
+                const float v = __builtin_ldexpf(as_f(zb) - kMagic, -sh);
+                yb[i] = bfi(kAbsMask, as_u(v), xb[i]);
+            }
+        }
+    }
+    if (CB == 8) {
+        // sign of element i sits at bit 8 i + 7 of its word: gather the top bytes
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+            const uint32_t t01 = __builtin_amdgcn_perm(xb[4 * k + 1], xb[4 * k], 0x0c0c0703u);
+            const uint32_t t23 = __builtin_amdgcn_perm(xb[4 * k + 3], xb[4 * k + 2], 0x07030c0cu);
+            w[k] = bfi(0x80808080u, t01 | t23, mag[k]);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < NW; ++k) w[k] = mag[k] | sgn[k];
+    }
+}
+
+
 // Two dwords at a dword-aligned (not 8-byte-aligned) address, as one access.
 __device__ __forceinline__ void store_pair_a4(uint32_t a, uint32_t b, void *p)
 {
     u32x2_a4 v = {a, b};
-    if (BDR_EXP_NT_CODES)
+    if (kNtPlanes)
         __builtin_nontemporal_store(v, reinterpret_cast<u32x2_a4 *>(p));
     else
         *reinterpret_cast<u32x2_a4 *>(p) = v;
 }
 __device__ __forceinline__ void load_pair_a4(const void *p, uint32_t &a, uint32_t &b)
 {
-#if defined(BDR_EXP_DEQ_TWO)
-    a = reinterpret_cast<const uint32_t *>(p)[0];
-    b = reinterpret_cast<const uint32_t *>(p)[1];
-#elif defined(BDR_EXP_DEQ_NT)
-    u32x2_a4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_a4 *>(p));
-    a = v.x;
-    b = v.y;
-#else
     u32x2_a4 v = *reinterpret_cast<const u32x2_a4 *>(p);
     a = v.x;
     b = v.y;
-#endif
 }
 
 // Load 8 consecutive elements as FP32 bit patterns.
 __device__ __forceinline__ void load8(const float *p, uint32_t (&xb)[8])
 {
     const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
-    u32x4 a = ldg<BDR_EXP_NT_LOAD>(q);
-    u32x4 b = ldg<BDR_EXP_NT_LOAD>(q + 1);
+    u32x4 a = ldg<kNtPairLoad>(q);
+    u32x4 b = ldg<kNtPairLoad>(q + 1);
     xb[0] = a.x; xb[1] = a.y; xb[2] = a.z; xb[3] = a.w;
     xb[4] = b.x; xb[5] = b.y; xb[6] = b.z; xb[7] = b.w;
 }
@@ -140,8 +241,8 @@ __device__ __forceinline__ void store8(float *p, const uint32_t (&yb)[8])
     u32x4 *q = reinterpret_cast<u32x4 *>(p);
     u32x4 a = {yb[0], yb[1], yb[2], yb[3]};
     u32x4 b = {yb[4], yb[5], yb[6], yb[7]};
-    stg<BDR_EXP_NT_OUT>(a, q);
-    stg<BDR_EXP_NT_OUT>(b, q + 1);
+    stg<kNtPairStore>(a, q);
+    stg<kNtPairStore>(b, q + 1);
 }
 
 __device__ __forceinline__ void store8(uint16_t *p, const uint32_t (&yb)[8])

@@ -19,84 +19,42 @@
 
 namespace bdr {
 
-#ifndef BDR_EXP_THREADS
-#define BDR_EXP_THREADS 256
-#endif
-constexpr int kThreads = BDR_EXP_THREADS;
+constexpr int kThreads = 256;
 constexpr int kTileElems = kThreads * 8;
 
 // ---------------------------------------------------------------- MX fast path
 
-// Quantize the 8 elements of one lane.  lo/hi: the 8 codes packed little-endian,
-// (MB+1) bits each.  se: biased shared exponent of the lane's block.  tau4: one
-// shift bit per sub-block.  yb (only when DEQ): the dequantized bit patterns.
+// Quantize the 8 elements of one lane (half a block; the other half is the
+// neighbouring lane).  lo/hi: the 8 codes packed little-endian, (MB+1) bits each.
 template <int MB, bool DEQ>
 __device__ __forceinline__ void mx_quant8(const uint32_t (&xb)[8], uint32_t &lo, uint32_t &hi,
                                           uint32_t &se, uint32_t &tau4, uint32_t (&yb)[8])
 {
-    constexpr int CB = MB + 1;
-    constexpr uint32_t MMASK = (1u << MB) - 1u;
-    constexpr float TOP = (float)MMASK;
-
-    uint32_t p[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        p[j] = clamp_mag(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask));
-    const uint32_t lm = umax(umax(p[0], p[1]), umax(p[2], p[3]));
-    const uint32_t bm = umax(lm, dpp<kQuadXor1>(lm));  // the other half of the block
-    const uint32_t thr = bm & kExpMask;
-    se = bm >> 23;
-    const int c0 = (MB - 1) + 127 - (int)se;  // x * 2^c0 puts the block maximum in [2^(m-1), 2^m)
-
-    lo = 0;
-    hi = 0;
-    tau4 = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t t = p[j] < thr ? 1u : 0u;  // sub-block exponent below the shared one
-        tau4 |= t << j;
-        const int sh = c0 + (int)t;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int i = 2 * j + k;
-            float y = __builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh);
-            y = __builtin_fminf(y, TOP);  // a magnitude that would round to 2^m stays at 2^m - 1
-            const uint32_t zb = as_u(y + kMagic);
-            const uint32_t code = bfi(MMASK, zb, xb[i] >> (31 - MB));
-            const int off = i * CB;
-            if (off < 32) lo |= code << off;
-            if (off >= 32)
-                hi |= code << (off - 32);
-            else if (off + CB > 32)
-                hi |= code >> (32 - off);
-            if (DEQ) {
-                const float v = __builtin_ldexpf(as_f(zb) - kMagic, -sh);
-                yb[i] = bfi(kAbsMask, as_u(v), xb[i]);
-            }
-        }
-    }
+    uint32_t w[MxWords<MB, 4>::kN];
+    mx_quant_lane<MB, 4, 1, DEQ>(xb, w, se, tau4, yb);
+    lo = w[0];
+    hi = MxWords<MB, 4>::kN > 1 ? w[MxWords<MB, 4>::kN - 1] : 0u;
 }
 
-template <int MB, typename T>
-__global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
-    const T *__restrict__ x, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
-    uint8_t *__restrict__ mexp, int64_t n_groups)
+// One group of 8 elements per thread and a one-shot grid: on this chip short
+// waves with high turnover beat loops and deeper per-thread prefetch (measured:
+// 2 or 4 groups per thread cost 10-25 %).
+constexpr int kIter = 1;
+
+// Pack and store what one lane produced for its 8 elements (group g).
+template <int MB>
+__device__ __forceinline__ void mx_store_group(uint32_t lo, uint32_t hi, uint32_t se, uint32_t tau4,
+                                               int64_t g, uint8_t *__restrict__ codes,
+                                               uint8_t *__restrict__ sexp,
+                                               uint8_t *__restrict__ mexp)
 {
     constexpr int CB = MB + 1;
-    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (g >= n_groups) return;  // whole quads leave together (n_groups % 4 == 0)
-
-    uint32_t xb[8], yb[8];
-    load8(x + 8 * g, xb);
-    uint32_t lo, hi, se, tau4;
-    mx_quant8<MB, false>(xb, lo, hi, se, tau4, yb);
-
     const uint32_t i = threadIdx.x & 3u;
     const int64_t quad = g >> 2;
 
     if (CB == 8) {
         u32x2 v = {lo, hi};
-        stg<BDR_EXP_NT_CODES>(v, reinterpret_cast<u32x2 *>(codes + 8 * g));
+        stg<kNtPlanes>(v, reinterpret_cast<u32x2 *>(codes + 8 * g));
     } else if (CB == 5) {
         // A quad holds 4 x 40 bits = 5 dwords.  Lane 0 writes dwords 0-1, lane i
         // writes dword i + 1; each needs the low word of the next lane.
@@ -106,14 +64,14 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
         if (i == 0) {
             store_pair_a4(lo, whi, qb);
         } else {
-            stg<BDR_EXP_NT_CODES>(funnel_r(whi, lo, 32u - 8u * i),
+            stg<kNtPlanes>(funnel_r(whi, lo, 32u - 8u * i),
                                   reinterpret_cast<uint32_t *>(qb + 4 * (i + 1)));
         }
     } else {
         // CB == 3: a quad holds 4 x 24 bits = 3 dwords, written by lanes 0-2.
         const uint32_t nlo = dpp<kQuadNext>(lo);
         if (i < 3)
-            stg<BDR_EXP_NT_CODES>((lo >> (8u * i)) | (nlo << (24u - 8u * i)),
+            stg<kNtPlanes>((lo >> (8u * i)) | (nlo << (24u - 8u * i)),
                                   reinterpret_cast<uint32_t *>(codes + 12 * quad + 4 * i));
     }
 
@@ -130,6 +88,31 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
 }
 
 template <int MB, typename T>
+__global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
+    const T *__restrict__ x, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
+    uint8_t *__restrict__ mexp, int64_t n_groups)
+{
+    // A thread takes kIter groups, kThreads apart; whole quads of lanes are in or
+    // out of range together (n_groups % 4 == 0).
+    const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
+    uint32_t xb[kIter][8];
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int64_t g = g0 + it * kThreads;
+        if (g < n_groups) load8(x + 8 * g, xb[it]);
+    }
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int64_t g = g0 + it * kThreads;
+        if (g < n_groups) {
+            uint32_t yb[8], lo, hi, se, tau4;
+            mx_quant8<MB, false>(xb[it], lo, hi, se, tau4, yb);
+            mx_store_group<MB>(lo, hi, se, tau4, g, codes, sexp, mexp);
+        }
+    }
+}
+
+template <int MB, typename T>
 __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups)
@@ -137,50 +120,64 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     constexpr int CB = MB + 1;
     constexpr uint32_t CMASK = (1u << CB) - 1u;
     constexpr uint32_t MMASK = (1u << MB) - 1u;
-    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (g >= n_groups) return;
+    const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
     const uint32_t i = threadIdx.x & 3u;
-    const int64_t quad = g >> 2;
 
-    uint32_t lo, hi = 0;
-    if (CB == 8) {
-        u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes + 8 * g));
-        lo = v.x;
-        hi = v.y;
-    } else if (CB == 5) {
-        // lane i's 40 bits start 8 i bits into dword i of the quad's 5 dwords
-        uint32_t v0, v1;
-        load_pair_a4(codes + 20 * quad + 4 * i, v0, v1);
-        lo = funnel_r(v1, v0, 8u * i);
-        hi = (v1 >> (8u * i)) & 0xffu;
-    } else {
-        // lane i's 24 bits start at bit 24 i of the quad's 3 dwords
-        const uint32_t j = i >> 1;
-        uint32_t v0, v1;
-        load_pair_a4(codes + 12 * quad + 4 * j, v0, v1);
-        const uint64_t w = ((uint64_t)v1 << 32) | v0;
-        lo = (uint32_t)(w >> (24u * i - 32u * j)) & 0xffffffu;
-    }
-    const uint32_t se = sexp[g >> 1];
-    const uint32_t tau4 = ((uint32_t)mexp[g >> 1] >> (4u * (i & 1u))) & 0xfu;
-
-    uint32_t yb[8];
+    uint32_t v0[kIter], v1[kIter], seb[kIter], tb[kIter];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int off = e * CB;
-        uint32_t c;
-        if (off >= 32)
-            c = hi >> (off - 32);
-        else if (off + CB > 32)
-            c = (lo >> off) | (hi << (32 - off));
-        else
-            c = lo >> off;
-        c &= CMASK;
-        const int q = (int)se - 127 - (int)((tau4 >> (e >> 1)) & 1u) - (MB - 1);
-        const float v = __builtin_ldexpf((float)(c & MMASK), q);
-        yb[e] = as_u(v) | ((c >> MB) << 31);
+    for (int it = 0; it < kIter; ++it) {
+        const int64_t g = g0 + it * kThreads;
+        if (g >= n_groups) continue;
+        const int64_t quad = g >> 2;
+        if (CB == 8) {
+            u32x2 v = ldg<true>(reinterpret_cast<const u32x2 *>(codes + 8 * g));
+            v0[it] = v.x;
+            v1[it] = v.y;
+        } else if (CB == 5) {
+            load_pair_a4(codes + 20 * quad + 4 * i, v0[it], v1[it]);
+        } else {
+            load_pair_a4(codes + 12 * quad + 4 * (i >> 1), v0[it], v1[it]);
+        }
+        seb[it] = sexp[g >> 1];
+        tb[it] = mexp[g >> 1];
     }
-    store8(y + 8 * g, yb);
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int64_t g = g0 + it * kThreads;
+        if (g >= n_groups) continue;
+        uint32_t lo, hi = 0;
+        if (CB == 8) {
+            lo = v0[it];
+            hi = v1[it];
+        } else if (CB == 5) {
+            // lane i's 40 bits start 8 i bits into dword i of the quad's 5 dwords
+            lo = funnel_r(v1[it], v0[it], 8u * i);
+            hi = (v1[it] >> (8u * i)) & 0xffu;
+        } else {
+            // lane i's 24 bits start at bit 24 i of the quad's 3 dwords
+            const uint64_t w = ((uint64_t)v1[it] << 32) | v0[it];
+            lo = (uint32_t)(w >> (24u * i - 32u * (i >> 1))) & 0xffffffu;
+        }
+        const uint32_t se = seb[it];
+        const uint32_t tau4 = (tb[it] >> (4u * (i & 1u))) & 0xfu;
+        uint32_t yb[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int off = e * CB;
+            uint32_t c;
+            if (off >= 32)
+                c = hi >> (off - 32);
+            else if (off + CB > 32)
+                c = (lo >> off) | (hi << (32 - off));
+            else
+                c = lo >> off;
+            c &= CMASK;
+            const int q = (int)se - 127 - (int)((tau4 >> (e >> 1)) & 1u) - (MB - 1);
+            const float v = __builtin_ldexpf((float)(c & MMASK), q);
+            yb[e] = as_u(v) | ((c >> MB) << 31);
+        }
+        store8(y + 8 * g, yb);
+    }
 }
 
 template <int MB, typename T>
@@ -194,6 +191,35 @@ __global__ __launch_bounds__(kThreads) void mx_qdq_row_kernel(const T *x, T *y, 
     uint32_t lo, hi, se, tau4;
     mx_quant8<MB, true>(xb, lo, hi, se, tau4, yb);
     store8(y + 8 * g, yb);
+}
+
+// ------------------------------------------------- FP32 kernels, 4 elements per lane
+//
+// For FP32 a lane that owns 4 consecutive elements makes every 16-byte access of
+// a wave contiguous (64 x 16 bytes), which is what the memory system likes best.
+// A block is then a quad of lanes and its maximum takes two DPP quad permutes.
+
+template <int MB, bool DEQ>
+__device__ __forceinline__ void mx_quant4(const uint32_t (&xb)[4], uint32_t &codes, uint32_t &se,
+                                          uint32_t &tau2, uint32_t (&yb)[4])
+{
+    uint32_t w[1];
+    mx_quant_lane<MB, 2, 2, DEQ>(xb, w, se, tau2, yb);
+    codes = w[0];
+}
+
+template <int MB>
+__global__ __launch_bounds__(kThreads) void mx_qdq_row_f32x4_kernel(const float *x, float *y,
+                                                                    int64_t n4)
+{
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= n4) return;  // whole quads leave together (n4 % 4 == 0)
+    const u32x4 v = ldg<true>(reinterpret_cast<const u32x4 *>(x) + g);
+    const uint32_t xb[4] = {v.x, v.y, v.z, v.w};
+    uint32_t yb[4], codes, se, tau2;
+    mx_quant4<MB, true>(xb, codes, se, tau2, yb);
+    const u32x4 o = {yb[0], yb[1], yb[2], yb[3]};
+    stg<true>(o, reinterpret_cast<u32x4 *>(y) + g);
 }
 
 // ------------------------------------------------------------- generic kernels
@@ -494,12 +520,13 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (mx_fast_ok(f, rows, cols, ld)) {
+        const dim3 fgrid((unsigned)((ng + kThreads * kIter - 1) / (kThreads * kIter)));
         if (f.m == 7)
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
         else if (f.m == 4)
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
         else
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), grid, block, 0, s, codes, sexp, mexp, y, ng);
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
     } else {
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         hipLaunchKernelGGL((generic_dequantize_kernel<T, false>), grid, block, 0, s, gen_of(f),
@@ -524,6 +551,17 @@ static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_
 {
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
+    if (is_mx(f) && ld == cols && sizeof(T) == 4) {
+        const int64_t n4 = rows * cols / 4;
+        const dim3 g4(blocks_for(n4));
+        if (f.m == 7)
+            hipLaunchKernelGGL((mx_qdq_row_f32x4_kernel<7>), g4, block, 0, s, (const float *)x, (float *)y, n4);
+        else if (f.m == 4)
+            hipLaunchKernelGGL((mx_qdq_row_f32x4_kernel<4>), g4, block, 0, s, (const float *)x, (float *)y, n4);
+        else
+            hipLaunchKernelGGL((mx_qdq_row_f32x4_kernel<2>), g4, block, 0, s, (const float *)x, (float *)y, n4);
+        return launch_status();
+    }
     if (is_mx(f) && ld == cols) {
         if (f.m == 7)
             hipLaunchKernelGGL((mx_qdq_row_kernel<7, T>), grid, block, 0, s, x, y, ng);
