@@ -2,13 +2,20 @@
 // operation are MX-quantized along the reduction dimension).
 //
 // A is the packed image of an [M x K] tensor, B of an [N x K] tensor, both
-// blocked along K.  A workgroup owns a 128 x 128 tile of C and walks K in steps
-// of 64: every thread pulls the packed bits of 32 elements of A and 32 of B
-// (two blocks each) from global memory, expands them exactly to BF16 (a BF16 has
-// 8 significant bits, an MX element at most 7, and the scale is a power of two),
-// and writes them to LDS; the four waves then feed 32x32x16 BF16 MFMAs from LDS
-// and accumulate in FP32.  Global loads for the next K step are issued before the
+// blocked along K.  A workgroup owns a BM x BN tile of C and walks K in steps of
+// 64: every thread pulls the packed bits of 32 elements of A and 32 of B (two
+// blocks each) from global memory, expands them exactly to BF16 (a BF16 has 8
+// significant bits, an MX element at most 7, and the scale is a power of two),
+// and writes them to LDS; the waves then feed 32x32x16 BF16 MFMAs from LDS and
+// accumulate in FP32.  Global loads for the next K step are issued before the
 // MFMAs of the current one, and LDS is double buffered, so one barrier per step.
+//
+// The expansion, not the MFMA, is what this kernel is bound by (about 6.5 VALU
+// operations per operand element against 32 matrix-pipe cycles per MFMA), so the
+// tile is as large as LDS allows (256 x 256: every operand element is expanded
+// once per 256 columns or rows of C) and the expansion is kept lean: field
+// extract, integer-to-float, ldexp, sign insert, and one byte permute per pair to
+// form the BF16 pair.
 //
 // This is not the dot-product engine of Sec. IV-B (integer Hadamard tree with a
 // conditional shift and fixed-point accumulation): that design targets a custom
@@ -21,10 +28,8 @@ namespace bdr {
 
 namespace {
 
-constexpr int kBM = 128, kBN = 128, kBK = 64;
-constexpr int kGemmThreads = 256;
+constexpr int kBK = 64;
 constexpr int kPitch = kBK * 2;  // bytes per LDS row: 64 BF16 = eight 16-byte chunks
-constexpr int kOperandBytes = kBM * kPitch;
 // LDS rows are 128 bytes, so the same chunk of consecutive rows would sit on the
 // same banks.  Chunk c of row r is stored at position c ^ (r & 7): eight
 // consecutive rows then spread one chunk index over all 32 banks.
@@ -41,8 +46,8 @@ typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 // The packed bits one thread needs for 32 consecutive elements (two blocks) of a row.
 template <int MB>
 struct Packed {
-    uint32_t c[MB + 1];  // 32 codes x (MB+1) bits = MB+1 dwords
-    uint32_t se2, tau16; // two exponent bytes, two microexponent bytes
+    uint32_t c[MB + 1];   // 32 codes x (MB+1) bits = MB+1 dwords
+    uint32_t se2, tau16;  // two exponent bytes, two microexponent bytes
 };
 
 template <int MB>
@@ -72,28 +77,37 @@ __device__ __forceinline__ void load_packed(const uint8_t *__restrict__ codes,
 
 // Expand the 32 elements to BF16 and store them as chunks 4*half .. 4*half+3 of
 // LDS row `row` of the operand tile at `base`.
+// value = (-1)^s * M * 2^(se - 127 - tau - (MB-1)); ldexp makes it exact for every
+// exponent, subnormal results included.
 template <int MB>
 __device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base, int row, int half)
 {
     constexpr int CB = MB + 1;
-    constexpr uint32_t CMASK = (1u << CB) - 1u, MMASK = (1u << MB) - 1u;
     uint32_t out[16];
+    int qb[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) qb[b] = (int)((p.se2 >> (8 * b)) & 0xffu) - (127 + MB - 1);
 #pragma unroll
     for (int j = 0; j < 16; ++j) {  // pair j: elements 2j, 2j+1, one microexponent bit
-        const int blk = j >> 3;
-        const int se = (int)((p.se2 >> (8 * blk)) & 0xffu);
-        const int q = se - 127 - (MB - 1) - (int)((p.tau16 >> j) & 1u);
+        const int q = qb[j >> 3] - (int)((p.tau16 >> j) & 1u);
         uint32_t h[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int off = (2 * j + e) * CB;
-            uint32_t c = p.c[off >> 5] >> (off & 31);
-            if constexpr (CB != 8)
-                if ((off & 31) + CB > 32) c |= p.c[((off >> 5) + 1) % CB] << (32 - (off & 31));
-            c &= CMASK;
-            h[e] = as_u(__builtin_ldexpf((float)(c & MMASK), q)) | ((c >> MB) << 31);
+            const int k = off >> 5;
+            int s = off & 31;
+            uint32_t win = p.c[k];
+            if constexpr (CB != 8) {
+                if (s + CB > 32) {  // the code straddles two words: funnel it down to bit 0
+                    win = funnel_r(p.c[(k + 1) % CB], p.c[k], s);
+                    s = 0;
+                }
+            }
+            const float f = __builtin_ldexpf((float)((win >> s) & ((1u << MB) - 1u)), q);
+            h[e] = bfi(kAbsMask, as_u(f), win << (31 - s - MB));  // sign bit from the code
         }
-        out[j] = (h[0] >> 16) | (h[1] & 0xffff0000u);  // exact: the low halves are zero
+        // the two high halves (exact: the low halves are zero) as one BF16 pair
+        out[j] = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u);
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
@@ -102,19 +116,25 @@ __device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base
     }
 }
 
-template <int MBA, int MBB>
-__global__ __launch_bounds__(kGemmThreads) void mx_gemm_kernel(
+// WM x WN waves, each computing TM x TN MFMA tiles of 32 x 32.
+template <int MBA, int MBB, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
     const uint8_t *__restrict__ a_codes, const uint8_t *__restrict__ a_sexp,
     const uint8_t *__restrict__ a_mexp, const uint8_t *__restrict__ b_codes,
     const uint8_t *__restrict__ b_sexp, const uint8_t *__restrict__ b_mexp, int M, int N, int K,
     float *__restrict__ C, int64_t ldc)
 {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr int THREADS = 64 * WM * WN;
+    constexpr int A_BYTES = BM * kPitch, B_BYTES = BN * kPitch;
+    constexpr int PA = 2 * BM / THREADS, PB = 2 * BN / THREADS;  // unpack passes per thread
+    static_assert(PA >= 1 && PB >= 1 && 2 * BM % THREADS == 0 && 2 * BN % THREADS == 0, "tile");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B]
 
     // Tile order: workgroup ids go round-robin over the 8 XCDs, each with its own
     // L2, so give every XCD a contiguous range of tiles and walk that range in
     // groups of 8 tile rows per tile column to keep the operands of a group hot.
-    const int ntm = M / kBM, ntn = N / kBN, total = ntm * ntn;
+    const int ntm = M / BM, ntn = N / BN, total = ntm * ntn;
     int t = blockIdx.x;
     if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
     int tm, tn;
@@ -126,107 +146,164 @@ __global__ __launch_bounds__(kGemmThreads) void mx_gemm_kernel(
         tm = t / ntn;
         tn = t % ntn;
     }
-    const int m0 = tm * kBM, n0 = tn * kBN;
+    const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
-    // unpack role: row tid/2 of the tile, elements 32*(tid&1) .. +31 of the K step
+    // unpack role: row tid/2 (+ THREADS/2 per pass), elements 32*(tid&1) .. +31 of the K step
     const int urow = tid >> 1, uhalf = tid & 1;
     const int64_t kblocks = K >> 4;
-    int64_t a_blk = (int64_t)(m0 + urow) * kblocks + 2 * uhalf;
-    int64_t b_blk = (int64_t)(n0 + urow) * kblocks + 2 * uhalf;
+    int64_t a_blk[PA], b_blk[PB];
+#pragma unroll
+    for (int i = 0; i < PA; ++i)
+        a_blk[i] = (int64_t)(m0 + urow + i * (THREADS / 2)) * kblocks + 2 * uhalf;
+#pragma unroll
+    for (int i = 0; i < PB; ++i)
+        b_blk[i] = (int64_t)(n0 + urow + i * (THREADS / 2)) * kblocks + 2 * uhalf;
 
-    f32x16 acc[2][2];
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    Packed<MBA> pa;
-    Packed<MBB> pb;
+    // Packed operands live in two register sets: while step kt is multiplied and
+    // step kt+1 (already in registers) is expanded into the other LDS buffer, the
+    // loads of step kt+2 are in flight.  A whole K step hides their latency.
+    Packed<MBA> pa[2][PA];
+    Packed<MBB> pb[2][PB];
     const int nk = K / kBK;
-    if (nk > 0) {
-        load_packed<MBA>(a_codes, a_sexp, a_mexp, a_blk, pa);
-        load_packed<MBB>(b_codes, b_sexp, b_mexp, b_blk, pb);
-        unpack_to_lds<MBA>(pa, smem, urow, uhalf);
-        unpack_to_lds<MBB>(pb, smem + kOperandBytes, urow, uhalf);
-    }
-    __syncthreads();
 
+    auto load_step = [&](int set) {  // advances the block pointers by one K step
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            load_packed<MBA>(a_codes, a_sexp, a_mexp, a_blk[i], pa[set][i]);
+            a_blk[i] += 4;
+        }
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+            load_packed<MBB>(b_codes, b_sexp, b_mexp, b_blk[i], pb[set][i]);
+            b_blk[i] += 4;
+        }
+    };
+    auto unpack_step = [&](int set, uint8_t *dst) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i)
+            unpack_to_lds<MBA>(pa[set][i], dst, urow + i * (THREADS / 2), uhalf);
+#pragma unroll
+        for (int i = 0; i < PB; ++i)
+            unpack_to_lds<MBB>(pb[set][i], dst + A_BYTES, urow + i * (THREADS / 2), uhalf);
+    };
     // fragment addresses: lane l feeds row l % 32, k offset 8 * (l / 32) of a 32 x 16 slab
     const int f_row = lane & 31, f_half = lane >> 5;
-    for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t *cur = smem + (kt & 1) * (2 * kOperandBytes);
-        uint8_t *nxt = smem + ((kt + 1) & 1) * (2 * kOperandBytes);
-        const bool more = kt + 1 < nk;
-        if (more) {
-            a_blk += 4;
-            b_blk += 4;
-            load_packed<MBA>(a_codes, a_sexp, a_mexp, a_blk, pa);
-            load_packed<MBB>(b_codes, b_sexp, b_mexp, b_blk, pb);
-        }
+    auto mfma_step = [&](const uint8_t *cur) {
 #pragma unroll
         for (int s = 0; s < kBK / 16; ++s) {
-            bf16x8 fa[2], fb[2];
+            bf16x8 fa[TM], fb[TN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < TM; ++i)
                 fa[i] = *reinterpret_cast<const bf16x8 *>(
-                    cur + lds_chunk(wm * 64 + i * 32 + f_row, 2 * s + f_half));
-                fb[i] = *reinterpret_cast<const bf16x8 *>(
-                    cur + kOperandBytes + lds_chunk(wn * 64 + i * 32 + f_row, 2 * s + f_half));
-            }
+                    cur + lds_chunk((wm * TM + i) * 32 + f_row, 2 * s + f_half));
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8 *>(
+                    cur + A_BYTES + lds_chunk((wn * TN + j) * 32 + f_row, 2 * s + f_half));
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (more) {
-            unpack_to_lds<MBA>(pa, nxt, urow, uhalf);
-            unpack_to_lds<MBB>(pb, nxt + kOperandBytes, urow, uhalf);
-        }
+    };
+    uint8_t *const buf0 = smem, *const buf1 = smem + A_BYTES + B_BYTES;
+
+    load_step(0);
+    unpack_step(0, buf0);
+    if (nk > 1) load_step(0);  // step 1 waits in set 0
+    __syncthreads();
+
+    int kt = 0;
+    // two K steps per trip so that register sets and LDS buffers have fixed names
+    for (; kt + 3 < nk; kt += 2) {
+        load_step(1);           // step kt+2
+        mfma_step(buf0);        // step kt
+        unpack_step(0, buf1);   // step kt+1
         __syncthreads();
+        load_step(0);           // step kt+3
+        mfma_step(buf1);        // step kt+1
+        unpack_step(1, buf0);   // step kt+2
+        __syncthreads();
+    }
+    // at most three steps left: kt (in buf0), kt+1 (in set 0), kt+2 (not loaded yet)
+    if (kt + 2 < nk) load_step(1);
+    mfma_step(buf0);
+    if (kt + 1 < nk) {
+        unpack_step(0, buf1);
+        __syncthreads();
+        mfma_step(buf1);
+        if (kt + 2 < nk) {
+            unpack_step(1, buf0);
+            __syncthreads();
+            mfma_step(buf0);
+        }
     }
 
     // 32 x 32 accumulator: register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+            float *cp = C + (int64_t)(m0 + (wm * TM + i) * 32 + 4 * (lane >> 5)) * ldc + col;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                C[(int64_t)row * ldc + col] = acc[i][j][r];
-            }
+            for (int r = 0; r < 16; ++r)
+                __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)(8 * (r >> 2) + (r & 3)) * ldc);
         }
 }
 
+// Two tile shapes: 256 x 256 with 8 waves (128 KiB of LDS, one workgroup per CU)
+// when the device grants that much LDS to a workgroup and M, N allow it, else
+// 128 x 128 with 4 waves (64 KiB).
 template <int MBA, int MBB>
-void launch_gemm(const uint8_t *ac, const uint8_t *as, const uint8_t *am, const uint8_t *bc,
-                 const uint8_t *bs, const uint8_t *bm, int M, int N, int K, float *C, int64_t ldc,
-                 hipStream_t s)
+int launch_gemm(const uint8_t *ac, const uint8_t *as, const uint8_t *am, const uint8_t *bc,
+                const uint8_t *bs, const uint8_t *bm, int M, int N, int K, float *C, int64_t ldc,
+                hipStream_t s)
 {
-    const unsigned grid = (unsigned)((M / kBM) * (N / kBN));
-    const size_t lds = 4 * (size_t)kOperandBytes;
-    hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB>), dim3(grid), dim3(kGemmThreads), lds, s, ac, as,
-                       am, bc, bs, bm, M, N, K, C, ldc);
+    constexpr size_t kBigLds = 2 * (256 + 256) * (size_t)kPitch;
+    constexpr size_t kSmallLds = 2 * (128 + 128) * (size_t)kPitch;
+    static int big_ok = -1;  // does this device allow a 128 KiB workgroup?  asked once
+    if (big_ok < 0) {
+        int dev = 0, lds = 0;
+        big_ok = hipGetDevice(&dev) == hipSuccess &&
+                 hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
+                 (size_t)lds >= kBigLds &&
+                 hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBigLds) == hipSuccess;
+        (void)hipGetLastError();
+    }
+    if (big_ok == 1 && M % 256 == 0 && N % 256 == 0) {
+        const unsigned grid = (unsigned)((M / 256) * (N / 256));
+        hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>), dim3(grid), dim3(512), kBigLds, s,
+                           ac, as, am, bc, bs, bm, M, N, K, C, ldc);
+    } else {
+        const unsigned grid = (unsigned)((M / 128) * (N / 128));
+        hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 2, 2, 2>), dim3(grid), dim3(256), kSmallLds,
+                           s, ac, as, am, bc, bs, bm, M, N, K, C, ldc);
+    }
+    return launch_status();
 }
 
 template <int MBA>
-void pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, const uint8_t *bc,
-            const uint8_t *bs, const uint8_t *bm, int M, int N, int K, float *C, int64_t ldc,
-            hipStream_t s)
+int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, const uint8_t *bc,
+           const uint8_t *bs, const uint8_t *bm, int M, int N, int K, float *C, int64_t ldc,
+           hipStream_t s)
 {
-    if (mb == 7)
-        launch_gemm<MBA, 7>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
-    else if (mb == 4)
-        launch_gemm<MBA, 4>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
-    else
-        launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
+    if (mb == 7) return launch_gemm<MBA, 7>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
+    if (mb == 4) return launch_gemm<MBA, 4>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
+    return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
 }
 
 __global__ void gemm_zero_kernel(float *C, int64_t ldc, int N)
@@ -249,13 +326,9 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
     const uint8_t *ac = (const uint8_t *)a_codes, *as = (const uint8_t *)a_sexp,
                   *am = (const uint8_t *)a_mexp, *bc = (const uint8_t *)b_codes,
                   *bs = (const uint8_t *)b_sexp, *bm = (const uint8_t *)b_mexp;
-    if (fa.m == 7)
-        pick_b<7>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
-    else if (fa.m == 4)
-        pick_b<4>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
-    else
-        pick_b<2>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
-    return launch_status();
+    if (fa.m == 7) return pick_b<7>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
+    if (fa.m == 4) return pick_b<4>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
+    return pick_b<2>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
 }
 
 }  // namespace bdr
