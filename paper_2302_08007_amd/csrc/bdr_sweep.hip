@@ -184,7 +184,9 @@ __device__ __forceinline__ float quant_err2(const float (&yp)[kG][8], const int 
     for (int j = 0; j < kG; ++j)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const float y = __builtin_fminf(yp[j][i], top);  // held at the top code
+            // held at the top code; both are non-negative, so the integer minimum of the
+            // bit patterns is the float minimum (and needs no NaN canonicalization)
+            const float y = as_f(umin(as_u(yp[j][i]), as_u(top)));
             float r;
             if (ROUNDING == BDR_RNE) {
                 r = (y + magic) - magic;
