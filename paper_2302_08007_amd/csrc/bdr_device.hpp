@@ -28,6 +28,7 @@ constexpr float kMagic = 8388608.0f;  // 2^23: adding it rounds to an integer, t
 constexpr int kQuadXor1 = 0xB1;  // quad_perm:[1,0,3,2]
 constexpr int kQuadXor2 = 0x4E;  // quad_perm:[2,3,0,1]
 constexpr int kQuadNext = 0xF9;  // quad_perm:[1,2,3,3]  lane i reads lane i+1 of its quad
+constexpr int kQuadPrev = 0x90;  // quad_perm:[0,0,1,2]  lane i reads lane i-1 of its quad
 constexpr int kRowHalfMirror = 0x141;
 constexpr int kRowMirror = 0x140;
 

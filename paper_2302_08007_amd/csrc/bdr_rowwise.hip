@@ -134,9 +134,16 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
             v0[it] = v.x;
             v1[it] = v.y;
         } else if (CB == 5) {
-            load_pair_a4(codes + 20 * quad + 4 * i, v0[it], v1[it]);
+            // aligned dword loads only: lane i takes dword i of the quad's five, the
+            // fifth is fetched by all four lanes and used by lane 3
+            const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 5 * quad;
+            v0[it] = cw[i];
+            v1[it] = cw[4];
         } else {
-            load_pair_a4(codes + 12 * quad + 4 * (i >> 1), v0[it], v1[it]);
+            // lane i takes dword min(i, 2) of the quad's three
+            const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 3 * quad;
+            v0[it] = cw[i < 2 ? i : 2];
+            v1[it] = 0;
         }
         seb[it] = sexp[g >> 1];
         tb[it] = mexp[g >> 1];
@@ -150,13 +157,17 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
             lo = v0[it];
             hi = v1[it];
         } else if (CB == 5) {
-            // lane i's 40 bits start 8 i bits into dword i of the quad's 5 dwords
-            lo = funnel_r(v1[it], v0[it], 8u * i);
-            hi = (v1[it] >> (8u * i)) & 0xffu;
+            // lane i's 40 bits start 8 i bits into dword i of the quad's 5 dwords; the
+            // following dword comes from the next lane (lane 3: the fifth dword)
+            const uint32_t nx = dpp<kQuadNext>(v0[it]);
+            const uint32_t up = i == 3 ? v1[it] : nx;
+            lo = funnel_r(up, v0[it], 8u * i);
+            hi = (up >> (8u * i)) & 0xffu;
         } else {
-            // lane i's 24 bits start at bit 24 i of the quad's 3 dwords
-            const uint64_t w = ((uint64_t)v1[it] << 32) | v0[it];
-            lo = (uint32_t)(w >> (24u * i - 32u * (i >> 1))) & 0xffffffu;
+            // lane i's 24 bits start at bit 24 i of the quad's 3 dwords: the end of the
+            // previous lane's dword and the start of its own (lane 3: all in dword 2)
+            const uint32_t pv = dpp<kQuadPrev>(v0[it]);
+            lo = funnel_r(v0[it], pv, 24u * i) & 0xffffffu;
         }
         const uint32_t se = seb[it];
         const uint32_t tau4 = (tb[it] >> (4u * (i & 1u))) & 0xfu;
