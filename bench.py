@@ -97,22 +97,27 @@ def main():
     planes = {n: B.alloc_planes(getattr(B, n), rows, cols) for n in FORMATS}
     fm = {n: getattr(B, n) for n in FORMATS}
     bits = {"MX9": 9, "MX6": 6, "MX4": 4}
-    q6_events = []
+    marks = []  # per timed step: 7 events bracketing the six kernels
 
     def step(record):
         # all three quantizes, then all three dequantizes: alternating a read-heavy and a
         # write-heavy kernel makes each wait for the other's write-back
+        ev = []
+
+        def mark():
+            if record:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                ev.append(e)
+        mark()
         for n in FORMATS:
-            if record and n == "MX6":
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                B.bdr_quantize(fm[n], x, out=planes[n])
-                b.record()
-                q6_events.append((a, b))
-            else:
-                B.bdr_quantize(fm[n], x, out=planes[n])
+            B.bdr_quantize(fm[n], x, out=planes[n])
+            mark()
         for n in FORMATS:
             B.bdr_dequantize(fm[n], planes[n], rows, cols, out=y)
+            mark()
+        if record:
+            marks.append(ev)
 
     if args.pmc_probe:
         # the copy reads 1 GiB and writes 1 GiB: it calibrates the counters' units
@@ -138,8 +143,12 @@ def main():
     step_bytes = sum(2 * alg_bytes(N_ELEMS, bits[n]) for n in FORMATS)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    q6_ms = sorted(a.elapsed_time(b) for a, b in q6_events)
-    q6_avg = sum(q6_ms) / len(q6_ms)
+    labels = ["quantize_" + n for n in FORMATS] + ["dequantize_" + n for n in FORMATS]
+    in_loop_us = {}
+    for k, lab in enumerate(labels):
+        ts = [ev[k].elapsed_time(ev[k + 1]) for ev in marks]
+        in_loop_us[lab] = sum(ts) / len(ts) * 1e3
+    q6_avg = in_loop_us["quantize_MX6"] * 1e-3
     q6_bytes = alg_bytes(N_ELEMS, 6)
     achieved = q6_bytes / (q6_avg * 1e-3) / 1e9
     roofline = {
@@ -169,15 +178,19 @@ def main():
 
     other = {}
     if not args.no_other:
+        # per-kernel figures from the timed loop itself (steady state, planes cold); the fused
+        # round trip is timed on its own (2 GiB of traffic per call, nothing fits a cache)
         per = {}
         for n in FORMATS:
-            tq = timed(lambda: B.bdr_quantize(fm[n], x, out=planes[n]))
-            td = timed(lambda: B.bdr_dequantize(fm[n], planes[n], rows, cols, out=y))
-            tf = timed(lambda: B.bdr_quantize_dequantize(fm[n], x, out=y))
             ab = alg_bytes(N_ELEMS, bits[n])
+            tq, td = in_loop_us["quantize_" + n] * 1e-3, in_loop_us["dequantize_" + n] * 1e-3
+            tf = timed(lambda: B.bdr_quantize_dequantize(fm[n], x, out=y))
             per[n] = {
-                "quantize_GBps": round(ab / tq / 1e6, 1), "quantize_frac": round(ab / tq / 1e6 / HBM_PEAK_GBS, 4),
-                "dequantize_GBps": round(ab / td / 1e6, 1), "dequantize_frac": round(ab / td / 1e6 / HBM_PEAK_GBS, 4),
+                "quantize_us": round(tq * 1e3, 1), "quantize_GBps": round(ab / tq / 1e6, 1),
+                "quantize_frac": round(ab / tq / 1e6 / HBM_PEAK_GBS, 4),
+                "dequantize_us": round(td * 1e3, 1), "dequantize_GBps": round(ab / td / 1e6, 1),
+                "dequantize_frac": round(ab / td / 1e6 / HBM_PEAK_GBS, 4),
+                "fused_roundtrip_us": round(tf * 1e3, 1),
                 "fused_roundtrip_GBps": round(8.0 * N_ELEMS / tf / 1e6, 1),
                 "fused_roundtrip_frac": round(8.0 * N_ELEMS / tf / 1e6 / HBM_PEAK_GBS, 4),
                 "quantize_Gelem_s": round(N_ELEMS / tq / 1e6, 1),

@@ -10,13 +10,17 @@
 //   - The exponent of the maximum over every aligned power-of-two group of
 //     1 .. 256 elements is computed once per load (in-lane for groups up to 8,
 //     DPP / one shuffle across lanes above that).
-//   - Formats are grouped on the host into "classes" (k1, k2, d2): within a
-//     class every element has the same effective exponent
-//         eps = max(E_block - beta, E_subblock)      (Sec. IX: tau <= beta)
-//     so it is computed once per class.  d2 = 0 and k2 = k1 both mean tau = 0
-//     and share a class; identical tuples share one accumulator.
-//   - A quantizer (class, m, rounding) then costs six VALU operations per
-//     element: scale, clamp, round, subtract, unscale, square-accumulate.
+//   - Formats are put on the host into groups of equal k1.  With E the block
+//     exponent, a format of the group quantizes an element at the effective
+//     exponent E - tau, tau = min(beta, E - E_sub) (Sec. IX), so for a given
+//     (m, rounding) the error of an element can only take beta + 1 values.  When
+//     every format of the group has beta <= 1 the two candidate squared errors
+//     (tau = 0 and tau = 1) are computed once per (m, rounding) and each
+//     (k2, d2) class just selects between them: one compare per element per
+//     class, one select and one add per element per quantizer.  d2 = 0 and
+//     k2 = k1 both mean tau = 0 and share a class; identical tuples share one
+//     accumulator.  Groups with a larger beta evaluate every class directly
+//     (scale, clamp, round, subtract, unscale, square-accumulate).
 //
 // Range: squares of FP32 numbers underflow for small tensors, so the kernel works
 // on x * 2^s with s chosen from the tensor's largest exponent (a tiny pre-pass)
@@ -25,8 +29,9 @@
 // than 126 binades below the tensor maximum, whose contribution is below 2^-250
 // of either sum.
 //
-// Sums: FP32 inside a lane over at most 32 elements, FP64 from there on;
-// per-block partials are combined in a fixed order, so results are reproducible.
+// Sums: every lane keeps one FP32 partial per quantizer in LDS (a lane sees only
+// n / 524288 elements, so FP32 is ample), lanes and workgroups are combined in
+// FP64 in a fixed order, so results are reproducible.
 #include "bdr_device.hpp"
 #include "bdr_internal.hpp"
 
@@ -35,26 +40,32 @@ namespace bdr {
 namespace {
 
 constexpr int kSweepThreads = 256;
-constexpr int kWaves = kSweepThreads / 64;
-constexpr int kG = 4;  // groups of 8 elements per lane per iteration
+constexpr int kG = 2;  // groups of 8 elements per lane per iteration
 constexpr int kMaxBlocks = 2048;
-constexpr int kChunk = 256;  // formats per launch: keeps the kernel arguments under 4 KiB
+constexpr int kChunk = 128;  // formats per launch: bounds kernel arguments (< 4 KiB) and LDS
+constexpr int kMaxGroups = kChunk;
 constexpr int kMaxClasses = kChunk;
-constexpr int kMaxQuant = kChunk;
-constexpr size_t kHeaderBytes = 256;                            // Header
-constexpr size_t kTotalsBytes = 4096 - 256;                     // kChunk + 1 doubles fit
+constexpr int kMR = 2;       // (m, rounding) pairs evaluated together in one group
+constexpr size_t kHeaderBytes = 256;          // Header
+constexpr size_t kTotalsBytes = 4096 - 256;   // kChunk + 1 doubles fit
+constexpr uint16_t kNone = 0xffff;
 
-struct ClassDesc {
-    uint8_t lk1, lk2, beta, nq;  // log2 k1, log2 k2, 2^d2 - 1, quantizers in the class
-    uint16_t first;              // index of its first quantizer
+struct GroupDesc {
+    uint8_t lk1;       // log2 k1
+    uint8_t shared;    // 1: all classes have beta <= 1 and select between two candidates
+    uint8_t n_mr;      // (m, rounding) pairs in use (<= kMR)
+    uint8_t n_cls;     // classes of this group
+    uint16_t first;    // index of its first class
+    uint8_t m[kMR], rnd[kMR];
 };
-struct QuantDesc {
-    uint8_t m, rounding;
+struct ClassDesc {
+    uint8_t lk2, beta;   // log2 k2, 2^d2 - 1
+    uint16_t q[kMR];     // accumulator of (this class, mr), kNone when no format asks for it
 };
 struct SweepPlan {
-    int32_t n_class, n_quant;
+    int32_t n_group, n_quant;
+    GroupDesc grp[kMaxGroups];
     ClassDesc cls[kMaxClasses];
-    QuantDesc q[kMaxQuant];
 };
 struct FormatMap {
     uint16_t idx[kChunk];  // format -> quantizer
@@ -168,49 +179,75 @@ __device__ __forceinline__ void level_exps(const Levels &L, int lk, int (&out)[8
     }
 }
 
-// Squared error of one quantizer summed over the lane's kG*8 elements, in the
-// tensor's (pre-scaled) units.  yp = |x| * 2^sh lies in [0, 2) with the top
-// magnitude bit at weight 2^0; nsh = -sh.
-//   nearest-even: adding 2^(24-m) to a value in [0, 2) rounds it to a multiple
-//   of 2^-(m-1), which is the step of an m-bit magnitude at that weight.
-template <int ROUNDING>
-__device__ __forceinline__ float quant_err2(const float (&yp)[kG][8], const int (&nsh)[kG][8], int m)
+// y in [0, 2) is |x| scaled so that the top magnitude bit has weight 2^0.  Returns
+// y minus its m-bit quantized value (exact): nearest-even by adding 2^(24-m)
+// (a value in [0, 2) then rounds to a multiple of 2^-(m-1), the step of an m-bit
+// magnitude at that weight), or through an integer for ties-away / truncation.
+struct MrConst {
+    float top, magic;
+    int m, rounding;
+};
+__device__ __forceinline__ MrConst mr_const(int m, int rounding)
 {
-    const float step = __builtin_ldexpf(1.0f, 1 - m);
-    const float top = 2.0f - step;
-    const float magic = __builtin_ldexpf(1.0f, 24 - m);
-    float acc = 0.f;
+    MrConst c;
+    c.top = 2.0f - __builtin_ldexpf(1.0f, 1 - m);
+    c.magic = __builtin_ldexpf(1.0f, 24 - m);
+    c.m = m;
+    c.rounding = rounding;
+    return c;
+}
+template <int ROUNDING>
+__device__ __forceinline__ float quant_diff(float yp, const MrConst &c)
+{
+    // held at the top code; both are non-negative, so the integer minimum of the
+    // bit patterns is the float minimum (and needs no NaN canonicalization)
+    const float y = as_f(umin(as_u(yp), as_u(c.top)));
+    float r;
+    if (ROUNDING == BDR_RNE) {
+        r = (y + c.magic) - c.magic;
+    } else {
+        const float sc = __builtin_ldexpf(y, c.m - 1);
+        const float t = __builtin_truncf(sc);
+        const float up = (ROUNDING == BDR_RNA && (sc - t) >= 0.5f) ? 1.0f : 0.0f;
+        r = __builtin_ldexpf(t + up, 1 - c.m);
+    }
+    return yp - r;
+}
+
+// squared error, in the tensor's (pre-scaled) units, of |x| = y * 2^-sh
+template <int ROUNDING>
+__device__ __forceinline__ float quant_err2(float y, int sh, const MrConst &c)
+{
+    const float d = __builtin_ldexpf(quant_diff<ROUNDING>(y, c), -sh);
+    return d * d;
+}
+
+// both candidate squared errors of one (m, rounding): block exponent as is, and one lower
+template <int ROUNDING>
+__device__ __forceinline__ void candidates(const float (&ax)[kG][8], const int (&cb)[kG][8],
+                                           const MrConst &c, float (&e0)[kG][8],
+                                           float (&e1)[kG][8])
+{
 #pragma unroll
     for (int j = 0; j < kG; ++j)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            // held at the top code; both are non-negative, so the integer minimum of the
-            // bit patterns is the float minimum (and needs no NaN canonicalization)
-            const float y = as_f(umin(as_u(yp[j][i]), as_u(top)));
-            float r;
-            if (ROUNDING == BDR_RNE) {
-                r = (y + magic) - magic;
-            } else {
-                const float sc = __builtin_ldexpf(y, m - 1);
-                const float t = __builtin_truncf(sc);
-                const float up = (ROUNDING == BDR_RNA && (sc - t) >= 0.5f) ? 1.0f : 0.0f;
-                r = __builtin_ldexpf(t + up, 1 - m);
-            }
-            const float d = __builtin_ldexpf(yp[j][i] - r, nsh[j][i]);  // difference is exact
-            acc = __builtin_fmaf(d, d, acc);
+            const float y0 = __builtin_ldexpf(ax[j][i], cb[j][i]);
+            e0[j][i] = quant_err2<ROUNDING>(y0, cb[j][i], c);
+            e1[j][i] = quant_err2<ROUNDING>(y0 + y0, cb[j][i] + 1, c);
         }
-    return acc;
 }
 
-__device__ __forceinline__ float wave_sum(float v)
+template <int ROUNDING>
+__device__ __forceinline__ float direct(const float (&yp)[kG][8], const int (&sh)[kG][8],
+                                        const MrConst &c)
 {
-    v += as_f(dpp<kQuadXor1>(as_u(v)));
-    v += as_f(dpp<kQuadXor2>(as_u(v)));
-    v += as_f(dpp<kRowHalfMirror>(as_u(v)));
-    v += as_f(dpp<kRowMirror>(as_u(v)));
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < kG; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += quant_err2<ROUNDING>(yp[j][i], sh[j][i], c);
+    return sum;
 }
 
 template <typename T>
@@ -218,12 +255,11 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
     SweepPlan plan, const T *__restrict__ x, int64_t cols, int64_t ld, int64_t n_groups,
     const Header *__restrict__ hdr, double *__restrict__ partials)
 {
-    extern __shared__ double s_acc[];  // [kWaves][n_quant + 1]
+    extern __shared__ float s_lane[];  // [n_quant + 1][kSweepThreads]: one partial per lane
     const int nq = plan.n_quant;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int t = threadIdx.x; t < kWaves * (nq + 1); t += kSweepThreads) s_acc[t] = 0.0;
-    __syncthreads();
-    double *wacc = s_acc + wave * (nq + 1);
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int q = 0; q <= nq; ++q) s_lane[q * kSweepThreads + tid] = 0.f;
+    auto add_to = [&](int q, float v) { s_lane[q * kSweepThreads + tid] += v; };
 
     // Work on x * 2^sref so that the tensor maximum lands in [1, 2).
     const int eref = (int)(umin(umax(hdr->absmax_bits, kMagLo), kMagHi) >> 23);
@@ -239,7 +275,7 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
         float sig = 0.f;
 #pragma unroll
         for (int j = 0; j < kG; ++j) {
-            const int64_t g = base + (int64_t)wave * (64 * kG) + j * 64 + lane;
+            const int64_t g = base + (int64_t)(tid >> 6) * (64 * kG) + j * 64 + lane;
             uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             if (g < n_groups) {
                 const int64_t t0 = 8 * g;
@@ -255,45 +291,119 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
             }
             build_levels(ab, mag_lo, L[j]);
         }
-        sig = wave_sum(sig);
-        if (lane == 0) wacc[nq] += (double)sig;
+        add_to(nq, sig);
 
-        for (int c = 0; c < plan.n_class; ++c) {
-            const ClassDesc cd = plan.cls[c];
-            // sh = 127 - max(E_block - beta, E_sub) = min(127 - E_block + beta, 127 - E_sub)
-            float yp[kG][8];
-            int nsh[kG][8];
+        for (int gi = 0; gi < plan.n_group; ++gi) {
+            const GroupDesc gd = plan.grp[gi];
+            int cb[kG][8];  // 127 - E_block: scaling |x| by 2^cb puts the block maximum in [1, 2)
 #pragma unroll
-            for (int j = 0; j < kG; ++j) {
-                int cb[8], cs[8];
-                level_exps(L[j], cd.lk1, cb);
-                level_exps(L[j], cd.lk2, cs);
+            for (int j = 0; j < kG; ++j) level_exps(L[j], gd.lk1, cb[j]);
+
+            if (gd.shared) {
+                // candidates: squared error at tau = 0 and at tau = 1, per (m, rounding)
+                float e0[kMR][kG][8], e1[kMR][kG][8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int sh = min(cb[i] + (int)cd.beta, cs[i]);
-                    yp[j][i] = __builtin_ldexpf(ax[j][i], sh);
-                    nsh[j][i] = -sh;
+                for (int r = 0; r < kMR; ++r) {
+                    if (r < gd.n_mr) {
+                        const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
+                        if (c.rounding == BDR_RNE)
+                            candidates<BDR_RNE>(ax, cb, c, e0[r], e1[r]);
+                        else if (c.rounding == BDR_RNA)
+                            candidates<BDR_RNA>(ax, cb, c, e0[r], e1[r]);
+                        else
+                            candidates<BDR_RTZ>(ax, cb, c, e0[r], e1[r]);
+                    }
                 }
-            }
-            for (int k = 0; k < cd.nq; ++k) {
-                const QuantDesc qd = plan.q[cd.first + k];
-                float e2;
-                if (qd.rounding == BDR_RNE)
-                    e2 = quant_err2<BDR_RNE>(yp, nsh, qd.m);
-                else if (qd.rounding == BDR_RNA)
-                    e2 = quant_err2<BDR_RNA>(yp, nsh, qd.m);
-                else
-                    e2 = quant_err2<BDR_RTZ>(yp, nsh, qd.m);
-                e2 = wave_sum(e2);
-                if (lane == 0) wacc[cd.first + k] += (double)e2;
+                for (int ci = 0; ci < gd.n_cls; ++ci) {
+                    const ClassDesc cd = plan.cls[gd.first + ci];
+                    if (cd.beta == 0) {
+#pragma unroll
+                        for (int r = 0; r < kMR; ++r) {
+                            if (r < gd.n_mr && cd.q[r] != kNone) {
+                                float sum = 0.f;
+#pragma unroll
+                                for (int j = 0; j < kG; ++j)
+#pragma unroll
+                                    for (int i = 0; i < 8; ++i) sum += e0[r][j][i];
+                                add_to(cd.q[r], sum);
+                            }
+                        }
+                    } else {
+                        // tau = 1 exactly where the sub-block exponent is below the block's
+                        bool down[kG][8];
+#pragma unroll
+                        for (int j = 0; j < kG; ++j) {
+                            int cs[8];
+                            level_exps(L[j], cd.lk2, cs);
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) down[j][i] = cs[i] > cb[j][i];
+                        }
+#pragma unroll
+                        for (int r = 0; r < kMR; ++r) {
+                            if (r < gd.n_mr && cd.q[r] != kNone) {
+                                float sum = 0.f;
+#pragma unroll
+                                for (int j = 0; j < kG; ++j)
+#pragma unroll
+                                    for (int i = 0; i < 8; ++i)
+                                        sum += down[j][i] ? e1[r][j][i] : e0[r][j][i];
+                                add_to(cd.q[r], sum);
+                            }
+                        }
+                    }
+                }
+            } else {
+                for (int ci = 0; ci < gd.n_cls; ++ci) {
+                    const ClassDesc cd = plan.cls[gd.first + ci];
+                    // sh = 127 - max(E_block - beta, E_sub) = min(127 - E_block + beta, 127 - E_sub)
+                    int sh[kG][8];
+                    float yp[kG][8];
+#pragma unroll
+                    for (int j = 0; j < kG; ++j) {
+                        int cs[8];
+                        level_exps(L[j], cd.lk2, cs);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            sh[j][i] = min(cb[j][i] + (int)cd.beta, cs[i]);
+                            yp[j][i] = __builtin_ldexpf(ax[j][i], sh[j][i]);
+                        }
+                    }
+#pragma unroll
+                    for (int r = 0; r < kMR; ++r) {
+                        if (r < gd.n_mr && cd.q[r] != kNone) {
+                            const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
+                            float sum;
+                            if (c.rounding == BDR_RNE)
+                                sum = direct<BDR_RNE>(yp, sh, c);
+                            else if (c.rounding == BDR_RNA)
+                                sum = direct<BDR_RNA>(yp, sh, c);
+                            else
+                                sum = direct<BDR_RTZ>(yp, sh, c);
+                            add_to(cd.q[r], sum);
+                        }
+                    }
+                }
             }
         }
     }
     __syncthreads();
-    for (int t = threadIdx.x; t <= nq; t += kSweepThreads) {
+    // Lane partials -> one FP64 value per quantizer for this workgroup.  32 quantizers
+    // at a time: 8 threads share a quantizer, each sums 32 lanes (start rotated so a
+    // wave touches 64 distinct banks), then the 8 are combined in a fixed order.
+    const int part = tid & 7, slot = tid >> 3;
+    const int rot = (slot & 7) + 8 * (part >> 1);
+    for (int q0 = 0; q0 <= nq; q0 += 32) {
+        const int q = q0 + slot;
         double v = 0.0;
-        for (int w = 0; w < kWaves; ++w) v += s_acc[w * (nq + 1) + t];
-        partials[(int64_t)blockIdx.x * (nq + 1) + t] = v;
+        if (q <= nq) {
+            const float *src = s_lane + q * kSweepThreads + part * 32;
+#pragma unroll 8
+            for (int i = 0; i < 32; ++i) v += (double)src[(i + rot) & 31];
+        }
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 4);
+        if (q <= nq && part == 0) partials[(int64_t)blockIdx.x * (nq + 1) + q] = v;
     }
 }
 
@@ -348,61 +458,101 @@ size_t sweep_workspace_bytes(int32_t n_fmts)
 
 namespace {
 
-// Host plan for up to kChunk formats: classes of (k1, k2, beta) with the tau = 0
-// formats merged, and within a class one quantizer per distinct (m, rounding).
+// Host plan for up to kChunk formats: groups of equal k1 (split so that a group
+// holds at most kMR (m, rounding) pairs and is either all beta <= 1 or all
+// beta >= 2), classes (k2, beta) inside a group with the tau = 0 formats merged,
+// and one accumulator per distinct (class, m, rounding).
 void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &map)
 {
-    struct Key {
-        int lk1, lk2, beta, m, rnd;
-    };
-    Key keys[kMaxQuant];
-    int order[kChunk];
-    int nq = 0;
+    int ng = 0;
+    int f_group[kChunk], f_mr[kChunk], f_lk2[kChunk], f_beta[kChunk];
     for (int f = 0; f < n_fmts; ++f) {
-        Key k = {ilog2(fmts[f].k1), ilog2(fmts[f].k2), (1 << fmts[f].d2) - 1, fmts[f].m,
-                 fmts[f].rounding};
-        if (k.beta == 0 || k.lk2 == k.lk1) {  // no sub-block shift: plain block floating point
-            k.beta = 0;
-            k.lk2 = k.lk1;
+        const int lk1 = ilog2(fmts[f].k1);
+        int lk2 = ilog2(fmts[f].k2), beta = (1 << fmts[f].d2) - 1;
+        const int m = fmts[f].m, rnd = fmts[f].rounding;
+        if (beta == 0 || lk2 == lk1) {  // no sub-block shift: plain block floating point
+            beta = 0;
+            lk2 = lk1;
         }
-        int found = -1;
-        for (int j = 0; j < nq && found < 0; ++j)
-            if (keys[j].lk1 == k.lk1 && keys[j].lk2 == k.lk2 && keys[j].beta == k.beta &&
-                keys[j].m == k.m && keys[j].rnd == k.rnd)
-                found = j;
-        if (found < 0) {
-            keys[nq] = k;
-            found = nq++;
+        const int shared = beta <= 1;
+        // a group of this k1 and kind that has this (m, rounding), else one with room for it
+        int gi = -1, r = -1;
+        for (int g = 0; g < ng && gi < 0; ++g) {
+            const GroupDesc &gd = plan.grp[g];
+            if (gd.lk1 != lk1 || gd.shared != shared) continue;
+            for (int k = 0; k < gd.n_mr; ++k)
+                if (gd.m[k] == m && gd.rnd[k] == rnd) {
+                    gi = g;
+                    r = k;
+                }
         }
-        order[f] = found;
+        for (int g = 0; g < ng && gi < 0; ++g) {
+            GroupDesc &gd = plan.grp[g];
+            if (gd.lk1 != lk1 || gd.shared != shared || gd.n_mr == kMR) continue;
+            gi = g;
+            r = gd.n_mr++;
+            gd.m[r] = (uint8_t)m;
+            gd.rnd[r] = (uint8_t)rnd;
+        }
+        if (gi < 0) {
+            gi = ng++;
+            GroupDesc &gd = plan.grp[gi];
+            gd = GroupDesc{};
+            gd.lk1 = (uint8_t)lk1;
+            gd.shared = (uint8_t)shared;
+            gd.n_mr = 1;
+            gd.m[0] = (uint8_t)m;
+            gd.rnd[0] = (uint8_t)rnd;
+            r = 0;
+        }
+        f_group[f] = gi;
+        f_mr[f] = r;
+        f_lk2[f] = lk2;
+        f_beta[f] = beta;
     }
-    int newidx[kMaxQuant];
-    bool placed[kMaxQuant] = {false};
-    int nc = 0, pos = 0;
-    for (int j = 0; j < nq; ++j) {
-        if (placed[j]) continue;
-        ClassDesc &cd = plan.cls[nc++];
-        cd.lk1 = (uint8_t)keys[j].lk1;
-        cd.lk2 = (uint8_t)keys[j].lk2;
-        cd.beta = (uint8_t)keys[j].beta;
-        cd.first = (uint16_t)pos;
-        int cnt = 0;
-        for (int i = j; i < nq; ++i) {
-            if (placed[i] || keys[i].lk1 != keys[j].lk1 || keys[i].lk2 != keys[j].lk2 ||
-                keys[i].beta != keys[j].beta)
-                continue;
-            placed[i] = true;
-            newidx[i] = pos;
-            plan.q[pos].m = (uint8_t)keys[i].m;
-            plan.q[pos].rounding = (uint8_t)keys[i].rnd;
-            ++pos;
-            ++cnt;
+    // classes of a group are contiguous; accumulators are numbered in that order
+    int nc = 0, nq = 0;
+    for (int g = 0; g < ng; ++g) {
+        GroupDesc &gd = plan.grp[g];
+        gd.first = (uint16_t)nc;
+        int n_cls = 0;
+        for (int f = 0; f < n_fmts; ++f) {
+            if (f_group[f] != g) continue;
+            int ci = -1;
+            for (int c = 0; c < n_cls && ci < 0; ++c)
+                if (plan.cls[nc + c].lk2 == f_lk2[f] && plan.cls[nc + c].beta == f_beta[f]) ci = c;
+            if (ci < 0) {
+                ci = n_cls++;
+                ClassDesc &cd = plan.cls[nc + ci];
+                cd.lk2 = (uint8_t)f_lk2[f];
+                cd.beta = (uint8_t)f_beta[f];
+                for (int k = 0; k < kMR; ++k) cd.q[k] = kNone;
+            }
+            ClassDesc &cd = plan.cls[nc + ci];
+            if (cd.q[f_mr[f]] == kNone) cd.q[f_mr[f]] = (uint16_t)nq++;
+            map.idx[f] = cd.q[f_mr[f]];
         }
-        cd.nq = (uint8_t)cnt;  // at most 8 values of m x 3 roundings
+        gd.n_cls = (uint8_t)n_cls;
+        nc += n_cls;
     }
-    plan.n_class = nc;
+    plan.n_group = ng;
     plan.n_quant = nq;
-    for (int f = 0; f < n_fmts; ++f) map.idx[f] = (uint16_t)newidx[order[f]];
+}
+
+// The lane-partial array needs (n_quant + 1) KiB of LDS; allow the full 160 KiB once.
+template <typename T>
+int sweep_lds_ok(size_t bytes)
+{
+    static int state = 0;  // 0 unknown, 1 ok, -1 failed
+    if (bytes <= 64 * 1024) return 1;
+    if (state == 0)
+        state = hipFuncSetAttribute((const void *)sweep_kernel<T>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)((kChunk + 1) * kSweepThreads * sizeof(float))) ==
+                        hipSuccess
+                    ? 1
+                    : -1;
+    return state;
 }
 
 }  // namespace
@@ -442,7 +592,9 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
         FormatMap map;
         make_plan(fmts + f0, nf, plan, map);
         const int nq = plan.n_quant;
-        const size_t lds = (size_t)kWaves * (size_t)(nq + 1) * sizeof(double);
+        const size_t lds = (size_t)(nq + 1) * kSweepThreads * sizeof(float);
+        if ((dtype == BDR_F32 ? sweep_lds_ok<float>(lds) : sweep_lds_ok<uint16_t>(lds)) < 0)
+            return BDR_ERR_LAUNCH;
         if (dtype == BDR_F32)
             hipLaunchKernelGGL(sweep_kernel<float>, dim3((unsigned)nb), dim3(kSweepThreads), lds,
                                s, plan, (const float *)x, cols, ld, n_groups, hdr, partials);
