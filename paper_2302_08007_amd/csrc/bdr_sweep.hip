@@ -29,9 +29,10 @@
 // than 126 binades below the tensor maximum, whose contribution is below 2^-250
 // of either sum.
 //
-// Sums: every lane keeps one FP32 partial per quantizer in LDS (a lane sees only
-// n / 524288 elements, so FP32 is ample), lanes and workgroups are combined in
-// FP64 in a fixed order, so results are reproducible.
+// Sums: every lane keeps one FP32 partial per quantizer in LDS; after at most
+// 1024 elements per lane the partials are folded, in a fixed order, into FP64
+// sums held by the workgroup, and workgroups are combined in FP64 in a fixed
+// order as well, so results are reproducible.
 #include "bdr_device.hpp"
 #include "bdr_internal.hpp"
 
@@ -41,16 +42,21 @@ namespace {
 
 constexpr int kSweepThreads = 256;
 constexpr int kG = 2;  // groups of 8 elements per lane per iteration
-constexpr int kMaxBlocks = 2048;
+constexpr int kSweepBlocks = 512;  // two resident workgroups per compute unit
+
 constexpr int kChunk = 128;  // formats per launch: bounds kernel arguments (< 4 KiB) and LDS
 constexpr int kMaxGroups = kChunk;
 constexpr int kMaxClasses = kChunk;
 constexpr int kMR = 2;       // (m, rounding) pairs evaluated together in one group
-constexpr size_t kHeaderBytes = 256;          // Header
-constexpr size_t kTotalsBytes = 4096 - 256;   // kChunk + 1 doubles fit
+constexpr int kAbsBlocks = 512;               // workgroups of the maximum pass
+constexpr size_t kHeaderBytes = 4096;         // per-workgroup maxima (kAbsBlocks words), rest unused
 constexpr uint16_t kNone = 0xffff;
+constexpr int kFoldPasses = (kChunk + 1 + 31) / 32;  // quantizers + signal, 32 per pass
+constexpr int kFoldEvery = 1024 / (8 * kG);          // iterations between folds
 
-struct GroupDesc {
+// Both descriptors are sized and aligned so that a wave fetches one with a single
+// scalar load.
+struct alignas(16) GroupDesc {
     uint8_t lk1;       // log2 k1
     uint8_t shared;    // 1: all classes have beta <= 1 and select between two candidates
     uint8_t n_mr;      // (m, rounding) pairs in use (<= kMR)
@@ -58,59 +64,72 @@ struct GroupDesc {
     uint16_t first;    // index of its first class
     uint8_t m[kMR], rnd[kMR];
 };
-struct ClassDesc {
+struct alignas(8) ClassDesc {
     uint8_t lk2, beta;   // log2 k2, 2^d2 - 1
     uint16_t q[kMR];     // accumulator of (this class, mr), kNone when no format asks for it
 };
 struct SweepPlan {
     int32_t n_group, n_quant;
     GroupDesc grp[kMaxGroups];
-    ClassDesc cls[kMaxClasses];
+    ClassDesc cls[kMaxClasses + 1];  // one past the end may be read ahead
 };
 struct FormatMap {
     uint16_t idx[kChunk];  // format -> quantizer
 };
 
-struct Header {
-    uint32_t absmax_bits;
-};
-
-__global__ void sweep_clear_kernel(Header *h) { h->absmax_bits = 0; }
-
-// Largest magnitude of the tensor.  Only its exponent is used, so a block whose
-// maximum does not raise the exponent already recorded skips the atomic.
+// Largest magnitude of the tensor, first pass: one value per workgroup (all
+// kAbsBlocks slots are written, zero when a workgroup had nothing to read).
 template <typename T>
 __global__ __launch_bounds__(256) void sweep_absmax_kernel(const T *__restrict__ x, int64_t cols,
-                                                           int64_t ld, int64_t n_groups, Header *h)
+                                                           int64_t ld, int64_t n_groups,
+                                                           uint32_t *__restrict__ blockmax)
 {
     __shared__ uint32_t s_m[4];
     uint32_t m = 0;
-    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < n_groups;
-         g += (int64_t)gridDim.x * 256) {
-        const int64_t t0 = 8 * g;
-        const int64_t r = ld == cols ? 0 : t0 / cols;
-        uint32_t xb[8];
-        load8(x + r * ld + (t0 - r * cols), xb);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < n_groups; g0 += 2 * stride) {
+        uint32_t xb[2][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) m = umax(m, xb[i] & kAbsMask);
+        for (int u = 0; u < 2; ++u) {
+            const int64_t g = g0 + u * stride;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xb[u][i] = 0;
+            if (g < n_groups) {
+                const int64_t t0 = 8 * g;
+                const int64_t r = ld == cols ? 0 : t0 / cols;
+                load8(x + r * ld + (t0 - r * cols), xb[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m = umax(m, xb[u][i] & kAbsMask);
     }
     for (int w = 32; w > 0; w >>= 1) m = umax(m, (uint32_t)__shfl_xor((int)m, w));
     if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        m = umax(umax(s_m[0], s_m[1]), umax(s_m[2], s_m[3]));
-        const uint32_t seen = __atomic_load_n(&h->absmax_bits, __ATOMIC_RELAXED);
-        if ((m >> 23) > (seen >> 23)) atomicMax(&h->absmax_bits, m);
-    }
+    if (threadIdx.x == 0) blockmax[blockIdx.x] = umax(umax(s_m[0], s_m[1]), umax(s_m[2], s_m[3]));
 }
 
-// Scaling exponents 127 - e of the maxima over aligned groups, for one run of 8
-// elements, as signed bytes (127 - e lies in [-127, 126]):
-//   w[0], w[1]  per element            w[2]  per pair
-//   w[3]        per 4 (bytes 0-1), per 8 and per 16 (bytes 2-3)
-//   w[4]        per 32, 64, 128, 256
+// Second pass, run by every wave that needs it: biased exponent of the largest
+// magnitude, held inside [1, 254].
+__device__ __forceinline__ int tensor_exponent(const uint32_t *__restrict__ blockmax)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t m = 0;
+#pragma unroll
+    for (int i = 0; i < kAbsBlocks / 64; ++i) m = umax(m, blockmax[i * 64 + lane]);
+    for (int w = 32; w > 0; w >>= 1) m = umax(m, (uint32_t)__shfl_xor((int)m, w));
+    return (int)(umin(umax(m, kMagLo), kMagHi) >> 23);
+}
+
+// Maxima over aligned groups for one run of 8 elements of a lane:
+//   p1, p2   magnitudes (held to the normal range) of the pairs and runs of 4
+//   w[0..1]  scaling exponents 127 - e, as signed bytes (range [-127, 126]), of
+//            the groups of 8, 16, 32, 64 (w[0]) and 128, 256 (w[1]) the lane is in
 struct Levels {
-    uint32_t w[5];
+    uint32_t p1[4], p2[2];
+    uint32_t w[2];
 };
 
 __device__ __forceinline__ uint32_t neg_exp_byte(uint32_t mag) { return (127u - (mag >> 23)) & 0xffu; }
@@ -122,11 +141,16 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 
 __device__ __forceinline__ void build_levels(const uint32_t (&ab)[8], uint32_t mag_lo, Levels &L)
 {
-    uint32_t p0[8], p1[4], p2[2], pl[6];
+    uint32_t p0[8], pl[6];
+    uint32_t(&p1)[4] = L.p1;
+    uint32_t(&p2)[2] = L.p2;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) p0[i] = umin(umax(ab[i], mag_lo), kMagHi);
+    for (int i = 0; i < 8; ++i) p0[i] = ab[i];
 #pragma unroll
     for (int i = 0; i < 4; ++i) p1[i] = umax(p0[2 * i], p0[2 * i + 1]);
+    // holding a maximum to the range is the same as holding each element to it
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p1[i] = umin(umax(p1[i], mag_lo), kMagHi);
 #pragma unroll
     for (int i = 0; i < 2; ++i) p2[i] = umax(p1[2 * i], p1[2 * i + 1]);
     uint32_t v = umax(p2[0], p2[1]);
@@ -141,37 +165,31 @@ __device__ __forceinline__ void build_levels(const uint32_t (&ab)[8], uint32_t m
     pl[4] = v;
     v = umax(v, (uint32_t)__shfl_xor((int)v, 16));
     pl[5] = v;
-    L.w[0] = pack4(neg_exp_byte(p0[0]), neg_exp_byte(p0[1]), neg_exp_byte(p0[2]), neg_exp_byte(p0[3]));
-    L.w[1] = pack4(neg_exp_byte(p0[4]), neg_exp_byte(p0[5]), neg_exp_byte(p0[6]), neg_exp_byte(p0[7]));
-    L.w[2] = pack4(neg_exp_byte(p1[0]), neg_exp_byte(p1[1]), neg_exp_byte(p1[2]), neg_exp_byte(p1[3]));
-    L.w[3] = pack4(neg_exp_byte(p2[0]), neg_exp_byte(p2[1]), neg_exp_byte(pl[0]), neg_exp_byte(pl[1]));
-    L.w[4] = pack4(neg_exp_byte(pl[2]), neg_exp_byte(pl[3]), neg_exp_byte(pl[4]), neg_exp_byte(pl[5]));
-}
-
-__device__ __forceinline__ int sbyte(uint32_t w, int idx)
-{
-    return __builtin_amdgcn_sbfe((int)w, 8 * idx, 8);
+    L.w[0] = pack4(neg_exp_byte(pl[0]), neg_exp_byte(pl[1]), neg_exp_byte(pl[2]), neg_exp_byte(pl[3]));
+    L.w[1] = pack4(neg_exp_byte(pl[4]), neg_exp_byte(pl[5]), 0, 0);
 }
 
 // 127 - e for a group of 8 or more elements (lk >= 3): one value per lane.
 __device__ __forceinline__ int lane_level(const Levels &L, int lk)
 {
-    const uint64_t both = ((uint64_t)L.w[4] << 32) | L.w[3];
-    return (int)(int8_t)(both >> (8 * (lk - 1)));  // lk = 3 is byte 2 of w[3]
+    const uint64_t both = ((uint64_t)L.w[1] << 32) | L.w[0];
+    return (int)(int8_t)(both >> (8 * (lk - 3)));
 }
 
 // 127 - e of the level-lk group each of the 8 elements belongs to.
-__device__ __forceinline__ void level_exps(const Levels &L, int lk, int (&out)[8])
+__device__ __forceinline__ void level_exps(const Levels &L, const uint32_t (&ab)[8],
+                                           uint32_t mag_lo, int lk, int (&out)[8])
 {
     if (lk == 0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = sbyte(L.w[i >> 2], i & 3);
+        for (int i = 0; i < 8; ++i)
+            out[i] = 127 - (int)(umin(umax(ab[i], mag_lo), kMagHi) >> 23);
     } else if (lk == 1) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = sbyte(L.w[2], i >> 1);
+        for (int i = 0; i < 8; ++i) out[i] = 127 - (int)(L.p1[i >> 1] >> 23);
     } else if (lk == 2) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) out[i] = sbyte(L.w[3], i >> 2);
+        for (int i = 0; i < 8; ++i) out[i] = 127 - (int)(L.p2[i >> 2] >> 23);
     } else {
         const int v = lane_level(L, lk);
 #pragma unroll
@@ -222,20 +240,35 @@ __device__ __forceinline__ float quant_err2(float y, int sh, const MrConst &c)
     return d * d;
 }
 
-// both candidate squared errors of one (m, rounding): block exponent as is, and one lower
+// Both candidate differences |x| - Q(|x|) of one (m, rounding) for a lane whose 8
+// elements share the block exponent: d0 with the block exponent as it is, d1 with
+// it lowered by one.  cb = 127 - E_block.  Nearest-even works on |x| directly with
+// the clamp value and the rounding constant moved to the block's scale (their
+// exponent fields lowered by cb resp. cb + 1; a field that would fall below 1
+// belongs to a candidate that no element selects, see the caller).
 template <int ROUNDING>
-__device__ __forceinline__ void candidates(const float (&ax)[kG][8], const int (&cb)[kG][8],
-                                           const MrConst &c, float (&e0)[kG][8],
-                                           float (&e1)[kG][8])
+__device__ __forceinline__ void candidates(const float (&ax)[8], int cb, const MrConst &c,
+                                           float (&d0)[8], float (&d1)[8])
 {
-#pragma unroll
-    for (int j = 0; j < kG; ++j)
+    if (ROUNDING == BDR_RNE) {
+        const uint32_t dn = (uint32_t)cb << 23;
+        const uint32_t top0 = as_u(c.top) - dn, top1 = top0 - (1u << 23);
+        const float mg0 = as_f(as_u(c.magic) - dn), mg1 = as_f(as_u(c.magic) - dn - (1u << 23));
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const float y0 = __builtin_ldexpf(ax[j][i], cb[j][i]);
-            e0[j][i] = quant_err2<ROUNDING>(y0, cb[j][i], c);
-            e1[j][i] = quant_err2<ROUNDING>(y0 + y0, cb[j][i] + 1, c);
+            const float y0 = as_f(umin(as_u(ax[i]), top0));
+            const float y1 = as_f(umin(as_u(ax[i]), top1));
+            d0[i] = ax[i] - ((y0 + mg0) - mg0);
+            d1[i] = ax[i] - ((y1 + mg1) - mg1);
         }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float y0 = __builtin_ldexpf(ax[i], cb);
+            d0[i] = __builtin_ldexpf(quant_diff<ROUNDING>(y0, c), -cb);
+            d1[i] = __builtin_ldexpf(quant_diff<ROUNDING>(y0 + y0, c), -cb - 1);
+        }
+    }
 }
 
 template <int ROUNDING>
@@ -250,10 +283,12 @@ __device__ __forceinline__ float direct(const float (&yp)[kG][8], const int (&sh
     return sum;
 }
 
-template <typename T>
+// ALL_RNE: every format of the launch rounds to nearest even (the usual case);
+// the other two modes are then compiled out.
+template <typename T, bool ALL_RNE>
 __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
     SweepPlan plan, const T *__restrict__ x, int64_t cols, int64_t ld, int64_t n_groups,
-    const Header *__restrict__ hdr, double *__restrict__ partials)
+    const uint32_t *__restrict__ blockmax, double *__restrict__ partials)
 {
     extern __shared__ float s_lane[];  // [n_quant + 1][kSweepThreads]: one partial per lane
     const int nq = plan.n_quant;
@@ -262,14 +297,52 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
     auto add_to = [&](int q, float v) { s_lane[q * kSweepThreads + tid] += v; };
 
     // Work on x * 2^sref so that the tensor maximum lands in [1, 2).
-    const int eref = (int)(umin(umax(hdr->absmax_bits, kMagLo), kMagHi) >> 23);
+    const int eref = tensor_exponent(blockmax);
     const int sref = 127 - eref;
     // the lowest exponent an element can carry (code 1 before scaling)
     const uint32_t mag_lo = (uint32_t)(1 + (sref > 0 ? sref : 0)) << 23;
 
+    // Lane partials -> FP64 sums of this workgroup, 32 quantizers at a time: 8 threads
+    // share a quantizer, each adds up 32 lanes (start rotated so that a wave touches
+    // 64 distinct banks) and clears them, then the 8 are combined in a fixed order.
+    const int part = tid & 7, slot = tid >> 3;
+    const int rot = (slot & 7) + 8 * (part >> 1);
+    double acc[kFoldPasses];
+#pragma unroll
+    for (int p = 0; p < kFoldPasses; ++p) acc[p] = 0.0;
+    auto fold = [&]() {
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < kFoldPasses; ++p) {
+            const int q = 32 * p + slot;
+            if (32 * p <= nq) {  // uniform
+                double v = 0.0;
+                if (q <= nq) {
+                    float *src = s_lane + q * kSweepThreads + part * 32;
+#pragma unroll 8
+                    for (int i = 0; i < 32; ++i) {
+                        v += (double)src[(i + rot) & 31];
+                        src[(i + rot) & 31] = 0.f;
+                    }
+                }
+                v += __shfl_xor(v, 1);
+                v += __shfl_xor(v, 2);
+                v += __shfl_xor(v, 4);
+                acc[p] += v;
+            }
+        }
+        __syncthreads();
+    };
+
+    int since_fold = 0;
     const int64_t per_iter = (int64_t)gridDim.x * kSweepThreads * kG;
     for (int64_t base = (int64_t)blockIdx.x * kSweepThreads * kG; base < n_groups;
          base += per_iter) {
+        if (since_fold == kFoldEvery) {  // same trip count for every lane of the workgroup
+            fold();
+            since_fold = 0;
+        }
+        ++since_fold;
         float ax[kG][8];
         Levels L[kG];
         float sig = 0.f;
@@ -295,28 +368,41 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
 
         for (int gi = 0; gi < plan.n_group; ++gi) {
             const GroupDesc gd = plan.grp[gi];
-            int cb[kG][8];  // 127 - E_block: scaling |x| by 2^cb puts the block maximum in [1, 2)
-#pragma unroll
-            for (int j = 0; j < kG; ++j) level_exps(L[j], gd.lk1, cb[j]);
-
+            ClassDesc cd = plan.cls[gd.first];  // the next one is fetched while this one runs
             if (gd.shared) {
-                // candidates: squared error at tau = 0 and at tau = 1, per (m, rounding)
-                float e0[kMR][kG][8], e1[kMR][kG][8];
+                // k1 >= 8: one block exponent per lane.  cb = 127 - E_block.
+                int cb[kG];
+                uint32_t thr[kG];  // elements / sub-blocks whose maximum is below 2^E_block get tau = 1
+                float d0[kMR][kG][8], d1[kMR][kG][8];
+#pragma unroll
+                for (int j = 0; j < kG; ++j) {
+                    cb[j] = lane_level(L[j], gd.lk1);
+                    // E_block at the bottom of the range: no sub-block can lie below it
+                    // (its own exponent is held at that bottom as well)
+                    const uint32_t t = (uint32_t)(127 - cb[j]) << 23;
+                    thr[j] = t > mag_lo ? t : 0u;
+                }
 #pragma unroll
                 for (int r = 0; r < kMR; ++r) {
                     if (r < gd.n_mr) {
                         const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
-                        if (c.rounding == BDR_RNE)
-                            candidates<BDR_RNE>(ax, cb, c, e0[r], e1[r]);
-                        else if (c.rounding == BDR_RNA)
-                            candidates<BDR_RNA>(ax, cb, c, e0[r], e1[r]);
-                        else
-                            candidates<BDR_RTZ>(ax, cb, c, e0[r], e1[r]);
+#pragma unroll
+                        for (int j = 0; j < kG; ++j) {
+                            if (ALL_RNE || c.rounding == BDR_RNE)
+                                candidates<BDR_RNE>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
+                            else if (c.rounding == BDR_RNA)
+                                candidates<BDR_RNA>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
+                            else
+                                candidates<BDR_RTZ>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
+                        }
                     }
                 }
                 for (int ci = 0; ci < gd.n_cls; ++ci) {
-                    const ClassDesc cd = plan.cls[gd.first + ci];
-                    if (cd.beta == 0) {
+                    const ClassDesc nxt = plan.cls[gd.first + ci + 1];
+                    // which elements take the lowered exponent: per element, pair or run
+                    // of 4 by comparing that maximum with 2^E_block, per lane above that
+                    const int kind = cd.beta == 0 ? -1 : (cd.lk2 < 3 ? (int)cd.lk2 : 3);
+                    auto run = [&](auto pick) {
 #pragma unroll
                         for (int r = 0; r < kMR; ++r) {
                             if (r < gd.n_mr && cd.q[r] != kNone) {
@@ -324,47 +410,53 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
 #pragma unroll
                                 for (int j = 0; j < kG; ++j)
 #pragma unroll
-                                    for (int i = 0; i < 8; ++i) sum += e0[r][j][i];
+                                    for (int i = 0; i < 8; ++i) {
+                                        const float d = pick(r, j, i);
+                                        sum = __builtin_fmaf(d, d, sum);
+                                    }
                                 add_to(cd.q[r], sum);
                             }
                         }
+                    };
+                    if (kind < 0) {
+                        run([&](int r, int j, int i) { return d0[r][j][i]; });
+                    } else if (kind == 0) {
+                        run([&](int r, int j, int i) {
+                            return as_u(ax[j][i]) < thr[j] ? d1[r][j][i] : d0[r][j][i];
+                        });
+                    } else if (kind == 1) {
+                        run([&](int r, int j, int i) {
+                            return L[j].p1[i >> 1] < thr[j] ? d1[r][j][i] : d0[r][j][i];
+                        });
+                    } else if (kind == 2) {
+                        run([&](int r, int j, int i) {
+                            return L[j].p2[i >> 2] < thr[j] ? d1[r][j][i] : d0[r][j][i];
+                        });
                     } else {
-                        // tau = 1 exactly where the sub-block exponent is below the block's
-                        bool down[kG][8];
+                        bool dl[kG];
 #pragma unroll
-                        for (int j = 0; j < kG; ++j) {
-                            int cs[8];
-                            level_exps(L[j], cd.lk2, cs);
-#pragma unroll
-                            for (int i = 0; i < 8; ++i) down[j][i] = cs[i] > cb[j][i];
-                        }
-#pragma unroll
-                        for (int r = 0; r < kMR; ++r) {
-                            if (r < gd.n_mr && cd.q[r] != kNone) {
-                                float sum = 0.f;
-#pragma unroll
-                                for (int j = 0; j < kG; ++j)
-#pragma unroll
-                                    for (int i = 0; i < 8; ++i)
-                                        sum += down[j][i] ? e1[r][j][i] : e0[r][j][i];
-                                add_to(cd.q[r], sum);
-                            }
-                        }
+                        for (int j = 0; j < kG; ++j) dl[j] = lane_level(L[j], cd.lk2) > cb[j];
+                        run([&](int r, int j, int i) { return dl[j] ? d1[r][j][i] : d0[r][j][i]; });
                     }
+                    cd = nxt;
                 }
             } else {
                 for (int ci = 0; ci < gd.n_cls; ++ci) {
-                    const ClassDesc cd = plan.cls[gd.first + ci];
+                    const ClassDesc nxt = plan.cls[gd.first + ci + 1];
                     // sh = 127 - max(E_block - beta, E_sub) = min(127 - E_block + beta, 127 - E_sub)
                     int sh[kG][8];
                     float yp[kG][8];
 #pragma unroll
                     for (int j = 0; j < kG; ++j) {
-                        int cs[8];
-                        level_exps(L[j], cd.lk2, cs);
+                        int cbe[8], cs[8];
+                        uint32_t ab[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) ab[i] = as_u(ax[j][i]);
+                        level_exps(L[j], ab, mag_lo, gd.lk1, cbe);
+                        level_exps(L[j], ab, mag_lo, cd.lk2, cs);
 #pragma unroll
                         for (int i = 0; i < 8; ++i) {
-                            sh[j][i] = min(cb[j][i] + (int)cd.beta, cs[i]);
+                            sh[j][i] = min(cbe[i] + (int)cd.beta, cs[i]);
                             yp[j][i] = __builtin_ldexpf(ax[j][i], sh[j][i]);
                         }
                     }
@@ -373,7 +465,7 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
                         if (r < gd.n_mr && cd.q[r] != kNone) {
                             const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
                             float sum;
-                            if (c.rounding == BDR_RNE)
+                            if (ALL_RNE || c.rounding == BDR_RNE)
                                 sum = direct<BDR_RNE>(yp, sh, c);
                             else if (c.rounding == BDR_RNA)
                                 sum = direct<BDR_RNA>(yp, sh, c);
@@ -382,64 +474,54 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
                             add_to(cd.q[r], sum);
                         }
                     }
+                    cd = nxt;
                 }
             }
         }
     }
-    __syncthreads();
-    // Lane partials -> one FP64 value per quantizer for this workgroup.  32 quantizers
-    // at a time: 8 threads share a quantizer, each sums 32 lanes (start rotated so a
-    // wave touches 64 distinct banks), then the 8 are combined in a fixed order.
-    const int part = tid & 7, slot = tid >> 3;
-    const int rot = (slot & 7) + 8 * (part >> 1);
-    for (int q0 = 0; q0 <= nq; q0 += 32) {
-        const int q = q0 + slot;
-        double v = 0.0;
-        if (q <= nq) {
-            const float *src = s_lane + q * kSweepThreads + part * 32;
-#pragma unroll 8
-            for (int i = 0; i < 32; ++i) v += (double)src[(i + rot) & 31];
-        }
-        v += __shfl_xor(v, 1);
-        v += __shfl_xor(v, 2);
-        v += __shfl_xor(v, 4);
-        if (q <= nq && part == 0) partials[(int64_t)blockIdx.x * (nq + 1) + q] = v;
+    fold();
+    for (int p = 0; p < kFoldPasses; ++p) {
+        const int q = 32 * p + slot;
+        if (q <= nq && part == 0) partials[(int64_t)blockIdx.x * (nq + 1) + q] = acc[p];
     }
 }
 
-// Column t of the per-block partial sums, added up in a fixed order: lane i takes
-// blocks i, i + 256, ... and the 256 lane sums go through a fixed tree.
-__global__ __launch_bounds__(256) void sweep_reduce_kernel(int32_t n_quant, int32_t n_blocks,
-                                                           const double *__restrict__ partials,
-                                                           double *__restrict__ totals)
+// One workgroup per format (plus one for the signal power alone): adds up the
+// format's column and the signal column of the per-workgroup partial sums in a
+// fixed order (lane i takes rows i, i + 256, ..., the 256 lane sums go through a
+// fixed tree) and writes noise power and QSNR (Sec. III).
+__global__ __launch_bounds__(256) void sweep_finalize_kernel(
+    FormatMap map, int32_t n_fmts, int32_t n_quant, int32_t n_blocks,
+    const uint32_t *__restrict__ blockmax, const double *__restrict__ partials,
+    double *__restrict__ qsnr_db, double *__restrict__ sums, double *sig_out)
 {
-    __shared__ double s_v[256];
-    const int t = blockIdx.x;
-    double v = 0.0;
-    for (int b = threadIdx.x; b < n_blocks; b += 256) v += partials[(int64_t)b * (n_quant + 1) + t];
-    s_v[threadIdx.x] = v;
+    __shared__ double s_e[256], s_s[256];
+    const int f = blockIdx.x;
+    const int col = f < n_fmts ? map.idx[f] : n_quant;
+    double e = 0.0, sg = 0.0;
+    for (int b = threadIdx.x; b < n_blocks; b += 256) {
+        e += partials[(int64_t)b * (n_quant + 1) + col];
+        sg += partials[(int64_t)b * (n_quant + 1) + n_quant];
+    }
+    s_e[threadIdx.x] = e;
+    s_s[threadIdx.x] = sg;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) s_v[threadIdx.x] += s_v[threadIdx.x + w];
+        if ((int)threadIdx.x < w) {
+            s_e[threadIdx.x] += s_e[threadIdx.x + w];
+            s_s[threadIdx.x] += s_s[threadIdx.x + w];
+        }
         __syncthreads();
     }
-    if (threadIdx.x == 0) totals[t] = s_v[0];
-}
-
-__global__ __launch_bounds__(256) void sweep_finalize_kernel(
-    FormatMap map, int32_t n_fmts, int32_t n_quant, const Header *__restrict__ hdr,
-    const double *__restrict__ totals, double *__restrict__ qsnr_db, double *__restrict__ sums,
-    double *sig_out)
-{
     // undo the pre-scale: sums were taken on x * 2^(127 - eref)
-    const int eref = (int)(umin(umax(hdr->absmax_bits, kMagLo), kMagHi) >> 23);
-    const double unscale = __builtin_ldexp(1.0, -2 * (127 - eref));
-    const double sig = totals[n_quant] * unscale;
-    for (int f = threadIdx.x; f <= n_fmts; f += blockDim.x) {
+    const int eref = tensor_exponent(blockmax);
+    if (threadIdx.x == 0) {
+        const double unscale = __builtin_ldexp(1.0, -2 * (127 - eref));
+        const double sig = s_s[0] * unscale;
         if (f == n_fmts) {
             *sig_out = sig;
         } else {
-            const double err = totals[map.idx[f]] * unscale;
+            const double err = s_e[0] * unscale;
             sums[f] = err;
             qsnr_db[f] = err > 0.0 ? 10.0 * log10(sig / err) : __builtin_inf();
         }
@@ -453,7 +535,7 @@ inline int ilog2(int v) { return __builtin_ctz((unsigned)v); }
 size_t sweep_workspace_bytes(int32_t n_fmts)
 {
     const int per_launch = n_fmts < kChunk ? n_fmts : kChunk;
-    return kHeaderBytes + kTotalsBytes + (size_t)kMaxBlocks * (size_t)(per_launch + 1) * sizeof(double);
+    return kHeaderBytes + (size_t)kSweepBlocks * (size_t)(per_launch + 1) * sizeof(double);
 }
 
 namespace {
@@ -474,7 +556,7 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
             beta = 0;
             lk2 = lk1;
         }
-        const int shared = beta <= 1;
+        const int shared = beta <= 1 && lk1 >= 3;  // one block exponent per lane
         // a group of this k1 and kind that has this (m, rounding), else one with room for it
         int gi = -1, r = -1;
         for (int g = 0; g < ng && gi < 0; ++g) {
@@ -539,20 +621,27 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
     plan.n_quant = nq;
 }
 
-// The lane-partial array needs (n_quant + 1) KiB of LDS; allow the full 160 KiB once.
-template <typename T>
-int sweep_lds_ok(size_t bytes)
+// One launch of the sweep kernel.  The lane-partial array needs (n_quant + 1) KiB
+// of LDS: above the default limit the kernel is allowed the full 160 KiB, once.
+template <typename T, bool ALL_RNE>
+int launch_sweep(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
+                 int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
 {
-    static int state = 0;  // 0 unknown, 1 ok, -1 failed
-    if (bytes <= 64 * 1024) return 1;
-    if (state == 0)
-        state = hipFuncSetAttribute((const void *)sweep_kernel<T>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)((kChunk + 1) * kSweepThreads * sizeof(float))) ==
-                        hipSuccess
-                    ? 1
-                    : -1;
-    return state;
+    static int big_lds = 0;  // 0 not asked for yet, 1 granted, -1 refused
+    const size_t lds = (size_t)(plan.n_quant + 1) * kSweepThreads * sizeof(float);
+    if (lds > 64 * 1024) {
+        if (big_lds == 0)
+            big_lds = hipFuncSetAttribute((const void *)sweep_kernel<T, ALL_RNE>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)((kChunk + 1) * kSweepThreads * sizeof(float))) ==
+                              hipSuccess
+                          ? 1
+                          : -1;
+        if (big_lds < 0) return BDR_ERR_LAUNCH;
+    }
+    hipLaunchKernelGGL((sweep_kernel<T, ALL_RNE>), dim3(nb), dim3(kSweepThreads), lds, s, plan,
+                       (const T *)x, cols, ld, n_groups, blockmax, partials);
+    return BDR_OK;
 }
 
 }  // namespace
@@ -562,50 +651,44 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
                hipStream_t s)
 {
     static_assert(sizeof(SweepPlan) + 64 < 4096, "kernel arguments must stay under 4 KiB");
-    Header *hdr = reinterpret_cast<Header *>(workspace);
-    static_assert((kChunk + 1) * sizeof(double) <= kTotalsBytes, "totals area too small");
-    double *totals = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes);
-    double *partials = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes +
-                                                  kTotalsBytes);
+    uint32_t *blockmax = reinterpret_cast<uint32_t *>(workspace);
+    static_assert(kAbsBlocks * sizeof(uint32_t) <= kHeaderBytes, "maxima area too small");
+    double *partials = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes);
     const int64_t n_groups = rows * cols / 8;
+    // enough workgroups to fill the chip at two per compute unit, each taking several
+    // rounds of kSweepThreads * kG groups so that set-up and the final combine amortize
     const int64_t per_block = (int64_t)kSweepThreads * kG;
     int64_t nb = (n_groups + per_block - 1) / per_block;
-    if (nb > kMaxBlocks) nb = kMaxBlocks;
+    if (nb > kSweepBlocks) nb = kSweepBlocks;
     if (nb < 1) nb = 1;
 
-    hipLaunchKernelGGL(sweep_clear_kernel, dim3(1), dim3(1), 0, s, hdr);
-    if (n_groups > 0) {
-        const int64_t want = (n_groups + 255) / 256;
-        const unsigned ab = (unsigned)(want < 1024 ? want : 1024);
-        if (dtype == BDR_F32)
-            hipLaunchKernelGGL(sweep_absmax_kernel<float>, dim3(ab), dim3(256), 0, s,
-                               (const float *)x, cols, ld, n_groups, hdr);
-        else
-            hipLaunchKernelGGL(sweep_absmax_kernel<uint16_t>, dim3(ab), dim3(256), 0, s,
-                               (const uint16_t *)x, cols, ld, n_groups, hdr);
-    }
+    if (dtype == BDR_F32)
+        hipLaunchKernelGGL(sweep_absmax_kernel<float>, dim3(kAbsBlocks), dim3(256), 0, s,
+                           (const float *)x, cols, ld, n_groups, blockmax);
+    else
+        hipLaunchKernelGGL(sweep_absmax_kernel<uint16_t>, dim3(kAbsBlocks), dim3(256), 0, s,
+                           (const uint16_t *)x, cols, ld, n_groups, blockmax);
     // Chunks of formats run one after the other on the stream and reuse the
     // partial-sum area; each launch gets its own copy of the plan by value.
     for (int32_t f0 = 0; f0 < n_fmts; f0 += kChunk) {
         const int nf = n_fmts - f0 < kChunk ? n_fmts - f0 : kChunk;
-        SweepPlan plan;
-        FormatMap map;
+        SweepPlan plan{};
+        FormatMap map{};
         make_plan(fmts + f0, nf, plan, map);
         const int nq = plan.n_quant;
-        const size_t lds = (size_t)(nq + 1) * kSweepThreads * sizeof(float);
-        if ((dtype == BDR_F32 ? sweep_lds_ok<float>(lds) : sweep_lds_ok<uint16_t>(lds)) < 0)
-            return BDR_ERR_LAUNCH;
+        bool all_rne = true;
+        for (int f = 0; f < nf; ++f) all_rne = all_rne && fmts[f0 + f].rounding == BDR_RNE;
+        int st;
         if (dtype == BDR_F32)
-            hipLaunchKernelGGL(sweep_kernel<float>, dim3((unsigned)nb), dim3(kSweepThreads), lds,
-                               s, plan, (const float *)x, cols, ld, n_groups, hdr, partials);
+            st = all_rne ? launch_sweep<float, true>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
+                         : launch_sweep<float, false>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
         else
-            hipLaunchKernelGGL(sweep_kernel<uint16_t>, dim3((unsigned)nb), dim3(kSweepThreads),
-                               lds, s, plan, (const uint16_t *)x, cols, ld, n_groups, hdr,
-                               partials);
-        hipLaunchKernelGGL(sweep_reduce_kernel, dim3((unsigned)(nq + 1)), dim3(256), 0, s, nq,
-                           (int32_t)nb, partials, totals);
-        hipLaunchKernelGGL(sweep_finalize_kernel, dim3(1), dim3(256), 0, s, map, nf, nq, hdr,
-                           totals, qsnr_db + f0, sums + f0, sums + n_fmts);
+            st = all_rne ? launch_sweep<uint16_t, true>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
+                         : launch_sweep<uint16_t, false>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
+        if (st != BDR_OK) return st;
+        hipLaunchKernelGGL(sweep_finalize_kernel, dim3((unsigned)(nf + 1)), dim3(256), 0, s, map,
+                           nf, nq, (int32_t)nb, blockmax, partials, qsnr_db + f0, sums + f0,
+                           sums + n_fmts);
     }
     return launch_status();
 }
