@@ -246,6 +246,65 @@ __device__ __forceinline__ void store8(float *p, const uint32_t (&yb)[8])
     stg<kNtPairStore>(b, q + 1);
 }
 
+// A wave's 512 consecutive floats, 8 per lane, written as two fully contiguous
+// 1 KiB rows (lane L stores floats 4L.. of each row) instead of two stores with a
+// 32-byte lane stride: a store instruction then fills whole 64-byte lines, and the
+// L2 takes a quarter of the write requests.  The exchange goes through kWaveStage
+// floats of LDS private to the wave; 4 floats of padding after every 64 keep both
+// the 32-byte-strided writes and the 16-byte-strided reads free of bank conflicts.
+// All 64 lanes must call it; n_left = floats from dst to the end of the tensor.
+constexpr int kWaveStage = 512 + 4 * 8;
+__device__ __forceinline__ void wave_store512(float *dst, const uint32_t (&yb)[8], int64_t n_left,
+                                              float *stage)
+{
+    const int L = threadIdx.x & 63;
+    u32x4 *w = reinterpret_cast<u32x4 *>(stage + 8 * L + 4 * (L >> 3));
+    w[0] = u32x4{yb[0], yb[1], yb[2], yb[3]};
+    w[1] = u32x4{yb[4], yb[5], yb[6], yb[7]};
+    // LDS operations of one wave complete in order; keep the compiler from moving them
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int i = 256 * k + 4 * L;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + i + 4 * (i >> 6));
+        if (i < n_left) stg<true>(v, reinterpret_cast<u32x4 *>(dst + i));
+    }
+    // the staging area may be refilled right away
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The reverse: two fully contiguous 1 KiB loads per wave, handed out as 8
+// consecutive floats per lane (zeros beyond n_left).
+__device__ __forceinline__ void wave_load512(const float *src, uint32_t (&xb)[8], int64_t n_left,
+                                             float *stage)
+{
+    const int L = threadIdx.x & 63;
+    u32x4 v[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int i = 256 * k + 4 * L;
+        v[k] = u32x4{0, 0, 0, 0};
+        if (i < n_left) v[k] = ldg<true>(reinterpret_cast<const u32x4 *>(src + i));
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int i = 256 * k + 4 * L;
+        *reinterpret_cast<u32x4 *>(stage + i + 4 * (i >> 6)) = v[k];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const u32x4 *r = reinterpret_cast<const u32x4 *>(stage + 8 * L + 4 * (L >> 3));
+    const u32x4 a = r[0], b = r[1];
+    xb[0] = a.x, xb[1] = a.y, xb[2] = a.z, xb[3] = a.w;
+    xb[4] = b.x, xb[5] = b.y, xb[6] = b.z, xb[7] = b.w;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __device__ __forceinline__ void store8(uint16_t *p, const uint32_t (&yb)[8])
 {
     u32x4 a = {(yb[0] >> 16) | (yb[1] & 0xffff0000u), (yb[2] >> 16) | (yb[3] & 0xffff0000u),

@@ -94,12 +94,23 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
 {
     // A thread takes kIter groups, kThreads apart; whole quads of lanes are in or
     // out of range together (n_groups % 4 == 0).
+#ifndef BDR_Q_STAGE
+#define BDR_Q_STAGE 1
+#endif
+    constexpr bool kStage = sizeof(T) == 4 && BDR_Q_STAGE;  // FP32 rows arrive through LDS
+    __shared__ float s_stage[kStage ? kThreads / 64 : 1][kStage ? kWaveStage : 1];
     const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
     uint32_t xb[kIter][8];
 #pragma unroll
     for (int it = 0; it < kIter; ++it) {
         const int64_t g = g0 + it * kThreads;
-        if (g < n_groups) load8(x + 8 * g, xb[it]);
+        if constexpr (kStage) {
+            const int64_t wave_g = g - (threadIdx.x & 63);
+            wave_load512(reinterpret_cast<const float *>(x) + 8 * wave_g, xb[it],
+                         8 * (n_groups - wave_g), s_stage[threadIdx.x >> 6]);
+        } else {
+            if (g < n_groups) load8(x + 8 * g, xb[it]);
+        }
     }
 #pragma unroll
     for (int it = 0; it < kIter; ++it) {
@@ -112,6 +123,11 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
     }
 }
 
+// Dequantize, 8 elements per lane and kDeqIter such groups per lane.  All loads of
+// a lane are issued before the first result is needed: a wave cannot write before
+// its codes have arrived, so the bytes it has in flight, not its instruction
+// count, set the rate when reads queue behind the kernel's own write stream.
+constexpr int kDeqIter = 2;
 template <int MB, typename T>
 __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
@@ -120,38 +136,41 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     constexpr int CB = MB + 1;
     constexpr uint32_t CMASK = (1u << CB) - 1u;
     constexpr uint32_t MMASK = (1u << MB) - 1u;
-    const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
+    constexpr bool kStage = sizeof(T) == 4;  // FP32 rows leave through LDS, see wave_store512
+    __shared__ float s_stage[kStage ? kThreads / 64 : 1][kStage ? kWaveStage : 1];
+    constexpr int kStep = kThreads;  // distance between a lane's groups
+    const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kDeqIter) + threadIdx.x;
     const uint32_t i = threadIdx.x & 3u;
 
-    uint32_t v0[kIter], v1[kIter], seb[kIter], tb[kIter];
+    uint32_t v0[kDeqIter], v1[kDeqIter], seb[kDeqIter], tbb[kDeqIter];
 #pragma unroll
-    for (int it = 0; it < kIter; ++it) {
-        const int64_t g = g0 + it * kThreads;
-        if (g >= n_groups) continue;
-        const int64_t quad = g >> 2;
-        if (CB == 8) {
-            u32x2 v = ldg<true>(reinterpret_cast<const u32x2 *>(codes + 8 * g));
-            v0[it] = v.x;
-            v1[it] = v.y;
-        } else if (CB == 5) {
-            // aligned dword loads only: lane i takes dword i of the quad's five, the
-            // fifth is fetched by all four lanes and used by lane 3
-            const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 5 * quad;
-            v0[it] = cw[i];
-            v1[it] = cw[4];
-        } else {
-            // lane i takes dword min(i, 2) of the quad's three
-            const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 3 * quad;
-            v0[it] = cw[i < 2 ? i : 2];
-            v1[it] = 0;
+    for (int it = 0; it < kDeqIter; ++it) {
+        const int64_t g = g0 + it * kStep;
+        v0[it] = v1[it] = seb[it] = tbb[it] = 0;
+        if (g < n_groups) {  // whole quads are live or not (n_groups % 4 == 0)
+            const int64_t quad = g >> 2;
+            if (CB == 8) {
+                u32x2 v = ldg<true>(reinterpret_cast<const u32x2 *>(codes + 8 * g));
+                v0[it] = v.x;
+                v1[it] = v.y;
+            } else if (CB == 5) {
+                // aligned dword loads only: lane i takes dword i of the quad's five, the
+                // fifth is fetched by all four lanes and used by lane 3
+                const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 5 * quad;
+                v0[it] = cw[i];
+                v1[it] = cw[4];
+            } else {
+                // lane i takes dword min(i, 2) of the quad's three
+                const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 3 * quad;
+                v0[it] = cw[i < 2 ? i : 2];
+            }
+            seb[it] = sexp[g >> 1];
+            tbb[it] = mexp[g >> 1];
         }
-        seb[it] = sexp[g >> 1];
-        tb[it] = mexp[g >> 1];
     }
 #pragma unroll
-    for (int it = 0; it < kIter; ++it) {
-        const int64_t g = g0 + it * kThreads;
-        if (g >= n_groups) continue;
+    for (int it = 0; it < kDeqIter; ++it) {
+        const int64_t g = g0 + it * kStep;
         uint32_t lo, hi = 0;
         if (CB == 8) {
             lo = v0[it];
@@ -170,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
             lo = funnel_r(v0[it], pv, 24u * i) & 0xffffffu;
         }
         const uint32_t se = seb[it];
-        const uint32_t tau4 = (tb[it] >> (4u * (i & 1u))) & 0xfu;
+        const uint32_t tau4 = (tbb[it] >> (4u * (i & 1u))) & 0xfu;
         uint32_t yb[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -187,7 +206,13 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
             const float v = __builtin_ldexpf((float)(c & MMASK), q);
             yb[e] = as_u(v) | ((c >> MB) << 31);
         }
-        store8(y + 8 * g, yb);
+        if constexpr (kStage) {
+            const int64_t wave_g = g - (threadIdx.x & 63);  // first group of this wave
+            wave_store512(reinterpret_cast<float *>(y) + 8 * wave_g, yb, 8 * (n_groups - wave_g),
+                          s_stage[threadIdx.x >> 6]);
+        } else {
+            if (g < n_groups) store8(y + 8 * g, yb);
+        }
     }
 }
 
@@ -531,7 +556,7 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (mx_fast_ok(f, rows, cols, ld)) {
-        const dim3 fgrid((unsigned)((ng + kThreads * kIter - 1) / (kThreads * kIter)));
+        const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
         if (f.m == 7)
             hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
         else if (f.m == 4)
