@@ -5,7 +5,7 @@
 // axis, and quantizing does not commute with transposing (Sec. V, "Training").
 // The result here is defined as the row-wise result on the transposed tensor,
 // plane indices included, but the transpose is never materialized: a workgroup
-// brings a 128-row x 64-column tile into LDS with row-contiguous 16-byte loads,
+// brings a 128-row tile (64 FP32 or 128 BF16 columns, 32 KiB) into LDS with row-contiguous 16-byte loads,
 // each lane then reads one 16-row block of one column out of LDS, quantizes it
 // entirely in registers (the block is in one lane, so no cross-lane reduction is
 // needed), and the eight lanes that hold the eight consecutive blocks of one
@@ -23,8 +23,8 @@ namespace bdr {
 namespace {
 
 constexpr int kTR = 128;       // tile rows = 8 blocks of 16
-constexpr int kTC = 64;        // tile columns
 constexpr int kColThreads = 256;
+constexpr uint32_t kColRun = 16;  // column tiles an XCD sweeps before it moves down one row tile
 
 typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
 
@@ -32,12 +32,14 @@ template <typename T>
 struct TileGeom;
 template <>
 struct TileGeom<uint16_t> {
+    static constexpr int kTC = 128;              // tile columns: 256-byte row segments, 32 KiB tile
     static constexpr int kEPC = 8;               // elements per 16-byte chunk
     static constexpr int kChunks = kTC / kEPC;   // chunks per tile row
     __device__ static int swz(int r) { return (r >> 4) & 7; }
 };
 template <>
 struct TileGeom<float> {
+    static constexpr int kTC = 64;
     static constexpr int kEPC = 4;
     static constexpr int kChunks = kTC / kEPC;
     __device__ static int swz(int r) { return ((r >> 4) & 7) << 1; }
@@ -190,9 +192,28 @@ __global__ __launch_bounds__(kColThreads) void mx_col_kernel(
     const T *x, T *y, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
     uint8_t *__restrict__ mexp, int64_t rows, int64_t ld)
 {
+    constexpr int kTC = TileGeom<T>::kTC;
     __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
-    const int64_t r0 = (int64_t)blockIdx.x * kTR;  // consecutive workgroups walk down the rows:
-    const int64_t c0 = (int64_t)blockIdx.y * kTC;  // their plane writes are adjacent
+    // Tiles that follow each other down a column write adjacent runs of the planes
+    // (8 blocks each: 48 to 128 bytes of codes, 8 bytes of exponents), so a 64-byte
+    // line is shared by several workgroups.  Workgroups are dealt to the 8 XCDs round
+    // robin by their linear index; the index is remapped so that an XCD owns a band
+    // of consecutive row tiles and walks it in chunks of kColRun column tiles: row
+    // neighbours of a tile follow within kColRun workgroups on the same XCD, whose
+    // L2 then sees whole lines before it writes them back, while the tiles in flight
+    // still cover several KiB of every row they read.
+    const uint32_t gx = gridDim.x, lin = blockIdx.x + gx * blockIdx.y;
+    uint32_t tx = blockIdx.x, ty = blockIdx.y;
+    if (gx % 8 == 0) {
+        const uint32_t per = gx / 8, xcd = lin % 8, j = lin / 8;
+        uint32_t cw = kColRun;
+        while (gridDim.y % cw) cw >>= 1;
+        const uint32_t chunk = j / (per * cw), rem = j % (per * cw);
+        tx = xcd * per + rem / cw;
+        ty = chunk * cw + rem % cw;
+    }
+    const int64_t r0 = (int64_t)tx * kTR;
+    const int64_t c0 = (int64_t)ty * kTC;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = lane & 7, cl = lane >> 3;
     const int64_t blocks_per_col = rows >> 4;
@@ -235,7 +256,7 @@ template <int MB, typename T>
 void launch_col(int mode, const T *x, T *y, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
                 int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
 {
-    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / kTC)), block(kColThreads);
+    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC)), block(kColThreads);
     if (mode == 0)
         hipLaunchKernelGGL((mx_col_kernel<MB, T, 0>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
     else if (mode == 1)
@@ -258,15 +279,15 @@ int col_dispatch(int mode, const bdr_format &f, const T *x, T *y, uint8_t *codes
 }
 
 // The tiled kernels need whole tiles and a grid the hardware accepts.
-bool tiled_ok(const bdr_format &f, int64_t rows, int64_t cols)
+bool tiled_ok(const bdr_format &f, int64_t rows, int64_t cols, int tc)
 {
-    return is_mx(f) && rows % kTR == 0 && cols % kTC == 0 && cols / kTC <= 65535;
+    return is_mx(f) && rows % kTR == 0 && cols % tc == 0 && cols / tc <= 65535;
 }
 
 int col_any(int mode, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
             int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
 {
-    if (!tiled_ok(f, rows, cols))
+    if (!tiled_ok(f, rows, cols, dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC))
         return generic_col(mode, f, x, y, dtype, rows, cols, ld, codes, sexp, mexp, s);
     if (dtype == BDR_F32)
         return col_dispatch(mode, f, (const float *)x, (float *)y, (uint8_t *)codes,

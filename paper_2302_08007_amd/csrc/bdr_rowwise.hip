@@ -39,7 +39,10 @@ __device__ __forceinline__ void mx_quant8(const uint32_t (&xb)[8], uint32_t &lo,
 // One group of 8 elements per thread and a one-shot grid: on this chip short
 // waves with high turnover beat loops and deeper per-thread prefetch (measured:
 // 2 or 4 groups per thread cost 10-25 %).
-constexpr int kIter = 1;
+// groups of 8 elements a lane quantizes: BF16 rows bring only 16 bytes per group, so a
+// lane takes four to have enough bytes in flight; FP32 rows are best with one
+template <typename T>
+constexpr int q_iter() { return sizeof(T) == 2 ? 4 : 1; }
 
 // Pack and store what one lane produced for its 8 elements (group g).
 template <int MB>
@@ -94,11 +97,9 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
 {
     // A thread takes kIter groups, kThreads apart; whole quads of lanes are in or
     // out of range together (n_groups % 4 == 0).
-#ifndef BDR_Q_STAGE
-#define BDR_Q_STAGE 1
-#endif
-    constexpr bool kStage = sizeof(T) == 4 && BDR_Q_STAGE;  // FP32 rows arrive through LDS
+    constexpr bool kStage = sizeof(T) == 4;  // FP32 rows arrive through LDS
     __shared__ float s_stage[kStage ? kThreads / 64 : 1][kStage ? kWaveStage : 1];
+    constexpr int kIter = q_iter<T>();
     const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
     uint32_t xb[kIter][8];
 #pragma unroll
@@ -525,12 +526,14 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (mx_fast_ok(f, rows, cols, ld)) {
+        constexpr int kIter = q_iter<T>();
+        const dim3 qgrid((unsigned)((ng + kThreads * kIter - 1) / (kThreads * kIter)));
         if (f.m == 7)
-            hipLaunchKernelGGL((mx_quantize_row_kernel<7, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
+            hipLaunchKernelGGL((mx_quantize_row_kernel<7, T>), qgrid, block, 0, s, x, codes, sexp, mexp, ng);
         else if (f.m == 4)
-            hipLaunchKernelGGL((mx_quantize_row_kernel<4, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
+            hipLaunchKernelGGL((mx_quantize_row_kernel<4, T>), qgrid, block, 0, s, x, codes, sexp, mexp, ng);
         else
-            hipLaunchKernelGGL((mx_quantize_row_kernel<2, T>), grid, block, 0, s, x, codes, sexp, mexp, ng);
+            hipLaunchKernelGGL((mx_quantize_row_kernel<2, T>), qgrid, block, 0, s, x, codes, sexp, mexp, ng);
     } else {
         hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false>), grid, block, 0, s, gen_of(f), x,
                            (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
