@@ -219,7 +219,7 @@ def main():
 def measured_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (profiles/), or None when no such summary has been recorded."""
-    path = os.path.join(ROOT, "profiles", "mx6_quantize_f32_1GiB_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "mx_rowwise_f32_1GiB_traffic.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):

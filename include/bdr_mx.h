@@ -71,7 +71,7 @@ enum bdr_status {
 const char *bdr_status_string(int status);
 
 /* Host only.  BDR_OK when the tuple is implemented: k1 and k2 powers of two,
- * k2 divides k1, 1 <= k1 <= 512, d1 = 8 (Theorem 1 fixes d1 = 8), 0 <= d2 <= 3,
+ * k2 divides k1, 1 <= k1 <= 256, d1 = 8 (Theorem 1 fixes d1 = 8), 0 <= d2 <= 3,
  * 1 <= m <= 8, rounding one of bdr_rounding.  (Sec. III.) */
 int bdr_format_validate(const bdr_format *fmt);
 
@@ -127,10 +127,17 @@ int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dt
  * two packed images blocked along K (Sec. V: both inputs of a tensor operation are
  * MX-quantized, along the reduction dimension).  Operands are expanded exactly to
  * BF16 on chip and accumulated in FP32.
- *   fa, fb : formats of A and B; both need k1 = 16, k2 = 2, d2 = 1, m <= 7 ... see
- *            the status returned; MX9, MX6 and MX4 are accepted
- *   C      : device, [M x N] floats, pitch ldc, fully overwritten
- * M and N must be multiples of 128 ... K a multiple of 64. */
+ *   fa, fb : formats of A and B, each one of Table II's family (k1 16, d1 8, k2 2,
+ *            d2 1, m 7, 4 or 2, any rounding: it plays no part here), else
+ *            BDR_ERR_FORMAT; the two may differ
+ *   a_*, b_* : device, the three planes of each image as bdr_quantize wrote them
+ *            (B is what BDR_AXIS_COL gives on a [K x N] tensor), 16-byte aligned
+ *   C      : device, [M x N] floats, pitch ldc >= N elements, 16-byte aligned rows,
+ *            fully overwritten
+ * M and N must be multiples of 128 and K a multiple of 64, each at most 2^20, else
+ * BDR_ERR_SHAPE.  M = 0 or N = 0 launches nothing; K = 0 writes zeros.  Inf/NaN
+ * codes and blocks whose exponent code is so low that an element is a BF16
+ * subnormal are outside the supported domain. */
 int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
             const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream);

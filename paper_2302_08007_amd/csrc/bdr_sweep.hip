@@ -30,7 +30,7 @@
 // of either sum.
 //
 // Sums: every lane keeps one FP32 partial per quantizer in LDS; after at most
-// 1024 elements per lane the partials are folded, in a fixed order, into FP64
+// 256 elements per lane the partials are folded, in a fixed order, into FP64
 // sums held by the workgroup, and workgroups are combined in FP64 in a fixed
 // order as well, so results are reproducible.
 #include "bdr_device.hpp"
@@ -52,7 +52,7 @@ constexpr int kAbsBlocks = 512;               // workgroups of the maximum pass
 constexpr size_t kHeaderBytes = 4096;         // per-workgroup maxima (kAbsBlocks words), rest unused
 constexpr uint16_t kNone = 0xffff;
 constexpr int kFoldPasses = (kChunk + 1 + 31) / 32;  // quantizers + signal, 32 per pass
-constexpr int kFoldEvery = 1024 / (8 * kG);          // iterations between folds
+constexpr int kFoldEvery = 256 / (8 * kG);           // iterations between folds: 256 elements per lane
 
 // Both descriptors are sized and aligned so that a wave fetches one with a single
 // scalar load.
