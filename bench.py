@@ -159,10 +159,10 @@ def main():
         "traffic": measured_traffic(),
     }
 
-    def timed(fn, reps=6, inner=5):
+    def timed(fn, reps=6, inner=5, warm=3):
         """Mean device time of one call: `inner` calls are enqueued between one pair of events, so
         the host's launch overhead overlaps with the previous call's execution."""
-        for _ in range(3):
+        for _ in range(warm):
             fn()
         torch.cuda.synchronize()
         ts = []
@@ -272,10 +272,17 @@ def other_legs(B, S, torch, timed):
         A, Bm = S.gemm_operands(M, N, K, device="cuda")
         pa, pb = B.bdr_quantize(B.MX6, A), B.bdr_quantize(B.MX6, Bm)
         C = torch.empty(M, N, device="cuda")
-        t = timed(lambda: B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C), reps=3, inner=4)
-        tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
-        out["mx_gemm_8192_MX6"] = {"ms": round(t, 3), "TFLOPs": round(tf, 1),
-                                   "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4)}
+        ws = torch.empty(B.mx_gemm_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        leg = {}
+        # two-pass form (operands expanded once to BF16 in a workspace) and single-kernel form
+        for name, w in (("two_pass", ws), ("single_kernel", None)):
+            # matrix-core clocks take about 30 ms of load to settle: 40 untimed calls first
+            t = timed(lambda: B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C, workspace=w),
+                      reps=5, inner=4, warm=40)
+            tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
+            leg[name] = {"ms": round(t, 3), "TFLOPs": round(tf, 1),
+                         "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4)}
+        out["mx_gemm_8192_MX6"] = leg
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
     return out

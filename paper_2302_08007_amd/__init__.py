@@ -21,7 +21,7 @@ OK = 0
 EXPORTS = (
     "bdr_status_string", "bdr_format_validate", "bdr_packed_sizes", "bdr_quantize",
     "bdr_dequantize", "bdr_quantize_dequantize", "bdr_qsnr_sweep_workspace_bytes",
-    "bdr_qsnr_sweep", "mx_gemm",
+    "bdr_qsnr_sweep", "mx_gemm_workspace_bytes", "mx_gemm",
 )
 
 
@@ -69,7 +69,9 @@ def _load():
     L.bdr_qsnr_sweep_workspace_bytes.argtypes = [I32]
     L.bdr_qsnr_sweep_workspace_bytes.restype = SZ
     L.bdr_qsnr_sweep.argtypes = [FP, I32, P, I32, I64, I64, I64, P, P, P, SZ, P]
-    L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P]
+    L.mx_gemm_workspace_bytes.argtypes = [I64, I64, I64]
+    L.mx_gemm_workspace_bytes.restype = SZ
+    L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P, SZ, P]
     return L
 
 
@@ -168,11 +170,18 @@ def bdr_qsnr_sweep(fmts, x, workspace=None, out=None):
     return out
 
 
-def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None):
-    """C[M, N] = Ahat @ Bhat^T for two packed operands blocked along K."""
+def mx_gemm_workspace_bytes(M, N, K):
+    return lib.mx_gemm_workspace_bytes(M, N, K)
+
+
+def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None):
+    """C[M, N] = Ahat @ Bhat^T for two packed operands blocked along K.  `workspace`: a
+    uint8 tensor of at least mx_gemm_workspace_bytes(M, N, K) bytes selects the two-pass
+    form, None the single-kernel form."""
     C = out if out is not None else torch.empty((M, N), dtype=torch.float32,
                                                 device=a_planes[0].device)
+    ws, wsb = (_p(workspace), workspace.numel()) if workspace is not None else (None, 0)
     _check(lib.mx_gemm(ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]),
                        _p(a_planes[2]), _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]), M, N, K,
-                       _p(C), C.stride(0), _stream()))
+                       _p(C), C.stride(0), ws, wsb, _stream()))
     return C

@@ -179,9 +179,21 @@ int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dt
                            static_cast<hipStream_t>(hip_stream));
 }
 
+static size_t gemm_ws_half(int64_t rows, int64_t K)
+{
+    return ((size_t)rows * (size_t)K * 2 + 255) & ~(size_t)255;
+}
+
+size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M < 0 || N < 0 || K < 0 || M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return 0;
+    return gemm_ws_half(M, K) + gemm_ws_half(N, K);
+}
+
 int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
             const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
-            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *hip_stream)
+            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,
+            size_t workspace_bytes, void *hip_stream)
 {
     int st = check_format(fa);
     if (st) return st;
@@ -200,8 +212,19 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         st = check_planes(fb, b_codes, b_sexp, b_mexp);
         if (st) return st;
     }
-    return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc,
-                     static_cast<hipStream_t>(hip_stream));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (workspace && K > 0) {
+        // two passes: each operand is expanded once to BF16 (exact), then a plain BF16 kernel
+        if (workspace_bytes < mx_gemm_workspace_bytes(M, N, K)) return BDR_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return BDR_ERR_ALIGN;
+        char *wa = static_cast<char *>(workspace), *wb = wa + gemm_ws_half(M, K);
+        st = bdr::dequantize_row(*fa, a_codes, a_sexp, a_mexp, M, K, wa, BDR_BF16, K, s);
+        if (st) return st;
+        st = bdr::dequantize_row(*fb, b_codes, b_sexp, b_mexp, N, K, wb, BDR_BF16, K, s);
+        if (st) return st;
+        return bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, s);
+    }
+    return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc, s);
 }
 
 }  // extern "C"

@@ -49,5 +49,7 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
 int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,
          const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
          int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
+int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+              hipStream_t s);
 
 }  // namespace bdr

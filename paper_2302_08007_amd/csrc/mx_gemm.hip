@@ -30,12 +30,14 @@ namespace {
 
 constexpr int kBK = 64;
 constexpr int kPitch = kBK * 2;  // bytes per LDS row: 64 BF16 = eight 16-byte chunks
-// LDS rows are 128 bytes, so the same chunk of consecutive rows would sit on the
-// same banks.  Chunk c of row r is stored at position c ^ (r & 7): eight
-// consecutive rows then spread one chunk index over all 32 banks.
+// LDS rows are 128 bytes = half of the 64 banks, so rows of equal parity put the
+// same chunk on the same banks.  A 16-byte access is served 16 lanes at a time, and
+// the 16 lanes of a fragment read hold 16 consecutive rows: chunk c of row r is
+// stored at position c ^ ((r >> 1) & 7), which gives each row pair its own
+// position and leaves the two rows of a pair on opposite halves of the banks.
 __device__ __forceinline__ int lds_chunk(int row, int chunk)
 {
-    return row * kPitch + ((chunk ^ (row & 7)) << 4);
+    return row * kPitch + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -264,6 +266,134 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
         }
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane p's data lands at
+// byte 16 p after `lds_block` (which must be the same for the whole wave).
+__device__ __forceinline__ void global_to_lds16(const void *src, void *lds_block)
+{
+#if defined(__HIP_DEVICE_COMPILE__)  // the builtin exists only in the device pass
+    __builtin_amdgcn_global_load_lds(src, lds_block, 16, 0, 0);
+#else
+    (void)src;
+    (void)lds_block;
+#endif
+}
+
+// The same tiling on operands that are already BF16 in memory ([M x K] and [N x K],
+// K contiguous) -- the second half of the two-pass form of mx_gemm, whose first
+// half expands each packed operand once instead of once per tile.  Operands come in
+// by direct global-to-LDS loads: a wave fills eight tile rows (1 KiB) per
+// instruction, lane p supplying the 16 bytes that belong at byte 16 p of that
+// block, i.e. chunk (p & 7) ^ swizzle of row p / 8.  No staging registers and no
+// LDS write instructions; the loads of step kt+1 are issued before the MFMAs of
+// step kt, and the fragment reads of sub-step s+1 before the MFMAs of sub-step s.
+template <int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(64 * WM * WN) void bf16_gemm_dl_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int N, int K,
+    float *__restrict__ C, int64_t ldc)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr int NW = WM * WN;
+    constexpr int A_BYTES = BM * kPitch, B_BYTES = BN * kPitch;
+    constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // 8-row blocks per wave and K step
+    static_assert(LA >= 1 && LB >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B]
+
+    const int ntm = M / BM, ntn = N / BN, total = ntm * ntn;
+    int t = blockIdx.x;
+    if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
+    int tm, tn;
+    if (ntm % 8 == 0) {
+        const int group = t / (8 * ntn);
+        tm = group * 8 + t % 8;
+        tn = (t % (8 * ntn)) / 8;
+    } else {
+        tm = t / ntn;
+        tn = t % ntn;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const uint16_t *ap[LA], *bp[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        const int row = (wave * LA + i) * 8 + (lane >> 3);
+        ap[i] = A + (int64_t)(m0 + row) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int row = (wave * LB + i) * 8 + (lane >> 3);
+        bp[i] = B + (int64_t)(n0 + row) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
+    }
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = K / kBK;
+    auto fill = [&](uint8_t *dst) {  // one K step of both operands, then advance
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            global_to_lds16(ap[i], dst + (wave * LA + i) * 8 * kPitch);
+            ap[i] += kBK;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            global_to_lds16(bp[i], dst + A_BYTES + (wave * LB + i) * 8 * kPitch);
+            bp[i] += kBK;
+        }
+    };
+    const int f_row = lane & 31, f_half = lane >> 5;
+    auto read_frags = [&](const uint8_t *cur, int sub, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[i] = *reinterpret_cast<const bf16x8 *>(
+                cur + lds_chunk((wm * TM + i) * 32 + f_row, 2 * sub + f_half));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[j] = *reinterpret_cast<const bf16x8 *>(
+                cur + A_BYTES + lds_chunk((wn * TN + j) * 32 + f_row, 2 * sub + f_half));
+    };
+    uint8_t *const buf0 = smem, *const buf1 = smem + A_BYTES + B_BYTES;
+    fill(buf0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        uint8_t *cur = (kt & 1) ? buf1 : buf0, *nxt = (kt & 1) ? buf0 : buf1;
+        if (kt + 1 < nk) fill(nxt);
+        bf16x8 fa[2][TM], fb[2][TN];
+        read_frags(cur, 0, fa[0], fb[0]);
+#pragma unroll
+        for (int sub = 0; sub < kBK / 16; ++sub) {
+            if (sub + 1 < kBK / 16) read_frags(cur, sub + 1, fa[(sub + 1) & 1], fb[(sub + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[sub & 1][i], fb[sub & 1][j],
+                                                                        acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(0);  // this wave's part of the next step has landed
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+            float *cp = C + (int64_t)(m0 + (wm * TM + i) * 32 + 4 * (lane >> 5)) * ldc + col;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)(8 * (r >> 2) + (r & 3)) * ldc);
+        }
+}
+
 // Two tile shapes: 256 x 256 with 8 waves (128 KiB of LDS, one workgroup per CU)
 // when the device grants that much LDS to a workgroup and M, N allow it, else
 // 128 x 128 with 4 waves (64 KiB).
@@ -306,6 +436,26 @@ int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, cons
     return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
 }
 
+template <int WM, int WN, int TM, int TN>
+int launch_bf16(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *C, int64_t ldc,
+                hipStream_t s)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t kLds = 2 * (BM + BN) * (size_t)kPitch;
+    static int ok = 0;  // 0 not asked yet, 1 granted, -1 refused
+    if (ok == 0) {
+        ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&bf16_gemm_dl_kernel<WM, WN, TM, TN>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) == hipSuccess
+                 ? 1
+                 : -1;
+        (void)hipGetLastError();
+    }
+    if (ok < 0) return BDR_ERR_LAUNCH;
+    hipLaunchKernelGGL((bf16_gemm_dl_kernel<WM, WN, TM, TN>), dim3((unsigned)((M / BM) * (N / BN))),
+                       dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc);
+    return launch_status();
+}
+
 __global__ void gemm_zero_kernel(float *C, int64_t ldc, int N)
 {
     const int64_t row = blockIdx.y;
@@ -329,6 +479,18 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
     if (fa.m == 7) return pick_b<7>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
     if (fa.m == 4) return pick_b<4>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
     return pick_b<2>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
+}
+
+// C = A * B^T for BF16 A [M x K] and B [N x K] (K > 0, shapes already validated).
+int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+              hipStream_t s)
+{
+    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+    if (M % 256 == 0 && N % 256 == 0) {
+        const int st = launch_bf16<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
+        if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
+    }
+    return launch_bf16<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
 }
 
 }  // namespace bdr

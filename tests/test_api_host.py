@@ -20,7 +20,7 @@ OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_LAUNCH, ERR_WS = 
 def test_exports_match_header():
     text = open(os.path.join(ROOT, "include", "bdr_mx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(bdr_\w+|mx_gemm)\s*\(", text))
+    names = set(re.findall(r"\b(bdr_\w+|mx_gemm\w*)\s*\(", text))
     names -= {"bdr_format"}
     assert names == set(B.EXPORTS)
     for n in names:
@@ -130,10 +130,16 @@ def test_sweep_and_gemm_argument_checks():
     assert sw(x=NULL) == ERR_NULL
     assert sw(s=FAKE_ODD) == ERR_ALIGN
     f = B.MX6
-    gm = lambda fa=f, fb=f, M=128, N=128, K=64, C=FAKE, ldc=128, a=FAKE: L.mx_gemm(
-        ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, C, ldc, NULL)
+    gm = lambda fa=f, fb=f, M=128, N=128, K=64, C=FAKE, ldc=128, a=FAKE, ws=NULL, wsb=0: L.mx_gemm(
+        ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, C, ldc, ws,
+        wsb, NULL)
     assert gm(fa=B.fmt(32, 2, 1, 4)) == ERR_FORMAT
     assert gm(M=100) == ERR_SHAPE and gm(K=48) == ERR_SHAPE and gm(ldc=64) == ERR_SHAPE
     assert gm(C=NULL) == ERR_NULL and gm(a=NULL) == ERR_NULL
     assert gm(C=FAKE_ODD) == ERR_ALIGN
     assert gm(M=0) == OK
+    need = L.mx_gemm_workspace_bytes(128, 128, 64)
+    assert need == 2 * 128 * 64 * 2 and L.mx_gemm_workspace_bytes(-1, 128, 64) == 0
+    assert L.mx_gemm_workspace_bytes(128, 384, 64) == (128 + 384) * 64 * 2
+    assert gm(ws=FAKE, wsb=need - 1) == ERR_WS
+    assert gm(ws=FAKE_ODD, wsb=need) == ERR_ALIGN

@@ -1,5 +1,7 @@
 """GPU parity: mx_gemm against the fp64 oracle.  Tolerance: |C - C_ref| <= 1e-4 * sum_k |a b|
-(norm-relative, because entries of C can be near zero)."""
+(norm-relative, because entries of C can be near zero).  Both forms of the call are checked:
+the single kernel (no workspace) and the two-pass form (operands expanded once to BF16 in a
+caller-supplied workspace); the two walk K in the same order and must agree bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -17,12 +19,18 @@ def _planes_np(planes):
     return [p.cpu().numpy() for p in planes]
 
 
+def _workspace(M, N, K, extra=0):
+    return torch.empty(B.mx_gemm_workspace_bytes(M, N, K) + extra, dtype=torch.uint8, device="cuda")
+
+
 def _check(fa, fb, A, Bm, what):
     M, K = A.shape
     N = Bm.shape[0]
     pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
     C = B.mx_gemm(fa, fb, pa, pb, M, N, K)
+    C2 = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=_workspace(M, N, K))
     torch.cuda.synchronize()
+    assert torch.equal(C, C2), what
     pan, pbn = _planes_np(pa), _planes_np(pb)
     Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
     Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
@@ -73,6 +81,16 @@ def test_strided_output_and_empty_k():
     assert torch.equal(big[:, :N], ref) and torch.all(big[:, N:] == 3.0)
     z = B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, 0)
     assert torch.count_nonzero(z) == 0
+    # the same through the two-pass form; the workspace is guarded by a canary behind it
+    need = B.mx_gemm_workspace_bytes(M, N, K)
+    ws = torch.full((need + 256,), 0x5A, dtype=torch.uint8, device="cuda")
+    big2 = torch.full((M, 2 * N), 3.0, device="cuda")
+    B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=big2[:, :N], workspace=ws)
+    assert torch.equal(big2, big) and torch.all(ws[need:] == 0x5A)
+    z = B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, 0, workspace=ws)
+    assert torch.count_nonzero(z) == 0
+    with pytest.raises(B.BdrError):
+        B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, workspace=ws[:need - 16])
 
 
 def test_full_size_sampled_entries():
@@ -82,7 +100,10 @@ def test_full_size_sampled_entries():
     f = B.MX6
     pa, pb = B.bdr_quantize(f, A), B.bdr_quantize(f, Bm)
     C = B.mx_gemm(f, f, pa, pb, M, N, K)
+    C2 = B.mx_gemm(f, f, pa, pb, M, N, K, workspace=_workspace(M, N, K))
     torch.cuda.synchronize()
+    assert torch.equal(C, C2)
+    del C2
     rng = np.random.default_rng(4)
     ri = np.sort(rng.choice(M, 64, replace=False))
     ci = np.sort(rng.choice(N, 64, replace=False))
