@@ -358,29 +358,53 @@ __global__ __launch_bounds__(64 * WM * WN) void bf16_gemm_dl_kernel(
             fb[j] = *reinterpret_cast<const bf16x8 *>(
                 cur + A_BYTES + lds_chunk((wn * TN + j) * 32 + f_row, 2 * sub + f_half));
     };
-    uint8_t *const buf0 = smem, *const buf1 = smem + A_BYTES + B_BYTES;
-    fill(buf0);
+    auto mfmas = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    static_assert(kBK == 64, "the schedule below is written for four sub-steps per K step");
+    // Schedule of one K step (cur holds step kt, nxt is being filled with step kt+1,
+    // fragment set 0 holds sub-step 0 of step kt):
+    //   reads of sub-step 1, 2, 3 are issued before the MFMAs of sub-step 0, 1, 2;
+    //   then wait for everything this wave has in flight and meet the other waves:
+    //   from here on nxt is complete and nobody reads cur any more (the fragments of
+    //   sub-step 3 are in registers), so the fill of step kt+2 into cur and the reads
+    //   of sub-step 0 of step kt+1 are issued and run under the MFMAs of sub-step 3.
+    // The barrier thus costs neither a fragment-read latency nor a load latency: both
+    // have a whole K step (loads) or eight MFMAs (reads) to arrive.
+    uint8_t *cur = smem, *nxt = smem + A_BYTES + B_BYTES;
+    bf16x8 fa[2][TM], fb[2][TN];
+    fill(cur);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if (nk > 1) fill(nxt);
+    read_frags(cur, 0, fa[0], fb[0]);
     for (int kt = 0; kt < nk; ++kt) {
-        uint8_t *cur = (kt & 1) ? buf1 : buf0, *nxt = (kt & 1) ? buf0 : buf1;
-        if (kt + 1 < nk) fill(nxt);
-        bf16x8 fa[2][TM], fb[2][TN];
-        read_frags(cur, 0, fa[0], fb[0]);
-#pragma unroll
-        for (int sub = 0; sub < kBK / 16; ++sub) {
-            if (sub + 1 < kBK / 16) read_frags(cur, sub + 1, fa[(sub + 1) & 1], fb[(sub + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[sub & 1][i], fb[sub & 1][j],
-                                                                        acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_s_waitcnt(0);  // this wave's part of the next step has landed
+        read_frags(cur, 1, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(cur, 2, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(cur, 3, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+        if (kt + 2 < nk) fill(cur);
+        if (kt + 1 < nk) read_frags(nxt, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        uint8_t *t2 = cur;
+        cur = nxt;
+        nxt = t2;
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
