@@ -129,3 +129,42 @@ def test_idempotent_on_gpu():
         y = B.bdr_quantize_dequantize(f, x)
         y2 = B.bdr_quantize_dequantize(f, y)
         assert torch.equal(y.view(torch.int32), y2.view(torch.int32))
+
+
+def test_bandwidth_config_full_size_sampled_rows():
+    # 2^28 fp32 (1 GiB), heavy-tailed, MX9 / MX6 / MX4: the tensor and launch shapes the bench
+    # times.  Blocks never cross rows, so the planes of a band of rows are a contiguous slice of
+    # the full planes: the oracle quantizes sampled 64-row bands (first, last, four random ones)
+    # and every byte and value of those bands is compared.  Then properties over the whole tensor.
+    x = S.bandwidth(device="cuda")
+    rows, cols = x.shape
+    assert rows * cols == 1 << 28
+    rng = np.random.default_rng(1)
+    bands = sorted(set([0, rows - 64] + [int(v) * 64 for v in rng.integers(0, rows // 64, 4)]))
+    for name in MX:
+        f = _fmt(name)
+        planes = B.bdr_quantize(f, x)
+        y = B.bdr_dequantize(f, planes, rows, cols)
+        torch.cuda.synchronize()
+        per_row = [cols * (f.m + 1) // 8, cols // 16, cols // 16]
+        for r0 in bands:
+            sub = x[r0:r0 + 64]
+            want = O.quantize(ofmt(f), to_np(sub))
+            got = [p[r0 * n:(r0 + 64) * n] for p, n in zip(planes, per_row)]
+            assert_planes_equal(got, want, "%s rows %d.." % (name, r0))
+            ywant = O.dequantize(ofmt(f), *want, 64, cols)
+            assert_bits_equal(y[r0:r0 + 64], ywant, "%s dequantize rows %d.." % (name, r0))
+        # whole tensor: the fused round trip gives the same bits as quantize then dequantize,
+        # and quantizing the result again changes nothing
+        y2 = B.bdr_quantize_dequantize(f, x)
+        assert torch.equal(y2.view(torch.int32), y.view(torch.int32)), name
+        del y2
+        p2 = B.bdr_quantize(f, y)
+        assert all(torch.equal(a, b) for a, b in zip(planes, p2)), name
+        # error bound of Sec. IX per element, wherever the magnitude did not saturate:
+        # |x - Q(x)| <= 2^(E - tau - m) <= 2^(E - m), E = exponent of the block maximum
+        se = planes[1].view(rows, cols // 16).to(torch.float32)
+        bound = torch.exp2(se - 127 - f.m).repeat_interleave(16, dim=1)
+        sat = y.abs() >= (2.0 - 2.0 ** (1 - f.m)) * torch.exp2(se - 127).repeat_interleave(16, dim=1)
+        assert torch.all(((x - y).abs() <= bound) | sat), name
+        del planes, y, p2, se, bound, sat
