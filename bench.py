@@ -285,6 +285,26 @@ def other_legs(B, S, torch, timed):
         out["mx_gemm_8192_MX6"] = leg
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
+    try:
+        # the three products of one training iteration of a GPT3-width linear layer (Sec. V):
+        # 6 quantizations (row- and column-wise) and 3 mx_gemm calls on BF16 tensors
+        from paper_2302_08007_amd.training import mx_linear
+        T, I, Osz = 8192, 12288, 12288
+        g = torch.Generator(device="cuda").manual_seed(6)
+        x = torch.randn(T, I, generator=g, device="cuda").to(torch.bfloat16).requires_grad_()
+        w = (torch.randn(Osz, I, generator=g, device="cuda") / I ** 0.5).to(torch.bfloat16).requires_grad_()
+        gy = torch.randn(T, Osz, generator=g, device="cuda").to(torch.bfloat16)
+
+        def step_fn():
+            x.grad = None
+            w.grad = None
+            mx_linear(x, w, B.MX9).backward(gy)
+        t = timed(step_fn, reps=3, inner=2, warm=8)
+        tf = 3 * 2.0 * T * I * Osz / (t * 1e-3) / 1e12
+        out["mx_linear_fwd_bwd_8192x12288x12288_MX9_bf16"] = {
+            "ms": round(t, 3), "TFLOPs": round(tf, 1), "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4)}
+    except B.BdrError as e:
+        out["mx_linear_fwd_bwd_8192x12288x12288_MX9_bf16"] = {"error": str(e)}
     return out
 
 

@@ -1,0 +1,72 @@
+"""The MX compute flow of one training iteration for a linear layer (Sec. V, "Training", and
+the compute-flow figure there): the three tensor reductions -- forward, backward-data and
+backward-weight -- each take BOTH operands MX-quantized along that reduction's own axis.
+
+MX is a directional format, so a tensor that is reduced along different axes in different
+passes is quantized once per axis; quantizing and transposing do not commute (Sec. V).  With
+x [T, I], w [O, I] and the incoming gradient g [T, O]:
+
+    forward          y[t, o] = sum_i x[t, i] w[o, i]    x, w blocked along I   (both row-wise)
+    backward-data   gx[t, i] = sum_o g[t, o] w[o, i]    g row-wise, w column-wise (image of w^T)
+    backward-weight gw[o, i] = sum_t g[t, o] x[t, i]    g and x column-wise (images of g^T, x^T)
+
+Column-wise quantization yields the packed image of the transpose directly, which is exactly
+the K-contiguous operand mx_gemm takes, so no transpose is ever materialized.  Everything that
+touches tensor data runs in the library's kernels (bdr_quantize, mx_gemm); this file only
+orders the calls and plugs them into autograd.  Element-wise work stays in the caller's dtype.
+"""
+import torch
+
+from . import AXIS_COL, AXIS_ROW, bdr_quantize, mx_gemm, mx_gemm_workspace_bytes
+
+_workspaces = {}
+
+
+def _workspace(device, nbytes):
+    """One scratch buffer per device, grown on demand, shared by the GEMMs of this module
+    (they run one after the other on the current stream)."""
+    ws = _workspaces.get(device)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _workspaces[device] = ws
+    return ws
+
+
+def _mx_matmul(fa, fb, a, a_axis, b, b_axis, M, N, K):
+    """C[M, N] = Q(a) Q(b)^T with a, b quantized along the K axis of the product."""
+    pa = bdr_quantize(fa, a, axis=a_axis)
+    pb = bdr_quantize(fb, b, axis=b_axis)
+    ws = _workspace(a.device, mx_gemm_workspace_bytes(M, N, K))
+    return mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws)
+
+
+class _MXLinear(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, w, fmt_fwd, fmt_bwd):
+        T, I = x.shape
+        O = w.shape[0]
+        ctx.save_for_backward(x, w)
+        ctx.fmt_bwd = fmt_bwd
+        y = _mx_matmul(fmt_fwd, fmt_fwd, x, AXIS_ROW, w, AXIS_ROW, T, O, I)
+        return y.to(x.dtype)
+
+    @staticmethod
+    def backward(ctx, g):
+        x, w = ctx.saved_tensors
+        f = ctx.fmt_bwd
+        T, I = x.shape
+        O = w.shape[0]
+        g = g.contiguous()
+        gx = gw = None
+        if ctx.needs_input_grad[0]:
+            gx = _mx_matmul(f, f, g, AXIS_ROW, w, AXIS_COL, T, I, O).to(x.dtype)
+        if ctx.needs_input_grad[1]:
+            gw = _mx_matmul(f, f, g, AXIS_COL, x, AXIS_COL, O, I, T).to(w.dtype)
+        return gx, gw, None, None
+
+
+def mx_linear(x, w, fmt_fwd, fmt_bwd=None):
+    """y = x w^T with the forward, backward-data and backward-weight products all computed on
+    MX-quantized operands (formats of Table II: MX9, MX6 or MX4).  x [T, I] and w [O, I] are
+    contiguous FP32 or BF16 CUDA tensors with T, I and O multiples of 128."""
+    return _MXLinear.apply(x, w, fmt_fwd, fmt_bwd if fmt_bwd is not None else fmt_fwd)
