@@ -286,6 +286,23 @@ def other_legs(B, S, torch, timed):
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
     try:
+        # embedding-table lookups from MX6 storage (Sec. V): 2^20 rows x 128, 2^20 random rows
+        rows_t, cols_t, n_look = 1 << 20, 128, 1 << 20
+        g = torch.Generator(device="cuda").manual_seed(7)
+        tab = torch.randn(rows_t, cols_t, generator=g, device="cuda") * 0.05
+        pt = B.bdr_quantize(B.MX6, tab)
+        del tab
+        idx = torch.randint(0, rows_t, (n_look,), generator=g, device="cuda", dtype=torch.int64)
+        yo = torch.empty(n_look, cols_t, device="cuda")
+        t = timed(lambda: B.bdr_gather_dequantize(B.MX6, pt, rows_t, cols_t, idx, out=yo), reps=4, inner=5)
+        ab = n_look * (cols_t * 6 // 8 + 8 + cols_t * 4)
+        out["gather_dequantize_MX6_1Mi_rows_x128_fp32"] = {
+            "us": round(t * 1e3, 1), "GBps": round(ab / t / 1e6, 1),
+            "frac": round(ab / t / 1e6 / HBM_PEAK_GBS, 4), "lookups_per_s": round(n_look / (t * 1e-3), 1)}
+        del pt, idx, yo
+    except B.BdrError as e:
+        out["gather_dequantize_MX6_1Mi_rows_x128_fp32"] = {"error": str(e)}
+    try:
         # the three products of one training iteration of a GPT3-width linear layer (Sec. V):
         # 6 quantizations (row- and column-wise) and 3 mx_gemm calls on BF16 tensors
         from paper_2302_08007_amd.training import mx_linear

@@ -102,6 +102,26 @@ int bdr_dequantize(const bdr_format *fmt, const void *codes, const void *sexp, c
                    int64_t rows, int64_t cols, int axis, void *y, int dtype, int64_t ld,
                    void *hip_stream);
 
+/* Gather + dequantize: y[j, :] = dequantized row indices[j] of a packed table
+ * (MX as a storage format for embedding tables, Sec. V "Inferencing": "quantizing both
+ * storage and compute" for recommendation models).  The table is the row-wise packed
+ * image of a [table_rows x cols] tensor in one of Table II's formats (else
+ * BDR_ERR_FORMAT); cols must be a multiple of 32.
+ *   indices : device, n_indices int64 values, 8-byte aligned; an index outside
+ *             [0, table_rows) yields a row of +0 (it is never dereferenced)
+ *   y       : device, [n_indices x cols] of `dtype`, contiguous, 16-byte aligned,
+ *             fully overwritten; values are exact in FP32 and in BF16 */
+int bdr_gather_dequantize(const bdr_format *fmt, const void *codes, const void *sexp,
+                          const void *mexp, int64_t table_rows, int64_t cols, const int64_t *indices,
+                          int64_t n_indices, void *y, int dtype, void *hip_stream);
+
+/* Host only.  Memory-interface packing of one tile (Sec. IV-B, "Memory Footprint": a
+ * tile of 256 elements into a 64-byte interface): bytes the tile's packed image takes,
+ * interface transfers needed, and efficiency = bytes / (transfers * interface_bytes).
+ * Any of the three outputs may be NULL. */
+int bdr_tile_packing(const bdr_format *fmt, int64_t tile_elements, int64_t interface_bytes,
+                     int64_t *packed_bytes, int64_t *transfers, double *efficiency);
+
 /* y = dequantize(quantize(x)) in one pass, without the packed image -- what an
  * emulation library does around every tensor operation (Sec. VI, "Experimental
  * Setup").  x and y have the same dtype, shape and pitch; y may alias x. */

@@ -20,7 +20,8 @@ OK = 0
 
 EXPORTS = (
     "bdr_status_string", "bdr_format_validate", "bdr_packed_sizes", "bdr_quantize",
-    "bdr_dequantize", "bdr_quantize_dequantize", "bdr_qsnr_sweep_workspace_bytes",
+    "bdr_dequantize", "bdr_gather_dequantize", "bdr_tile_packing", "bdr_quantize_dequantize",
+    "bdr_qsnr_sweep_workspace_bytes",
     "bdr_qsnr_sweep", "mx_gemm_workspace_bytes", "mx_gemm",
 )
 
@@ -66,6 +67,8 @@ def _load():
     L.bdr_quantize.argtypes = [FP, P, I32, I64, I64, I64, I32, P, P, P, P]
     L.bdr_dequantize.argtypes = [FP, P, P, P, I64, I64, I32, P, I32, I64, P]
     L.bdr_quantize_dequantize.argtypes = [FP, P, P, I32, I64, I64, I64, I32, P]
+    L.bdr_gather_dequantize.argtypes = [FP, P, P, P, I64, I64, P, I64, P, I32, P]
+    L.bdr_tile_packing.argtypes = [FP, I64, I64, P, P, P]
     L.bdr_qsnr_sweep_workspace_bytes.argtypes = [I32]
     L.bdr_qsnr_sweep_workspace_bytes.restype = SZ
     L.bdr_qsnr_sweep.argtypes = [FP, I32, P, I32, I64, I64, I64, P, P, P, SZ, P]
@@ -168,6 +171,25 @@ def bdr_qsnr_sweep(fmts, x, workspace=None, out=None):
     _check(lib.bdr_qsnr_sweep(arr, n, _p(x), _dtype_code(x), rows, cols, ld, _p(out[0]),
                               _p(out[1]), _p(workspace), workspace.numel(), _stream()))
     return out
+
+
+def bdr_gather_dequantize(fmt, planes, table_rows, cols, indices, dtype=None, out=None):
+    """out[j, :] = dequantized row indices[j] of the packed table (indices: int64 tensor)."""
+    dtype = dtype or torch.float32
+    n = indices.numel()
+    y = out if out is not None else torch.empty((n, cols), dtype=dtype, device=indices.device)
+    _check(lib.bdr_gather_dequantize(ctypes.byref(fmt), _p(planes[0]), _p(planes[1]), _p(planes[2]),
+                                     table_rows, cols, _p(indices), n, _p(y), _dtype_code(y),
+                                     _stream()))
+    return y
+
+
+def bdr_tile_packing(fmt, tile_elements=256, interface_bytes=64):
+    """(packed bytes, interface transfers, efficiency) of one tile (Sec. IV-B, Memory Footprint)."""
+    b, t, e = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_double()
+    _check(lib.bdr_tile_packing(ctypes.byref(fmt), tile_elements, interface_bytes, ctypes.byref(b),
+                                ctypes.byref(t), ctypes.byref(e)))
+    return b.value, t.value, e.value
 
 
 def mx_gemm_workspace_bytes(M, N, K):

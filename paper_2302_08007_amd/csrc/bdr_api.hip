@@ -130,6 +130,50 @@ int bdr_dequantize(const bdr_format *fmt, const void *codes, const void *sexp, c
     return bdr::dequantize_col(*fmt, codes, sexp, mexp, rows, cols, y, dtype, ld, s);
 }
 
+int bdr_gather_dequantize(const bdr_format *fmt, const void *codes, const void *sexp,
+                          const void *mexp, int64_t table_rows, int64_t cols, const int64_t *indices,
+                          int64_t n_indices, void *y, int dtype, void *hip_stream)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    if (!bdr::is_mx(*fmt)) return BDR_ERR_FORMAT;
+    if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
+    if (table_rows < 0 || cols < 0 || n_indices < 0 || cols % 32 != 0) return BDR_ERR_SHAPE;
+    if (cols > ((int64_t)1 << 24) || table_rows > ((int64_t)1 << 40) / (cols > 0 ? cols : 1) ||
+        n_indices > ((int64_t)1 << 40) / (cols > 0 ? cols : 1))
+        return BDR_ERR_SHAPE;
+    if (n_indices == 0 || cols == 0) return BDR_OK;
+    if (!indices) return BDR_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(indices) & 7u) != 0) return BDR_ERR_ALIGN;
+    st = check_tensor_ptr(y, dtype, cols);
+    if (st) return st;
+    if (table_rows > 0) {
+        st = check_planes(fmt, codes, sexp, mexp);
+        if (st) return st;
+    }
+    return bdr::gather_dequantize_row(*fmt, codes, sexp, mexp, table_rows, cols, indices, n_indices, y,
+                                      dtype, static_cast<hipStream_t>(hip_stream));
+}
+
+int bdr_tile_packing(const bdr_format *fmt, int64_t tile_elements, int64_t interface_bytes,
+                     int64_t *packed_bytes, int64_t *transfers, double *efficiency)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    if (tile_elements < 1 || interface_bytes < 1 || tile_elements > ((int64_t)1 << 40) ||
+        interface_bytes > ((int64_t)1 << 20))
+        return BDR_ERR_SHAPE;
+    // bits = tile * ((m+1) + d1/k1 + d2/k2), taken over whole blocks and sub-blocks
+    const int64_t nb = (tile_elements + fmt->k1 - 1) / fmt->k1, ns = (tile_elements + fmt->k2 - 1) / fmt->k2;
+    const int64_t bits = tile_elements * (fmt->m + 1) + nb * fmt->d1 + ns * fmt->d2;
+    const int64_t bytes = (bits + 7) / 8;
+    const int64_t lines = (bytes + interface_bytes - 1) / interface_bytes;
+    if (packed_bytes) *packed_bytes = bytes;
+    if (transfers) *transfers = lines;
+    if (efficiency) *efficiency = (double)bytes / (double)(lines * interface_bytes);
+    return BDR_OK;
+}
+
 int bdr_quantize_dequantize(const bdr_format *fmt, const void *x, void *y, int dtype,
                             int64_t rows, int64_t cols, int64_t ld, int axis, void *hip_stream)
 {

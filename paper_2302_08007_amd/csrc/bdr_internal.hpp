@@ -25,6 +25,9 @@ int quantize_row(const bdr_format &f, const void *x, int dtype, int64_t rows, in
                  int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s);
 int dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
                    int64_t rows, int64_t cols, void *y, int dtype, int64_t ld, hipStream_t s);
+int gather_dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+                          int64_t table_rows, int64_t cols, const int64_t *idx, int64_t n_idx, void *y,
+                          int dtype, hipStream_t s);
 int qdq_row(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
             int64_t ld, hipStream_t s);
 

@@ -129,10 +129,20 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
 // its codes have arrived, so the bytes it has in flight, not its instruction
 // count, set the rate when reads queue behind the kernel's own write stream.
 constexpr int kDeqIter = 2;
-template <int MB, typename T>
+//
+// GATHER: the output is [n_idx x cols] and output row j is row idx[j] of the packed
+// table (a storage format for embedding tables, Sec. V "Inferencing" / recommendation
+// models): a group of the output maps to a group of the table through one index
+// load.  An index outside [0, table_rows) gives a row of +0.
+struct GatherArgs {
+    const int64_t *idx;
+    int64_t table_rows;
+    int32_t groups_per_row;  // cols / 8, a multiple of 4
+};
+template <int MB, typename T, bool GATHER = false>
 __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
-    const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups)
+    const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups, GatherArgs ga)
 {
     constexpr int CB = MB + 1;
     constexpr uint32_t CMASK = (1u << CB) - 1u;
@@ -146,12 +156,20 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     uint32_t v0[kDeqIter], v1[kDeqIter], seb[kDeqIter], tbb[kDeqIter];
 #pragma unroll
     for (int it = 0; it < kDeqIter; ++it) {
-        const int64_t g = g0 + it * kStep;
+        const int64_t go = g0 + it * kStep;  // group of the output
         v0[it] = v1[it] = seb[it] = tbb[it] = 0;
-        if (g < n_groups) {  // whole quads are live or not (n_groups % 4 == 0)
+        bool live = go < n_groups;  // whole quads are live or not (n_groups % 4 == 0)
+        int64_t g = go;             // group of the packed image it comes from
+        if (GATHER && live) {
+            const int64_t j = go / ga.groups_per_row;
+            const int64_t r = ga.idx[j];
+            live = r >= 0 && r < ga.table_rows;
+            g = r * ga.groups_per_row + (go - j * ga.groups_per_row);
+        }
+        if (live) {
             const int64_t quad = g >> 2;
             if (CB == 8) {
-                u32x2 v = ldg<true>(reinterpret_cast<const u32x2 *>(codes + 8 * g));
+                u32x2 v = ldg<!GATHER>(reinterpret_cast<const u32x2 *>(codes + 8 * g));
                 v0[it] = v.x;
                 v1[it] = v.y;
             } else if (CB == 5) {
@@ -561,11 +579,11 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
     if (mx_fast_ok(f, rows, cols, ld)) {
         const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
         if (f.m == 7)
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
         else if (f.m == 4)
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
         else
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng);
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
     } else {
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         hipLaunchKernelGGL((generic_dequantize_kernel<T, false>), grid, block, 0, s, gen_of(f),
@@ -582,6 +600,35 @@ int dequantize_row(const bdr_format &f, const void *codes, const void *sexp, con
                                 (const uint8_t *)mexp, rows, cols, (float *)y, ld, s);
     return dequantize_row_t(f, (const uint8_t *)codes, (const uint8_t *)sexp,
                             (const uint8_t *)mexp, rows, cols, (uint16_t *)y, ld, s);
+}
+
+template <typename T>
+static int gather_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t *sexp,
+                        const uint8_t *mexp, int64_t table_rows, int64_t cols, const int64_t *idx,
+                        int64_t n_idx, T *y, hipStream_t s)
+{
+    const int64_t ng = n_idx * cols / 8;
+    const dim3 block(kThreads);
+    const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
+    const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8)};
+    if (f.m == 7)
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
+    else if (f.m == 4)
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
+    else
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
+    return launch_status();
+}
+
+int gather_dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+                          int64_t table_rows, int64_t cols, const int64_t *idx, int64_t n_idx, void *y,
+                          int dtype, hipStream_t s)
+{
+    if (dtype == BDR_F32)
+        return gather_row_t(f, (const uint8_t *)codes, (const uint8_t *)sexp, (const uint8_t *)mexp,
+                            table_rows, cols, idx, n_idx, (float *)y, s);
+    return gather_row_t(f, (const uint8_t *)codes, (const uint8_t *)sexp, (const uint8_t *)mexp,
+                        table_rows, cols, idx, n_idx, (uint16_t *)y, s);
 }
 
 template <typename T>

@@ -143,3 +143,33 @@ def test_sweep_and_gemm_argument_checks():
     assert L.mx_gemm_workspace_bytes(128, 384, 64) == (128 + 384) * 64 * 2
     assert gm(ws=FAKE, wsb=need - 1) == ERR_WS
     assert gm(ws=FAKE_ODD, wsb=need) == ERR_ALIGN
+
+
+def test_tile_packing_of_the_paper_formats():
+    # Sec. IV-B "Memory Footprint": a 256-element tile into a 64-byte interface.  Table II gives
+    # 9 / 6 / 4 bits per element, so the tile is 288 / 192 / 128 bytes: 5 / 3 / 2 transfers,
+    # i.e. MX9 fills 4.5 of 5 (90 %), MX6 and MX4 fill theirs completely.
+    assert B.bdr_tile_packing(B.MX9) == (288, 5, 0.9)
+    assert B.bdr_tile_packing(B.MX6) == (192, 3, 1.0)
+    assert B.bdr_tile_packing(B.MX4) == (128, 2, 1.0)
+    # block floating point with 8-bit mantissas and sign over 16 elements: 9.5 bits per element
+    assert B.bdr_tile_packing(B.fmt(16, 16, 0, 8))[0] == 304
+    # a tile that is not a whole number of blocks still pays for the last block's exponent
+    assert B.bdr_tile_packing(B.MX9, tile_elements=8)[0] == (8 * 8 + 8 + 4 + 7) // 8
+    L = B.lib
+    assert L.bdr_tile_packing(ctypes.byref(B.MX9), 0, 64, NULL, NULL, NULL) == ERR_SHAPE
+    assert L.bdr_tile_packing(ctypes.byref(B.fmt(16, 3, 1, 7)), 256, 64, NULL, NULL, NULL) == ERR_FORMAT
+    assert L.bdr_tile_packing(ctypes.byref(B.MX9), 256, 64, NULL, NULL, NULL) == OK
+
+
+def test_gather_argument_checks():
+    L = B.lib
+    f = B.MX6
+    ga = lambda fm=f, rows=100, cols=128, idx=FAKE, n=10, y=FAKE, dtype=0, codes=FAKE: L.bdr_gather_dequantize(
+        ctypes.byref(fm), codes, FAKE, FAKE, rows, cols, idx, n, y, dtype, NULL)
+    assert ga(fm=B.fmt(32, 2, 1, 4)) == ERR_FORMAT
+    assert ga(cols=48) == ERR_SHAPE and ga(n=-1) == ERR_SHAPE and ga(rows=-1) == ERR_SHAPE
+    assert ga(dtype=5) == ERR_DTYPE
+    assert ga(idx=NULL) == ERR_NULL and ga(y=NULL) == ERR_NULL and ga(codes=NULL) == ERR_NULL
+    assert ga(idx=FAKE_ODD) == ERR_ALIGN and ga(y=FAKE_ODD) == ERR_ALIGN
+    assert ga(n=0) == OK
