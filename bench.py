@@ -76,14 +76,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other", action="store_true", help="skip the separately timed legs")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 25)
+    ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a 1 GiB tensor copy and one launch of each row-wise MX kernel, "
                          "three times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (every shard of the path is "
-                 "independent; see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (blocks are independent, so the path "
+                 "shards by rows with no exchange and one GPU shows all of it); run with --gpus 1")
 
     import torch
 
