@@ -5,7 +5,9 @@
 //   mx_*      the Table II formats (k1 16, k2 2, d2 1, nearest-even), m in {7,4,2}.
 //             One lane owns 8 consecutive elements (four sub-blocks, half a
 //             block); the two lanes of a block meet through one DPP quad
-//             permute.  HBM bound: every byte is read once and written once.
+//             permute.  HBM bound: every byte is read once and written once;
+//             FP32 tensors move as fully contiguous 1 KiB wave rows staged
+//             through wave-private LDS (wave_load512 / wave_store512).
 //   generic_* any format the library accepts, parameters at run time.
 //
 // Quantization follows Sec. IX of the paper: the shared exponent is the exponent
@@ -36,11 +38,9 @@ __device__ __forceinline__ void mx_quant8(const uint32_t (&xb)[8], uint32_t &lo,
     hi = MxWords<MB, 4>::kN > 1 ? w[MxWords<MB, 4>::kN - 1] : 0u;
 }
 
-// One group of 8 elements per thread and a one-shot grid: on this chip short
-// waves with high turnover beat loops and deeper per-thread prefetch (measured:
-// 2 or 4 groups per thread cost 10-25 %).
-// groups of 8 elements a lane quantizes: BF16 rows bring only 16 bytes per group, so a
-// lane takes four to have enough bytes in flight; FP32 rows are best with one
+// One-shot grids (measured: persistent grids are slower on this chip).  Groups of 8
+// elements a lane quantizes: BF16 rows bring only 16 bytes per group, so a lane takes
+// four to have enough bytes in flight; FP32 rows are best with one (two cost 2 %).
 template <typename T>
 constexpr int q_iter() { return sizeof(T) == 2 ? 4 : 1; }
 
