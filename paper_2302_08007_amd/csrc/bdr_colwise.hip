@@ -22,7 +22,9 @@ namespace bdr {
 
 namespace {
 
-constexpr int kTR = 128;       // tile rows = 8 blocks of 16
+constexpr int kTR = 128;              // tile rows = kBPT blocks of 16 (64-row tiles measured slower)
+constexpr int kBPT = kTR / 16;        // blocks per tile column (a power of two <= 8)
+constexpr int kCPW = 64 / kBPT;       // columns a wave takes per pass
 constexpr int kColThreads = 256;
 constexpr uint32_t kColRun = 16;  // column tiles an XCD sweeps before it moves down one row tile
 
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(kColThreads) void mx_col_kernel(
     const int64_t r0 = (int64_t)tx * kTR;
     const int64_t c0 = (int64_t)ty * kTC;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b = lane & 7, cl = lane >> 3;
+    const int b = lane & (kBPT - 1), cl = lane / kBPT;
     const int64_t blocks_per_col = rows >> 4;
 
     if (MODE != 1) {
@@ -223,8 +225,8 @@ __global__ __launch_bounds__(kColThreads) void mx_col_kernel(
         __syncthreads();
     }
 #pragma unroll
-    for (int it = 0; it < kTC / 32; ++it) {
-        const int c = 8 * (wave + 4 * it) + cl;  // column inside the tile
+    for (int it = 0; it < kTC / (4 * kCPW); ++it) {
+        const int c = kCPW * (wave + 4 * it) + cl;  // column inside the tile
         const int64_t blk = (c0 + c) * blocks_per_col + (r0 >> 4) + b;
         uint32_t xb[16], yb[16], w[4], se, tau8;
         if (MODE != 1) {
