@@ -42,7 +42,7 @@ namespace {
 
 constexpr int kSweepThreads = 256;
 constexpr int kG = 2;  // groups of 8 elements per lane per iteration
-constexpr int kSweepBlocks = 512;  // two resident workgroups per compute unit
+constexpr int kSweepBlocks = 768;  // three resident workgroups per compute unit
 
 constexpr int kChunk = 128;  // formats per launch: bounds kernel arguments (< 4 KiB) and LDS
 constexpr int kMaxGroups = kChunk;
@@ -286,7 +286,7 @@ __device__ __forceinline__ float direct(const float (&yp)[kG][8], const int (&sh
 // ALL_RNE: every format of the launch rounds to nearest even (the usual case);
 // the other two modes are then compiled out.
 template <typename T, bool ALL_RNE>
-__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
+__global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
     SweepPlan plan, const T *__restrict__ x, int64_t cols, int64_t ld, int64_t n_groups,
     const uint32_t *__restrict__ blockmax, double *__restrict__ partials)
 {
@@ -384,17 +384,17 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
                 }
 #pragma unroll
                 for (int r = 0; r < kMR; ++r) {
-                    if (r < gd.n_mr) {
-                        const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
+                    // an unused slot repeats slot 0 (the host fills it so): computing it
+                    // anyway keeps the candidate arrays free of conditional definitions
+                    const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
 #pragma unroll
-                        for (int j = 0; j < kG; ++j) {
-                            if (ALL_RNE || c.rounding == BDR_RNE)
-                                candidates<BDR_RNE>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
-                            else if (c.rounding == BDR_RNA)
-                                candidates<BDR_RNA>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
-                            else
-                                candidates<BDR_RTZ>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
-                        }
+                    for (int j = 0; j < kG; ++j) {
+                        if (ALL_RNE || c.rounding == BDR_RNE)
+                            candidates<BDR_RNE>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
+                        else if (c.rounding == BDR_RNA)
+                            candidates<BDR_RNA>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
+                        else
+                            candidates<BDR_RTZ>(ax[j], cb[j], c, d0[r][j], d1[r][j]);
                     }
                 }
                 for (int ci = 0; ci < gd.n_cls; ++ci) {
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(
                     auto run = [&](auto pick) {
 #pragma unroll
                         for (int r = 0; r < kMR; ++r) {
-                            if (r < gd.n_mr && cd.q[r] != kNone) {
+                            if (cd.q[r] != kNone) {
                                 float sum = 0.f;
 #pragma unroll
                                 for (int j = 0; j < kG; ++j)
@@ -583,8 +583,10 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
             gd.lk1 = (uint8_t)lk1;
             gd.shared = (uint8_t)shared;
             gd.n_mr = 1;
-            gd.m[0] = (uint8_t)m;
-            gd.rnd[0] = (uint8_t)rnd;
+            for (int k = 0; k < kMR; ++k) {  // unused slots repeat slot 0
+                gd.m[k] = (uint8_t)m;
+                gd.rnd[k] = (uint8_t)rnd;
+            }
             r = 0;
         }
         f_group[f] = gi;
