@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a 1 GiB tensor copy and one launch of each row-wise MX kernel, "
                          "three times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--other-probe", action="store_true",
+                    help="run mx_gemm (both forms, 8192^3 MX6) and the 64-format sweep a few times and "
+                         "exit (for rocprofv3 --pmc MfmaUtil VALUBusy)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (blocks are independent, so the path "
@@ -118,6 +121,27 @@ def main():
             mark()
         if record:
             marks.append(ev)
+
+    if args.other_probe:
+        del x, y, planes
+        M = N = K = 8192
+        A, Bm = S.gemm_operands(M, N, K, device="cuda")
+        pa, pb = B.bdr_quantize(B.MX6, A), B.bdr_quantize(B.MX6, Bm)
+        C = torch.empty(M, N, device="cuda")
+        ws = torch.empty(B.mx_gemm_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        for i in range(45):  # the first 40 settle the matrix-core clock, the last 5 are the sample
+            B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C, workspace=ws)
+        for i in range(5):
+            B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C)
+        xs = S.sweep(device="cuda")
+        fmts = [B.fmt(k1, k1 if k2 == 0 else k2, d2, m) for k1 in (8, 16, 32, 64)
+                for k2 in (1, 2, 4, 0) for d2 in (0, 1) for m in (2, 4)]
+        wsw = torch.empty(B.lib.bdr_qsnr_sweep_workspace_bytes(len(fmts)), dtype=torch.uint8, device="cuda")
+        for i in range(5):
+            B.bdr_qsnr_sweep(fmts, xs, workspace=wsw)
+        torch.cuda.synchronize()
+        print(json.dumps({"other_probe": "45 x two-pass mx_gemm, 5 x single-kernel mx_gemm, 5 x 64-format sweep"}))
+        return
 
     if args.pmc_probe:
         # the copy reads 1 GiB and writes 1 GiB: it calibrates the counters' units
