@@ -20,6 +20,29 @@ inline int launch_status()
     return hipGetLastError() == hipSuccess ? BDR_OK : BDR_ERR_LAUNCH;
 }
 
+// A workgroup may use more than 64 KiB of dynamic LDS only after the kernel has been
+// given that limit on the device it is launched on.  `state` (one per kernel, zero
+// initialised) remembers the answer per device: 0 not asked, 1 granted, -1 refused.
+// Two host threads that race on the first call both ask and get the same answer.
+constexpr int kMaxDevices = 64;
+inline bool grant_dynamic_lds(const void *kernel, size_t bytes, signed char (&state)[kMaxDevices])
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return false;
+    signed char local = 0;
+    signed char &st = dev < kMaxDevices ? state[dev] : local;
+    if (st == 0) {
+        int lds = 0;
+        const bool ok =
+            hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
+            (size_t)lds >= bytes &&
+            hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+        (void)hipGetLastError();
+        st = ok ? 1 : -1;
+    }
+    return st > 0;
+}
+
 // Blocks along the contiguous axis.  All arguments were validated by the caller.
 int quantize_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,
                  int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s);

@@ -629,18 +629,12 @@ template <typename T, bool ALL_RNE>
 int launch_sweep(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
                  int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
 {
-    static int big_lds = 0;  // 0 not asked for yet, 1 granted, -1 refused
+    static signed char granted[kMaxDevices];
     const size_t lds = (size_t)(plan.n_quant + 1) * kSweepThreads * sizeof(float);
-    if (lds > 64 * 1024) {
-        if (big_lds == 0)
-            big_lds = hipFuncSetAttribute((const void *)sweep_kernel<T, ALL_RNE>,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)((kChunk + 1) * kSweepThreads * sizeof(float))) ==
-                              hipSuccess
-                          ? 1
-                          : -1;
-        if (big_lds < 0) return BDR_ERR_LAUNCH;
-    }
+    if (lds > 64 * 1024 &&
+        !grant_dynamic_lds((const void *)sweep_kernel<T, ALL_RNE>,
+                           (kChunk + 1) * kSweepThreads * sizeof(float), granted))
+        return BDR_ERR_LAUNCH;
     hipLaunchKernelGGL((sweep_kernel<T, ALL_RNE>), dim3(nb), dim3(kSweepThreads), lds, s, plan,
                        (const T *)x, cols, ld, n_groups, blockmax, partials);
     return BDR_OK;

@@ -428,17 +428,11 @@ int launch_gemm(const uint8_t *ac, const uint8_t *as, const uint8_t *am, const u
 {
     constexpr size_t kBigLds = 2 * (256 + 256) * (size_t)kPitch;
     constexpr size_t kSmallLds = 2 * (128 + 128) * (size_t)kPitch;
-    static int big_ok = -1;  // does this device allow a 128 KiB workgroup?  asked once
-    if (big_ok < 0) {
-        int dev = 0, lds = 0;
-        big_ok = hipGetDevice(&dev) == hipSuccess &&
-                 hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
-                 (size_t)lds >= kBigLds &&
-                 hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBigLds) == hipSuccess;
-        (void)hipGetLastError();
-    }
-    if (big_ok == 1 && M % 256 == 0 && N % 256 == 0) {
+    static signed char granted[kMaxDevices];  // does the device allow a 128 KiB workgroup?
+    const bool big_ok =
+        M % 256 == 0 && N % 256 == 0 &&
+        grant_dynamic_lds(reinterpret_cast<const void *>(&mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>), kBigLds, granted);
+    if (big_ok) {
         const unsigned grid = (unsigned)((M / 256) * (N / 256));
         hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>), dim3(grid), dim3(512), kBigLds, s,
                            ac, as, am, bc, bs, bm, M, N, K, C, ldc);
@@ -466,15 +460,10 @@ int launch_bf16(const uint16_t *A, const uint16_t *B, int M, int N, int K, float
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t kLds = 2 * (BM + BN) * (size_t)kPitch;
-    static int ok = 0;  // 0 not asked yet, 1 granted, -1 refused
-    if (ok == 0) {
-        ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&bf16_gemm_dl_kernel<WM, WN, TM, TN>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) == hipSuccess
-                 ? 1
-                 : -1;
-        (void)hipGetLastError();
-    }
-    if (ok < 0) return BDR_ERR_LAUNCH;
+    static signed char granted[kMaxDevices];
+    if (kLds > 64 * 1024 &&
+        !grant_dynamic_lds(reinterpret_cast<const void *>(&bf16_gemm_dl_kernel<WM, WN, TM, TN>), kLds, granted))
+        return BDR_ERR_LAUNCH;
     hipLaunchKernelGGL((bf16_gemm_dl_kernel<WM, WN, TM, TN>), dim3((unsigned)((M / BM) * (N / BN))),
                        dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc);
     return launch_status();
