@@ -112,6 +112,27 @@ def _p(t):
     return ctypes.c_void_p(0 if t is None or t.numel() == 0 else t.data_ptr())
 
 
+def _check_planes(f, planes, rows, cols, axis=AXIS_ROW):
+    """The C ABI takes bare pointers, so buffer sizes are verified here: a plane shorter than
+    bdr_packed_sizes says would be written (or read) past its end."""
+    need = bdr_packed_sizes(f, rows, cols, axis)
+    if len(planes) != 3:
+        raise ValueError("expected (codes, sexp, mexp)")
+    for name, t, n in zip(("codes", "sexp", "mexp"), planes, need):
+        if n == 0:
+            continue
+        if t is None or not (t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous()):
+            raise ValueError("%s plane must be a contiguous uint8 GPU tensor" % name)
+        if t.numel() < n:
+            raise ValueError("%s plane holds %d bytes, %d needed" % (name, t.numel(), n))
+
+
+def _check_buffer(name, t, dtype, numel):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous() and t.numel() >= numel):
+        raise ValueError("%s must be a contiguous %s GPU tensor of at least %d elements"
+                         % (name, dtype, numel))
+
+
 def bdr_format_validate(f):
     return lib.bdr_format_validate(ctypes.byref(f))
 
@@ -133,6 +154,8 @@ def bdr_quantize(f, x, axis=AXIS_ROW, out=None):
     """Quantize a 2-D GPU tensor into (codes, sexp, mexp) uint8 planes."""
     rows, cols, ld = _dev2d(x)
     planes = out if out is not None else alloc_planes(f, rows, cols, axis, x.device)
+    if out is not None:
+        _check_planes(f, planes, rows, cols, axis)
     _check(lib.bdr_quantize(ctypes.byref(f), _p(x), _dtype_code(x), rows, cols, ld, axis,
                             _p(planes[0]), _p(planes[1]), _p(planes[2]), _stream()))
     return planes
@@ -141,7 +164,9 @@ def bdr_quantize(f, x, axis=AXIS_ROW, out=None):
 def bdr_dequantize(f, planes, rows, cols, axis=AXIS_ROW, dtype=torch.float32, out=None):
     y = out if out is not None else torch.empty((rows, cols), dtype=dtype, device=planes[0].device)
     r, c, ld = _dev2d(y)
-    assert (r, c) == (rows, cols)
+    if (r, c) != (rows, cols):
+        raise ValueError("output must be [rows x cols]")
+    _check_planes(f, planes, rows, cols, axis)
     _check(lib.bdr_dequantize(ctypes.byref(f), _p(planes[0]), _p(planes[1]), _p(planes[2]), rows,
                               cols, axis, _p(y), _dtype_code(y), ld, _stream()))
     return y
@@ -168,6 +193,9 @@ def bdr_qsnr_sweep(fmts, x, workspace=None, out=None):
     if out is None:
         out = (torch.empty(n, dtype=torch.float64, device=x.device),
                torch.empty(n + 1, dtype=torch.float64, device=x.device))
+    _check_buffer("qsnr_db", out[0], torch.float64, n)
+    _check_buffer("sums", out[1], torch.float64, n + 1)
+    _check_buffer("workspace", workspace, torch.uint8, 0)
     _check(lib.bdr_qsnr_sweep(arr, n, _p(x), _dtype_code(x), rows, cols, ld, _p(out[0]),
                               _p(out[1]), _p(workspace), workspace.numel(), _stream()))
     return out
@@ -178,6 +206,10 @@ def bdr_gather_dequantize(fmt, planes, table_rows, cols, indices, dtype=None, ou
     dtype = dtype or torch.float32
     n = indices.numel()
     y = out if out is not None else torch.empty((n, cols), dtype=dtype, device=indices.device)
+    _check_buffer("indices", indices, torch.int64, n)
+    if not (y.is_cuda and y.is_contiguous() and tuple(y.shape) == (n, cols)):
+        raise ValueError("output must be a contiguous [n_indices x cols] GPU tensor")
+    _check_planes(fmt, planes, table_rows, cols)
     _check(lib.bdr_gather_dequantize(ctypes.byref(fmt), _p(planes[0]), _p(planes[1]), _p(planes[2]),
                                      table_rows, cols, _p(indices), n, _p(y), _dtype_code(y),
                                      _stream()))
@@ -202,6 +234,14 @@ def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None):
     form, None the single-kernel form."""
     C = out if out is not None else torch.empty((M, N), dtype=torch.float32,
                                                 device=a_planes[0].device)
+    if not (C.is_cuda and C.dtype == torch.float32 and C.dim() == 2 and tuple(C.shape) == (M, N)
+            and C.stride(1) == 1):
+        raise ValueError("output must be an [M x N] float32 GPU tensor with unit column stride")
+    if K > 0:
+        _check_planes(fa, a_planes, M, K)
+        _check_planes(fb, b_planes, N, K)
+    if workspace is not None:
+        _check_buffer("workspace", workspace, torch.uint8, 0)
     ws, wsb = (_p(workspace), workspace.numel()) if workspace is not None else (None, 0)
     _check(lib.mx_gemm(ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]),
                        _p(a_planes[2]), _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]), M, N, K,
