@@ -349,22 +349,32 @@ __device__ __forceinline__ float gen_round(float ax, int sh, float top, int roun
 }
 
 // MODE 0: write the packed planes.  MODE 1: write the dequantized tensor.
-template <typename T, int MODE, bool STRIDED>
+// CONTIG (FP32, pitch = row length): the tensor side moves as contiguous 1 KiB
+// wave rows through LDS like in the MX kernels.  The planes of a workgroup's 2048
+// elements are contiguous runs of the three planes; they are assembled in LDS and
+// leave as coalesced stores by consecutive lanes.
+template <typename T, int MODE, bool STRIDED, bool CONTIG>
 __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     GenFmt f, const T *x, T *y, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp, int64_t cols, int64_t sr, int64_t sc,
     int64_t n_groups)
 {
-    __shared__ uint32_t s_mexp[kTileElems * 3 / 32 + 1];
-    if (MODE == 0 && f.d2 > 0) {
-        for (int t = threadIdx.x; t < kTileElems * 3 / 32 + 1; t += kThreads) s_mexp[t] = 0;
-        __syncthreads();
-    }
+    static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
+    __shared__ uint32_t s_mexp[MODE == 0 ? kTileElems * 3 / 32 + 1 : 1];
+    __shared__ uint32_t s_codes[MODE == 0 ? kThreads * 9 / 4 : 1];  // up to 9 bytes per lane
+    __shared__ uint32_t s_sexp[MODE == 0 ? kTileElems / 4 : 1];     // up to one byte per element
+    __shared__ float s_stage[CONTIG ? kThreads / 64 : 1][CONTIG ? kWaveStage : 1];
     const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const bool active = g < n_groups;
     uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int64_t addr = 0;
-    if (active) {
+    const int64_t wave_g = g - (threadIdx.x & 63);  // first group of this wave
+    if (MODE == 0 && f.d2 > 0)  // cleared while the loads below are in flight
+        for (int t = threadIdx.x; t < kTileElems * 3 / 32 + 1; t += kThreads) s_mexp[t] = 0;
+    if (CONTIG) {
+        wave_load512(reinterpret_cast<const float *>(x) + 8 * wave_g, xb, 8 * (n_groups - wave_g),
+                     s_stage[threadIdx.x >> 6]);
+    } else if (active) {
         const int64_t t0 = 8 * g;
         const int64_t r = t0 / cols;
         addr = r * sr + (t0 - r * cols) * sc;
@@ -375,6 +385,7 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
             load8(x + addr, xb);
         }
     }
+    if (MODE == 0 && f.d2 > 0) __syncthreads();
     uint32_t pe[8], be[8];
     gen_maxima(f, xb, pe, be);
 
@@ -394,7 +405,10 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         if (MODE == 1) yb[i] = as_u(__builtin_ldexpf(mf, -sh)) | (xb[i] & 0x80000000u);
     }
     if (MODE == 1) {
-        if (active) {
+        if (CONTIG) {
+            wave_store512(reinterpret_cast<float *>(y) + 8 * wave_g, yb, 8 * (n_groups - wave_g),
+                          s_stage[threadIdx.x >> 6]);
+        } else if (active) {
             if (STRIDED) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) store1(y + addr + i * sc, yb[i]);
@@ -405,32 +419,35 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         return;
     }
 
+    // ---- planes of this workgroup, assembled in LDS
+    const int64_t block_g0 = (int64_t)blockIdx.x * kThreads;
+    const int n_active = (int)(n_groups - block_g0 < kThreads ? n_groups - block_g0 : kThreads);
+    uint8_t *lc = reinterpret_cast<uint8_t *>(s_codes);
+    uint8_t *ls = reinterpret_cast<uint8_t *>(s_sexp);
+    const int lk1 = __builtin_ctz(f.k1);
     if (active) {
         // 8 codes of cb <= 9 bits: 64 bits plus, for cb = 9, one more byte
         uint64_t w = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) w |= (uint64_t)code[i] << (i * cb);
         const uint32_t extra = code[7] >> 1;
-        uint8_t *cp = codes + (int64_t)cb * g;
+        uint8_t *cp = lc + cb * threadIdx.x;
         for (int b = 0; b < cb; ++b) cp[b] = b < 8 ? (uint8_t)(w >> (8 * b)) : (uint8_t)extra;
 
         if (f.k1 >= 8) {
             const int lanes = f.k1 / 8;
-            if ((g & (lanes - 1)) == 0) sexp[g / lanes] = (uint8_t)(be[0] >> 23);
+            if ((threadIdx.x & (lanes - 1)) == 0) ls[threadIdx.x / lanes] = (uint8_t)(be[0] >> 23);
         } else {
-            const int lk1 = __builtin_ctz(f.k1);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                if ((i & (f.k1 - 1)) == 0) sexp[((8 * g) >> lk1) + (i >> lk1)] = (uint8_t)(be[i] >> 23);
+                if ((i & (f.k1 - 1)) == 0)
+                    ls[((8 * threadIdx.x) >> lk1) + (i >> lk1)] = (uint8_t)(be[i] >> 23);
         }
     }
-    if (f.d2 == 0) return;
-
-    // Microexponents: each lane ORs its bits into the tile's bit stream in LDS,
-    // then the tile is written out byte by byte.  A tile's stream starts on a
-    // byte boundary because kTileElems / k2 is a multiple of 8.
+    // Microexponents: each lane ORs its bits into the tile's bit stream.  A tile's
+    // stream starts on a byte boundary because kTileElems / k2 is a multiple of 8.
     const int64_t tile_sub0 = (int64_t)blockIdx.x * (kTileElems / f.k2);
-    if (active) {
+    if (active && f.d2 > 0) {
         uint32_t field = 0;
         int width = 0;
         int64_t u0;
@@ -451,12 +468,33 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         }
         if (width > 0) {
             const uint32_t bit = (uint32_t)((u0 - tile_sub0) * f.d2);
-            const uint32_t s = bit & 31u;
-            atomicOr(&s_mexp[bit >> 5], field << s);
-            if (s + (uint32_t)width > 32u) atomicOr(&s_mexp[(bit >> 5) + 1], field >> (32u - s));
+            const uint32_t sft = bit & 31u;
+            atomicOr(&s_mexp[bit >> 5], field << sft);
+            if (sft + (uint32_t)width > 32u) atomicOr(&s_mexp[(bit >> 5) + 1], field >> (32u - sft));
         }
     }
     __syncthreads();
+    // ---- flush: consecutive lanes write consecutive dwords (bytes at the ragged end)
+    {
+        const int nbytes = cb * n_active;  // the workgroup's codes start at byte cb * 256 * blockIdx
+        uint8_t *gp = codes + (int64_t)cb * block_g0;
+        uint32_t *gw = reinterpret_cast<uint32_t *>(gp);
+        for (int t = threadIdx.x; t < nbytes / 4; t += kThreads) gw[t] = s_codes[t];
+        for (int t = (nbytes & ~3) + threadIdx.x; t < nbytes; t += kThreads) gp[t] = lc[t];
+    }
+    {
+        const int64_t e0 = 8 * block_g0;                  // first element of the workgroup
+        const int nbytes = (int)((8 * (int64_t)n_active) >> lk1);  // whole blocks only (host-checked)
+        uint8_t *gp = sexp + (e0 >> lk1);
+        if (((e0 >> lk1) & 3) == 0) {
+            uint32_t *gw = reinterpret_cast<uint32_t *>(gp);
+            for (int t = threadIdx.x; t < nbytes / 4; t += kThreads) gw[t] = s_sexp[t];
+            for (int t = (nbytes & ~3) + threadIdx.x; t < nbytes; t += kThreads) gp[t] = ls[t];
+        } else {
+            for (int t = threadIdx.x; t < nbytes; t += kThreads) gp[t] = ls[t];
+        }
+    }
+    if (f.d2 == 0) return;
     const int64_t n_sub = n_groups * 8 / f.k2;
     int64_t tile_subs = n_sub - tile_sub0;
     if (tile_subs > kTileElems / f.k2) tile_subs = kTileElems / f.k2;
@@ -466,46 +504,82 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         mp[b] = (uint8_t)(s_mexp[b >> 2] >> (8 * (b & 3)));
 }
 
-template <typename T, bool STRIDED>
+template <typename T, bool STRIDED, bool CONTIG>
 __global__ __launch_bounds__(kThreads) void generic_dequantize_kernel(
     GenFmt f, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, int64_t mexp_bytes, T *__restrict__ y, int64_t cols,
     int64_t sr, int64_t sc, int64_t n_groups)
 {
+    static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
+    __shared__ float s_stage[CONTIG ? kThreads / 64 : 1][CONTIG ? kWaveStage : 1];
     const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (g >= n_groups) return;
+    const bool active = g < n_groups;
+    if (!CONTIG && !active) return;
     const int cb = f.m + 1;
     const uint32_t cmask = (1u << cb) - 1u, mmask = (1u << f.m) - 1u;
     const uint32_t beta = (1u << f.d2) - 1u;
-
     const int lk1 = __builtin_ctz(f.k1), lk2 = __builtin_ctz(f.k2);
-    const uint8_t *cp = codes + (int64_t)cb * g;
-    uint64_t w = 0;
-    uint32_t extra = 0;
-    for (int b = 0; b < cb; ++b) {
-        if (b < 8)
-            w |= (uint64_t)cp[b] << (8 * b);
-        else
-            extra = cp[b];
-    }
-    uint32_t yb[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        uint32_t c = (uint32_t)(w >> (i * cb));
-        if (i == 7 && cb == 9) c |= extra << 1;
-        c &= cmask;
-        const int64_t t = 8 * g + i;
-        const int se = sexp[t >> lk1];
-        uint32_t tau = 0;
-        if (f.d2 > 0) {
-            const int64_t bit = (t >> lk2) * f.d2;
-            const int64_t byte = bit >> 3;
-            uint32_t v = mexp[byte];
-            if (byte + 1 < mexp_bytes) v |= (uint32_t)mexp[byte + 1] << 8;
-            tau = (v >> (bit & 7)) & beta;
+
+    uint32_t yb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (active) {
+        // the lane's cb bytes sit inside three aligned dwords; at the very end of the
+        // plane, where a dword would reach past it, they are fetched one by one
+        const int64_t base = (int64_t)cb * g, a0 = base & ~(int64_t)3, total = (int64_t)cb * n_groups;
+        uint64_t w = 0;
+        uint32_t extra = 0;
+        if (a0 + 12 <= total) {
+            const uint32_t *dp = reinterpret_cast<const uint32_t *>(codes + a0);
+            const uint32_t d0 = dp[0], d1 = dp[1], d2w = dp[2];
+            const uint32_t sft = 8u * (uint32_t)(base - a0);
+            w = (uint64_t)funnel_r(d1, d0, sft) | ((uint64_t)funnel_r(d2w, d1, sft) << 32);
+            extra = (d2w >> sft) & 0xffu;
+        } else {
+            const uint8_t *cp = codes + base;
+            for (int b = 0; b < cb; ++b) {
+                if (b < 8)
+                    w |= (uint64_t)cp[b] << (8 * b);
+                else
+                    extra = cp[b];
+            }
         }
-        const int q = se - 127 - (int)tau - (f.m - 1);
-        yb[i] = as_u(__builtin_ldexpf((float)(c & mmask), q)) | ((c >> f.m) << 31);
+        // shared exponents: one per lane when the block spans the lane's 8 elements
+        int se[8];
+        if (lk1 >= 3) {
+            const int v = sexp[(8 * g) >> lk1];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) se[i] = v;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) se[i] = sexp[((8 * g) >> lk1) + (i >> lk1)];
+        }
+        // microexponents: the lane's fields are at most 24 consecutive bits of the stream
+        uint32_t tau[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (f.d2 > 0) {
+            const int64_t bit0 = ((8 * g) >> lk2) * f.d2;
+            const int64_t byte0 = bit0 >> 3;
+            const int nsub = lk2 >= 3 ? 1 : 8 >> lk2;
+            const int last = (int)(((bit0 & 7) + nsub * f.d2 - 1) >> 3);  // index of the last byte needed
+            uint32_t v = 0;
+            for (int b = 0; b <= last; ++b)
+                if (byte0 + b < mexp_bytes) v |= (uint32_t)mexp[byte0 + b] << (8 * b);
+            v >>= (bit0 & 7);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) tau[i] = (v >> ((lk2 >= 3 ? 0 : i >> lk2) * f.d2)) & beta;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t c = (uint32_t)(w >> (i * cb));
+            if (i == 7 && cb == 9) c |= extra << 1;
+            c &= cmask;
+            const int q = se[i] - 127 - (int)tau[i] - (f.m - 1);
+            yb[i] = as_u(__builtin_ldexpf((float)(c & mmask), q)) | ((c >> f.m) << 31);
+        }
+    }
+    if (CONTIG) {
+        const int64_t wave_g = g - (threadIdx.x & 63);
+        wave_store512(reinterpret_cast<float *>(y) + 8 * wave_g, yb, 8 * (n_groups - wave_g),
+                      s_stage[threadIdx.x >> 6]);
+        return;
     }
     const int64_t t0 = 8 * g;
     const int64_t r = t0 / cols;
@@ -553,8 +627,17 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
         else
             hipLaunchKernelGGL((mx_quantize_row_kernel<2, T>), qgrid, block, 0, s, x, codes, sexp, mexp, ng);
     } else {
-        hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false>), grid, block, 0, s, gen_of(f), x,
-                           (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
+        bool done = false;
+        if constexpr (sizeof(T) == 4) {
+            if (ld == cols) {
+                hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, true>), grid, block, 0, s, gen_of(f),
+                                   x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
+                done = true;
+            }
+        }
+        if (!done)
+            hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, false>), grid, block, 0, s, gen_of(f),
+                               x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
     }
     return launch_status();
 }
@@ -586,8 +669,17 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
             hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
     } else {
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
-        hipLaunchKernelGGL((generic_dequantize_kernel<T, false>), grid, block, 0, s, gen_of(f),
-                           codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
+        bool done = false;
+        if constexpr (sizeof(T) == 4) {
+            if (ld == cols) {
+                hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
+                                   codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
+                done = true;
+            }
+        }
+        if (!done)
+            hipLaunchKernelGGL((generic_dequantize_kernel<T, false, false>), grid, block, 0, s, gen_of(f),
+                               codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
     }
     return launch_status();
 }
@@ -656,9 +748,19 @@ static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_
         else
             hipLaunchKernelGGL((mx_qdq_row_kernel<2, T>), grid, block, 0, s, x, y, ng);
     } else {
-        hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false>), grid, block, 0, s, gen_of(f), x,
-                           y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols, ld,
-                           (int64_t)1, ng);
+        bool done = false;
+        if constexpr (sizeof(T) == 4) {
+            if (ld == cols) {
+                hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, true>), grid, block, 0, s, gen_of(f),
+                                   x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,
+                                   ld, (int64_t)1, ng);
+                done = true;
+            }
+        }
+        if (!done)
+            hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, false>), grid, block, 0, s, gen_of(f),
+                               x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,
+                               ld, (int64_t)1, ng);
     }
     return launch_status();
 }
@@ -679,14 +781,14 @@ static int generic_col_t(int what, const bdr_format &f, const T *x, T *y, int64_
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (what == 0)
-        hipLaunchKernelGGL((generic_quantize_kernel<T, 0, true>), grid, block, 0, s, gen_of(f), x,
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 0, true, false>), grid, block, 0, s, gen_of(f), x,
                            (T *)nullptr, codes, sexp, mexp, rows, (int64_t)1, ld, ng);
     else if (what == 1)
-        hipLaunchKernelGGL((generic_dequantize_kernel<T, true>), grid, block, 0, s, gen_of(f),
+        hipLaunchKernelGGL((generic_dequantize_kernel<T, true, false>), grid, block, 0, s, gen_of(f),
                            codes, sexp, mexp, (rows * cols / f.k2 * f.d2 + 7) / 8, y, rows,
                            (int64_t)1, ld, ng);
     else
-        hipLaunchKernelGGL((generic_quantize_kernel<T, 1, true>), grid, block, 0, s, gen_of(f), x,
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 1, true, false>), grid, block, 0, s, gen_of(f), x,
                            y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, rows,
                            (int64_t)1, ld, ng);
     return launch_status();
