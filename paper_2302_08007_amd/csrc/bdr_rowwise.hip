@@ -348,6 +348,21 @@ __device__ __forceinline__ float gen_round(float ax, int sh, float top, int roun
     return t;
 }
 
+// The lane's 8 codes of CB bits each as CB bytes at cp (LDS), little-endian bit stream.
+template <int CB>
+__device__ __forceinline__ void pack_codes(const uint32_t (&code)[8], uint8_t *cp)
+{
+    uint32_t w[3] = {0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int off = i * CB;
+        w[off >> 5] |= code[i] << (off & 31);
+        if ((off & 31) + CB > 32) w[(off >> 5) + 1] |= code[i] >> (32 - (off & 31));
+    }
+#pragma unroll
+    for (int b = 0; b < CB; ++b) cp[b] = (uint8_t)(w[b >> 2] >> (8 * (b & 3)));
+}
+
 // MODE 0: write the packed planes.  MODE 1: write the dequantized tensor.
 // CONTIG (FP32, pitch = row length): the tensor side moves as contiguous 1 KiB
 // wave rows through LDS like in the MX kernels.  The planes of a workgroup's 2048
@@ -426,13 +441,19 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     uint8_t *ls = reinterpret_cast<uint8_t *>(s_sexp);
     const int lk1 = __builtin_ctz(f.k1);
     if (active) {
-        // 8 codes of cb <= 9 bits: 64 bits plus, for cb = 9, one more byte
-        uint64_t w = 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) w |= (uint64_t)code[i] << (i * cb);
-        const uint32_t extra = code[7] >> 1;
+        // 8 codes of cb <= 9 bits: cb bytes; the code width is dispatched once so that
+        // all shifts are immediate
         uint8_t *cp = lc + cb * threadIdx.x;
-        for (int b = 0; b < cb; ++b) cp[b] = b < 8 ? (uint8_t)(w >> (8 * b)) : (uint8_t)extra;
+        switch (cb) {
+        case 2: pack_codes<2>(code, cp); break;
+        case 3: pack_codes<3>(code, cp); break;
+        case 4: pack_codes<4>(code, cp); break;
+        case 5: pack_codes<5>(code, cp); break;
+        case 6: pack_codes<6>(code, cp); break;
+        case 7: pack_codes<7>(code, cp); break;
+        case 8: pack_codes<8>(code, cp); break;
+        default: pack_codes<9>(code, cp); break;
+        }
 
         if (f.k1 >= 8) {
             const int lanes = f.k1 / 8;
