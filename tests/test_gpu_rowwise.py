@@ -168,3 +168,34 @@ def test_bandwidth_config_full_size_sampled_rows():
         sat = y.abs() >= (2.0 - 2.0 ** (1 - f.m)) * torch.exp2(se - 127).repeat_interleave(16, dim=1)
         assert torch.all(((x - y).abs() <= bound) | sat), name
         del planes, y, p2, se, bound, sat
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_more_than_four_gibi_elements(dtype):
+    # 2^32 + 2^18 elements: every element index, byte offset and plane offset passes 2^32.
+    # Row bands around the 2^31 and 2^32 element marks and at both ends go through the oracle.
+    cols = 4096
+    rows = (1 << 20) + 64
+    g = torch.Generator(device="cuda").manual_seed(77)
+    x = torch.empty(rows, cols, dtype=dtype, device="cuda")
+    step = 1 << 16
+    for r in range(0, rows, step):                       # filled in pieces to bound temporaries
+        n = min(step, rows - r)
+        x[r:r + n] = (torch.randn(n, cols, generator=g, device="cuda") * 0.3).to(dtype)
+    f = B.MX6
+    planes = B.bdr_quantize(f, x)
+    y = B.bdr_dequantize(f, planes, rows, cols, dtype=dtype)
+    y2 = B.bdr_quantize_dequantize(f, x)
+    torch.cuda.synchronize()
+    per_row = [cols * 5 // 8, cols // 16, cols // 16]
+    out_dtype = np.float32 if dtype == torch.float32 else np.uint16
+    for r0 in (0, (1 << 19) - 8, (1 << 20) - 8, rows - 16):
+        sub = x[r0:r0 + 16]
+        want = O.quantize(ofmt(f), to_np(sub))
+        got = [p[r0 * n:(r0 + 16) * n] for p, n in zip(planes, per_row)]
+        assert_planes_equal(got, want, "rows %d.." % r0)
+        ywant = O.dequantize(ofmt(f), *want, 16, cols, out_dtype=out_dtype)
+        assert_bits_equal(y[r0:r0 + 16], ywant, "dequantize rows %d.." % r0)
+        assert_bits_equal(y2[r0:r0 + 16], ywant, "fused rows %d.." % r0)
+    itype = torch.int32 if dtype == torch.float32 else torch.int16
+    assert torch.equal(y.view(itype), y2.view(itype))
