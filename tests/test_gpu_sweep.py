@@ -117,3 +117,17 @@ def test_full_size_sweep_properties_and_sampled_formats():
     # run twice: bit-identical (fixed-order reduction)
     q2, s2b = B.bdr_qsnr_sweep(fmts, x)
     assert np.array_equal(q2.cpu().numpy(), q) and np.array_equal(s2b.cpu().numpy(), s)
+
+
+def test_large_tensor_by_repetition():
+    # 2^30 elements made of 64 copies of a 2^24-element tensor: every sum must be 64 times the
+    # base tensor's (up to the order of the FP64 additions) and every QSNR the same
+    base = S.sweep(device="cuda")
+    fmts = sweep64()[::5] + [B.fmt(256, 4, 2, 5, rounding=B.RNA)]
+    qb, sb = B.bdr_qsnr_sweep(fmts, base)
+    big = base.repeat(64, 1)
+    assert big.numel() == 1 << 30
+    q, s = B.bdr_qsnr_sweep(fmts, big)
+    torch.cuda.synchronize()
+    assert np.allclose(s.cpu().numpy(), 64.0 * sb.cpu().numpy(), rtol=1e-6)
+    assert np.allclose(q.cpu().numpy(), qb.cpu().numpy(), rtol=1e-7)
