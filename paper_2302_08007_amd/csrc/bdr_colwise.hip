@@ -5,7 +5,8 @@
 // axis, and quantizing does not commute with transposing (Sec. V, "Training").
 // The result here is defined as the row-wise result on the transposed tensor,
 // plane indices included, but the transpose is never materialized: a workgroup
-// brings a 128-row tile (64 FP32 or 128 BF16 columns, 32 KiB) into LDS with row-contiguous 16-byte loads,
+// brings a 128-row tile (64 FP32 or 128 BF16 columns, 32 KiB) into LDS with
+// row-contiguous 16-byte loads,
 // each lane then reads one 16-row block of one column out of LDS, quantizes it
 // entirely in registers (the block is in one lane, so no cross-lane reduction is
 // needed), and the eight lanes that hold the eight consecutive blocks of one
