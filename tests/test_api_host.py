@@ -173,3 +173,27 @@ def test_gather_argument_checks():
     assert ga(idx=NULL) == ERR_NULL and ga(y=NULL) == ERR_NULL and ga(codes=NULL) == ERR_NULL
     assert ga(idx=FAKE_ODD) == ERR_ALIGN and ga(y=FAKE_ODD) == ERR_ALIGN
     assert ga(n=0) == OK
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, and a C caller must
+    # be able to name every entry point and build a format from the macros
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "bdr_mx.h"\n'
+        "static const bdr_format mx9 = BDR_FORMAT_MX9, mx6 = BDR_FORMAT_MX6, mx4 = BDR_FORMAT_MX4;\n"
+        "int probe(void) {\n"
+        "    size_t a, b, c;\n"
+        "    void *fns[] = {(void *)bdr_status_string, (void *)bdr_format_validate, (void *)bdr_packed_sizes,\n"
+        "                   (void *)bdr_quantize, (void *)bdr_dequantize, (void *)bdr_gather_dequantize,\n"
+        "                   (void *)bdr_tile_packing, (void *)bdr_quantize_dequantize,\n"
+        "                   (void *)bdr_qsnr_sweep_workspace_bytes, (void *)bdr_qsnr_sweep,\n"
+        "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm};\n"
+        "    (void)fns;\n"
+        "    return bdr_packed_sizes(&mx9, 4, 64, BDR_AXIS_ROW, &a, &b, &c) + mx6.m + mx4.m;\n"
+        "}\n")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-Wno-pedantic", "-I",
+                        os.path.join(ROOT, "include"), "-c", str(src), "-o", str(tmp_path / "use_header.o")],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr

@@ -199,3 +199,22 @@ def test_more_than_four_gibi_elements(dtype):
         assert_bits_equal(y2[r0:r0 + 16], ywant, "fused rows %d.." % r0)
     itype = torch.int32 if dtype == torch.float32 else torch.int16
     assert torch.equal(y.view(itype), y2.view(itype))
+
+
+def test_work_goes_to_the_callers_stream():
+    # the library enqueues on the stream it is handed and never synchronizes: work issued on a
+    # side stream behind a long-running kernel must not have run before that stream is waited for
+    f = B.MX6
+    x = S.tiny(device="cuda")
+    want = O.quantize(ofmt(f), to_np(x))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    big = torch.empty(1 << 28, device="cuda")
+    with torch.cuda.stream(side):
+        for _ in range(20):
+            big.normal_()                                 # keeps the side stream busy for a while
+        planes = B.bdr_quantize(f, x)
+        y = B.bdr_dequantize(f, planes, *x.shape)
+    side.synchronize()
+    assert_planes_equal(planes, want, "side stream")
+    assert_bits_equal(y, O.dequantize(ofmt(f), *want, *x.shape), "side stream dequantize")
