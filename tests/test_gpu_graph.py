@@ -1,0 +1,56 @@
+"""The library allocates nothing, clears nothing with memset and never synchronizes, so a
+sequence of its calls can be captured in a HIP graph and replayed.  Every replay, with the
+program's own eager work and synchronizations in between, is checked against the eager result."""
+import pytest
+import torch
+
+import paper_2302_08007_amd as B
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+
+def test_calls_replay_from_a_graph():
+    f = B.MX6
+    rows, cols = 512, 2048
+    M = N = 256
+    x = torch.zeros(rows, cols, device="cuda")
+    planes = B.alloc_planes(f, rows, cols)
+    y = torch.empty_like(x)
+    yf = torch.empty_like(x)
+    fmts = [B.MX9, B.MX6, B.MX4, B.fmt(32, 4, 2, 3)]
+    ws = torch.empty(B.lib.bdr_qsnr_sweep_workspace_bytes(len(fmts)), dtype=torch.uint8, device="cuda")
+    out = (torch.empty(len(fmts), dtype=torch.float64, device="cuda"),
+           torch.empty(len(fmts) + 1, dtype=torch.float64, device="cuda"))
+    pa = B.alloc_planes(f, M, cols)
+    C = torch.empty(M, N, device="cuda")
+    gws = torch.empty(B.mx_gemm_workspace_bytes(M, N, cols), dtype=torch.uint8, device="cuda")
+
+    def work():
+        B.bdr_quantize(f, x, out=planes)
+        B.bdr_dequantize(f, planes, rows, cols, out=y)
+        B.bdr_quantize_dequantize(f, x, out=yf)
+        B.bdr_qsnr_sweep(fmts, x, workspace=ws, out=out)
+        B.bdr_quantize(f, x[:M], out=pa)
+        B.mx_gemm(f, f, pa, pa, M, N, cols, out=C, workspace=gws)
+
+    x.copy_(S.wide_range(rows, cols, device="cuda", seed=0, spread=3))
+    work()                      # first use outside the capture (one-time kernel attributes)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    for seed in (1, 2, 3):
+        x.copy_(S.wide_range(rows, cols, device="cuda", seed=seed, spread=3))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (*planes, y, yf, out[0], out[1], C)]
+        for t in (*planes, y, yf, out[0], out[1], C):
+            t.zero_()           # eager work of the program between replays
+        work()
+        torch.cuda.synchronize()
+        want = (*planes, y, yf, out[0], out[1], C)
+        for a, b in zip(got, want):
+            a = a.view(torch.uint8) if a.dtype != torch.uint8 else a
+            b = b.view(torch.uint8) if b.dtype != torch.uint8 else b
+            assert torch.equal(a, b), seed
