@@ -1,0 +1,135 @@
+"""Property tests of the CPU oracle on generated formats and data (hypothesis, fixed seed via
+derandomize): the invariants the paper and the arithmetic fix, each written without calling the
+function under test in the expected value."""
+import math
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import oracle as O
+
+SET = settings(max_examples=60, deadline=None, derandomize=True)
+
+
+@st.composite
+def formats(draw, max_lk1=6):
+    lk1 = draw(st.integers(0, max_lk1))
+    lk2 = draw(st.integers(0, lk1))
+    return O.fmt(1 << lk1, 1 << lk2, draw(st.integers(0, 3)), draw(st.integers(1, 8)),
+                 rounding=draw(st.integers(0, 2)))
+
+
+@st.composite
+def tensors(draw, f):
+    rows = draw(st.integers(1, 4))
+    nblk = draw(st.integers(1, 4))
+    seed = draw(st.integers(0, 2 ** 31 - 1))
+    spread = draw(st.integers(0, 30))
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, nblk * max(f.k1, 1))) * np.exp2(rng.integers(-spread, spread + 1, (rows, 1)))
+    x = x * np.exp2(rng.integers(-3, 4, x.shape))
+    x[rng.random(x.shape) < 0.05] = 0.0
+    return x.astype(np.float32)
+
+
+@SET
+@given(st.data())
+def test_decode_of_every_element_matches_the_value_formula(data):
+    # value = (-1)^s * M * 2^(E - tau - (m - 1)) with the planes read back by hand (Sec. IX)
+    f = data.draw(formats())
+    x = data.draw(tensors(f))
+    rows, cols = x.shape
+    codes, sexp, mexp = O.quantize(f, x)
+    y = O.dequantize(f, codes, sexp, mexp, rows, cols)
+    bits = np.unpackbits(codes, bitorder="little")
+    mb = np.unpackbits(mexp, bitorder="little") if f.d2 else None
+    for t in range(rows * cols):
+        c = int(sum(int(bits[t * (f.m + 1) + k]) << k for k in range(f.m + 1)))
+        mag, sgn = c & ((1 << f.m) - 1), c >> f.m
+        se = int(sexp[t // f.k1])
+        tau = int(sum(int(mb[(t // f.k2) * f.d2 + k]) << k for k in range(f.d2))) if f.d2 else 0
+        want = math.ldexp(mag, se - 127 - tau - (f.m - 1)) * (-1.0 if sgn else 1.0)
+        assert y.reshape(-1)[t] == np.float32(want)
+        assert math.copysign(1.0, y.reshape(-1)[t]) == (-1.0 if sgn else 1.0)
+
+
+@SET
+@given(st.data())
+def test_error_bound_and_shift_rule(data):
+    # per element |x - Q(x)| <= 2^(E - tau - m) unless the magnitude saturated (nearest rounding;
+    # twice that for truncation), tau = min(beta, E - E_sub) with exponents taken via frexp
+    f = data.draw(formats())
+    x = data.draw(tensors(f))
+    rows, cols = x.shape
+    codes, sexp, mexp = O.quantize(f, x)
+    y = O.dequantize(f, codes, sexp, mexp, rows, cols).astype(np.float64)
+    xd = x.astype(np.float64)
+    beta = (1 << f.d2) - 1
+    mb = np.unpackbits(mexp, bitorder="little") if f.d2 else None
+    flat = np.abs(xd).reshape(-1)
+
+    def expo(v):  # exponent field the quantizer sees: floor(log2 v) + 127 held in [1, 254]
+        if v == 0.0:
+            return 1
+        return min(254, max(1, math.frexp(v)[1] - 1 + 127))
+
+    for b in range(rows * cols // f.k1):
+        blk = flat[b * f.k1:(b + 1) * f.k1]
+        E = expo(blk.max())
+        assert int(sexp[b]) == E
+        for s in range(f.k1 // f.k2):
+            sub = blk[s * f.k2:(s + 1) * f.k2]
+            u = b * (f.k1 // f.k2) + s
+            tau = int(sum(int(mb[u * f.d2 + k]) << k for k in range(f.d2))) if f.d2 else 0
+            assert tau == min(beta, E - expo(sub.max()))
+            step = math.ldexp(1.0, E - 127 - tau - (f.m - 1))
+            top = ((1 << f.m) - 1) * step
+            for i in range(f.k2):
+                t = b * f.k1 + s * f.k2 + i
+                e = abs(y.reshape(-1)[t] - xd.reshape(-1)[t])
+                if abs(y.reshape(-1)[t]) == top and flat[t] > top:
+                    continue                      # saturated at the top code
+                assert e <= (step if f.rounding == O.RTZ else step / 2) * (1 + 1e-12)
+
+
+@SET
+@given(st.data())
+def test_symmetries(data):
+    f = data.draw(formats())
+    x = data.draw(tensors(f))
+    rows, cols = x.shape
+    p = O.quantize(f, x)
+    y = O.dequantize(f, *p, rows, cols)
+    # Q(Q(x)) = Q(x), bit for bit
+    p2 = O.quantize(f, y)
+    assert all(np.array_equal(a, b) for a, b in zip(p, p2))
+    # Q(-x) = -Q(x): only the sign bits of the codes change
+    yn = O.quantize_dequantize(f, -x)
+    assert np.array_equal(yn.view(np.uint32), (-y).view(np.uint32))
+    # Q(2^j x) = 2^j Q(x) while every exponent stays inside the normal range
+    j = data.draw(st.integers(-20, 20))
+    nz = np.abs(x[x != 0])
+    if nz.size and math.frexp(float(nz.min()))[1] + j > -120 and math.frexp(float(nz.max()))[1] + j < 120:
+        ys = O.quantize_dequantize(f, np.ldexp(x, j).astype(np.float32))
+        assert np.array_equal(ys, np.ldexp(y, j).astype(np.float32))
+
+
+@SET
+@given(st.data())
+def test_theorem1_lower_bound(data):
+    # QSNR >= 6.02 m + 10 log10(2^(2 beta) / (min(N, k1) + (2^(2 beta) - 1) k2)) for nearest rounding
+    # on blocks without a saturated element; checked per tensor with N = row length
+    f = data.draw(formats(max_lk1=5))
+    if f.rounding == O.RTZ:
+        f.rounding = O.RNE
+    seed = data.draw(st.integers(0, 2 ** 31 - 1))
+    rng = np.random.default_rng(seed)
+    cols = max(f.k1, 1) * 8
+    x = (rng.standard_normal((64, cols)) * np.exp2(rng.integers(-6, 7, (64, 1)))).astype(np.float32)
+    q, sums = O.qsnr_sweep([f], x)
+    beta = (1 << f.d2) - 1
+    bound = 6.02 * f.m + 10 * math.log10(4.0 ** beta / (min(cols, f.k1) + (4.0 ** beta - 1) * f.k2))
+    # elements that round up into the top code are held there (reading R3) and may miss the
+    # per-element bound by one step; the aggregate bound has 6.02 (< 20 log10 2) of slack per bit
+    assert q[0] >= bound - 1.0
