@@ -144,14 +144,18 @@ int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dt
                    size_t workspace_bytes, void *hip_stream);
 
 /* Host only.  Bytes of device workspace with which mx_gemm runs in its two-pass
- * form: (M + N) * K BF16 values, each operand rounded up to 256 bytes.  0 when a
- * size is negative or above 2^20. */
+ * form: (M + N) * K BF16 values, each operand rounded up to 256 bytes (the FP6 block
+ * images need half of that).  0 when a size is negative or above 2^20. */
 size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /* C = Ahat * Bhat^T in FP32, where Ahat [M x K] and Bhat [N x K] are the values of
  * two packed images blocked along K (Sec. V: both inputs of a tensor operation are
- * MX-quantized, along the reduction dimension).  Operands are expanded exactly to
- * BF16 and accumulated in FP32 by the matrix cores.
+ * MX-quantized, along the reduction dimension).  Operands are brought, exactly, to a
+ * form the matrix cores take and the products are accumulated in FP32: BF16 (8
+ * significant bits hold any MX element), or, in the two-pass form when both formats
+ * have m <= 4 and K is a multiple of 128, FP6 elements under one power-of-two scale
+ * per block of 16 (M 2^-tau has at most 4 significant bits over 5 binades, which
+ * sign + 2 exponent + 3 fraction bits hold), at twice the BF16 rate.
  *   fa, fb : formats of A and B, each one of Table II's family (k1 16, d1 8, k2 2,
  *            d2 1, m 7, 4 or 2, any rounding: it plays no part here), else
  *            BDR_ERR_FORMAT; the two may differ
@@ -161,15 +165,18 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *            fully overwritten
  *   workspace : device, 16-byte aligned, or NULL.  With at least
  *            mx_gemm_workspace_bytes(M, N, K) bytes (less is BDR_ERR_WORKSPACE) each
- *            operand is expanded once into it and a BF16 kernel does the products
- *            (the faster form: 1.7x at 8192^3); it is scratch, overwritten, and
- *            calls that share it must be ordered on one stream.  With NULL the
- *            expansion happens inside the GEMM kernel, once per tile of C, and no
- *            memory beyond the arguments is touched.  Both forms give the same bits.
+ *            operand is rewritten once into it (as BF16 or as FP6 blocks) and a plain
+ *            GEMM kernel does the products (the faster form: 2.6x at 8192^3 for
+ *            MX6); it is scratch, overwritten, and calls that share it must be
+ *            ordered on one stream.  With NULL the expansion to BF16 happens inside
+ *            the GEMM kernel, once per tile of C, and no memory beyond the arguments
+ *            is touched.  Every product is exact in all forms; the forms differ only
+ *            in where the FP32 sum over K is rounded (the BF16 forms give the same
+ *            bits as each other).
  * M and N must be multiples of 128 and K a multiple of 64, each at most 2^20, else
  * BDR_ERR_SHAPE.  M = 0 or N = 0 launches nothing; K = 0 writes zeros.  Inf/NaN
- * codes and blocks whose exponent code is so low that an element is a BF16
- * subnormal are outside the supported domain. */
+ * codes, blocks whose exponent code is so low that an element is a BF16
+ * subnormal, and sums that are FP32 subnormals are outside the supported domain. */
 int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
             const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,

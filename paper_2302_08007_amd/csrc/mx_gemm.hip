@@ -21,6 +21,8 @@
 // conditional shift and fixed-point accumulation): that design targets a custom
 // datapath.  On gfx950 the matrix cores take BF16, so the operands are brought to
 // BF16 and the hardware does the rest.
+#include <type_traits>
+
 #include "bdr_device.hpp"
 #include "bdr_internal.hpp"
 
@@ -42,6 +44,8 @@ __device__ __forceinline__ int lds_chunk(int row, int chunk)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
@@ -266,6 +270,73 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
         }
 }
 
+// The block-scaled FP6 MFMA of gfx950 multiplies E2M3 elements (sign, 2 exponent bits,
+// 3 fraction bits: m / 8 for exponent field 0, else (1 + m / 8) 2^(e - 1)) and applies
+// one power-of-two scale (a byte b meaning 2^(b - 127)) per lane, i.e. per 32 elements of
+// K.  An MX6 or MX4 element is +-M 2^(SE - 127 - tau - (m - 1)) with M < 2^m, tau <= 1
+// (Sec. III): M 2^-tau has at most 4 significant bits and spans 5 binades, which E2M3
+// holds exactly, and the rest is a power of two per block of 16 that fits the scale
+// byte.  The hardware block is 32 long and k1 is 16, so each lane gets one block in the
+// lower half of its 32 values and zeros in the upper half.
+//
+// This kernel rewrites the three planes of an operand as one 16-byte chunk per block:
+// dwords 0-2 hold the 16 FP6 codes (element j at bits 6 j .. 6 j + 5), dword 3 holds
+// the scale byte.  The MFMA reads dword 3 both as the scale operand and as elements
+// 16 .. 21 of the lane (which must contribute nothing): an A operand keeps its scale in
+// byte 0 (bits of elements 16, 17), a B operand in byte 2 (elements 18, 19), so each
+// of those products has a zero factor.  FP6 has no infinities or NaNs, so 0 * x = 0.
+//   MX6: element = (M << (2 - tau - z)) / 8, scale byte = SE - 2 + z, z = (SE == 1)
+//        (the top binade of E2M3 is needed for M = 15, tau = 0, which leaves SE - 2; a
+//        block with SE = 1 moves its elements one binade down instead, still exact)
+//   MX4: element = (M << (3 - tau)) / 8,     scale byte = SE - 1
+constexpr int kFp6 = 2;  // operand format selector of the f8f6f4 MFMA: E2M3
+constexpr int kScaleByteA = 0, kScaleByteB = 2;
+
+template <int MB, bool B_OPERAND>
+__global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restrict__ codes,
+                                                        const uint8_t *__restrict__ sexp,
+                                                        const uint8_t *__restrict__ mexp,
+                                                        int64_t n_pairs, u32x4 *__restrict__ out)
+{
+    static_assert(MB == 4 || MB == 2, "MX6 or MX4");
+    constexpr int CB = MB + 1;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;  // two blocks per thread
+    if (p >= n_pairs) return;
+    Packed<MB> pk;
+    load_packed<MB>(codes, sexp, mexp, 2 * p, pk);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int se = (int)((pk.se2 >> (8 * b)) & 0xffu);
+        const int z = (MB == 4 && se == 1) ? 1 : 0;
+        const int scale = MB == 4 ? se - 2 + z : se - 1;
+        uint32_t w[3] = {0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int off = (16 * b + j) * CB;
+            const int k = off >> 5;
+            int sh = off & 31;
+            uint32_t win = pk.c[k];
+            if (sh + CB > 32) {  // the code straddles two words
+                win = funnel_r(pk.c[(k + 1) % CB], pk.c[k], sh);
+                sh = 0;
+            }
+            const uint32_t code = win >> sh;
+            const uint32_t mag = code & ((1u << MB) - 1u), sign = (code >> MB) & 1u;
+            const int tau = (int)((pk.tau16 >> (8 * b + (j >> 1))) & 1u);
+            const uint32_t u = mag << ((MB == 4 ? 2 : 3) - tau - z);  // element = u / 8, u <= 60
+            // u >= 8: FP32 of u has exponent field 127 + p (p = 3 .. 5) and u's next three
+            // bits on top of its fraction; E2M3 wants exponent field p - 2 and those bits
+            const uint32_t em = u < 8u ? u : (as_u((float)u) >> 20) - ((127u + 2u) << 3);
+            const uint32_t c6 = (sign << 5) | em;
+            const int bit = 6 * j;
+            w[bit >> 5] |= c6 << (bit & 31);
+            if ((bit & 31) + 6 > 32) w[(bit >> 5) + 1] |= c6 >> (32 - (bit & 31));
+        }
+        const u32x4 chunk = {w[0], w[1], w[2], (uint32_t)scale << (B_OPERAND ? 8 * kScaleByteB : 8 * kScaleByteA)};
+        out[2 * p + b] = chunk;
+    }
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane p's data lands at
 // byte 16 p after `lds_block` (which must be the same for the whole wave).
 __device__ __forceinline__ void global_to_lds16(const void *src, void *lds_block)
@@ -286,16 +357,23 @@ __device__ __forceinline__ void global_to_lds16(const void *src, void *lds_block
 // block, i.e. chunk (p & 7) ^ swizzle of row p / 8.  No staging registers and no
 // LDS write instructions; the loads of step kt+1 are issued before the MFMAs of
 // step kt, and the fragment reads of sub-step s+1 before the MFMAs of sub-step s.
-template <int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(64 * WM * WN) void bf16_gemm_dl_kernel(
-    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int N, int K,
+//
+// With FP6 set the operands are FP6 block images instead (see mx_to_fp6_kernel): a
+// 16-byte chunk is then one block of 16 elements, a row of the tile 8 blocks = 128
+// elements of K, and each 32 x 32 x 16 BF16 MFMA becomes one block-scaled FP6 MFMA
+// over two blocks.  Addresses, swizzle and schedule are the same, byte for byte;
+// `pitch` is the length of an operand row in 2-byte units (K, or K / 2 for FP6).
+template <int WM, int WN, int TM, int TN, bool FP6>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int N, int pitch,
     float *__restrict__ C, int64_t ldc)
 {
+    const int K = pitch;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int NW = WM * WN;
     constexpr int A_BYTES = BM * kPitch, B_BYTES = BN * kPitch;
     constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // 8-row blocks per wave and K step
-    static_assert(LA >= 1 && LB >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile");
+    static_assert(LA >= 1 && LB >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TM % 2 == 0, "tile");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B]
 
     const int ntm = M / BM, ntn = N / BN, total = ntm * ntn;
@@ -348,22 +426,42 @@ __global__ __launch_bounds__(64 * WM * WN) void bf16_gemm_dl_kernel(
         }
     };
     const int f_row = lane & 31, f_half = lane >> 5;
-    auto read_frags = [&](const uint8_t *cur, int sub, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+    // A fragment is the 16 bytes of one chunk.  The FP6 MFMA takes six registers per
+    // operand, of which the upper two stay zero for the whole kernel: the fragment
+    // variables are eight wide and a read replaces only their lower half.
+    using Frag = typename std::conditional<FP6, i32x8, u32x4>::type;
+    auto read_frag = [&](const uint8_t *p, Frag &f) {
+        if constexpr (FP6) {
+            const i32x4 v = *reinterpret_cast<const i32x4 *>(p);
+            const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 2, 3, 0, 1, 2, 3);
+            f = __builtin_shufflevector(wide, f, 0, 1, 2, 3, 12, 13, 14, 15);
+        } else {
+            f = *reinterpret_cast<const u32x4 *>(p);
+        }
+    };
+    auto read_frags = [&](const uint8_t *cur, int sub, Frag (&fa)[TM], Frag (&fb)[TN]) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            fa[i] = *reinterpret_cast<const bf16x8 *>(
-                cur + lds_chunk((wm * TM + i) * 32 + f_row, 2 * sub + f_half));
+            read_frag(cur + lds_chunk((wm * TM + i) * 32 + f_row, 2 * sub + f_half), fa[i]);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            fb[j] = *reinterpret_cast<const bf16x8 *>(
-                cur + A_BYTES + lds_chunk((wn * TN + j) * 32 + f_row, 2 * sub + f_half));
+            read_frag(cur + A_BYTES + lds_chunk((wn * TN + j) * 32 + f_row, 2 * sub + f_half), fb[j]);
     };
-    auto mfmas = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+    auto mfmas = [&](const Frag (&fa)[TM], const Frag (&fb)[TN], int half) {  // half of the tiles
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = half * (TM / 2); i < (half + 1) * (TM / 2); ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (FP6) {
+                    // lane l: row l % 32, K values 32 (l / 32) .. +31 of the 64, of which the
+                    // upper 16 are zero; one scale byte per lane, taken from the chunk itself
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fa[i], fb[j], acc[i][j], kFp6, kFp6, kScaleByteA, fa[i][3], kScaleByteB, fb[j][3]);
+                } else {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
+                }
+            }
     };
     static_assert(kBK == 64, "the schedule below is written for four sub-steps per K step");
     // Schedule of one K step (cur holds step kt, nxt is being filled with step kt+1,
@@ -376,36 +474,58 @@ __global__ __launch_bounds__(64 * WM * WN) void bf16_gemm_dl_kernel(
     // The barrier thus costs neither a fragment-read latency nor a load latency: both
     // have a whole K step (loads) or eight MFMAs (reads) to arrive.
     uint8_t *cur = smem, *nxt = smem + A_BYTES + B_BYTES;
-    bf16x8 fa[2][TM], fb[2][TN];
+    Frag fa[2][TM], fb[2][TN];
+    if constexpr (FP6) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[h][i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[h][j] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
     fill(cur);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (nk > 1) fill(nxt);
     read_frags(cur, 0, fa[0], fb[0]);
-    for (int kt = 0; kt < nk; ++kt) {
+    // One K step.  The last two steps have nothing left to fill or to read ahead; they are
+    // peeled so that the body of the steady-state loop is one straight block.
+    auto k_step = [&](auto do_fill, auto do_read) {
+        mfmas(fa[0], fb[0], 0);
+        __builtin_amdgcn_sched_barrier(0);
         read_frags(cur, 1, fa[1], fb[1]);
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[0], fb[0]);
+        mfmas(fa[0], fb[0], 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[1], fb[1], 0);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(cur, 2, fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[1], fb[1]);
+        mfmas(fa[1], fb[1], 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[0], fb[0], 0);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(cur, 3, fa[1], fb[1]);
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[0], fb[0]);
+        mfmas(fa[0], fb[0], 1);
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (kt + 2 < nk) fill(cur);
-        if (kt + 1 < nk) read_frags(nxt, 0, fa[0], fb[0]);
+        mfmas(fa[1], fb[1], 0);
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[1], fb[1]);
+        if constexpr (decltype(do_fill)::value) fill(cur);
+        if constexpr (decltype(do_read)::value) read_frags(nxt, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(fa[1], fb[1], 1);
         __builtin_amdgcn_sched_barrier(0);
         uint8_t *t2 = cur;
         cur = nxt;
         nxt = t2;
-    }
+    };
+    for (int kt = 0; kt + 2 < nk; ++kt) k_step(std::true_type{}, std::true_type{});
+    if (nk > 1) k_step(std::false_type{}, std::true_type{});
+    k_step(std::false_type{}, std::false_type{});
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -454,19 +574,31 @@ int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, cons
     return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
 }
 
-template <int WM, int WN, int TM, int TN>
-int launch_bf16(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *C, int64_t ldc,
-                hipStream_t s)
+template <int WM, int WN, int TM, int TN, bool FP6>
+int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int pitch, float *C, int64_t ldc,
+              hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t kLds = 2 * (BM + BN) * (size_t)kPitch;
     static signed char granted[kMaxDevices];
     if (kLds > 64 * 1024 &&
-        !grant_dynamic_lds(reinterpret_cast<const void *>(&bf16_gemm_dl_kernel<WM, WN, TM, TN>), kLds, granted))
+        !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN, FP6>), kLds, granted))
         return BDR_ERR_LAUNCH;
-    hipLaunchKernelGGL((bf16_gemm_dl_kernel<WM, WN, TM, TN>), dim3((unsigned)((M / BM) * (N / BN))),
-                       dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc);
+    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN, FP6>), dim3((unsigned)((M / BM) * (N / BN))),
+                       dim3(64 * WM * WN), kLds, s, A, B, M, N, pitch, C, ldc);
     return launch_status();
+}
+
+template <bool FP6>
+int gemm_dl(const void *A, const void *B, int64_t M, int64_t N, int pitch, float *C, int64_t ldc,
+            hipStream_t s)
+{
+    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+    if (M % 256 == 0 && N % 256 == 0) {
+        const int st = launch_dl<2, 4, 4, 2, FP6>(a, b, (int)M, (int)N, pitch, C, ldc, s);
+        if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
+    }
+    return launch_dl<2, 2, 2, 2, FP6>(a, b, (int)M, (int)N, pitch, C, ldc, s);
 }
 
 __global__ void gemm_zero_kernel(float *C, int64_t ldc, int N)
@@ -498,12 +630,33 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
 int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
               hipStream_t s)
 {
-    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
-    if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_bf16<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
-        if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
+    return gemm_dl<false>(A, B, M, N, (int)K, C, ldc, s);
+}
+
+// C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 128 == 0.
+int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+             hipStream_t s)
+{
+    return gemm_dl<true>(A, B, M, N, (int)(K / 2), C, ldc, s);
+}
+
+// Packed MX6 or MX4 planes of n_blocks blocks (an even number) -> n_blocks 16-byte chunks.
+int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
+           int64_t n_blocks, void *out, bool b_operand, hipStream_t s)
+{
+    if (n_blocks == 0) return BDR_OK;
+    const uint8_t *c = (const uint8_t *)codes, *e = (const uint8_t *)sexp, *m = (const uint8_t *)mexp;
+    const int64_t pairs = n_blocks / 2;
+    const dim3 grid((unsigned)((pairs + 255) / 256)), block(256);
+    u32x4 *o = (u32x4 *)out;
+    if (f.m == 4) {
+        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<4, true>), grid, block, 0, s, c, e, m, pairs, o);
+        else hipLaunchKernelGGL((mx_to_fp6_kernel<4, false>), grid, block, 0, s, c, e, m, pairs, o);
+    } else {
+        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<2, true>), grid, block, 0, s, c, e, m, pairs, o);
+        else hipLaunchKernelGGL((mx_to_fp6_kernel<2, false>), grid, block, 0, s, c, e, m, pairs, o);
     }
-    return launch_bf16<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
+    return launch_status();
 }
 
 }  // namespace bdr
