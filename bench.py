@@ -81,7 +81,7 @@ def main():
                     help="run a 1 GiB tensor copy and one launch of each row-wise MX kernel, "
                          "three times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--other-probe", action="store_true",
-                    help="run mx_gemm (both forms, 8192^3 MX6) and the 64-format sweep a few times and "
+                    help="run mx_gemm (both forms, 8192^3, MX6 and MX9) and the 64-format sweep a few times and "
                          "exit (for rocprofv3 --pmc MfmaUtil VALUBusy)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -133,6 +133,9 @@ def main():
             B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C, workspace=ws)
         for i in range(5):
             B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C)
+        pa, pb = B.bdr_quantize(B.MX9, A), B.bdr_quantize(B.MX9, Bm)
+        for i in range(10):  # MX9: the BF16 product kernel
+            B.mx_gemm(B.MX9, B.MX9, pa, pb, M, N, K, out=C, workspace=ws)
         xs = S.sweep(device="cuda")
         fmts = [B.fmt(k1, k1 if k2 == 0 else k2, d2, m) for k1 in (8, 16, 32, 64)
                 for k2 in (1, 2, 4, 0) for d2 in (0, 1) for m in (2, 4)]
@@ -140,7 +143,8 @@ def main():
         for i in range(5):
             B.bdr_qsnr_sweep(fmts, xs, workspace=wsw)
         torch.cuda.synchronize()
-        print(json.dumps({"other_probe": "45 x two-pass mx_gemm, 5 x single-kernel mx_gemm, 5 x 64-format sweep"}))
+        print(json.dumps({"other_probe": "45 x two-pass MX6 mx_gemm, 5 x single-kernel MX6 mx_gemm, "
+                                         "10 x two-pass MX9 mx_gemm, 5 x 64-format sweep"}))
         return
 
     if args.pmc_probe:
@@ -298,15 +302,28 @@ def other_legs(B, S, torch, timed):
         C = torch.empty(M, N, device="cuda")
         ws = torch.empty(B.mx_gemm_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
         leg = {}
-        # two-pass form (operands expanded once to BF16 in a workspace) and single-kernel form
-        for name, w in (("two_pass", ws), ("single_kernel", None)):
+        # two-pass form (MX6: operands rewritten once as block-scaled FP6, FP6 matrix instructions
+        # with one block of 16 per 32-wide hardware block, so at most half of the FP6 peak) and
+        # single-kernel form (BF16 in LDS, BF16 matrix instructions)
+        for name, w, peak, key in (("two_pass", ws, 10100.0, "frac_of_fp6_mfma_peak_10100"),
+                                   ("single_kernel", None, 2500.0, "frac_of_bf16_mfma_peak_2500")):
             # matrix-core clocks take about 30 ms of load to settle: 40 untimed calls first
             t = timed(lambda: B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C, workspace=w),
                       reps=5, inner=4, warm=40)
             tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
-            leg[name] = {"ms": round(t, 3), "TFLOPs": round(tf, 1),
-                         "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4)}
+            leg[name] = {"ms": round(t, 3), "TFLOPs": round(tf, 1), key: round(tf / peak, 4)}
+        leg["two_pass"]["matrix_instruction"] = "fp6 block-scaled, 16 of 32 K positions used"
+        leg["single_kernel"]["matrix_instruction"] = "bf16"
         out["mx_gemm_8192_MX6"] = leg
+        # MX9 needs 8 significant bits: the two-pass form expands to BF16
+        p9a, p9b = B.bdr_quantize(B.MX9, A), B.bdr_quantize(B.MX9, Bm)
+        t = timed(lambda: B.mx_gemm(B.MX9, B.MX9, p9a, p9b, M, N, K, out=C, workspace=ws),
+                  reps=5, inner=4, warm=40)
+        tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
+        out["mx_gemm_8192_MX9"] = {"two_pass": {"ms": round(t, 3), "TFLOPs": round(tf, 1),
+                                                "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4),
+                                                "matrix_instruction": "bf16"}}
+        del p9a, p9b
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
     try:
