@@ -353,14 +353,16 @@ def other_legs(B, S, torch, timed):
         w = (torch.randn(Osz, I, generator=g, device="cuda") / I ** 0.5).to(torch.bfloat16).requires_grad_()
         gy = torch.randn(T, Osz, generator=g, device="cuda").to(torch.bfloat16)
 
-        def step_fn():
-            x.grad = None
-            w.grad = None
-            mx_linear(x, w, B.MX9).backward(gy)
-        t = timed(step_fn, reps=3, inner=2, warm=8)
-        tf = 3 * 2.0 * T * I * Osz / (t * 1e-3) / 1e12
-        out["mx_linear_fwd_bwd_8192x12288x12288_MX9_bf16"] = {
-            "ms": round(t, 3), "TFLOPs": round(tf, 1), "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4)}
+        for name, f, peak, key in (("MX9", B.MX9, 2500.0, "frac_of_bf16_mfma_peak_2500"),
+                                   ("MX6", B.MX6, 10100.0, "frac_of_fp6_mfma_peak_10100")):
+            def step_fn():
+                x.grad = None
+                w.grad = None
+                mx_linear(x, w, f).backward(gy)
+            t = timed(step_fn, reps=3, inner=2, warm=8)
+            tf = 3 * 2.0 * T * I * Osz / (t * 1e-3) / 1e12
+            out["mx_linear_fwd_bwd_8192x12288x12288_%s_bf16" % name] = {
+                "ms": round(t, 3), "TFLOPs": round(tf, 1), key: round(tf / peak, 4)}
     except B.BdrError as e:
         out["mx_linear_fwd_bwd_8192x12288x12288_MX9_bf16"] = {"error": str(e)}
     return out
