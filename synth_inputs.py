@@ -42,6 +42,16 @@ def sweep(n=1 << 24, cols=256, device="cpu", seed=2):
     return x.view(n // cols, cols)
 
 
+def design_space(vectors=16384, k=256, device="cpu", seed=5):
+    """The workload of the paper's QSNR-versus-cost study (caption of the Pareto figure in
+    Sec. IV): X ~ N(0, |N(0,1)|) -- Gaussian vectors whose variance is itself drawn, once per
+    vector, as the magnitude of a standard normal ("variable variance" in Sec. IV-C); more than
+    10K vectors.  fp32, [vectors, k]."""
+    g = _gen(seed, device)
+    var = torch.randn(vectors, 1, generator=g, device=device).abs()
+    return torch.randn(vectors, k, generator=g, device=device) * var.sqrt()
+
+
 def activation(rows=8192, cols=12288, device="cpu", seed=3):
     """N(0,1) with round(1%) of the columns scaled by 50 (channel outliers), cast to bf16."""
     g = _gen(seed, device)

@@ -42,6 +42,16 @@ def test_tiny_config_qsnr():
     assert q[0] > q[1] > q[2]
 
 
+def test_design_space_workload_and_the_printed_gap():
+    # the paper's own QSNR workload (Gaussian vectors of varying variance), the three MX formats
+    # and the two block floating-point formats it names; Sec. IV-C prints MX9 - MSFP16 ~ 3.6 dB
+    x = S.design_space(device="cuda")
+    fmts = [B.MX9, B.MX6, B.MX4, B.fmt(16, 16, 0, 7), B.fmt(16, 16, 0, 3)]
+    q = check(fmts, x, "design space")
+    assert abs((q[0] - q[3]) - 3.6) <= 0.05
+    assert q[0] > q[1] > q[4] > q[2]          # MX9 > MX6 > MSFP12 > MX4
+
+
 def test_sweep_64_formats_reduced_size():
     x = S.sweep(1 << 18, device="cuda")
     q = check(sweep64(), x, "sweep64")

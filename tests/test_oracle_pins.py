@@ -117,6 +117,32 @@ def test_validate_rejects_bad_tuples():
         assert O.validate(bad) == O.ERR_FORMAT
 
 
+# --------------------------------------------------------------- values the paper prints
+
+def _printed_qsnr_lines():
+    with open(os.path.join(HERE, "golden", "printed_qsnr.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                yield line
+
+
+@pytest.mark.parametrize("line", list(_printed_qsnr_lines()))
+def test_printed_qsnr_differences(line):
+    # A wrong shift rule, sub-block size, microexponent width or rounding moves this difference
+    # by 0.8 dB or more (k2 = 4: 2.4, k2 = 1: 4.5, d2 = 2: 4.4, truncation: -2.4); the seed moves
+    # it by 0.005.
+    import synth_inputs as S
+    fa, fb, want, tol = [p.split() for p in line.split("|")]
+    k1, k2, d2, m = map(int, fa)
+    A = O.fmt(k1, k2, d2, m)
+    k1, k2, d2, m = map(int, fb)
+    Bf = O.fmt(k1, k2, d2, m)
+    x = S.design_space().numpy()
+    q, _ = O.qsnr_sweep([A, Bf], x)
+    assert abs((q[0] - q[1]) - float(want[0])) <= float(tol[0]), (q[0], q[1])
+
+
 # --------------------------------------------------------------- hand-worked examples
 
 def _golden_lines():
