@@ -143,6 +143,18 @@ def test_printed_qsnr_differences(line):
     assert abs((q[0] - q[1]) - float(want[0])) <= float(tol[0]), (q[0], q[1])
 
 
+def test_knee_of_each_parameter_sweep_for_all_selected_formats():
+    # Sec. IV-C, qualitatively, for m = 7, 4, 2: a second microexponent bit buys under 1 dB, finer
+    # sub-blocks 8 -> 2 buy 2 .. 2.5 dB, 2 -> 1 under 1 dB; and each step helps
+    import synth_inputs as S
+    x = S.design_space().numpy()
+    for m in (7, 4, 2):
+        q, _ = O.qsnr_sweep([O.fmt(16, 2, 1, m), O.fmt(16, 2, 2, m), O.fmt(16, 8, 1, m), O.fmt(16, 1, 1, m)], x)
+        assert 0.3 < q[1] - q[0] < 1.0
+        assert 1.9 < q[0] - q[2] < 2.6
+        assert 0.5 < q[3] - q[0] < 1.0
+
+
 # --------------------------------------------------------------- hand-worked examples
 
 def _golden_lines():
