@@ -17,10 +17,16 @@
 // extract, integer-to-float, ldexp, sign insert, and one byte permute per pair to
 // form the BF16 pair.
 //
-// This is not the dot-product engine of Sec. IV-B (integer Hadamard tree with a
-// conditional shift and fixed-point accumulation): that design targets a custom
-// datapath.  On gfx950 the matrix cores take BF16, so the operands are brought to
-// BF16 and the hardware does the rest.
+// That is the single-kernel form (mx_gemm_kernel).  The two-pass form rewrites each
+// operand once in global memory and runs gemm_dl_kernel on the two images: BF16
+// images for MX9, and for MX6 / MX4 images of FP6 elements with one scale byte per
+// block, which the block-scaled matrix instruction of gfx950 multiplies at twice
+// the BF16 rate (mx_to_fp6_kernel and the notes above it).
+//
+// None of this is the dot-product engine of Sec. IV-B (integer Hadamard tree with
+// a conditional shift and fixed-point accumulation): that design targets a custom
+// datapath.  The FP6 form is the nearest thing this chip offers: small-integer
+// elements under a shared power-of-two scale that the hardware applies.
 #include <type_traits>
 
 #include "bdr_device.hpp"

@@ -117,6 +117,14 @@ def test_wide_exponent_range_and_signs():
     _check(B.MX6, B.MX9, A, Bm, "wide")
 
 
+def test_wide_exponent_range_fp6_form():
+    # the same mix (16 binades of spread, zeros, negative zeros) through the FP6 form, both roles
+    A = S.wide_range(128, 256, device="cuda", seed=43, spread=8)
+    Bm = S.wide_range(256, 256, device="cuda", seed=44, spread=8)
+    _check(B.MX6, B.MX4, A, Bm, "wide fp6")
+    _check(B.MX4, B.MX6, A, Bm, "wide fp6, roles swapped")
+
+
 def test_strided_output_and_empty_k():
     M, N, K = 128, 128, 64
     A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=8)
