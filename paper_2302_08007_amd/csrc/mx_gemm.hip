@@ -314,7 +314,9 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
     for (int b = 0; b < 2; ++b) {
         const int se = (int)((pk.se2 >> (8 * b)) & 0xffu);
         const int z = (MB == 4 && se == 1) ? 1 : 0;
-        const int scale = MB == 4 ? se - 2 + z : se - 1;
+        // exponent code 0 is never written by the quantizer (codes are 1 .. 254); it is held
+        // at scale byte 0 here rather than wrapped
+        const int scale = max(MB == 4 ? se - 2 + z : se - 1, 0);
         uint32_t w[3] = {0u, 0u, 0u};
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
