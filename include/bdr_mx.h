@@ -153,7 +153,7 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  * MX-quantized, along the reduction dimension).  Operands are brought, exactly, to a
  * form the matrix cores take and the products are accumulated in FP32: BF16 (8
  * significant bits hold any MX element), or, in the two-pass form when both formats
- * have m <= 4 and K is a multiple of 128, FP6 elements under one power-of-two scale
+ * have m <= 4, FP6 elements under one power-of-two scale
  * per block of 16 (M 2^-tau has at most 4 significant bits over 5 binades, which
  * sign + 2 exponent + 3 fraction bits hold), at twice the BF16 rate.
  *   fa, fb : formats of A and B, each one of Table II's family (k1 16, d1 8, k2 2,

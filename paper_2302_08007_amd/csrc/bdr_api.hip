@@ -263,14 +263,16 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         if (workspace_bytes < mx_gemm_workspace_bytes(M, N, K)) return BDR_ERR_WORKSPACE;
         if (!aligned16(workspace)) return BDR_ERR_ALIGN;
         char *wa = static_cast<char *>(workspace), *wb = wa + gemm_ws_half(M, K);
-        if (fa->m <= 4 && fb->m <= 4 && K % 128 == 0) {
+        if (fa->m <= 4 && fb->m <= 4) {
             // MX6 and MX4 elements are exact FP6 values under a per-block power of two:
-            // block-scaled FP6 MFMAs, twice the rate of BF16 (1 byte per element of workspace)
-            st = bdr::to_fp6(*fa, a_codes, a_sexp, a_mexp, M * (K / 16), wa, false, s);
+            // block-scaled FP6 MFMAs, twice the rate of BF16.  One byte per element of
+            // workspace; K is brought up to a multiple of 128 with zero blocks.
+            const int64_t Kp = (K + 127) / 128 * 128;
+            st = bdr::to_fp6(*fa, a_codes, a_sexp, a_mexp, M, K, Kp, wa, false, s);
             if (st) return st;
-            st = bdr::to_fp6(*fb, b_codes, b_sexp, b_mexp, N * (K / 16), wb, true, s);
+            st = bdr::to_fp6(*fb, b_codes, b_sexp, b_mexp, N, K, Kp, wb, true, s);
             if (st) return st;
-            return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, s);
+            return bdr::gemm_fp6(wa, wb, M, N, Kp, C, ldc, s);
         }
         // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact)
         st = bdr::dequantize_row(*fa, a_codes, a_sexp, a_mexp, M, K, wa, BDR_BF16, K, s);

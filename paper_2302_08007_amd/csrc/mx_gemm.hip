@@ -302,12 +302,28 @@ template <int MB, bool B_OPERAND>
 __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restrict__ codes,
                                                         const uint8_t *__restrict__ sexp,
                                                         const uint8_t *__restrict__ mexp,
-                                                        int64_t n_pairs, u32x4 *__restrict__ out)
+                                                        int64_t n_pairs, int row_pairs,
+                                                        int row_pairs_out, u32x4 *__restrict__ out)
 {
     static_assert(MB == 4 || MB == 2, "MX6 or MX4");
     constexpr int CB = MB + 1;
-    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;  // two blocks per thread
-    if (p >= n_pairs) return;
+    // Two blocks per thread.  A row of the operand has row_pairs pairs of blocks; the image
+    // has row_pairs_out >= row_pairs per row, the excess being zero chunks (K brought up to
+    // a whole K step of the product kernel).  n_pairs counts pairs of the image.
+    const int64_t po = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (po >= n_pairs) return;
+    int64_t p = po;
+    if (row_pairs_out != row_pairs) {
+        const int64_t row = po / row_pairs_out;
+        const int q = (int)(po - row * row_pairs_out);
+        if (q >= row_pairs) {
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            out[2 * po] = zero;
+            out[2 * po + 1] = zero;
+            return;
+        }
+        p = row * row_pairs + q;
+    }
     Packed<MB> pk;
     load_packed<MB>(codes, sexp, mexp, 2 * p, pk);
 #pragma unroll
@@ -341,7 +357,7 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
             if ((bit & 31) + 6 > 32) w[(bit >> 5) + 1] |= c6 >> (32 - (bit & 31));
         }
         const u32x4 chunk = {w[0], w[1], w[2], (uint32_t)scale << (B_OPERAND ? 8 * kScaleByteB : 8 * kScaleByteA)};
-        out[2 * p + b] = chunk;
+        out[2 * po + b] = chunk;
     }
 }
 
@@ -648,21 +664,23 @@ int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, floa
     return gemm_dl<true>(A, B, M, N, (int)(K / 2), C, ldc, s);
 }
 
-// Packed MX6 or MX4 planes of n_blocks blocks (an even number) -> n_blocks 16-byte chunks.
+// Packed MX6 or MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 16 chunks
+// of 16 bytes, K_out >= K a multiple of 32; blocks past K are zero chunks.
 int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
-           int64_t n_blocks, void *out, bool b_operand, hipStream_t s)
+           int64_t rows, int64_t K, int64_t K_out, void *out, bool b_operand, hipStream_t s)
 {
-    if (n_blocks == 0) return BDR_OK;
+    if (rows == 0 || K_out == 0) return BDR_OK;
     const uint8_t *c = (const uint8_t *)codes, *e = (const uint8_t *)sexp, *m = (const uint8_t *)mexp;
-    const int64_t pairs = n_blocks / 2;
+    const int rp = (int)(K / 32), rpo = (int)(K_out / 32);
+    const int64_t pairs = rows * rpo;
     const dim3 grid((unsigned)((pairs + 255) / 256)), block(256);
     u32x4 *o = (u32x4 *)out;
     if (f.m == 4) {
-        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<4, true>), grid, block, 0, s, c, e, m, pairs, o);
-        else hipLaunchKernelGGL((mx_to_fp6_kernel<4, false>), grid, block, 0, s, c, e, m, pairs, o);
+        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<4, true>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
+        else hipLaunchKernelGGL((mx_to_fp6_kernel<4, false>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
     } else {
-        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<2, true>), grid, block, 0, s, c, e, m, pairs, o);
-        else hipLaunchKernelGGL((mx_to_fp6_kernel<2, false>), grid, block, 0, s, c, e, m, pairs, o);
+        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<2, true>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
+        else hipLaunchKernelGGL((mx_to_fp6_kernel<2, false>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
     }
     return launch_status();
 }
