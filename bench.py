@@ -244,6 +244,19 @@ def main():
     }))
 
 
+def profiled_mfma_util(kernel_prefix):
+    """MfmaUtil (%) of a kernel from the committed rocprofv3 summary, or None."""
+    path = os.path.join(ROOT, "profiles", "mx_gemm_and_sweep_unit_utilisation.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith(kernel_prefix):
+                    return float(line.split()[-2])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def measured_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (profiles/), or None when no such summary has been recorded."""
@@ -314,16 +327,26 @@ def other_legs(B, S, torch, timed):
             leg[name] = {"ms": round(t, 3), "TFLOPs": round(tf, 1), key: round(tf / peak, 4)}
         leg["two_pass"]["matrix_instruction"] = "fp6 block-scaled, 16 of 32 K positions used"
         leg["single_kernel"]["matrix_instruction"] = "bf16"
+        leg["two_pass"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("gemm_dl_kernel<2,4,4,2,FP6>")
+        leg["single_kernel"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("mx_gemm_kernel<4,4,2,4,4,2>")
+        # fidelity of C against the product of the unquantized operands (library FP32 GEMM)
+        B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C, workspace=ws)
+        Cfp = A @ Bm.t()
+        leg["qsnr_db_vs_fp32_gemm"] = round(
+            (10 * torch.log10(Cfp.double().square().sum() / (C.double() - Cfp.double()).square().sum())).item(), 3)
         out["mx_gemm_8192_MX6"] = leg
         # MX9 needs 8 significant bits: the two-pass form expands to BF16
         p9a, p9b = B.bdr_quantize(B.MX9, A), B.bdr_quantize(B.MX9, Bm)
         t = timed(lambda: B.mx_gemm(B.MX9, B.MX9, p9a, p9b, M, N, K, out=C, workspace=ws),
                   reps=5, inner=4, warm=40)
         tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
+        q9 = (10 * torch.log10(Cfp.double().square().sum() / (C.double() - Cfp.double()).square().sum())).item()
         out["mx_gemm_8192_MX9"] = {"two_pass": {"ms": round(t, 3), "TFLOPs": round(tf, 1),
                                                 "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4),
-                                                "matrix_instruction": "bf16"}}
-        del p9a, p9b
+                                                "matrix_instruction": "bf16",
+                                                "mfma_util_pct_rocprofv3": profiled_mfma_util("gemm_dl_kernel<2,4,4,2,BF16>")},
+                                   "qsnr_db_vs_fp32_gemm": round(q9, 3)}
+        del p9a, p9b, Cfp
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
     try:
