@@ -284,7 +284,9 @@ def other_legs(B, S, torch, timed):
         out["qsnr_sweep_64fmt_16Mi"] = {
             "ms": round(t, 4), "configs_per_s": round(64 / (t * 1e-3), 1),
             "Gelem_configs_per_s": round(64 * xs.numel() / (t * 1e-3) / 1e9, 1),
-            "distinct_quantizers": 32}
+            "distinct_quantizers": 32,
+            # QSNR (dB) per format, in the order k1 (8, 16, 32, 64) x k2 (1, 2, 4, k1) x d2 (0, 1) x m (2, 4)
+            "qsnr_db": [round(v, 3) for v in res[0].cpu().tolist()]}
         del xs
     except B.BdrError as e:
         out["qsnr_sweep_64fmt_16Mi"] = {"error": str(e)}
