@@ -244,17 +244,22 @@ def main():
     }))
 
 
-def profiled_mfma_util(kernel_prefix):
-    """MfmaUtil (%) of a kernel from the committed rocprofv3 summary, or None."""
+def profiled_util(kernel_prefix, column):
+    """MfmaUtil (column -2) or VALUBusy (column -1), in percent, of a kernel from the committed
+    rocprofv3 summary, or None."""
     path = os.path.join(ROOT, "profiles", "mx_gemm_and_sweep_unit_utilisation.txt")
     try:
         with open(path) as fh:
             for line in fh:
                 if line.startswith(kernel_prefix):
-                    return float(line.split()[-2])
+                    return float(line.split()[column])
     except (OSError, ValueError, IndexError):
         pass
     return None
+
+
+def profiled_mfma_util(kernel_prefix):
+    return profiled_util(kernel_prefix, -2)
 
 
 def measured_traffic():
@@ -285,6 +290,7 @@ def other_legs(B, S, torch, timed):
             "ms": round(t, 4), "configs_per_s": round(64 / (t * 1e-3), 1),
             "Gelem_configs_per_s": round(64 * xs.numel() / (t * 1e-3) / 1e9, 1),
             "distinct_quantizers": 32,
+            "valu_busy_pct_rocprofv3": profiled_util("sweep_kernel<float,true>", -1),
             # QSNR (dB) per format, in the order k1 (8, 16, 32, 64) x k2 (1, 2, 4, k1) x d2 (0, 1) x m (2, 4)
             "qsnr_db": [round(v, 3) for v in res[0].cpu().tolist()]}
         del xs
