@@ -307,6 +307,21 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
 {
     static_assert(MB == 4 || MB == 2, "MX6 or MX4");
     constexpr int CB = MB + 1;
+    // The element map as a table in LDS: index = code | tau << CB | z << (CB + 1), value =
+    // the FP6 code.  It spans at most 32 dwords, one per bank, so look-ups never conflict.
+    __shared__ uint8_t s_map[4 << CB];
+    if (threadIdx.x < (4u << CB)) {
+        const uint32_t idx = threadIdx.x;
+        const uint32_t mag = idx & ((1u << MB) - 1u), sign = (idx >> MB) & 1u;
+        const int tau = (int)((idx >> CB) & 1u), z = (int)(idx >> (CB + 1));
+        const int sh = (MB == 4 ? 2 : 3) - tau - z;
+        const uint32_t u = sh >= 0 ? mag << sh : 0u;  // element = u / 8, u <= 60 (MX4 has no z)
+        // u >= 8: FP32 of u has exponent field 127 + p (p = 3 .. 5) and u's next three
+        // bits on top of its fraction; E2M3 wants exponent field p - 2 and those bits
+        const uint32_t em = u < 8u ? u : (as_u((float)u) >> 20) - ((127u + 2u) << 3);
+        s_map[idx] = (uint8_t)((sign << 5) | em);
+    }
+    __syncthreads();
     // Two blocks per thread.  A row of the operand has row_pairs pairs of blocks; the image
     // has row_pairs_out >= row_pairs per row, the excess being zero chunks (K brought up to
     // a whole K step of the product kernel).  n_pairs counts pairs of the image.
@@ -344,14 +359,8 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
                 win = funnel_r(pk.c[(k + 1) % CB], pk.c[k], sh);
                 sh = 0;
             }
-            const uint32_t code = win >> sh;
-            const uint32_t mag = code & ((1u << MB) - 1u), sign = (code >> MB) & 1u;
-            const int tau = (int)((pk.tau16 >> (8 * b + (j >> 1))) & 1u);
-            const uint32_t u = mag << ((MB == 4 ? 2 : 3) - tau - z);  // element = u / 8, u <= 60
-            // u >= 8: FP32 of u has exponent field 127 + p (p = 3 .. 5) and u's next three
-            // bits on top of its fraction; E2M3 wants exponent field p - 2 and those bits
-            const uint32_t em = u < 8u ? u : (as_u((float)u) >> 20) - ((127u + 2u) << 3);
-            const uint32_t c6 = (sign << 5) | em;
+            const uint32_t tz = (((pk.tau16 >> (8 * b + (j >> 1))) & 1u) << CB) | ((uint32_t)z << (CB + 1));
+            const uint32_t c6 = s_map[((win >> sh) & ((1u << CB) - 1u)) | tz];
             const int bit = 6 * j;
             w[bit >> 5] |= c6 << (bit & 31);
             if ((bit & 31) + 6 > 32) w[(bit >> 5) + 1] |= c6 >> (32 - (bit & 31));
