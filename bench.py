@@ -334,6 +334,8 @@ def other_legs(B, S, torch, timed):
             tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
             leg[name] = {"ms": round(t, 3), "TFLOPs": round(tf, 1), key: round(tf / peak, 4)}
         leg["two_pass"]["matrix_instruction"] = "fp6 block-scaled, 16 of 32 K positions used"
+        # k1 = 16 against a hardware scale group of 32: half of each instruction multiplies zeros
+        leg["two_pass"]["frac_of_usable_half_of_fp6_peak"] = round(leg["two_pass"]["TFLOPs"] / 5050.0, 4)
         leg["single_kernel"]["matrix_instruction"] = "bf16"
         leg["two_pass"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("gemm_dl_kernel<2,4,4,2,FP6>")
         leg["single_kernel"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("mx_gemm_kernel<4,4,2,4,4,2>")
