@@ -149,20 +149,22 @@ def test_strided_output_and_empty_k():
         B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, workspace=ws[:need - 16])
 
 
-def test_full_size_sampled_entries():
-    # 8192^3, MX6 x MX6, the bench configuration: 64 x 64 sampled entries against the oracle
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX9", "MX9"), ("MX4", "MX4"), ("MX6", "MX4")])
+def test_full_size_sampled_entries(names):
+    # 8192^3, the bench configuration (MX6 x MX6) and the other instruction paths at that size:
+    # 64 x 64 sampled entries against the oracle
     M = N = K = 8192
     A, Bm = S.gemm_operands(M, N, K, device="cuda")
-    f = B.MX6
-    pa, pb = B.bdr_quantize(f, A), B.bdr_quantize(f, Bm)
-    C = B.mx_gemm(f, f, pa, pb, M, N, K)
-    C2 = B.mx_gemm(f, f, pa, pb, M, N, K, workspace=_workspace(M, N, K))
+    f, fb = getattr(B, names[0]), getattr(B, names[1])
+    pa, pb = B.bdr_quantize(f, A), B.bdr_quantize(fb, Bm)
+    C = B.mx_gemm(f, fb, pa, pb, M, N, K)
+    C2 = B.mx_gemm(f, fb, pa, pb, M, N, K, workspace=_workspace(M, N, K))
     torch.cuda.synchronize()
     rng = np.random.default_rng(4)
     ri = np.sort(rng.choice(M, 64, replace=False))
     ci = np.sort(rng.choice(N, 64, replace=False))
     ii, jj = [a.reshape(-1) for a in np.meshgrid(ri, ci, indexing="ij")]
-    want, absdot = O.mx_gemm_sampled(ofmt(f), ofmt(f), _planes_np(pa), _planes_np(pb), M, N, K, ii, jj)
+    want, absdot = O.mx_gemm_sampled(ofmt(f), ofmt(fb), _planes_np(pa), _planes_np(pb), M, N, K, ii, jj)
     for got_all in (C, C2):
         got = got_all[torch.as_tensor(ii, device="cuda"), torch.as_tensor(jj, device="cuda")].cpu().numpy()
         err = np.abs(got.astype(np.float64) - want.astype(np.float64))
@@ -173,4 +175,4 @@ def test_full_size_sampled_entries():
     # fidelity against the unquantized FP32 product (library GEMM): finite and in a sane band
     Cfp = A @ Bm.t()
     q = 10 * torch.log10(Cfp.double().square().sum() / (C.double() - Cfp.double()).square().sum())
-    assert 10.0 < q.item() < 40.0
+    assert 10.0 < q.item() < 50.0
