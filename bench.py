@@ -294,6 +294,21 @@ def other_legs(B, S, torch, timed):
             # QSNR (dB) per format, in the order k1 (8, 16, 32, 64) x k2 (1, 2, 4, k1) x d2 (0, 1) x m (2, 4)
             "qsnr_db": [round(v, 3) for v in res[0].cpu().tolist()]}
         del xs
+        # a sweep of the size of the paper's design-space exploration ("800+ configurations",
+        # Sec. IV) on its workload (Gaussian vectors of varying variance, 16384 x 256)
+        xd = S.design_space(device="cuda")
+        big = [B.fmt(k1, k2, d2, m) for k1 in (8, 16, 32, 64, 128, 256) for k2 in (1, 2, 4, 8, 16)
+               if k2 <= k1 for d2 in (0, 1, 2, 3) for m in range(2, 9)]
+        wsb = torch.empty(B.lib.bdr_qsnr_sweep_workspace_bytes(len(big)), dtype=torch.uint8, device="cuda")
+        resb = (torch.empty(len(big), dtype=torch.float64, device="cuda"),
+                torch.empty(len(big) + 1, dtype=torch.float64, device="cuda"))
+        t = timed(lambda: B.bdr_qsnr_sweep(big, xd, workspace=wsb, out=resb), reps=3, inner=3)
+        qs = resb[0].cpu()
+        out["qsnr_sweep_%dfmt_design_space_4Mi" % len(big)] = {
+            "ms": round(t, 4), "configs_per_s": round(len(big) / (t * 1e-3), 1),
+            "Gelem_configs_per_s": round(len(big) * xd.numel() / (t * 1e-3) / 1e9, 1),
+            "qsnr_db_min": round(qs.min().item(), 3), "qsnr_db_max": round(qs.max().item(), 3)}
+        del xd
     except B.BdrError as e:
         out["qsnr_sweep_64fmt_16Mi"] = {"error": str(e)}
     try:

@@ -52,6 +52,16 @@ def test_design_space_workload_and_the_printed_gap():
     assert q[0] > q[1] > q[4] > q[2]          # MX9 > MX6 > MSFP12 > MX4
 
 
+def test_sweep_of_the_papers_size():
+    # 812 formats ("800+ configurations", Sec. IV: every k1, k2, d2, m the library takes), seven
+    # launches' worth, on a reduced number of the design-space vectors
+    x = S.design_space(vectors=256, device="cuda")
+    fmts = [B.fmt(k1, k2, d2, m) for k1 in (8, 16, 32, 64, 128, 256) for k2 in (1, 2, 4, 8, 16)
+            if k2 <= k1 for d2 in (0, 1, 2, 3) for m in range(2, 9)]
+    assert len(fmts) == 812
+    check(fmts, x, "812 formats")
+
+
 def test_sweep_64_formats_reduced_size():
     x = S.sweep(1 << 18, device="cuda")
     q = check(sweep64(), x, "sweep64")
