@@ -62,6 +62,27 @@ def test_sweep_of_the_papers_size():
     check(fmts, x, "812 formats")
 
 
+def test_theorem1_bound_on_the_full_design_space_workload():
+    # all 812 formats on all 16384 vectors (a property that holds at any size): Theorem 1's lower
+    # bound with N = 256 >= k1, and the orderings the section states (more mantissa bits, finer
+    # sub-blocks and more microexponent bits never lower the QSNR)
+    x = S.design_space(device="cuda")
+    keys = [(k1, k2, d2, m) for k1 in (8, 16, 32, 64, 128, 256) for k2 in (1, 2, 4, 8, 16)
+            if k2 <= k1 for d2 in (0, 1, 2, 3) for m in range(2, 9)]
+    q, _ = B.bdr_qsnr_sweep([B.fmt(*k) for k in keys], x)
+    q = dict(zip(keys, q.cpu().tolist()))
+    for (k1, k2, d2, m), v in q.items():
+        beta = (1 << d2) - 1
+        bound = 6.02 * m + 10 * math.log10(4.0 ** beta / (k1 + (4.0 ** beta - 1) * k2))
+        assert v >= bound - 1.0, (k1, k2, d2, m, v, bound)
+        if m < 8:
+            assert q[(k1, k2, d2, m + 1)] > v + 4.0           # close to 6.02 dB per bit
+        if d2 and k2 > 1:
+            assert q[(k1, k2 // 2, d2, m)] >= v - 1e-6
+        if d2 < 3:
+            assert q[(k1, k2, d2 + 1, m)] >= v - 1e-6
+
+
 def test_sweep_64_formats_reduced_size():
     x = S.sweep(1 << 18, device="cuda")
     q = check(sweep64(), x, "sweep64")
