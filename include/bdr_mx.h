@@ -161,8 +161,7 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *            BDR_ERR_FORMAT; the two may differ
  *   a_*, b_* : device, the three planes of each image as bdr_quantize wrote them
  *            (B is what BDR_AXIS_COL gives on a [K x N] tensor), 16-byte aligned
- *   C      : device, [M x N] floats, pitch ldc >= N elements, 16-byte aligned rows,
- *            fully overwritten
+ *   C      : device, [M x N] floats, pitch ldc >= N elements, fully overwritten
  *   workspace : device, 16-byte aligned, or NULL.  With at least
  *            mx_gemm_workspace_bytes(M, N, K) bytes (less is BDR_ERR_WORKSPACE) each
  *            operand is rewritten once into it (as BF16 or as FP6 blocks) and a plain
@@ -173,8 +172,9 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *            is touched.  Every product is exact in all forms; the forms differ only
  *            in where the FP32 sum over K is rounded (the BF16 forms give the same
  *            bits as each other).
- * M and N must be multiples of 128 and K a multiple of 64, each at most 2^20, else
- * BDR_ERR_SHAPE.  M = 0 or N = 0 launches nothing; K = 0 writes zeros.  Inf/NaN
+ * K must be a multiple of 64 and M, N, K at most 2^20 each, else BDR_ERR_SHAPE; M and N
+ * are free (tiles that hang over the edge of C cost as much as full ones: multiples of 256,
+ * else of 128, waste nothing).  M = 0 or N = 0 launches nothing; K = 0 writes zeros.  Inf/NaN
  * codes, blocks whose exponent code is so low that an element is a BF16
  * subnormal, and sums that are FP32 subnormals are outside the supported domain. */
 int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,

@@ -128,6 +128,30 @@ __device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base
     }
 }
 
+// Write the TM x TN accumulator tiles of a wave.  32 x 32 accumulator: register r of lane l
+// is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32.  Tiles on the lower or right edge
+// of C may hang over it (M, N need not be multiples of the tile): those check every element.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], float *__restrict__ C,
+                                            int64_t ldc, int M, int N, int row0, int col0, int lane,
+                                            bool inside)
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = col0 + j * 32 + (lane & 31);
+            const int row = row0 + i * 32 + 4 * (lane >> 5);
+            float *cp = C + (int64_t)row * ldc + col;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r >> 2) + (r & 3);
+                if (inside || (row + dr < M && col < N))
+                    __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)dr * ldc);
+            }
+        }
+}
+
 // WM x WN waves, each computing TM x TN MFMA tiles of 32 x 32.
 template <int MBA, int MBB, int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
@@ -146,7 +170,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
     // Tile order: workgroup ids go round-robin over the 8 XCDs, each with its own
     // L2, so give every XCD a contiguous range of tiles and walk that range in
     // groups of 8 tile rows per tile column to keep the operands of a group hot.
-    const int ntm = M / BM, ntn = N / BN, total = ntm * ntn;
+    const int ntm = (M + BM - 1) / BM, ntn = (N + BN - 1) / BN, total = ntm * ntn;
     int t = blockIdx.x;
     if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
     int tm, tn;
@@ -168,11 +192,11 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
     const int64_t kblocks = K >> 4;
     int64_t a_blk[PA], b_blk[PB];
 #pragma unroll
-    for (int i = 0; i < PA; ++i)
-        a_blk[i] = (int64_t)(m0 + urow + i * (THREADS / 2)) * kblocks + 2 * uhalf;
+    for (int i = 0; i < PA; ++i)  // rows past the edge of an operand repeat its last row (never stored)
+        a_blk[i] = (int64_t)min(m0 + urow + i * (THREADS / 2), M - 1) * kblocks + 2 * uhalf;
 #pragma unroll
     for (int i = 0; i < PB; ++i)
-        b_blk[i] = (int64_t)(n0 + urow + i * (THREADS / 2)) * kblocks + 2 * uhalf;
+        b_blk[i] = (int64_t)min(n0 + urow + i * (THREADS / 2), N - 1) * kblocks + 2 * uhalf;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -263,17 +287,8 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
         }
     }
 
-    // 32 x 32 accumulator: register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-            float *cp = C + (int64_t)(m0 + (wm * TM + i) * 32 + 4 * (lane >> 5)) * ldc + col;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)(8 * (r >> 2) + (r & 3)) * ldc);
-        }
+    store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
+                        m0 + BM <= M && n0 + BN <= N);
 }
 
 // The block-scaled FP6 MFMA of gfx950 multiplies E2M3 elements (sign, 2 exponent bits,
@@ -409,7 +424,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
     static_assert(LA >= 1 && LB >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TM % 2 == 0, "tile");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B]
 
-    const int ntm = M / BM, ntn = N / BN, total = ntm * ntn;
+    const int ntm = (M + BM - 1) / BM, ntn = (N + BN - 1) / BN, total = ntm * ntn;
     int t = blockIdx.x;
     if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
     int tm, tn;
@@ -429,12 +444,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int row = (wave * LA + i) * 8 + (lane >> 3);
-        ap[i] = A + (int64_t)(m0 + row) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
+        // rows past the edge of an operand repeat its last row (their products are never stored)
+        ap[i] = A + (int64_t)min(m0 + row, M - 1) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int row = (wave * LB + i) * 8 + (lane >> 3);
-        bp[i] = B + (int64_t)(n0 + row) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
+        bp[i] = B + (int64_t)min(n0 + row, N - 1) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
     }
 
     f32x16 acc[TM][TN];
@@ -559,16 +575,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
     for (int kt = 0; kt + 2 < nk; ++kt) k_step(std::true_type{}, std::true_type{});
     if (nk > 1) k_step(std::false_type{}, std::true_type{});
     k_step(std::false_type{}, std::false_type{});
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-            float *cp = C + (int64_t)(m0 + (wm * TM + i) * 32 + 4 * (lane >> 5)) * ldc + col;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)(8 * (r >> 2) + (r & 3)) * ldc);
-        }
+    store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
+                        m0 + BM <= M && n0 + BN <= N);
 }
 
 // Two tile shapes: 256 x 256 with 8 waves (128 KiB of LDS, one workgroup per CU)
@@ -590,7 +598,7 @@ int launch_gemm(const uint8_t *ac, const uint8_t *as, const uint8_t *am, const u
         hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>), dim3(grid), dim3(512), kBigLds, s,
                            ac, as, am, bc, bs, bm, M, N, K, C, ldc);
     } else {
-        const unsigned grid = (unsigned)((M / 128) * (N / 128));
+        const unsigned grid = (unsigned)(((M + 127) / 128) * ((N + 127) / 128));
         hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 2, 2, 2>), dim3(grid), dim3(256), kSmallLds,
                            s, ac, as, am, bc, bs, bm, M, N, K, C, ldc);
     }
@@ -617,7 +625,7 @@ int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int pitch, flo
     if (kLds > 64 * 1024 &&
         !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN, FP6>), kLds, granted))
         return BDR_ERR_LAUNCH;
-    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN, FP6>), dim3((unsigned)((M / BM) * (N / BN))),
+    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN, FP6>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
                        dim3(64 * WM * WN), kLds, s, A, B, M, N, pitch, C, ldc);
     return launch_status();
 }

@@ -68,5 +68,6 @@ class _MXLinear(torch.autograd.Function):
 def mx_linear(x, w, fmt_fwd, fmt_bwd=None):
     """y = x w^T with the forward, backward-data and backward-weight products all computed on
     MX-quantized operands (formats of Table II: MX9, MX6 or MX4).  x [T, I] and w [O, I] are
-    contiguous FP32 or BF16 CUDA tensors with T, I and O multiples of 128."""
+    contiguous FP32 or BF16 CUDA tensors with T, I and O multiples of 64 (each is the reduction
+    length of one of the three products)."""
     return _MXLinear.apply(x, w, fmt_fwd, fmt_bwd if fmt_bwd is not None else fmt_fwd)

@@ -134,9 +134,10 @@ def test_sweep_and_gemm_argument_checks():
         ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, C, ldc, ws,
         wsb, NULL)
     assert gm(fa=B.fmt(32, 2, 1, 4)) == ERR_FORMAT
-    assert gm(M=100) == ERR_SHAPE and gm(K=48) == ERR_SHAPE and gm(ldc=64) == ERR_SHAPE
+    assert gm(M=-1) == ERR_SHAPE and gm(K=48) == ERR_SHAPE and gm(ldc=64) == ERR_SHAPE
+    assert gm(N=(1 << 20) + 1, ldc=(1 << 20) + 1) == ERR_SHAPE
     assert gm(C=NULL) == ERR_NULL and gm(a=NULL) == ERR_NULL
-    assert gm(C=FAKE_ODD) == ERR_ALIGN
+    assert gm(C=ctypes.c_void_p(0x10002)) == ERR_ALIGN   # C needs only the alignment of a float
     assert gm(M=0) == OK
     need = L.mx_gemm_workspace_bytes(128, 128, 64)
     assert need == 2 * 128 * 64 * 2 and L.mx_gemm_workspace_bytes(-1, 128, 64) == 0

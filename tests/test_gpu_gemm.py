@@ -59,6 +59,23 @@ def test_small_full_matrix(shape, names):
     _check(getattr(B, names[0]), getattr(B, names[1]), A, Bm, "%s %s" % (shape, names))
 
 
+@pytest.mark.parametrize("shape", [(1, 1, 64), (130, 70, 128), (257, 129, 64), (100, 384, 192), (33, 31, 256)])
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX9", "MX6")])
+def test_c_edges_that_are_not_tile_multiples(shape, names):
+    # M and N are free: edge tiles read the last operand row again and store only what lies
+    # inside C; the canary columns behind each row of a pitched C stay untouched
+    M, N, K = shape
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=3 * M + N)
+    fa, fb = getattr(B, names[0]), getattr(B, names[1])
+    _check(fa, fb, A, Bm, "%s %s" % (shape, names))
+    pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
+    for ws in (None, _workspace(M, N, K)):
+        big = torch.full((M + 3, N + 5), 7.0, device="cuda")
+        B.mx_gemm(fa, fb, pa, pb, M, N, K, out=big[:M, :N], workspace=ws)
+        assert torch.all(big[M:] == 7.0) and torch.all(big[:, N:] == 7.0)
+        assert torch.equal(big[:M, :N], B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws))
+
+
 def test_exact_on_small_integers():
     # integers below 2^m sharing one exponent are exact in MX: the product is an integer matrix
     g = torch.Generator(device="cuda").manual_seed(5)
