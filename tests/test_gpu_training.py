@@ -34,7 +34,7 @@ def _close(got, want, absdot, what):
 
 
 @pytest.mark.parametrize("names", [("MX9", "MX9"), ("MX6", "MX9"), ("MX4", "MX6")])
-@pytest.mark.parametrize("shape", [(128, 128, 128), (256, 384, 128)])
+@pytest.mark.parametrize("shape", [(128, 128, 128), (256, 384, 128), (192, 64, 320)])
 def test_linear_layer_flow_fp32(names, shape):
     T, I, Osz = shape
     ff, fb = getattr(B, names[0]), getattr(B, names[1])
