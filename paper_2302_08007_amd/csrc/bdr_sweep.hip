@@ -47,10 +47,10 @@ constexpr int kSweepBlocks = 768;  // three resident workgroups per compute unit
 constexpr int kChunk = 128;  // formats per launch: bounds kernel arguments (< 4 KiB) and LDS
 constexpr int kMaxGroups = kChunk;
 constexpr int kMaxClasses = kChunk;
-constexpr int kMR = 2;       // (m, rounding) pairs evaluated together in one group
+constexpr int kMR = 2;       // (m, rounding) pairs evaluated together in a group that selects
+constexpr int kMRd = 8;      // ... and in a group that evaluates every class directly
 constexpr int kAbsBlocks = 512;               // workgroups of the maximum pass
 constexpr size_t kHeaderBytes = 4096;         // per-workgroup maxima (kAbsBlocks words), rest unused
-constexpr uint16_t kNone = 0xffff;
 constexpr int kFoldPasses = (kChunk + 1 + 31) / 32;  // quantizers + signal, 32 per pass
 constexpr int kFoldEvery = 256 / (8 * kG);           // iterations between folds: 256 elements per lane
 
@@ -59,15 +59,24 @@ constexpr int kFoldEvery = 256 / (8 * kG);           // iterations between folds
 struct alignas(16) GroupDesc {
     uint8_t lk1;       // log2 k1
     uint8_t shared;    // 1: all classes have beta <= 1 and select between two candidates
-    uint8_t n_mr;      // (m, rounding) pairs in use (<= kMR)
+    uint8_t n_mr;      // (m, rounding) pairs in use (<= kMR when shared, else <= kMRd)
     uint8_t n_cls;     // classes of this group
     uint16_t first;    // index of its first class
-    uint8_t m[kMR], rnd[kMR];
+    uint8_t mr[kMRd];  // m in the low nibble, rounding in the high one
+    __host__ __device__ int m(int r) const { return mr[r] & 15; }
+    __host__ __device__ int rnd(int r) const { return mr[r] >> 4; }
 };
 struct alignas(8) ClassDesc {
     uint8_t lk2, beta;   // log2 k2, 2^d2 - 1
-    uint16_t q[kMR];     // accumulator of (this class, mr), kNone when no format asks for it
+    uint8_t mask;        // bit r: some format asks for (this class, mr r)
+    uint8_t pad;
+    uint16_t base;       // accumulators of the requested pairs follow each other from here
+    uint16_t q1;         // accumulator of pair 1 (base, or base + 1 when pair 0 is requested too)
+    __host__ __device__ bool wants(int r) const { return (mask >> r) & 1; }
+    __host__ __device__ int q(int r) const { return base + __builtin_popcount(mask & ((1u << r) - 1u)); }
+    __host__ __device__ int q01(int r) const { return r == 0 ? base : q1; }  // r < 2
 };
+static_assert(sizeof(GroupDesc) == 16 && sizeof(ClassDesc) == 8, "descriptor sizes");
 struct SweepPlan {
     int32_t n_group, n_quant;
     GroupDesc grp[kMaxGroups];
@@ -285,7 +294,7 @@ __device__ __forceinline__ float direct(const float (&yp)[kG][8], const int (&sh
 
 // ALL_RNE: every format of the launch rounds to nearest even (the usual case);
 // the other two modes are then compiled out.
-template <typename T, bool ALL_RNE>
+template <typename T, bool ALL_RNE, bool WIDE>
 __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
     SweepPlan plan, const T *__restrict__ x, int64_t cols, int64_t ld, int64_t n_groups,
     const uint32_t *__restrict__ blockmax, double *__restrict__ partials)
@@ -386,7 +395,7 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
                 for (int r = 0; r < kMR; ++r) {
                     // an unused slot repeats slot 0 (the host fills it so): computing it
                     // anyway keeps the candidate arrays free of conditional definitions
-                    const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
+                    const MrConst c = mr_const(gd.m(r), gd.rnd(r));
 #pragma unroll
                     for (int j = 0; j < kG; ++j) {
                         if (ALL_RNE || c.rounding == BDR_RNE)
@@ -405,7 +414,7 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
                     auto run = [&](auto pick) {
 #pragma unroll
                         for (int r = 0; r < kMR; ++r) {
-                            if (cd.q[r] != kNone) {
+                            if (cd.wants(r)) {
                                 float sum = 0.f;
 #pragma unroll
                                 for (int j = 0; j < kG; ++j)
@@ -414,7 +423,7 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
                                         const float d = pick(r, j, i);
                                         sum = __builtin_fmaf(d, d, sum);
                                     }
-                                add_to(cd.q[r], sum);
+                                add_to(cd.q01(r), sum);
                             }
                         }
                     };
@@ -461,9 +470,9 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
                         }
                     }
 #pragma unroll
-                    for (int r = 0; r < kMR; ++r) {
-                        if (r < gd.n_mr && cd.q[r] != kNone) {
-                            const MrConst c = mr_const(gd.m[r], gd.rnd[r]);
+                    for (int r = 0; r < (WIDE ? kMRd : kMR); ++r) {
+                        if (r < gd.n_mr && cd.wants(r)) {
+                            const MrConst c = mr_const(gd.m(r), gd.rnd(r));
                             float sum;
                             if (ALL_RNE || c.rounding == BDR_RNE)
                                 sum = direct<BDR_RNE>(yp, sh, c);
@@ -471,7 +480,7 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
                                 sum = direct<BDR_RNA>(yp, sh, c);
                             else
                                 sum = direct<BDR_RTZ>(yp, sh, c);
-                            add_to(cd.q[r], sum);
+                            add_to(cd.q(r), sum);
                         }
                     }
                     cd = nxt;
@@ -541,13 +550,13 @@ size_t sweep_workspace_bytes(int32_t n_fmts)
 namespace {
 
 // Host plan for up to kChunk formats: groups of equal k1 (split so that a group
-// holds at most kMR (m, rounding) pairs and is either all beta <= 1 or all
-// beta >= 2), classes (k2, beta) inside a group with the tau = 0 formats merged,
-// and one accumulator per distinct (class, m, rounding).
+// is either all beta <= 1 or all beta >= 2 and holds at most kMR, respectively
+// kMRd, (m, rounding) pairs), classes (k2, beta) inside a group with the tau = 0
+// formats merged, and one accumulator per distinct (class, m, rounding).
 void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &map)
 {
     int ng = 0;
-    int f_group[kChunk], f_mr[kChunk], f_lk2[kChunk], f_beta[kChunk];
+    int f_group[kChunk], f_mr[kChunk], f_lk2[kChunk], f_beta[kChunk], f_cls[kChunk];
     for (int f = 0; f < n_fmts; ++f) {
         const int lk1 = ilog2(fmts[f].k1);
         int lk2 = ilog2(fmts[f].k2), beta = (1 << fmts[f].d2) - 1;
@@ -563,18 +572,17 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
             const GroupDesc &gd = plan.grp[g];
             if (gd.lk1 != lk1 || gd.shared != shared) continue;
             for (int k = 0; k < gd.n_mr; ++k)
-                if (gd.m[k] == m && gd.rnd[k] == rnd) {
+                if (gd.m(k) == m && gd.rnd(k) == rnd) {
                     gi = g;
                     r = k;
                 }
         }
         for (int g = 0; g < ng && gi < 0; ++g) {
             GroupDesc &gd = plan.grp[g];
-            if (gd.lk1 != lk1 || gd.shared != shared || gd.n_mr == kMR) continue;
+            if (gd.lk1 != lk1 || gd.shared != shared || gd.n_mr == (shared ? kMR : kMRd)) continue;
             gi = g;
             r = gd.n_mr++;
-            gd.m[r] = (uint8_t)m;
-            gd.rnd[r] = (uint8_t)rnd;
+            gd.mr[r] = (uint8_t)(m | (rnd << 4));
         }
         if (gi < 0) {
             gi = ng++;
@@ -583,10 +591,7 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
             gd.lk1 = (uint8_t)lk1;
             gd.shared = (uint8_t)shared;
             gd.n_mr = 1;
-            for (int k = 0; k < kMR; ++k) {  // unused slots repeat slot 0
-                gd.m[k] = (uint8_t)m;
-                gd.rnd[k] = (uint8_t)rnd;
-            }
+            for (int k = 0; k < kMRd; ++k) gd.mr[k] = (uint8_t)(m | (rnd << 4));  // unused slots repeat slot 0
             r = 0;
         }
         f_group[f] = gi;
@@ -608,36 +613,55 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
             if (ci < 0) {
                 ci = n_cls++;
                 ClassDesc &cd = plan.cls[nc + ci];
+                cd = ClassDesc{};
                 cd.lk2 = (uint8_t)f_lk2[f];
                 cd.beta = (uint8_t)f_beta[f];
-                for (int k = 0; k < kMR; ++k) cd.q[k] = kNone;
             }
-            ClassDesc &cd = plan.cls[nc + ci];
-            if (cd.q[f_mr[f]] == kNone) cd.q[f_mr[f]] = (uint16_t)nq++;
-            map.idx[f] = cd.q[f_mr[f]];
+            plan.cls[nc + ci].mask |= (uint8_t)(1u << f_mr[f]);
+            f_cls[f] = nc + ci;
+        }
+        for (int c = 0; c < n_cls; ++c) {  // accumulators: class by class, requested pairs in slot order
+            plan.cls[nc + c].base = (uint16_t)nq;
+            plan.cls[nc + c].q1 = (uint16_t)(nq + (plan.cls[nc + c].mask & 1));
+            nq += __builtin_popcount(plan.cls[nc + c].mask);
         }
         gd.n_cls = (uint8_t)n_cls;
         nc += n_cls;
     }
+    for (int f = 0; f < n_fmts; ++f) map.idx[f] = (uint16_t)plan.cls[f_cls[f]].q(f_mr[f]);
     plan.n_group = ng;
     plan.n_quant = nq;
 }
 
 // One launch of the sweep kernel.  The lane-partial array needs (n_quant + 1) KiB
 // of LDS: above the default limit the kernel is allowed the full 160 KiB, once.
-template <typename T, bool ALL_RNE>
-int launch_sweep(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
-                 int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
+template <typename T, bool ALL_RNE, bool WIDE>
+int launch_sweep_w(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
+                   int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
 {
     static signed char granted[kMaxDevices];
     const size_t lds = (size_t)(plan.n_quant + 1) * kSweepThreads * sizeof(float);
     if (lds > 64 * 1024 &&
-        !grant_dynamic_lds((const void *)sweep_kernel<T, ALL_RNE>,
+        !grant_dynamic_lds((const void *)sweep_kernel<T, ALL_RNE, WIDE>,
                            (kChunk + 1) * kSweepThreads * sizeof(float), granted))
         return BDR_ERR_LAUNCH;
-    hipLaunchKernelGGL((sweep_kernel<T, ALL_RNE>), dim3(nb), dim3(kSweepThreads), lds, s, plan,
+    hipLaunchKernelGGL((sweep_kernel<T, ALL_RNE, WIDE>), dim3(nb), dim3(kSweepThreads), lds, s, plan,
                        (const T *)x, cols, ld, n_groups, blockmax, partials);
     return BDR_OK;
+}
+
+// WIDE: some directly evaluated group holds more than kMR (m, rounding) pairs.  The
+// narrow kernel is kept for the plans that do not need it (its loop over the pairs is
+// a quarter as long and the compiler's register assignment for the selecting path is
+// better without the long one next to it).
+template <typename T, bool ALL_RNE>
+int launch_sweep(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
+                 int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
+{
+    bool wide = false;
+    for (int g = 0; g < plan.n_group; ++g) wide = wide || plan.grp[g].n_mr > kMR;
+    return wide ? launch_sweep_w<T, ALL_RNE, true>(plan, nb, x, cols, ld, n_groups, blockmax, partials, s)
+                : launch_sweep_w<T, ALL_RNE, false>(plan, nb, x, cols, ld, n_groups, blockmax, partials, s);
 }
 
 }  // namespace
