@@ -13,8 +13,16 @@
  *   - The library allocates nothing, frees nothing and never synchronizes: work is
  *     enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the null
  *     stream) and the call returns at once.
- *   - Every function returns a bdr_status.  On any status other than BDR_OK nothing
- *     was launched and no output was touched.  Nothing throws or aborts.
+ *   - Every function returns a bdr_status; nothing throws or aborts.  All argument
+ *     checks, and every request for a resource a kernel needs (more than 64 KiB of
+ *     LDS per workgroup), are made before the first launch of a call: on any status
+ *     other than BDR_OK and BDR_ERR_LAUNCH nothing was launched and no output was
+ *     touched, and the same holds for a BDR_ERR_LAUNCH that comes from such a
+ *     request.  BDR_ERR_LAUNCH can also mean that the HIP runtime refused a launch
+ *     itself; in a call that enqueues several kernels (bdr_qsnr_sweep, mx_gemm with a
+ *     workspace) the earlier ones may then already be enqueued, and workspace and
+ *     outputs hold unspecified data.  A HIP error that was already pending when the
+ *     call was made is reported, and consumed, as this call's BDR_ERR_LAUNCH.
  *   - A tensor is [rows x cols], row-major, with `ld` elements between the starts
  *     of consecutive rows (ld >= cols).
  *

@@ -136,7 +136,7 @@ int bdr_gather_dequantize(const bdr_format *fmt, const void *codes, const void *
 {
     int st = check_format(fmt);
     if (st) return st;
-    if (!bdr::is_mx(*fmt)) return BDR_ERR_FORMAT;
+    if (!bdr::is_mx_layout(*fmt)) return BDR_ERR_FORMAT;
     if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
     if (table_rows < 0 || cols < 0 || n_indices < 0 || cols % 32 != 0) return BDR_ERR_SHAPE;
     if (cols > ((int64_t)1 << 24) || table_rows > ((int64_t)1 << 40) / (cols > 0 ? cols : 1) ||
@@ -243,7 +243,7 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
     if (st) return st;
     st = check_format(fb);
     if (st) return st;
-    if (!bdr::is_mx(*fa) || !bdr::is_mx(*fb)) return BDR_ERR_FORMAT;
+    if (!bdr::is_mx_layout(*fa) || !bdr::is_mx_layout(*fb)) return BDR_ERR_FORMAT;
     if (M < 0 || N < 0 || K < 0 || ldc < N) return BDR_ERR_SHAPE;
     if (K % 64 != 0) return BDR_ERR_SHAPE;
     if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;

@@ -288,15 +288,16 @@ int col_dispatch(int mode, const bdr_format &f, const T *x, T *y, uint8_t *codes
 }
 
 // The tiled kernels need whole tiles and a grid the hardware accepts.
-bool tiled_ok(const bdr_format &f, int64_t rows, int64_t cols, int tc)
+bool tiled_ok(int mode, const bdr_format &f, int64_t rows, int64_t cols, int tc)
 {
-    return is_mx(f) && rows % kTR == 0 && cols % tc == 0 && cols / tc <= 65535;
+    // dequantize (mode 1) only reads the image: the rounding rule plays no part
+    return (mode == 1 ? is_mx_layout(f) : is_mx(f)) && rows % kTR == 0 && cols % tc == 0 && cols / tc <= 65535;
 }
 
 int col_any(int mode, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
             int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
 {
-    if (!tiled_ok(f, rows, cols, dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC))
+    if (!tiled_ok(mode, f, rows, cols, dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC))
         return generic_col(mode, f, x, y, dtype, rows, cols, ld, codes, sexp, mexp, s);
     if (dtype == BDR_F32)
         return col_dispatch(mode, f, (const float *)x, (float *)y, (uint8_t *)codes,

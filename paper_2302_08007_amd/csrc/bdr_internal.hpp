@@ -8,12 +8,15 @@
 
 namespace bdr {
 
-inline bool is_mx(const bdr_format &f)
+// Table II family by layout alone: k1 16, k2 2, d1 8, d2 1; m 7, 4 or 2.  This is all
+// that reading a packed image depends on (decoding never looks at the rounding rule).
+inline bool is_mx_layout(const bdr_format &f)
 {
-    // Table II family: k1 16, k2 2, d1 8, d2 1, nearest-even; m 7, 4 or 2.
-    return f.k1 == 16 && f.k2 == 2 && f.d1 == 8 && f.d2 == 1 && f.rounding == BDR_RNE &&
-           (f.m == 7 || f.m == 4 || f.m == 2);
+    return f.k1 == 16 && f.k2 == 2 && f.d1 == 8 && f.d2 == 1 && (f.m == 7 || f.m == 4 || f.m == 2);
 }
+
+// ... and rounded to nearest even: what the specialised quantizers implement.
+inline bool is_mx(const bdr_format &f) { return is_mx_layout(f) && f.rounding == BDR_RNE; }
 
 inline int launch_status()
 {

@@ -627,9 +627,11 @@ static inline GenFmt gen_of(const bdr_format &f)
 }
 
 // The fast kernels see the tensor as one flat run of whole quads of lanes.
-static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, int64_t ld)
+// decode: reading an image does not depend on how it was rounded
+static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, int64_t ld,
+                              bool decode = false)
 {
-    return is_mx(f) && ld == cols && (rows * cols) % 32 == 0;
+    return (decode ? is_mx_layout(f) : is_mx(f)) && ld == cols && (rows * cols) % 32 == 0;
 }
 
 template <typename T>
@@ -680,7 +682,7 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
 {
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
-    if (mx_fast_ok(f, rows, cols, ld)) {
+    if (mx_fast_ok(f, rows, cols, ld, true)) {
         const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
         if (f.m == 7)
             hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});

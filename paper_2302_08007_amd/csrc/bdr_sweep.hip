@@ -635,9 +635,11 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
 
 // One launch of the sweep kernel.  The lane-partial array needs (n_quant + 1) KiB
 // of LDS: above the default limit the kernel is allowed the full 160 KiB, once.
+// dry: only make sure the launch is possible (the grant), launch nothing.
 template <typename T, bool ALL_RNE, bool WIDE>
-int launch_sweep_w(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
-                   int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
+int launch_sweep_w(const SweepPlan &plan, bool dry, unsigned nb, const void *x, int64_t cols,
+                   int64_t ld, int64_t n_groups, const uint32_t *blockmax, double *partials,
+                   hipStream_t s)
 {
     static signed char granted[kMaxDevices];
     const size_t lds = (size_t)(plan.n_quant + 1) * kSweepThreads * sizeof(float);
@@ -645,6 +647,7 @@ int launch_sweep_w(const SweepPlan &plan, unsigned nb, const void *x, int64_t co
         !grant_dynamic_lds((const void *)sweep_kernel<T, ALL_RNE, WIDE>,
                            (kChunk + 1) * kSweepThreads * sizeof(float), granted))
         return BDR_ERR_LAUNCH;
+    if (dry) return BDR_OK;
     hipLaunchKernelGGL((sweep_kernel<T, ALL_RNE, WIDE>), dim3(nb), dim3(kSweepThreads), lds, s, plan,
                        (const T *)x, cols, ld, n_groups, blockmax, partials);
     return BDR_OK;
@@ -655,13 +658,14 @@ int launch_sweep_w(const SweepPlan &plan, unsigned nb, const void *x, int64_t co
 // a quarter as long and the compiler's register assignment for the selecting path is
 // better without the long one next to it).
 template <typename T, bool ALL_RNE>
-int launch_sweep(const SweepPlan &plan, unsigned nb, const void *x, int64_t cols, int64_t ld,
-                 int64_t n_groups, const uint32_t *blockmax, double *partials, hipStream_t s)
+int launch_sweep(const SweepPlan &plan, bool dry, unsigned nb, const void *x, int64_t cols,
+                 int64_t ld, int64_t n_groups, const uint32_t *blockmax, double *partials,
+                 hipStream_t s)
 {
     bool wide = false;
     for (int g = 0; g < plan.n_group; ++g) wide = wide || plan.grp[g].n_mr > kMR;
-    return wide ? launch_sweep_w<T, ALL_RNE, true>(plan, nb, x, cols, ld, n_groups, blockmax, partials, s)
-                : launch_sweep_w<T, ALL_RNE, false>(plan, nb, x, cols, ld, n_groups, blockmax, partials, s);
+    return wide ? launch_sweep_w<T, ALL_RNE, true>(plan, dry, nb, x, cols, ld, n_groups, blockmax, partials, s)
+                : launch_sweep_w<T, ALL_RNE, false>(plan, dry, nb, x, cols, ld, n_groups, blockmax, partials, s);
 }
 
 }  // namespace
@@ -682,33 +686,52 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
     if (nb > kSweepBlocks) nb = kSweepBlocks;
     if (nb < 1) nb = 1;
 
+    // Chunks of formats run one after the other on the stream and reuse the
+    // partial-sum area; each launch gets its own copy of the plan by value.  The first
+    // walk over the chunks builds the plans and launches nothing: it only settles whether
+    // every launch of the second walk can be made (kernels that need more than 64 KiB of
+    // LDS have to be given that limit once per device), so a refusal is reported before
+    // anything is enqueued.
+    constexpr int kMaxChunks = (1024 + kChunk - 1) / kChunk;  // the entry point takes <= 1024 formats
+    SweepPlan plans[kMaxChunks];
+    FormatMap maps[kMaxChunks];
+    if (n_fmts > kMaxChunks * kChunk) return BDR_ERR_SHAPE;
+    auto chunk_launch = [&](int c, bool dry) {
+        const int32_t f0 = c * kChunk;
+        const int nf = n_fmts - f0 < kChunk ? n_fmts - f0 : kChunk;
+        bool all_rne = true;
+        for (int f = 0; f < nf; ++f) all_rne = all_rne && fmts[f0 + f].rounding == BDR_RNE;
+        const SweepPlan &plan = plans[c];
+        if (dtype == BDR_F32)
+            return all_rne ? launch_sweep<float, true>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
+                           : launch_sweep<float, false>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
+        return all_rne ? launch_sweep<uint16_t, true>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
+                       : launch_sweep<uint16_t, false>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
+    };
+    const int n_chunks = (n_fmts + kChunk - 1) / kChunk;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int32_t f0 = c * kChunk;
+        const int nf = n_fmts - f0 < kChunk ? n_fmts - f0 : kChunk;
+        plans[c] = SweepPlan{};
+        maps[c] = FormatMap{};
+        make_plan(fmts + f0, nf, plans[c], maps[c]);
+        const int st = chunk_launch(c, true);
+        if (st != BDR_OK) return st;
+    }
     if (dtype == BDR_F32)
         hipLaunchKernelGGL(sweep_absmax_kernel<float>, dim3(kAbsBlocks), dim3(256), 0, s,
                            (const float *)x, cols, ld, n_groups, blockmax);
     else
         hipLaunchKernelGGL(sweep_absmax_kernel<uint16_t>, dim3(kAbsBlocks), dim3(256), 0, s,
                            (const uint16_t *)x, cols, ld, n_groups, blockmax);
-    // Chunks of formats run one after the other on the stream and reuse the
-    // partial-sum area; each launch gets its own copy of the plan by value.
-    for (int32_t f0 = 0; f0 < n_fmts; f0 += kChunk) {
+    for (int c = 0; c < n_chunks; ++c) {
+        const int32_t f0 = c * kChunk;
         const int nf = n_fmts - f0 < kChunk ? n_fmts - f0 : kChunk;
-        SweepPlan plan{};
-        FormatMap map{};
-        make_plan(fmts + f0, nf, plan, map);
-        const int nq = plan.n_quant;
-        bool all_rne = true;
-        for (int f = 0; f < nf; ++f) all_rne = all_rne && fmts[f0 + f].rounding == BDR_RNE;
-        int st;
-        if (dtype == BDR_F32)
-            st = all_rne ? launch_sweep<float, true>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
-                         : launch_sweep<float, false>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
-        else
-            st = all_rne ? launch_sweep<uint16_t, true>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
-                         : launch_sweep<uint16_t, false>(plan, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
-        if (st != BDR_OK) return st;
-        hipLaunchKernelGGL(sweep_finalize_kernel, dim3((unsigned)(nf + 1)), dim3(256), 0, s, map,
-                           nf, nq, (int32_t)nb, blockmax, partials, qsnr_db + f0, sums + f0,
-                           sums + n_fmts);
+        const int st = chunk_launch(c, false);
+        if (st != BDR_OK) return st;  // not reached: the first walk settled it
+        hipLaunchKernelGGL(sweep_finalize_kernel, dim3((unsigned)(nf + 1)), dim3(256), 0, s, maps[c],
+                           nf, plans[c].n_quant, (int32_t)nb, blockmax, partials, qsnr_db + f0,
+                           sums + f0, sums + n_fmts);
     }
     return launch_status();
 }

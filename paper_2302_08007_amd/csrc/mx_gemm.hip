@@ -642,11 +642,12 @@ int gemm_dl(const void *A, const void *B, int64_t M, int64_t N, int pitch, float
     return launch_dl<2, 2, 2, 2, FP6>(a, b, (int)M, (int)N, pitch, C, ldc, s);
 }
 
+// K = 0: one workgroup per row of C (rows on grid.x, which takes up to 2^31 - 1 workgroups;
+// grid.y stops at 65535 and M may be 2^20).
 __global__ void gemm_zero_kernel(float *C, int64_t ldc, int N)
 {
-    const int64_t row = blockIdx.y;
-    for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < N; c += gridDim.x * blockDim.x)
-        C[row * ldc + c] = 0.f;
+    const int64_t row = blockIdx.x;
+    for (int c = threadIdx.x; c < N; c += blockDim.x) C[row * ldc + c] = 0.f;
 }
 
 }  // namespace
@@ -656,7 +657,7 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
          int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s)
 {
     if (K == 0) {  // empty sum
-        hipLaunchKernelGGL(gemm_zero_kernel, dim3(4, (unsigned)M), dim3(256), 0, s, C, ldc, (int)N);
+        hipLaunchKernelGGL(gemm_zero_kernel, dim3((unsigned)M), dim3(256), 0, s, C, ldc, (int)N);
         return launch_status();
     }
     const uint8_t *ac = (const uint8_t *)a_codes, *as = (const uint8_t *)a_sexp,

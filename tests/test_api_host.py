@@ -146,6 +146,26 @@ def test_sweep_and_gemm_argument_checks():
     assert gm(ws=FAKE_ODD, wsb=need) == ERR_ALIGN
 
 
+def test_resources_are_asked_for_before_the_first_launch():
+    # A sweep of more than 63 distinct quantizers needs more than 64 KiB of LDS per workgroup,
+    # which a kernel has to be granted once per device.  That request is made for every chunk of
+    # the format list before the first kernel of the call is enqueued; without a device it is
+    # refused, and the call must come back with BDR_ERR_LAUNCH from that request.
+    import torch
+    if torch.cuda.device_count() > 0:
+        pytest.skip("needs a machine without a GPU: with one, the placeholder pointers would be used")
+    fmts = [B.fmt(k1, k2, 1, m) for k1 in (16, 32, 64) for k2 in (1, 2, 4) for m in range(1, 9)]
+    assert len(fmts) == 72
+    arr = (B.Format * len(fmts))(*fmts)
+    need = B.lib.bdr_qsnr_sweep_workspace_bytes(len(fmts))
+    assert B.lib.bdr_qsnr_sweep(arr, len(fmts), FAKE, 0, 4, 64, 64, FAKE, FAKE, FAKE, need, NULL) == ERR_LAUNCH
+    # ... also when only the last chunk of a long list needs it
+    small = [B.MX6] * 128 + fmts
+    arr = (B.Format * len(small))(*small)
+    need = B.lib.bdr_qsnr_sweep_workspace_bytes(len(small))
+    assert B.lib.bdr_qsnr_sweep(arr, len(small), FAKE, 0, 4, 64, 64, FAKE, FAKE, FAKE, need, NULL) == ERR_LAUNCH
+
+
 def test_tile_packing_of_the_paper_formats():
     # Sec. IV-B "Memory Footprint": a 256-element tile into a 64-byte interface.  Table II gives
     # 9 / 6 / 4 bits per element, so the tile is 288 / 192 / 128 bytes: 5 / 3 / 2 transfers,

@@ -55,6 +55,27 @@ def test_out_of_range_indices_give_zero_rows_and_nothing_else_is_touched():
     assert torch.all(buf[0] == 7.0) and torch.all(buf[-1] == 7.0)
 
 
+@pytest.mark.parametrize("rounding", [B.RNA, B.RTZ])
+def test_tables_rounded_another_way(rounding):
+    # a lookup only decodes: a table quantized with ties-away or truncation is read like any
+    # other, by the same kernels (the rounding rule is not part of the stored image)
+    rows, cols = 200, 96
+    f = B.fmt(16, 2, 1, 4, rounding=rounding)
+    x = _table(rows, cols, 17)
+    planes = B.bdr_quantize(f, x)
+    idx = torch.randint(0, rows, (333,), device="cuda", dtype=torch.int64,
+                        generator=torch.Generator(device="cuda").manual_seed(5))
+    y = B.bdr_gather_dequantize(f, planes, rows, cols, idx)
+    full = O.dequantize(ofmt(f), *[p.cpu().numpy() for p in planes], rows, cols)
+    assert_bits_equal(y, full[idx.cpu().numpy()], "rounding %d" % rounding)
+    # the planes themselves are the oracle's for that rounding rule, and differ from nearest-even
+    want = O.quantize(ofmt(f), to_np(x))
+    assert all(np.array_equal(p.cpu().numpy(), w) for p, w in zip(planes, want))
+    assert not torch.equal(planes[0], B.bdr_quantize(B.MX6, x)[0])
+    # the row-wise dequantize of such an image takes the same path
+    assert_bits_equal(B.bdr_dequantize(f, planes, rows, cols), full, "dequantize")
+
+
 def test_identity_gather_equals_dequantize_and_empty():
     rows, cols = 256, 256
     f = B.MX9

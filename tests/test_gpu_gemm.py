@@ -128,6 +128,80 @@ def test_two_pass_fp6_form_reproduces_every_element(name, side):
         assert torch.equal(torch.signbit(C[keep & (Xh != 0)]), torch.signbit(want[keep & (Xh != 0)]))
 
 
+@pytest.mark.parametrize("name", ["MX9", "MX6", "MX4"])
+@pytest.mark.parametrize("form", ["single kernel", "two-pass"])
+def test_bf16_forms_reproduce_every_element_down_to_the_lowest_exponent(name, form):
+    # The BF16 forms (single kernel for every format; two-pass for MX9 and mixed pairs) expand an
+    # element to BF16.  In a block whose exponent code is small the elements are BF16 subnormals
+    # (below 2^-126), which the matrix cores of this chip take as they are: one operand is 2^s
+    # times the identity, so every entry of C is a single product and must equal 2^s times the
+    # dequantized element of the other operand, bit for bit, for block exponents from code 1 up.
+    f = getattr(B, name)
+    other = B.MX9                       # keeps the pair on the BF16 path in the two-pass form too
+    rows, K = 256, 256
+    g = torch.Generator(device="cuda").manual_seed(13)
+    X = torch.randn(rows, K, generator=g, device="cuda")
+    X = X * torch.exp2(torch.randint(-3, 4, X.shape, generator=g, device="cuda").float())
+    blk_exp = torch.tensor([-126.0, -125.0, -124.0, -122.0, -119.0, -60.0, 0.0, 60.0], device="cuda")
+    pick = torch.randint(0, len(blk_exp), (rows, K // 16), generator=g, device="cuda")
+    X = X.view(rows, K // 16, 16)
+    X = X / X.abs().amax(dim=2, keepdim=True) * 1.9
+    X = (X * torch.exp2(blk_exp[pick]).unsqueeze(2)).view(rows, K).contiguous()
+    X[:, 16:32] = 0.0
+    px = B.bdr_quantize(f, X)
+    assert int(px[1].min()) == 1 and int(px[1].max()) >= 127 + 60
+    Xh = B.bdr_dequantize(f, px, rows, K)
+    assert int(((Xh != 0) & (Xh.abs() < 2.0 ** -126)).sum()) > 1000     # BF16 subnormals are there
+    for s in (40.0, 0.0, -40.0):
+        keep = (Xh == 0) | ((Xh.abs() * 2.0 ** s >= 2.0 ** -126) & (Xh.abs() * 2.0 ** s < 2.0 ** 127))
+        I = torch.eye(K, device="cuda") * 2.0 ** s
+        pi = B.bdr_quantize(other, I)
+        ws = _workspace(max(rows, K), max(rows, K), K) if form == "two-pass" else None
+        for side in ("A", "B"):
+            if side == "A":
+                C = B.mx_gemm(f, other, px, pi, rows, K, K, workspace=ws)
+            else:
+                C = B.mx_gemm(other, f, pi, px, K, rows, K, workspace=ws).t()
+            want = Xh * 2.0 ** s
+            assert torch.equal(C[keep], want[keep]), (name, form, side, s)
+            nz = keep & (Xh != 0)
+            assert torch.equal(torch.signbit(C[nz]), torch.signbit(want[nz]))
+
+
+@pytest.mark.parametrize("ws", [False, True])
+def test_operands_rounded_another_way_decode_the_same(ws):
+    # reading a packed image never depends on the rounding rule it was made with: images
+    # quantized with ties-away or truncation multiply like any other (Sec. III: the rule is
+    # part of the quantizer, not of the stored format)
+    M, N, K = 128, 256, 128
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=77)
+    for fa, fb in ((B.fmt(16, 2, 1, 4, rounding=B.RNA), B.fmt(16, 2, 1, 7, rounding=B.RTZ)),
+                   (B.fmt(16, 2, 1, 2, rounding=B.RTZ), B.fmt(16, 2, 1, 4, rounding=B.RNA))):
+        pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
+        w = _workspace(M, N, K) if ws else None
+        C = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=w)
+        torch.cuda.synchronize()
+        pan, pbn = _planes_np(pa), _planes_np(pb)
+        Cref = O.mx_gemm(ofmt(fa), ofmt(fb), pan, pbn, M, N, K)
+        Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
+        Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
+        err = np.abs(C.cpu().numpy().astype(np.float64) - Cref)
+        assert np.all(err <= RTOL * (np.abs(Ah) @ np.abs(Bh).T) + 1e-30)
+        # the same call with the rounding field set to nearest-even gives the same bits
+        fa0, fb0 = B.fmt(16, 2, 1, fa.m), B.fmt(16, 2, 1, fb.m)
+        assert torch.equal(C, B.mx_gemm(fa0, fb0, pa, pb, M, N, K, workspace=w))
+
+
+def test_empty_k_with_many_rows():
+    # K = 0 is an empty sum: C is all zeros, also when M is above what one grid axis takes
+    M, N = 70000, 24
+    C = torch.full((M, N + 8), 5.0, device="cuda")
+    f = B.MX6
+    e = torch.empty(0, dtype=torch.uint8, device="cuda")
+    B.mx_gemm(f, f, (e, e, e), (e, e, e), M, N, 0, out=C[:, :N])
+    assert torch.count_nonzero(C[:, :N]) == 0 and torch.all(C[:, N:] == 5.0)
+
+
 def test_wide_exponent_range_and_signs():
     A = S.wide_range(128, 256, device="cuda", seed=41, spread=8)
     Bm = S.wide_range(256, 256, device="cuda", seed=42, spread=8)

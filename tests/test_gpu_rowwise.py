@@ -170,6 +170,37 @@ def test_bandwidth_config_full_size_sampled_rows():
         del planes, y, p2, se, bound, sat
 
 
+def test_activation_config_full_size_sampled_rows():
+    # 8192 x 12288 bf16 with channel outliers, the activation-shaped bench configuration, along
+    # rows (the forward operand layout, Sec. V): MX9 / MX6 / MX4 through the BF16 row kernels at
+    # the launch shape the bench times.  The oracle quantizes sampled 64-row bands (first, last,
+    # four random ones); every byte of their planes and every dequantized BF16 value is compared.
+    x = S.activation(device="cuda")
+    rows, cols = x.shape
+    assert (rows, cols) == (8192, 12288) and x.dtype == torch.bfloat16
+    rng = np.random.default_rng(2)
+    bands = sorted(set([0, rows - 64] + [int(v) * 64 for v in rng.integers(0, rows // 64, 4)]))
+    for name in MX:
+        f = _fmt(name)
+        planes = B.bdr_quantize(f, x)
+        y = B.bdr_dequantize(f, planes, rows, cols, dtype=torch.bfloat16)
+        y2 = B.bdr_quantize_dequantize(f, x)
+        torch.cuda.synchronize()
+        per_row = [cols * (f.m + 1) // 8, cols // 16, cols // 16]
+        for r0 in bands:
+            want = O.quantize(ofmt(f), to_np(x[r0:r0 + 64]))
+            got = [p[r0 * n:(r0 + 64) * n] for p, n in zip(planes, per_row)]
+            assert_planes_equal(got, want, "%s bf16 rows %d.." % (name, r0))
+            ywant = O.dequantize(ofmt(f), *want, 64, cols, out_dtype=np.uint16)
+            assert_bits_equal(y[r0:r0 + 64], ywant, "%s bf16 dequantize rows %d.." % (name, r0))
+            assert_bits_equal(y2[r0:r0 + 64], ywant, "%s bf16 fused rows %d.." % (name, r0))
+        # whole tensor: fused = quantize then dequantize, and the result is a fixed point
+        assert torch.equal(y2.view(torch.int16), y.view(torch.int16)), name
+        p2 = B.bdr_quantize(f, y)
+        assert all(torch.equal(a, b) for a, b in zip(planes, p2)), name
+        del planes, y, y2, p2
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_more_than_four_gibi_elements(dtype):
     # 2^32 + 2^18 elements: every element index, byte offset and plane offset passes 2^32.

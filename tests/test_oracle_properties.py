@@ -131,5 +131,7 @@ def test_theorem1_lower_bound(data):
     beta = (1 << f.d2) - 1
     bound = 6.02 * f.m + 10 * math.log10(4.0 ** beta / (min(cols, f.k1) + (4.0 ** beta - 1) * f.k2))
     # elements that round up into the top code are held there (reading R3) and may miss the
-    # per-element bound by one step; the aggregate bound has 6.02 (< 20 log10 2) of slack per bit
-    assert q[0] >= bound - 1.0
+    # per-element bound by one step, but such elements carry four times the signal power the
+    # proof assumes, so the aggregate bound holds as printed: no slack (the smallest margin over
+    # thousands of random formats on this recipe is above 2 dB)
+    assert q[0] >= bound
