@@ -1,6 +1,7 @@
 """Compile the HIP sources under csrc/ for gfx950 into paper_2302_08007_amd/libbdr_mx.so.
 
-hipcc cross-compiles without a GPU.  Run as ``python -m paper_2302_08007_amd.build``.
+hipcc cross-compiles without a GPU.  Run as ``python paper_2302_08007_amd/build.py`` (as a
+script: importing the package needs the library this builds).
 """
 import os
 import subprocess
