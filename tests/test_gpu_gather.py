@@ -71,7 +71,8 @@ def test_tables_rounded_another_way(rounding):
     # the planes themselves are the oracle's for that rounding rule, and differ from nearest-even
     want = O.quantize(ofmt(f), to_np(x))
     assert all(np.array_equal(p.cpu().numpy(), w) for p, w in zip(planes, want))
-    assert not torch.equal(planes[0], B.bdr_quantize(B.MX6, x)[0])
+    if rounding == B.RTZ:       # ties-away differs from ties-to-even only on exact ties
+        assert not torch.equal(planes[0], B.bdr_quantize(B.MX6, x)[0])
     # the row-wise dequantize of such an image takes the same path
     assert_bits_equal(B.bdr_dequantize(f, planes, rows, cols), full, "dequantize")
 
