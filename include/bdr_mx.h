@@ -182,9 +182,10 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *            bits as each other).
  * K must be a multiple of 64 and M, N, K at most 2^20 each, else BDR_ERR_SHAPE; M and N
  * are free (tiles that hang over the edge of C cost as much as full ones: multiples of 256,
- * else of 128, waste nothing).  M = 0 or N = 0 launches nothing; K = 0 writes zeros.  Inf/NaN
- * codes, blocks whose exponent code is so low that an element is a BF16
- * subnormal, and sums that are FP32 subnormals are outside the supported domain. */
+ * else of 128, waste nothing).  M = 0 or N = 0 launches nothing; K = 0 writes zeros.  Block
+ * exponent codes from 1 up are exact in every form: the matrix cores take BF16 subnormals
+ * (elements of blocks with the lowest codes) as they are.  Inf/NaN codes and sums that are
+ * FP32 subnormals are outside the supported domain. */
 int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
             const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,
