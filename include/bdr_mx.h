@@ -151,6 +151,26 @@ int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dt
                    int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
                    size_t workspace_bytes, void *hip_stream);
 
+/* bdr_qsnr_sweep for callers that cannot allocate device memory and have no workspace
+ * to bring: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same kernels, same results bit for
+ * bit; the scratch is a fixed array of bdr_qsnr_sweep_static_scratch_bytes() bytes
+ * (under 1 MiB) that is part of the library's device image: every GPU the library runs
+ * on holds one until the process ends.  Nothing is allocated or freed, by this call
+ * or by anything it calls, and the scratch needs no clearing between calls.  The
+ * limit is the one of bdr_qsnr_sweep: 1 <= n_fmts <= 1024, else BDR_ERR_SHAPE
+ * (longer lists reuse the array chunk by chunk, so the tensor and the list may have
+ * any size the other entry point takes).  All calls on one GPU share that GPU's
+ * array: calls that overlap in time on one GPU (two streams, two host threads) race
+ * on it and give undefined sums; order them on one stream.  BDR_ERR_LAUNCH when the
+ * array's address cannot be resolved on the current device. */
+int bdr_qsnr_sweep_static(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
+                          int64_t rows, int64_t cols, int64_t ld, double *qsnr_db, double *sums,
+                          void *hip_stream);
+
+/* Host only.  Size of the fixed scratch array bdr_qsnr_sweep_static works in. */
+size_t bdr_qsnr_sweep_static_scratch_bytes(void);
+
 /* Host only.  Bytes of device workspace with which mx_gemm runs in its two-pass
  * form: (M + N) * K BF16 values, each operand rounded up to 256 bytes (the FP6 block
  * images need half of that).  0 when a size is negative or above 2^20. */

@@ -22,7 +22,8 @@ EXPORTS = (
     "bdr_status_string", "bdr_format_validate", "bdr_packed_sizes", "bdr_quantize",
     "bdr_dequantize", "bdr_gather_dequantize", "bdr_tile_packing", "bdr_quantize_dequantize",
     "bdr_qsnr_sweep_workspace_bytes",
-    "bdr_qsnr_sweep", "mx_gemm_workspace_bytes", "mx_gemm",
+    "bdr_qsnr_sweep", "bdr_qsnr_sweep_static", "bdr_qsnr_sweep_static_scratch_bytes",
+    "mx_gemm_workspace_bytes", "mx_gemm",
 )
 
 
@@ -55,7 +56,7 @@ class BdrError(RuntimeError):
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            "%s is missing: build it with `python -m paper_2302_08007_amd.build` "
+            "%s is missing: build it with `python paper_2302_08007_amd/build.py` "
             "(there is no fallback path)" % LIB_PATH)
     L = ctypes.CDLL(LIB_PATH)
     P, I32, I64, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
@@ -72,6 +73,9 @@ def _load():
     L.bdr_qsnr_sweep_workspace_bytes.argtypes = [I32]
     L.bdr_qsnr_sweep_workspace_bytes.restype = SZ
     L.bdr_qsnr_sweep.argtypes = [FP, I32, P, I32, I64, I64, I64, P, P, P, SZ, P]
+    L.bdr_qsnr_sweep_static.argtypes = [FP, I32, P, I32, I64, I64, I64, P, P, P]
+    L.bdr_qsnr_sweep_static_scratch_bytes.argtypes = []
+    L.bdr_qsnr_sweep_static_scratch_bytes.restype = SZ
     L.mx_gemm_workspace_bytes.argtypes = [I64, I64, I64]
     L.mx_gemm_workspace_bytes.restype = SZ
     L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P, SZ, P]
@@ -198,6 +202,20 @@ def bdr_qsnr_sweep(fmts, x, workspace=None, out=None):
     _check_buffer("workspace", workspace, torch.uint8, 0)
     _check(lib.bdr_qsnr_sweep(arr, n, _p(x), _dtype_code(x), rows, cols, ld, _p(out[0]),
                               _p(out[1]), _p(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def bdr_qsnr_sweep_static(fmts, x, out):
+    """bdr_qsnr_sweep without a workspace: the library's own fixed scratch array is used and
+    nothing is allocated, so `out` = (qsnr_db[n], sums[n+1]) float64 tensors must be given.
+    Calls that overlap in time on one GPU race on that array."""
+    rows, cols, ld = _dev2d(x)
+    n = len(fmts)
+    arr = (Format * max(n, 1))(*fmts)
+    _check_buffer("qsnr_db", out[0], torch.float64, n)
+    _check_buffer("sums", out[1], torch.float64, n + 1)
+    _check(lib.bdr_qsnr_sweep_static(arr, n, _p(x), _dtype_code(x), rows, cols, ld, _p(out[0]),
+                                     _p(out[1]), _stream()))
     return out
 
 

@@ -198,9 +198,9 @@ size_t bdr_qsnr_sweep_workspace_bytes(int32_t n_fmts)
     return bdr::sweep_workspace_bytes(n_fmts);
 }
 
-int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
-                   int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
-                   size_t workspace_bytes, void *hip_stream)
+// Argument checks shared by the two sweep entry points: formats and outputs ...
+static int check_sweep_head(const bdr_format *fmts, int32_t n_fmts, int dtype, int64_t rows,
+                            int64_t cols, int64_t ld, const double *qsnr_db, const double *sums)
 {
     if (!fmts) return BDR_ERR_NULL;
     if (n_fmts < 1 || n_fmts > 1024) return BDR_ERR_SHAPE;
@@ -211,16 +211,45 @@ int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dt
         if (st) return st;
     }
     if (!qsnr_db || !sums) return BDR_ERR_NULL;
-    if (!workspace || workspace_bytes < bdr::sweep_workspace_bytes(n_fmts)) return BDR_ERR_WORKSPACE;
-    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(qsnr_db) & 7u) ||
-        (reinterpret_cast<uintptr_t>(sums) & 7u))
+    return BDR_OK;
+}
+
+// ... then alignment and the tensor.
+static int check_sweep_tail(const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                            const double *qsnr_db, const double *sums)
+{
+    if ((reinterpret_cast<uintptr_t>(qsnr_db) & 7u) || (reinterpret_cast<uintptr_t>(sums) & 7u))
         return BDR_ERR_ALIGN;
-    if (rows > 0 && cols > 0) {
-        int st = check_tensor_ptr(x, dtype, ld);
-        if (st) return st;
-    }
+    if (rows > 0 && cols > 0) return check_tensor_ptr(x, dtype, ld);
+    return BDR_OK;
+}
+
+int bdr_qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+                   int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
+                   size_t workspace_bytes, void *hip_stream)
+{
+    int st = check_sweep_head(fmts, n_fmts, dtype, rows, cols, ld, qsnr_db, sums);
+    if (st) return st;
+    if (!workspace || workspace_bytes < bdr::sweep_workspace_bytes(n_fmts)) return BDR_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return BDR_ERR_ALIGN;
+    st = check_sweep_tail(x, dtype, rows, cols, ld, qsnr_db, sums);
+    if (st) return st;
     return bdr::qsnr_sweep(fmts, n_fmts, x, dtype, rows, cols, ld, qsnr_db, sums, workspace,
                            static_cast<hipStream_t>(hip_stream));
+}
+
+size_t bdr_qsnr_sweep_static_scratch_bytes(void) { return bdr::sweep_static_scratch_bytes(); }
+
+int bdr_qsnr_sweep_static(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
+                          int64_t rows, int64_t cols, int64_t ld, double *qsnr_db, double *sums,
+                          void *hip_stream)
+{
+    int st = check_sweep_head(fmts, n_fmts, dtype, rows, cols, ld, qsnr_db, sums);
+    if (st) return st;
+    st = check_sweep_tail(x, dtype, rows, cols, ld, qsnr_db, sums);
+    if (st) return st;
+    return bdr::qsnr_sweep_static(fmts, n_fmts, x, dtype, rows, cols, ld, qsnr_db, sums,
+                                  static_cast<hipStream_t>(hip_stream));
 }
 
 static size_t gemm_ws_half(int64_t rows, int64_t K)

@@ -75,6 +75,11 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
                int64_t cols, int64_t ld, double *qsnr_db, double *sums, void *workspace,
                hipStream_t s);
 
+// The same with the library's own fixed scratch array (no workspace argument, nothing allocated).
+size_t sweep_static_scratch_bytes();
+int qsnr_sweep_static(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+                      int64_t cols, int64_t ld, double *qsnr_db, double *sums, hipStream_t s);
+
 int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,
          const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
          int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);

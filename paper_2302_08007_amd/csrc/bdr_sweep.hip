@@ -33,6 +33,8 @@
 // 256 elements per lane the partials are folded, in a fixed order, into FP64
 // sums held by the workgroup, and workgroups are combined in FP64 in a fixed
 // order as well, so results are reproducible.
+#include <atomic>
+
 #include "bdr_device.hpp"
 #include "bdr_internal.hpp"
 
@@ -734,6 +736,43 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
                            sums + f0, sums + n_fmts);
     }
     return launch_status();
+}
+
+// ---------------------------------------------------------------- no workspace
+//
+// Scratch of the entry point that takes no workspace: a fixed array in device memory
+// (every GPU the library runs on holds its own copy until the process ends), large
+// enough for one launch of kChunk formats; longer format lists reuse it chunk by
+// chunk, exactly as they reuse a caller's workspace.  In host code the array's name
+// is only a handle: its device address is looked up once per device and that
+// address is what the kernels are given.
+constexpr size_t kStaticScratchBytes =
+    kHeaderBytes + (size_t)kSweepBlocks * (size_t)(kChunk + 1) * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t sweep_static_scratch_bytes() { return kStaticScratchBytes; }
+
+int qsnr_sweep_static(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype, int64_t rows,
+                      int64_t cols, int64_t ld, double *qsnr_db, double *sums, hipStream_t s)
+{
+    static_assert(kStaticScratchBytes % 256 == 0, "scratch size");
+    static std::atomic<void *> resolved[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();
+        return BDR_ERR_LAUNCH;
+    }
+    void *ptr = dev < kMaxDevices ? resolved[dev].load(std::memory_order_acquire) : nullptr;
+    if (!ptr) {
+        // two host threads that race here look up the same address
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return BDR_ERR_LAUNCH;
+        }
+        if (dev < kMaxDevices) resolved[dev].store(ptr, std::memory_order_release);
+    }
+    if (sweep_workspace_bytes(n_fmts) > kStaticScratchBytes) return BDR_ERR_WORKSPACE;
+    return qsnr_sweep(fmts, n_fmts, x, dtype, rows, cols, ld, qsnr_db, sums, ptr, s);
 }
 
 }  // namespace bdr

@@ -129,6 +129,13 @@ def test_sweep_and_gemm_argument_checks():
     assert sw(ws=NULL) == ERR_WS and sw(wsb=need - 1) == ERR_WS
     assert sw(x=NULL) == ERR_NULL
     assert sw(s=FAKE_ODD) == ERR_ALIGN
+    # the entry point without a workspace checks the same things (its limit on n_fmts included)
+    st = lambda n=2, x=FAKE, cols=64, q=FAKE, s=FAKE: L.bdr_qsnr_sweep_static(
+        arr, n, x, 0, 4, cols, cols, q, s, NULL)
+    assert st(n=0) == ERR_SHAPE and st(n=1025) == ERR_SHAPE and st(cols=32) == ERR_SHAPE
+    assert st(q=NULL) == ERR_NULL and st(x=NULL) == ERR_NULL and st(s=FAKE_ODD) == ERR_ALIGN
+    assert L.bdr_qsnr_sweep_static(None, 2, FAKE, 0, 4, 64, 64, FAKE, FAKE, NULL) == ERR_NULL
+    assert 0 < L.bdr_qsnr_sweep_static_scratch_bytes() <= 1 << 20
     f = B.MX6
     gm = lambda fa=f, fb=f, M=128, N=128, K=64, C=FAKE, ldc=128, a=FAKE, ws=NULL, wsb=0: L.mx_gemm(
         ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, C, ldc, ws,
@@ -210,6 +217,7 @@ def test_header_is_plain_c(tmp_path):
         "                   (void *)bdr_quantize, (void *)bdr_dequantize, (void *)bdr_gather_dequantize,\n"
         "                   (void *)bdr_tile_packing, (void *)bdr_quantize_dequantize,\n"
         "                   (void *)bdr_qsnr_sweep_workspace_bytes, (void *)bdr_qsnr_sweep,\n"
+        "                   (void *)bdr_qsnr_sweep_static, (void *)bdr_qsnr_sweep_static_scratch_bytes,\n"
         "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm};\n"
         "    (void)fns;\n"
         "    return bdr_packed_sizes(&mx9, 4, 64, BDR_AXIS_ROW, &a, &b, &c) + mx6.m + mx4.m;\n"
