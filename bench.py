@@ -8,9 +8,12 @@ FP32 (six kernels).  The headline value is the algorithmic traffic of a step div
 wall time: 2 * n * (4 + bits/8) bytes per format.
 
 Prints ONE JSON line.  Besides the contract keys it carries
-  roofline      HBM roofline of the dominant kernel (the MX6 quantize), timed with device
-                events around each of its launches inside the timed region;
-  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload;
+  roofline      HBM roofline of the dominant kernel of the step -- the one with the largest
+                share of the timed region, found from device events around every launch inside
+                that region (it is the MX9 dequantize) -- and, under `kernels`, the same figures
+                for all six, with `frac_min` the lowest of them;
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload, on all host
+                threads it may use and on one;
   other         separately timed legs: fused round trip, QSNR sweep, column-wise quantize,
                 mx_gemm (whatever the library implements), not part of `value`.
 """
@@ -35,9 +38,10 @@ def alg_bytes(n, bits, elem_bytes=4):
     return n * (elem_bytes + bits / 8.0)
 
 
-def cpu_baseline(sample_elems, threads):
+def cpu_baseline(sample_elems, threads, single_sample_elems):
     """The oracle as it stands, on the first `sample_elems` of the same tensor recipe, the same
-    step (quantize + dequantize for MX9, MX6, MX4), rows split over `threads` host threads."""
+    step (quantize + dequantize for MX9, MX6, MX4), rows split over `threads` host threads; then
+    the same on one thread over a smaller prefix."""
     from concurrent.futures import ThreadPoolExecutor
 
     import numpy as np
@@ -46,9 +50,6 @@ def cpu_baseline(sample_elems, threads):
     import synth_inputs as S
 
     x = S.bandwidth(sample_elems, COLS, device="cpu").numpy()
-    rows = x.shape[0]
-    parts = [x[i * rows // threads:(i + 1) * rows // threads] for i in range(threads)]
-    parts = [np.ascontiguousarray(p) for p in parts if p.shape[0]]
     fmts = (O.MX9, O.MX6, O.MX4)
 
     def work(p):
@@ -56,17 +57,37 @@ def cpu_baseline(sample_elems, threads):
             planes = O.quantize(f, p)
             O.dequantize(f, *planes, *p.shape)
 
+    def run(xs, nthreads):
+        rows = xs.shape[0]
+        parts = [xs[i * rows // nthreads:(i + 1) * rows // nthreads] for i in range(nthreads)]
+        parts = [np.ascontiguousarray(p) for p in parts if p.shape[0]]
+        t0 = time.perf_counter()
+        if len(parts) == 1:
+            work(parts[0])
+        else:
+            with ThreadPoolExecutor(max_workers=len(parts)) as ex:
+                list(ex.map(work, parts))
+        dt = time.perf_counter() - t0
+        nbytes = sum(2 * alg_bytes(xs.size, b) for b in (9, 6, 4))
+        return nbytes / dt / 1e9, dt, len(parts)
+
     O.lib()
-    t0 = time.perf_counter()
-    with ThreadPoolExecutor(max_workers=len(parts)) as ex:
-        list(ex.map(work, parts))
-    dt = time.perf_counter() - t0
-    nbytes = sum(2 * alg_bytes(sample_elems, b) for b in (9, 6, 4))
+    v, dt, used = run(x, threads)
+    v1, dt1, _ = run(x[:single_sample_elems // COLS], 1)
     return {
-        "value": nbytes / dt / 1e9, "unit": "GB/s", "cores": len(parts), "kind": "oracle",
+        "value": round(v, 3), "unit": "GB/s", "cores": used, "kind": "oracle",
         "sample": "first %d elements of the same tensor recipe, same step (MX9+MX6+MX4 quantize"
-                  " and dequantize), %.1f s wall" % (sample_elems, dt),
+                  " and dequantize), %.1f s wall on %d threads" % (sample_elems, dt, used),
+        "host_cores": os.cpu_count(),
+        "single_thread": {"value": round(v1, 3), "unit": "GB/s", "cores": 1,
+                          "sample": "first %d elements, %.1f s wall" % (single_sample_elems, dt1)},
     }
+
+
+def median(v):
+    v = sorted(v)
+    n = len(v)
+    return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
 
 
 def main():
@@ -77,6 +98,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other", action="store_true", help="skip the separately timed legs")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
+    ap.add_argument("--cpu-single-sample", type=int, default=1 << 24)
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a 1 GiB tensor copy and one launch of each row-wise MX kernel, "
                          "three times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -172,24 +194,44 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     labels = ["quantize_" + n for n in FORMATS] + ["dequantize_" + n for n in FORMATS]
-    in_loop_us = {}
+    kern = {}
+    for n in FORMATS:
+        mb = {"MX9": 7, "MX6": 4, "MX4": 2}[n]
+        kern["quantize_" + n] = "mx_quantize_row_kernel<%d, float>" % mb
+        kern["dequantize_" + n] = "mx_dequantize_row_kernel<%d, float>" % mb
+    in_loop_us, kernels = {}, {}
     for k, lab in enumerate(labels):
-        ts = [ev[k].elapsed_time(ev[k + 1]) for ev in marks]
-        in_loop_us[lab] = sum(ts) / len(ts) * 1e3
-    q6_avg = in_loop_us["quantize_MX6"] * 1e-3
-    q6_bytes = alg_bytes(N_ELEMS, 6)
-    achieved = q6_bytes / (q6_avg * 1e-3) / 1e9
+        ts = [ev[k].elapsed_time(ev[k + 1]) * 1e3 for ev in marks]      # one per timed step
+        in_loop_us[lab] = median(ts)
+        mean_us = sum(ts) / len(ts)
+        ab = alg_bytes(N_ELEMS, bits[lab.split("_")[1]])
+        # `achieved` follows the average launch duration (what rocprofv3 --stats reports as
+        # AverageNs, so the two can be compared); the median is given next to it
+        kernels[lab] = {"kernel": kern[lab], "avg_launch_us": round(mean_us, 2),
+                        "median_launch_us": round(in_loop_us[lab], 2), "launches": len(ts),
+                        "algorithmic_bytes_per_launch": ab,
+                        "achieved": round(ab / mean_us / 1e3, 1),
+                        "frac": round(ab / mean_us / 1e3 / HBM_PEAK_GBS, 4),
+                        "achieved_median": round(ab / in_loop_us[lab] / 1e3, 1),
+                        "share_of_step": round(mean_us / (ms_per_step * 1e3), 4)}
+    dom = max(labels, key=lambda l: kernels[l]["avg_launch_us"])     # largest share of the timed region
+    traffic, traffic_commit = measured_traffic(dom)
     roofline = {
-        "kernel": "mx_quantize_row_kernel<4, float> (MX6 quantize, fp32 in)",
-        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "algorithmic_bytes_per_launch": q6_bytes, "avg_launch_us": round(q6_avg * 1e3, 2),
-        "traffic": measured_traffic(),
+        "kernel": "%s (%s, fp32, 2^28 elements per launch)" % (kern[dom], dom.replace("_", " ")),
+        "bound": "hbm", "achieved": kernels[dom]["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": kernels[dom]["frac"],
+        "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
+        "avg_launch_us": kernels[dom]["avg_launch_us"], "median_launch_us": kernels[dom]["median_launch_us"],
+        "traffic": traffic, "traffic_profile_commit": traffic_commit,
+        "frac_min": min(v["frac"] for v in kernels.values()),
+        "kernels": kernels,
     }
 
-    def timed(fn, reps=6, inner=5, warm=3):
-        """Mean device time of one call: `inner` calls are enqueued between one pair of events, so
-        the host's launch overhead overlaps with the previous call's execution."""
+    def timed(fn, reps=7, inner=3, warm=3):
+        """Median, over `reps` samples, of the device time of one call.  A sample is `inner` calls
+        enqueued between one pair of events (so the host's launch overhead overlaps with the
+        previous call's execution) divided by `inner`; reps * inner >= 20 launches in every leg."""
+        assert reps * inner >= 20
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
@@ -202,7 +244,7 @@ def main():
             b.record()
             b.synchronize()
             ts.append(a.elapsed_time(b) / inner)
-        return sum(ts) / len(ts)
+        return median(ts)
 
     other = {}
     if not args.no_other:
@@ -230,7 +272,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
-        cpu = cpu_baseline(args.cpu_sample, threads)
+        cpu = cpu_baseline(args.cpu_sample, threads, args.cpu_single_sample)
 
     print(json.dumps({
         "metric": "MX9/MX6/MX4 quantize+dequantize algorithmic GB/s (fp32, row-wise)",
@@ -241,15 +283,29 @@ def main():
                                "step = quantize+dequantize for MX9, MX6, MX4",
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "other": other,
+        "profile_commit": {"unit_utilisation": profile_commit(UTIL_PROFILE)},
     }))
+
+
+def profile_commit(path):
+    """The commit a summary under profiles/ says it was taken at (a line `commit: <hash>`)."""
+    try:
+        for line in open(path):
+            if line.startswith("commit:"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
+UTIL_PROFILE = os.path.join(ROOT, "profiles", "mx_gemm_and_sweep_unit_utilisation.txt")
 
 
 def profiled_util(kernel_prefix, column):
     """MfmaUtil (column -2) or VALUBusy (column -1), in percent, of a kernel from the committed
-    rocprofv3 summary, or None."""
-    path = os.path.join(ROOT, "profiles", "mx_gemm_and_sweep_unit_utilisation.txt")
+    rocprofv3 summary (not measured in this run; `profile_commit` says when it was), or None."""
     try:
-        with open(path) as fh:
+        with open(UTIL_PROFILE) as fh:
             for line in fh:
                 if line.startswith(kernel_prefix):
                     return float(line.split()[column])
@@ -262,17 +318,19 @@ def profiled_mfma_util(kernel_prefix):
     return profiled_util(kernel_prefix, -2)
 
 
-def measured_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (profiles/), or None when no such summary has been recorded."""
+def measured_traffic(label):
+    """(HBM bytes per launch, commit) of one of the six kernels of the step, e.g.
+    "dequantize_MX9", from the committed rocprofv3 --pmc summary (profiles/), else (None, None)."""
     path = os.path.join(ROOT, "profiles", "mx_rowwise_f32_1GiB_traffic.txt")
+    op, fm = label.split("_")
+    key = "traffic_bytes_per_launch[%s_%s]" % (fm.lower(), op)
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+            if line.startswith(key):
+                return float(line.split("=")[1]), profile_commit(path)
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def other_legs(B, S, torch, timed):
@@ -302,7 +360,7 @@ def other_legs(B, S, torch, timed):
         wsb = torch.empty(B.lib.bdr_qsnr_sweep_workspace_bytes(len(big)), dtype=torch.uint8, device="cuda")
         resb = (torch.empty(len(big), dtype=torch.float64, device="cuda"),
                 torch.empty(len(big) + 1, dtype=torch.float64, device="cuda"))
-        t = timed(lambda: B.bdr_qsnr_sweep(big, xd, workspace=wsb, out=resb), reps=3, inner=3)
+        t = timed(lambda: B.bdr_qsnr_sweep(big, xd, workspace=wsb, out=resb), reps=7, inner=3)
         qs = resb[0].cpu()
         out["qsnr_sweep_%dfmt_design_space_4Mi" % len(big)] = {
             "ms": round(t, 4), "configs_per_s": round(len(big) / (t * 1e-3), 1),
@@ -324,7 +382,7 @@ def other_legs(B, S, torch, timed):
             def run():
                 B.bdr_quantize(B.MX9, xa[k[0] % 3], axis=axis, out=pl)
                 k[0] += 1
-            t = timed(run, reps=4, inner=6)
+            t = timed(run, reps=7, inner=6)
             leg[name] = {"us": round(t * 1e3, 1), "GBps": round(ab / t / 1e6, 1),
                          "frac": round(ab / t / 1e6 / HBM_PEAK_GBS, 4)}
         out["activation_bf16_8192x12288_MX9"] = leg
@@ -383,7 +441,7 @@ def other_legs(B, S, torch, timed):
         del tab
         idx = torch.randint(0, rows_t, (n_look,), generator=g, device="cuda", dtype=torch.int64)
         yo = torch.empty(n_look, cols_t, device="cuda")
-        t = timed(lambda: B.bdr_gather_dequantize(B.MX6, pt, rows_t, cols_t, idx, out=yo), reps=4, inner=5)
+        t = timed(lambda: B.bdr_gather_dequantize(B.MX6, pt, rows_t, cols_t, idx, out=yo), reps=5, inner=5)
         ab = n_look * (cols_t * 6 // 8 + 8 + cols_t * 4)
         out["gather_dequantize_MX6_1Mi_rows_x128_fp32"] = {
             "us": round(t * 1e3, 1), "GBps": round(ab / t / 1e6, 1),
@@ -407,7 +465,7 @@ def other_legs(B, S, torch, timed):
                 x.grad = None
                 w.grad = None
                 mx_linear(x, w, f).backward(gy)
-            t = timed(step_fn, reps=3, inner=2, warm=8)
+            t = timed(step_fn, reps=10, inner=2, warm=8)
             tf = 3 * 2.0 * T * I * Osz / (t * 1e-3) / 1e12
             out["mx_linear_fwd_bwd_8192x12288x12288_%s_bf16" % name] = {
                 "ms": round(t, 3), "TFLOPs": round(tf, 1), key: round(tf / peak, 4)}

@@ -23,13 +23,21 @@ _workspaces = {}
 
 
 def _workspace(device, nbytes):
-    """One scratch buffer per device, grown on demand, shared by the GEMMs of this module
-    (they run one after the other on the current stream)."""
-    ws = _workspaces.get(device)
+    """One scratch buffer per (device, stream), grown on demand: the GEMMs that share it run one
+    after the other on that stream, and work on another stream gets a buffer of its own, so two
+    streams never meet in one workspace.  `release_workspaces()` drops them all."""
+    key = (device, torch.cuda.current_stream(device).cuda_stream)
+    ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        _workspaces[device] = ws
+        _workspaces[key] = ws
     return ws
+
+
+def release_workspaces():
+    """Forget every cached GEMM workspace (their memory goes back to torch's allocator once the
+    work that uses them has run)."""
+    _workspaces.clear()
 
 
 def _mx_matmul(fa, fb, a, a_axis, b, b_axis, M, N, K):

@@ -80,3 +80,30 @@ def test_linear_layer_flow_bf16():
     wantw = gc.T @ xc
     gotw = w.grad.float().cpu().numpy().astype(np.float64)
     assert np.all(np.abs(gotw - wantw) <= 2.0 ** -8 * np.abs(wantw) + RTOL * (np.abs(gc).T @ np.abs(xc)))
+
+
+def test_two_streams_do_not_share_a_workspace():
+    # forward products issued on two streams at once: each stream's GEMMs work in a scratch
+    # buffer of their own, and both results equal what one stream alone gives
+    from paper_2302_08007_amd import training
+    T, I, Osz = 512, 1024, 512
+    g = torch.Generator(device="cuda").manual_seed(21)
+    xs = [torch.randn(T, I, generator=g, device="cuda") for _ in range(2)]
+    ws = [torch.randn(Osz, I, generator=g, device="cuda") / 32 for _ in range(2)]
+    want = [mx_linear(x, w, B.MX6) for x, w in zip(xs, ws)]
+    torch.cuda.synchronize()
+    training.release_workspaces()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = [None, None]
+    for rep in range(4):
+        for k in (0, 1):
+            with torch.cuda.stream(streams[k]):
+                got[k] = mx_linear(xs[k], ws[k], B.MX6)
+    torch.cuda.synchronize()
+    keys = list(training._workspaces)
+    assert len(keys) == 2 and keys[0] != keys[1]
+    assert training._workspaces[keys[0]].data_ptr() != training._workspaces[keys[1]].data_ptr()
+    for k in (0, 1):
+        assert torch.equal(got[k], want[k])
+    training.release_workspaces()
+    assert not training._workspaces
