@@ -370,6 +370,41 @@ def other_legs(B, S, torch, timed):
     except B.BdrError as e:
         out["qsnr_sweep_64fmt_16Mi"] = {"error": str(e)}
     try:
+        # formats of the design-space sweep other than Table II's, as storage formats (Sec. IV):
+        # 1 GiB fp32, quantize then dequantize in a loop, an event after every launch (so each
+        # kernel runs against cold planes, as in the headline step)
+        xg = S.bandwidth(N_ELEMS, COLS, device="cuda")
+        yg = torch.empty_like(xg)
+        r, c = xg.shape
+        leg = {}
+        for label, f in (("k1_32_k2_2_d2_1_m4", B.fmt(32, 2, 1, 4)), ("k1_64_k2_4_d2_1_m2", B.fmt(64, 4, 1, 2)),
+                         ("k1_8_k2_1_d2_1_m4", B.fmt(8, 1, 1, 4)), ("bfp_k1_16_m4", B.fmt(16, 16, 0, 4)),
+                         ("run_time_tuple_k1_32_k2_4_d2_2_m4", B.fmt(32, 4, 2, 4))):
+            pl = B.alloc_planes(f, r, c)
+            fbits = (f.m + 1) + 8.0 / f.k1 + float(f.d2) / f.k2
+            ab = alg_bytes(N_ELEMS, fbits)
+            tq, td = [], []
+            for it in range(23):
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                e[0].record()
+                B.bdr_quantize(f, xg, out=pl)
+                e[1].record()
+                B.bdr_dequantize(f, pl, r, c, out=yg)
+                e[2].record()
+                e[2].synchronize()
+                if it >= 3:
+                    tq.append(e[0].elapsed_time(e[1]))
+                    td.append(e[1].elapsed_time(e[2]))
+            tq, td = median(tq), median(td)
+            leg[label] = {"bits_per_element": fbits,
+                          "quantize_us": round(tq * 1e3, 1), "quantize_frac": round(ab / tq / 1e6 / HBM_PEAK_GBS, 4),
+                          "dequantize_us": round(td * 1e3, 1), "dequantize_frac": round(ab / td / 1e6 / HBM_PEAK_GBS, 4)}
+            del pl
+        out["general_formats_fp32_1GiB_rowwise"] = leg
+        del xg, yg
+    except B.BdrError as e:
+        out["general_formats_fp32_1GiB_rowwise"] = {"error": str(e)}
+    try:
         # three buffers in rotation so the 192 MiB input is not served from the 256 MB cache
         xa = [S.activation(device="cuda", seed=3 + i) for i in range(3)]
         r, c = xa[0].shape

@@ -44,17 +44,16 @@ __device__ __forceinline__ void mx_quant8(const uint32_t (&xb)[8], uint32_t &lo,
 template <typename T>
 constexpr int q_iter() { return sizeof(T) == 2 ? 4 : 1; }
 
-// Pack and store what one lane produced for its 8 elements (group g).
-template <int MB>
-__device__ __forceinline__ void mx_store_group(uint32_t lo, uint32_t hi, uint32_t se, uint32_t tau4,
-                                               int64_t g, uint8_t *__restrict__ codes,
-                                               uint8_t *__restrict__ sexp,
-                                               uint8_t *__restrict__ mexp)
+// Store the 8 codes of a lane (group g), packed little-endian in lo / hi, CB bits each.
+// Whole quads of lanes call it together: for 5- and 3-bit codes a quad's 20 or 12 bytes
+// leave as aligned dwords after a funnel shift across the quad.
+template <int CB>
+__device__ __forceinline__ void store_codes_quad(uint32_t lo, uint32_t hi, int64_t g,
+                                                 uint8_t *__restrict__ codes)
 {
-    constexpr int CB = MB + 1;
+    static_assert(CB == 8 || CB == 5 || CB == 3, "code widths with a quad funnel");
     const uint32_t i = threadIdx.x & 3u;
     const int64_t quad = g >> 2;
-
     if (CB == 8) {
         u32x2 v = {lo, hi};
         stg<kNtPlanes>(v, reinterpret_cast<u32x2 *>(codes + 8 * g));
@@ -77,6 +76,18 @@ __device__ __forceinline__ void mx_store_group(uint32_t lo, uint32_t hi, uint32_
             stg<kNtPlanes>((lo >> (8u * i)) | (nlo << (24u - 8u * i)),
                                   reinterpret_cast<uint32_t *>(codes + 12 * quad + 4 * i));
     }
+}
+
+// Pack and store what one lane produced for its 8 elements (group g).
+template <int MB>
+__device__ __forceinline__ void mx_store_group(uint32_t lo, uint32_t hi, uint32_t se, uint32_t tau4,
+                                               int64_t g, uint8_t *__restrict__ codes,
+                                               uint8_t *__restrict__ sexp,
+                                               uint8_t *__restrict__ mexp)
+{
+    const uint32_t i = threadIdx.x & 3u;
+    const int64_t quad = g >> 2;
+    store_codes_quad<MB + 1>(lo, hi, g, codes);
 
     // The quad's two exponent bytes and two microexponent bytes, gathered with
     // two DPP ORs; lane 0 writes the exponents, lane 2 the microexponents.
@@ -294,6 +305,33 @@ struct GenFmt {
     int k1, k2, d2, m, rounding;
 };
 
+// Formats the general kernels are also compiled for with the tuple as a compile-time
+// constant (SPEC = index into this table; SPEC < 0 = tuple at run time): the formats of the
+// design-space sweep of Sec. IV around Table II -- k1 8 .. 64, k2 1, 2, 4 or k1, d2 0 or 1,
+// m 2 or 4, nearest-even.  d2 = 0 is listed once per (k1, m) with k2 = k1 (k2 plays no part
+// then); Table II's own members have kernels of their own.  With the tuple known, every
+// loop over group sizes unrolls and every shift is an immediate, which is what the
+// run-time-format kernels spend their time on.
+constexpr int kHotK1[4] = {8, 16, 32, 64};
+constexpr int kHotM[2] = {2, 4};
+constexpr int kHotCount = 4 * 2 * 5;  // per (k1, m): d2 = 0, then d2 = 1 with k2 = 1, 2, 4, k1
+__host__ __device__ constexpr GenFmt hot_format(int spec)
+{
+    const int k1 = kHotK1[spec / 10], m = kHotM[(spec / 5) % 2], v = spec % 5;
+    return GenFmt{k1, v == 0 || v == 4 ? k1 : 1 << (v - 1), v == 0 ? 0 : 1, m, BDR_RNE};
+}
+// index of a format in the table, or -1
+static inline int hot_index(const bdr_format &f)
+{
+    for (int sp = 0; sp < kHotCount; ++sp) {
+        const GenFmt h = hot_format(sp);
+        if (f.k1 == h.k1 && f.m == h.m && f.d2 == h.d2 && f.rounding == h.rounding &&
+            (f.d2 == 0 || f.k2 == h.k2))
+            return sp;
+    }
+    return -1;
+}
+
 // Sub-block and block maxima (exponent-clamped magnitudes) for the 8 elements
 // of a lane; the block or sub-block may be smaller than the lane's run, or span
 // up to 32 lanes.
@@ -368,13 +406,14 @@ __device__ __forceinline__ void pack_codes(const uint32_t (&code)[8], uint8_t *c
 // wave rows through LDS like in the MX kernels.  The planes of a workgroup's 2048
 // elements are contiguous runs of the three planes; they are assembled in LDS and
 // leave as coalesced stores by consecutive lanes.
-template <typename T, int MODE, bool STRIDED, bool CONTIG>
+template <typename T, int MODE, bool STRIDED, bool CONTIG, int SPEC = -1>
 __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
-    GenFmt f, const T *x, T *y, uint8_t *__restrict__ codes,
+    GenFmt f_arg, const T *x, T *y, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp, int64_t cols, int64_t sr, int64_t sc,
     int64_t n_groups)
 {
     static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
+    const GenFmt f = SPEC >= 0 ? hot_format(SPEC >= 0 ? SPEC : 0) : f_arg;
     __shared__ uint32_t s_mexp[MODE == 0 ? kTileElems * 3 / 32 + 1 : 1];
     __shared__ uint32_t s_codes[MODE == 0 ? kThreads * 9 / 4 : 1];  // up to 9 bytes per lane
     __shared__ uint32_t s_sexp[MODE == 0 ? kTileElems / 4 : 1];     // up to one byte per element
@@ -384,7 +423,8 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int64_t addr = 0;
     const int64_t wave_g = g - (threadIdx.x & 63);  // first group of this wave
-    if (MODE == 0 && f.d2 > 0)  // cleared while the loads below are in flight
+    const bool mexp_atomics = MODE == 0 && f.d2 > 0 && !(SPEC >= 0 && f.d2 == 1);
+    if (mexp_atomics)  // cleared while the loads below are in flight
         for (int t = threadIdx.x; t < kTileElems * 3 / 32 + 1; t += kThreads) s_mexp[t] = 0;
     if (CONTIG) {
         wave_load512(reinterpret_cast<const float *>(x) + 8 * wave_g, xb, 8 * (n_groups - wave_g),
@@ -400,7 +440,7 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
             load8(x + addr, xb);
         }
     }
-    if (MODE == 0 && f.d2 > 0) __syncthreads();
+    if (mexp_atomics) __syncthreads();
     uint32_t pe[8], be[8];
     gen_maxima(f, xb, pe, be);
 
@@ -440,7 +480,23 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     uint8_t *lc = reinterpret_cast<uint8_t *>(s_codes);
     uint8_t *ls = reinterpret_cast<uint8_t *>(s_sexp);
     const int lk1 = __builtin_ctz(f.k1);
+    // Compiled-for-the-tuple kernels with 5- or 3-bit codes store them straight from
+    // registers, a quad of lanes at a time (the launcher sends only tensors made of whole
+    // quads here); everything else assembles the workgroup's codes in LDS first.
+    constexpr bool kDirectCodes = SPEC >= 0 && (hot_format(SPEC >= 0 ? SPEC : 0).m == 4 ||
+                                                hot_format(SPEC >= 0 ? SPEC : 0).m == 2);
     if (active) {
+        if constexpr (kDirectCodes) {
+            constexpr int CBK = hot_format(SPEC >= 0 ? SPEC : 0).m + 1;
+            uint32_t w[2] = {0, 0};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int off = i * CBK;
+                w[off >> 5] |= code[i] << (off & 31);
+                if ((off & 31) + CBK > 32) w[(off >> 5) + 1] |= code[i] >> (32 - (off & 31));
+            }
+            store_codes_quad<CBK>(w[0], w[1], g, codes);
+        } else {
         // 8 codes of cb <= 9 bits: cb bytes; the code width is dispatched once so that
         // all shifts are immediate
         uint8_t *cp = lc + cb * threadIdx.x;
@@ -454,6 +510,7 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         case 8: pack_codes<8>(code, cp); break;
         default: pack_codes<9>(code, cp); break;
         }
+        }
 
         if (f.k1 >= 8) {
             const int lanes = f.k1 / 8;
@@ -465,10 +522,36 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
                     ls[((8 * threadIdx.x) >> lk1) + (i >> lk1)] = (uint8_t)(be[i] >> 23);
         }
     }
-    // Microexponents: each lane ORs its bits into the tile's bit stream.  A tile's
-    // stream starts on a byte boundary because kTileElems / k2 is a multiple of 8.
+    // Microexponents.  A tile's stream starts on a byte boundary because kTileElems / k2 is a
+    // multiple of 8.
     const int64_t tile_sub0 = (int64_t)blockIdx.x * (kTileElems / f.k2);
-    if (active && f.d2 > 0) {
+    if (SPEC >= 0 && f.d2 == 1) {
+        // One bit per sub-block: a byte of the stream is the 8 sub-blocks = 8 k2 elements = k2
+        // lanes (k2 a power of two <= 64), so the byte is OR-ed together across those lanes in
+        // registers and its first lane stores it: every byte has one writer, no atomics, and
+        // nothing to clear.  Lanes past the end of the tensor hold zeros (their byte is not
+        // written out below).
+        uint32_t field = 0;
+        if (f.k2 <= 8) {
+            const int nb = 8 / f.k2;  // bits this lane owns
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if ((i & (f.k2 - 1)) == 0) field |= (tau[i] & 1u) << (i / f.k2);
+            field <<= (threadIdx.x & (f.k2 - 1)) * nb;
+        } else {
+            const int lanes = f.k2 / 8;  // lanes per sub-block; its first lane carries the bit
+            if ((threadIdx.x & (lanes - 1)) == 0) field = (tau[0] & 1u) << ((threadIdx.x & (f.k2 - 1)) / lanes);
+        }
+        if (f.k2 >= 2) field |= dpp<kQuadXor1>(field);
+        if (f.k2 >= 4) field |= dpp<kQuadXor2>(field);
+        if (f.k2 >= 8) field |= dpp<kRowHalfMirror>(field);
+        if (f.k2 >= 16) field |= dpp<kRowMirror>(field);
+        if (f.k2 >= 32) field |= (uint32_t)__shfl_xor((int)field, 16);
+        if (f.k2 >= 64) field |= (uint32_t)__shfl_xor((int)field, 32);
+        if ((threadIdx.x & (f.k2 - 1)) == 0)
+            reinterpret_cast<uint8_t *>(s_mexp)[threadIdx.x / f.k2] = (uint8_t)field;
+    } else if (active && f.d2 > 0) {
+        // run-time tuple: each lane ORs its bits into the tile's bit stream
         uint32_t field = 0;
         int width = 0;
         int64_t u0;
@@ -496,7 +579,7 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     }
     __syncthreads();
     // ---- flush: consecutive lanes write consecutive dwords (bytes at the ragged end)
-    {
+    if constexpr (!kDirectCodes) {
         const int nbytes = cb * n_active;  // the workgroup's codes start at byte cb * 256 * blockIdx
         uint8_t *gp = codes + (int64_t)cb * block_g0;
         uint32_t *gw = reinterpret_cast<uint32_t *>(gp);
@@ -525,13 +608,14 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         mp[b] = (uint8_t)(s_mexp[b >> 2] >> (8 * (b & 3)));
 }
 
-template <typename T, bool STRIDED, bool CONTIG>
+template <typename T, bool STRIDED, bool CONTIG, int SPEC = -1>
 __global__ __launch_bounds__(kThreads) void generic_dequantize_kernel(
-    GenFmt f, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
+    GenFmt f_arg, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, int64_t mexp_bytes, T *__restrict__ y, int64_t cols,
     int64_t sr, int64_t sc, int64_t n_groups)
 {
     static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
+    const GenFmt f = SPEC >= 0 ? hot_format(SPEC >= 0 ? SPEC : 0) : f_arg;
     __shared__ float s_stage[CONTIG ? kThreads / 64 : 1][CONTIG ? kWaveStage : 1];
     const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const bool active = g < n_groups;
@@ -634,6 +718,27 @@ static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, i
     return (decode ? is_mx_layout(f) : is_mx(f)) && ld == cols && (rows * cols) % 32 == 0;
 }
 
+// Launch the kernel compiled for table entry `spec` (FP32 rows with pitch = row length).
+// what: 0 quantize, 1 dequantize.
+template <int SP = 0>
+static void launch_hot(int spec, int what, dim3 grid, hipStream_t s, const float *x, float *y,
+                       uint8_t *codes, uint8_t *sexp, uint8_t *mexp, int64_t mexp_bytes, int64_t cols,
+                       int64_t ng)
+{
+    if constexpr (SP < kHotCount) {
+        if (spec != SP)
+            return launch_hot<SP + 1>(spec, what, grid, s, x, y, codes, sexp, mexp, mexp_bytes, cols, ng);
+        const GenFmt f = hot_format(SP);
+        const dim3 block(kThreads);
+        if (what == 0)
+            hipLaunchKernelGGL((generic_quantize_kernel<float, 0, false, true, SP>), grid, block, 0, s, f, x,
+                               (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng);
+        else
+            hipLaunchKernelGGL((generic_dequantize_kernel<float, false, true, SP>), grid, block, 0, s, f,
+                               codes, sexp, mexp, mexp_bytes, y, cols, cols, (int64_t)1, ng);
+    }
+}
+
 template <typename T>
 static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
                           uint8_t *codes, uint8_t *sexp, uint8_t *mexp, hipStream_t s)
@@ -652,7 +757,11 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
     } else {
         bool done = false;
         if constexpr (sizeof(T) == 4) {
-            if (ld == cols) {
+            const int spec = ld == cols && ng % 4 == 0 ? hot_index(f) : -1;
+            if (spec >= 0) {
+                launch_hot(spec, 0, grid, s, x, nullptr, codes, sexp, mexp, 0, cols, ng);
+                done = true;
+            } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, true>), grid, block, 0, s, gen_of(f),
                                    x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
                 done = true;
@@ -694,7 +803,14 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         bool done = false;
         if constexpr (sizeof(T) == 4) {
-            if (ld == cols) {
+            bdr_format fr = f;
+            fr.rounding = BDR_RNE;  // reading an image does not depend on how it was rounded
+            const int spec = ld == cols ? hot_index(fr) : -1;
+            if (spec >= 0) {
+                launch_hot(spec, 1, grid, s, nullptr, y, const_cast<uint8_t *>(codes),
+                           const_cast<uint8_t *>(sexp), const_cast<uint8_t *>(mexp), mexp_bytes, cols, ng);
+                done = true;
+            } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
                                    codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
                 done = true;
@@ -773,6 +889,8 @@ static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_
     } else {
         bool done = false;
         if constexpr (sizeof(T) == 4) {
+            // (the fused round trip writes no planes and gains nothing from a compiled-in
+            // tuple: it is bound by its 2 x 4 bytes per element either way)
             if (ld == cols) {
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, true>), grid, block, 0, s, gen_of(f),
                                    x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,

@@ -95,6 +95,24 @@ def test_generic_formats(kw, dtype):
         _roundtrip_check(f, x, "%r %s %s" % (f, dtype, shape))
 
 
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("d2", [0, 1])
+@pytest.mark.parametrize("k2", [1, 2, 4, 0])
+@pytest.mark.parametrize("k1", [8, 16, 32, 64])
+def test_design_space_sweep_formats(k1, k2, d2, m):
+    # the 64 formats of the design-space sweep (Sec. IV) as storage formats: FP32 rows with
+    # pitch = row length take kernels compiled for the tuple; several workgroups and a ragged
+    # last one, a single block, and (pitched rows) the run-time-tuple kernels on the same data
+    f = B.fmt(k1, k1 if k2 == 0 else k2, d2, m)
+    for shape in ((5, 1088), (1, 64), (40, 64)):
+        x = S.wide_range(*shape, device="cuda", seed=k1 + shape[1], spread=4)
+        _roundtrip_check(f, x, "%r %s" % (f, shape))
+    big = S.wide_range(6, 1024, device="cuda", seed=k1 + 1, spread=4)
+    sub = big[:, 128:128 + 704]
+    want = O.quantize(ofmt(f), to_np(sub))
+    assert_planes_equal(B.bdr_quantize(f, sub), want, "%r pitched" % f)
+
+
 @pytest.mark.parametrize("name", MX)
 def test_strided_rows(name):
     # ld > cols: a column slice of a wider tensor
