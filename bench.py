@@ -102,6 +102,10 @@ def main():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run a 1 GiB tensor copy and one launch of each row-wise MX kernel, "
                          "three times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--aux-probe", action="store_true",
+                    help="run a 1 GiB tensor copy, then the column-wise and row-wise BF16 kernels "
+                         "(8192 x 12288, MX9), the gather kernel and general-format kernels, three "
+                         "times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--other-probe", action="store_true",
                     help="run mx_gemm (both forms, 8192^3, MX6 and MX9) and the 64-format sweep a few times and "
                          "exit (for rocprofv3 --pmc MfmaUtil VALUBusy)")
@@ -116,6 +120,8 @@ def main():
     import synth_inputs as S
 
     torch.cuda.set_device(0)
+    if args.aux_probe:
+        return aux_probe(B, S, torch)
     x = S.bandwidth(N_ELEMS, COLS, device="cuda")
     rows, cols = x.shape
     y = torch.empty_like(x)
@@ -285,6 +291,44 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "other": other,
         "profile_commit": {"unit_utilisation": profile_commit(UTIL_PROFILE)},
     }))
+
+
+def aux_probe(B, S, torch):
+    """One launch each, three times over, of the kernels outside the headline step whose HBM
+    traffic is worth counting, after a copy of known size that calibrates the counters."""
+    x = S.bandwidth(N_ELEMS, COLS, device="cuda")
+    y = torch.empty_like(x)
+    rows, cols = x.shape
+    xa = S.activation(device="cuda")
+    ra, ca = xa.shape
+    ya = torch.empty_like(xa)
+    prow = B.alloc_planes(B.MX9, ra, ca, B.AXIS_ROW)
+    pcol = B.alloc_planes(B.MX9, ra, ca, B.AXIS_COL)
+    fh, fr = B.fmt(32, 2, 1, 4), B.fmt(32, 4, 2, 4)
+    ph, pr = B.alloc_planes(fh, rows, cols), B.alloc_planes(fr, rows, cols)
+    rows_t, cols_t, n_look = 1 << 20, 128, 1 << 20
+    g = torch.Generator(device="cuda").manual_seed(7)
+    tab = torch.randn(rows_t, cols_t, generator=g, device="cuda") * 0.05
+    pt = B.bdr_quantize(B.MX6, tab)
+    del tab
+    idx = torch.randint(0, rows_t, (n_look,), generator=g, device="cuda", dtype=torch.int64)
+    yo = torch.empty(n_look, cols_t, device="cuda")
+    for _ in range(3):
+        y.copy_(x)
+        B.bdr_quantize(B.MX9, xa, axis=B.AXIS_COL, out=pcol)
+        B.bdr_dequantize(B.MX9, pcol, ra, ca, axis=B.AXIS_COL, out=ya)
+        B.bdr_quantize_dequantize(B.MX9, xa, axis=B.AXIS_COL, out=ya)
+        B.bdr_quantize(B.MX9, xa, axis=B.AXIS_ROW, out=prow)
+        B.bdr_dequantize(B.MX9, prow, ra, ca, axis=B.AXIS_ROW, out=ya)
+        B.bdr_gather_dequantize(B.MX6, pt, rows_t, cols_t, idx, out=yo)
+        B.bdr_quantize(fh, x, out=ph)
+        B.bdr_dequantize(fh, ph, rows, cols, out=y)
+        B.bdr_quantize(fr, x, out=pr)
+        B.bdr_dequantize(fr, pr, rows, cols, out=y)
+    torch.cuda.synchronize()
+    print(json.dumps({"aux_probe": "3 x (1 GiB copy; MX9 bf16 8192x12288 column quantize, dequantize, fused, "
+                                   "row quantize, dequantize; MX6 gather 2^20 x 128; k1 32 k2 2 d2 1 m 4 and "
+                                   "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32)"}))
 
 
 def profile_commit(path):

@@ -62,6 +62,8 @@ def lib():
         L.bdr_ref_mx_gemm_sampled.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, I64,
                                               P, P, P, P]
         L.bdr_ref_mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64]
+        L.bdr_ref_dot_pipeline_sampled.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, I64,
+                                                   I32, I64, P, P, P]
         _lib = L
     return _lib
 
@@ -177,3 +179,21 @@ def mx_gemm(fa, fb, a_planes, b_planes, M, N, K):
         _ptr(a_planes[2]), _ptr(b_planes[0]), _ptr(b_planes[1]), _ptr(b_planes[2]), M, N, K,
         _ptr(C), N))
     return C
+
+
+def dot_pipeline_sampled(fa, fb, a_planes, b_planes, M, N, K, idx_i, idx_j, r=None, f_bits=25):
+    """Entries (idx_i[s], idx_j[s]) of C = A B^T through the dot-product pipeline model."""
+    idx_i = np.ascontiguousarray(idx_i, np.int64)
+    idx_j = np.ascontiguousarray(idx_j, np.int64)
+    out = np.zeros(idx_i.size, np.float32)
+    _check(lib().bdr_ref_dot_pipeline_sampled(
+        ctypes.byref(fa), ctypes.byref(fb), _ptr(a_planes[0]), _ptr(a_planes[1]),
+        _ptr(a_planes[2]), _ptr(b_planes[0]), _ptr(b_planes[1]), _ptr(b_planes[2]), M, N, K,
+        K if r is None else r, f_bits, idx_i.size, _ptr(idx_i), _ptr(idx_j), _ptr(out)))
+    return out
+
+
+def dot_pipeline(fa, fb, a_planes, b_planes, M, N, K, r=None, f_bits=25):
+    """The full [M x N] matrix of the same."""
+    ii, jj = [a.reshape(-1) for a in np.meshgrid(np.arange(M), np.arange(N), indexing="ij")]
+    return dot_pipeline_sampled(fa, fb, a_planes, b_planes, M, N, K, ii, jj, r, f_bits).reshape(M, N)

@@ -531,3 +531,163 @@ int bdr_ref_mx_gemm(const bdr_ref_format *fa, const bdr_ref_format *fb, const ui
     free(bh);
     return BDR_REF_OK;
 }
+
+/* --------------------------------------------------- dot-product pipeline */
+
+/*
+ * Sec. IV-B, "Dot Product Architecture" (and the caption of the pipeline figure): for k1 > 1
+ * the first part of the pipeline reduces the Hadamard product of the k1 elements of a block to
+ * a single element, with a conditional right shift of up to 2^d2 - 1 bits at depth log2(k2)
+ * when there are sub-blocks; there are r / k1 such reductions, whose results are normalized to
+ * the largest element and reduced in fixed point with f bits.  The text stops there (the figure
+ * is not part of it), so what follows is a reading, step by step:
+ *
+ *   D1  Element products are exact integers: P_i = (+-Ma_i)(+-Mb_i), the sign-magnitude
+ *       mantissas of the two codes.
+ *   D2  The k2 products of a sub-block share their shifts and are added exactly:
+ *       S_j = sum of P_i over sub-block j (adder tree of depth log2 k2).
+ *   D3  At that depth sub-block j is shifted right by tau_a[j] + tau_b[j] bits (each operand
+ *       contributes up to its own 2^d2 - 1) and the k1 / k2 results are added.  The datapath
+ *       keeps the bits that are shifted out (it is beta_a + beta_b bits wider below the binary
+ *       point), so the block result is the exact integer
+ *       T = sum_j S_j 2^(beta_a + beta_b - tau_a[j] - tau_b[j])
+ *       in units of 2^(Ea + Eb - (ma - 1) - (mb - 1) - beta_a - beta_b), Ea, Eb the shared
+ *       exponents of the two blocks.  |T| < 2^W, W = ma + mb + log2(k1) + beta_a + beta_b.
+ *   D4  "Normalized to the largest element": the r / k1 block results of a pass are aligned to
+ *       the largest exponent sum e_max = max_b (SEa_b + SEb_b) (exponents are compared, as in a
+ *       floating-point adder; the values are not inspected); block b is shifted right by
+ *       s_b = e_max - (SEa_b + SEb_b).
+ *   D5  The f-bit fixed-point word is a two's complement number with f - 1 magnitude bits whose
+ *       top magnitude bit is aligned with bit W - 1 of a block result that has the largest
+ *       exponent sum: g = f - 1 - W guard bits lie below the integer T (g may be negative).
+ *       U_b = floor(T_b 2^(g - s_b)): bits that fall below the word are dropped (arithmetic
+ *       shift of a two's complement number: towards minus infinity).
+ *   D6  V = sum_b U_b exactly (the adder tree grows by log2(r / k1) carry bits; nothing
+ *       saturates).
+ *   D7  The result of the pass is V 2^(e_max - 254 - (ma-1) - (mb-1) - beta_a - beta_b - g),
+ *       rounded once to FP32, nearest even.
+ *   D8  The K / r passes of a longer dot product are added in FP32, in order of increasing k
+ *       (the text's remark on scalar formats, "serially accumulating in a floating-point type"
+ *       with f - 2 mantissa bits: FP32 for f = 25).
+ */
+
+/* floor(t * 2^sh) for |t| < 2^63 and any sh; sh > 0 only where the result fits. */
+static __int128 shift_floor(__int128 t, int sh)
+{
+    if (sh >= 0) return t * ((__int128)1 << sh);
+    int n = -sh;
+    if (n >= 100) return t < 0 ? -1 : 0;
+    __int128 d = (__int128)1 << n;
+    __int128 q = t / d; /* truncates towards zero */
+    if (t < 0 && q * d != t) q -= 1;
+    return q;
+}
+
+/* v * 2^x rounded once to FP32, nearest even, subnormals and overflow included. */
+static float round_scaled_to_float(__int128 v, int x)
+{
+    if (v == 0) return 0.0f;
+    int neg = v < 0;
+    unsigned __int128 mag = neg ? (unsigned __int128)(-v) : (unsigned __int128)v;
+    int nb = 0;
+    for (unsigned __int128 t = mag; t; t >>= 1) ++nb;
+    int e = nb - 1 + x;                            /* exponent of the leading bit */
+    int keep = e >= -126 ? 24 : 24 - (-126 - e);   /* significant bits FP32 holds there */
+    float out;
+    if (keep <= 0) {
+        /* below half of the smallest subnormal, or exactly at it: ties go to even (zero) */
+        out = (keep == 0 && mag > ((unsigned __int128)1 << (nb - 1))) ? ldexpf(1.0f, -149) : 0.0f;
+    } else if (nb <= keep) {
+        out = ldexpf((float)(uint64_t)mag, x); /* nb <= 24: exact */
+    } else {
+        int drop = nb - keep;
+        unsigned __int128 q = mag >> drop, rem = mag - (q << drop);
+        unsigned __int128 half = (unsigned __int128)1 << (drop - 1);
+        if (rem > half || (rem == half && (q & 1))) q += 1;
+        out = ldexpf((float)(uint64_t)q, x + drop); /* q <= 2^24: exact; overflow gives inf */
+    }
+    return neg ? -out : out;
+}
+
+static int ilog2_i32(int32_t v)
+{
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+int bdr_ref_dot_pipeline_sampled(const bdr_ref_format *fa, const bdr_ref_format *fb,
+                                 const uint8_t *a_codes, const uint8_t *a_sexp,
+                                 const uint8_t *a_mexp, const uint8_t *b_codes,
+                                 const uint8_t *b_sexp, const uint8_t *b_mexp, int64_t M,
+                                 int64_t N, int64_t K, int64_t r, int32_t f_bits,
+                                 int64_t n_samples, const int64_t *idx_i, const int64_t *idx_j,
+                                 float *out)
+{
+    int st = bdr_ref_format_validate(fa);
+    if (st) return st;
+    st = bdr_ref_format_validate(fb);
+    if (st) return st;
+    if (fa->k1 != fb->k1 || fa->k2 != fb->k2) return BDR_REF_ERR_FORMAT;
+    if (M < 0 || N < 0 || K < 0 || n_samples < 0) return BDR_REF_ERR_SHAPE;
+    if (r < 1 || r % fa->k1 != 0 || K % r != 0) return BDR_REF_ERR_SHAPE;
+    if (f_bits < 2 || f_bits > 64) return BDR_REF_ERR_SHAPE;
+    if (n_samples == 0) return BDR_REF_OK;
+    if (!idx_i || !idx_j || !out) return BDR_REF_ERR_NULL;
+    if (K > 0 && (!a_codes || !a_sexp || !b_codes || !b_sexp)) return BDR_REF_ERR_NULL;
+    if (K > 0 && ((fa->d2 > 0 && !a_mexp) || (fb->d2 > 0 && !b_mexp))) return BDR_REF_ERR_NULL;
+
+    const int k1 = fa->k1, k2 = fa->k2, ma = fa->m, mb = fb->m;
+    const int beta_a = (1 << fa->d2) - 1, beta_b = (1 << fb->d2) - 1;
+    const int W = ma + mb + ilog2_i32(k1) + beta_a + beta_b;
+    const int g = f_bits - 1 - W;
+    const int64_t blocks_per_row = K / k1, subs_per_row = K / k2;
+
+    for (int64_t s = 0; s < n_samples; ++s) {
+        const int64_t i = idx_i[s], j = idx_j[s];
+        if (i < 0 || i >= M || j < 0 || j >= N) return BDR_REF_ERR_SHAPE;
+        float acc = 0.0f;
+        for (int64_t k0 = 0; k0 < K; k0 += r) {
+            /* D4: the largest exponent sum among the blocks of this pass */
+            int e_max = 0;
+            for (int64_t b = k0 / k1; b < (k0 + r) / k1; ++b) {
+                int e = (int)a_sexp[i * blocks_per_row + b] + (int)b_sexp[j * blocks_per_row + b];
+                if (e > e_max) e_max = e;
+            }
+            __int128 V = 0;
+            for (int64_t b = k0 / k1; b < (k0 + r) / k1; ++b) {
+                /* D1-D3: the block's integer result */
+                int64_t T = 0;
+                for (int u = 0; u < k1 / k2; ++u) {
+                    const int64_t su = b * (k1 / k2) + u; /* sub-block index within the row */
+                    int64_t S = 0;
+                    for (int t = 0; t < k2; ++t) {
+                        const uint64_t ea = (uint64_t)i * (uint64_t)K + (uint64_t)(su * k2 + t);
+                        const uint64_t eb = (uint64_t)j * (uint64_t)K + (uint64_t)(su * k2 + t);
+                        const uint32_t ca = get_bits(a_codes, ea * (uint64_t)(ma + 1), ma + 1);
+                        const uint32_t cb = get_bits(b_codes, eb * (uint64_t)(mb + 1), mb + 1);
+                        int64_t pa = (int64_t)(ca & ((1u << ma) - 1u)), pb = (int64_t)(cb & ((1u << mb) - 1u));
+                        if ((ca >> ma) & 1u) pa = -pa;
+                        if ((cb >> mb) & 1u) pb = -pb;
+                        S += pa * pb;
+                    }
+                    int ta = 0, tb = 0;
+                    if (fa->d2 > 0)
+                        ta = (int)get_bits(a_mexp, ((uint64_t)i * (uint64_t)subs_per_row + (uint64_t)su) * (uint64_t)fa->d2, fa->d2);
+                    if (fb->d2 > 0)
+                        tb = (int)get_bits(b_mexp, ((uint64_t)j * (uint64_t)subs_per_row + (uint64_t)su) * (uint64_t)fb->d2, fb->d2);
+                    T += S * ((int64_t)1 << (beta_a + beta_b - ta - tb));
+                }
+                /* D4-D6: align to e_max inside the f-bit word, drop what falls below it, add */
+                const int e = (int)a_sexp[i * blocks_per_row + b] + (int)b_sexp[j * blocks_per_row + b];
+                V += shift_floor((__int128)T, g - (e_max - e));
+            }
+            /* D7, D8 */
+            const float pass = round_scaled_to_float(
+                V, e_max - 254 - (ma - 1) - (mb - 1) - beta_a - beta_b - g);
+            acc = k0 == 0 ? pass : acc + pass;
+        }
+        out[s] = acc;
+    }
+    return BDR_REF_OK;
+}

@@ -35,6 +35,16 @@
  * textbook block floating point for d2 = 0, and numpy for the product.  Every
  * function has such a pin; absolute QSNR values other than the printed
  * differences are not printed anywhere in the paper.
+ *
+ * bdr_ref_dot_pipeline_sampled (the dot-product pipeline of Sec. IV-B) is PARITY UNPINNED in
+ * the part only a reading decides: the paper gives the pipeline in one paragraph and a figure
+ * that is not in the text, and prints no worked value.  What the arithmetic fixes is pinned
+ * (tests/test_oracle_dot_pipeline.py): the exact integer block product for d2 = 0, the shift
+ * tau_a + tau_b per sub-block pair, equality with the exactly rounded dot product of the
+ * dequantized operands once f is large enough, the error bound of one unit per block, and
+ * power-of-two scale equivariance.  Where the dropped bits go (floor), what the partial
+ * results are aligned to (the largest exponent sum) and where the f-bit word sits are
+ * readings, checked only against hand-worked examples derived from those same readings.
  */
 #ifndef BDR_REF_H
 #define BDR_REF_H
@@ -130,6 +140,22 @@ int bdr_ref_mx_gemm(const bdr_ref_format *fa, const bdr_ref_format *fb, const ui
                     const uint8_t *a_sexp, const uint8_t *a_mexp, const uint8_t *b_codes,
                     const uint8_t *b_sexp, const uint8_t *b_mexp, int64_t M, int64_t N, int64_t K,
                     float *C, int64_t ldc);
+
+/* The dot-product pipeline the paper outlines for BDR formats (Sec. IV-B, "Dot Product
+ * Architecture", and the caption of the pipeline figure there), modelled bit for bit under the
+ * readings D1-D8 stated in bdr_ref.c.  A and B are packed row-wise ([M x K] and [N x K], blocks
+ * along K) in formats with the same k1 and k2 (a symmetric unit).  A dot product of length K is
+ * taken in K / r passes of the pipeline, r the "dot product length" of the unit (a multiple of
+ * k1 that divides K); f_bits is its "fixed-point reduction accumulation precision" (2 .. 64;
+ * the paper uses min(25, dynamic range), i.e. 25 for every d1 = 8 format).  Evaluates the
+ * n_samples entries (idx_i[s], idx_j[s]) of C = A B^T into out[s]. */
+int bdr_ref_dot_pipeline_sampled(const bdr_ref_format *fa, const bdr_ref_format *fb,
+                                 const uint8_t *a_codes, const uint8_t *a_sexp,
+                                 const uint8_t *a_mexp, const uint8_t *b_codes,
+                                 const uint8_t *b_sexp, const uint8_t *b_mexp, int64_t M,
+                                 int64_t N, int64_t K, int64_t r, int32_t f_bits,
+                                 int64_t n_samples, const int64_t *idx_i, const int64_t *idx_j,
+                                 float *out);
 
 #ifdef __cplusplus
 }

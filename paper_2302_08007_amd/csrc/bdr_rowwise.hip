@@ -608,14 +608,13 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         mp[b] = (uint8_t)(s_mexp[b >> 2] >> (8 * (b & 3)));
 }
 
-template <typename T, bool STRIDED, bool CONTIG, int SPEC = -1>
+template <typename T, bool STRIDED, bool CONTIG>
 __global__ __launch_bounds__(kThreads) void generic_dequantize_kernel(
-    GenFmt f_arg, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
+    GenFmt f, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, int64_t mexp_bytes, T *__restrict__ y, int64_t cols,
     int64_t sr, int64_t sc, int64_t n_groups)
 {
     static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
-    const GenFmt f = SPEC >= 0 ? hot_format(SPEC >= 0 ? SPEC : 0) : f_arg;
     __shared__ float s_stage[CONTIG ? kThreads / 64 : 1][CONTIG ? kWaveStage : 1];
     const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const bool active = g < n_groups;
@@ -718,24 +717,18 @@ static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, i
     return (decode ? is_mx_layout(f) : is_mx(f)) && ld == cols && (rows * cols) % 32 == 0;
 }
 
-// Launch the kernel compiled for table entry `spec` (FP32 rows with pitch = row length).
-// what: 0 quantize, 1 dequantize.
+// Launch the quantize kernel compiled for table entry `spec` (FP32 rows with pitch = row
+// length, whole quads of lanes).  Only quantize has such kernels: dequantize and the fused
+// round trip are bound by their 4-byte-per-element write stream with the tuple at run time
+// already (measured: compiled-in tuples made neither faster).
 template <int SP = 0>
-static void launch_hot(int spec, int what, dim3 grid, hipStream_t s, const float *x, float *y,
-                       uint8_t *codes, uint8_t *sexp, uint8_t *mexp, int64_t mexp_bytes, int64_t cols,
-                       int64_t ng)
+static void launch_hot(int spec, dim3 grid, hipStream_t s, const float *x, uint8_t *codes,
+                       uint8_t *sexp, uint8_t *mexp, int64_t cols, int64_t ng)
 {
     if constexpr (SP < kHotCount) {
-        if (spec != SP)
-            return launch_hot<SP + 1>(spec, what, grid, s, x, y, codes, sexp, mexp, mexp_bytes, cols, ng);
-        const GenFmt f = hot_format(SP);
-        const dim3 block(kThreads);
-        if (what == 0)
-            hipLaunchKernelGGL((generic_quantize_kernel<float, 0, false, true, SP>), grid, block, 0, s, f, x,
-                               (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng);
-        else
-            hipLaunchKernelGGL((generic_dequantize_kernel<float, false, true, SP>), grid, block, 0, s, f,
-                               codes, sexp, mexp, mexp_bytes, y, cols, cols, (int64_t)1, ng);
+        if (spec != SP) return launch_hot<SP + 1>(spec, grid, s, x, codes, sexp, mexp, cols, ng);
+        hipLaunchKernelGGL((generic_quantize_kernel<float, 0, false, true, SP>), grid, dim3(kThreads), 0, s,
+                           hot_format(SP), x, (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng);
     }
 }
 
@@ -759,7 +752,7 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
         if constexpr (sizeof(T) == 4) {
             const int spec = ld == cols && ng % 4 == 0 ? hot_index(f) : -1;
             if (spec >= 0) {
-                launch_hot(spec, 0, grid, s, x, nullptr, codes, sexp, mexp, 0, cols, ng);
+                launch_hot(spec, grid, s, x, codes, sexp, mexp, cols, ng);
                 done = true;
             } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, true>), grid, block, 0, s, gen_of(f),
@@ -803,14 +796,7 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         bool done = false;
         if constexpr (sizeof(T) == 4) {
-            bdr_format fr = f;
-            fr.rounding = BDR_RNE;  // reading an image does not depend on how it was rounded
-            const int spec = ld == cols ? hot_index(fr) : -1;
-            if (spec >= 0) {
-                launch_hot(spec, 1, grid, s, nullptr, y, const_cast<uint8_t *>(codes),
-                           const_cast<uint8_t *>(sexp), const_cast<uint8_t *>(mexp), mexp_bytes, cols, ng);
-                done = true;
-            } else if (ld == cols) {
+            if (ld == cols) {
                 hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
                                    codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
                 done = true;
