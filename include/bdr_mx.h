@@ -211,6 +211,35 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,
             size_t workspace_bytes, void *hip_stream);
 
+/* Host only.  Bytes of device workspace mx_dot_pipeline needs: (M + N) * K BF16 values, each
+ * operand rounded up to 256 bytes.  0 when a size is negative or above 2^20. */
+size_t mx_dot_pipeline_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/* C = Ahat * Bhat^T through a bit-true model of the dot-product pipeline the paper outlines
+ * for BDR formats (Sec. IV-B, "Dot Product Architecture" and the caption of the pipeline
+ * figure): the Hadamard product of every block of k1 elements is reduced to one integer, each
+ * sub-block shifted right by its two microexponents on the way; the r / k1 block results of a
+ * pass are aligned to the largest exponent among them and added in a fixed-point word of
+ * f_bits bits; a dot product longer than r takes K / r passes, added in FP32.  Where the text
+ * leaves the arithmetic open the model takes these readings: nothing is lost inside a block
+ * (the datapath is two bits wider below the binary point); blocks are aligned to the largest
+ * SEa + SEb of the pass; the word has f_bits - 1 magnitude bits, the top one level with the
+ * top bit a block result can have (ma + mb + 6 bits), and what falls below the word is dropped
+ * towards minus infinity; a pass is rounded once to FP32, nearest even.  With f_bits = 25 (the
+ * paper's choice for every d1 = 8 format) and r = 64 this is what the paper's evaluation
+ * assumes a native unit does; mx_gemm adds the same exact products in FP32 instead.
+ *   fa, fb, planes, M, N, C, ldc : as for mx_gemm (Table II formats, images blocked along K)
+ *   K      : a multiple of 64, at least 64
+ *   r      : the unit's dot-product length: a multiple of 64 that divides K (r = K: one pass)
+ *   f_bits : 2 .. 26
+ *   workspace : device, 16-byte aligned, mx_dot_pipeline_workspace_bytes(M, N, K) bytes; scratch
+ * Results that are FP32 subnormals and Inf/NaN codes are outside the supported domain. */
+int mx_dot_pipeline(const bdr_format *fa, const bdr_format *fb, const void *a_codes,
+                    const void *a_sexp, const void *a_mexp, const void *b_codes, const void *b_sexp,
+                    const void *b_mexp, int64_t M, int64_t N, int64_t K, int64_t r, int32_t f_bits,
+                    float *C, int64_t ldc, void *workspace, size_t workspace_bytes,
+                    void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

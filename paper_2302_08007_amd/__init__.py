@@ -23,7 +23,7 @@ EXPORTS = (
     "bdr_dequantize", "bdr_gather_dequantize", "bdr_tile_packing", "bdr_quantize_dequantize",
     "bdr_qsnr_sweep_workspace_bytes",
     "bdr_qsnr_sweep", "bdr_qsnr_sweep_static", "bdr_qsnr_sweep_static_scratch_bytes",
-    "mx_gemm_workspace_bytes", "mx_gemm",
+    "mx_gemm_workspace_bytes", "mx_gemm", "mx_dot_pipeline_workspace_bytes", "mx_dot_pipeline",
 )
 
 
@@ -79,6 +79,9 @@ def _load():
     L.mx_gemm_workspace_bytes.argtypes = [I64, I64, I64]
     L.mx_gemm_workspace_bytes.restype = SZ
     L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P, SZ, P]
+    L.mx_dot_pipeline_workspace_bytes.argtypes = [I64, I64, I64]
+    L.mx_dot_pipeline_workspace_bytes.restype = SZ
+    L.mx_dot_pipeline.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, I64, I32, P, I64, P, SZ, P]
     return L
 
 
@@ -264,4 +267,26 @@ def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None):
     _check(lib.mx_gemm(ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]),
                        _p(a_planes[2]), _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]), M, N, K,
                        _p(C), C.stride(0), ws, wsb, _stream()))
+    return C
+
+
+def mx_dot_pipeline(fa, fb, a_planes, b_planes, M, N, K, r=None, f_bits=25, out=None, workspace=None):
+    """C[M, N] = Ahat @ Bhat^T through the bit-true model of the paper's dot-product pipeline
+    (Sec. IV-B): r = dot-product length of the unit (default K: one pass), f_bits = width of its
+    fixed-point accumulation word."""
+    C = out if out is not None else torch.empty((M, N), dtype=torch.float32,
+                                                device=a_planes[0].device)
+    if not (C.is_cuda and C.dtype == torch.float32 and C.dim() == 2 and tuple(C.shape) == (M, N)
+            and C.stride(1) == 1):
+        raise ValueError("output must be an [M x N] float32 GPU tensor with unit column stride")
+    _check_planes(fa, a_planes, M, K)
+    _check_planes(fb, b_planes, N, K)
+    need = lib.mx_dot_pipeline_workspace_bytes(M, N, K)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=C.device)
+    _check_buffer("workspace", workspace, torch.uint8, need)
+    _check(lib.mx_dot_pipeline(ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]),
+                               _p(a_planes[2]), _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]),
+                               M, N, K, K if r is None else r, f_bits, _p(C), C.stride(0),
+                               _p(workspace), workspace.numel(), _stream()))
     return C

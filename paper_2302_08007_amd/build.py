@@ -13,7 +13,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbdr_mx.so")
-SOURCES = ["bdr_api.hip", "bdr_rowwise.hip", "bdr_colwise.hip", "bdr_sweep.hip", "mx_gemm.hip"]
+SOURCES = ["bdr_api.hip", "bdr_rowwise.hip", "bdr_colwise.hip", "bdr_sweep.hip", "mx_gemm.hip",
+           "mx_dot_pipeline.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

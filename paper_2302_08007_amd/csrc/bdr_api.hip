@@ -313,4 +313,36 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
     return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc, s);
 }
 
+size_t mx_dot_pipeline_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    return mx_gemm_workspace_bytes(M, N, K);
+}
+
+int mx_dot_pipeline(const bdr_format *fa, const bdr_format *fb, const void *a_codes,
+                    const void *a_sexp, const void *a_mexp, const void *b_codes, const void *b_sexp,
+                    const void *b_mexp, int64_t M, int64_t N, int64_t K, int64_t r, int32_t f_bits,
+                    float *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int st = check_format(fa);
+    if (st) return st;
+    st = check_format(fb);
+    if (st) return st;
+    if (!bdr::is_mx_layout(*fa) || !bdr::is_mx_layout(*fb)) return BDR_ERR_FORMAT;
+    if (M < 0 || N < 0 || K < 64 || ldc < N) return BDR_ERR_SHAPE;
+    if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
+    if (K % 64 != 0 || r < 64 || r % 64 != 0 || K % r != 0) return BDR_ERR_SHAPE;
+    if (f_bits < 2 || f_bits > 26) return BDR_ERR_SHAPE;
+    if (M == 0 || N == 0) return BDR_OK;
+    if (!C) return BDR_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(C) % 4 != 0) return BDR_ERR_ALIGN;
+    st = check_planes(fa, a_codes, a_sexp, a_mexp);
+    if (st) return st;
+    st = check_planes(fb, b_codes, b_sexp, b_mexp);
+    if (st) return st;
+    if (!workspace || workspace_bytes < mx_gemm_workspace_bytes(M, N, K)) return BDR_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return BDR_ERR_ALIGN;
+    return bdr::dot_pipeline(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, r,
+                             f_bits, C, ldc, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // extern "C"

@@ -51,6 +51,10 @@ int quantize_row(const bdr_format &f, const void *x, int dtype, int64_t rows, in
                  int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s);
 int dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
                    int64_t rows, int64_t cols, void *y, int dtype, int64_t ld, hipStream_t s);
+// Table II operand -> BF16, every block taking the exponent code se_code instead of its own
+// (rows * cols a multiple of 32; the exponent plane is not read).
+int dequantize_row_fixed_exponent(const bdr_format &f, const void *codes, const void *mexp, int64_t rows,
+                                  int64_t cols, void *y, int se_code, hipStream_t s);
 int gather_dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
                           int64_t table_rows, int64_t cols, const int64_t *idx, int64_t n_idx, void *y,
                           int dtype, hipStream_t s);
@@ -92,5 +96,11 @@ int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void 
            int64_t rows, int64_t K, int64_t K_out, void *out, bool b_operand, hipStream_t s);
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
              hipStream_t s);
+
+// The dot-product pipeline model (mx_dot_pipeline.hip); arguments validated by the caller.
+int dot_pipeline(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,
+                 const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+                 int64_t M, int64_t N, int64_t K, int64_t r, int f_bits, float *C, int64_t ldc,
+                 void *workspace, hipStream_t s);
 
 }  // namespace bdr

@@ -149,8 +149,12 @@ struct GatherArgs {
     const int64_t *idx;
     int64_t table_rows;
     int32_t groups_per_row;  // cols / 8, a multiple of 4
+    int32_t fixed_se;        // FIXED_SE: the exponent code every block is given
 };
-template <int MB, typename T, bool GATHER = false>
+// FIXED_SE: the exponent plane is not read; every block takes the exponent code
+// ga.fixed_se instead, which turns the elements into the scaled integers
+// M 2^(fixed_se - 127 - (MB - 1) - tau) (used by the dot-product pipeline model).
+template <int MB, typename T, bool GATHER = false, bool FIXED_SE = false>
 __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups, GatherArgs ga)
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
                 const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 3 * quad;
                 v0[it] = cw[i < 2 ? i : 2];
             }
-            seb[it] = sexp[g >> 1];
+            seb[it] = FIXED_SE ? (uint32_t)ga.fixed_se : sexp[g >> 1];
             tbb[it] = mexp[g >> 1];
         }
     }
@@ -819,6 +823,26 @@ int dequantize_row(const bdr_format &f, const void *codes, const void *sexp, con
                             (const uint8_t *)mexp, rows, cols, (uint16_t *)y, ld, s);
 }
 
+// BF16 image of a Table II operand with every block's exponent code replaced by se_code.
+int dequantize_row_fixed_exponent(const bdr_format &f, const void *codes, const void *mexp, int64_t rows,
+                                  int64_t cols, void *y, int se_code, hipStream_t s)
+{
+    const int64_t ng = rows * cols / 8;
+    const dim3 block(kThreads);
+    const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
+    const uint8_t *c = (const uint8_t *)codes, *m = (const uint8_t *)mexp;
+    uint16_t *out = (uint16_t *)y;
+    GatherArgs ga{};
+    ga.fixed_se = se_code;
+    if (f.m == 7)
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, uint16_t, false, true>), fgrid, block, 0, s, c, c, m, out, ng, ga);
+    else if (f.m == 4)
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, uint16_t, false, true>), fgrid, block, 0, s, c, c, m, out, ng, ga);
+    else
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, uint16_t, false, true>), fgrid, block, 0, s, c, c, m, out, ng, ga);
+    return launch_status();
+}
+
 template <typename T>
 static int gather_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t *sexp,
                         const uint8_t *mexp, int64_t table_rows, int64_t cols, const int64_t *idx,
@@ -827,7 +851,7 @@ static int gather_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t
     const int64_t ng = n_idx * cols / 8;
     const dim3 block(kThreads);
     const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
-    const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8)};
+    const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0};
     if (f.m == 7)
         hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
     else if (f.m == 4)

@@ -20,7 +20,7 @@ OK, ERR_NULL, ERR_FORMAT, ERR_SHAPE, ERR_ALIGN, ERR_DTYPE, ERR_LAUNCH, ERR_WS = 
 def test_exports_match_header():
     text = open(os.path.join(ROOT, "include", "bdr_mx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(bdr_\w+|mx_gemm\w*)\s*\(", text))
+    names = set(re.findall(r"\b(bdr_\w+|mx_\w+)\s*\(", text))
     names -= {"bdr_format"}
     assert names == set(B.EXPORTS)
     for n in names:
@@ -153,6 +153,22 @@ def test_sweep_and_gemm_argument_checks():
     assert gm(ws=FAKE_ODD, wsb=need) == ERR_ALIGN
 
 
+def test_dot_pipeline_argument_checks():
+    L, f = B.lib, B.MX6
+    need = L.mx_dot_pipeline_workspace_bytes(128, 128, 128)
+    assert need == 2 * 128 * 128 * 2 == L.mx_gemm_workspace_bytes(128, 128, 128)
+    dp = lambda fa=f, fb=f, M=128, N=128, K=128, r=64, fbits=25, C=FAKE, ldc=128, a=FAKE, ws=FAKE, wsb=need: \
+        L.mx_dot_pipeline(ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, r,
+                          fbits, C, ldc, ws, wsb, NULL)
+    assert dp(fa=B.fmt(32, 2, 1, 4)) == ERR_FORMAT and dp(fb=B.fmt(16, 2, 2, 4)) == ERR_FORMAT
+    assert dp(K=0) == ERR_SHAPE and dp(K=96) == ERR_SHAPE and dp(M=-1) == ERR_SHAPE and dp(ldc=64) == ERR_SHAPE
+    assert dp(r=32) == ERR_SHAPE and dp(r=96) == ERR_SHAPE and dp(r=0) == ERR_SHAPE and dp(r=256) == ERR_SHAPE
+    assert dp(fbits=1) == ERR_SHAPE and dp(fbits=27) == ERR_SHAPE
+    assert dp(C=NULL) == ERR_NULL and dp(a=NULL) == ERR_NULL
+    assert dp(ws=NULL) == ERR_WS and dp(wsb=need - 1) == ERR_WS and dp(ws=FAKE_ODD) == ERR_ALIGN
+    assert dp(M=0) == OK
+
+
 def test_resources_are_asked_for_before_the_first_launch():
     # A sweep of more than 63 distinct quantizers needs more than 64 KiB of LDS per workgroup,
     # which a kernel has to be granted once per device.  That request is made for every chunk of
@@ -218,7 +234,8 @@ def test_header_is_plain_c(tmp_path):
         "                   (void *)bdr_tile_packing, (void *)bdr_quantize_dequantize,\n"
         "                   (void *)bdr_qsnr_sweep_workspace_bytes, (void *)bdr_qsnr_sweep,\n"
         "                   (void *)bdr_qsnr_sweep_static, (void *)bdr_qsnr_sweep_static_scratch_bytes,\n"
-        "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm};\n"
+        "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm,\n"
+        "                   (void *)mx_dot_pipeline_workspace_bytes, (void *)mx_dot_pipeline};\n"
         "    (void)fns;\n"
         "    return bdr_packed_sizes(&mx9, 4, 64, BDR_AXIS_ROW, &a, &b, &c) + mx6.m + mx4.m;\n"
         "}\n")
