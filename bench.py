@@ -19,6 +19,7 @@ Prints ONE JSON line.  Besides the contract keys it carries
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -511,6 +512,41 @@ def other_legs(B, S, torch, timed):
         del p9a, p9b, Cfp
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
+    try:
+        # the paper's own dot-product pipeline (Sec. IV-B), modelled bit for bit: how far is the
+        # FP32-accumulating matrix-core path from it?  Both add the same exact products; the
+        # reference is the FP64 product of the dequantized operands.
+        M = N = K = 8192
+        A, Bm = S.gemm_operands(M, N, K, device="cuda")
+        C = torch.empty(M, N, device="cuda")
+        ws = torch.empty(B.mx_gemm_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        leg = {}
+        for name, f in (("MX6", B.MX6), ("MX9", B.MX9)):
+            pa, pb = B.bdr_quantize(f, A), B.bdr_quantize(f, Bm)
+            ref = B.bdr_dequantize(f, pa, M, K).double() @ B.bdr_dequantize(f, pb, N, K).double().t()
+            sig = ref.square().sum()
+
+            def acc_qsnr(c):
+                err = (c.double() - ref).square().sum().item()
+                # no error at all (every sum exactly representable): reported as the string "exact"
+                return round(10 * math.log10(sig.item() / err), 2) if err > 0 else "exact"
+            ent = {}
+            for r in (64, K):
+                t = timed(lambda: B.mx_dot_pipeline(f, f, pa, pb, M, N, K, r=r, f_bits=25, out=C, workspace=ws),
+                          reps=5, inner=4, warm=2)
+                ent["r_%d" % r] = {"ms": round(t, 3), "TFLOPs_equivalent": round(2.0 * M * N * K / (t * 1e-3) / 1e12, 1),
+                                   "qsnr_db_vs_fp64_product": acc_qsnr(C)}
+            B.mx_gemm(f, f, pa, pb, M, N, K, out=C, workspace=ws)
+            ent["mx_gemm_two_pass_qsnr_db_vs_fp64_product"] = acc_qsnr(C)
+            B.mx_gemm(f, f, pa, pb, M, N, K, out=C)
+            ent["mx_gemm_single_kernel_qsnr_db_vs_fp64_product"] = acc_qsnr(C)
+            leg[name] = ent
+            del pa, pb, ref
+        leg["f_bits"] = 25
+        out["mx_dot_pipeline_8192"] = leg
+        del A, Bm, C, ws
+    except B.BdrError as e:
+        out["mx_dot_pipeline_8192"] = {"error": str(e)}
     try:
         # embedding-table lookups from MX6 storage (Sec. V): 2^20 rows x 128, 2^20 random rows
         rows_t, cols_t, n_look = 1 << 20, 128, 1 << 20

@@ -154,7 +154,12 @@ struct GatherArgs {
 // FIXED_SE: the exponent plane is not read; every block takes the exponent code
 // ga.fixed_se instead, which turns the elements into the scaled integers
 // M 2^(fixed_se - 127 - (MB - 1) - tau) (used by the dot-product pipeline model).
-template <int MB, typename T, bool GATHER = false, bool FIXED_SE = false>
+//
+// LK1, LK2, D2: log2 k1 (3 .. 6), log2 k2 (<= LK1) and d2 (0 or 1) of the format; Table II's
+// own (4, 1, 1) by default.  Only where the lane finds its exponent byte and its microexponent
+// bits depends on them: the codes of 8 elements are MB + 1 bytes whatever the block sizes.
+template <int MB, typename T, bool GATHER = false, bool FIXED_SE = false, int LK1 = 4, int LK2 = 1,
+          int D2 = 1>
 __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups, GatherArgs ga)
@@ -198,8 +203,11 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
                 const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 3 * quad;
                 v0[it] = cw[i < 2 ? i : 2];
             }
-            seb[it] = FIXED_SE ? (uint32_t)ga.fixed_se : sexp[g >> 1];
-            tbb[it] = mexp[g >> 1];
+            seb[it] = FIXED_SE ? (uint32_t)ga.fixed_se : sexp[g >> (LK1 - 3)];
+            // the byte that holds the lane's microexponent bits: 8 >> LK2 of them from bit
+            // g (8 >> LK2) of the stream when k2 <= 8, else the one bit of sub-block
+            // g / (k2 / 8); byte g >> LK2 either way
+            if (D2) tbb[it] = mexp[g >> LK2];
         }
     }
 #pragma unroll
@@ -223,7 +231,11 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
             lo = funnel_r(v0[it], pv, 24u * i) & 0xffffffu;
         }
         const uint32_t se = seb[it];
-        const uint32_t tau4 = (tbb[it] >> (4u * (i & 1u))) & 0xfu;
+        // the lane's bits moved down to bit 0 (one bit per sub-block; a single bit when the
+        // sub-block is as long as the lane's run or longer)
+        const uint32_t tau4 =
+            LK2 <= 3 ? tbb[it] >> ((uint32_t)(g & ((1 << LK2) - 1)) * (8u >> LK2))
+                     : (tbb[it] >> ((uint32_t)(g >> (LK2 - 3)) & 7u)) & 1u;
         uint32_t yb[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -236,7 +248,8 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
             else
                 c = lo >> off;
             c &= CMASK;
-            const int q = (int)se - 127 - (int)((tau4 >> (e >> 1)) & 1u) - (MB - 1);
+            const int t = D2 ? (int)((tau4 >> (LK2 <= 3 ? e >> LK2 : 0)) & 1u) : 0;
+            const int q = (int)se - 127 - t - (MB - 1);
             const float v = __builtin_ldexpf((float)(c & MMASK), q);
             yb[e] = as_u(v) | ((c >> MB) << 31);
         }
@@ -722,9 +735,8 @@ static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, i
 }
 
 // Launch the quantize kernel compiled for table entry `spec` (FP32 rows with pitch = row
-// length, whole quads of lanes).  Only quantize has such kernels: dequantize and the fused
-// round trip are bound by their 4-byte-per-element write stream with the tuple at run time
-// already (measured: compiled-in tuples made neither faster).
+// length, whole quads of lanes).  The fused round trip has no such kernels: it is bound by
+// its 2 x 4 bytes per element with the tuple at run time already.
 template <int SP = 0>
 static void launch_hot(int spec, dim3 grid, hipStream_t s, const float *x, uint8_t *codes,
                        uint8_t *sexp, uint8_t *mexp, int64_t cols, int64_t ng)
@@ -733,6 +745,23 @@ static void launch_hot(int spec, dim3 grid, hipStream_t s, const float *x, uint8
         if (spec != SP) return launch_hot<SP + 1>(spec, grid, s, x, codes, sexp, mexp, cols, ng);
         hipLaunchKernelGGL((generic_quantize_kernel<float, 0, false, true, SP>), grid, dim3(kThreads), 0, s,
                            hot_format(SP), x, (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng);
+    }
+}
+
+// Dequantize kernel for table entry `spec`: the Table II kernel with the tuple's block sizes
+// (FP32, pitch = row length, whole quads of lanes).  Reading an image does not depend on the
+// rounding rule, so the table's nearest-even entries serve every rounding.
+template <int SP = 0>
+static void launch_hot_dequantize(int spec, dim3 grid, hipStream_t s, const uint8_t *codes,
+                                  const uint8_t *sexp, const uint8_t *mexp, float *y, int64_t ng)
+{
+    if constexpr (SP < kHotCount) {
+        if (spec != SP) return launch_hot_dequantize<SP + 1>(spec, grid, s, codes, sexp, mexp, y, ng);
+        constexpr GenFmt f = hot_format(SP);
+        constexpr int lk1 = f.k1 == 8 ? 3 : f.k1 == 16 ? 4 : f.k1 == 32 ? 5 : 6;
+        constexpr int lk2 = f.k2 == 1 ? 0 : f.k2 == 2 ? 1 : f.k2 == 4 ? 2 : lk1;
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<f.m, float, false, false, lk1, lk2, f.d2>), grid,
+                           dim3(kThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
     }
 }
 
@@ -800,7 +829,14 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         bool done = false;
         if constexpr (sizeof(T) == 4) {
-            if (ld == cols) {
+            bdr_format fr = f;
+            fr.rounding = BDR_RNE;
+            const int spec = ld == cols && ng % 4 == 0 ? hot_index(fr) : -1;
+            if (spec >= 0) {
+                const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
+                launch_hot_dequantize(spec, fgrid, s, codes, sexp, mexp, y, ng);
+                done = true;
+            } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
                                    codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
                 done = true;
