@@ -543,6 +543,16 @@ def other_legs(B, S, torch, timed):
             leg[name] = ent
             del pa, pb, ref
         leg["f_bits"] = 25
+        # ALU-bound: about 6.1 vector-ALU lane-ops per entry of C and block of K (counted in the
+        # kernel's code: 392 wave instructions per K step of 4 blocks and 16 entries per lane)
+        # against 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
+        lane_ops = 6.1 * M * N * (K // 16)
+        roof_ms = lane_ops / 39.3e12 * 1e3
+        leg["roofline"] = {"bound": "alu", "unit": "T lane-op/s", "peak": 39.3,
+                           "lane_ops_per_entry_and_block": 6.1, "time_at_peak_ms": round(roof_ms, 3),
+                           "achieved": round(lane_ops / (leg["MX6"]["r_%d" % K]["ms"] * 1e-3) / 1e12, 2),
+                           "frac": round(roof_ms / leg["MX6"]["r_%d" % K]["ms"], 4),
+                           "of": "MX6, one pass (r = K)"}
         out["mx_dot_pipeline_8192"] = leg
         del A, Bm, C, ws
     except B.BdrError as e:
