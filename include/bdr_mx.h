@@ -184,9 +184,13 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  * have m <= 4, FP6 elements under one power-of-two scale
  * per block of 16 (M 2^-tau has at most 4 significant bits over 5 binades, which
  * sign + 2 exponent + 3 fraction bits hold), at twice the BF16 rate.
- *   fa, fb : formats of A and B, each one of Table II's family (k1 16, d1 8, k2 2,
- *            d2 1, m 7, 4 or 2, any rounding: it plays no part here), else
- *            BDR_ERR_FORMAT; the two may differ
+ *   fa, fb : formats of A and B; the two may differ.  Table II's family (k1 16, d1 8,
+ *            k2 2, d2 1, m 7, 4 or 2) has kernels of its own in every form.  Any other
+ *            format whose elements BF16 holds exactly (m + 2^d2 - 1 <= 8: e.g. block
+ *            floating point, d2 = 0, which Sec. IV compares against) is taken in the
+ *            two-pass BF16 form, so it needs the workspace (BDR_ERR_WORKSPACE without)
+ *            and K a multiple of its k1; anything else is BDR_ERR_FORMAT.  The rounding
+ *            rule plays no part here
  *   a_*, b_* : device, the three planes of each image as bdr_quantize wrote them
  *            (B is what BDR_AXIS_COL gives on a [K x N] tensor), 16-byte aligned
  *   C      : device, [M x N] floats, pitch ldc >= N elements, fully overwritten

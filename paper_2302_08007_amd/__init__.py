@@ -252,7 +252,8 @@ def mx_gemm_workspace_bytes(M, N, K):
 def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None):
     """C[M, N] = Ahat @ Bhat^T for two packed operands blocked along K.  `workspace`: a
     uint8 tensor of at least mx_gemm_workspace_bytes(M, N, K) bytes selects the two-pass
-    form, None the single-kernel form."""
+    form, None the single-kernel form (Table II formats only; other BF16-exact formats need
+    the workspace)."""
     C = out if out is not None else torch.empty((M, N), dtype=torch.float32,
                                                 device=a_planes[0].device)
     if not (C.is_cuda and C.dtype == torch.float32 and C.dim() == 2 and tuple(C.shape) == (M, N)

@@ -272,9 +272,14 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
     if (st) return st;
     st = check_format(fb);
     if (st) return st;
-    if (!bdr::is_mx_layout(*fa) || !bdr::is_mx_layout(*fb)) return BDR_ERR_FORMAT;
+    // Table II's formats have kernels of their own.  Any other pair of formats whose elements
+    // BF16 holds exactly goes through the two-pass BF16 form (general dequantize to BF16,
+    // then the BF16 product kernel) and therefore needs the workspace.
+    const bool both_mx = bdr::is_mx_layout(*fa) && bdr::is_mx_layout(*fb);
+    if (!both_mx && (!bf16_exact(fa) || !bf16_exact(fb))) return BDR_ERR_FORMAT;
     if (M < 0 || N < 0 || K < 0 || ldc < N) return BDR_ERR_SHAPE;
     if (K % 64 != 0) return BDR_ERR_SHAPE;
+    if (!both_mx && (K % fa->k1 != 0 || K % fb->k1 != 0)) return BDR_ERR_SHAPE;
     if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
     if (M == 0 || N == 0) return BDR_OK;
     if (!C) return BDR_ERR_NULL;
@@ -285,6 +290,7 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         st = check_planes(fb, b_codes, b_sexp, b_mexp);
         if (st) return st;
     }
+    if (!both_mx && K > 0 && !workspace) return BDR_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (workspace && K > 0) {
         // two passes: each operand is rewritten once in the form the matrix cores take, then
@@ -292,7 +298,7 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         if (workspace_bytes < mx_gemm_workspace_bytes(M, N, K)) return BDR_ERR_WORKSPACE;
         if (!aligned16(workspace)) return BDR_ERR_ALIGN;
         char *wa = static_cast<char *>(workspace), *wb = wa + gemm_ws_half(M, K);
-        if (fa->m <= 4 && fb->m <= 4) {
+        if (both_mx && fa->m <= 4 && fb->m <= 4) {
             // MX6 and MX4 elements are exact FP6 values under a per-block power of two:
             // block-scaled FP6 MFMAs, twice the rate of BF16.  One byte per element of
             // workspace; K is brought up to a multiple of 128 with zero blocks.
@@ -303,7 +309,8 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
             if (st) return st;
             return bdr::gemm_fp6(wa, wb, M, N, Kp, C, ldc, s);
         }
-        // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact)
+        // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact);
+        // so is every other format that passed the check above
         st = bdr::dequantize_row(*fa, a_codes, a_sexp, a_mexp, M, K, wa, BDR_BF16, K, s);
         if (st) return st;
         st = bdr::dequantize_row(*fb, b_codes, b_sexp, b_mexp, N, K, wb, BDR_BF16, K, s);

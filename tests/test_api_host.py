@@ -140,7 +140,9 @@ def test_sweep_and_gemm_argument_checks():
     gm = lambda fa=f, fb=f, M=128, N=128, K=64, C=FAKE, ldc=128, a=FAKE, ws=NULL, wsb=0: L.mx_gemm(
         ctypes.byref(fa), ctypes.byref(fb), a, FAKE, FAKE, FAKE, FAKE, FAKE, M, N, K, C, ldc, ws,
         wsb, NULL)
-    assert gm(fa=B.fmt(32, 2, 1, 4)) == ERR_FORMAT
+    assert gm(fa=B.fmt(32, 2, 3, 4)) == ERR_FORMAT       # m + beta = 11: BF16 cannot hold it
+    assert gm(fa=B.fmt(32, 2, 1, 4)) == ERR_WS           # other BF16-exact formats need the workspace
+    assert gm(fa=B.fmt(128, 2, 1, 4), ws=FAKE, wsb=1 << 20) == ERR_SHAPE    # K = 64 is not a multiple of k1
     assert gm(M=-1) == ERR_SHAPE and gm(K=48) == ERR_SHAPE and gm(ldc=64) == ERR_SHAPE
     assert gm(N=(1 << 20) + 1, ldc=(1 << 20) + 1) == ERR_SHAPE
     assert gm(C=NULL) == ERR_NULL and gm(a=NULL) == ERR_NULL

@@ -192,6 +192,37 @@ def test_operands_rounded_another_way_decode_the_same(ws):
         assert torch.equal(C, B.mx_gemm(fa0, fb0, pa, pb, M, N, K, workspace=w))
 
 
+@pytest.mark.parametrize("pair", [
+    (dict(k1=16, k2=16, d2=0, m=7), dict(k1=16, k2=16, d2=0, m=7)),     # MSFP16-like block floating point
+    (dict(k1=16, k2=16, d2=0, m=3), dict(k1=16, k2=2, d2=1, m=4)),      # MSFP12-like x MX6
+    (dict(k1=32, k2=4, d2=1, m=4), dict(k1=64, k2=1, d2=2, m=5, rounding=1)),
+    (dict(k1=8, k2=1, d2=1, m=7), dict(k1=128, k2=8, d2=0, m=8)),
+], ids=lambda p: "%d-%d-%d-%d" % (p[0]["k1"], p[0]["m"], p[1]["k1"], p[1]["m"]))
+def test_formats_outside_table_two(pair):
+    # block floating point (d2 = 0, which the paper's design-space study compares against,
+    # Sec. IV) and other tuples whose elements BF16 holds exactly: two-pass BF16 form
+    fa, fb = B.fmt(**pair[0]), B.fmt(**pair[1])
+    M, N, K = 160, 96, 384
+    A = S.wide_range(M, K, device="cuda", seed=51, spread=6)
+    Bm = S.wide_range(N, K, device="cuda", seed=52, spread=6)
+    pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
+    C = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=_workspace(M, N, K))
+    torch.cuda.synchronize()
+    pan, pbn = _planes_np(pa), _planes_np(pb)
+    Cref = O.mx_gemm(ofmt(fa), ofmt(fb), pan, pbn, M, N, K)
+    Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
+    Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
+    err = np.abs(C.cpu().numpy().astype(np.float64) - Cref)
+    assert np.all(err <= RTOL * (np.abs(Ah) @ np.abs(Bh).T) + 1e-30)
+    with pytest.raises(B.BdrError) as e:
+        B.mx_gemm(fa, fb, pa, pb, M, N, K)                  # no workspace
+    assert e.value.status == 7
+    wide = B.fmt(16, 2, 2, 7)                                # 10 significant bits: not BF16-exact
+    with pytest.raises(B.BdrError) as e:
+        B.mx_gemm(wide, fb, B.bdr_quantize(wide, A), pb, M, N, K, workspace=_workspace(M, N, K))
+    assert e.value.status == 2
+
+
 def test_empty_k_with_many_rows():
     # K = 0 is an empty sum: C is all zeros, also when M is above what one grid axis takes
     M, N = 70000, 24
