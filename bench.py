@@ -108,8 +108,9 @@ def main():
                          "(8192 x 12288, MX9), the gather kernel and general-format kernels, three "
                          "times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--other-probe", action="store_true",
-                    help="run mx_gemm (both forms, 8192^3, MX6 and MX9) and the 64-format sweep a few times and "
-                         "exit (for rocprofv3 --pmc MfmaUtil VALUBusy)")
+                    help="run mx_gemm (both forms, 8192^3, MX6 and MX9), the 64-format sweep and the "
+                         "dot-product pipeline model a few times and exit (for rocprofv3 --kernel-trace "
+                         "and --pmc MfmaUtil VALUBusy)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (blocks are independent, so the path "
@@ -171,9 +172,15 @@ def main():
         wsw = torch.empty(B.lib.bdr_qsnr_sweep_workspace_bytes(len(fmts)), dtype=torch.uint8, device="cuda")
         for i in range(5):
             B.bdr_qsnr_sweep(fmts, xs, workspace=wsw)
+        pa, pb = B.bdr_quantize(B.MX6, A), B.bdr_quantize(B.MX6, Bm)
+        for i in range(5):
+            B.mx_dot_pipeline(B.MX6, B.MX6, pa, pb, M, N, K, r=K, out=C, workspace=ws)
+        for i in range(5):
+            B.mx_dot_pipeline(B.MX6, B.MX6, pa, pb, M, N, K, r=64, out=C, workspace=ws)
         torch.cuda.synchronize()
         print(json.dumps({"other_probe": "45 x two-pass MX6 mx_gemm, 5 x single-kernel MX6 mx_gemm, "
-                                         "10 x two-pass MX9 mx_gemm, 5 x 64-format sweep"}))
+                                         "10 x two-pass MX9 mx_gemm, 5 x 64-format sweep, 5 + 5 x MX6 "
+                                         "mx_dot_pipeline (one pass, r = 64), all at 8192^3"}))
         return
 
     if args.pmc_probe:
