@@ -25,6 +25,12 @@ def test_calls_replay_from_a_graph():
     pa = B.alloc_planes(f, M, cols)
     C = torch.empty(M, N, device="cuda")
     gws = torch.empty(B.mx_gemm_workspace_bytes(M, N, cols), dtype=torch.uint8, device="cuda")
+    out_s = (torch.empty(len(fmts), dtype=torch.float64, device="cuda"),
+             torch.empty(len(fmts) + 1, dtype=torch.float64, device="cuda"))
+    fh = B.fmt(32, 2, 1, 4)                      # a tuple with kernels compiled for it
+    ph = B.alloc_planes(fh, rows, cols)
+    yh = torch.empty_like(x)
+    Cp = torch.empty(M, N, device="cuda")
 
     def work():
         B.bdr_quantize(f, x, out=planes)
@@ -33,6 +39,10 @@ def test_calls_replay_from_a_graph():
         B.bdr_qsnr_sweep(fmts, x, workspace=ws, out=out)
         B.bdr_quantize(f, x[:M], out=pa)
         B.mx_gemm(f, f, pa, pa, M, N, cols, out=C, workspace=gws)
+        B.bdr_qsnr_sweep_static(fmts, x, out_s)                     # the library's own scratch array
+        B.bdr_quantize(fh, x, out=ph)
+        B.bdr_dequantize(fh, ph, rows, cols, out=yh)
+        B.mx_dot_pipeline(f, f, pa, pa, M, N, cols, r=256, out=Cp, workspace=gws)
 
     x.copy_(S.wide_range(rows, cols, device="cuda", seed=0, spread=3))
     work()                      # first use outside the capture (one-time kernel attributes)
@@ -44,12 +54,13 @@ def test_calls_replay_from_a_graph():
         x.copy_(S.wide_range(rows, cols, device="cuda", seed=seed, spread=3))
         graph.replay()
         torch.cuda.synchronize()
-        got = [t.clone() for t in (*planes, y, yf, out[0], out[1], C)]
-        for t in (*planes, y, yf, out[0], out[1], C):
+        every = (*planes, y, yf, out[0], out[1], C, out_s[0], out_s[1], *ph, yh, Cp)
+        got = [t.clone() for t in every]
+        for t in every:
             t.zero_()           # eager work of the program between replays
         work()
         torch.cuda.synchronize()
-        want = (*planes, y, yf, out[0], out[1], C)
+        want = every
         for a, b in zip(got, want):
             a = a.view(torch.uint8) if a.dtype != torch.uint8 else a
             b = b.view(torch.uint8) if b.dtype != torch.uint8 else b
