@@ -344,7 +344,7 @@ def profile_commit(path):
     try:
         for line in open(path):
             if line.startswith("commit:"):
-                return line.split(":", 1)[1].strip()
+                return line.split(":", 1)[1].split()[0]
     except OSError:
         pass
     return None
