@@ -96,6 +96,13 @@ int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void 
            int64_t rows, int64_t K, int64_t K_out, void *out, bool b_operand, hipStream_t s);
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
              hipStream_t s);
+// The FP4 form of the two-pass product (MX4 x MX4): image writer, size of its scale image,
+// and the product on two such images (K_out % 256 == 0).
+int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, int64_t K, int64_t K_out,
+           void *out, void *scales, hipStream_t s);
+size_t fp4_scale_bytes(int64_t rows, int64_t K_out);
+int gemm_fp4(const void *A, const void *SA, const void *B, const void *SB, int64_t M, int64_t N, int64_t K,
+             float *C, int64_t ldc, hipStream_t s);
 
 // The dot-product pipeline model (mx_dot_pipeline.hip); arguments validated by the caller.
 int dot_pipeline(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,

@@ -28,6 +28,7 @@
 // datapath.  The FP6 form is the nearest thing this chip offers: small-integer
 // elements under a shared power-of-two scale that the hardware applies.
 #include <type_traits>
+#include <utility>
 
 #include "bdr_device.hpp"
 #include "bdr_internal.hpp"
@@ -52,6 +53,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+// the same in LDS (address space 3: 32-bit addresses, ds_read instructions)
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+typedef __attribute__((address_space(3))) i32x4 lds_i32x4;
+typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
 typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
@@ -385,6 +392,72 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
     }
 }
 
+// MX4 x MX4 goes one step further.  An MX4 element is +-M 2^(SE - 127 - tau - 1) with
+// M <= 3 and tau <= 1: M 2^-tau is one of 0, 0.5, 1, 1.5, 2, 3, all of which the 4-bit E2M1
+// format holds (sign, 2 exponent bits, 1 fraction bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6), and the
+// rest is 2^(SE - 1 - 127), one scale byte per block.  At 4 bits per element a block is
+// 8 bytes, so the image has two blocks per 16-byte chunk and a K step of the product
+// kernel covers 256 elements at the same LDS footprint; that halves the bytes the product
+// kernel moves per flop, which is what bounds the FP6 form.
+//
+// Scale bytes no longer ride in the chunk; they form an image of their own, laid out in the
+// order the product kernel loads it: [128-row group][K step][row in group][16 bytes], the 16
+// bytes being the scales of the step's 8 even blocks and then of its 8 odd blocks (a lane of
+// the MFMA serves blocks of one parity).  Rows are padded to whole groups with zero scales.
+constexpr int kFp4 = 4;  // operand format selector of the f8f6f4 MFMA: E2M1
+
+__global__ __launch_bounds__(256) void mx_to_fp4_kernel(const uint8_t *__restrict__ codes,
+                                                        const uint8_t *__restrict__ sexp,
+                                                        const uint8_t *__restrict__ mexp,
+                                                        int64_t n_pairs, int rows, int row_pairs,
+                                                        int row_pairs_out, u32x4 *__restrict__ out,
+                                                        uint8_t *__restrict__ scales)
+{
+    // index = code (sign << 2 | M) | tau << 3, value = the E2M1 code
+    __shared__ uint8_t s_map[16];
+    if (threadIdx.x < 16u) {
+        const uint32_t idx = threadIdx.x, mag = idx & 3u, sign = (idx >> 2) & 1u, tau = idx >> 3;
+        s_map[idx] = (uint8_t)((sign << 3) | (tau ? mag : 2u * mag - (mag == 3u ? 1u : 0u)));
+    }
+    __syncthreads();
+    // One pair of blocks (one chunk) per thread; n_pairs counts the pairs of the padded image
+    // (rows brought up to a multiple of 128, K to a whole K step of the product kernel).
+    const int64_t po = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (po >= n_pairs) return;
+    const int64_t row = po / row_pairs_out;
+    const int q = (int)(po - row * row_pairs_out);
+    const int nk = row_pairs_out >> 3;
+    uint8_t *sc = scales + ((((row >> 7) * nk + (q >> 3)) * 128 + (row & 127)) * 16 + (q & 7));
+    if (row >= rows || q >= row_pairs) {
+        sc[0] = 0;
+        sc[8] = 0;
+        if (row < rows) out[po] = u32x4{0u, 0u, 0u, 0u};
+        return;
+    }
+    Packed<2> pk;
+    load_packed<2>(codes, sexp, mexp, 2 * (row * row_pairs + q), pk);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const int off = 3 * j;
+        const int k = off >> 5;
+        int sh = off & 31;
+        uint32_t win = pk.c[k];
+        if (sh + 3 > 32) {  // the code straddles two words
+            win = funnel_r(pk.c[(k + 1) % 3], pk.c[k], sh);
+            sh = 0;
+        }
+        const uint32_t tau = (pk.tau16 >> (j >> 1)) & 1u;
+        w[j >> 3] |= (uint32_t)s_map[((win >> sh) & 7u) | (tau << 3)] << (4 * (j & 7));
+    }
+    // rows with bit 4 set hold the two blocks of a chunk in swapped order: the 32 lanes of a
+    // half wave (32 consecutive rows, one block each) then read 32 different 8-byte slots of LDS
+    out[po] = (row & 16) ? u32x4{w[2], w[3], w[0], w[1]} : u32x4{w[0], w[1], w[2], w[3]};
+    // exponent code 0 is never written by the quantizer; it is held at scale byte 0
+    sc[0] = (uint8_t)max((int)(pk.se2 & 0xffu) - 1, 0);
+    sc[8] = (uint8_t)max((int)((pk.se2 >> 8) & 0xffu) - 1, 0);
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane p's data lands at
 // byte 16 p after `lds_block` (which must be the same for the whole wave).
 __device__ __forceinline__ void global_to_lds16(const void *src, void *lds_block)
@@ -406,23 +479,47 @@ __device__ __forceinline__ void global_to_lds16(const void *src, void *lds_block
 // LDS write instructions; the loads of step kt+1 are issued before the MFMAs of
 // step kt, and the fragment reads of sub-step s+1 before the MFMAs of sub-step s.
 //
-// With FP6 set the operands are FP6 block images instead (see mx_to_fp6_kernel): a
+// With FMT = kFmtFp6 the operands are FP6 block images instead (see mx_to_fp6_kernel): a
 // 16-byte chunk is then one block of 16 elements, a row of the tile 8 blocks = 128
 // elements of K, and each 32 x 32 x 16 BF16 MFMA becomes one block-scaled FP6 MFMA
 // over two blocks.  Addresses, swizzle and schedule are the same, byte for byte;
-// `pitch` is the length of an operand row in 2-byte units (K, or K / 2 for FP6).
-template <int WM, int WN, int TM, int TN, bool FP6>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
-    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int N, int pitch,
-    float *__restrict__ C, int64_t ldc)
+// `pitch` is the length of an operand row in 2-byte units (K, K / 2 for FP6, K / 4 for FP4).
+//
+// With FMT = kFmtFp4 (see mx_to_fp4_kernel) a chunk is two blocks, a row of the tile 16
+// blocks = 256 elements of K, and a K step has eight sub-steps: sub-step s takes chunk s,
+// lanes 0-31 its first block, lanes 32-63 its second (stored in swapped order in rows
+// with bit 4 set, which keeps the 8-byte reads free of bank conflicts).  The scale images SA, SB come into
+// LDS beside the tiles (one 16-byte load per row and K step) and each lane keeps the
+// eight scale bytes of its parity of blocks in two registers per fragment row.
+constexpr int kFmtBf16 = 0, kFmtFp6 = 1, kFmtFp4 = 2;
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
 {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <int WM, int WN, int TM, int TN, int FMT, int FILL_SLOTS = (FMT == kFmtFp4 ? 5 : 2)>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, const uint8_t *__restrict__ SA,
+    const uint8_t *__restrict__ SB, int M, int N, int pitch, float *__restrict__ C, int64_t ldc)
+{
+    constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4;
     const int K = pitch;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int NW = WM * WN;
     constexpr int A_BYTES = BM * kPitch, B_BYTES = BN * kPitch;
     constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // 8-row blocks per wave and K step
+    constexpr int NSUB = FP4 ? 8 : 4;                  // sub-steps (fragment reads) per K step
     static_assert(LA >= 1 && LB >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TM % 2 == 0, "tile");
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B]
+    // the scale tiles of a K step are (BM + BN) / 64 pieces of 1 KiB, one per wave
+    static_assert(!FP4 || (BM == 32 * NW && BN == 32 * NW), "one scale piece per wave");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B], FP4: + [2][SA | SB]
 
     const int ntm = (M + BM - 1) / BM, ntn = (N + BN - 1) / BN, total = ntm * ntn;
     int t = blockIdx.x;
@@ -437,20 +534,41 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
         tn = t % ntn;
     }
     const int m0 = tm * BM, n0 = tn * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: everything derived from it (LDS destinations of the direct
+    // loads, tile offsets) then stays out of the vector ALU
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
+    const int nk = K / kBK;
 
-    const uint16_t *ap[LA], *bp[LB];
+    // Vector-ALU instructions between the MFMAs of the steady-state loop cost matrix-pipe time,
+    // so the loop is kept nearly free of them: global addresses are a scalar base that advances
+    // per K step plus a fixed 32-bit lane offset; LDS read addresses are computed once per
+    // sub-step (all fragments of a lane share the swizzle, rows 32 apart, so fragment i is an
+    // immediate offset) and flipped between the two buffers with one XOR per K step.
+    const uint8_t *a_base = reinterpret_cast<const uint8_t *>(A + (int64_t)m0 * K);
+    const uint8_t *b_base = reinterpret_cast<const uint8_t *>(B + (int64_t)n0 * K);
+    uint32_t a_off[LA], b_off[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int row = (wave * LA + i) * 8 + (lane >> 3);
         // rows past the edge of an operand repeat its last row (their products are never stored)
-        ap[i] = A + (int64_t)min(m0 + row, M - 1) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
+        a_off[i] = (uint32_t)(min(row, M - 1 - m0) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7))) * 2u;
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int row = (wave * LB + i) * 8 + (lane >> 3);
-        bp[i] = B + (int64_t)min(n0 + row, N - 1) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7));
+        b_off[i] = (uint32_t)(min(row, N - 1 - n0) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7))) * 2u;
+    }
+    // FP4: this wave's piece of the scale tiles, 64 rows of one operand; lane p brings row p's
+    // 16 bytes.  The image is padded to whole 128-row groups, so no row needs clamping.
+    const uint8_t *s_base = nullptr;
+    int s_piece = 0;
+    if constexpr (FP4) {
+        const bool is_b = wave >= NW / 2;
+        const int piece = wave % (NW / 2), row0 = (is_b ? n0 : m0) + piece * 64;
+        s_base = (is_b ? SB : SA) + (((int64_t)(row0 >> 7) * nk) * 128 + (row0 & 127)) * 16;
+        s_piece = (is_b ? BM * 16 : 0) + piece * 1024;
     }
 
     f32x16 acc[TM][TN];
@@ -461,42 +579,105 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = K / kBK;
-    auto fill = [&](uint8_t *dst) {  // one K step of both operands, then advance
+    // One K step of both operands is kLoads direct loads per wave.  They are issued in kSlots
+    // groups, one group per sub-step, so that the memory pipeline takes them in a trickle and
+    // no wave sits in a queue of loads while the matrix pipe runs dry; the last group leaves
+    // the rest of the K step for its data to arrive.
+    constexpr int kLoads = LA + LB + (FP4 ? 1 : 0);
+    constexpr int kSlots = FILL_SLOTS, kPerSlot = (kLoads + kSlots - 1) / kSlots;
+    static_assert(kSlots >= 1 && kSlots <= NSUB - 1, "fill slots are sub-steps before the last");
+    auto fill_slot = [&](auto SLOT, uint8_t *dst, uint8_t *sdst) {
+        constexpr int slot = decltype(SLOT)::value;
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            global_to_lds16(ap[i], dst + (wave * LA + i) * 8 * kPitch);
-            ap[i] += kBK;
+        for (int q = slot * kPerSlot; q < (slot + 1) * kPerSlot && q < kLoads; ++q) {
+            if (q < LA)
+                global_to_lds16(a_base + a_off[q], dst + (wave * LA + q) * 8 * kPitch);
+            else if (q < LA + LB)
+                global_to_lds16(b_base + b_off[q - LA], dst + A_BYTES + (wave * LB + (q - LA)) * 8 * kPitch);
+            else if constexpr (FP4)
+                global_to_lds16(s_base + lane * 16, sdst + s_piece);
         }
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            global_to_lds16(bp[i], dst + A_BYTES + (wave * LB + i) * 8 * kPitch);
-            bp[i] += kBK;
+        if constexpr ((slot + 1) * kPerSlot >= kLoads && slot * kPerSlot < kLoads) {  // the last group: advance
+            a_base += kBK * 2;
+            b_base += kBK * 2;
+            if constexpr (FP4) s_base += 128 * 16;
         }
+    };
+    auto fill = [&](uint8_t *dst, uint8_t *sdst) {
+        static_for<kSlots>([&](auto SLOT) { fill_slot(SLOT, dst, sdst); });
     };
     const int f_row = lane & 31, f_half = lane >> 5;
-    // A fragment is the 16 bytes of one chunk.  The FP6 MFMA takes six registers per
-    // operand, of which the upper two stay zero for the whole kernel: the fragment
-    // variables are eight wide and a read replaces only their lower half.
-    using Frag = typename std::conditional<FP6, i32x8, u32x4>::type;
-    auto read_frag = [&](const uint8_t *p, Frag &f) {
+    // A fragment is the 16 bytes of one chunk (FP4: the 8 bytes of one block).  The FP6 MFMA
+    // takes six registers per operand (FP4: four), of which the upper two hold elements 22-31
+    // (16-31) of the lane; those must contribute nothing.  FP6 and FP4 have no infinities or
+    // NaNs, so it is enough that ONE factor of each such product is zero: B fragments keep
+    // zeros there for the whole kernel (the fragment variables are eight wide and a read
+    // replaces only their lower part), A fragments leave those registers undefined.
+    using Frag = typename std::conditional<FMT != kFmtBf16, i32x8, u32x4>::type;
+    auto read_frag = [&](uint32_t at, Frag &f, auto keep_zeros) {  // `at`: an LDS byte address
+        constexpr bool Z = decltype(keep_zeros)::value;
         if constexpr (FP6) {
-            const i32x4 v = *reinterpret_cast<const i32x4 *>(p);
-            const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 2, 3, 0, 1, 2, 3);
-            f = __builtin_shufflevector(wide, f, 0, 1, 2, 3, 12, 13, 14, 15);
+            const i32x4 v = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
+            if constexpr (Z) {
+                const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 2, 3, 0, 1, 2, 3);
+                f = __builtin_shufflevector(wide, f, 0, 1, 2, 3, 12, 13, 14, 15);
+            } else {
+                f = __builtin_shufflevector(v, v, 0, 1, 2, 3, -1, -1, -1, -1);
+            }
+        } else if constexpr (FP4) {
+            // volatile: two 8-byte reads fused into one instruction land in one register
+            // tuple and would have to be copied apart again
+            const i32x2 v = *reinterpret_cast<const volatile lds_i32x2 *>((uintptr_t)at);
+            if constexpr (Z) {
+                const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 0, 1, 0, 1, 0, 1);
+                f = __builtin_shufflevector(wide, f, 0, 1, 10, 11, 12, 13, 14, 15);
+            } else {
+                f = __builtin_shufflevector(v, v, 0, 1, -1, -1, -1, -1, -1, -1);
+            }
         } else {
-            f = *reinterpret_cast<const u32x4 *>(p);
+            const i32x4 v = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
+            f = __builtin_bit_cast(u32x4, v);
         }
     };
-    auto read_frags = [&](const uint8_t *cur, int sub, Frag (&fa)[TM], Frag (&fb)[TN]) {
+    // LDS byte addresses of this lane's fragment 0 of each sub-step, in the buffer that
+    // sub-step is read from next.  A read moves its address to the other buffer: +flip for
+    // the sub-steps read from cur, -flip for sub-step 0 (read ahead from nxt), and flip
+    // changes sign every K step.
+    constexpr int kBuf = A_BYTES + B_BYTES, kSBuf = (BM + BN) * 16;
+    const uint32_t smem_at = (uint32_t)(uintptr_t)(lds_u8 *)smem;
+    uint32_t ra[NSUB], rb[NSUB];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            read_frag(cur + lds_chunk((wm * TM + i) * 32 + f_row, 2 * sub + f_half), fa[i]);
+    for (int sub = 0; sub < NSUB; ++sub) {
+        const int chunk = FP4 ? sub : 2 * sub + f_half, byte = FP4 ? 8 * (f_half ^ (f_row >> 4)) : 0;
+        const uint32_t pos = smem_at + (uint32_t)(((chunk ^ ((f_row >> 1) & 7)) << 4) + byte);
+        ra[sub] = (uint32_t)((wm * TM * 32 + f_row) * kPitch) + pos;
+        rb[sub] = (uint32_t)(A_BYTES + (wn * TN * 32 + f_row) * kPitch) + pos;
+    }
+    int flip = -kBuf, sflip = -kSBuf;  // the first reads (buffer 0) move on to buffer 1
+    auto read_frags = [&](auto S, Frag (&fa)[TM], Frag (&fb)[TN]) {
+        constexpr int sub = decltype(S)::value;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            read_frag(cur + A_BYTES + lds_chunk((wn * TN + j) * 32 + f_row, 2 * sub + f_half), fb[j]);
+        for (int i = 0; i < TM; ++i) read_frag(ra[sub] + i * 32 * kPitch, fa[i], std::false_type{});
+#pragma unroll
+        for (int j = 0; j < TN; ++j) read_frag(rb[sub] + j * 32 * kPitch, fb[j], std::true_type{});
+        ra[sub] += sub == 0 ? -flip : flip;
+        rb[sub] += sub == 0 ? -flip : flip;
     };
-    auto mfmas = [&](const Frag (&fa)[TM], const Frag (&fb)[TN], int half) {  // half of the tiles
+    // FP4: the scale bytes of this lane's rows for one K step, sub-step s in byte s
+    u32x2 sa[TM], sb[TN], sa_next[TM], sb_next[TN];
+    uint32_t sra = smem_at + 2 * kBuf + (uint32_t)((wm * TM * 32 + f_row) * 16 + 8 * f_half);
+    uint32_t srb = smem_at + 2 * kBuf + (uint32_t)(BM * 16 + (wn * TN * 32 + f_row) * 16 + 8 * f_half);
+    auto read_scales = [&](u32x2 (&xa)[TM], u32x2 (&xb)[TN]) {  // always read ahead, like sub-step 0
+#pragma unroll
+        for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const lds_u32x2 *>((uintptr_t)(sra + i * 32 * 16));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) xb[j] = *reinterpret_cast<const lds_u32x2 *>((uintptr_t)(srb + j * 32 * 16));
+        sra -= sflip;
+        srb -= sflip;
+    };
+    // half of the tiles of sub-step S
+    auto mfmas = [&](auto S, const Frag (&fa)[TM], const Frag (&fb)[TN], int half) {
+        constexpr int sub = decltype(S)::value;
 #pragma unroll
         for (int i = half * (TM / 2); i < (half + 1) * (TM / 2); ++i)
 #pragma unroll
@@ -506,75 +687,89 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
                     // upper 16 are zero; one scale byte per lane, taken from the chunk itself
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                         fa[i], fb[j], acc[i][j], kFp6, kFp6, kScaleByteA, fa[i][3], kScaleByteB, fb[j][3]);
+                } else if constexpr (FP4) {
+                    // the same split of K, the scale from byte sub of the lane's scale registers
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fa[i], fb[j], acc[i][j], kFp4, kFp4, sub & 3, (int)sa[i][sub >> 2], sub & 3,
+                        (int)sb[j][sub >> 2]);
                 } else {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
                 }
             }
     };
-    static_assert(kBK == 64, "the schedule below is written for four sub-steps per K step");
-    // Schedule of one K step (cur holds step kt, nxt is being filled with step kt+1,
-    // fragment set 0 holds sub-step 0 of step kt):
-    //   reads of sub-step 1, 2, 3 are issued before the MFMAs of sub-step 0, 1, 2;
-    //   then wait for everything this wave has in flight and meet the other waves:
-    //   from here on nxt is complete and nobody reads cur any more (the fragments of
-    //   sub-step 3 are in registers), so the fill of step kt+2 into cur and the reads
-    //   of sub-step 0 of step kt+1 are issued and run under the MFMAs of sub-step 3.
-    // The barrier thus costs neither a fragment-read latency nor a load latency: both
-    // have a whole K step (loads) or eight MFMAs (reads) to arrive.
-    uint8_t *cur = smem, *nxt = smem + A_BYTES + B_BYTES;
+    // Schedule of one K step (cur holds step kt, fragment set 0 holds its sub-step 0, nxt is
+    // free: every wave has passed the barrier that ended step kt-1):
+    //   sub-step s < last: half of the MFMAs, then the reads of sub-step s+1 and one group
+    //   of the loads of step kt+1 into nxt, then the other half of the MFMAs;
+    //   then wait for everything this wave has in flight and meet the other waves: from
+    //   here on nxt is complete and nobody reads cur any more (the fragments of the last
+    //   sub-step are in registers), so the reads of sub-step 0 of step kt+1 are issued and
+    //   run under the MFMAs of the last sub-step.
+    // The barrier thus costs neither a fragment-read latency nor a load latency: reads have
+    // eight MFMAs to arrive, loads the rest of the K step.
+    static_assert(NSUB % 2 == 0, "the last sub-step must leave fragment set 0 free");
+    uint8_t *cur = smem, *nxt = smem + kBuf;
+    uint8_t *cur_s = smem + 2 * kBuf, *nxt_s = cur_s + kSBuf;
     Frag fa[2][TM], fb[2][TN];
-    if constexpr (FP6) {
+    if constexpr (FMT != kFmtBf16) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[h][i] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int j = 0; j < TN; ++j) fb[h][j] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
     }
-    fill(cur);
+    constexpr std::integral_constant<int, 0> first{};
+    constexpr std::integral_constant<int, NSUB - 1> last{};
+    fill(cur, cur_s);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (nk > 1) fill(nxt);
-    read_frags(cur, 0, fa[0], fb[0]);
-    // One K step.  The last two steps have nothing left to fill or to read ahead; they are
-    // peeled so that the body of the steady-state loop is one straight block.
-    auto k_step = [&](auto do_fill, auto do_read) {
-        mfmas(fa[0], fb[0], 0);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(cur, 1, fa[1], fb[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[0], fb[0], 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[1], fb[1], 0);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(cur, 2, fa[0], fb[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[1], fb[1], 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[0], fb[0], 0);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(cur, 3, fa[1], fb[1]);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[0], fb[0], 1);
-        __builtin_amdgcn_sched_barrier(0);
+    read_frags(first, fa[0], fb[0]);  // from buffer 0; sub-step 0 now points at buffer 1 = nxt
+    if constexpr (FP4) read_scales(sa, sb);
+    flip = -flip;
+    sflip = -sflip;
+    // One K step; `more` says whether another step follows (loads and read-ahead for it).
+    auto k_step = [&](auto more) {
+        constexpr bool kMore = decltype(more)::value;
+        static_for<NSUB - 1>([&](auto S) {
+            constexpr int s = decltype(S)::value;
+            mfmas(S, fa[s & 1], fb[s & 1], 0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(std::integral_constant<int, s + 1>{}, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+            if constexpr (kMore && s < kSlots) fill_slot(S, nxt, nxt_s);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(S, fa[s & 1], fb[s & 1], 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        mfmas(fa[1], fb[1], 0);
+        mfmas(last, fa[1], fb[1], 0);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (decltype(do_fill)::value) fill(cur);
-        if constexpr (decltype(do_read)::value) read_frags(nxt, 0, fa[0], fb[0]);
+        if constexpr (kMore) {
+            read_frags(first, fa[0], fb[0]);
+            if constexpr (FP4) read_scales(sa_next, sb_next);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(fa[1], fb[1], 1);
+        mfmas(last, fa[1], fb[1], 1);
         __builtin_amdgcn_sched_barrier(0);
+        flip = -flip;
+        sflip = -sflip;
         uint8_t *t2 = cur;
         cur = nxt;
         nxt = t2;
+        if constexpr (FP4) {
+            t2 = cur_s;
+            cur_s = nxt_s;
+            nxt_s = t2;
+            if constexpr (kMore) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) sa[i] = sa_next[i];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) sb[j] = sb_next[j];
+            }
+        }
     };
-    for (int kt = 0; kt + 2 < nk; ++kt) k_step(std::true_type{}, std::true_type{});
-    if (nk > 1) k_step(std::false_type{}, std::true_type{});
-    k_step(std::false_type{}, std::false_type{});
+    for (int kt = 0; kt + 1 < nk; ++kt) k_step(std::true_type{});
+    k_step(std::false_type{});
     store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
                         m0 + BM <= M && n0 + BN <= N);
 }
@@ -615,31 +810,32 @@ int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, cons
     return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
 }
 
-template <int WM, int WN, int TM, int TN, bool FP6>
-int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int pitch, float *C, int64_t ldc,
-              hipStream_t s)
+template <int WM, int WN, int TM, int TN, int FMT>
+int launch_dl(const uint16_t *A, const uint16_t *B, const uint8_t *SA, const uint8_t *SB, int M, int N,
+              int pitch, float *C, int64_t ldc, hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t kLds = 2 * (BM + BN) * (size_t)kPitch;
+    constexpr size_t kLds = 2 * (BM + BN) * (size_t)(kPitch + (FMT == kFmtFp4 ? 16 : 0));
     static signed char granted[kMaxDevices];
     if (kLds > 64 * 1024 &&
-        !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN, FP6>), kLds, granted))
+        !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN, FMT>), kLds, granted))
         return BDR_ERR_LAUNCH;
-    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN, FP6>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
-                       dim3(64 * WM * WN), kLds, s, A, B, M, N, pitch, C, ldc);
+    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN, FMT>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
+                       dim3(64 * WM * WN), kLds, s, A, B, SA, SB, M, N, pitch, C, ldc);
     return launch_status();
 }
 
-template <bool FP6>
-int gemm_dl(const void *A, const void *B, int64_t M, int64_t N, int pitch, float *C, int64_t ldc,
-            hipStream_t s)
+template <int FMT>
+int gemm_dl(const void *A, const void *B, const void *SA, const void *SB, int64_t M, int64_t N, int pitch,
+            float *C, int64_t ldc, hipStream_t s)
 {
     const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+    const uint8_t *sa = (const uint8_t *)SA, *sb = (const uint8_t *)SB;
     if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_dl<2, 4, 4, 2, FP6>(a, b, (int)M, (int)N, pitch, C, ldc, s);
+        const int st = launch_dl<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, pitch, C, ldc, s);
         if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
     }
-    return launch_dl<2, 2, 2, 2, FP6>(a, b, (int)M, (int)N, pitch, C, ldc, s);
+    return launch_dl<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, pitch, C, ldc, s);
 }
 
 // K = 0: one workgroup per row of C (rows on grid.x, which takes up to 2^31 - 1 workgroups;
@@ -672,14 +868,14 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
 int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
               hipStream_t s)
 {
-    return gemm_dl<false>(A, B, M, N, (int)K, C, ldc, s);
+    return gemm_dl<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)K, C, ldc, s);
 }
 
 // C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 128 == 0.
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
              hipStream_t s)
 {
-    return gemm_dl<true>(A, B, M, N, (int)(K / 2), C, ldc, s);
+    return gemm_dl<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 2), C, ldc, s);
 }
 
 // Packed MX6 or MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 16 chunks
@@ -700,6 +896,34 @@ int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void 
         if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<2, true>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
         else hipLaunchKernelGGL((mx_to_fp6_kernel<2, false>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
     }
+    return launch_status();
+}
+
+// The scale image of an FP4 operand: rows padded to whole 128-row groups, 1 byte per block.
+size_t fp4_scale_bytes(int64_t rows, int64_t K_out)
+{
+    return (size_t)((rows + 127) / 128 * 128) * (size_t)(K_out / 16);
+}
+
+// C = A * B^T for FP4 block images (to_fp4) of A [M x K] and B [N x K]; K % 256 == 0.
+int gemm_fp4(const void *A, const void *SA, const void *B, const void *SB, int64_t M, int64_t N, int64_t K,
+             float *C, int64_t ldc, hipStream_t s)
+{
+    return gemm_dl<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 4), C, ldc, s);
+}
+
+// Packed MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 32 chunks of 16
+// bytes at `out` and fp4_scale_bytes(rows, K_out) scale bytes at `scales`; K_out >= K a
+// multiple of 256, blocks past K are zero.
+int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, int64_t K, int64_t K_out,
+           void *out, void *scales, hipStream_t s)
+{
+    if (rows == 0 || K_out == 0) return BDR_OK;
+    const int rp = (int)(K / 32), rpo = (int)(K_out / 32);
+    const int64_t pairs = (rows + 127) / 128 * 128 * rpo;
+    hipLaunchKernelGGL(mx_to_fp4_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t *)codes, (const uint8_t *)sexp, (const uint8_t *)mexp, pairs, (int)rows, rp,
+                       rpo, (u32x4 *)out, (uint8_t *)scales);
     return launch_status();
 }
 

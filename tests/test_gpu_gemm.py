@@ -128,6 +128,21 @@ def test_two_pass_fp6_form_reproduces_every_element(name, side):
         assert torch.equal(torch.signbit(C[keep & (Xh != 0)]), torch.signbit(want[keep & (Xh != 0)]))
 
 
+@pytest.mark.parametrize("shape", [(128, 128, 256), (256, 256, 1024), (384, 130, 320), (200, 517, 832),
+                                   (512, 256, 2048), (129, 128, 256), (127, 256, 512), (256, 256, 192)])
+def test_mx4_pair_fp4_form_shapes(shape):
+    # MX4 x MX4 with M, N >= 128 and K >= 256 runs on 4-bit images with a scale image beside
+    # them: several K steps, K padded up to a whole step (320, 832), both tile shapes, edge
+    # tiles whose rows run past M or N, and the shapes just outside the condition (127 rows,
+    # K = 192), which take the FP6 form.  Block exponents vary so that the scale bytes matter.
+    M, N, K = shape
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=M + 7 * N + K)
+    g = torch.Generator(device="cuda").manual_seed(K)
+    A = A * torch.exp2(torch.randint(-6, 7, (M, K // 16), generator=g, device="cuda").float()).repeat_interleave(16, 1)
+    Bm = Bm * torch.exp2(torch.randint(-6, 7, (N, K // 16), generator=g, device="cuda").float()).repeat_interleave(16, 1)
+    _check(B.MX4, B.MX4, A.contiguous(), Bm.contiguous(), "fp4 %s" % (shape,))
+
+
 @pytest.mark.parametrize("name", ["MX9", "MX6", "MX4"])
 @pytest.mark.parametrize("form", ["single kernel", "two-pass"])
 def test_bf16_forms_reproduce_every_element_down_to_the_lowest_exponent(name, form):
