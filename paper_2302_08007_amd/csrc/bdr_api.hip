@@ -298,11 +298,11 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         if (workspace_bytes < mx_gemm_workspace_bytes(M, N, K)) return BDR_ERR_WORKSPACE;
         if (!aligned16(workspace)) return BDR_ERR_ALIGN;
         char *wa = static_cast<char *>(workspace), *wb = wa + gemm_ws_half(M, K);
-        if (both_mx && fa->m == 2 && fb->m == 2 && M >= 128 && N >= 128 && K >= 256) {
+        if (both_mx && fa->m == 2 && fb->m == 2 && M >= 128 && N >= 128 && K >= 128) {
             // MX4 x MX4: both operands as 4-bit E2M1 images, half a byte per element plus one
-            // scale byte per block in an image of its own (rows padded to 128, K to 256).  The
+            // scale byte per block in an image of its own (rows padded to 128, K to 128).  The
             // size conditions keep both inside the operand's half of the workspace.
-            const int64_t Kp = (K + 255) / 256 * 256;
+            const int64_t Kp = (K + 127) / 128 * 128;
             char *sa = wa + (size_t)M * (size_t)(Kp / 2), *sb = wb + (size_t)N * (size_t)(Kp / 2);
             st = bdr::to_fp4(a_codes, a_sexp, a_mexp, M, K, Kp, wa, sa, s);
             if (st) return st;
@@ -312,14 +312,12 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         }
         if (both_mx && fa->m <= 4 && fb->m <= 4) {
             // MX6 and MX4 elements are exact FP6 values under a per-block power of two:
-            // block-scaled FP6 MFMAs, twice the rate of BF16.  One byte per element of
-            // workspace; K is brought up to a multiple of 128 with zero blocks.
-            const int64_t Kp = (K + 127) / 128 * 128;
-            st = bdr::to_fp6(*fa, a_codes, a_sexp, a_mexp, M, K, Kp, wa, false, s);
+            // block-scaled FP6 MFMAs, twice the rate of BF16.  One byte per element of workspace.
+            st = bdr::to_fp6(*fa, a_codes, a_sexp, a_mexp, M, K, wa, false, s);
             if (st) return st;
-            st = bdr::to_fp6(*fb, b_codes, b_sexp, b_mexp, N, K, Kp, wb, true, s);
+            st = bdr::to_fp6(*fb, b_codes, b_sexp, b_mexp, N, K, wb, true, s);
             if (st) return st;
-            return bdr::gemm_fp6(wa, wb, M, N, Kp, C, ldc, s);
+            return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, s);
         }
         // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact);
         // so is every other format that passed the check above

@@ -89,15 +89,14 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
          int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
 int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
               hipStream_t s);
-// MX6 / MX4 planes of a [rows x K] operand -> one 16-byte FP6 chunk per block, rows of
-// K_out / 16 chunks (K_out >= K, zero chunks past K), and the GEMM on two such images
-// (its K is the images' K_out, a multiple of 128).
+// MX6 / MX4 planes of a [rows x K] operand (K % 64 == 0) -> one 16-byte FP6 chunk per block,
+// tiled along K ([K / 64][rows][4 chunks]), and the GEMM on two such images.
 int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
-           int64_t rows, int64_t K, int64_t K_out, void *out, bool b_operand, hipStream_t s);
+           int64_t rows, int64_t K, void *out, bool b_operand, hipStream_t s);
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
              hipStream_t s);
 // The FP4 form of the two-pass product (MX4 x MX4): image writer, size of its scale image,
-// and the product on two such images (K_out % 256 == 0).
+// and the product on two such images (K_out % 128 == 0).
 int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, int64_t K, int64_t K_out,
            void *out, void *scales, hipStream_t s);
 size_t fp4_scale_bytes(int64_t rows, int64_t K_out);

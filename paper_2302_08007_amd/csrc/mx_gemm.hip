@@ -59,6 +59,7 @@ typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef __attribute__((address_space(3))) i32x4 lds_i32x4;
 typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
 typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
 typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
 typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
@@ -324,8 +325,8 @@ template <int MB, bool B_OPERAND>
 __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restrict__ codes,
                                                         const uint8_t *__restrict__ sexp,
                                                         const uint8_t *__restrict__ mexp,
-                                                        int64_t n_pairs, int row_pairs,
-                                                        int row_pairs_out, u32x4 *__restrict__ out)
+                                                        int64_t n_pairs, int rows, int row_pairs,
+                                                        u32x4 *__restrict__ out)
 {
     static_assert(MB == 4 || MB == 2, "MX6 or MX4");
     constexpr int CB = MB + 1;
@@ -344,23 +345,13 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
         s_map[idx] = (uint8_t)((sign << 5) | em);
     }
     __syncthreads();
-    // Two blocks per thread.  A row of the operand has row_pairs pairs of blocks; the image
-    // has row_pairs_out >= row_pairs per row, the excess being zero chunks (K brought up to
-    // a whole K step of the product kernel).  n_pairs counts pairs of the image.
-    const int64_t po = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (po >= n_pairs) return;
-    int64_t p = po;
-    if (row_pairs_out != row_pairs) {
-        const int64_t row = po / row_pairs_out;
-        const int q = (int)(po - row * row_pairs_out);
-        if (q >= row_pairs) {
-            const u32x4 zero = {0u, 0u, 0u, 0u};
-            out[2 * po] = zero;
-            out[2 * po + 1] = zero;
-            return;
-        }
-        p = row * row_pairs + q;
-    }
+    // Two blocks per thread; n_pairs = rows * row_pairs.  The image is tiled along K for the
+    // product kernel: [K step of 4 blocks][row][4 chunks].
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= n_pairs) return;
+    const int64_t row = p / row_pairs;
+    const int q = (int)(p - row * row_pairs);
+    u32x4 *const dst = out + (((int64_t)(q >> 1) * rows + row) * 4 + 2 * (q & 1));
     Packed<MB> pk;
     load_packed<MB>(codes, sexp, mexp, 2 * p, pk);
 #pragma unroll
@@ -388,7 +379,7 @@ __global__ __launch_bounds__(256) void mx_to_fp6_kernel(const uint8_t *__restric
             if ((bit & 31) + 6 > 32) w[(bit >> 5) + 1] |= c6 >> (32 - (bit & 31));
         }
         const u32x4 chunk = {w[0], w[1], w[2], (uint32_t)scale << (B_OPERAND ? 8 * kScaleByteB : 8 * kScaleByteA)};
-        out[2 * po + b] = chunk;
+        dst[b] = chunk;
     }
 }
 
@@ -421,17 +412,19 @@ __global__ __launch_bounds__(256) void mx_to_fp4_kernel(const uint8_t *__restric
     }
     __syncthreads();
     // One pair of blocks (one chunk) per thread; n_pairs counts the pairs of the padded image
-    // (rows brought up to a multiple of 128, K to a whole K step of the product kernel).
+    // (rows brought up to a multiple of 128, K to a whole K step of 8 blocks).  Both images are
+    // tiled along K: chunks as [K step][row][4 chunks], scales as [K step][padded row][8 bytes].
     const int64_t po = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (po >= n_pairs) return;
     const int64_t row = po / row_pairs_out;
     const int q = (int)(po - row * row_pairs_out);
-    const int nk = row_pairs_out >> 3;
-    uint8_t *sc = scales + ((((row >> 7) * nk + (q >> 3)) * 128 + (row & 127)) * 16 + (q & 7));
+    const int64_t rows_pad = ((int64_t)rows + 127) / 128 * 128;
+    uint8_t *sc = scales + (((int64_t)(q >> 2) * rows_pad + row) * 8 + (q & 3));
+    u32x4 *const dst = out + (((int64_t)(q >> 2) * rows + row) * 4 + (q & 3));
     if (row >= rows || q >= row_pairs) {
         sc[0] = 0;
-        sc[8] = 0;
-        if (row < rows) out[po] = u32x4{0u, 0u, 0u, 0u};
+        sc[4] = 0;
+        if (row < rows) *dst = u32x4{0u, 0u, 0u, 0u};
         return;
     }
     Packed<2> pk;
@@ -452,10 +445,10 @@ __global__ __launch_bounds__(256) void mx_to_fp4_kernel(const uint8_t *__restric
     }
     // rows with bit 4 set hold the two blocks of a chunk in swapped order: the 32 lanes of a
     // half wave (32 consecutive rows, one block each) then read 32 different 8-byte slots of LDS
-    out[po] = (row & 16) ? u32x4{w[2], w[3], w[0], w[1]} : u32x4{w[0], w[1], w[2], w[3]};
+    *dst = (row & 16) ? u32x4{w[2], w[3], w[0], w[1]} : u32x4{w[0], w[1], w[2], w[3]};
     // exponent code 0 is never written by the quantizer; it is held at scale byte 0
     sc[0] = (uint8_t)max((int)(pk.se2 & 0xffu) - 1, 0);
-    sc[8] = (uint8_t)max((int)((pk.se2 >> 8) & 0xffu) - 1, 0);
+    sc[4] = (uint8_t)max((int)((pk.se2 >> 8) & 0xffu) - 1, 0);
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane p's data lands at
@@ -774,6 +767,304 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
                         m0 + BM <= M && n0 + BN <= N);
 }
 
+// The product on FP6 or FP4 block images with a ring of four LDS stages.
+//
+// With two stages the loads of step kt+1 are all that is in flight while step kt computes,
+// and every barrier waits until the last of them has landed: the memory pipeline drains
+// once per K step, and at 256 x 256 that drain takes about as long as the MFMAs of the
+// step.  Here a stage holds 64 bytes per tile row (half as much), four stages fit the same
+// LDS, and the loads of steps kt+1 .. kt+3 are in flight together: the barrier at the end
+// of step kt needs only step kt+1 complete (vmcnt counts loads in order, so "at most the
+// loads of two steps outstanding" says exactly that).
+//
+// The images are tiled along K to match: [K step][row][64 bytes], so that the 16 rows one
+// wave instruction brings are 1 KiB of consecutive memory (whole cache lines).
+//   FP6: 64 bytes = 4 blocks = 2 sub-steps (lanes 0-31 take block 2 s, lanes 32-63 block 2 s + 1)
+//   FP4: 64 bytes = 8 blocks = 4 sub-steps (chunk s, one 8-byte block per half wave), and a
+//        scale image [K step][row padded to 128][8 bytes]: the step's four even-block scales,
+//        then its four odd-block scales
+// LDS rows are 64 bytes = a quarter of the banks: the 16 lanes served together (16
+// consecutive rows) are conflict-free when chunk c of row r sits at position
+// c ^ ((r >> 2) & 3).
+constexpr int kRingRow = 64, kRingStages = 4;
+
+// Wait until at most N of this wave's vector-memory loads are outstanding and all its LDS
+// reads have returned, then meet the other waves.  __syncthreads() would not do: its fences
+// wait for every outstanding load, which is exactly the drain the ring is there to avoid.
+// The data hazards are covered by hand: a stage is read only after a barrier that every wave
+// reached with that stage's loads landed, and refilled only after a barrier that every wave
+// reached with its reads of that stage returned.
+template <int N>
+__device__ __forceinline__ void ring_barrier()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+#endif
+}
+
+template <int WM, int WN, int TM, int TN, int FMT>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
+    const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const uint8_t *__restrict__ SA,
+    const uint8_t *__restrict__ SB, int M, int N, int nk, float *__restrict__ C, int64_t ldc)
+{
+    constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4;
+    static_assert(FP6 || FP4, "block-scaled images only");
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr int NW = WM * WN;
+    constexpr int A_BYTES = BM * kRingRow, B_BYTES = BN * kRingRow, kStage = A_BYTES + B_BYTES;
+    constexpr int kSStage = (BM + BN) * 8;            // FP4: scale bytes of one stage
+    constexpr int LA = BM / 16 / NW, LB = BN / 16 / NW;  // 16-row blocks per wave and K step
+    constexpr int kLoads = LA + LB;                   // loads per wave and K step (FP4: some waves one more)
+    constexpr int NSUB = FP4 ? 4 : 2;
+    constexpr int kScaleWaves = (BM + BN) / 128;      // FP4: one 128-row piece of scales per wave
+    static_assert(LA >= 1 && LB >= 1 && BM % (16 * NW) == 0 && BN % (16 * NW) == 0 && TM % 2 == 0, "tile");
+    static_assert((kStage & (kStage - 1)) == 0 && (kSStage & (kSStage - 1)) == 0, "ring positions wrap with a mask");
+    static_assert(BM % 128 == 0 && BN % 128 == 0 && kScaleWaves <= NW, "scale pieces");
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [4][A | B], FP4: + [4][SA | SB]
+
+    const int ntm = (M + BM - 1) / BM, ntn = (N + BN - 1) / BN, total = ntm * ntn;
+    int t = blockIdx.x;
+    if (total % 8 == 0) t = (t % 8) * (total / 8) + t / 8;
+    int tm, tn;
+    if (ntm % 8 == 0) {
+        const int group = t / (8 * ntn);
+        tm = group * 8 + t % 8;
+        tn = (t % (8 * ntn)) / 8;
+    } else {
+        tm = t / ntn;
+        tn = t % ntn;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // global side: a scalar base per operand that moves one K step (all rows x 64 bytes) at a
+    // time, plus a fixed lane offset; lane p of a load brings row p / 4 of its 16-row block,
+    // the chunk that belongs at position p % 4 of that row
+    const uint8_t *a_base = A + (int64_t)m0 * kRingRow, *b_base = B + (int64_t)n0 * kRingRow;
+    const int64_t a_step = (int64_t)M * kRingRow, b_step = (int64_t)N * kRingRow;
+    uint32_t a_off[LA], b_off[LB];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+        const int row = (wave * LA + i) * 16 + (lane >> 2);
+        // rows past the edge of an operand repeat its last row (their products are never stored)
+        a_off[i] = (uint32_t)(min(row, M - 1 - m0) * kRingRow + (((lane & 3) ^ ((row >> 2) & 3)) << 4));
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int row = (wave * LB + i) * 16 + (lane >> 2);
+        b_off[i] = (uint32_t)(min(row, N - 1 - n0) * kRingRow + (((lane & 3) ^ ((row >> 2) & 3)) << 4));
+    }
+    const uint8_t *s_base = nullptr;
+    int64_t s_step = 0;
+    int s_piece = 0;
+    if constexpr (FP4) {
+        if (wave < kScaleWaves) {
+            const bool is_b = wave >= BM / 128;
+            const int piece = is_b ? wave - BM / 128 : wave;
+            const int rows_pad = ((is_b ? N : M) + 127) / 128 * 128;
+            s_base = (is_b ? SB : SA) + ((int64_t)(is_b ? n0 : m0) + piece * 128) * 8 + lane * 16;
+            s_step = (int64_t)rows_pad * 8;
+            s_piece = (is_b ? BM * 8 : 0) + piece * 1024;
+        }
+    }
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // ring positions (byte offsets, scalars): the stage being read and the stage being filled
+    int rd = 0, wr = 0, srd = 0, swr = 0;
+    auto fill = [&]() {  // one K step of both operands into stage wr, then advance
+#pragma unroll
+        for (int i = 0; i < LA; ++i) global_to_lds16(a_base + a_off[i], smem + wr + (wave * LA + i) * 16 * kRingRow);
+#pragma unroll
+        for (int i = 0; i < LB; ++i)
+            global_to_lds16(b_base + b_off[i], smem + wr + A_BYTES + (wave * LB + i) * 16 * kRingRow);
+        a_base += a_step;
+        b_base += b_step;
+        if constexpr (FP4) {
+            if (wave < kScaleWaves) {
+                global_to_lds16(s_base, smem + kRingStages * kStage + swr + s_piece);
+                s_base += s_step;
+            }
+            swr = (swr + kSStage) & (kRingStages * kSStage - 1);
+        }
+        wr = (wr + kStage) & (kRingStages * kStage - 1);
+    };
+
+    const int f_row = lane & 31, f_half = lane >> 5;
+    // Fragments as in gemm_dl_kernel: eight-wide variables of which the MFMA takes the lower
+    // six (FP4: four) registers; B fragments keep zeros above the data for the whole kernel,
+    // A fragments leave those registers undefined (one zero factor per product is enough).
+    using Frag = i32x8;
+    auto read_frag = [&](uint32_t at, Frag &f, auto keep_zeros) {  // `at`: an LDS byte address
+        constexpr bool Z = decltype(keep_zeros)::value;
+        if constexpr (FP6) {
+            const i32x4 v = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
+            if constexpr (Z) {
+                const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 2, 3, 0, 1, 2, 3);
+                f = __builtin_shufflevector(wide, f, 0, 1, 2, 3, 12, 13, 14, 15);
+            } else {
+                f = __builtin_shufflevector(v, v, 0, 1, 2, 3, -1, -1, -1, -1);
+            }
+        } else {
+            // volatile: two 8-byte reads fused into one instruction land in one register
+            // tuple and would have to be copied apart again
+            const i32x2 v = *reinterpret_cast<const volatile lds_i32x2 *>((uintptr_t)at);
+            if constexpr (Z) {
+                const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 0, 1, 0, 1, 0, 1);
+                f = __builtin_shufflevector(wide, f, 0, 1, 10, 11, 12, 13, 14, 15);
+            } else {
+                f = __builtin_shufflevector(v, v, 0, 1, -1, -1, -1, -1, -1, -1);
+            }
+        }
+    };
+    // LDS byte addresses of this lane's fragment 0 of each sub-step within stage 0 (all
+    // fragments of a lane share the swizzle, rows 32 apart: fragment i is an immediate offset)
+    const uint32_t smem_at = (uint32_t)(uintptr_t)(lds_u8 *)smem;
+    uint32_t ra[NSUB], rb[NSUB];
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+        const int chunk = FP4 ? sub : 2 * sub + f_half, byte = FP4 ? 8 * (f_half ^ (f_row >> 4)) : 0;
+        const uint32_t pos = smem_at + (uint32_t)(((chunk ^ ((f_row >> 2) & 3)) << 4) + byte);
+        ra[sub] = (uint32_t)((wm * TM * 32 + f_row) * kRingRow) + pos;
+        rb[sub] = (uint32_t)(A_BYTES + (wn * TN * 32 + f_row) * kRingRow) + pos;
+    }
+    auto read_frags = [&](auto S, int stage, Frag (&fa)[TM], Frag (&fb)[TN]) {
+        constexpr int sub = decltype(S)::value;
+        const uint32_t pa = ra[sub] + (uint32_t)stage, pb = rb[sub] + (uint32_t)stage;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) read_frag(pa + i * 32 * kRingRow, fa[i], std::false_type{});
+#pragma unroll
+        for (int j = 0; j < TN; ++j) read_frag(pb + j * 32 * kRingRow, fb[j], std::true_type{});
+    };
+    // FP4: the four scale bytes of this lane's parity of blocks, sub-step s in byte s
+    uint32_t sa[TM], sb[TN], sa_next[TM], sb_next[TN];
+    const uint32_t sra = smem_at + kRingStages * kStage + (uint32_t)((wm * TM * 32 + f_row) * 8 + 4 * f_half);
+    const uint32_t srb = smem_at + kRingStages * kStage + (uint32_t)(BM * 8 + (wn * TN * 32 + f_row) * 8 + 4 * f_half);
+    auto read_scales = [&](int sstage, uint32_t (&xa)[TM], uint32_t (&xb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const lds_u32 *>((uintptr_t)(sra + sstage + i * 32 * 8));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) xb[j] = *reinterpret_cast<const lds_u32 *>((uintptr_t)(srb + sstage + j * 32 * 8));
+    };
+    auto mfmas = [&](auto S, const Frag (&fa)[TM], const Frag (&fb)[TN], int half) {  // half of the tiles
+        constexpr int sub = decltype(S)::value;
+#pragma unroll
+        for (int i = half * (TM / 2); i < (half + 1) * (TM / 2); ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (FP6) {
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fa[i], fb[j], acc[i][j], kFp6, kFp6, kScaleByteA, fa[i][3], kScaleByteB, fb[j][3]);
+                } else {
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fa[i], fb[j], acc[i][j], kFp4, kFp4, sub, (int)sa[i], sub, (int)sb[j]);
+                }
+            }
+    };
+
+    Frag fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[h][j] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+    constexpr std::integral_constant<int, 0> first{};
+    constexpr std::integral_constant<int, NSUB - 1> last{};
+    static_assert(NSUB % 2 == 0, "the last sub-step must leave fragment set 0 free");
+
+    // stages 0 .. 2 go out at once; then wait for stage 0 alone
+    fill();
+    if (nk > 1) fill();
+    if (nk > 2) fill();
+    if (nk > 2) ring_barrier<2 * kLoads>();
+    else if (nk > 1) ring_barrier<kLoads>();
+    else ring_barrier<0>();
+    read_frags(first, rd, fa[0], fb[0]);
+    if constexpr (FP4) read_scales(srd, sa, sb);
+
+    // One K step (stage rd holds step kt, fragment set 0 its sub-step 0).  AHEAD is the number
+    // of later steps whose loads may still be in flight at the barrier that ends this step
+    // (-1: this is the last step, no barrier); with FILL the loads of step kt+3 go out first,
+    // into the stage that step kt-1 was read from (every wave is past the barrier after it).
+    auto k_step = [&](auto FILL, auto AHEAD) {
+        constexpr int ahead = decltype(AHEAD)::value;
+        static_for<NSUB - 1>([&](auto S) {
+            constexpr int s = decltype(S)::value;
+            mfmas(S, fa[s & 1], fb[s & 1], 0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(std::integral_constant<int, s + 1>{}, rd, fa[(s + 1) & 1], fb[(s + 1) & 1]);
+            if constexpr (decltype(FILL)::value && s == 0) fill();
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(S, fa[s & 1], fb[s & 1], 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        const int next = (rd + kStage) & (kRingStages * kStage - 1);
+        const int snext = (srd + kSStage) & (kRingStages * kSStage - 1);
+        if constexpr (ahead >= 0) ring_barrier<ahead * kLoads>();
+        mfmas(last, fa[1], fb[1], 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (ahead >= 0) {
+            read_frags(first, next, fa[0], fb[0]);
+            if constexpr (FP4) read_scales(snext, sa_next, sb_next);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(last, fa[1], fb[1], 1);
+        __builtin_amdgcn_sched_barrier(0);
+        rd = next;
+        srd = snext;
+        if constexpr (FP4 && ahead >= 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) sa[i] = sa_next[i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) sb[j] = sb_next[j];
+        }
+    };
+    int kt = 0;
+    for (; kt + 3 < nk; ++kt) k_step(std::true_type{}, std::integral_constant<int, 2>{});
+    if (kt + 2 < nk) {
+        k_step(std::false_type{}, std::integral_constant<int, 1>{});
+        ++kt;
+    }
+    if (kt + 1 < nk) k_step(std::false_type{}, std::integral_constant<int, 0>{});
+    k_step(std::false_type{}, std::integral_constant<int, -1>{});
+    store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
+                        m0 + BM <= M && n0 + BN <= N);
+}
+
+template <int WM, int WN, int TM, int TN, int FMT>
+int launch_ring(const uint8_t *A, const uint8_t *B, const uint8_t *SA, const uint8_t *SB, int M, int N, int nk,
+                float *C, int64_t ldc, hipStream_t s)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    constexpr size_t kLds = kRingStages * (BM + BN) * (size_t)(kRingRow + (FMT == kFmtFp4 ? 8 : 0));
+    static signed char granted[kMaxDevices];
+    if (kLds > 64 * 1024 &&
+        !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_ring_kernel<WM, WN, TM, TN, FMT>), kLds, granted))
+        return BDR_ERR_LAUNCH;
+    hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN, FMT>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
+                       dim3(64 * WM * WN), kLds, s, A, B, SA, SB, M, N, nk, C, ldc);
+    return launch_status();
+}
+
+template <int FMT>
+int gemm_ring(const void *A, const void *B, const void *SA, const void *SB, int64_t M, int64_t N, int nk, float *C,
+              int64_t ldc, hipStream_t s)
+{
+    const uint8_t *a = (const uint8_t *)A, *b = (const uint8_t *)B, *sa = (const uint8_t *)SA, *sb = (const uint8_t *)SB;
+    if (M % 256 == 0 && N % 256 == 0) {
+        const int st = launch_ring<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, s);
+        if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
+    }
+    return launch_ring<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, s);
+}
+
 // Two tile shapes: 256 x 256 with 8 waves (128 KiB of LDS, one workgroup per CU)
 // when the device grants that much LDS to a workgroup and M, N allow it, else
 // 128 x 128 with 4 waves (64 KiB).
@@ -871,30 +1162,30 @@ int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, flo
     return gemm_dl<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)K, C, ldc, s);
 }
 
-// C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 128 == 0.
+// C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 64 == 0.
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
              hipStream_t s)
 {
-    return gemm_dl<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 2), C, ldc, s);
+    return gemm_ring<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 64), C, ldc, s);
 }
 
-// Packed MX6 or MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 16 chunks
-// of 16 bytes, K_out >= K a multiple of 32; blocks past K are zero chunks.
+// Packed MX6 or MX4 planes of a [rows x K] operand (K % 64 == 0) -> rows x K / 16 chunks of
+// 16 bytes, tiled along K as the product kernel reads them.
 int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
-           int64_t rows, int64_t K, int64_t K_out, void *out, bool b_operand, hipStream_t s)
+           int64_t rows, int64_t K, void *out, bool b_operand, hipStream_t s)
 {
-    if (rows == 0 || K_out == 0) return BDR_OK;
+    if (rows == 0 || K == 0) return BDR_OK;
     const uint8_t *c = (const uint8_t *)codes, *e = (const uint8_t *)sexp, *m = (const uint8_t *)mexp;
-    const int rp = (int)(K / 32), rpo = (int)(K_out / 32);
-    const int64_t pairs = rows * rpo;
+    const int rp = (int)(K / 32);
+    const int64_t pairs = rows * rp;
     const dim3 grid((unsigned)((pairs + 255) / 256)), block(256);
     u32x4 *o = (u32x4 *)out;
     if (f.m == 4) {
-        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<4, true>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
-        else hipLaunchKernelGGL((mx_to_fp6_kernel<4, false>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
+        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<4, true>), grid, block, 0, s, c, e, m, pairs, (int)rows, rp, o);
+        else hipLaunchKernelGGL((mx_to_fp6_kernel<4, false>), grid, block, 0, s, c, e, m, pairs, (int)rows, rp, o);
     } else {
-        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<2, true>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
-        else hipLaunchKernelGGL((mx_to_fp6_kernel<2, false>), grid, block, 0, s, c, e, m, pairs, rp, rpo, o);
+        if (b_operand) hipLaunchKernelGGL((mx_to_fp6_kernel<2, true>), grid, block, 0, s, c, e, m, pairs, (int)rows, rp, o);
+        else hipLaunchKernelGGL((mx_to_fp6_kernel<2, false>), grid, block, 0, s, c, e, m, pairs, (int)rows, rp, o);
     }
     return launch_status();
 }
@@ -905,16 +1196,16 @@ size_t fp4_scale_bytes(int64_t rows, int64_t K_out)
     return (size_t)((rows + 127) / 128 * 128) * (size_t)(K_out / 16);
 }
 
-// C = A * B^T for FP4 block images (to_fp4) of A [M x K] and B [N x K]; K % 256 == 0.
+// C = A * B^T for FP4 block images (to_fp4) of A [M x K] and B [N x K]; K % 128 == 0.
 int gemm_fp4(const void *A, const void *SA, const void *B, const void *SB, int64_t M, int64_t N, int64_t K,
              float *C, int64_t ldc, hipStream_t s)
 {
-    return gemm_dl<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 4), C, ldc, s);
+    return gemm_ring<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 128), C, ldc, s);
 }
 
 // Packed MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 32 chunks of 16
-// bytes at `out` and fp4_scale_bytes(rows, K_out) scale bytes at `scales`; K_out >= K a
-// multiple of 256, blocks past K are zero.
+// bytes at `out` and fp4_scale_bytes(rows, K_out) scale bytes at `scales`, both tiled along K;
+// K_out >= K a multiple of 128, blocks past K are zero.
 int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, int64_t K, int64_t K_out,
            void *out, void *scales, hipStream_t s)
 {
