@@ -319,8 +319,16 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
             if (st) return st;
             return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, s);
         }
-        // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact);
-        // so is every other format that passed the check above
+        if (both_mx) {
+            // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact),
+            // in the K-tiled layout of the ring kernel
+            st = bdr::to_bf16_tiled(*fa, a_codes, a_sexp, a_mexp, M, K, wa, s);
+            if (st) return st;
+            st = bdr::to_bf16_tiled(*fb, b_codes, b_sexp, b_mexp, N, K, wb, s);
+            if (st) return st;
+            return bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, s);
+        }
+        // any other format that passed the check above: general dequantize to row-major BF16
         st = bdr::dequantize_row(*fa, a_codes, a_sexp, a_mexp, M, K, wa, BDR_BF16, K, s);
         if (st) return st;
         st = bdr::dequantize_row(*fb, b_codes, b_sexp, b_mexp, N, K, wb, BDR_BF16, K, s);

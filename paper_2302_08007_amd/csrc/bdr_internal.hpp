@@ -89,6 +89,12 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
          int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
 int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
               hipStream_t s);
+// Table II planes of a [rows x K] operand -> BF16 tiled along K ([K / 32][rows][32 elements]),
+// and the GEMM on two such images.
+int to_bf16_tiled(const bdr_format &f, const void *codes, const void *sexp, const void *mexp, int64_t rows,
+                  int64_t K, void *out, hipStream_t s);
+int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+                    hipStream_t s);
 // MX6 / MX4 planes of a [rows x K] operand (K % 64 == 0) -> one 16-byte FP6 chunk per block,
 // tiled along K ([K / 64][rows][4 chunks]), and the GEMM on two such images.
 int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,

@@ -18,10 +18,12 @@
 // form the BF16 pair.
 //
 // That is the single-kernel form (mx_gemm_kernel).  The two-pass form rewrites each
-// operand once in global memory and runs gemm_dl_kernel on the two images: BF16
-// images for MX9, and for MX6 / MX4 images of FP6 elements with one scale byte per
-// block, which the block-scaled matrix instruction of gfx950 multiplies at twice
-// the BF16 rate (mx_to_fp6_kernel and the notes above it).
+// operand once in global memory, tiled along K, and runs gemm_ring_kernel on the two
+// images: BF16 images when MX9 takes part; images of FP6 elements with one scale byte per
+// block for MX6 / MX4, which the block-scaled matrix instruction of gfx950 multiplies at
+// twice the BF16 rate (mx_to_fp6_kernel and the notes above it); images of FP4 elements
+// for MX4 x MX4 (mx_to_fp4_kernel).  Formats outside Table II go through the general
+// dequantize kernel and gemm_dl_kernel (row-major BF16).
 //
 // None of this is the dot-product engine of Sec. IV-B (integer Hadamard tree with
 // a conditional shift and fixed-point accumulation): that design targets a custom
@@ -95,15 +97,13 @@ __device__ __forceinline__ void load_packed(const uint8_t *__restrict__ codes,
     p.tau16 = *reinterpret_cast<const uint16_t *>(mexp + blk);
 }
 
-// Expand the 32 elements to BF16 and store them as chunks 4*half .. 4*half+3 of
-// LDS row `row` of the operand tile at `base`.
+// Expand the 32 elements to BF16, two per word.
 // value = (-1)^s * M * 2^(se - 127 - tau - (MB-1)); ldexp makes it exact for every
 // exponent, subnormal results included.
 template <int MB>
-__device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base, int row, int half)
+__device__ __forceinline__ void unpack32(const Packed<MB> &p, uint32_t (&out)[16])
 {
     constexpr int CB = MB + 1;
-    uint32_t out[16];
     int qb[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) qb[b] = (int)((p.se2 >> (8 * b)) & 0xffu) - (127 + MB - 1);
@@ -129,6 +129,14 @@ __device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base
         // the two high halves (exact: the low halves are zero) as one BF16 pair
         out[j] = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u);
     }
+}
+
+// ... and store them as chunks 4*half .. 4*half+3 of LDS row `row` of the operand tile at `base`.
+template <int MB>
+__device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base, int row, int half)
+{
+    uint32_t out[16];
+    unpack32<MB>(p, out);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const u32x4 w = {out[4 * v], out[4 * v + 1], out[4 * v + 2], out[4 * v + 3]};
@@ -463,27 +471,15 @@ __device__ __forceinline__ void global_to_lds16(const void *src, void *lds_block
 #endif
 }
 
-// The same tiling on operands that are already BF16 in memory ([M x K] and [N x K],
-// K contiguous) -- the second half of the two-pass form of mx_gemm, whose first
-// half expands each packed operand once instead of once per tile.  Operands come in
-// by direct global-to-LDS loads: a wave fills eight tile rows (1 KiB) per
-// instruction, lane p supplying the 16 bytes that belong at byte 16 p of that
-// block, i.e. chunk (p & 7) ^ swizzle of row p / 8.  No staging registers and no
-// LDS write instructions; the loads of step kt+1 are issued before the MFMAs of
-// step kt, and the fragment reads of sub-step s+1 before the MFMAs of sub-step s.
-//
-// With FMT = kFmtFp6 the operands are FP6 block images instead (see mx_to_fp6_kernel): a
-// 16-byte chunk is then one block of 16 elements, a row of the tile 8 blocks = 128
-// elements of K, and each 32 x 32 x 16 BF16 MFMA becomes one block-scaled FP6 MFMA
-// over two blocks.  Addresses, swizzle and schedule are the same, byte for byte;
-// `pitch` is the length of an operand row in 2-byte units (K, K / 2 for FP6, K / 4 for FP4).
-//
-// With FMT = kFmtFp4 (see mx_to_fp4_kernel) a chunk is two blocks, a row of the tile 16
-// blocks = 256 elements of K, and a K step has eight sub-steps: sub-step s takes chunk s,
-// lanes 0-31 its first block, lanes 32-63 its second (stored in swapped order in rows
-// with bit 4 set, which keeps the 8-byte reads free of bank conflicts).  The scale images SA, SB come into
-// LDS beside the tiles (one 16-byte load per row and K step) and each lane keeps the
-// eight scale bytes of its parity of blocks in two registers per fragment row.
+// The same tiling on operands that are already BF16 in memory, row-major ([M x K] and
+// [N x K], K contiguous): the second half of the two-pass form for formats outside Table II,
+// whose operands the general dequantize kernel expands.  Operands come in by direct
+// global-to-LDS loads: a wave fills eight tile rows (1 KiB) per instruction, lane p
+// supplying the 16 bytes that belong at byte 16 p of that block, i.e. chunk (p & 7) ^
+// swizzle of row p / 8.  No staging registers and no LDS write instructions; two LDS
+// stages, the loads of step kt+2 issued right after the barrier that ends step kt, and the
+// fragment reads of sub-step s+1 before the MFMAs of sub-step s.  (Table II's formats use
+// the ring kernel further down, which keeps more loads in flight.)
 constexpr int kFmtBf16 = 0, kFmtFp6 = 1, kFmtFp4 = 2;
 
 template <class F, int... I>
@@ -497,22 +493,18 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-template <int WM, int WN, int TM, int TN, int FMT, int FILL_SLOTS = (FMT == kFmtFp4 ? 5 : 2)>
+template <int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
-    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, const uint8_t *__restrict__ SA,
-    const uint8_t *__restrict__ SB, int M, int N, int pitch, float *__restrict__ C, int64_t ldc)
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int N, int K,
+    float *__restrict__ C, int64_t ldc)
 {
-    constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4;
-    const int K = pitch;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int NW = WM * WN;
-    constexpr int A_BYTES = BM * kPitch, B_BYTES = BN * kPitch;
+    constexpr int A_BYTES = BM * kPitch, B_BYTES = BN * kPitch, kBuf = A_BYTES + B_BYTES;
     constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // 8-row blocks per wave and K step
-    constexpr int NSUB = FP4 ? 8 : 4;                  // sub-steps (fragment reads) per K step
+    constexpr int NSUB = kBK / 16;                     // sub-steps (fragment reads) per K step
     static_assert(LA >= 1 && LB >= 1 && BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && TM % 2 == 0, "tile");
-    // the scale tiles of a K step are (BM + BN) / 64 pieces of 1 KiB, one per wave
-    static_assert(!FP4 || (BM == 32 * NW && BN == 32 * NW), "one scale piece per wave");
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B], FP4: + [2][SA | SB]
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];  // [2][A | B]
 
     const int ntm = (M + BM - 1) / BM, ntn = (N + BN - 1) / BN, total = ntm * ntn;
     int t = blockIdx.x;
@@ -534,11 +526,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
     const int wm = wave / WN, wn = wave % WN;
     const int nk = K / kBK;
 
-    // Vector-ALU instructions between the MFMAs of the steady-state loop cost matrix-pipe time,
-    // so the loop is kept nearly free of them: global addresses are a scalar base that advances
-    // per K step plus a fixed 32-bit lane offset; LDS read addresses are computed once per
-    // sub-step (all fragments of a lane share the swizzle, rows 32 apart, so fragment i is an
-    // immediate offset) and flipped between the two buffers with one XOR per K step.
+    // Vector-ALU instructions between the MFMAs of the steady-state loop cost matrix-pipe
+    // issue slots, so the loop is kept nearly free of them: global addresses are a scalar base
+    // that advances per K step plus a fixed 32-bit lane offset; LDS read addresses are computed
+    // once per sub-step (all fragments of a lane share the swizzle, rows 32 apart, so fragment
+    // i is an immediate offset) and moved between the two buffers with one add per K step.
     const uint8_t *a_base = reinterpret_cast<const uint8_t *>(A + (int64_t)m0 * K);
     const uint8_t *b_base = reinterpret_cast<const uint8_t *>(B + (int64_t)n0 * K);
     uint32_t a_off[LA], b_off[LB];
@@ -553,16 +545,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
         const int row = (wave * LB + i) * 8 + (lane >> 3);
         b_off[i] = (uint32_t)(min(row, N - 1 - n0) * K + 8 * ((lane & 7) ^ ((row >> 1) & 7))) * 2u;
     }
-    // FP4: this wave's piece of the scale tiles, 64 rows of one operand; lane p brings row p's
-    // 16 bytes.  The image is padded to whole 128-row groups, so no row needs clamping.
-    const uint8_t *s_base = nullptr;
-    int s_piece = 0;
-    if constexpr (FP4) {
-        const bool is_b = wave >= NW / 2;
-        const int piece = wave % (NW / 2), row0 = (is_b ? n0 : m0) + piece * 64;
-        s_base = (is_b ? SB : SA) + (((int64_t)(row0 >> 7) * nk) * 128 + (row0 & 127)) * 16;
-        s_piece = (is_b ? BM * 16 : 0) + piece * 1024;
-    }
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -572,202 +554,135 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // One K step of both operands is kLoads direct loads per wave.  They are issued in kSlots
-    // groups, one group per sub-step, so that the memory pipeline takes them in a trickle and
-    // no wave sits in a queue of loads while the matrix pipe runs dry; the last group leaves
-    // the rest of the K step for its data to arrive.
-    constexpr int kLoads = LA + LB + (FP4 ? 1 : 0);
-    constexpr int kSlots = FILL_SLOTS, kPerSlot = (kLoads + kSlots - 1) / kSlots;
-    static_assert(kSlots >= 1 && kSlots <= NSUB - 1, "fill slots are sub-steps before the last");
-    auto fill_slot = [&](auto SLOT, uint8_t *dst, uint8_t *sdst) {
-        constexpr int slot = decltype(SLOT)::value;
+    auto fill = [&](uint8_t *dst) {  // one K step of both operands, then advance
 #pragma unroll
-        for (int q = slot * kPerSlot; q < (slot + 1) * kPerSlot && q < kLoads; ++q) {
-            if (q < LA)
-                global_to_lds16(a_base + a_off[q], dst + (wave * LA + q) * 8 * kPitch);
-            else if (q < LA + LB)
-                global_to_lds16(b_base + b_off[q - LA], dst + A_BYTES + (wave * LB + (q - LA)) * 8 * kPitch);
-            else if constexpr (FP4)
-                global_to_lds16(s_base + lane * 16, sdst + s_piece);
-        }
-        if constexpr ((slot + 1) * kPerSlot >= kLoads && slot * kPerSlot < kLoads) {  // the last group: advance
-            a_base += kBK * 2;
-            b_base += kBK * 2;
-            if constexpr (FP4) s_base += 128 * 16;
-        }
-    };
-    auto fill = [&](uint8_t *dst, uint8_t *sdst) {
-        static_for<kSlots>([&](auto SLOT) { fill_slot(SLOT, dst, sdst); });
+        for (int i = 0; i < LA; ++i) global_to_lds16(a_base + a_off[i], dst + (wave * LA + i) * 8 * kPitch);
+#pragma unroll
+        for (int i = 0; i < LB; ++i)
+            global_to_lds16(b_base + b_off[i], dst + A_BYTES + (wave * LB + i) * 8 * kPitch);
+        a_base += kBK * 2;
+        b_base += kBK * 2;
     };
     const int f_row = lane & 31, f_half = lane >> 5;
-    // A fragment is the 16 bytes of one chunk (FP4: the 8 bytes of one block).  The FP6 MFMA
-    // takes six registers per operand (FP4: four), of which the upper two hold elements 22-31
-    // (16-31) of the lane; those must contribute nothing.  FP6 and FP4 have no infinities or
-    // NaNs, so it is enough that ONE factor of each such product is zero: B fragments keep
-    // zeros there for the whole kernel (the fragment variables are eight wide and a read
-    // replaces only their lower part), A fragments leave those registers undefined.
-    using Frag = typename std::conditional<FMT != kFmtBf16, i32x8, u32x4>::type;
-    auto read_frag = [&](uint32_t at, Frag &f, auto keep_zeros) {  // `at`: an LDS byte address
-        constexpr bool Z = decltype(keep_zeros)::value;
-        if constexpr (FP6) {
-            const i32x4 v = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
-            if constexpr (Z) {
-                const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 2, 3, 0, 1, 2, 3);
-                f = __builtin_shufflevector(wide, f, 0, 1, 2, 3, 12, 13, 14, 15);
-            } else {
-                f = __builtin_shufflevector(v, v, 0, 1, 2, 3, -1, -1, -1, -1);
-            }
-        } else if constexpr (FP4) {
-            // volatile: two 8-byte reads fused into one instruction land in one register
-            // tuple and would have to be copied apart again
-            const i32x2 v = *reinterpret_cast<const volatile lds_i32x2 *>((uintptr_t)at);
-            if constexpr (Z) {
-                const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 0, 1, 0, 1, 0, 1);
-                f = __builtin_shufflevector(wide, f, 0, 1, 10, 11, 12, 13, 14, 15);
-            } else {
-                f = __builtin_shufflevector(v, v, 0, 1, -1, -1, -1, -1, -1, -1);
-            }
-        } else {
-            const i32x4 v = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
-            f = __builtin_bit_cast(u32x4, v);
-        }
-    };
     // LDS byte addresses of this lane's fragment 0 of each sub-step, in the buffer that
     // sub-step is read from next.  A read moves its address to the other buffer: +flip for
     // the sub-steps read from cur, -flip for sub-step 0 (read ahead from nxt), and flip
     // changes sign every K step.
-    constexpr int kBuf = A_BYTES + B_BYTES, kSBuf = (BM + BN) * 16;
     const uint32_t smem_at = (uint32_t)(uintptr_t)(lds_u8 *)smem;
     uint32_t ra[NSUB], rb[NSUB];
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
-        const int chunk = FP4 ? sub : 2 * sub + f_half, byte = FP4 ? 8 * (f_half ^ (f_row >> 4)) : 0;
-        const uint32_t pos = smem_at + (uint32_t)(((chunk ^ ((f_row >> 1) & 7)) << 4) + byte);
+        const uint32_t pos = smem_at + (uint32_t)(((2 * sub + f_half) ^ ((f_row >> 1) & 7)) << 4);
         ra[sub] = (uint32_t)((wm * TM * 32 + f_row) * kPitch) + pos;
         rb[sub] = (uint32_t)(A_BYTES + (wn * TN * 32 + f_row) * kPitch) + pos;
     }
-    int flip = -kBuf, sflip = -kSBuf;  // the first reads (buffer 0) move on to buffer 1
+    int flip = -kBuf;  // the first reads (buffer 0) move on to buffer 1
+    using Frag = i32x4;
     auto read_frags = [&](auto S, Frag (&fa)[TM], Frag (&fb)[TN]) {
         constexpr int sub = decltype(S)::value;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) read_frag(ra[sub] + i * 32 * kPitch, fa[i], std::false_type{});
+        for (int i = 0; i < TM; ++i)
+            fa[i] = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)(ra[sub] + i * 32 * kPitch));
 #pragma unroll
-        for (int j = 0; j < TN; ++j) read_frag(rb[sub] + j * 32 * kPitch, fb[j], std::true_type{});
+        for (int j = 0; j < TN; ++j)
+            fb[j] = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)(rb[sub] + j * 32 * kPitch));
         ra[sub] += sub == 0 ? -flip : flip;
         rb[sub] += sub == 0 ? -flip : flip;
     };
-    // FP4: the scale bytes of this lane's rows for one K step, sub-step s in byte s
-    u32x2 sa[TM], sb[TN], sa_next[TM], sb_next[TN];
-    uint32_t sra = smem_at + 2 * kBuf + (uint32_t)((wm * TM * 32 + f_row) * 16 + 8 * f_half);
-    uint32_t srb = smem_at + 2 * kBuf + (uint32_t)(BM * 16 + (wn * TN * 32 + f_row) * 16 + 8 * f_half);
-    auto read_scales = [&](u32x2 (&xa)[TM], u32x2 (&xb)[TN]) {  // always read ahead, like sub-step 0
-#pragma unroll
-        for (int i = 0; i < TM; ++i) xa[i] = *reinterpret_cast<const lds_u32x2 *>((uintptr_t)(sra + i * 32 * 16));
-#pragma unroll
-        for (int j = 0; j < TN; ++j) xb[j] = *reinterpret_cast<const lds_u32x2 *>((uintptr_t)(srb + j * 32 * 16));
-        sra -= sflip;
-        srb -= sflip;
-    };
-    // half of the tiles of sub-step S
-    auto mfmas = [&](auto S, const Frag (&fa)[TM], const Frag (&fb)[TN], int half) {
-        constexpr int sub = decltype(S)::value;
+    auto mfmas = [&](const Frag (&fa)[TM], const Frag (&fb)[TN], int half) {  // half of the tiles
 #pragma unroll
         for (int i = half * (TM / 2); i < (half + 1) * (TM / 2); ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                if constexpr (FP6) {
-                    // lane l: row l % 32, K values 32 (l / 32) .. +31 of the 64, of which the
-                    // upper 16 are zero; one scale byte per lane, taken from the chunk itself
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        fa[i], fb[j], acc[i][j], kFp6, kFp6, kScaleByteA, fa[i][3], kScaleByteB, fb[j][3]);
-                } else if constexpr (FP4) {
-                    // the same split of K, the scale from byte sub of the lane's scale registers
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        fa[i], fb[j], acc[i][j], kFp4, kFp4, sub & 3, (int)sa[i][sub >> 2], sub & 3,
-                        (int)sb[j][sub >> 2]);
-                } else {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-                }
-            }
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
     };
-    // Schedule of one K step (cur holds step kt, fragment set 0 holds its sub-step 0, nxt is
-    // free: every wave has passed the barrier that ended step kt-1):
-    //   sub-step s < last: half of the MFMAs, then the reads of sub-step s+1 and one group
-    //   of the loads of step kt+1 into nxt, then the other half of the MFMAs;
-    //   then wait for everything this wave has in flight and meet the other waves: from
-    //   here on nxt is complete and nobody reads cur any more (the fragments of the last
-    //   sub-step are in registers), so the reads of sub-step 0 of step kt+1 are issued and
-    //   run under the MFMAs of the last sub-step.
-    // The barrier thus costs neither a fragment-read latency nor a load latency: reads have
-    // eight MFMAs to arrive, loads the rest of the K step.
+    // Schedule of one K step (cur holds step kt, nxt is being filled with step kt+1,
+    // fragment set 0 holds sub-step 0 of step kt):
+    //   reads of sub-step s+1 are issued before the MFMAs of sub-step s, up to the last;
+    //   then wait for everything this wave has in flight and meet the other waves:
+    //   from here on nxt is complete and nobody reads cur any more (the fragments of
+    //   the last sub-step are in registers), so the fill of step kt+2 into cur and the reads
+    //   of sub-step 0 of step kt+1 are issued and run under the MFMAs of the last sub-step.
     static_assert(NSUB % 2 == 0, "the last sub-step must leave fragment set 0 free");
     uint8_t *cur = smem, *nxt = smem + kBuf;
-    uint8_t *cur_s = smem + 2 * kBuf, *nxt_s = cur_s + kSBuf;
     Frag fa[2][TM], fb[2][TN];
-    if constexpr (FMT != kFmtBf16) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[h][j] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
-    }
     constexpr std::integral_constant<int, 0> first{};
-    constexpr std::integral_constant<int, NSUB - 1> last{};
-    fill(cur, cur_s);
+    fill(cur);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if (nk > 1) fill(nxt);
     read_frags(first, fa[0], fb[0]);  // from buffer 0; sub-step 0 now points at buffer 1 = nxt
-    if constexpr (FP4) read_scales(sa, sb);
     flip = -flip;
-    sflip = -sflip;
-    // One K step; `more` says whether another step follows (loads and read-ahead for it).
-    auto k_step = [&](auto more) {
-        constexpr bool kMore = decltype(more)::value;
+    // One K step.  The last two steps have nothing left to fill or to read ahead; they are
+    // peeled so that the body of the steady-state loop is one straight block.
+    auto k_step = [&](auto do_fill, auto do_read) {
         static_for<NSUB - 1>([&](auto S) {
             constexpr int s = decltype(S)::value;
-            mfmas(S, fa[s & 1], fb[s & 1], 0);
+            mfmas(fa[s & 1], fb[s & 1], 0);
             __builtin_amdgcn_sched_barrier(0);
             read_frags(std::integral_constant<int, s + 1>{}, fa[(s + 1) & 1], fb[(s + 1) & 1]);
-            if constexpr (kMore && s < kSlots) fill_slot(S, nxt, nxt_s);
             __builtin_amdgcn_sched_barrier(0);
-            mfmas(S, fa[s & 1], fb[s & 1], 1);
+            mfmas(fa[s & 1], fb[s & 1], 1);
             __builtin_amdgcn_sched_barrier(0);
         });
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        mfmas(last, fa[1], fb[1], 0);
+        mfmas(fa[1], fb[1], 0);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kMore) {
-            read_frags(first, fa[0], fb[0]);
-            if constexpr (FP4) read_scales(sa_next, sb_next);
-        }
+        if constexpr (decltype(do_fill)::value) fill(cur);
+        if constexpr (decltype(do_read)::value) read_frags(first, fa[0], fb[0]);
         __builtin_amdgcn_sched_barrier(0);
-        mfmas(last, fa[1], fb[1], 1);
+        mfmas(fa[1], fb[1], 1);
         __builtin_amdgcn_sched_barrier(0);
         flip = -flip;
-        sflip = -sflip;
         uint8_t *t2 = cur;
         cur = nxt;
         nxt = t2;
-        if constexpr (FP4) {
-            t2 = cur_s;
-            cur_s = nxt_s;
-            nxt_s = t2;
-            if constexpr (kMore) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) sa[i] = sa_next[i];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) sb[j] = sb_next[j];
-            }
-        }
     };
-    for (int kt = 0; kt + 1 < nk; ++kt) k_step(std::true_type{});
-    k_step(std::false_type{});
+    for (int kt = 0; kt + 2 < nk; ++kt) k_step(std::true_type{}, std::true_type{});
+    if (nk > 1) k_step(std::false_type{}, std::true_type{});
+    k_step(std::false_type{}, std::false_type{});
     store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
                         m0 + BM <= M && n0 + BN <= N);
 }
 
-// The product on FP6 or FP4 block images with a ring of four LDS stages.
+// Packed Table II planes -> BF16, tiled along K for the ring kernel: [K step of 32
+// elements][row][64 bytes].  A workgroup covers 16 rows x 16 K steps.  Thread (row, step)
+// reads the packed bits of its 32 elements (per row the 16 steps are consecutive memory) and
+// expands them into LDS; then the workgroup writes the 16 KiB out in image order, where each
+// K step's 16 rows are 1 KiB of consecutive memory: every store instruction of a wave
+// covers whole cache lines.
+template <int MB>
+__global__ __launch_bounds__(256) void mx_to_bf16_tiled_kernel(const uint8_t *__restrict__ codes,
+                                                               const uint8_t *__restrict__ sexp,
+                                                               const uint8_t *__restrict__ mexp, int rows,
+                                                               int row_pairs, u32x4 *__restrict__ out)
+{
+    __shared__ u32x4 s_tile[16 * 16 * 4];  // [step][row][4 chunks], chunk c of row r at c ^ ((r >> 2) & 3)
+    const int r_l = threadIdx.x & 15, q_l = threadIdx.x >> 4;
+    const int row0 = blockIdx.x * 16, q0 = blockIdx.y * 16;
+    if (row0 + r_l < rows && q0 + q_l < row_pairs) {
+        Packed<MB> pk;
+        load_packed<MB>(codes, sexp, mexp, 2 * ((int64_t)(row0 + r_l) * row_pairs + q0 + q_l), pk);
+        uint32_t w[16];
+        unpack32<MB>(pk, w);
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            s_tile[(q_l * 16 + r_l) * 4 + (v ^ ((r_l >> 2) & 3))] =
+                u32x4{w[4 * v], w[4 * v + 1], w[4 * v + 2], w[4 * v + 3]};
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int u = it * 256 + threadIdx.x;  // chunk u of the tile in image order
+        const int q = u >> 6, r = (u >> 2) & 15, c = u & 3;
+        if (row0 + r < rows && q0 + q < row_pairs)
+            out[((int64_t)(q0 + q) * rows + row0 + r) * 4 + c] = s_tile[(q * 16 + r) * 4 + (c ^ ((r >> 2) & 3))];
+    }
+}
+
+// The product on K-tiled images (BF16, or FP6 / FP4 blocks) with a ring of four LDS stages.
 //
 // With two stages the loads of step kt+1 are all that is in flight while step kt computes,
 // and every barrier waits until the last of them has landed: the memory pipeline drains
@@ -779,6 +694,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
 //
 // The images are tiled along K to match: [K step][row][64 bytes], so that the 16 rows one
 // wave instruction brings are 1 KiB of consecutive memory (whole cache lines).
+//   BF16: 64 bytes = 32 elements = 2 sub-steps of one 32 x 32 x 16 MFMA (chunk 2 s + l / 32)
 //   FP6: 64 bytes = 4 blocks = 2 sub-steps (lanes 0-31 take block 2 s, lanes 32-63 block 2 s + 1)
 //   FP4: 64 bytes = 8 blocks = 4 sub-steps (chunk s, one 8-byte block per half wave), and a
 //        scale image [K step][row padded to 128][8 bytes]: the step's four even-block scales,
@@ -807,8 +723,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
     const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const uint8_t *__restrict__ SA,
     const uint8_t *__restrict__ SB, int M, int N, int nk, float *__restrict__ C, int64_t ldc)
 {
-    constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4;
-    static_assert(FP6 || FP4, "block-scaled images only");
+    constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4, BF16 = FMT == kFmtBf16;
+    static_assert(FP6 || FP4 || BF16, "format");
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int NW = WM * WN;
     constexpr int A_BYTES = BM * kRingRow, B_BYTES = BN * kRingRow, kStage = A_BYTES + B_BYTES;
@@ -899,13 +815,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
     };
 
     const int f_row = lane & 31, f_half = lane >> 5;
-    // Fragments as in gemm_dl_kernel: eight-wide variables of which the MFMA takes the lower
-    // six (FP4: four) registers; B fragments keep zeros above the data for the whole kernel,
-    // A fragments leave those registers undefined (one zero factor per product is enough).
-    using Frag = i32x8;
+    // A fragment is the 16 bytes of one chunk (FP4: the 8 bytes of one block).  The FP6 MFMA
+    // takes six registers per operand (FP4: four), of which the upper two hold elements 22-31
+    // (16-31) of the lane; those must contribute nothing.  FP6 and FP4 have no infinities or
+    // NaNs, so it is enough that ONE factor of each such product is zero: B fragments keep
+    // zeros there for the whole kernel (the fragment variables are eight wide and a read
+    // replaces only their lower part), A fragments leave those registers undefined.
+    using Frag = typename std::conditional<BF16, i32x4, i32x8>::type;
     auto read_frag = [&](uint32_t at, Frag &f, auto keep_zeros) {  // `at`: an LDS byte address
         constexpr bool Z = decltype(keep_zeros)::value;
-        if constexpr (FP6) {
+        if constexpr (BF16) {
+            f = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
+        } else if constexpr (FP6) {
             const i32x4 v = *reinterpret_cast<const lds_i32x4 *>((uintptr_t)at);
             if constexpr (Z) {
                 const i32x8 wide = __builtin_shufflevector(v, v, 0, 1, 2, 3, 0, 1, 2, 3);
@@ -960,7 +881,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
         for (int i = half * (TM / 2); i < (half + 1) * (TM / 2); ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                if constexpr (FP6) {
+                if constexpr (BF16) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, fa[i]), __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
+                } else if constexpr (FP6) {
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                         fa[i], fb[j], acc[i][j], kFp6, kFp6, kScaleByteA, fa[i][3], kScaleByteB, fb[j][3]);
                 } else {
@@ -971,10 +895,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
     };
 
     Frag fa[2][TM], fb[2][TN];
+    if constexpr (!BF16) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[h][j] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+            for (int j = 0; j < TN; ++j) fb[h][j] = i32x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
     constexpr std::integral_constant<int, 0> first{};
     constexpr std::integral_constant<int, NSUB - 1> last{};
     static_assert(NSUB % 2 == 0, "the last sub-step must leave fragment set 0 free");
@@ -1101,32 +1027,18 @@ int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, cons
     return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
 }
 
-template <int WM, int WN, int TM, int TN, int FMT>
-int launch_dl(const uint16_t *A, const uint16_t *B, const uint8_t *SA, const uint8_t *SB, int M, int N,
-              int pitch, float *C, int64_t ldc, hipStream_t s)
+template <int WM, int WN, int TM, int TN>
+int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *C, int64_t ldc, hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    constexpr size_t kLds = 2 * (BM + BN) * (size_t)(kPitch + (FMT == kFmtFp4 ? 16 : 0));
+    constexpr size_t kLds = 2 * (BM + BN) * (size_t)kPitch;
     static signed char granted[kMaxDevices];
     if (kLds > 64 * 1024 &&
-        !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN, FMT>), kLds, granted))
+        !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN>), kLds, granted))
         return BDR_ERR_LAUNCH;
-    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN, FMT>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
-                       dim3(64 * WM * WN), kLds, s, A, B, SA, SB, M, N, pitch, C, ldc);
+    hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
+                       dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc);
     return launch_status();
-}
-
-template <int FMT>
-int gemm_dl(const void *A, const void *B, const void *SA, const void *SB, int64_t M, int64_t N, int pitch,
-            float *C, int64_t ldc, hipStream_t s)
-{
-    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
-    const uint8_t *sa = (const uint8_t *)SA, *sb = (const uint8_t *)SB;
-    if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_dl<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, pitch, C, ldc, s);
-        if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
-    }
-    return launch_dl<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, pitch, C, ldc, s);
 }
 
 // K = 0: one workgroup per row of C (rows on grid.x, which takes up to 2^31 - 1 workgroups;
@@ -1155,11 +1067,39 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
     return pick_b<2>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
 }
 
-// C = A * B^T for BF16 A [M x K] and B [N x K] (K > 0, shapes already validated).
+// C = A * B^T for row-major BF16 A [M x K] and B [N x K] (K > 0, shapes already validated).
 int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
               hipStream_t s)
 {
-    return gemm_dl<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)K, C, ldc, s);
+    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+    if (M % 256 == 0 && N % 256 == 0) {
+        const int st = launch_dl<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
+        if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
+    }
+    return launch_dl<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
+}
+
+// C = A * B^T for K-tiled BF16 images (to_bf16_tiled) of A [M x K] and B [N x K]; K % 32 == 0.
+int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+                    hipStream_t s)
+{
+    return gemm_ring<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)(K / 32), C, ldc, s);
+}
+
+// Packed Table II planes of a [rows x K] operand (K % 32 == 0) -> BF16, tiled along K.
+int to_bf16_tiled(const bdr_format &f, const void *codes, const void *sexp, const void *mexp, int64_t rows,
+                  int64_t K, void *out, hipStream_t s)
+{
+    if (rows == 0 || K == 0) return BDR_OK;
+    const uint8_t *c = (const uint8_t *)codes, *e = (const uint8_t *)sexp, *m = (const uint8_t *)mexp;
+    const int rp = (int)(K / 32);
+    // rows on grid.x (up to 2^31 - 1 workgroups), K steps on grid.y (K <= 2^20: at most 2048)
+    const dim3 grid((unsigned)((rows + 15) / 16), (unsigned)((rp + 15) / 16)), block(256);
+    u32x4 *o = (u32x4 *)out;
+    if (f.m == 7) hipLaunchKernelGGL((mx_to_bf16_tiled_kernel<7>), grid, block, 0, s, c, e, m, (int)rows, rp, o);
+    else if (f.m == 4) hipLaunchKernelGGL((mx_to_bf16_tiled_kernel<4>), grid, block, 0, s, c, e, m, (int)rows, rp, o);
+    else hipLaunchKernelGGL((mx_to_bf16_tiled_kernel<2>), grid, block, 0, s, c, e, m, (int)rows, rp, o);
+    return launch_status();
 }
 
 // C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 64 == 0.

@@ -1,9 +1,10 @@
 """GPU parity: mx_gemm against the fp64 oracle.  Tolerance: |C - C_ref| <= 1e-4 * sum_k |a b|
 (norm-relative, because entries of C can be near zero).  Both forms of the call are checked
 against the oracle: the single kernel (no workspace, BF16 in LDS) and the two-pass form
-(operands rewritten once in a caller-supplied workspace, as BF16, or as block-scaled FP6 when
-both formats have m <= 4).  The BF16 forms walk K in the same order and must
-agree bit for bit; the FP6 form rounds the sum at other points and is held to the tolerance."""
+(operands rewritten once in a caller-supplied workspace, as BF16, as block-scaled FP6 when
+both formats have m <= 4, or as block-scaled FP4 for MX4 x MX4).  The BF16 forms walk K in the
+same order and must agree bit for bit; the FP6 and FP4 forms round the sum at other points and
+are held to the tolerance."""
 import numpy as np
 import pytest
 import torch
@@ -129,12 +130,14 @@ def test_two_pass_fp6_form_reproduces_every_element(name, side):
 
 
 @pytest.mark.parametrize("shape", [(128, 128, 256), (256, 256, 1024), (384, 130, 320), (200, 517, 832),
-                                   (512, 256, 2048), (129, 128, 256), (127, 256, 512), (256, 256, 192)])
+                                   (512, 256, 2048), (129, 128, 256), (127, 256, 512), (256, 256, 192),
+                                   (256, 128, 128), (128, 384, 384), (256, 256, 640)])
 def test_mx4_pair_fp4_form_shapes(shape):
-    # MX4 x MX4 with M, N >= 128 and K >= 256 runs on 4-bit images with a scale image beside
-    # them: several K steps, K padded up to a whole step (320, 832), both tile shapes, edge
-    # tiles whose rows run past M or N, and the shapes just outside the condition (127 rows,
-    # K = 192), which take the FP6 form.  Block exponents vary so that the scale bytes matter.
+    # MX4 x MX4 with M, N >= 128 and K >= 128 runs on 4-bit images with a scale image beside
+    # them: one to sixteen K steps of 128 (fewer and more than the ring's four stages), K padded
+    # up to a whole step (320, 832, 192), both tile shapes, edge tiles whose rows run past M or
+    # N, and a shape just outside the condition (127 rows), which takes the FP6 form.  Block
+    # exponents vary so that the scale bytes matter.
     M, N, K = shape
     A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=M + 7 * N + K)
     g = torch.Generator(device="cuda").manual_seed(K)
