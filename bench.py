@@ -108,7 +108,7 @@ def main():
                          "(8192 x 12288, MX9), the gather kernel and general-format kernels, three "
                          "times, and exit (for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--other-probe", action="store_true",
-                    help="run mx_gemm (both forms, 8192^3, MX6 and MX9), the 64-format sweep and the "
+                    help="run mx_gemm (both forms, 8192^3, MX6, MX9 and MX4), the 64-format sweep and the "
                          "dot-product pipeline model a few times and exit (for rocprofv3 --kernel-trace "
                          "and --pmc MfmaUtil VALUBusy)")
     args = ap.parse_args()
@@ -166,6 +166,9 @@ def main():
         pa, pb = B.bdr_quantize(B.MX9, A), B.bdr_quantize(B.MX9, Bm)
         for i in range(10):  # MX9: the BF16 product kernel
             B.mx_gemm(B.MX9, B.MX9, pa, pb, M, N, K, out=C, workspace=ws)
+        pa, pb = B.bdr_quantize(B.MX4, A), B.bdr_quantize(B.MX4, Bm)
+        for i in range(10):  # MX4 x MX4: the FP4 product kernel
+            B.mx_gemm(B.MX4, B.MX4, pa, pb, M, N, K, out=C, workspace=ws)
         xs = S.sweep(device="cuda")
         fmts = [B.fmt(k1, k1 if k2 == 0 else k2, d2, m) for k1 in (8, 16, 32, 64)
                 for k2 in (1, 2, 4, 0) for d2 in (0, 1) for m in (2, 4)]
@@ -179,7 +182,8 @@ def main():
             B.mx_dot_pipeline(B.MX6, B.MX6, pa, pb, M, N, K, r=64, out=C, workspace=ws)
         torch.cuda.synchronize()
         print(json.dumps({"other_probe": "45 x two-pass MX6 mx_gemm, 5 x single-kernel MX6 mx_gemm, "
-                                         "10 x two-pass MX9 mx_gemm, 5 x 64-format sweep, 5 + 5 x MX6 "
+                                         "10 x two-pass MX9 mx_gemm, 10 x two-pass MX4 mx_gemm, "
+                                         "5 x 64-format sweep, 5 + 5 x MX6 "
                                          "mx_dot_pipeline (one pass, r = 64), all at 8192^3"}))
         return
 
@@ -497,7 +501,7 @@ def other_legs(B, S, torch, timed):
         # k1 = 16 against a hardware scale group of 32: half of each instruction multiplies zeros
         leg["two_pass"]["frac_of_usable_half_of_fp6_peak"] = round(leg["two_pass"]["TFLOPs"] / 5050.0, 4)
         leg["single_kernel"]["matrix_instruction"] = "bf16"
-        leg["two_pass"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("gemm_dl_kernel<2,4,4,2,FP6>")
+        leg["two_pass"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("gemm_ring_kernel<2,4,4,2,FP6>")
         leg["single_kernel"]["mfma_util_pct_rocprofv3"] = profiled_mfma_util("mx_gemm_kernel<4,4,2,4,4,2>")
         # fidelity of C against the product of the unquantized operands (library FP32 GEMM)
         B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, out=C, workspace=ws)
@@ -514,9 +518,22 @@ def other_legs(B, S, torch, timed):
         out["mx_gemm_8192_MX9"] = {"two_pass": {"ms": round(t, 3), "TFLOPs": round(tf, 1),
                                                 "frac_of_bf16_mfma_peak_2500": round(tf / 2500.0, 4),
                                                 "matrix_instruction": "bf16",
-                                                "mfma_util_pct_rocprofv3": profiled_mfma_util("gemm_dl_kernel<2,4,4,2,BF16>")},
+                                                "mfma_util_pct_rocprofv3": profiled_mfma_util("gemm_ring_kernel<2,4,4,2,BF16>")},
                                    "qsnr_db_vs_fp32_gemm": round(q9, 3)}
-        del p9a, p9b, Cfp
+        del p9a, p9b
+        # MX4 x MX4: the two-pass form uses block-scaled FP4 images (half the operand bytes)
+        p4a, p4b = B.bdr_quantize(B.MX4, A), B.bdr_quantize(B.MX4, Bm)
+        t = timed(lambda: B.mx_gemm(B.MX4, B.MX4, p4a, p4b, M, N, K, out=C, workspace=ws),
+                  reps=5, inner=4, warm=40)
+        tf = 2.0 * M * N * K / (t * 1e-3) / 1e12
+        q4 = (10 * torch.log10(Cfp.double().square().sum() / (C.double() - Cfp.double()).square().sum())).item()
+        out["mx_gemm_8192_MX4"] = {"two_pass": {"ms": round(t, 3), "TFLOPs": round(tf, 1),
+                                                "frac_of_fp4_mfma_peak_10100": round(tf / 10100.0, 4),
+                                                "frac_of_usable_half_of_fp4_peak": round(tf / 5050.0, 4),
+                                                "matrix_instruction": "fp4 block-scaled, 16 of 32 K positions used",
+                                                "mfma_util_pct_rocprofv3": profiled_mfma_util("gemm_ring_kernel<2,4,4,2,FP4>")},
+                                   "qsnr_db_vs_fp32_gemm": round(q4, 3)}
+        del p4a, p4b, Cfp
     except B.BdrError as e:
         out["mx_gemm_8192_MX6"] = {"error": str(e)}
     try:
