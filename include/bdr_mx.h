@@ -172,8 +172,8 @@ int bdr_qsnr_sweep_static(const bdr_format *fmts, int32_t n_fmts, const void *x,
 size_t bdr_qsnr_sweep_static_scratch_bytes(void);
 
 /* Host only.  Bytes of device workspace with which mx_gemm runs in its two-pass
- * form: (M + N) * K BF16 values, each operand rounded up to 256 bytes (the FP6 block
- * images need half of that).  0 when a size is negative or above 2^20. */
+ * form: (M + N) * K BF16 values, each operand rounded up to 256 bytes (the FP6 and FP4
+ * block images need less).  0 when a size is negative or above 2^20. */
 size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /* C = Ahat * Bhat^T in FP32, where Ahat [M x K] and Bhat [N x K] are the values of
@@ -183,7 +183,9 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  * significant bits hold any MX element), or, in the two-pass form when both formats
  * have m <= 4, FP6 elements under one power-of-two scale
  * per block of 16 (M 2^-tau has at most 4 significant bits over 5 binades, which
- * sign + 2 exponent + 3 fraction bits hold), at twice the BF16 rate.
+ * sign + 2 exponent + 3 fraction bits hold), at twice the BF16 rate; when both have
+ * m = 2 and M, N, K are at least 128, FP4 elements (M 2^-tau is one of 0, 0.5, 1, 1.5, 2, 3,
+ * which sign + 2 exponent + 1 fraction bit hold) at the same rate and half the bytes.
  *   fa, fb : formats of A and B; the two may differ.  Table II's family (k1 16, d1 8,
  *            k2 2, d2 1, m 7, 4 or 2) has kernels of its own in every form.  Any other
  *            format whose elements BF16 holds exactly (m + 2^d2 - 1 <= 8: e.g. block
@@ -196,8 +198,8 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *   C      : device, [M x N] floats, pitch ldc >= N elements, fully overwritten
  *   workspace : device, 16-byte aligned, or NULL.  With at least
  *            mx_gemm_workspace_bytes(M, N, K) bytes (less is BDR_ERR_WORKSPACE) each
- *            operand is rewritten once into it (as BF16 or as FP6 blocks) and a plain
- *            GEMM kernel does the products (the faster form: 2.6x at 8192^3 for
+ *            operand is rewritten once into it (as BF16, FP6 blocks or FP4 blocks) and
+ *            a plain GEMM kernel does the products (the faster form: 2.9x at 8192^3 for
  *            MX6); it is scratch, overwritten, and calls that share it must be
  *            ordered on one stream.  With NULL the expansion to BF16 happens inside
  *            the GEMM kernel, once per tile of C, and no memory beyond the arguments
