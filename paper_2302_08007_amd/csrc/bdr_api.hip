@@ -298,42 +298,52 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
         if (workspace_bytes < mx_gemm_workspace_bytes(M, N, K)) return BDR_ERR_WORKSPACE;
         if (!aligned16(workspace)) return BDR_ERR_ALIGN;
         char *wa = static_cast<char *>(workspace), *wb = wa + gemm_ws_half(M, K);
+        // In each form the product kernel's resources are asked for first (a dry call), so that a
+        // refusal comes back before anything is enqueued.
         if (both_mx && fa->m == 2 && fb->m == 2 && M >= 128 && N >= 128 && K >= 128) {
             // MX4 x MX4: both operands as 4-bit E2M1 images, half a byte per element plus one
             // scale byte per block in an image of its own (rows padded to 128, K to 128).  The
             // size conditions keep both inside the operand's half of the workspace.
             const int64_t Kp = (K + 127) / 128 * 128;
             char *sa = wa + (size_t)M * (size_t)(Kp / 2), *sb = wb + (size_t)N * (size_t)(Kp / 2);
+            st = bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, true, s);
+            if (st) return st;
             st = bdr::to_fp4(a_codes, a_sexp, a_mexp, M, K, Kp, wa, sa, s);
             if (st) return st;
             st = bdr::to_fp4(b_codes, b_sexp, b_mexp, N, K, Kp, wb, sb, s);
             if (st) return st;
-            return bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, s);
+            return bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, false, s);
         }
         if (both_mx && fa->m <= 4 && fb->m <= 4) {
             // MX6 and MX4 elements are exact FP6 values under a per-block power of two:
             // block-scaled FP6 MFMAs, twice the rate of BF16.  One byte per element of workspace.
+            st = bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, true, s);
+            if (st) return st;
             st = bdr::to_fp6(*fa, a_codes, a_sexp, a_mexp, M, K, wa, false, s);
             if (st) return st;
             st = bdr::to_fp6(*fb, b_codes, b_sexp, b_mexp, N, K, wb, true, s);
             if (st) return st;
-            return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, s);
+            return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, false, s);
         }
         if (both_mx) {
             // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact),
             // in the K-tiled layout of the ring kernel
+            st = bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, true, s);
+            if (st) return st;
             st = bdr::to_bf16_tiled(*fa, a_codes, a_sexp, a_mexp, M, K, wa, s);
             if (st) return st;
             st = bdr::to_bf16_tiled(*fb, b_codes, b_sexp, b_mexp, N, K, wb, s);
             if (st) return st;
-            return bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, s);
+            return bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, false, s);
         }
         // any other format that passed the check above: general dequantize to row-major BF16
+        st = bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, true, s);
+        if (st) return st;
         st = bdr::dequantize_row(*fa, a_codes, a_sexp, a_mexp, M, K, wa, BDR_BF16, K, s);
         if (st) return st;
         st = bdr::dequantize_row(*fb, b_codes, b_sexp, b_mexp, N, K, wb, BDR_BF16, K, s);
         if (st) return st;
-        return bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, s);
+        return bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, false, s);
     }
     return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc, s);
 }

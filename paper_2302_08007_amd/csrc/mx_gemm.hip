@@ -964,9 +964,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
                         m0 + BM <= M && n0 + BN <= N);
 }
 
+// With `dry` set the launch functions below only ask for what the kernel needs (a workgroup
+// of more than 64 KiB of LDS has to be granted once per device) and launch nothing: the entry
+// point calls them that way before it enqueues the image writers.
 template <int WM, int WN, int TM, int TN, int FMT>
 int launch_ring(const uint8_t *A, const uint8_t *B, const uint8_t *SA, const uint8_t *SB, int M, int N, int nk,
-                float *C, int64_t ldc, hipStream_t s)
+                float *C, int64_t ldc, bool dry, hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t kLds = kRingStages * (BM + BN) * (size_t)(kRingRow + (FMT == kFmtFp4 ? 8 : 0));
@@ -974,6 +977,7 @@ int launch_ring(const uint8_t *A, const uint8_t *B, const uint8_t *SA, const uin
     if (kLds > 64 * 1024 &&
         !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_ring_kernel<WM, WN, TM, TN, FMT>), kLds, granted))
         return BDR_ERR_LAUNCH;
+    if (dry) return BDR_OK;
     hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN, FMT>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
                        dim3(64 * WM * WN), kLds, s, A, B, SA, SB, M, N, nk, C, ldc);
     return launch_status();
@@ -981,14 +985,14 @@ int launch_ring(const uint8_t *A, const uint8_t *B, const uint8_t *SA, const uin
 
 template <int FMT>
 int gemm_ring(const void *A, const void *B, const void *SA, const void *SB, int64_t M, int64_t N, int nk, float *C,
-              int64_t ldc, hipStream_t s)
+              int64_t ldc, bool dry, hipStream_t s)
 {
     const uint8_t *a = (const uint8_t *)A, *b = (const uint8_t *)B, *sa = (const uint8_t *)SA, *sb = (const uint8_t *)SB;
     if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_ring<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, s);
+        const int st = launch_ring<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, dry, s);
         if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
     }
-    return launch_ring<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, s);
+    return launch_ring<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, dry, s);
 }
 
 // Two tile shapes: 256 x 256 with 8 waves (128 KiB of LDS, one workgroup per CU)
@@ -1028,7 +1032,8 @@ int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, cons
 }
 
 template <int WM, int WN, int TM, int TN>
-int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *C, int64_t ldc, hipStream_t s)
+int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *C, int64_t ldc, bool dry,
+              hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t kLds = 2 * (BM + BN) * (size_t)kPitch;
@@ -1036,6 +1041,7 @@ int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *
     if (kLds > 64 * 1024 &&
         !grant_dynamic_lds(reinterpret_cast<const void *>(&gemm_dl_kernel<WM, WN, TM, TN>), kLds, granted))
         return BDR_ERR_LAUNCH;
+    if (dry) return BDR_OK;
     hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
                        dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc);
     return launch_status();
@@ -1069,21 +1075,21 @@ int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const 
 
 // C = A * B^T for row-major BF16 A [M x K] and B [N x K] (K > 0, shapes already validated).
 int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
-              hipStream_t s)
+              bool dry, hipStream_t s)
 {
     const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
     if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_dl<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
+        const int st = launch_dl<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, dry, s);
         if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
     }
-    return launch_dl<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, s);
+    return launch_dl<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, dry, s);
 }
 
 // C = A * B^T for K-tiled BF16 images (to_bf16_tiled) of A [M x K] and B [N x K]; K % 32 == 0.
 int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
-                    hipStream_t s)
+                    bool dry, hipStream_t s)
 {
-    return gemm_ring<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)(K / 32), C, ldc, s);
+    return gemm_ring<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)(K / 32), C, ldc, dry, s);
 }
 
 // Packed Table II planes of a [rows x K] operand (K % 32 == 0) -> BF16, tiled along K.
@@ -1104,9 +1110,9 @@ int to_bf16_tiled(const bdr_format &f, const void *codes, const void *sexp, cons
 
 // C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 64 == 0.
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
-             hipStream_t s)
+             bool dry, hipStream_t s)
 {
-    return gemm_ring<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 64), C, ldc, s);
+    return gemm_ring<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 64), C, ldc, dry, s);
 }
 
 // Packed MX6 or MX4 planes of a [rows x K] operand (K % 64 == 0) -> rows x K / 16 chunks of
@@ -1138,9 +1144,9 @@ size_t fp4_scale_bytes(int64_t rows, int64_t K_out)
 
 // C = A * B^T for FP4 block images (to_fp4) of A [M x K] and B [N x K]; K % 128 == 0.
 int gemm_fp4(const void *A, const void *SA, const void *B, const void *SB, int64_t M, int64_t N, int64_t K,
-             float *C, int64_t ldc, hipStream_t s)
+             float *C, int64_t ldc, bool dry, hipStream_t s)
 {
-    return gemm_ring<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 128), C, ldc, s);
+    return gemm_ring<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 128), C, ldc, dry, s);
 }
 
 // Packed MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 32 chunks of 16

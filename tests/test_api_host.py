@@ -189,6 +189,12 @@ def test_resources_are_asked_for_before_the_first_launch():
     arr = (B.Format * len(small))(*small)
     need = B.lib.bdr_qsnr_sweep_workspace_bytes(len(small))
     assert B.lib.bdr_qsnr_sweep(arr, len(small), FAKE, 0, 4, 64, 64, FAKE, FAKE, FAKE, need, NULL) == ERR_LAUNCH
+    # the two-pass mx_gemm asks for its product kernel's LDS before it enqueues the image writers
+    # (MX4 x MX4 on FP4 images: 72 KiB even with the small tile)
+    f = B.MX4
+    need = B.lib.mx_gemm_workspace_bytes(128, 128, 128)
+    assert B.lib.mx_gemm(ctypes.byref(f), ctypes.byref(f), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 128, 128, 128,
+                         FAKE, 128, FAKE, need, NULL) == ERR_LAUNCH
 
 
 def test_tile_packing_of_the_paper_formats():
