@@ -461,6 +461,31 @@ def other_legs(B, S, torch, timed):
     except B.BdrError as e:
         out["general_formats_fp32_1GiB_rowwise"] = {"error": str(e)}
     try:
+        # the same kind of format blocked down the columns (the tiled general kernel): fp32
+        # 8192 x 8192, two inputs in rotation, quantize and dequantize timed separately
+        xc = [S.gemm_operands(8192, 8, 8192, device="cuda", seed=40 + i)[0] for i in range(2)]
+        r, c = xc[0].shape
+        yc = torch.empty_like(xc[0])
+        leg = {}
+        for label, f, fbits in (("k1_32_k2_2_d2_1_m_4", B.fmt(32, 2, 1, 4), 5 + 8 / 32 + 1 / 2),
+                                ("bfp_k1_16_m_4", B.fmt(16, 16, 0, 4), 5 + 8 / 16)):
+            ab = alg_bytes(r * c, fbits, 4)
+            pl = B.alloc_planes(f, r, c, B.AXIS_COL)
+            k = [0]
+
+            def runq():
+                B.bdr_quantize(f, xc[k[0] % 2], axis=B.AXIS_COL, out=pl)
+                k[0] += 1
+            tq = timed(runq, reps=7, inner=3)
+            td = timed(lambda: B.bdr_dequantize(f, pl, r, c, axis=B.AXIS_COL, out=yc), reps=7, inner=3)
+            leg[label] = {"quantize_us": round(tq * 1e3, 1), "quantize_frac": round(ab / tq / 1e6 / HBM_PEAK_GBS, 4),
+                          "dequantize_us": round(td * 1e3, 1), "dequantize_frac": round(ab / td / 1e6 / HBM_PEAK_GBS, 4)}
+            del pl
+        out["general_formats_fp32_8192x8192_colwise"] = leg
+        del xc, yc
+    except B.BdrError as e:
+        out["general_formats_fp32_8192x8192_colwise"] = {"error": str(e)}
+    try:
         # three buffers in rotation so the 192 MiB input is not served from the 256 MB cache
         xa = [S.activation(device="cuda", seed=3 + i) for i in range(3)]
         r, c = xa[0].shape

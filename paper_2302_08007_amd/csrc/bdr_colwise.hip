@@ -1,5 +1,6 @@
 // Column-wise (blocks down the columns) quantize, dequantize and fused round
-// trip for the Table II formats, staged through LDS.
+// trip, staged through LDS: kernels for the Table II formats, and further down one
+// kernel that takes any format tuple at run time.
 //
 // MX is a directional format: a tensor must be quantized along the reduction
 // axis, and quantizing does not commute with transposing (Sec. V, "Training").
@@ -287,6 +288,185 @@ int col_dispatch(int mode, const bdr_format &f, const T *x, T *y, uint8_t *codes
     return launch_status();
 }
 
+// ---- any format tuple with 8 <= k1 <= 128 on the same tiles
+//
+// The same staging (row-contiguous loads of a 128-row tile into LDS, one lane per block of
+// one column), with the tuple at run time: a lane walks its block in LDS three times (block
+// maximum; per sub-block its maximum; per element the code), packs the codes of its block
+// (a whole number of bytes, since k1 is a multiple of 8) into a staging area in LDS, and the
+// workgroup then writes each column's run of the three planes with consecutive lanes.  The
+// microexponent stream of a column gets (128 / k2) d2 bits per tile; where that is not a
+// whole number of bytes the workgroup walks rt = 2, 4 or 8 tiles down the column and writes
+// the stream once at the end.  Dequantize and the fused round trip use the same walk.
+constexpr int kGenCodesMax = 16 * 9 + 4;  // bytes per tile column: 128 codes of up to 9 bits (+ read-ahead)
+constexpr int kGenSexpMax = 16;           // 128 / k1 with k1 >= 8
+constexpr int kGenMexpMax = 48 + 4;       // (128 / k2) d2 / 8 with k2 = 1, d2 = 3 (taller bands have larger k2) + read-ahead
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(kColThreads) void generic_col_tiled_kernel(
+    GenFmt f, int rt, const T *x, T *y, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
+    uint8_t *__restrict__ mexp, int64_t rows, int64_t ld)
+{
+    constexpr int kTC = TileGeom<T>::kTC;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
+    __shared__ uint32_t s_codes[MODE == 2 ? 1 : kTC * kGenCodesMax / 4];
+    __shared__ uint8_t s_sexp[MODE == 2 ? 1 : kTC * kGenSexpMax];
+    __shared__ uint32_t s_mexp[MODE == 2 ? 1 : kTC * kGenMexpMax / 4];
+    uint8_t *const lc = reinterpret_cast<uint8_t *>(s_codes);
+    uint8_t *const lm = reinterpret_cast<uint8_t *>(s_mexp);
+
+    const int cb = f.m + 1, lk1 = __builtin_ctz(f.k1), lk2 = __builtin_ctz(f.k2);
+    const int nb = kTR >> lk1, lnb = __builtin_ctz(nb);  // blocks per tile column
+    const int nsub = f.k1 >> lk2;                        // sub-blocks per block
+    const int beta = (1 << f.d2) - 1;
+    const float top = (float)((1u << f.m) - 1u);
+    const uint32_t cmask = (1u << cb) - 1u, mmask = (1u << f.m) - 1u;
+    const int mbytes = rt * (kTR >> lk2) * f.d2 / 8;     // microexponent bytes per column and band
+    const int64_t band0 = (int64_t)blockIdx.x * rt * kTR, c0 = (int64_t)blockIdx.y * kTC;
+    const int tid = threadIdx.x;
+
+    if (MODE != 2 && f.d2 > 0) {
+        if (MODE == 0) {
+            for (int i = tid; i < kTC * kGenMexpMax / 4; i += kColThreads) s_mexp[i] = 0;
+        } else {
+            for (int i = tid; i < kTC * mbytes; i += kColThreads) {
+                const int c = i / mbytes, b = i - c * mbytes;
+                lm[c * kGenMexpMax + b] = mexp[((((c0 + c) * rows + band0) >> lk2) * f.d2 >> 3) + b];
+            }
+        }
+    }
+    for (int it = 0; it < rt; ++it) {
+        const int64_t r0 = band0 + (int64_t)it * kTR;
+        if (MODE != 1) tile_load(x, ld, r0, c0, tile);
+        if (MODE == 1) {
+            for (int i = tid; i < kTC * 4 * cb; i += kColThreads) {
+                const int c = i / (4 * cb), w = i - c * 4 * cb;
+                s_codes[c * (kGenCodesMax / 4) + w] =
+                    reinterpret_cast<const uint32_t *>(codes + (((c0 + c) * rows + r0) * cb >> 3))[w];
+            }
+            for (int i = tid; i < kTC * nb; i += kColThreads) {
+                const int c = i >> lnb, b = i & (nb - 1);
+                s_sexp[c * kGenSexpMax + b] = sexp[(((c0 + c) * rows + r0) >> lk1) + b];
+            }
+        }
+        __syncthreads();
+        for (int q = tid; q < kTC * nb; q += kColThreads) {
+            const int c = q >> lnb, b = q & (nb - 1), rbase = b << lk1;
+            int mpos = ((it * kTR + rbase) >> lk2) * f.d2;  // bit of this block's first field in the column's stream
+            if (MODE != 1) {
+                uint32_t bm = 0;
+                for (int i = 0; i < f.k1; ++i)
+                    bm = umax(bm, clamp_mag(lds_get(tile, lds_off<T>(rbase + i, c), T()) & kAbsMask));
+                const int se = (int)(bm >> 23);
+                uint64_t acc = 0;
+                int nbits = 0;
+                uint8_t *cp = lc + c * kGenCodesMax + (rbase * cb >> 3);
+                for (int j = 0; j < nsub; ++j) {
+                    const int e0 = rbase + (j << lk2);
+                    uint32_t sm = 0;
+                    for (int e = 0; e < f.k2; ++e)
+                        sm = umax(sm, clamp_mag(lds_get(tile, lds_off<T>(e0 + e, c), T()) & kAbsMask));
+                    int t = se - (int)(sm >> 23);
+                    t = t < beta ? t : beta;
+                    const int sh = (f.m - 1) + 127 - se + t;
+                    if (MODE == 0 && f.d2 > 0) {
+                        uint32_t *mw = s_mexp + c * (kGenMexpMax / 4) + (mpos >> 5);
+                        atomicOr(mw, (uint32_t)t << (mpos & 31));
+                        if ((mpos & 31) + f.d2 > 32) atomicOr(mw + 1, (uint32_t)t >> (32 - (mpos & 31)));
+                        mpos += f.d2;
+                    }
+                    for (int e = 0; e < f.k2; ++e) {
+                        const int off = lds_off<T>(e0 + e, c);
+                        const uint32_t xb = lds_get(tile, off, T());
+                        const float mf = gen_round(__builtin_fabsf(as_f(xb)), sh, top, f.rounding);
+                        if (MODE == 0) {
+                            acc |= (uint64_t)((uint32_t)mf | ((xb >> 31) << f.m)) << nbits;
+                            nbits += cb;
+                            while (nbits >= 8) {
+                                *cp++ = (uint8_t)acc;
+                                acc >>= 8;
+                                nbits -= 8;
+                            }
+                        } else {
+                            lds_put(tile, off, as_u(__builtin_ldexpf(mf, -sh)) | (xb & 0x80000000u), T());
+                        }
+                    }
+                }
+                if (MODE == 0) s_sexp[c * kGenSexpMax + b] = (uint8_t)se;
+            } else {
+                const int se = s_sexp[c * kGenSexpMax + b];
+                const uint8_t *cp = lc + c * kGenCodesMax;
+                const uint8_t *mp = lm + c * kGenMexpMax;
+                for (int j = 0; j < nsub; ++j) {
+                    int tau = 0;
+                    if (f.d2 > 0) {
+                        const int byte = mpos >> 3;  // a field of up to 3 bits spans at most two bytes
+                        tau = (int)((((uint32_t)mp[byte] | ((uint32_t)mp[byte + 1] << 8)) >> (mpos & 7)) & (uint32_t)beta);
+                        mpos += f.d2;
+                    }
+                    const int qe = se - 127 - tau - (f.m - 1);
+                    const int e0 = rbase + (j << lk2);
+                    for (int e = 0; e < f.k2; ++e) {
+                        const int bit = (e0 + e) * cb, byte = bit >> 3;  // up to 9 bits from bit 0 .. 7: two bytes
+                        const uint32_t cd = ((((uint32_t)cp[byte] | ((uint32_t)cp[byte + 1] << 8)) >> (bit & 7))) & cmask;
+                        lds_put(tile, lds_off<T>(e0 + e, c),
+                                as_u(__builtin_ldexpf((float)(cd & mmask), qe)) | ((cd >> f.m) << 31), T());
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (MODE == 0) {
+            for (int i = tid; i < kTC * 4 * cb; i += kColThreads) {
+                const int c = i / (4 * cb), w = i - c * 4 * cb;
+                reinterpret_cast<uint32_t *>(codes + (((c0 + c) * rows + r0) * cb >> 3))[w] =
+                    s_codes[c * (kGenCodesMax / 4) + w];
+            }
+            for (int i = tid; i < kTC * nb; i += kColThreads) {
+                const int c = i >> lnb, b = i & (nb - 1);
+                sexp[(((c0 + c) * rows + r0) >> lk1) + b] = s_sexp[c * kGenSexpMax + b];
+            }
+        } else {
+            tile_store(y, ld, r0, c0, tile);
+        }
+        if (it + 1 < rt) __syncthreads();  // the tile and the staging areas are reused
+    }
+    if (MODE == 0 && f.d2 > 0) {
+        for (int i = tid; i < kTC * mbytes; i += kColThreads) {
+            const int c = i / mbytes, b = i - c * mbytes;
+            mexp[((((c0 + c) * rows + band0) >> lk2) * f.d2 >> 3) + b] = lm[c * kGenMexpMax + b];
+        }
+    }
+}
+
+// Tiles walked per workgroup so that a column's microexponent bits come to whole bytes, or 0
+// when this kernel does not take the case.
+int generic_tiled_rt(const bdr_format &f, int64_t rows, int64_t cols, int tc)
+{
+    if (f.k1 < 8 || f.k1 > kTR || rows % kTR != 0 || cols % tc != 0 || cols / tc > 65535) return 0;
+    for (int rt = 1; rt <= 8; rt *= 2) {
+        if (rows % ((int64_t)rt * kTR) != 0) return 0;
+        const int bits = rt * (kTR / f.k2) * f.d2;
+        if (bits % 8 == 0 && bits / 8 <= kGenMexpMax - 4) return rt;
+    }
+    return 0;
+}
+
+template <typename T>
+int generic_tiled(int mode, const bdr_format &f, int rt, const T *x, T *y, uint8_t *codes, uint8_t *sexp,
+                  uint8_t *mexp, int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
+{
+    const GenFmt g{f.k1, f.k2, f.d2, f.m, f.rounding};
+    const dim3 grid((unsigned)(rows / ((int64_t)rt * kTR)), (unsigned)(cols / TileGeom<T>::kTC)), block(kColThreads);
+    if (mode == 0)
+        hipLaunchKernelGGL((generic_col_tiled_kernel<T, 0>), grid, block, 0, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+    else if (mode == 1)
+        hipLaunchKernelGGL((generic_col_tiled_kernel<T, 1>), grid, block, 0, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+    else
+        hipLaunchKernelGGL((generic_col_tiled_kernel<T, 2>), grid, block, 0, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+    return launch_status();
+}
+
 // The tiled kernels need whole tiles and a grid the hardware accepts.
 bool tiled_ok(int mode, const bdr_format &f, int64_t rows, int64_t cols, int tc)
 {
@@ -297,8 +477,16 @@ bool tiled_ok(int mode, const bdr_format &f, int64_t rows, int64_t cols, int tc)
 int col_any(int mode, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
             int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
 {
-    if (!tiled_ok(mode, f, rows, cols, dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC))
-        return generic_col(mode, f, x, y, dtype, rows, cols, ld, codes, sexp, mexp, s);
+    const int tc = dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC;
+    if (!tiled_ok(mode, f, rows, cols, tc)) {
+        const int rt = generic_tiled_rt(f, rows, cols, tc);
+        if (rt == 0) return generic_col(mode, f, x, y, dtype, rows, cols, ld, codes, sexp, mexp, s);
+        if (dtype == BDR_F32)
+            return generic_tiled(mode, f, rt, (const float *)x, (float *)y, (uint8_t *)codes, (uint8_t *)sexp,
+                                 (uint8_t *)mexp, rows, cols, ld, s);
+        return generic_tiled(mode, f, rt, (const uint16_t *)x, (uint16_t *)y, (uint8_t *)codes, (uint8_t *)sexp,
+                             (uint8_t *)mexp, rows, cols, ld, s);
+    }
     if (dtype == BDR_F32)
         return col_dispatch(mode, f, (const float *)x, (float *)y, (uint8_t *)codes,
                             (uint8_t *)sexp, (uint8_t *)mexp, rows, cols, ld, s);

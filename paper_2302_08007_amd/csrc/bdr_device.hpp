@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "bdr_mx.h"
+
 namespace bdr {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -310,6 +312,21 @@ __device__ __forceinline__ void store8(uint16_t *p, const uint32_t (&yb)[8])
     u32x4 a = {(yb[0] >> 16) | (yb[1] & 0xffff0000u), (yb[2] >> 16) | (yb[3] & 0xffff0000u),
                (yb[4] >> 16) | (yb[5] & 0xffff0000u), (yb[6] >> 16) | (yb[7] & 0xffff0000u)};
     __builtin_nontemporal_store(a, reinterpret_cast<u32x4 *>(p));
+}
+
+// A format tuple as the general (run-time-tuple) kernels take it.
+struct GenFmt {
+    int k1, k2, d2, m, rounding;
+};
+
+// |x| * 2^sh rounded to an integer in [0, top] by the format's rule.
+__device__ __forceinline__ float gen_round(float ax, int sh, float top, int rounding)
+{
+    float y = __builtin_fminf(__builtin_ldexpf(ax, sh), top);
+    if (rounding == BDR_RNE) return __builtin_rintf(y);
+    const float t = __builtin_truncf(y);
+    if (rounding == BDR_RNA) return (y - t) >= 0.5f ? t + 1.0f : t;
+    return t;
 }
 
 }  // namespace bdr

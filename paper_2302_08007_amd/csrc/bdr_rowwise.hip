@@ -318,9 +318,6 @@ __device__ __forceinline__ uint32_t load1(const uint16_t *p) { return (uint32_t)
 __device__ __forceinline__ void store1(float *p, uint32_t b) { *p = as_f(b); }
 __device__ __forceinline__ void store1(uint16_t *p, uint32_t b) { *p = (uint16_t)(b >> 16); }
 
-struct GenFmt {
-    int k1, k2, d2, m, rounding;
-};
 
 // Formats the general kernels are also compiled for with the tuple as a compile-time
 // constant (SPEC = index into this table; SPEC < 0 = tuple at run time): the formats of the
@@ -391,16 +388,6 @@ __device__ __forceinline__ void gen_maxima(const GenFmt &f, const uint32_t (&xb)
 #pragma unroll
         for (int i = 0; i < 8; ++i) be[i] = v;
     }
-}
-
-// |x| * 2^sh rounded to an integer in [0, top] by the format's rule.
-__device__ __forceinline__ float gen_round(float ax, int sh, float top, int rounding)
-{
-    float y = __builtin_fminf(__builtin_ldexpf(ax, sh), top);
-    if (rounding == BDR_RNE) return __builtin_rintf(y);
-    const float t = __builtin_truncf(y);
-    if (rounding == BDR_RNA) return (y - t) >= 0.5f ? t + 1.0f : t;
-    return t;
 }
 
 // The lane's 8 codes of CB bits each as CB bytes at cp (LDS), little-endian bit stream.

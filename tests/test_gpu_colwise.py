@@ -56,6 +56,59 @@ def test_other_formats_column_wise(kw):
     _check_col(f, x, repr(f))
 
 
+GEN_TILED = [dict(k1=8, k2=1, d2=1, m=2), dict(k1=8, k2=8, d2=1, m=4), dict(k1=32, k2=4, d2=2, m=3),
+             dict(k1=32, k2=32, d2=1, m=4), dict(k1=64, k2=64, d2=0, m=4), dict(k1=64, k2=64, d2=1, m=2),
+             dict(k1=64, k2=4, d2=1, m=2), dict(k1=128, k2=16, d2=3, m=5), dict(k1=128, k2=128, d2=1, m=4),
+             dict(k1=16, k2=1, d2=3, m=8), dict(k1=16, k2=2, d2=1, m=4, rounding=1),
+             dict(k1=16, k2=2, d2=1, m=7, rounding=2), dict(k1=16, k2=16, d2=0, m=7)]
+
+
+@pytest.mark.parametrize("kw", GEN_TILED, ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+@pytest.mark.parametrize("shape", [(1024, 64), (2048, 192)])
+def test_other_formats_on_whole_tiles(kw, shape):
+    # Formats outside Table II (or rounded another way) on shapes made of whole 128-row tiles take
+    # the tiled general kernel: block sizes 8 to 128, codes of 3 to 9 bits, microexponent streams
+    # of 1 to 384 bits per tile column (those below a byte make a workgroup walk 2, 4 or 8 tiles).
+    f = B.fmt(**kw)
+    x = S.wide_range(*shape, device="cuda", seed=shape[1] + kw["k1"] + kw["m"])
+    _check_col(f, x, repr(f))
+
+
+@pytest.mark.parametrize("kw", [GEN_TILED[0], GEN_TILED[2], GEN_TILED[4], GEN_TILED[6], GEN_TILED[11]],
+                         ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+def test_other_formats_on_whole_tiles_bf16(kw):
+    f = B.fmt(**kw)
+    x = S.wide_range(1024, 256, device="cuda", seed=kw["k1"], dtype=torch.bfloat16)
+    _check_col(f, x, repr(f) + " bf16")
+
+
+def test_other_formats_on_whole_tiles_strided_in_place_and_special_values():
+    f = B.fmt(32, 2, 1, 4)
+    big = S.wide_range(512, 512, device="cuda", seed=33)
+    x = big[:, 64:64 + 128]                        # ld > cols
+    xn = np.ascontiguousarray(to_np(big)[:, 64:64 + 128])
+    want = O.quantize(ofmt(f), xn, axis=O.AXIS_COL)
+    assert_planes_equal(B.bdr_quantize(f, x, axis=B.AXIS_COL), want, "strided")
+    ywant = O.quantize_dequantize(ofmt(f), xn, axis=O.AXIS_COL)
+    z = x.clone()
+    B.bdr_quantize_dequantize(f, z, axis=B.AXIS_COL, out=z)
+    assert_bits_equal(z, ywant, "in place")
+    y = torch.full((512, 512), 7.0, device="cuda")
+    B.bdr_dequantize(f, [torch.from_numpy(p).cuda() for p in want], 512, 128, axis=B.AXIS_COL, out=y[:, 64:64 + 128])
+    assert_bits_equal(y[:, 64:64 + 128].contiguous(), ywant, "strided dequantize")
+    assert torch.all(y[:, :64] == 7.0) and torch.all(y[:, 192:] == 7.0)
+    s = torch.zeros(128, 64, device="cuda")
+    s[3, 0] = -0.0
+    s[:32, 1] = 2.0 ** -140
+    s[5, 1] = -3 * 2.0 ** -149
+    s[:32, 2] = 2.0 ** -126
+    s[0, 3], s[1, 3], s[2, 3] = 3.4e38, -1.7e38, 1e-30
+    s[0, 4], s[1, 4], s[2, 4], s[3, 4] = float("inf"), -float("inf"), float("nan"), 1.0
+    s[:, 6] = 1.9999999
+    for kw in (dict(k1=32, k2=2, d2=1, m=4), dict(k1=8, k2=4, d2=2, m=2), dict(k1=64, k2=1, d2=1, m=6)):
+        _check_col(B.fmt(**kw), s, "special %r" % (kw,))
+
+
 @pytest.mark.parametrize("name", MX)
 def test_column_blocks_equal_row_blocks_of_the_transpose(name):
     f = getattr(B, name)
