@@ -172,3 +172,28 @@ def test_activation_config_full_size_sampled_columns():
     # the outlier columns really are there, and row-wise quantization of the same tensor differs
     pr = B.bdr_quantize(f, x, axis=B.AXIS_ROW)
     assert not torch.equal(pr[1][:4096], planes[1][:4096])
+
+
+@pytest.mark.parametrize("kw", [dict(k1=32, k2=2, d2=1, m=4), dict(k1=64, k2=64, d2=1, m=2)],
+                         ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+def test_other_formats_full_size_sampled_columns(kw):
+    # 8192 x 8192 fp32, the size of the bench leg for formats outside Table II blocked down the
+    # columns (the second format makes a workgroup walk four tiles per microexponent byte): the
+    # oracle checks whole column tiles sampled across the tensor, planes, dequantize and fused
+    f = B.fmt(**kw)
+    x = S.gemm_operands(8192, 8, 8192, device="cuda", seed=40)[0]
+    rows, cols = x.shape
+    planes = B.bdr_quantize(f, x, axis=B.AXIS_COL)
+    y = B.bdr_quantize_dequantize(f, x, axis=B.AXIS_COL)
+    yd = B.bdr_dequantize(f, planes, rows, cols, axis=B.AXIS_COL)
+    torch.cuda.synchronize()
+    assert torch.equal(y, yd)
+    rng = np.random.default_rng(1)
+    per_col = [rows * (f.m + 1) // 8, rows // f.k1, rows // f.k2 * f.d2 // 8]
+    for c0 in sorted(set([0, cols - 64] + [int(v) * 64 for v in rng.integers(0, cols // 64, 3)])):
+        sub = x[:, c0:c0 + 64].contiguous()
+        want = O.quantize(ofmt(f), to_np(sub), axis=O.AXIS_COL)
+        got = [p[c0 * n:(c0 + 64) * n] for p, n in zip(planes, per_col)]
+        assert_planes_equal(got, want, "columns %d.." % c0)
+        ywant = O.dequantize(ofmt(f), *want, rows, 64, axis=O.AXIS_COL, out_dtype=np.float32)
+        assert_bits_equal(y[:, c0:c0 + 64].contiguous(), ywant, "fused columns %d.." % c0)
