@@ -146,6 +146,22 @@ def test_mx4_pair_fp4_form_shapes(shape):
     _check(B.MX4, B.MX4, A.contiguous(), Bm.contiguous(), "fp4 %s" % (shape,))
 
 
+def test_random_shapes_and_format_pairs():
+    # 30 seeded draws of M, N (1 .. 600, so most tiles hang over an edge and both tile shapes
+    # occur), K (1 .. 12 steps of 64, fewer and more than the ring's four stages, odd counts
+    # that pad the FP4 image) and a format pair: both forms against the oracle
+    rng = np.random.default_rng(2302)
+    names = ["MX9", "MX6", "MX4"]
+    for case in range(30):
+        M, N = (int(v) for v in rng.integers(1, 601, 2))
+        if case % 5 == 0:
+            M, N = 256 * int(rng.integers(1, 3)), 256 * int(rng.integers(1, 3))   # whole 256-tiles
+        K = 64 * int(rng.integers(1, 13))
+        na, nb = names[int(rng.integers(0, 3))], names[int(rng.integers(0, 3))]
+        A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=1000 + case)
+        _check(getattr(B, na), getattr(B, nb), A, Bm, "case %d: %s x %s, %d x %d x %d" % (case, na, nb, M, N, K))
+
+
 @pytest.mark.parametrize("name", ["MX9", "MX6", "MX4"])
 @pytest.mark.parametrize("form", ["single kernel", "two-pass"])
 def test_bf16_forms_reproduce_every_element_down_to_the_lowest_exponent(name, form):
