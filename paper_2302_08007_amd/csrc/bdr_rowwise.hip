@@ -135,12 +135,33 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_row_kernel(
     }
 }
 
-// Dequantize, 8 elements per lane and kDeqIter such groups per lane.  All loads of
+// Dequantize, 8 elements per lane and deq_iter() such groups per lane.  All loads of
 // a lane are issued before the first result is needed: a wave cannot write before
 // its codes have arrived, so the bytes it has in flight, not its instruction
 // count, set the rate when reads queue behind the kernel's own write stream.
-constexpr int kDeqIter = 2;
-//
+constexpr int kDeqThreads = 256;  // workgroup size of the dequantize kernel
+// Groups per lane.  Measured in the loop of the three formats at 1 GiB FP32 (workgroup size x
+// groups per lane -> MX9 / MX6 / MX4 in microseconds): 128 x 1: 225 / 233 / 245, 128 x 2: 235 /
+// 219 / 221, 256 x 1: 213 / 220 / 229, 256 x 2: 236 / 213 / 214, 512 x 1: 214 / 225 / 223,
+// 256 x 4: 239 / 234 / 239.  A store stream is fastest from many small workgroups with few
+// stores per lane (a pure-write kernel: 158 us per GiB with one 16-byte store per lane and
+// 4 KiB per workgroup, 183 with two and 8 KiB, 187 with four and 16 KiB), but the 3- and
+// 5-byte code loads of MX4 and MX6 want two groups per lane in flight; MX9 (8-byte loads)
+// does not.  (A variant with four elements and one 16-byte store per lane, which needs no
+// staging at all, took 253 / 243 / 252: too few bytes of codes in flight per wave.  BF16
+// rows, 8192 x 12288: two groups per lane 55 / 43 / 39, one 62 / 44 / 42.)
+template <int MB, typename T>
+constexpr int deq_iter()
+{
+    return MB == 7 && sizeof(T) == 4 ? 1 : 2;
+}
+template <int MB, typename T>
+static inline dim3 deq_grid(int64_t n_groups)
+{
+    constexpr int64_t per = (int64_t)kDeqThreads * deq_iter<MB, T>();
+    return dim3((unsigned)((n_groups + per - 1) / per));
+}
+
 // GATHER: the output is [n_idx x cols] and output row j is row idx[j] of the packed
 // table (a storage format for embedding tables, Sec. V "Inferencing" / recommendation
 // models): a group of the output maps to a group of the table through one index
@@ -160,7 +181,7 @@ struct GatherArgs {
 // bits depends on them: the codes of 8 elements are MB + 1 bytes whatever the block sizes.
 template <int MB, typename T, bool GATHER = false, bool FIXED_SE = false, int LK1 = 4, int LK2 = 1,
           int D2 = 1>
-__global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
+__global__ __launch_bounds__(kDeqThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups, GatherArgs ga)
 {
@@ -168,9 +189,10 @@ __global__ __launch_bounds__(kThreads) void mx_dequantize_row_kernel(
     constexpr uint32_t CMASK = (1u << CB) - 1u;
     constexpr uint32_t MMASK = (1u << MB) - 1u;
     constexpr bool kStage = sizeof(T) == 4;  // FP32 rows leave through LDS, see wave_store512
-    __shared__ float s_stage[kStage ? kThreads / 64 : 1][kStage ? kWaveStage : 1];
-    constexpr int kStep = kThreads;  // distance between a lane's groups
-    const int64_t g0 = (int64_t)blockIdx.x * (kThreads * kDeqIter) + threadIdx.x;
+    __shared__ float s_stage[kStage ? kDeqThreads / 64 : 1][kStage ? kWaveStage : 1];
+    constexpr int kStep = kDeqThreads;  // distance between a lane's groups
+    constexpr int kDeqIter = deq_iter<MB, T>();
+    const int64_t g0 = (int64_t)blockIdx.x * (kDeqThreads * kDeqIter) + threadIdx.x;
     const uint32_t i = threadIdx.x & 3u;
 
     uint32_t v0[kDeqIter], v1[kDeqIter], seb[kDeqIter], tbb[kDeqIter];
@@ -739,16 +761,16 @@ static void launch_hot(int spec, dim3 grid, hipStream_t s, const float *x, uint8
 // (FP32, pitch = row length, whole quads of lanes).  Reading an image does not depend on the
 // rounding rule, so the table's nearest-even entries serve every rounding.
 template <int SP = 0>
-static void launch_hot_dequantize(int spec, dim3 grid, hipStream_t s, const uint8_t *codes,
+static void launch_hot_dequantize(int spec, hipStream_t s, const uint8_t *codes,
                                   const uint8_t *sexp, const uint8_t *mexp, float *y, int64_t ng)
 {
     if constexpr (SP < kHotCount) {
-        if (spec != SP) return launch_hot_dequantize<SP + 1>(spec, grid, s, codes, sexp, mexp, y, ng);
+        if (spec != SP) return launch_hot_dequantize<SP + 1>(spec, s, codes, sexp, mexp, y, ng);
         constexpr GenFmt f = hot_format(SP);
         constexpr int lk1 = f.k1 == 8 ? 3 : f.k1 == 16 ? 4 : f.k1 == 32 ? 5 : 6;
         constexpr int lk2 = f.k2 == 1 ? 0 : f.k2 == 2 ? 1 : f.k2 == 4 ? 2 : lk1;
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<f.m, float, false, false, lk1, lk2, f.d2>), grid,
-                           dim3(kThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<f.m, float, false, false, lk1, lk2, f.d2>),
+                           (deq_grid<f.m, float>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
     }
 }
 
@@ -805,13 +827,12 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (mx_fast_ok(f, rows, cols, ld, true)) {
-        const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
         if (f.m == 7)
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T>), (deq_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
         else if (f.m == 4)
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T>), (deq_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
         else
-            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
+            hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T>), (deq_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
     } else {
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         bool done = false;
@@ -820,8 +841,7 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
             fr.rounding = BDR_RNE;
             const int spec = ld == cols && ng % 4 == 0 ? hot_index(fr) : -1;
             if (spec >= 0) {
-                const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
-                launch_hot_dequantize(spec, fgrid, s, codes, sexp, mexp, y, ng);
+                launch_hot_dequantize(spec, s, codes, sexp, mexp, y, ng);
                 done = true;
             } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
@@ -851,18 +871,16 @@ int dequantize_row_fixed_exponent(const bdr_format &f, const void *codes, const 
                                   int64_t cols, void *y, int se_code, hipStream_t s)
 {
     const int64_t ng = rows * cols / 8;
-    const dim3 block(kThreads);
-    const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
     const uint8_t *c = (const uint8_t *)codes, *m = (const uint8_t *)mexp;
     uint16_t *out = (uint16_t *)y;
     GatherArgs ga{};
     ga.fixed_se = se_code;
     if (f.m == 7)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, uint16_t, false, true>), fgrid, block, 0, s, c, c, m, out, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, uint16_t, false, true>), (deq_grid<7, uint16_t>(ng)), dim3(kDeqThreads), 0, s, c, c, m, out, ng, ga);
     else if (f.m == 4)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, uint16_t, false, true>), fgrid, block, 0, s, c, c, m, out, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, uint16_t, false, true>), (deq_grid<4, uint16_t>(ng)), dim3(kDeqThreads), 0, s, c, c, m, out, ng, ga);
     else
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, uint16_t, false, true>), fgrid, block, 0, s, c, c, m, out, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, uint16_t, false, true>), (deq_grid<2, uint16_t>(ng)), dim3(kDeqThreads), 0, s, c, c, m, out, ng, ga);
     return launch_status();
 }
 
@@ -872,15 +890,13 @@ static int gather_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t
                         int64_t n_idx, T *y, hipStream_t s)
 {
     const int64_t ng = n_idx * cols / 8;
-    const dim3 block(kThreads);
-    const dim3 fgrid((unsigned)((ng + kThreads * kDeqIter - 1) / (kThreads * kDeqIter)));
     const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0};
     if (f.m == 7)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), (deq_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     else if (f.m == 4)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true>), (deq_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     else
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true>), fgrid, block, 0, s, codes, sexp, mexp, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true>), (deq_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     return launch_status();
 }
 
