@@ -325,6 +325,9 @@ def aux_probe(B, S, torch):
     del tab
     idx = torch.randint(0, rows_t, (n_look,), generator=g, device="cuda", dtype=torch.int64)
     yo = torch.empty(n_look, cols_t, device="cuda")
+    xc = x.view(-1)[:8192 * 8192].view(8192, 8192)   # a square slice for the column-wise general kernel
+    yc = y.view(-1)[:8192 * 8192].view(8192, 8192)
+    pc = B.alloc_planes(fh, 8192, 8192, B.AXIS_COL)
     for _ in range(3):
         y.copy_(x)
         B.bdr_quantize(B.MX9, xa, axis=B.AXIS_COL, out=pcol)
@@ -337,10 +340,13 @@ def aux_probe(B, S, torch):
         B.bdr_dequantize(fh, ph, rows, cols, out=y)
         B.bdr_quantize(fr, x, out=pr)
         B.bdr_dequantize(fr, pr, rows, cols, out=y)
+        B.bdr_quantize(fh, xc, axis=B.AXIS_COL, out=pc)
+        B.bdr_dequantize(fh, pc, 8192, 8192, axis=B.AXIS_COL, out=yc)
     torch.cuda.synchronize()
     print(json.dumps({"aux_probe": "3 x (1 GiB copy; MX9 bf16 8192x12288 column quantize, dequantize, fused, "
                                    "row quantize, dequantize; MX6 gather 2^20 x 128; k1 32 k2 2 d2 1 m 4 and "
-                                   "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32)"}))
+                                   "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32; k1 32 k2 2 d2 1 m 4 "
+                                   "column quantize, dequantize on 8192 x 8192 fp32)"}))
 
 
 def profile_commit(path):
