@@ -58,15 +58,16 @@ __device__ __forceinline__ int lds_off(int r, int c)
     return (r * G::kChunks + (k ^ G::swz(r))) * 16 + e * (int)sizeof(T);
 }
 
-template <typename T>
+template <typename T, int THREADS = kColThreads>
 __device__ __forceinline__ void tile_load(const T *__restrict__ x, int64_t ld, int64_t r0,
                                           int64_t c0, uint8_t *tile)
 {
     typedef TileGeom<T> G;
     constexpr int kTotal = kTR * G::kChunks;
+    static_assert(kTotal % THREADS == 0, "whole passes");
 #pragma unroll
-    for (int j = 0; j < kTotal / kColThreads; ++j) {
-        const int q = threadIdx.x + j * kColThreads;
+    for (int j = 0; j < kTotal / THREADS; ++j) {
+        const int q = threadIdx.x + j * THREADS;
         const int r = q / G::kChunks, k = q % G::kChunks;
         const u32x4 v = ldg<true>(
             reinterpret_cast<const u32x4 *>(x + (r0 + r) * ld + c0 + k * G::kEPC));
@@ -74,15 +75,16 @@ __device__ __forceinline__ void tile_load(const T *__restrict__ x, int64_t ld, i
     }
 }
 
-template <typename T>
+template <typename T, int THREADS = kColThreads>
 __device__ __forceinline__ void tile_store(T *__restrict__ y, int64_t ld, int64_t r0, int64_t c0,
                                            const uint8_t *tile)
 {
     typedef TileGeom<T> G;
     constexpr int kTotal = kTR * G::kChunks;
+    static_assert(kTotal % THREADS == 0, "whole passes");
 #pragma unroll
-    for (int j = 0; j < kTotal / kColThreads; ++j) {
-        const int q = threadIdx.x + j * kColThreads;
+    for (int j = 0; j < kTotal / THREADS; ++j) {
+        const int q = threadIdx.x + j * THREADS;
         const int r = q / G::kChunks, k = q % G::kChunks;
         const u32x4 v = *reinterpret_cast<const u32x4 *>(tile + (r * G::kChunks + (k ^ G::swz(r))) * 16);
         stg<true>(v, reinterpret_cast<u32x4 *>(y + (r0 + r) * ld + c0 + k * G::kEPC));
@@ -190,13 +192,24 @@ __device__ __forceinline__ void codes_load(const uint8_t *codes, int64_t blk, ui
     }
 }
 
+// Threads per tile.  Quantize runs fastest with one lane per block of the tile (BF16 8192 x
+// 12288, MX9 / MX6 / MX4 in microseconds: 256 threads 65 / 73 / 66, 512: 62 / 72 / 64, 1024: 59 /
+// 66 / 59); dequantize and the fused round trip, which end in the store of the tile, do not
+// gain (48 / 42 / 39 -> 48 / 43 / 40 and 72 -> 74) and stay at 256.
+template <typename T, int MODE>
+constexpr int col_threads()
+{
+    return MODE == 0 ? kTR / 16 * TileGeom<T>::kTC : kColThreads;
+}
+
 // MODE 0 quantize (x -> planes), 1 dequantize (planes -> y), 2 fused (x -> y).
 template <int MB, typename T, int MODE>
-__global__ __launch_bounds__(kColThreads) void mx_col_kernel(
+__global__ __launch_bounds__((col_threads<T, MODE>())) void mx_col_kernel(
     const T *x, T *y, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
     uint8_t *__restrict__ mexp, int64_t rows, int64_t ld)
 {
     constexpr int kTC = TileGeom<T>::kTC;
+    constexpr int THREADS = col_threads<T, MODE>(), kWaves = THREADS / 64;
     __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
     // Tiles that follow each other down a column write adjacent runs of the planes
     // (8 blocks each: 48 to 128 bytes of codes, 8 bytes of exponents), so a 64-byte
@@ -229,12 +242,12 @@ __global__ __launch_bounds__(kColThreads) void mx_col_kernel(
     const int64_t blocks_per_col = rows >> 4;
 
     if (MODE != 1) {
-        tile_load(x, ld, r0, c0, tile);
+        tile_load<T, THREADS>(x, ld, r0, c0, tile);
         __syncthreads();
     }
 #pragma unroll
-    for (int it = 0; it < kTC / (4 * kCPW); ++it) {
-        const int c = kCPW * (wave + 4 * it) + cl;  // column inside the tile
+    for (int it = 0; it < kTC / (kWaves * kCPW); ++it) {
+        const int c = kCPW * (wave + kWaves * it) + cl;  // column inside the tile
         const int64_t blk = (c0 + c) * blocks_per_col + (r0 >> 4) + b;
         uint32_t xb[16], yb[16], w[4], se, tau8;
         if (MODE != 1) {
@@ -258,7 +271,7 @@ __global__ __launch_bounds__(kColThreads) void mx_col_kernel(
     }
     if (MODE != 0) {
         __syncthreads();
-        tile_store(y, ld, r0, c0, tile);
+        tile_store<T, THREADS>(y, ld, r0, c0, tile);
     }
 }
 
@@ -266,13 +279,13 @@ template <int MB, typename T>
 void launch_col(int mode, const T *x, T *y, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
                 int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
 {
-    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC)), block(kColThreads);
+    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC));
     if (mode == 0)
-        hipLaunchKernelGGL((mx_col_kernel<MB, T, 0>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
+        hipLaunchKernelGGL((mx_col_kernel<MB, T, 0>), grid, dim3(col_threads<T, 0>()), 0, s, x, y, codes, sexp, mexp, rows, ld);
     else if (mode == 1)
-        hipLaunchKernelGGL((mx_col_kernel<MB, T, 1>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
+        hipLaunchKernelGGL((mx_col_kernel<MB, T, 1>), grid, dim3(col_threads<T, 1>()), 0, s, x, y, codes, sexp, mexp, rows, ld);
     else
-        hipLaunchKernelGGL((mx_col_kernel<MB, T, 2>), grid, block, 0, s, x, y, codes, sexp, mexp, rows, ld);
+        hipLaunchKernelGGL((mx_col_kernel<MB, T, 2>), grid, dim3(col_threads<T, 2>()), 0, s, x, y, codes, sexp, mexp, rows, ld);
 }
 
 template <typename T>
