@@ -192,6 +192,37 @@ __device__ __forceinline__ void codes_load(const uint8_t *codes, int64_t blk, ui
     }
 }
 
+// Which tile a workgroup takes.  Tiles that follow each other down a column write adjacent
+// runs of the planes (8 blocks each: 48 to 128 bytes of codes, 8 bytes of exponents), so a
+// 64-byte line is shared by several workgroups.  Workgroups are dealt to the 8 XCDs round
+// robin by their linear index; the index is remapped so that an XCD owns a band of
+// consecutive row tiles and walks it in chunks of kColRun column tiles: row neighbours of a
+// tile follow within kColRun workgroups on the same XCD, whose L2 then sees whole lines
+// before it writes them back, while the tiles in flight still cover several KiB of every
+// row they read.  With ALONG_ROWS (no plane is written) tiles simply follow each other along
+// the rows of the tensor, so that the tiles in flight cover whole rows (measured: a 2-D tile
+// copy runs 12 % faster this way than walking down the columns first); row neighbours then
+// meet on one XCD whenever the number of column tiles is a multiple of 8, which keeps the
+// plane lines they share in one L2.
+template <bool ALONG_ROWS>
+__device__ __forceinline__ void tile_of(uint32_t &tx, uint32_t &ty)
+{
+    const uint32_t gx = gridDim.x, lin = blockIdx.x + gx * blockIdx.y;
+    tx = blockIdx.x;
+    ty = blockIdx.y;
+    if (ALONG_ROWS) {
+        ty = lin % gridDim.y;
+        tx = lin / gridDim.y;
+    } else if (gx % 8 == 0) {
+        const uint32_t per = gx / 8, xcd = lin % 8, j = lin / 8;
+        uint32_t cw = kColRun;
+        while (gridDim.y % cw) cw >>= 1;
+        const uint32_t chunk = j / (per * cw), rem = j % (per * cw);
+        tx = xcd * per + rem / cw;
+        ty = chunk * cw + rem % cw;
+    }
+}
+
 // Threads per tile.  Quantize runs fastest with one lane per block of the tile (BF16 8192 x
 // 12288, MX9 / MX6 / MX4 in microseconds: 256 threads 65 / 73 / 66, 512: 62 / 72 / 64, 1024: 59 /
 // 66 / 59); dequantize and the fused round trip, which end in the store of the tile, do not
@@ -211,30 +242,8 @@ __global__ __launch_bounds__((col_threads<T, MODE>())) void mx_col_kernel(
     constexpr int kTC = TileGeom<T>::kTC;
     constexpr int THREADS = col_threads<T, MODE>(), kWaves = THREADS / 64;
     __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
-    // Tiles that follow each other down a column write adjacent runs of the planes
-    // (8 blocks each: 48 to 128 bytes of codes, 8 bytes of exponents), so a 64-byte
-    // line is shared by several workgroups.  Workgroups are dealt to the 8 XCDs round
-    // robin by their linear index; the index is remapped so that an XCD owns a band
-    // of consecutive row tiles and walks it in chunks of kColRun column tiles: row
-    // neighbours of a tile follow within kColRun workgroups on the same XCD, whose
-    // L2 then sees whole lines before it writes them back, while the tiles in flight
-    // still cover several KiB of every row they read.
-    const uint32_t gx = gridDim.x, lin = blockIdx.x + gx * blockIdx.y;
-    uint32_t tx = blockIdx.x, ty = blockIdx.y;
-    if (MODE != 0) {
-        // no plane is written: tiles simply follow each other along the rows of the
-        // tensor, so that the tiles in flight cover whole rows (measured: a 2-D tile
-        // copy runs 12 % faster this way than walking down the columns first)
-        ty = lin % gridDim.y;
-        tx = lin / gridDim.y;
-    } else if (gx % 8 == 0) {
-        const uint32_t per = gx / 8, xcd = lin % 8, j = lin / 8;
-        uint32_t cw = kColRun;
-        while (gridDim.y % cw) cw >>= 1;
-        const uint32_t chunk = j / (per * cw), rem = j % (per * cw);
-        tx = xcd * per + rem / cw;
-        ty = chunk * cw + rem % cw;
-    }
+    uint32_t tx, ty;
+    tile_of<MODE != 0>(tx, ty);
     const int64_t r0 = (int64_t)tx * kTR;
     const int64_t c0 = (int64_t)ty * kTC;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -335,7 +344,9 @@ __global__ __launch_bounds__(kColThreads) void generic_col_tiled_kernel(
     const float top = (float)((1u << f.m) - 1u);
     const uint32_t cmask = (1u << cb) - 1u, mmask = (1u << f.m) - 1u;
     const int mbytes = rt * (kTR >> lk2) * f.d2 / 8;     // microexponent bytes per column and band
-    const int64_t band0 = (int64_t)blockIdx.x * rt * kTR, c0 = (int64_t)blockIdx.y * kTC;
+    uint32_t tx, ty;
+    tile_of<MODE != 0>(tx, ty);
+    const int64_t band0 = (int64_t)tx * rt * kTR, c0 = (int64_t)ty * kTC;
     const int tid = threadIdx.x;
 
     if (MODE != 2 && f.d2 > 0) {
