@@ -63,8 +63,8 @@ enum bdr_status {
     BDR_OK = 0,
     BDR_ERR_NULL = 1,   /* a required pointer is NULL */
     BDR_ERR_FORMAT = 2, /* the format tuple is not one this library implements */
-    BDR_ERR_SHAPE = 3,  /* negative size, ld < cols, or the blocked axis is not a multiple of what the kernels need */
-    BDR_ERR_ALIGN = 4,  /* a pointer or row pitch is not 16-byte aligned */
+    BDR_ERR_SHAPE = 3,  /* negative size, ld < cols, or a size the call does not take */
+    BDR_ERR_ALIGN = 4,  /* a pointer or row pitch is not aligned as the call asks */
     BDR_ERR_DTYPE = 5,  /* unknown dtype, or BF16 output asked for a format it cannot hold exactly */
     BDR_ERR_LAUNCH = 6, /* the HIP runtime refused a launch (hipGetLastError was consumed) */
     BDR_ERR_WORKSPACE = 7 /* workspace missing or too small */
@@ -85,8 +85,12 @@ int bdr_format_validate(const bdr_format *fmt);
 
 /* Host only.  Byte sizes of the three planes of a [rows x cols] tensor blocked
  * along `axis`; the three together hold (m+1) + d1/k1 + d2/k2 bits per element
- * (Sec. III).  The blocked axis must be a multiple of max(k1, 8).  Any of the
- * three outputs may be NULL. */
+ * (Sec. III).  A blocked axis that is not a whole number of blocks is stored
+ * padded with +0 to the next multiple of k1, the pads as code 0 (Sec. IX, the
+ * remark after Theorem 1: fewer than k1 elements form a block of their own
+ * length, and zeros change neither its maximum nor its error); the sizes are those
+ * of the padded tensor.  The padded length must be a multiple of 8, which only
+ * k1 < 8 can miss (BDR_ERR_SHAPE).  Any of the three outputs may be NULL. */
 int bdr_packed_sizes(const bdr_format *fmt, int64_t rows, int64_t cols, int axis,
                      size_t *codes_bytes, size_t *sexp_bytes, size_t *mexp_bytes);
 
@@ -97,15 +101,21 @@ int bdr_packed_sizes(const bdr_format *fmt, int64_t rows, int64_t cols, int axis
  *          ld * sizeof(element) a multiple of 16
  *   codes, sexp, mexp   device, sizes from bdr_packed_sizes, 16-byte aligned,
  *          fully overwritten; mexp may be NULL when d2 = 0
- * The blocked axis must be a multiple of max(k1, 8); for BDR_AXIS_COL cols must
- * also be a multiple of 8.  rows = 0 or cols = 0 is BDR_OK and launches nothing. */
+ * Whole shapes - the blocked axis a multiple of max(k1, 8) and, for BDR_AXIS_COL,
+ * cols a multiple of 8 - run on the fast kernels.  Any other shape whose padded
+ * blocked axis (see bdr_packed_sizes) is a multiple of 8 is taken too, element by
+ * element: correct, several times slower, and x then needs only the alignment of
+ * one element and any ld >= cols.  rows = 0 or cols = 0 is BDR_OK and launches
+ * nothing. */
 int bdr_quantize(const bdr_format *fmt, const void *x, int dtype, int64_t rows, int64_t cols,
                  int64_t ld, int axis, void *codes, void *sexp, void *mexp, void *hip_stream);
 
 /* Rebuild y from the packed image: y = (-1)^sign * M * 2^(sexp-127-tau-(m-1))
  * (the descaling step of Sec. II / Fig. 4).  Exact in FP32 for every format; BF16
  * output needs m + 2^d2 - 1 <= 8 (then it is exact too), else BDR_ERR_DTYPE.
- * Same shape and alignment rules as bdr_quantize; y is fully overwritten. */
+ * Same shape and alignment rules as bdr_quantize; the [rows x cols] elements of y
+ * are all written and nothing else is (the pads of a short last block are not
+ * part of y). */
 int bdr_dequantize(const bdr_format *fmt, const void *codes, const void *sexp, const void *mexp,
                    int64_t rows, int64_t cols, int axis, void *y, int dtype, int64_t ld,
                    void *hip_stream);

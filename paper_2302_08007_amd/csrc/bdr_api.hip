@@ -24,25 +24,38 @@ int check_format(const bdr_format *f)
     return BDR_OK;
 }
 
-// Shape rules common to quantize / dequantize / fused: the blocked axis is a
-// multiple of max(k1, 8) (a lane owns 8 consecutive elements of a block row),
-// and for column blocks the contiguous axis is a multiple of 8 as well.
-int check_shape(const bdr_format *f, int dtype, int64_t rows, int64_t cols, int64_t ld, int axis)
+// Length of the blocked axis as the planes store it: a short last block is stored whole, its
+// pads as code 0 (Sec. IX, the remark after Theorem 1: a vector shorter than k1 is a block of
+// its own length).
+inline int64_t padded_len(const bdr_format *f, int64_t n) { return (n + f->k1 - 1) / f->k1 * f->k1; }
+
+// Shape rules common to quantize / dequantize / fused.  Whole shapes: the blocked axis is a
+// multiple of max(k1, 8) (a lane owns 8 consecutive elements of a block row), and for column
+// blocks the contiguous axis is a multiple of 8 as well.  Other shapes are taken when `loose`
+// is given (it is set for them): they run element by element, so all they need is a padded
+// length that is a multiple of 8, which only k1 < 8 can miss.
+int check_shape(const bdr_format *f, int dtype, int64_t rows, int64_t cols, int64_t ld, int axis,
+                bool *loose = nullptr)
 {
+    if (loose) *loose = false;
     if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
     if (axis != BDR_AXIS_ROW && axis != BDR_AXIS_COL) return BDR_ERR_SHAPE;
     if (rows < 0 || cols < 0 || ld < cols) return BDR_ERR_SHAPE;
     if (rows > 0 && cols > 0 && rows > ((int64_t)1 << 40) / cols) return BDR_ERR_SHAPE;
     const int64_t unit = f->k1 > 8 ? f->k1 : 8;
     const int64_t blocked = axis == BDR_AXIS_ROW ? cols : rows;
-    if (blocked % unit != 0) return BDR_ERR_SHAPE;
-    if (axis == BDR_AXIS_COL && cols % 8 != 0) return BDR_ERR_SHAPE;
+    if (blocked % unit != 0 || (axis == BDR_AXIS_COL && cols % 8 != 0)) {
+        if (!loose || padded_len(f, blocked) % 8 != 0) return BDR_ERR_SHAPE;
+        *loose = true;
+    }
     return BDR_OK;
 }
 
-int check_tensor_ptr(const void *p, int dtype, int64_t ld)
+// Whole shapes move in 16-byte pieces; loose ones element by element.
+int check_tensor_ptr(const void *p, int dtype, int64_t ld, bool loose = false)
 {
     if (!p) return BDR_ERR_NULL;
+    if (loose) return reinterpret_cast<uintptr_t>(p) % elem_size(dtype) ? BDR_ERR_ALIGN : BDR_OK;
     if (!aligned16(p) || (ld * (int64_t)elem_size(dtype)) % 16 != 0) return BDR_ERR_ALIGN;
     return BDR_OK;
 }
@@ -83,9 +96,11 @@ int bdr_packed_sizes(const bdr_format *fmt, int64_t rows, int64_t cols, int axis
 {
     int st = check_format(fmt);
     if (st) return st;
-    st = check_shape(fmt, BDR_F32, rows, cols, cols, axis);
+    bool loose;
+    st = check_shape(fmt, BDR_F32, rows, cols, cols, axis, &loose);
     if (st) return st;
-    const uint64_t n = (uint64_t)rows * (uint64_t)cols;
+    const uint64_t n = axis == BDR_AXIS_ROW ? (uint64_t)rows * (uint64_t)padded_len(fmt, cols)
+                                            : (uint64_t)cols * (uint64_t)padded_len(fmt, rows);
     if (codes_bytes) *codes_bytes = (size_t)(n * (uint64_t)(fmt->m + 1) / 8u);  // n % 8 == 0
     if (sexp_bytes) *sexp_bytes = (size_t)(n / (uint64_t)fmt->k1);
     if (mexp_bytes) *mexp_bytes = (size_t)((n / (uint64_t)fmt->k2 * (uint64_t)fmt->d2 + 7u) / 8u);
@@ -97,10 +112,11 @@ int bdr_quantize(const bdr_format *fmt, const void *x, int dtype, int64_t rows, 
 {
     int st = check_format(fmt);
     if (st) return st;
-    st = check_shape(fmt, dtype, rows, cols, ld, axis);
+    bool loose;
+    st = check_shape(fmt, dtype, rows, cols, ld, axis, &loose);
     if (st) return st;
     if (rows == 0 || cols == 0) return BDR_OK;
-    st = check_tensor_ptr(x, dtype, ld);
+    st = check_tensor_ptr(x, dtype, ld, loose);
     if (st) return st;
     st = check_planes(fmt, codes, sexp, mexp);
     if (st) return st;
@@ -116,11 +132,12 @@ int bdr_dequantize(const bdr_format *fmt, const void *codes, const void *sexp, c
 {
     int st = check_format(fmt);
     if (st) return st;
-    st = check_shape(fmt, dtype, rows, cols, ld, axis);
+    bool loose;
+    st = check_shape(fmt, dtype, rows, cols, ld, axis, &loose);
     if (st) return st;
     if (dtype == BDR_BF16 && !bf16_exact(fmt)) return BDR_ERR_DTYPE;
     if (rows == 0 || cols == 0) return BDR_OK;
-    st = check_tensor_ptr(y, dtype, ld);
+    st = check_tensor_ptr(y, dtype, ld, loose);
     if (st) return st;
     st = check_planes(fmt, codes, sexp, mexp);
     if (st) return st;
@@ -179,13 +196,14 @@ int bdr_quantize_dequantize(const bdr_format *fmt, const void *x, void *y, int d
 {
     int st = check_format(fmt);
     if (st) return st;
-    st = check_shape(fmt, dtype, rows, cols, ld, axis);
+    bool loose;
+    st = check_shape(fmt, dtype, rows, cols, ld, axis, &loose);
     if (st) return st;
     if (dtype == BDR_BF16 && !bf16_exact(fmt)) return BDR_ERR_DTYPE;
     if (rows == 0 || cols == 0) return BDR_OK;
-    st = check_tensor_ptr(x, dtype, ld);
+    st = check_tensor_ptr(x, dtype, ld, loose);
     if (st) return st;
-    st = check_tensor_ptr(y, dtype, ld);
+    st = check_tensor_ptr(y, dtype, ld, loose);
     if (st) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (axis == BDR_AXIS_ROW) return bdr::qdq_row(*fmt, x, y, dtype, rows, cols, ld, s);

@@ -440,7 +440,7 @@ template <typename T, int MODE, bool STRIDED, bool CONTIG, int SPEC = -1>
 __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     GenFmt f_arg, const T *x, T *y, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp, int64_t cols, int64_t sr, int64_t sc,
-    int64_t n_groups)
+    int64_t n_groups, int64_t valid)
 {
     static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
     const GenFmt f = SPEC >= 0 ? hot_format(SPEC >= 0 ? SPEC : 0) : f_arg;
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const bool active = g < n_groups;
     uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    int64_t addr = 0;
+    int64_t addr = 0, c0 = 0;
     const int64_t wave_g = g - (threadIdx.x & 63);  // first group of this wave
     const bool mexp_atomics = MODE == 0 && f.d2 > 0 && !(SPEC >= 0 && f.d2 == 1);
     if (mexp_atomics)  // cleared while the loads below are in flight
@@ -462,10 +462,12 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
     } else if (active) {
         const int64_t t0 = 8 * g;
         const int64_t r = t0 / cols;
-        addr = r * sr + (t0 - r * cols) * sc;
+        c0 = t0 - r * cols;
+        addr = r * sr + c0 * sc;
         if (STRIDED) {
+            // elements past the end of a row whose last block is short read as +0
 #pragma unroll
-            for (int i = 0; i < 8; ++i) xb[i] = load1(x + addr + i * sc);
+            for (int i = 0; i < 8; ++i) xb[i] = c0 + i < valid ? load1(x + addr + i * sc) : 0u;
         } else {
             load8(x + addr, xb);
         }
@@ -496,7 +498,8 @@ __global__ __launch_bounds__(kThreads) void generic_quantize_kernel(
         } else if (active) {
             if (STRIDED) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) store1(y + addr + i * sc, yb[i]);
+                for (int i = 0; i < 8; ++i)
+                    if (c0 + i < valid) store1(y + addr + i * sc, yb[i]);
             } else {
                 store8(y + addr, yb);
             }
@@ -642,7 +645,7 @@ template <typename T, bool STRIDED, bool CONTIG>
 __global__ __launch_bounds__(kThreads) void generic_dequantize_kernel(
     GenFmt f, const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, int64_t mexp_bytes, T *__restrict__ y, int64_t cols,
-    int64_t sr, int64_t sc, int64_t n_groups)
+    int64_t sr, int64_t sc, int64_t n_groups, int64_t valid)
 {
     static_assert(!CONTIG || (sizeof(T) == 4 && !STRIDED), "contiguous staging is for FP32 rows");
     __shared__ float s_stage[CONTIG ? kThreads / 64 : 1][CONTIG ? kWaveStage : 1];
@@ -717,10 +720,12 @@ __global__ __launch_bounds__(kThreads) void generic_dequantize_kernel(
     }
     const int64_t t0 = 8 * g;
     const int64_t r = t0 / cols;
-    const int64_t addr = r * sr + (t0 - r * cols) * sc;
+    const int64_t c0 = t0 - r * cols;
+    const int64_t addr = r * sr + c0 * sc;
     if (STRIDED) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) store1(y + addr + i * sc, yb[i]);
+        for (int i = 0; i < 8; ++i)
+            if (c0 + i < valid) store1(y + addr + i * sc, yb[i]);  // pads of a short last block are not part of y
     } else {
         store8(y + addr, yb);
     }
@@ -757,7 +762,7 @@ static void launch_hot(int spec, dim3 grid, hipStream_t s, const float *x, uint8
     if constexpr (SP < kHotCount) {
         if (spec != SP) return launch_hot<SP + 1>(spec, grid, s, x, codes, sexp, mexp, cols, ng);
         hipLaunchKernelGGL((generic_quantize_kernel<float, 0, false, true, SP>), grid, dim3(kThreads), 0, s,
-                           hot_format(SP), x, (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng);
+                           hot_format(SP), x, (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng, cols);
     }
 }
 
@@ -778,10 +783,20 @@ static void launch_hot_dequantize(int spec, hipStream_t s, const uint8_t *codes,
     }
 }
 
+// Rows the flat kernels cannot take: a short last block (or, for k1 < 8, a length that is not
+// a multiple of 8).  They go through the element-at-a-time view.
+static inline bool ragged(const bdr_format &f, int64_t n) { return n % (f.k1 > 8 ? f.k1 : 8) != 0; }
+
+template <typename T>
+static int generic_view_t(int what, const bdr_format &f, const T *x, T *y, int64_t R, int64_t n,
+                          int64_t sr, int64_t sc, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
+                          hipStream_t s);
+
 template <typename T>
 static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
                           uint8_t *codes, uint8_t *sexp, uint8_t *mexp, hipStream_t s)
 {
+    if (ragged(f, cols)) return generic_view_t(0, f, x, (T *)nullptr, rows, cols, ld, (int64_t)1, codes, sexp, mexp, s);
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (mx_fast_ok(f, rows, cols, ld)) {
@@ -802,13 +817,13 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
                 done = true;
             } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, true>), grid, block, 0, s, gen_of(f),
-                                   x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
+                                   x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng, cols);
                 done = true;
             }
         }
         if (!done)
             hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, false>), grid, block, 0, s, gen_of(f),
-                               x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng);
+                               x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng, cols);
     }
     return launch_status();
 }
@@ -828,6 +843,9 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
                             const uint8_t *mexp, int64_t rows, int64_t cols, T *y, int64_t ld,
                             hipStream_t s)
 {
+    if (ragged(f, cols))
+        return generic_view_t(1, f, (const T *)nullptr, y, rows, cols, ld, (int64_t)1, const_cast<uint8_t *>(codes),
+                              const_cast<uint8_t *>(sexp), const_cast<uint8_t *>(mexp), s);
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (mx_fast_ok(f, rows, cols, ld, true)) {
@@ -849,13 +867,13 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
                 done = true;
             } else if (ld == cols) {
                 hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
-                                   codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
+                                   codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng, cols);
                 done = true;
             }
         }
         if (!done)
             hipLaunchKernelGGL((generic_dequantize_kernel<T, false, false>), grid, block, 0, s, gen_of(f),
-                               codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng);
+                               codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng, cols);
     }
     return launch_status();
 }
@@ -919,6 +937,9 @@ template <typename T>
 static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_t cols, int64_t ld,
                      hipStream_t s)
 {
+    if (ragged(f, cols))
+        return generic_view_t(2, f, x, y, rows, cols, ld, (int64_t)1, (uint8_t *)nullptr, (uint8_t *)nullptr,
+                              (uint8_t *)nullptr, s);
     const int64_t ng = rows * cols / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (is_mx(f) && ld == cols && sizeof(T) == 4) {
@@ -947,14 +968,14 @@ static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_
             if (ld == cols) {
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, true>), grid, block, 0, s, gen_of(f),
                                    x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,
-                                   ld, (int64_t)1, ng);
+                                   ld, (int64_t)1, ng, cols);
                 done = true;
             }
         }
         if (!done)
             hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, false>), grid, block, 0, s, gen_of(f),
                                x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,
-                               ld, (int64_t)1, ng);
+                               ld, (int64_t)1, ng, cols);
     }
     return launch_status();
 }
@@ -966,36 +987,41 @@ int qdq_row(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows
     return qdq_row_t(f, (const uint16_t *)x, (uint16_t *)y, rows, cols, ld, s);
 }
 
-// Column blocks through the generic kernels: the transposed view [cols x rows].
+// Any view through the element-at-a-time forms of the general kernels: R rows of n elements,
+// element (r, c) at offset r * sr + c * sc.  A row whose length is not a whole number of
+// blocks is stored as if it were padded with +0 to the next multiple of k1 (a last block of
+// N < k1 elements is a block of size N: its maximum and its errors are those of the N
+// elements; Sec. IX, the remark after Theorem 1); the pads' codes are 0 and dequantize does
+// not write them.  The padded length is a multiple of 8 (checked by the caller).
 template <typename T>
-static int generic_col_t(int what, const bdr_format &f, const T *x, T *y, int64_t rows,
-                         int64_t cols, int64_t ld, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
-                         hipStream_t s)
+static int generic_view_t(int what, const bdr_format &f, const T *x, T *y, int64_t R, int64_t n,
+                          int64_t sr, int64_t sc, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
+                          hipStream_t s)
 {
-    const int64_t ng = rows * cols / 8;
+    const int64_t np = (n + f.k1 - 1) / f.k1 * f.k1;
+    const int64_t ng = R * np / 8;
     const dim3 grid(blocks_for(ng)), block(kThreads);
     if (what == 0)
         hipLaunchKernelGGL((generic_quantize_kernel<T, 0, true, false>), grid, block, 0, s, gen_of(f), x,
-                           (T *)nullptr, codes, sexp, mexp, rows, (int64_t)1, ld, ng);
+                           (T *)nullptr, codes, sexp, mexp, np, sr, sc, ng, n);
     else if (what == 1)
         hipLaunchKernelGGL((generic_dequantize_kernel<T, true, false>), grid, block, 0, s, gen_of(f),
-                           codes, sexp, mexp, (rows * cols / f.k2 * f.d2 + 7) / 8, y, rows,
-                           (int64_t)1, ld, ng);
+                           codes, sexp, mexp, (R * np / f.k2 * f.d2 + 7) / 8, y, np, sr, sc, ng, n);
     else
         hipLaunchKernelGGL((generic_quantize_kernel<T, 1, true, false>), grid, block, 0, s, gen_of(f), x,
-                           y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, rows,
-                           (int64_t)1, ld, ng);
+                           y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, np, sr, sc, ng, n);
     return launch_status();
 }
 
+// Column blocks: the transposed view [cols x rows].
 int generic_col(int what, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
                 int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)
 {
     if (dtype == BDR_F32)
-        return generic_col_t(what, f, (const float *)x, (float *)y, rows, cols, ld,
-                             (uint8_t *)codes, (uint8_t *)sexp, (uint8_t *)mexp, s);
-    return generic_col_t(what, f, (const uint16_t *)x, (uint16_t *)y, rows, cols, ld,
-                         (uint8_t *)codes, (uint8_t *)sexp, (uint8_t *)mexp, s);
+        return generic_view_t(what, f, (const float *)x, (float *)y, cols, rows, (int64_t)1, ld,
+                              (uint8_t *)codes, (uint8_t *)sexp, (uint8_t *)mexp, s);
+    return generic_view_t(what, f, (const uint16_t *)x, (uint16_t *)y, cols, rows, (int64_t)1, ld,
+                          (uint8_t *)codes, (uint8_t *)sexp, (uint8_t *)mexp, s);
 }
 
 }  // namespace bdr

@@ -58,12 +58,26 @@ def test_packed_sizes_formula_and_oracle(f):
         assert 8 * (nc + ns + nm) == n * (f.m + 2)
 
 
+def test_packed_sizes_of_ragged_shapes():
+    """A row whose length is not a whole number of blocks is stored padded to the next multiple
+    of k1 (Sec. IX, the remark after Theorem 1); the sizes agree with the oracle's."""
+    for f, rows, cols in ((B.MX6, 4, 24), (B.MX9, 7, 1000), (B.fmt(64, 4, 1, 4), 3, 65),
+                          (B.fmt(4, 2, 1, 3), 5, 14), (B.fmt(128, 128, 0, 7), 9, 1)):
+        of = O.Format(f.k1, f.d1, f.k2, f.d2, f.m, f.rounding)
+        pc = -(-cols // f.k1) * f.k1
+        assert B.bdr_packed_sizes(f, rows, cols) == O.packed_sizes(of, rows, cols) == \
+            B.bdr_packed_sizes(f, rows, pc)
+        assert B.bdr_packed_sizes(f, cols, rows, B.AXIS_COL) == O.packed_sizes(of, cols, rows, O.AXIS_COL)
+    # column blocks with a ragged contiguous axis: every column is a padded row of the transpose
+    assert B.bdr_packed_sizes(B.MX6, 50, 7, B.AXIS_COL) == B.bdr_packed_sizes(B.MX6, 7, 64)
+
+
 def test_packed_sizes_errors():
     with pytest.raises(B.BdrError) as e:
-        B.bdr_packed_sizes(B.MX6, 4, 24)           # not a multiple of k1
+        B.bdr_packed_sizes(B.fmt(4, 2, 1, 3), 4, 12)   # 12 is whole blocks of 4, but not a multiple of 8
     assert e.value.status == ERR_SHAPE
     with pytest.raises(B.BdrError):
-        B.bdr_packed_sizes(B.fmt(4, 2, 1, 3), 4, 12)   # not a multiple of 8
+        B.bdr_packed_sizes(B.fmt(4, 2, 1, 3), 4, 9)    # padded to 12: still not a multiple of 8
     with pytest.raises(B.BdrError):
         B.bdr_packed_sizes(B.MX6, -1, 16)
     with pytest.raises(B.BdrError):
@@ -81,10 +95,12 @@ def test_quantize_argument_checks():
     assert _q(B.fmt(16, 2, 1, 12)) == ERR_FORMAT
     assert _q(f, dtype=2) == ERR_DTYPE
     assert _q(f, axis=5) == ERR_SHAPE
-    assert _q(f, cols=40, ld=40) == ERR_SHAPE            # 40 % 16 != 0
+    assert _q(B.fmt(4, 2, 1, 3), cols=12, ld=12) == ERR_SHAPE   # k1 < 8: padded length not a multiple of 8
+    assert _q(f, cols=40, ld=40, x=ctypes.c_void_p(0x10002)) == ERR_ALIGN   # a short last block: the alignment of an element
+    assert _q(f, cols=40, ld=40, codes=FAKE_ODD) == ERR_ALIGN
     assert _q(f, ld=32) == ERR_SHAPE                     # ld < cols
     assert _q(f, rows=-1) == ERR_SHAPE
-    assert _q(f, rows=6, axis=1) == ERR_SHAPE            # blocked axis = rows
+    assert _q(B.fmt(2, 1, 1, 3), rows=6, axis=1) == ERR_SHAPE   # blocked axis = rows
     assert _q(f, rows=1 << 30, cols=1 << 20, ld=1 << 20) == ERR_SHAPE   # too large
     assert _q(f, x=NULL) == ERR_NULL
     assert _q(f, codes=NULL) == ERR_NULL
@@ -103,7 +119,8 @@ def test_dequantize_and_fused_argument_checks():
         ctypes.byref(f), FAKE, FAKE, FAKE, rows, cols, 0, y, dtype, ld, NULL)
     assert deq(f, y=NULL) == ERR_NULL
     assert deq(f, y=FAKE_ODD) == ERR_ALIGN
-    assert deq(f, cols=8, ld=8) == ERR_SHAPE
+    assert deq(B.fmt(2, 2, 0, 3), cols=6, ld=8) == ERR_SHAPE
+    assert deq(f, cols=8, ld=8, y=ctypes.c_void_p(0x10002)) == ERR_ALIGN   # half a block is taken (stored as a whole one)
     assert deq(B.fmt(16, 2, 2, 7), dtype=1) == ERR_DTYPE         # m + beta = 10 > 8: not exact in bf16
     assert deq(B.fmt(16, 2, 3, 2), dtype=1) == ERR_DTYPE
     assert deq(f, rows=0) == OK

@@ -109,6 +109,40 @@ def test_other_formats_on_whole_tiles_strided_in_place_and_special_values():
         _check_col(B.fmt(**kw), s, "special %r" % (kw,))
 
 
+@pytest.mark.parametrize("kw", [dict(k1=16, k2=2, d2=1, m=7), dict(k1=16, k2=2, d2=1, m=4),
+                                dict(k1=16, k2=2, d2=1, m=2), dict(k1=64, k2=8, d2=2, m=4, rounding=1),
+                                dict(k1=8, k2=8, d2=0, m=6), dict(k1=2, k2=1, d2=1, m=3)],
+                         ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_columns_with_a_short_last_block(kw, dtype):
+    """Column blocks on shapes whose column length is not a whole number of blocks, or whose
+    row length is not a multiple of 8: every column is a padded row of the transpose."""
+    f = B.fmt(**kw)
+    if dtype == torch.bfloat16 and f.m + (1 << f.d2) - 1 > 8:
+        pytest.skip("bf16 cannot hold this format exactly")
+    for rows, cols in ((50, 7), (1, 1), (1000, 24), (130, 64), (16, 3), (24, 9)):
+        if (-(-rows // f.k1) * f.k1) % 8:
+            continue
+        x = S.wide_range(rows, cols, device="cuda", seed=3 * rows + cols, dtype=dtype)
+        planes = _check_col(f, x, "%r %s %s" % (f, dtype, (rows, cols)))
+        want = O.quantize(ofmt(f), np.ascontiguousarray(to_np(x).T))
+        assert_planes_equal(planes, want, "%r %s: rows of the transpose" % (f, (rows, cols)))
+    if (-(-45 // f.k1) * f.k1) % 8:
+        return
+    big = S.wide_range(45, 131, device="cuda", seed=78, dtype=dtype)
+    view = big[:, 5:5 + 9]
+    xn = np.ascontiguousarray(to_np(big)[:, 5:5 + 9])
+    want = O.quantize(ofmt(f), xn, axis=O.AXIS_COL)
+    planes = B.bdr_quantize(f, view, axis=B.AXIS_COL)
+    assert_planes_equal(planes, want, "%r view" % f)
+    out_dtype = np.float32 if dtype == torch.float32 else np.uint16
+    ywant = O.dequantize(ofmt(f), *want, 45, 9, axis=O.AXIS_COL, out_dtype=out_dtype)
+    out = torch.full_like(big, 7.0)
+    B.bdr_dequantize(f, planes, 45, 9, axis=B.AXIS_COL, out=out[:, 5:5 + 9])
+    assert_bits_equal(out[:, 5:5 + 9].contiguous(), ywant, "%r view dequantize" % f)
+    assert bool((out[:, :5] == 7).all()) and bool((out[:, 14:] == 7).all())
+
+
 @pytest.mark.parametrize("name", MX)
 def test_column_blocks_equal_row_blocks_of_the_transpose(name):
     f = getattr(B, name)

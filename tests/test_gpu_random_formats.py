@@ -50,6 +50,34 @@ def test_random_format_row_and_column(seed):
         assert_bits_equal(B.bdr_quantize_dequantize(f, x, axis=axis), ywant, what + " fused")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_format_on_shapes_of_any_size(seed):
+    """Random formats on shapes whose blocked axis is any length (a short last block is stored
+    as a whole one, its pads as code 0) and whose other axis is any length too."""
+    rng = np.random.default_rng(3000 + seed)
+    f = _random_format(rng)
+    dtype = torch.float32 if seed % 2 == 0 or f.m + (1 << f.d2) - 1 > 8 else torch.bfloat16
+    for axis in (B.AXIS_ROW, B.AXIS_COL):
+        while True:
+            blocked = int(rng.integers(1, 3000))
+            if (-(-blocked // f.k1) * f.k1) % 8 == 0:       # only k1 < 8 can miss this
+                break
+        other = int(rng.integers(1, 60))
+        rows, cols = (other, blocked) if axis == B.AXIS_ROW else (blocked, other)
+        x = S.wide_range(rows, cols, device="cuda", seed=seed * 11 + axis, spread=10, dtype=dtype)
+        oaxis = O.AXIS_ROW if axis == B.AXIS_ROW else O.AXIS_COL
+        want = O.quantize(ofmt(f), to_np(x), axis=oaxis)
+        what = "%r axis %d %s %dx%d" % (f, axis, dtype, rows, cols)
+        planes = B.bdr_quantize(f, x, axis=axis)
+        torch.cuda.synchronize()
+        assert_planes_equal(planes, want, what + " quantize")
+        out_dtype = np.float32 if dtype == torch.float32 else np.uint16
+        ywant = O.dequantize(ofmt(f), *want, rows, cols, axis=oaxis, out_dtype=out_dtype)
+        assert_bits_equal(B.bdr_dequantize(f, planes, rows, cols, axis=axis, dtype=dtype), ywant,
+                          what + " dequantize")
+        assert_bits_equal(B.bdr_quantize_dequantize(f, x, axis=axis), ywant, what + " fused")
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_format_lists_in_the_sweep(seed):
     rng = np.random.default_rng(2000 + seed)

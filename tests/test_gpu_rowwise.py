@@ -113,6 +113,47 @@ def test_design_space_sweep_formats(k1, k2, d2, m):
     assert_planes_equal(B.bdr_quantize(f, sub), want, "%r pitched" % f)
 
 
+RAGGED_FORMATS = [dict(k1=16, k2=2, d2=1, m=7), dict(k1=16, k2=2, d2=1, m=4), dict(k1=16, k2=2, d2=1, m=2),
+                  dict(k1=64, k2=4, d2=1, m=4), dict(k1=32, k2=32, d2=0, m=5, rounding=2),
+                  dict(k1=8, k2=1, d2=2, m=3, rounding=1), dict(k1=256, k2=16, d2=3, m=8),
+                  dict(k1=4, k2=2, d2=1, m=3), dict(k1=128, k2=128, d2=1, m=1)]
+
+
+@pytest.mark.parametrize("kw", RAGGED_FORMATS, ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_rows_with_a_short_last_block(kw, dtype):
+    """Row lengths that are not a whole number of blocks (Sec. IX, the remark after Theorem 1:
+    fewer than k1 elements are a block of their own length): planes as the oracle pads them,
+    pads stored as code 0, dequantize and the fused form writing the real elements only."""
+    f = B.fmt(**kw)
+    if dtype == torch.bfloat16 and f.m + (1 << f.d2) - 1 > 8:
+        pytest.skip("bf16 cannot hold this format exactly")
+    for rows, cols in ((1, 1), (3, 24), (5, 1000), (2, 2049), (33, 40), (300, 7)):
+        if (-(-cols // f.k1) * f.k1) % 8:
+            with pytest.raises(B.BdrError):
+                B.bdr_packed_sizes(f, rows, cols)
+            continue
+        x = S.wide_range(rows, cols, device="cuda", seed=rows + cols, dtype=dtype)
+        _roundtrip_check(f, x, "%r %s %s" % (f, dtype, (rows, cols)))
+    # inside a wider tensor (odd pitch, odd offset): nothing outside the view is touched
+    big = S.wide_range(9, 131, device="cuda", seed=77, dtype=dtype)
+    view = big[:, 3:3 + 45]
+    xn = np.ascontiguousarray(to_np(big)[:, 3:3 + 45])
+    want = O.quantize(ofmt(f), xn)
+    planes = B.bdr_quantize(f, view)
+    assert_planes_equal(planes, want, "%r view" % f)
+    out_dtype = np.float32 if dtype == torch.float32 else np.uint16
+    ywant = O.dequantize(ofmt(f), *want, 9, 45, out_dtype=out_dtype)
+    out = torch.full_like(big, 7.0)
+    B.bdr_dequantize(f, planes, 9, 45, out=out[:, 3:3 + 45])
+    assert_bits_equal(out[:, 3:3 + 45].contiguous(), ywant, "%r view dequantize" % f)
+    assert bool((out[:, :3] == 7).all()) and bool((out[:, 48:] == 7).all())
+    keep = big.clone()
+    B.bdr_quantize_dequantize(f, view, out=view)       # in place
+    assert_bits_equal(view.contiguous(), ywant, "%r view fused in place" % f)
+    assert torch.equal(big[:, :3], keep[:, :3]) and torch.equal(big[:, 48:], keep[:, 48:])
+
+
 @pytest.mark.parametrize("name", MX)
 def test_strided_rows(name):
     # ld > cols: a column slice of a wider tensor
