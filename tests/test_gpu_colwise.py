@@ -31,7 +31,9 @@ def _check_col(f, x, what):
 
 @pytest.mark.parametrize("name", MX)
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("shape", [(128, 64), (256, 192), (384, 64), (1024, 320)])
+# (odd and even numbers of column tiles: the quantize kernel takes tiles in pairs when it can)
+@pytest.mark.parametrize("shape", [(128, 64), (256, 192), (384, 64), (1024, 320), (256, 256), (384, 1024),
+                                   (128, 128 * 17), (1024, 128 * 34)])
 def test_tiled_path(name, dtype, shape):
     x = S.wide_range(*shape, device="cuda", seed=shape[0] + shape[1], dtype=dtype)
     _check_col(getattr(B, name), x, "%s %s %s" % (name, dtype, shape))
