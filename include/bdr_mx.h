@@ -133,6 +133,29 @@ int bdr_gather_dequantize(const bdr_format *fmt, const void *codes, const void *
                           const void *mexp, int64_t table_rows, int64_t cols, const int64_t *indices,
                           int64_t n_indices, void *y, int dtype, void *hip_stream);
 
+/* The same lookup on a table that keeps each row's bytes together.  A lookup in the
+ * three-plane image reads three separate runs per row (codes, exponent bytes,
+ * microexponent bytes), each at least one memory line; for embedding rows of a few
+ * hundred elements that is several times the bytes a row holds.  In the table image a
+ * row is bdr_table_row_bytes(fmt, cols) consecutive bytes: the row's run of the codes
+ * plane, then its run of the exponent plane, then its run of the microexponent plane,
+ * unchanged; rows follow each other without gaps.  (Storage of embedding tables,
+ * Sec. V "Inferencing"; the bytes are those of Sec. III's format, (m+1) + d1/k1 + d2/k2
+ * bits per element.)  Table II's formats only (else BDR_ERR_FORMAT); cols a multiple
+ * of 64 (else BDR_ERR_SHAPE).
+ *
+ * bdr_table_row_bytes: host only; 0 for a format or cols the table image does not take.
+ * bdr_table_pack: planes (device, as bdr_quantize wrote them for [table_rows x cols],
+ *   row blocks) -> table (device, table_rows * row bytes, 16-byte aligned, fully
+ *   overwritten).
+ * bdr_table_gather_dequantize: as bdr_gather_dequantize, reading the table image. */
+size_t bdr_table_row_bytes(const bdr_format *fmt, int64_t cols);
+int bdr_table_pack(const bdr_format *fmt, const void *codes, const void *sexp, const void *mexp,
+                   int64_t table_rows, int64_t cols, void *table, void *hip_stream);
+int bdr_table_gather_dequantize(const bdr_format *fmt, const void *table, int64_t table_rows,
+                                int64_t cols, const int64_t *indices, int64_t n_indices, void *y,
+                                int dtype, void *hip_stream);
+
 /* Host only.  Memory-interface packing of one tile (Sec. IV-B, "Memory Footprint": a
  * tile of 256 elements into a 64-byte interface): bytes the tile's packed image takes,
  * interface transfers needed, and efficiency = bytes / (transfers * interface_bytes).

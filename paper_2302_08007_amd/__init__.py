@@ -20,7 +20,8 @@ OK = 0
 
 EXPORTS = (
     "bdr_status_string", "bdr_format_validate", "bdr_packed_sizes", "bdr_quantize",
-    "bdr_dequantize", "bdr_gather_dequantize", "bdr_tile_packing", "bdr_quantize_dequantize",
+    "bdr_dequantize", "bdr_gather_dequantize", "bdr_table_row_bytes", "bdr_table_pack",
+    "bdr_table_gather_dequantize", "bdr_tile_packing", "bdr_quantize_dequantize",
     "bdr_qsnr_sweep_workspace_bytes",
     "bdr_qsnr_sweep", "bdr_qsnr_sweep_static", "bdr_qsnr_sweep_static_scratch_bytes",
     "mx_gemm_workspace_bytes", "mx_gemm", "mx_dot_pipeline_workspace_bytes", "mx_dot_pipeline",
@@ -69,6 +70,10 @@ def _load():
     L.bdr_dequantize.argtypes = [FP, P, P, P, I64, I64, I32, P, I32, I64, P]
     L.bdr_quantize_dequantize.argtypes = [FP, P, P, I32, I64, I64, I64, I32, P]
     L.bdr_gather_dequantize.argtypes = [FP, P, P, P, I64, I64, P, I64, P, I32, P]
+    L.bdr_table_row_bytes.argtypes = [FP, I64]
+    L.bdr_table_row_bytes.restype = SZ
+    L.bdr_table_pack.argtypes = [FP, P, P, P, I64, I64, P, P]
+    L.bdr_table_gather_dequantize.argtypes = [FP, P, I64, I64, P, I64, P, I32, P]
     L.bdr_tile_packing.argtypes = [FP, I64, I64, P, P, P]
     L.bdr_qsnr_sweep_workspace_bytes.argtypes = [I32]
     L.bdr_qsnr_sweep_workspace_bytes.restype = SZ
@@ -234,6 +239,42 @@ def bdr_gather_dequantize(fmt, planes, table_rows, cols, indices, dtype=None, ou
     _check(lib.bdr_gather_dequantize(ctypes.byref(fmt), _p(planes[0]), _p(planes[1]), _p(planes[2]),
                                      table_rows, cols, _p(indices), n, _p(y), _dtype_code(y),
                                      _stream()))
+    return y
+
+
+def bdr_table_row_bytes(fmt, cols):
+    """Bytes of one row of the table image that keeps a row's runs together (0: not taken)."""
+    return int(lib.bdr_table_row_bytes(ctypes.byref(fmt), cols))
+
+
+def bdr_table_pack(fmt, planes, table_rows, cols, out=None):
+    """Three-plane image of a [table_rows x cols] table -> the image whose rows are
+    [codes | exponent bytes | microexponent bytes] (uint8 tensor of table_rows * row bytes)."""
+    rb = bdr_table_row_bytes(fmt, cols)
+    if rb == 0 and cols != 0:
+        raise ValueError("the table image takes Table II's formats with cols a multiple of 64")
+    _check_planes(fmt, planes, table_rows, cols)
+    t = out if out is not None else torch.empty(table_rows * rb, dtype=torch.uint8, device=planes[0].device)
+    _check_buffer("table", t, torch.uint8, table_rows * rb)
+    _check(lib.bdr_table_pack(ctypes.byref(fmt), _p(planes[0]), _p(planes[1]), _p(planes[2]), table_rows,
+                              cols, _p(t), _stream()))
+    return t
+
+
+def bdr_table_gather_dequantize(fmt, table, table_rows, cols, indices, dtype=None, out=None):
+    """bdr_gather_dequantize on the image bdr_table_pack made."""
+    dtype = dtype or torch.float32
+    n = indices.numel()
+    y = out if out is not None else torch.empty((n, cols), dtype=dtype, device=indices.device)
+    _check_buffer("indices", indices, torch.int64, n)
+    if not (y.is_cuda and y.is_contiguous() and tuple(y.shape) == (n, cols)):
+        raise ValueError("output must be a contiguous [n_indices x cols] GPU tensor")
+    rb = bdr_table_row_bytes(fmt, cols)
+    if rb == 0 and cols != 0:
+        raise ValueError("the table image takes Table II's formats with cols a multiple of 64")
+    _check_buffer("table", table, torch.uint8, table_rows * rb)
+    _check(lib.bdr_table_gather_dequantize(ctypes.byref(fmt), _p(table), table_rows, cols, _p(indices), n,
+                                           _p(y), _dtype_code(y), _stream()))
     return y
 
 

@@ -172,6 +172,57 @@ int bdr_gather_dequantize(const bdr_format *fmt, const void *codes, const void *
                                       dtype, static_cast<hipStream_t>(hip_stream));
 }
 
+// Checks shared by the two calls on tables that keep a row's runs together.
+static int check_table(const bdr_format *fmt, int64_t table_rows, int64_t cols)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    if (!bdr::is_mx_layout(*fmt)) return BDR_ERR_FORMAT;
+    if (table_rows < 0 || cols < 0 || cols % 64 != 0) return BDR_ERR_SHAPE;
+    if (cols > ((int64_t)1 << 24) || table_rows > ((int64_t)1 << 40) / (cols > 0 ? cols : 1)) return BDR_ERR_SHAPE;
+    return BDR_OK;
+}
+
+size_t bdr_table_row_bytes(const bdr_format *fmt, int64_t cols)
+{
+    if (check_table(fmt, 0, cols) != BDR_OK) return 0;
+    return (size_t)(cols / 8 * (fmt->m + 1) + 2 * (cols / 16));
+}
+
+int bdr_table_pack(const bdr_format *fmt, const void *codes, const void *sexp, const void *mexp,
+                   int64_t table_rows, int64_t cols, void *table, void *hip_stream)
+{
+    int st = check_table(fmt, table_rows, cols);
+    if (st) return st;
+    if (table_rows == 0 || cols == 0) return BDR_OK;
+    st = check_planes(fmt, codes, sexp, mexp);
+    if (st) return st;
+    if (!table) return BDR_ERR_NULL;
+    if (!aligned16(table)) return BDR_ERR_ALIGN;
+    return bdr::table_pack(*fmt, codes, sexp, mexp, table_rows, cols, table, static_cast<hipStream_t>(hip_stream));
+}
+
+int bdr_table_gather_dequantize(const bdr_format *fmt, const void *table, int64_t table_rows, int64_t cols,
+                                const int64_t *indices, int64_t n_indices, void *y, int dtype,
+                                void *hip_stream)
+{
+    int st = check_table(fmt, table_rows, cols);
+    if (st) return st;
+    if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
+    if (n_indices < 0 || n_indices > ((int64_t)1 << 40) / (cols > 0 ? cols : 1)) return BDR_ERR_SHAPE;
+    if (n_indices == 0 || cols == 0) return BDR_OK;
+    if (!indices) return BDR_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(indices) & 7u) != 0) return BDR_ERR_ALIGN;
+    st = check_tensor_ptr(y, dtype, cols);
+    if (st) return st;
+    if (table_rows > 0) {
+        if (!table) return BDR_ERR_NULL;
+        if (!aligned16(table)) return BDR_ERR_ALIGN;
+    }
+    return bdr::table_gather_dequantize(*fmt, table, table_rows, cols, indices, n_indices, y, dtype,
+                                        static_cast<hipStream_t>(hip_stream));
+}
+
 int bdr_tile_packing(const bdr_format *fmt, int64_t tile_elements, int64_t interface_bytes,
                      int64_t *packed_bytes, int64_t *transfers, double *efficiency)
 {

@@ -58,6 +58,11 @@ int dequantize_row_fixed_exponent(const bdr_format &f, const void *codes, const 
 int gather_dequantize_row(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
                           int64_t table_rows, int64_t cols, const int64_t *idx, int64_t n_idx, void *y,
                           int dtype, hipStream_t s);
+// tables whose rows keep their three runs together (cols a multiple of 64)
+int table_pack(const bdr_format &f, const void *codes, const void *sexp, const void *mexp, int64_t rows,
+               int64_t cols, void *table, hipStream_t s);
+int table_gather_dequantize(const bdr_format &f, const void *table, int64_t table_rows, int64_t cols,
+                            const int64_t *idx, int64_t n_idx, void *y, int dtype, hipStream_t s);
 int qdq_row(const bdr_format &f, const void *x, void *y, int dtype, int64_t rows, int64_t cols,
             int64_t ld, hipStream_t s);
 

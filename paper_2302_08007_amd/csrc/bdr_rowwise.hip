@@ -175,6 +175,10 @@ struct GatherArgs {
     int64_t table_rows;
     int32_t groups_per_row;  // cols / 8, a multiple of 4
     int32_t fixed_se;        // FIXED_SE: the exponent code every block is given
+    // ROWS_TOGETHER: the table keeps each row's three runs next to each other (`codes` is the
+    // table): row_bytes per row, the exponent bytes codes_row bytes into it, the
+    // microexponent bytes sexp_row bytes after those
+    int32_t row_bytes, codes_row, sexp_row;
 };
 // FIXED_SE: the exponent plane is not read; every block takes the exponent code
 // ga.fixed_se instead, which turns the elements into the scaled integers
@@ -184,7 +188,7 @@ struct GatherArgs {
 // own (4, 1, 1) by default.  Only where the lane finds its exponent byte and its microexponent
 // bits depends on them: the codes of 8 elements are MB + 1 bytes whatever the block sizes.
 template <int MB, typename T, bool GATHER = false, bool FIXED_SE = false, int LK1 = 4, int LK2 = 1,
-          int D2 = 1>
+          int D2 = 1, bool ROWS_TOGETHER = false>
 __global__ __launch_bounds__(kDeqThreads) void mx_dequantize_row_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ sexp,
     const uint8_t *__restrict__ mexp, T *__restrict__ y, int64_t n_groups, GatherArgs ga)
@@ -206,34 +210,42 @@ __global__ __launch_bounds__(kDeqThreads) void mx_dequantize_row_kernel(
         v0[it] = v1[it] = seb[it] = tbb[it] = 0;
         bool live = go < n_groups;  // whole quads are live or not (n_groups % 4 == 0)
         int64_t g = go;             // group of the packed image it comes from
+        const uint8_t *cp = codes, *sp = sexp, *mp = mexp;
         if (GATHER && live) {
             const int64_t j = go / ga.groups_per_row;
             const int64_t r = ga.idx[j];
             live = r >= 0 && r < ga.table_rows;
-            g = r * ga.groups_per_row + (go - j * ga.groups_per_row);
+            g = go - j * ga.groups_per_row;
+            if (ROWS_TOGETHER) {
+                cp = codes + r * ga.row_bytes;  // the row's own runs; g counts inside the row
+                sp = cp + ga.codes_row;
+                mp = sp + ga.sexp_row;
+            } else {
+                g += r * ga.groups_per_row;
+            }
         }
         if (live) {
             const int64_t quad = g >> 2;
             if (CB == 8) {
-                u32x2 v = ldg<!GATHER>(reinterpret_cast<const u32x2 *>(codes + 8 * g));
+                u32x2 v = ldg<!GATHER>(reinterpret_cast<const u32x2 *>(cp + 8 * g));
                 v0[it] = v.x;
                 v1[it] = v.y;
             } else if (CB == 5) {
                 // aligned dword loads only: lane i takes dword i of the quad's five, the
                 // fifth is fetched by all four lanes and used by lane 3
-                const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 5 * quad;
+                const uint32_t *cw = reinterpret_cast<const uint32_t *>(cp) + 5 * quad;
                 v0[it] = cw[i];
                 v1[it] = cw[4];
             } else {
                 // lane i takes dword min(i, 2) of the quad's three
-                const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes) + 3 * quad;
+                const uint32_t *cw = reinterpret_cast<const uint32_t *>(cp) + 3 * quad;
                 v0[it] = cw[i < 2 ? i : 2];
             }
-            seb[it] = FIXED_SE ? (uint32_t)ga.fixed_se : sexp[g >> (LK1 - 3)];
+            seb[it] = FIXED_SE ? (uint32_t)ga.fixed_se : sp[g >> (LK1 - 3)];
             // the byte that holds the lane's microexponent bits: 8 >> LK2 of them from bit
             // g (8 >> LK2) of the stream when k2 <= 8, else the one bit of sub-block
             // g / (k2 / 8); byte g >> LK2 either way
-            if (D2) tbb[it] = mexp[g >> LK2];
+            if (D2) tbb[it] = mp[g >> LK2];
         }
     }
 #pragma unroll
@@ -906,13 +918,75 @@ int dequantize_row_fixed_exponent(const bdr_format &f, const void *codes, const 
     return launch_status();
 }
 
+// ---- tables that keep a row's three runs together
+//
+// A lookup of a random row touches three places of the three-plane image (its codes, its
+// exponent bytes, its microexponent bytes); each costs at least one memory line, which for
+// rows of a few hundred elements is several times the bytes the row holds.  A table whose
+// rows are [codes | exponent bytes | microexponent bytes], one after the other, is read as
+// one run per lookup.  Same bytes, another order.
+__global__ __launch_bounds__(kThreads) void table_pack_kernel(
+    const uint32_t *__restrict__ codes, const uint32_t *__restrict__ sexp,
+    const uint32_t *__restrict__ mexp, int64_t n_dwords, int32_t codes_dw, int32_t sexp_dw,
+    int32_t mexp_dw, uint32_t *__restrict__ table)
+{
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= n_dwords) return;
+    const int32_t row_dw = codes_dw + sexp_dw + mexp_dw;
+    const int64_t r = t / row_dw;
+    const int32_t o = (int32_t)(t - r * row_dw);
+    uint32_t v;
+    if (o < codes_dw)
+        v = codes[r * codes_dw + o];
+    else if (o < codes_dw + sexp_dw)
+        v = sexp[r * sexp_dw + (o - codes_dw)];
+    else
+        v = mexp[r * mexp_dw + (o - codes_dw - sexp_dw)];
+    table[t] = v;
+}
+
+int table_pack(const bdr_format &f, const void *codes, const void *sexp, const void *mexp, int64_t rows,
+               int64_t cols, void *table, hipStream_t s)
+{
+    const int32_t codes_dw = (int32_t)(cols / 8 * (f.m + 1) / 4), e_dw = (int32_t)(cols / 64);
+    const int64_t n = rows * (codes_dw + 2 * (int64_t)e_dw);
+    hipLaunchKernelGGL(table_pack_kernel, dim3(blocks_for(n)), dim3(kThreads), 0, s, (const uint32_t *)codes,
+                       (const uint32_t *)sexp, (const uint32_t *)mexp, n, codes_dw, e_dw, e_dw,
+                       (uint32_t *)table);
+    return launch_status();
+}
+
+template <typename T>
+static int table_gather_t(const bdr_format &f, const uint8_t *table, int64_t table_rows, int64_t cols,
+                          const int64_t *idx, int64_t n_idx, T *y, hipStream_t s)
+{
+    const int64_t ng = n_idx * cols / 8;
+    const int32_t codes_row = (int32_t)(cols / 8 * (f.m + 1)), e_row = (int32_t)(cols / 16);
+    const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0, codes_row + 2 * e_row, codes_row, e_row};
+    if (f.m == 7)
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true, false, 4, 1, 1, true>), (deq_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
+    else if (f.m == 4)
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true, false, 4, 1, 1, true>), (deq_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
+    else
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true, false, 4, 1, 1, true>), (deq_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
+    return launch_status();
+}
+
+int table_gather_dequantize(const bdr_format &f, const void *table, int64_t table_rows, int64_t cols,
+                            const int64_t *idx, int64_t n_idx, void *y, int dtype, hipStream_t s)
+{
+    if (dtype == BDR_F32)
+        return table_gather_t(f, (const uint8_t *)table, table_rows, cols, idx, n_idx, (float *)y, s);
+    return table_gather_t(f, (const uint8_t *)table, table_rows, cols, idx, n_idx, (uint16_t *)y, s);
+}
+
 template <typename T>
 static int gather_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t *sexp,
                         const uint8_t *mexp, int64_t table_rows, int64_t cols, const int64_t *idx,
                         int64_t n_idx, T *y, hipStream_t s)
 {
     const int64_t ng = n_idx * cols / 8;
-    const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0};
+    const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0, 0, 0, 0};
     if (f.m == 7)
         hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), (deq_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     else if (f.m == 4)

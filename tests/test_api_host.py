@@ -231,6 +231,29 @@ def test_tile_packing_of_the_paper_formats():
     assert L.bdr_tile_packing(ctypes.byref(B.MX9), 256, 64, NULL, NULL, NULL) == OK
 
 
+def test_table_image_argument_checks():
+    L, f = B.lib, B.MX6
+    assert B.bdr_table_row_bytes(B.MX9, 128) == 144 and B.bdr_table_row_bytes(B.MX6, 128) == 96
+    assert B.bdr_table_row_bytes(B.MX4, 64) == 32
+    for f2, cols in ((B.MX6, 128), (B.MX9, 64), (B.MX4, 1024)):
+        assert 1000 * B.bdr_table_row_bytes(f2, cols) == sum(B.bdr_packed_sizes(f2, 1000, cols))
+    assert B.bdr_table_row_bytes(B.MX6, 96) == 0 and B.bdr_table_row_bytes(B.fmt(32, 2, 1, 4), 128) == 0
+    assert B.bdr_table_row_bytes(B.MX6, 0) == 0 and B.bdr_table_row_bytes(B.MX6, -64) == 0
+    pk = lambda fm=f, rows=10, cols=128, codes=FAKE, sexp=FAKE, mexp=FAKE, t=FAKE: L.bdr_table_pack(
+        ctypes.byref(fm), codes, sexp, mexp, rows, cols, t, NULL)
+    assert pk(fm=B.fmt(16, 16, 0, 4)) == ERR_FORMAT and pk(cols=96) == ERR_SHAPE and pk(rows=-1) == ERR_SHAPE
+    assert pk(codes=NULL) == ERR_NULL and pk(t=NULL) == ERR_NULL and pk(mexp=NULL) == ERR_NULL
+    assert pk(t=FAKE_ODD) == ERR_ALIGN and pk(sexp=FAKE_ODD) == ERR_ALIGN
+    assert pk(rows=0) == OK and pk(rows=0, codes=NULL, t=NULL) == OK
+    tg = lambda fm=f, t=FAKE, rows=100, cols=128, idx=FAKE, n=10, y=FAKE, dtype=0: L.bdr_table_gather_dequantize(
+        ctypes.byref(fm), t, rows, cols, idx, n, y, dtype, NULL)
+    assert tg(fm=B.fmt(32, 2, 1, 4)) == ERR_FORMAT and tg(dtype=3) == ERR_DTYPE
+    assert tg(cols=32) == ERR_SHAPE and tg(n=-1) == ERR_SHAPE and tg(rows=-1) == ERR_SHAPE
+    assert tg(idx=NULL) == ERR_NULL and tg(y=NULL) == ERR_NULL and tg(t=NULL) == ERR_NULL
+    assert tg(idx=FAKE_ODD) == ERR_ALIGN and tg(y=FAKE_ODD) == ERR_ALIGN and tg(t=FAKE_ODD) == ERR_ALIGN
+    assert tg(n=0) == OK and tg(n=0, idx=NULL, y=NULL, t=NULL) == OK
+
+
 def test_gather_argument_checks():
     L = B.lib
     f = B.MX6
@@ -256,6 +279,7 @@ def test_header_is_plain_c(tmp_path):
         "    size_t a, b, c;\n"
         "    void *fns[] = {(void *)bdr_status_string, (void *)bdr_format_validate, (void *)bdr_packed_sizes,\n"
         "                   (void *)bdr_quantize, (void *)bdr_dequantize, (void *)bdr_gather_dequantize,\n"
+        "                   (void *)bdr_table_row_bytes, (void *)bdr_table_pack, (void *)bdr_table_gather_dequantize,\n"
         "                   (void *)bdr_tile_packing, (void *)bdr_quantize_dequantize,\n"
         "                   (void *)bdr_qsnr_sweep_workspace_bytes, (void *)bdr_qsnr_sweep,\n"
         "                   (void *)bdr_qsnr_sweep_static, (void *)bdr_qsnr_sweep_static_scratch_bytes,\n"

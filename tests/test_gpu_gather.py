@@ -107,3 +107,64 @@ def test_embedding_table_shape_sampled():
     sub = [np.concatenate([p[r * k:(r + 1) * k] for r in src]) for p, k in zip(pn, per_row)]
     want = O.dequantize(ofmt(f), *sub, len(src), cols)
     assert_bits_equal(y[torch.as_tensor(pick, device="cuda")], want, "sampled lookups")
+
+
+def _rows_together(f, planes, rows, cols):
+    """The table image written out from the oracle-checked planes: per row, its run of each
+    plane, one after the other (pure byte movement)."""
+    cb = cols // 8 * (f.m + 1)
+    c, s, m = (p.cpu().numpy() for p in planes)
+    return np.concatenate([c.reshape(rows, cb), s.reshape(rows, cols // 16), m.reshape(rows, cols // 16)],
+                          axis=1).reshape(-1)
+
+
+@pytest.mark.parametrize("name", MX)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(50, 64, 7), (1000, 128, 513), (300, 448, 1031), (3, 2048, 100)])
+def test_tables_that_keep_a_row_together(name, dtype, shape):
+    rows, cols, n = shape
+    f = getattr(B, name)
+    x = _table(rows, cols, rows + cols)
+    want = O.quantize(ofmt(f), to_np(x))
+    planes = B.bdr_quantize(f, x)
+    assert all(np.array_equal(p.cpu().numpy(), w) for p, w in zip(planes, want))
+    table = B.bdr_table_pack(f, planes, rows, cols)
+    torch.cuda.synchronize()
+    assert B.bdr_table_row_bytes(f, cols) * rows == table.numel() == sum(w.size for w in want)
+    assert np.array_equal(table.cpu().numpy(), _rows_together(f, planes, rows, cols))
+    g = torch.Generator(device="cuda").manual_seed(n)
+    idx = torch.randint(0, rows, (n,), generator=g, device="cuda", dtype=torch.int64)
+    idx[0], idx[-1] = rows - 1, 0
+    idx[1] = -3                                            # outside the table: a row of +0
+    y = B.bdr_table_gather_dequantize(f, table, rows, cols, idx, dtype=dtype)
+    torch.cuda.synchronize()
+    out_dtype = np.float32 if dtype == torch.float32 else np.uint16
+    full = O.dequantize(ofmt(f), *want, rows, cols, out_dtype=out_dtype)
+    ref = full[idx.cpu().numpy().clip(0, rows - 1)]
+    ref[1] = 0
+    assert_bits_equal(y, ref, "%s %s %s" % (name, dtype, shape))
+    # the same rows as the three-plane lookup gives
+    assert torch.equal(y, B.bdr_gather_dequantize(f, planes, rows, cols, idx, dtype=dtype))
+
+
+def test_table_image_full_size_sampled():
+    """The bench's table (2^20 rows of 128, MX6): sampled rows of the image and of the lookup."""
+    rows, cols, f = 1 << 20, 128, B.MX6
+    x = S.wide_range(rows, cols, device="cuda", seed=41, spread=4)
+    planes = B.bdr_quantize(f, x)
+    table = B.bdr_table_pack(f, planes, rows, cols)
+    idx = torch.randint(0, rows, (1 << 20,), device="cuda", dtype=torch.int64,
+                        generator=torch.Generator(device="cuda").manual_seed(9))
+    y = B.bdr_table_gather_dequantize(f, table, rows, cols, idx)
+    torch.cuda.synchronize()
+    rb = B.bdr_table_row_bytes(f, cols)
+    pick = np.concatenate([[0, 1, (1 << 20) - 1], np.random.default_rng(4).integers(0, 1 << 20, 400)])
+    ii = idx[pick].cpu().numpy()
+    xs = np.ascontiguousarray(to_np(x[torch.from_numpy(ii).cuda()]))
+    want = O.quantize(ofmt(f), xs)
+    got = table.view(rows, rb)[torch.from_numpy(ii).cuda()].cpu().numpy()
+    exp = np.concatenate([want[0].reshape(len(ii), -1), want[1].reshape(len(ii), -1),
+                          want[2].reshape(len(ii), -1)], axis=1)
+    assert np.array_equal(got, exp)
+    assert_bits_equal(y[torch.from_numpy(pick).cuda()], O.dequantize(ofmt(f), *want, len(ii), cols), "sampled lookups")
+
