@@ -320,15 +320,27 @@ int col_dispatch(int mode, const bdr_format &f, const T *x, T *y, uint8_t *codes
 // microexponent stream of a column gets (128 / k2) d2 bits per tile; where that is not a
 // whole number of bytes the workgroup walks rt = 2, 4 or 8 tiles down the column and writes
 // the stream once at the end.  Dequantize and the fused round trip use the same walk.
+// smallest number of tiles (1, 2, 4, 8) down a column whose microexponent bits fill whole bytes
+__host__ __device__ constexpr int tiles_for_whole_bytes(const GenFmt &f)
+{
+    for (int rt = 1; rt < 8; rt *= 2)
+        if (rt * (kTR / f.k2) * f.d2 % 8 == 0) return rt;
+    return 8;
+}
+
 constexpr int kGenCodesMax = 16 * 9 + 4;  // bytes per tile column: 128 codes of up to 9 bits (+ read-ahead)
 constexpr int kGenSexpMax = 16;           // 128 / k1 with k1 >= 8
 constexpr int kGenMexpMax = 48 + 4;       // (128 / k2) d2 / 8 with k2 = 1, d2 = 3 (taller bands have larger k2) + read-ahead
 
-template <typename T, int MODE>
+// SPEC >= 0: the tuple is entry SPEC of the table of formats the general kernels are compiled for
+// (hot_format), so the walks unroll and the shifts are immediates; SPEC < 0: tuple at run time.
+template <typename T, int MODE, int SPEC = -1>
 __global__ __launch_bounds__(kColThreads) void generic_col_tiled_kernel(
-    GenFmt f, int rt, const T *x, T *y, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
+    GenFmt f_arg, int rt_arg, const T *x, T *y, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
     uint8_t *__restrict__ mexp, int64_t rows, int64_t ld)
 {
+    const GenFmt f = SPEC >= 0 ? hot_format(SPEC >= 0 ? SPEC : 0) : f_arg;
+    const int rt = SPEC >= 0 ? tiles_for_whole_bytes(hot_format(SPEC >= 0 ? SPEC : 0)) : rt_arg;
     constexpr int kTC = TileGeom<T>::kTC;
     __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
     __shared__ uint32_t s_codes[MODE == 2 ? 1 : kTC * kGenCodesMax / 4];
@@ -476,12 +488,38 @@ int generic_tiled_rt(const bdr_format &f, int64_t rows, int64_t cols, int tc)
     return 0;
 }
 
+// Compiled-in tuples: launch the kernel of table entry `spec` (rt must be what the kernel
+// derives for itself: tiles_for_whole_bytes of the entry).
+template <typename T, int MODE, int SP = 0>
+void launch_generic_tiled_hot(int spec, dim3 grid, hipStream_t s, const GenFmt &g, int rt, const T *x, T *y,
+                              uint8_t *codes, uint8_t *sexp, uint8_t *mexp, int64_t rows, int64_t ld)
+{
+    if constexpr (SP < kHotCount) {
+        if (spec != SP)
+            return launch_generic_tiled_hot<T, MODE, SP + 1>(spec, grid, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+        hipLaunchKernelGGL((generic_col_tiled_kernel<T, MODE, SP>), grid, dim3(kColThreads), 0, s, g, rt, x, y,
+                           codes, sexp, mexp, rows, ld);
+    }
+}
+
 template <typename T>
 int generic_tiled(int mode, const bdr_format &f, int rt, const T *x, T *y, uint8_t *codes, uint8_t *sexp,
                   uint8_t *mexp, int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
 {
     const GenFmt g{f.k1, f.k2, f.d2, f.m, f.rounding};
     const dim3 grid((unsigned)(rows / ((int64_t)rt * kTR)), (unsigned)(cols / TileGeom<T>::kTC)), block(kColThreads);
+    bdr_format fr = f;
+    if (mode == 1) fr.rounding = BDR_RNE;  // reading an image does not depend on how it was rounded
+    const int spec = hot_index(fr);
+    if (spec >= 0 && rt == tiles_for_whole_bytes(hot_format(spec))) {
+        if (mode == 0)
+            launch_generic_tiled_hot<T, 0>(spec, grid, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+        else if (mode == 1)
+            launch_generic_tiled_hot<T, 1>(spec, grid, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+        else
+            launch_generic_tiled_hot<T, 2>(spec, grid, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
+        return launch_status();
+    }
     if (mode == 0)
         hipLaunchKernelGGL((generic_col_tiled_kernel<T, 0>), grid, block, 0, s, g, rt, x, y, codes, sexp, mexp, rows, ld);
     else if (mode == 1)

@@ -329,4 +329,31 @@ __device__ __forceinline__ float gen_round(float ax, int sh, float top, int roun
     return t;
 }
 
+// Formats the general kernels are also compiled for with the tuple as a compile-time
+// constant (SPEC = index into this table; SPEC < 0 = tuple at run time): the formats of the
+// design-space sweep of Sec. IV around Table II -- k1 8 .. 64, k2 1, 2, 4 or k1, d2 0 or 1,
+// m 2 or 4, nearest-even.  d2 = 0 is listed once per (k1, m) with k2 = k1 (k2 plays no part
+// then); Table II's own members have kernels of their own.  With the tuple known, every
+// loop over group sizes unrolls and every shift is an immediate, which is what the
+// run-time-format kernels spend their time on.
+constexpr int kHotK1[4] = {8, 16, 32, 64};
+constexpr int kHotM[2] = {2, 4};
+constexpr int kHotCount = 4 * 2 * 5;  // per (k1, m): d2 = 0, then d2 = 1 with k2 = 1, 2, 4, k1
+__host__ __device__ constexpr GenFmt hot_format(int spec)
+{
+    const int k1 = kHotK1[spec / 10], m = kHotM[(spec / 5) % 2], v = spec % 5;
+    return GenFmt{k1, v == 0 || v == 4 ? k1 : 1 << (v - 1), v == 0 ? 0 : 1, m, BDR_RNE};
+}
+// index of a format in the table, or -1
+static inline int hot_index(const bdr_format &f)
+{
+    for (int sp = 0; sp < kHotCount; ++sp) {
+        const GenFmt h = hot_format(sp);
+        if (f.k1 == h.k1 && f.m == h.m && f.d2 == h.d2 && f.rounding == h.rounding &&
+            (f.d2 == 0 || f.k2 == h.k2))
+            return sp;
+    }
+    return -1;
+}
+
 }  // namespace bdr

@@ -76,6 +76,27 @@ def test_other_formats_on_whole_tiles(kw, shape):
     _check_col(f, x, repr(f))
 
 
+@pytest.mark.parametrize("m", [2, 4])
+@pytest.mark.parametrize("d2", [0, 1])
+@pytest.mark.parametrize("k2", [1, 2, 4, 0])
+@pytest.mark.parametrize("k1", [8, 16, 32, 64])
+def test_design_space_sweep_formats_column_wise(k1, k2, d2, m):
+    # the 64 formats of the design-space sweep (Sec. IV) along columns: on whole tiles the tiled
+    # kernel compiled for the tuple (FP32 and BF16; one, two or four tiles per workgroup
+    # depending on how many microexponent bits a tile column has), with special values in
+    # some columns; the same data rounded another way goes through the run-time-tuple kernel
+    f = B.fmt(k1, k1 if k2 == 0 else k2, d2, m)
+    x = S.wide_range(1024, 128, device="cuda", seed=k1 + 3 * m + d2, spread=5)
+    x[0, 0], x[1, 0], x[17, 0] = float("inf"), float("nan"), -float("inf")
+    x[:, 1] = 0.0
+    x[5, 1] = -0.0
+    x[:64, 2] = 2.0 ** -140
+    x[:, 3] = 1.9999999
+    _check_col(f, x, "%r fp32" % f)
+    _check_col(f, x.to(torch.bfloat16), "%r bf16" % f)
+    _check_col(B.fmt(k1, k1 if k2 == 0 else k2, d2, m, rounding=B.RTZ), x[:512], "%r truncating" % f)
+
+
 @pytest.mark.parametrize("kw", [GEN_TILED[0], GEN_TILED[2], GEN_TILED[4], GEN_TILED[6], GEN_TILED[11]],
                          ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
 def test_other_formats_on_whole_tiles_bf16(kw):
