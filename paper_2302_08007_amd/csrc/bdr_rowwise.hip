@@ -147,11 +147,14 @@ constexpr int kDeqThreads = 256;  // workgroup size of the dequantize kernel
 // Groups per lane.  Measured in the loop of the three formats at 1 GiB FP32 (workgroup size x
 // groups per lane -> MX9 / MX6 / MX4 in microseconds): 128 x 1: 225 / 233 / 245, 128 x 2: 235 /
 // 219 / 221, 256 x 1: 213 / 220 / 229, 256 x 2: 236 / 213 / 214, 512 x 1: 214 / 225 / 223,
-// 256 x 4: 239 / 234 / 239.  A store stream is fastest from many small workgroups with few
-// stores per lane (a pure-write kernel: 158 us per GiB with one 16-byte store per lane and
-// 4 KiB per workgroup, 183 with two and 8 KiB, 187 with four and 16 KiB), but the 3- and
-// 5-byte code loads of MX4 and MX6 want two groups per lane in flight; MX9 (8-byte loads)
-// does not.  (A variant with four elements and one 16-byte store per lane, which needs no
+// 256 x 4: 239 / 234 / 239, 64 x 1: 233 / 260 / 259, 64 x 2: 240 / 240 / 237, 64 x 4: 246 / 249 /
+// 255, 128 x 4: 236 / 237 / 239, 512 x 2: 231 / 217 / 221, 1024 x 1: 225 / 250 / 230.  A pure
+// store stream is fastest from workgroups that write 4 KiB each, however many stores a lane
+// makes (per GiB: 160 us from 256 threads x one 16-byte store, 164 from 128 x two, 169 from
+// 64 x four; 8 KiB: 167 from 512 x one, 183 from 256 x two; 16 KiB: 188; 2 KiB: 180 - 187;
+// 1 KiB: 224), but a dequantize is not a pure store stream: its 4 KiB shapes (128 x 1, 64 x
+// 2) lose more on the loads than they gain, and the 3- and 5-byte code loads of MX4 and MX6
+// want two groups per lane in flight where MX9 (8-byte loads) does not.  (A variant with four elements and one 16-byte store per lane, which needs no
 // staging at all, took 253 / 243 / 252: too few bytes of codes in flight per wave.  BF16
 // rows, 8192 x 12288: two groups per lane 55 / 43 / 39, one 62 / 44 / 42.)
 template <int MB, typename T>
