@@ -743,31 +743,32 @@ static inline bool mx_fast_ok(const bdr_format &f, int64_t rows, int64_t cols, i
 // Launch the quantize kernel compiled for table entry `spec` (FP32 rows with pitch = row
 // length, whole quads of lanes).  The fused round trip has no such kernels: it is bound by
 // its 2 x 4 bytes per element with the tuple at run time already.
-template <int SP = 0>
-static void launch_hot(int spec, dim3 grid, hipStream_t s, const float *x, uint8_t *codes,
+template <typename T, int SP = 0>
+static void launch_hot(int spec, dim3 grid, hipStream_t s, const T *x, uint8_t *codes,
                        uint8_t *sexp, uint8_t *mexp, int64_t cols, int64_t ng)
 {
     if constexpr (SP < kHotCount) {
-        if (spec != SP) return launch_hot<SP + 1>(spec, grid, s, x, codes, sexp, mexp, cols, ng);
-        hipLaunchKernelGGL((generic_quantize_kernel<float, 0, false, true, SP>), grid, dim3(kThreads), 0, s,
-                           hot_format(SP), x, (float *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng, cols);
+        if (spec != SP) return launch_hot<T, SP + 1>(spec, grid, s, x, codes, sexp, mexp, cols, ng);
+        // FP32 rows move as contiguous wave rows through LDS; a BF16 lane's 8 elements are one 16-byte load
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, sizeof(T) == 4, SP>), grid, dim3(kThreads), 0, s,
+                           hot_format(SP), x, (T *)nullptr, codes, sexp, mexp, cols, cols, (int64_t)1, ng, cols);
     }
 }
 
 // Dequantize kernel for table entry `spec`: the Table II kernel with the tuple's block sizes
-// (FP32, pitch = row length, whole quads of lanes).  Reading an image does not depend on the
+// (pitch = row length, whole quads of lanes).  Reading an image does not depend on the
 // rounding rule, so the table's nearest-even entries serve every rounding.
-template <int SP = 0>
+template <typename T, int SP = 0>
 static void launch_hot_dequantize(int spec, hipStream_t s, const uint8_t *codes,
-                                  const uint8_t *sexp, const uint8_t *mexp, float *y, int64_t ng)
+                                  const uint8_t *sexp, const uint8_t *mexp, T *y, int64_t ng)
 {
     if constexpr (SP < kHotCount) {
-        if (spec != SP) return launch_hot_dequantize<SP + 1>(spec, s, codes, sexp, mexp, y, ng);
+        if (spec != SP) return launch_hot_dequantize<T, SP + 1>(spec, s, codes, sexp, mexp, y, ng);
         constexpr GenFmt f = hot_format(SP);
         constexpr int lk1 = f.k1 == 8 ? 3 : f.k1 == 16 ? 4 : f.k1 == 32 ? 5 : 6;
         constexpr int lk2 = f.k2 == 1 ? 0 : f.k2 == 2 ? 1 : f.k2 == 4 ? 2 : lk1;
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<f.m, float, false, false, lk1, lk2, f.d2>),
-                           (deq_grid<f.m, float>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<f.m, T, false, false, lk1, lk2, f.d2>),
+                           (deq_grid<f.m, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, GatherArgs{});
     }
 }
 
@@ -798,12 +799,13 @@ static int quantize_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t
             hipLaunchKernelGGL((mx_quantize_row_kernel<2, T>), qgrid, qblock, 0, s, x, codes, sexp, mexp, ng);
     } else {
         bool done = false;
+        const int spec = ld == cols && ng % 4 == 0 ? hot_index(f) : -1;
+        if (spec >= 0) {
+            launch_hot<T>(spec, grid, s, x, codes, sexp, mexp, cols, ng);
+            done = true;
+        }
         if constexpr (sizeof(T) == 4) {
-            const int spec = ld == cols && ng % 4 == 0 ? hot_index(f) : -1;
-            if (spec >= 0) {
-                launch_hot(spec, grid, s, x, codes, sexp, mexp, cols, ng);
-                done = true;
-            } else if (ld == cols) {
+            if (!done && ld == cols) {
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 0, false, true>), grid, block, 0, s, gen_of(f),
                                    x, (T *)nullptr, codes, sexp, mexp, cols, ld, (int64_t)1, ng, cols);
                 done = true;
@@ -846,14 +848,15 @@ static int dequantize_row_t(const bdr_format &f, const uint8_t *codes, const uin
     } else {
         const int64_t mexp_bytes = (rows * cols / f.k2 * f.d2 + 7) / 8;
         bool done = false;
+        bdr_format fr = f;
+        fr.rounding = BDR_RNE;
+        const int spec = ld == cols && ng % 4 == 0 ? hot_index(fr) : -1;
+        if (spec >= 0) {
+            launch_hot_dequantize<T>(spec, s, codes, sexp, mexp, y, ng);
+            done = true;
+        }
         if constexpr (sizeof(T) == 4) {
-            bdr_format fr = f;
-            fr.rounding = BDR_RNE;
-            const int spec = ld == cols && ng % 4 == 0 ? hot_index(fr) : -1;
-            if (spec >= 0) {
-                launch_hot_dequantize(spec, s, codes, sexp, mexp, y, ng);
-                done = true;
-            } else if (ld == cols) {
+            if (!done && ld == cols) {
                 hipLaunchKernelGGL((generic_dequantize_kernel<T, false, true>), grid, block, 0, s, gen_of(f),
                                    codes, sexp, mexp, mexp_bytes, y, cols, ld, (int64_t)1, ng, cols);
                 done = true;

@@ -107,6 +107,7 @@ def test_design_space_sweep_formats(k1, k2, d2, m):
     for shape in ((5, 1088), (1, 64), (40, 64)):
         x = S.wide_range(*shape, device="cuda", seed=k1 + shape[1], spread=4)
         _roundtrip_check(f, x, "%r %s" % (f, shape))
+        _roundtrip_check(f, x.to(torch.bfloat16), "%r %s bf16" % (f, shape))   # BF16 rows: compiled for the tuple too
     big = S.wide_range(6, 1024, device="cuda", seed=k1 + 1, spread=4)
     sub = big[:, 128:128 + 704]
     want = O.quantize(ofmt(f), to_np(sub))
