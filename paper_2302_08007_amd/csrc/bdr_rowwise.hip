@@ -772,6 +772,17 @@ static void launch_hot_dequantize(int spec, hipStream_t s, const uint8_t *codes,
     }
 }
 
+template <typename T, int SP = 0>
+static void launch_hot_fused(int spec, dim3 grid, hipStream_t s, const T *x, T *y, int64_t cols, int64_t ng)
+{
+    if constexpr (SP < kHotCount) {
+        if (spec != SP) return launch_hot_fused<T, SP + 1>(spec, grid, s, x, y, cols, ng);
+        hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, false, SP>), grid, dim3(kThreads), 0, s,
+                           hot_format(SP), x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,
+                           cols, (int64_t)1, ng, cols);
+    }
+}
+
 // Rows the flat kernels cannot take: a short last block (or, for k1 < 8, a length that is not
 // a multiple of 8).  They go through the element-at-a-time view.
 static inline bool ragged(const bdr_format &f, int64_t n) { return n % (f.k1 > 8 ? f.k1 : 8) != 0; }
@@ -1022,6 +1033,14 @@ static int qdq_row_t(const bdr_format &f, const T *x, T *y, int64_t rows, int64_
                 hipLaunchKernelGGL((generic_quantize_kernel<T, 1, false, true>), grid, block, 0, s, gen_of(f),
                                    x, y, (uint8_t *)nullptr, (uint8_t *)nullptr, (uint8_t *)nullptr, cols,
                                    ld, (int64_t)1, ng, cols);
+                done = true;
+            }
+        }
+        if constexpr (sizeof(T) == 2) {
+            // BF16 rows carry twice the elements per byte, and there the compiled-in tuple does pay
+            const int spec = ld == cols ? hot_index(f) : -1;
+            if (spec >= 0) {
+                launch_hot_fused<T>(spec, grid, s, x, y, cols, ng);
                 done = true;
             }
         }
