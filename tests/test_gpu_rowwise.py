@@ -261,6 +261,58 @@ def test_activation_config_full_size_sampled_rows():
         del planes, y, y2, p2
 
 
+@pytest.mark.parametrize("kw", [dict(k1=32, k2=2, d2=1, m=4), dict(k1=64, k2=64, d2=1, m=2),
+                                dict(k1=8, k2=1, d2=1, m=4), dict(k1=16, k2=16, d2=0, m=4)],
+                         ids=lambda kw: "-".join("%s%d" % kv for kv in kw.items()))
+def test_design_space_formats_on_the_activation_tensor_sampled_rows(kw):
+    # BF16 8192 x 12288 through the kernels compiled for the tuple (quantize, dequantize, fused),
+    # at full size: sampled 64-row bands against the oracle, the rest through identities
+    f = B.fmt(**kw)
+    x = S.activation(device="cuda")
+    rows, cols = x.shape
+    rng = np.random.default_rng(5)
+    bands = sorted(set([0, rows - 64] + [int(v) * 64 for v in rng.integers(0, rows // 64, 3)]))
+    planes = B.bdr_quantize(f, x)
+    y = B.bdr_dequantize(f, planes, rows, cols, dtype=torch.bfloat16)
+    y2 = B.bdr_quantize_dequantize(f, x)
+    torch.cuda.synchronize()
+    sizes = B.bdr_packed_sizes(f, rows, cols)
+    per_row = [n // rows for n in sizes]
+    for r0 in bands:
+        want = O.quantize(ofmt(f), to_np(x[r0:r0 + 64]))
+        got = [p[r0 * n:(r0 + 64) * n] for p, n in zip(planes, per_row)]
+        assert_planes_equal(got, want, "%r rows %d.." % (f, r0))
+        ywant = O.dequantize(ofmt(f), *want, 64, cols, out_dtype=np.uint16)
+        assert_bits_equal(y[r0:r0 + 64], ywant, "%r dequantize rows %d.." % (f, r0))
+        assert_bits_equal(y2[r0:r0 + 64], ywant, "%r fused rows %d.." % (f, r0))
+    assert torch.equal(y2.view(torch.int16), y.view(torch.int16))
+    p2 = B.bdr_quantize(f, y)
+    assert all(torch.equal(a, b) for a, b in zip(planes, p2))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_rows_with_a_short_last_block_at_a_large_size(dtype):
+    # 4099 x 12295: neither axis a multiple of anything; sampled rows against the oracle
+    rows, cols = 4099, 12295
+    x = S.wide_range(rows, cols, device="cuda", seed=91, spread=5, dtype=dtype)
+    pick = np.array([0, 1, 63, 64, 2048, 4097, 4098])
+    out_dtype = np.float32 if dtype == torch.float32 else np.uint16
+    for f in (B.MX9, B.fmt(32, 4, 1, 4), B.fmt(128, 2, 2, 3, rounding=B.RNA)):
+        planes = B.bdr_quantize(f, x)
+        y = B.bdr_dequantize(f, planes, rows, cols, dtype=dtype)
+        y2 = B.bdr_quantize_dequantize(f, x)
+        torch.cuda.synchronize()
+        per_row = [n // rows for n in B.bdr_packed_sizes(f, rows, cols)]
+        for r in pick:
+            want = O.quantize(ofmt(f), np.ascontiguousarray(to_np(x[r:r + 1])))
+            got = [p[r * n:(r + 1) * n] for p, n in zip(planes, per_row)]
+            assert_planes_equal(got, want, "%r row %d" % (f, r))
+            ywant = O.dequantize(ofmt(f), *want, 1, cols, out_dtype=out_dtype)
+            assert_bits_equal(y[r:r + 1], ywant, "%r dequantize row %d" % (f, r))
+        assert torch.equal(y.view(torch.int32 if dtype == torch.float32 else torch.int16),
+                           y2.view(torch.int32 if dtype == torch.float32 else torch.int16))
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_more_than_four_gibi_elements(dtype):
     # 2^32 + 2^18 elements: every element index, byte offset and plane offset passes 2^32.
