@@ -22,12 +22,15 @@
 //     accumulator.  Groups with a larger beta evaluate every class directly
 //     (scale, clamp, round, subtract, unscale, square-accumulate).
 //
-// Range: squares of FP32 numbers underflow for small tensors, so the kernel works
-// on x * 2^s with s chosen from the tensor's largest exponent (a tiny pre-pass)
-// and undoes the scale in FP64 at the end.  Scaling by a power of two commutes
-// with the quantizer (end of Sec. IX), so nothing changes except for values more
-// than 126 binades below the tensor maximum, whose contribution is below 2^-250
-// of either sum.
+// Range: squares of FP32 numbers underflow for small tensors and overflow for large
+// ones, so a workgroup works on x * 2^s with s chosen from the largest exponent it
+// has met so far (found in the registers of each iteration's loads: no pass over the
+// tensor beforehand) and undoes the scale, exactly, whenever it folds its FP32
+// partials into FP64; when a larger exponent turns up, the partials are folded at the
+// old scale first.  Scaling by a power of two commutes with the quantizer (end of
+// Sec. IX), so nothing changes except for values more than 126 binades below the
+// largest one the workgroup has seen, whose contribution is below 2^-250 of either
+// sum.
 //
 // Sums: every lane keeps one FP32 partial per quantizer in LDS; after at most
 // 256 elements per lane the partials are folded, in a fixed order, into FP64
@@ -51,8 +54,7 @@ constexpr int kMaxGroups = kChunk;
 constexpr int kMaxClasses = kChunk;
 constexpr int kMR = 2;       // (m, rounding) pairs evaluated together in a group that selects
 constexpr int kMRd = 8;      // ... and in a group that evaluates every class directly
-constexpr int kAbsBlocks = 512;               // workgroups of the maximum pass
-constexpr size_t kHeaderBytes = 4096;         // per-workgroup maxima (kAbsBlocks words), rest unused
+constexpr size_t kHeaderBytes = 0;            // the workspace holds the FP64 partials and nothing else
 constexpr int kFoldPasses = (kChunk + 1 + 31) / 32;  // quantizers + signal, 32 per pass
 constexpr int kFoldEvery = 256 / (8 * kG);           // iterations between folds: 256 elements per lane
 
@@ -87,52 +89,6 @@ struct SweepPlan {
 struct FormatMap {
     uint16_t idx[kChunk];  // format -> quantizer
 };
-
-// Largest magnitude of the tensor, first pass: one value per workgroup (all
-// kAbsBlocks slots are written, zero when a workgroup had nothing to read).
-template <typename T>
-__global__ __launch_bounds__(256) void sweep_absmax_kernel(const T *__restrict__ x, int64_t cols,
-                                                           int64_t ld, int64_t n_groups,
-                                                           uint32_t *__restrict__ blockmax)
-{
-    __shared__ uint32_t s_m[4];
-    uint32_t m = 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < n_groups; g0 += 2 * stride) {
-        uint32_t xb[2][8];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t g = g0 + u * stride;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) xb[u][i] = 0;
-            if (g < n_groups) {
-                const int64_t t0 = 8 * g;
-                const int64_t r = ld == cols ? 0 : t0 / cols;
-                load8(x + r * ld + (t0 - r * cols), xb[u]);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) m = umax(m, xb[u][i] & kAbsMask);
-    }
-    for (int w = 32; w > 0; w >>= 1) m = umax(m, (uint32_t)__shfl_xor((int)m, w));
-    if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) blockmax[blockIdx.x] = umax(umax(s_m[0], s_m[1]), umax(s_m[2], s_m[3]));
-}
-
-// Second pass, run by every wave that needs it: biased exponent of the largest
-// magnitude, held inside [1, 254].
-__device__ __forceinline__ int tensor_exponent(const uint32_t *__restrict__ blockmax)
-{
-    const int lane = threadIdx.x & 63;
-    uint32_t m = 0;
-#pragma unroll
-    for (int i = 0; i < kAbsBlocks / 64; ++i) m = umax(m, blockmax[i * 64 + lane]);
-    for (int w = 32; w > 0; w >>= 1) m = umax(m, (uint32_t)__shfl_xor((int)m, w));
-    return (int)(umin(umax(m, kMagLo), kMagHi) >> 23);
-}
 
 // Maxima over aligned groups for one run of 8 elements of a lane:
 //   p1, p2   magnitudes (held to the normal range) of the pairs and runs of 4
@@ -299,19 +255,26 @@ __device__ __forceinline__ float direct(const float (&yp)[kG][8], const int (&sh
 template <typename T, bool ALL_RNE, bool WIDE>
 __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
     SweepPlan plan, const T *__restrict__ x, int64_t cols, int64_t ld, int64_t n_groups,
-    const uint32_t *__restrict__ blockmax, double *__restrict__ partials)
+    double *__restrict__ partials)
 {
     extern __shared__ float s_lane[];  // [n_quant + 1][kSweepThreads]: one partial per lane
+    __shared__ int s_wsref[kSweepThreads / 64];
     const int nq = plan.n_quant;
     const int tid = threadIdx.x, lane = tid & 63;
     for (int q = 0; q <= nq; ++q) s_lane[q * kSweepThreads + tid] = 0.f;
+    if (tid < kSweepThreads / 64) s_wsref[tid] = 0;
+    __syncthreads();
     auto add_to = [&](int q, float v) { s_lane[q * kSweepThreads + tid] += v; };
 
-    // Work on x * 2^sref so that the tensor maximum lands in [1, 2).
-    const int eref = tensor_exponent(blockmax);
-    const int sref = 127 - eref;
-    // the lowest exponent an element can carry (code 1 before scaling)
-    const uint32_t mag_lo = (uint32_t)(1 + (sref > 0 ? sref : 0)) << 23;
+    // The FP32 work of a wave is done on x * 2^sref, sref = 127 - eref, where eref is the
+    // exponent of the largest magnitude the wave has met so far (so that it lands in [1, 2) and
+    // squares neither overflow nor lose more than they would at the tensor's own scale; scaling
+    // by a power of two commutes with the quantizer, end of Sec. IX).  When an iteration brings
+    // a larger one, the wave moves its lanes' partials to the new scale (a power of two:
+    // exact).  The fold takes every wave's partials back to the tensor's own scale, so the FP64
+    // sums are unscaled.  No pass over the tensor is needed beforehand, and no barrier here.
+    int eref = 0, sref = 0;
+    uint32_t mag_lo = 0;  // the lowest exponent an element can carry (code 1 before scaling)
 
     // Lane partials -> FP64 sums of this workgroup, 32 quantizers at a time: 8 threads
     // share a quantizer, each adds up 32 lanes (start rotated so that a wave touches
@@ -336,6 +299,7 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
                         src[(i + rot) & 31] = 0.f;
                     }
                 }
+                v = __builtin_ldexp(v, -2 * s_wsref[part >> 1]);  // the 32 lanes are half of one wave; exact
                 v += __shfl_xor(v, 1);
                 v += __shfl_xor(v, 2);
                 v += __shfl_xor(v, 4);
@@ -349,6 +313,34 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
     const int64_t per_iter = (int64_t)gridDim.x * kSweepThreads * kG;
     for (int64_t base = (int64_t)blockIdx.x * kSweepThreads * kG; base < n_groups;
          base += per_iter) {
+        uint32_t xr[kG][8];
+        uint32_t mx = 0;
+#pragma unroll
+        for (int j = 0; j < kG; ++j) {
+            const int64_t g = base + (int64_t)(tid >> 6) * (64 * kG) + j * 64 + lane;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xr[j][i] = 0;
+            if (g < n_groups) {
+                const int64_t t0 = 8 * g;
+                const int64_t r = ld == cols ? 0 : t0 / cols;
+                load8(x + r * ld + (t0 - r * cols), xr[j]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mx = umax(mx, xr[j][i] & kAbsMask);
+        }
+        // largest magnitude of the wave's iteration (uniform across the wave: scalar registers)
+        for (int w = 32; w > 0; w >>= 1) mx = umax(mx, (uint32_t)__shfl_xor((int)mx, w));
+        const int e_it = __builtin_amdgcn_readfirstlane((int)(umin(umax(mx, kMagLo), kMagHi) >> 23));
+        if (e_it > eref) {
+            if (eref != 0)  // partials taken at the old scale move to the new one
+                for (int q = 0; q <= nq; ++q)
+                    s_lane[q * kSweepThreads + tid] =
+                        __builtin_ldexpf(s_lane[q * kSweepThreads + tid], 2 * (eref - e_it));
+            eref = e_it;
+            sref = 127 - eref;
+            mag_lo = (uint32_t)(1 + (sref > 0 ? sref : 0)) << 23;
+            if (lane == 0) s_wsref[tid >> 6] = sref;  // read by the fold, after its barrier
+        }
         if (since_fold == kFoldEvery) {  // same trip count for every lane of the workgroup
             fold();
             since_fold = 0;
@@ -359,13 +351,7 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
         float sig = 0.f;
 #pragma unroll
         for (int j = 0; j < kG; ++j) {
-            const int64_t g = base + (int64_t)(tid >> 6) * (64 * kG) + j * 64 + lane;
-            uint32_t xb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (g < n_groups) {
-                const int64_t t0 = 8 * g;
-                const int64_t r = ld == cols ? 0 : t0 / cols;
-                load8(x + r * ld + (t0 - r * cols), xb);
-            }
+            const uint32_t(&xb)[8] = xr[j];
             uint32_t ab[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -503,8 +489,8 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
 // fixed tree) and writes noise power and QSNR (Sec. III).
 __global__ __launch_bounds__(256) void sweep_finalize_kernel(
     FormatMap map, int32_t n_fmts, int32_t n_quant, int32_t n_blocks,
-    const uint32_t *__restrict__ blockmax, const double *__restrict__ partials,
-    double *__restrict__ qsnr_db, double *__restrict__ sums, double *sig_out)
+    const double *__restrict__ partials, double *__restrict__ qsnr_db, double *__restrict__ sums,
+    double *sig_out)
 {
     __shared__ double s_e[256], s_s[256];
     const int f = blockIdx.x;
@@ -524,15 +510,12 @@ __global__ __launch_bounds__(256) void sweep_finalize_kernel(
         }
         __syncthreads();
     }
-    // undo the pre-scale: sums were taken on x * 2^(127 - eref)
-    const int eref = tensor_exponent(blockmax);
     if (threadIdx.x == 0) {
-        const double unscale = __builtin_ldexp(1.0, -2 * (127 - eref));
-        const double sig = s_s[0] * unscale;
+        const double sig = s_s[0];
         if (f == n_fmts) {
             *sig_out = sig;
         } else {
-            const double err = s_e[0] * unscale;
+            const double err = s_e[0];
             sums[f] = err;
             qsnr_db[f] = err > 0.0 ? 10.0 * log10(sig / err) : __builtin_inf();
         }
@@ -640,8 +623,7 @@ void make_plan(const bdr_format *fmts, int n_fmts, SweepPlan &plan, FormatMap &m
 // dry: only make sure the launch is possible (the grant), launch nothing.
 template <typename T, bool ALL_RNE, bool WIDE>
 int launch_sweep_w(const SweepPlan &plan, bool dry, unsigned nb, const void *x, int64_t cols,
-                   int64_t ld, int64_t n_groups, const uint32_t *blockmax, double *partials,
-                   hipStream_t s)
+                   int64_t ld, int64_t n_groups, double *partials, hipStream_t s)
 {
     static signed char granted[kMaxDevices];
     const size_t lds = (size_t)(plan.n_quant + 1) * kSweepThreads * sizeof(float);
@@ -651,7 +633,7 @@ int launch_sweep_w(const SweepPlan &plan, bool dry, unsigned nb, const void *x, 
         return BDR_ERR_LAUNCH;
     if (dry) return BDR_OK;
     hipLaunchKernelGGL((sweep_kernel<T, ALL_RNE, WIDE>), dim3(nb), dim3(kSweepThreads), lds, s, plan,
-                       (const T *)x, cols, ld, n_groups, blockmax, partials);
+                       (const T *)x, cols, ld, n_groups, partials);
     return BDR_OK;
 }
 
@@ -661,13 +643,12 @@ int launch_sweep_w(const SweepPlan &plan, bool dry, unsigned nb, const void *x, 
 // better without the long one next to it).
 template <typename T, bool ALL_RNE>
 int launch_sweep(const SweepPlan &plan, bool dry, unsigned nb, const void *x, int64_t cols,
-                 int64_t ld, int64_t n_groups, const uint32_t *blockmax, double *partials,
-                 hipStream_t s)
+                 int64_t ld, int64_t n_groups, double *partials, hipStream_t s)
 {
     bool wide = false;
     for (int g = 0; g < plan.n_group; ++g) wide = wide || plan.grp[g].n_mr > kMR;
-    return wide ? launch_sweep_w<T, ALL_RNE, true>(plan, dry, nb, x, cols, ld, n_groups, blockmax, partials, s)
-                : launch_sweep_w<T, ALL_RNE, false>(plan, dry, nb, x, cols, ld, n_groups, blockmax, partials, s);
+    return wide ? launch_sweep_w<T, ALL_RNE, true>(plan, dry, nb, x, cols, ld, n_groups, partials, s)
+                : launch_sweep_w<T, ALL_RNE, false>(plan, dry, nb, x, cols, ld, n_groups, partials, s);
 }
 
 }  // namespace
@@ -677,8 +658,6 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
                hipStream_t s)
 {
     static_assert(sizeof(SweepPlan) + 64 < 4096, "kernel arguments must stay under 4 KiB");
-    uint32_t *blockmax = reinterpret_cast<uint32_t *>(workspace);
-    static_assert(kAbsBlocks * sizeof(uint32_t) <= kHeaderBytes, "maxima area too small");
     double *partials = reinterpret_cast<double *>(static_cast<char *>(workspace) + kHeaderBytes);
     const int64_t n_groups = rows * cols / 8;
     // enough workgroups to fill the chip at two per compute unit, each taking several
@@ -705,10 +684,10 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
         for (int f = 0; f < nf; ++f) all_rne = all_rne && fmts[f0 + f].rounding == BDR_RNE;
         const SweepPlan &plan = plans[c];
         if (dtype == BDR_F32)
-            return all_rne ? launch_sweep<float, true>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
-                           : launch_sweep<float, false>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
-        return all_rne ? launch_sweep<uint16_t, true>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s)
-                       : launch_sweep<uint16_t, false>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, blockmax, partials, s);
+            return all_rne ? launch_sweep<float, true>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, partials, s)
+                           : launch_sweep<float, false>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, partials, s);
+        return all_rne ? launch_sweep<uint16_t, true>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, partials, s)
+                       : launch_sweep<uint16_t, false>(plan, dry, (unsigned)nb, x, cols, ld, n_groups, partials, s);
     };
     const int n_chunks = (n_fmts + kChunk - 1) / kChunk;
     for (int c = 0; c < n_chunks; ++c) {
@@ -720,19 +699,13 @@ int qsnr_sweep(const bdr_format *fmts, int32_t n_fmts, const void *x, int dtype,
         const int st = chunk_launch(c, true);
         if (st != BDR_OK) return st;
     }
-    if (dtype == BDR_F32)
-        hipLaunchKernelGGL(sweep_absmax_kernel<float>, dim3(kAbsBlocks), dim3(256), 0, s,
-                           (const float *)x, cols, ld, n_groups, blockmax);
-    else
-        hipLaunchKernelGGL(sweep_absmax_kernel<uint16_t>, dim3(kAbsBlocks), dim3(256), 0, s,
-                           (const uint16_t *)x, cols, ld, n_groups, blockmax);
     for (int c = 0; c < n_chunks; ++c) {
         const int32_t f0 = c * kChunk;
         const int nf = n_fmts - f0 < kChunk ? n_fmts - f0 : kChunk;
         const int st = chunk_launch(c, false);
         if (st != BDR_OK) return st;  // not reached: the first walk settled it
         hipLaunchKernelGGL(sweep_finalize_kernel, dim3((unsigned)(nf + 1)), dim3(256), 0, s, maps[c],
-                           nf, plans[c].n_quant, (int32_t)nb, blockmax, partials, qsnr_db + f0,
+                           nf, plans[c].n_quant, (int32_t)nb, partials, qsnr_db + f0,
                            sums + f0, sums + n_fmts);
     }
     return launch_status();
