@@ -114,6 +114,30 @@ def test_tensor_scale_does_not_matter(shift):
     assert np.allclose(q, q0.cpu().numpy(), rtol=1e-6)
 
 
+@pytest.mark.parametrize("order", ["rising", "falling", "mixed"])
+def test_magnitudes_that_change_along_the_tensor(order):
+    # The kernel scales by the largest exponent a wave has met so far and moves its partial sums
+    # when that grows: rows whose magnitudes rise (every iteration of a workgroup brings a larger
+    # one), fall, or jump about by up to 2^±40, enough rows that every workgroup iterates several
+    # times.  Sixteen of the sweep's formats and a few that evaluate their classes directly.
+    rows, cols = 24576, 256                         # 768 workgroups x 8 iterations of 4096 elements
+    g = torch.Generator(device="cuda").manual_seed(12)
+    x = torch.randn(rows, cols, generator=g, device="cuda")
+    ramp = torch.linspace(-40, 40, rows, device="cuda").round()
+    if order == "falling":
+        ramp = ramp.flip(0)
+    elif order == "mixed":
+        ramp = ramp[torch.randperm(rows, generator=g, device="cuda")]
+    x = torch.ldexp(x, ramp.to(torch.int32)[:, None])
+    fmts = sweep64()[1::4] + [B.fmt(16, 2, 2, 3), B.fmt(32, 1, 3, 5, rounding=B.RNA), B.fmt(128, 8, 2, 7, rounding=B.RTZ)]
+    check(fmts, x, order)
+    # and with the largest rows at the edge of FP32's range next to rows 200 binades below them
+    y = x.clone()
+    y[::7] = torch.ldexp(torch.randn(y[::7].shape, generator=g, device="cuda"), torch.tensor(120, device="cuda"))
+    y[3::7] = torch.ldexp(y[3::7], torch.tensor(-80, device="cuda"))
+    check([B.MX9, B.MX6, B.MX4, B.fmt(64, 4, 1, 4)], y, order + " extremes")
+
+
 def test_strided_ragged_and_exact():
     big = S.tiny(77, 1024, device="cuda", seed=4)
     check([B.MX6, B.fmt(64, 4, 1, 4)], big[:, 128:128 + 320], "strided")       # ld > cols
