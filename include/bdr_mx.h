@@ -35,6 +35,9 @@
  *   mexp  : sub-block u = r * (C / k2) + c / k2 holds bits [u d2, (u+1) d2): the
  *           shift tau of that sub-block.  Absent (may be NULL) when d2 = 0.
  * The value of an element is (-1)^sign * M * 2^(sexp - 127 - tau - (m - 1)).
+ * When the row length is not a multiple of k1, C above is the row length rounded up
+ * to the next multiple of k1: the last block of a row is stored whole, the elements
+ * it lacks as code 0 (see bdr_packed_sizes).
  * BDR_AXIS_COL means: exactly what BDR_AXIS_ROW gives on the transposed tensor
  * ([cols x rows]), plane indices included.
  */
