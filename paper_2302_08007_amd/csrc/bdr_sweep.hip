@@ -329,8 +329,16 @@ __global__ __launch_bounds__(kSweepThreads, 3) void sweep_kernel(
             for (int i = 0; i < 8; ++i) mx = umax(mx, xr[j][i] & kAbsMask);
         }
         // largest magnitude of the wave's iteration (uniform across the wave: scalar registers)
-        for (int w = 32; w > 0; w >>= 1) mx = umax(mx, (uint32_t)__shfl_xor((int)mx, w));
-        const int e_it = __builtin_amdgcn_readfirstlane((int)(umin(umax(mx, kMagLo), kMagHi) >> 23));
+        // (within rows of 16 lanes by DPP, the four rows by lane reads: no trip through LDS)
+        mx = umax(mx, dpp<kQuadXor1>(mx));
+        mx = umax(mx, dpp<kQuadXor2>(mx));
+        mx = umax(mx, dpp<kRowHalfMirror>(mx));
+        mx = umax(mx, dpp<kRowMirror>(mx));
+        const uint32_t wmx = umax(umax((uint32_t)__builtin_amdgcn_readlane((int)mx, 0),
+                                       (uint32_t)__builtin_amdgcn_readlane((int)mx, 16)),
+                                  umax((uint32_t)__builtin_amdgcn_readlane((int)mx, 32),
+                                       (uint32_t)__builtin_amdgcn_readlane((int)mx, 48)));
+        const int e_it = (int)(umin(umax(wmx, kMagLo), kMagHi) >> 23);
         if (e_it > eref) {
             if (eref != 0)  // partials taken at the old scale move to the new one
                 for (int q = 0; q <= nq; ++q)
