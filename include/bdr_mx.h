@@ -253,6 +253,17 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
             int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,
             size_t workspace_bytes, void *hip_stream);
 
+/* mx_gemm with the type of C chosen by the caller: c_dtype BDR_F32 is mx_gemm itself;
+ * with BDR_BF16 each FP32 sum is rounded once more, to nearest even, as it is stored
+ * (the tensors between tensor operations are BF16 in the paper's compute flow, Sec. V
+ * "Training": this is the cast the consumer of the product would otherwise make in a pass
+ * of its own).  C then needs the alignment of one element; everything else as for
+ * mx_gemm.  Any other c_dtype is BDR_ERR_DTYPE. */
+int mx_gemm_to(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
+               const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+               int64_t M, int64_t N, int64_t K, void *C, int c_dtype, int64_t ldc, void *workspace,
+               size_t workspace_bytes, void *hip_stream);
+
 /* Host only.  Bytes of device workspace mx_dot_pipeline needs: (M + N) * K BF16 values, each
  * operand rounded up to 256 bytes.  0 when a size is negative or above 2^20. */
 size_t mx_dot_pipeline_workspace_bytes(int64_t M, int64_t N, int64_t K);

@@ -24,7 +24,7 @@ EXPORTS = (
     "bdr_table_gather_dequantize", "bdr_tile_packing", "bdr_quantize_dequantize",
     "bdr_qsnr_sweep_workspace_bytes",
     "bdr_qsnr_sweep", "bdr_qsnr_sweep_static", "bdr_qsnr_sweep_static_scratch_bytes",
-    "mx_gemm_workspace_bytes", "mx_gemm", "mx_dot_pipeline_workspace_bytes", "mx_dot_pipeline",
+    "mx_gemm_workspace_bytes", "mx_gemm", "mx_gemm_to", "mx_dot_pipeline_workspace_bytes", "mx_dot_pipeline",
 )
 
 
@@ -84,6 +84,7 @@ def _load():
     L.mx_gemm_workspace_bytes.argtypes = [I64, I64, I64]
     L.mx_gemm_workspace_bytes.restype = SZ
     L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P, SZ, P]
+    L.mx_gemm_to.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I32, I64, P, SZ, P]
     L.mx_dot_pipeline_workspace_bytes.argtypes = [I64, I64, I64]
     L.mx_dot_pipeline_workspace_bytes.restype = SZ
     L.mx_dot_pipeline.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, I64, I32, P, I64, P, SZ, P]
@@ -290,25 +291,29 @@ def mx_gemm_workspace_bytes(M, N, K):
     return lib.mx_gemm_workspace_bytes(M, N, K)
 
 
-def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None):
+def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None, dtype=None):
     """C[M, N] = Ahat @ Bhat^T for two packed operands blocked along K.  `workspace`: a
     uint8 tensor of at least mx_gemm_workspace_bytes(M, N, K) bytes selects the two-pass
     form, None the single-kernel form (Table II formats only; other BF16-exact formats need
-    the workspace)."""
-    C = out if out is not None else torch.empty((M, N), dtype=torch.float32,
-                                                device=a_planes[0].device)
-    if not (C.is_cuda and C.dtype == torch.float32 and C.dim() == 2 and tuple(C.shape) == (M, N)
-            and C.stride(1) == 1):
-        raise ValueError("output must be an [M x N] float32 GPU tensor with unit column stride")
+    the workspace).  C is float32, or bfloat16 (the sums rounded once more as they are stored)
+    when `out` or `dtype` says so."""
+    dtype = out.dtype if out is not None else (dtype or torch.float32)
+    C = out if out is not None else torch.empty((M, N), dtype=dtype, device=a_planes[0].device)
+    if not (C.is_cuda and C.dtype in (torch.float32, torch.bfloat16) and C.dim() == 2
+            and tuple(C.shape) == (M, N) and C.stride(1) == 1):
+        raise ValueError("output must be an [M x N] float32 or bfloat16 GPU tensor with unit column stride")
     if K > 0:
         _check_planes(fa, a_planes, M, K)
         _check_planes(fb, b_planes, N, K)
     if workspace is not None:
         _check_buffer("workspace", workspace, torch.uint8, 0)
     ws, wsb = (_p(workspace), workspace.numel()) if workspace is not None else (None, 0)
-    _check(lib.mx_gemm(ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]),
-                       _p(a_planes[2]), _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]), M, N, K,
-                       _p(C), C.stride(0), ws, wsb, _stream()))
+    args = (ctypes.byref(fa), ctypes.byref(fb), _p(a_planes[0]), _p(a_planes[1]), _p(a_planes[2]),
+            _p(b_planes[0]), _p(b_planes[1]), _p(b_planes[2]), M, N, K, _p(C))
+    if C.dtype == torch.float32:
+        _check(lib.mx_gemm(*args, C.stride(0), ws, wsb, _stream()))
+    else:
+        _check(lib.mx_gemm_to(*args, _dtype_code(C), C.stride(0), ws, wsb, _stream()))
     return C
 
 

@@ -332,11 +332,13 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return gemm_ws_half(M, K) + gemm_ws_half(N, K);
 }
 
-int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
-            const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
-            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,
-            size_t workspace_bytes, void *hip_stream)
+int mx_gemm_to(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
+               const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+               int64_t M, int64_t N, int64_t K, void *C, int c_dtype, int64_t ldc, void *workspace,
+               size_t workspace_bytes, void *hip_stream)
 {
+    if (c_dtype != BDR_F32 && c_dtype != BDR_BF16) return BDR_ERR_DTYPE;
+    const int c_bf16 = c_dtype == BDR_BF16;
     int st = check_format(fa);
     if (st) return st;
     st = check_format(fb);
@@ -352,7 +354,7 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
     if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
     if (M == 0 || N == 0) return BDR_OK;
     if (!C) return BDR_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(C) % 4 != 0) return BDR_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(C) % elem_size(c_dtype) != 0) return BDR_ERR_ALIGN;
     if (K > 0) {
         st = check_planes(fa, a_codes, a_sexp, a_mexp);
         if (st) return st;
@@ -375,46 +377,55 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
             // size conditions keep both inside the operand's half of the workspace.
             const int64_t Kp = (K + 127) / 128 * 128;
             char *sa = wa + (size_t)M * (size_t)(Kp / 2), *sb = wb + (size_t)N * (size_t)(Kp / 2);
-            st = bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, true, s);
+            st = bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, c_bf16, true, s);
             if (st) return st;
             st = bdr::to_fp4(a_codes, a_sexp, a_mexp, M, K, Kp, wa, sa, s);
             if (st) return st;
             st = bdr::to_fp4(b_codes, b_sexp, b_mexp, N, K, Kp, wb, sb, s);
             if (st) return st;
-            return bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, false, s);
+            return bdr::gemm_fp4(wa, sa, wb, sb, M, N, Kp, C, ldc, c_bf16, false, s);
         }
         if (both_mx && fa->m <= 4 && fb->m <= 4) {
             // MX6 and MX4 elements are exact FP6 values under a per-block power of two:
             // block-scaled FP6 MFMAs, twice the rate of BF16.  One byte per element of workspace.
-            st = bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, true, s);
+            st = bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, c_bf16, true, s);
             if (st) return st;
             st = bdr::to_fp6(*fa, a_codes, a_sexp, a_mexp, M, K, wa, false, s);
             if (st) return st;
             st = bdr::to_fp6(*fb, b_codes, b_sexp, b_mexp, N, K, wb, true, s);
             if (st) return st;
-            return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, false, s);
+            return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, c_bf16, false, s);
         }
         if (both_mx) {
             // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact),
             // in the K-tiled layout of the ring kernel
-            st = bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, true, s);
+            st = bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, c_bf16, true, s);
             if (st) return st;
             st = bdr::to_bf16_tiled(*fa, a_codes, a_sexp, a_mexp, M, K, wa, s);
             if (st) return st;
             st = bdr::to_bf16_tiled(*fb, b_codes, b_sexp, b_mexp, N, K, wb, s);
             if (st) return st;
-            return bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, false, s);
+            return bdr::gemm_bf16_tiled(wa, wb, M, N, K, C, ldc, c_bf16, false, s);
         }
         // any other format that passed the check above: general dequantize to row-major BF16
-        st = bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, true, s);
+        st = bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, c_bf16, true, s);
         if (st) return st;
         st = bdr::dequantize_row(*fa, a_codes, a_sexp, a_mexp, M, K, wa, BDR_BF16, K, s);
         if (st) return st;
         st = bdr::dequantize_row(*fb, b_codes, b_sexp, b_mexp, N, K, wb, BDR_BF16, K, s);
         if (st) return st;
-        return bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, false, s);
+        return bdr::gemm_bf16(wa, wb, M, N, K, C, ldc, c_bf16, false, s);
     }
-    return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc, s);
+    return bdr::gemm(*fa, *fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, ldc, c_bf16, s);
+}
+
+int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, const void *a_sexp,
+            const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
+            int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, void *workspace,
+            size_t workspace_bytes, void *hip_stream)
+{
+    return mx_gemm_to(fa, fb, a_codes, a_sexp, a_mexp, b_codes, b_sexp, b_mexp, M, N, K, C, BDR_F32, ldc,
+                      workspace, workspace_bytes, hip_stream);
 }
 
 size_t mx_dot_pipeline_workspace_bytes(int64_t M, int64_t N, int64_t K)

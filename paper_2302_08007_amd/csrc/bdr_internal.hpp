@@ -91,21 +91,21 @@ int qsnr_sweep_static(const bdr_format *fmts, int32_t n_fmts, const void *x, int
 
 int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,
          const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
-         int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s);
+         int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16, hipStream_t s);
 // (`dry`: only request what the kernel needs, launch nothing; the same for the products below)
-int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
               bool dry, hipStream_t s);
 // Table II planes of a [rows x K] operand -> BF16 tiled along K ([K / 32][rows][32 elements]),
 // and the GEMM on two such images.
 int to_bf16_tiled(const bdr_format &f, const void *codes, const void *sexp, const void *mexp, int64_t rows,
                   int64_t K, void *out, hipStream_t s);
-int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
                     bool dry, hipStream_t s);
 // MX6 / MX4 planes of a [rows x K] operand (K % 64 == 0) -> one 16-byte FP6 chunk per block,
 // tiled along K ([K / 64][rows][4 chunks]), and the GEMM on two such images.
 int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void *mexp,
            int64_t rows, int64_t K, void *out, bool b_operand, hipStream_t s);
-int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
              bool dry, hipStream_t s);
 // The FP4 form of the two-pass product (MX4 x MX4): image writer, size of its scale image,
 // and the product on two such images (K_out % 128 == 0).
@@ -113,7 +113,7 @@ int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, 
            void *out, void *scales, hipStream_t s);
 size_t fp4_scale_bytes(int64_t rows, int64_t K_out);
 int gemm_fp4(const void *A, const void *SA, const void *B, const void *SB, int64_t M, int64_t N, int64_t K,
-             float *C, int64_t ldc, bool dry, hipStream_t s);
+             void *C, int64_t ldc, int c_bf16, bool dry, hipStream_t s);
 
 // The dot-product pipeline model (mx_dot_pipeline.hip); arguments validated by the caller.
 int dot_pipeline(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,

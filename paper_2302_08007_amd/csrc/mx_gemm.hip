@@ -147,10 +147,18 @@ __device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base
 // Write the TM x TN accumulator tiles of a wave.  32 x 32 accumulator: register r of lane l
 // is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32.  Tiles on the lower or right edge
 // of C may hang over it (M, N need not be multiples of the tile): those check every element.
+// C is FP32, or BF16 when c_bf16 is set: each sum is then rounded once more, to nearest even
+// (what a BF16 element-wise consumer of the product would do itself, Sec. V).
+__device__ __forceinline__ uint16_t bf16_rne(float v)
+{
+    const uint32_t u = as_u(v);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
 template <int TM, int TN>
-__device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], float *__restrict__ C,
-                                            int64_t ldc, int M, int N, int row0, int col0, int lane,
-                                            bool inside)
+__device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], void *__restrict__ C,
+                                            int64_t ldc, int c_bf16, int M, int N, int row0, int col0,
+                                            int lane, bool inside)
 {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -158,12 +166,22 @@ __device__ __forceinline__ void store_tiles(const f32x16 (&acc)[TM][TN], float *
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + j * 32 + (lane & 31);
             const int row = row0 + i * 32 + 4 * (lane >> 5);
-            float *cp = C + (int64_t)row * ldc + col;
+            if (c_bf16) {  // uniform
+                uint16_t *cp = static_cast<uint16_t *>(C) + (int64_t)row * ldc + col;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = 8 * (r >> 2) + (r & 3);
-                if (inside || (row + dr < M && col < N))
-                    __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)dr * ldc);
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 8 * (r >> 2) + (r & 3);
+                    if (inside || (row + dr < M && col < N))
+                        __builtin_nontemporal_store(bf16_rne(acc[i][j][r]), cp + (int64_t)dr * ldc);
+                }
+            } else {
+                float *cp = static_cast<float *>(C) + (int64_t)row * ldc + col;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 8 * (r >> 2) + (r & 3);
+                    if (inside || (row + dr < M && col < N))
+                        __builtin_nontemporal_store(acc[i][j][r], cp + (int64_t)dr * ldc);
+                }
             }
         }
 }
@@ -174,7 +192,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
     const uint8_t *__restrict__ a_codes, const uint8_t *__restrict__ a_sexp,
     const uint8_t *__restrict__ a_mexp, const uint8_t *__restrict__ b_codes,
     const uint8_t *__restrict__ b_sexp, const uint8_t *__restrict__ b_mexp, int M, int N, int K,
-    float *__restrict__ C, int64_t ldc)
+    void *__restrict__ C, int64_t ldc, int c_bf16)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int THREADS = 64 * WM * WN;
@@ -303,7 +321,7 @@ __global__ __launch_bounds__(64 * WM * WN) void mx_gemm_kernel(
         }
     }
 
-    store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
+    store_tiles<TM, TN>(acc, C, ldc, c_bf16, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
                         m0 + BM <= M && n0 + BN <= N);
 }
 
@@ -496,7 +514,7 @@ __device__ __forceinline__ void static_for(F &&f)
 template <int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int N, int K,
-    float *__restrict__ C, int64_t ldc)
+    void *__restrict__ C, int64_t ldc, int c_bf16)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr int NW = WM * WN;
@@ -643,7 +661,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dl_kernel(
     for (int kt = 0; kt + 2 < nk; ++kt) k_step(std::true_type{}, std::true_type{});
     if (nk > 1) k_step(std::false_type{}, std::true_type{});
     k_step(std::false_type{}, std::false_type{});
-    store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
+    store_tiles<TM, TN>(acc, C, ldc, c_bf16, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
                         m0 + BM <= M && n0 + BN <= N);
 }
 
@@ -721,7 +739,7 @@ __device__ __forceinline__ void ring_barrier()
 template <int WM, int WN, int TM, int TN, int FMT>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
     const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const uint8_t *__restrict__ SA,
-    const uint8_t *__restrict__ SB, int M, int N, int nk, float *__restrict__ C, int64_t ldc)
+    const uint8_t *__restrict__ SB, int M, int N, int nk, void *__restrict__ C, int64_t ldc, int c_bf16)
 {
     constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4, BF16 = FMT == kFmtBf16;
     static_assert(FP6 || FP4 || BF16, "format");
@@ -960,7 +978,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
     }
     if (kt + 1 < nk) k_step(std::false_type{}, std::integral_constant<int, 0>{});
     k_step(std::false_type{}, std::integral_constant<int, -1>{});
-    store_tiles<TM, TN>(acc, C, ldc, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
+    store_tiles<TM, TN>(acc, C, ldc, c_bf16, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, lane,
                         m0 + BM <= M && n0 + BN <= N);
 }
 
@@ -969,7 +987,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
 // point calls them that way before it enqueues the image writers.
 template <int WM, int WN, int TM, int TN, int FMT>
 int launch_ring(const uint8_t *A, const uint8_t *B, const uint8_t *SA, const uint8_t *SB, int M, int N, int nk,
-                float *C, int64_t ldc, bool dry, hipStream_t s)
+                void *C, int64_t ldc, int c_bf16, bool dry, hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     constexpr size_t kLds = kRingStages * (BM + BN) * (size_t)(kRingRow + (FMT == kFmtFp4 ? 8 : 0));
@@ -979,20 +997,20 @@ int launch_ring(const uint8_t *A, const uint8_t *B, const uint8_t *SA, const uin
         return BDR_ERR_LAUNCH;
     if (dry) return BDR_OK;
     hipLaunchKernelGGL((gemm_ring_kernel<WM, WN, TM, TN, FMT>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
-                       dim3(64 * WM * WN), kLds, s, A, B, SA, SB, M, N, nk, C, ldc);
+                       dim3(64 * WM * WN), kLds, s, A, B, SA, SB, M, N, nk, C, ldc, c_bf16);
     return launch_status();
 }
 
 template <int FMT>
-int gemm_ring(const void *A, const void *B, const void *SA, const void *SB, int64_t M, int64_t N, int nk, float *C,
-              int64_t ldc, bool dry, hipStream_t s)
+int gemm_ring(const void *A, const void *B, const void *SA, const void *SB, int64_t M, int64_t N, int nk, void *C,
+              int64_t ldc, int c_bf16, bool dry, hipStream_t s)
 {
     const uint8_t *a = (const uint8_t *)A, *b = (const uint8_t *)B, *sa = (const uint8_t *)SA, *sb = (const uint8_t *)SB;
     if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_ring<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, dry, s);
+        const int st = launch_ring<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, c_bf16, dry, s);
         if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
     }
-    return launch_ring<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, dry, s);
+    return launch_ring<2, 2, 2, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, c_bf16, dry, s);
 }
 
 // Two tile shapes: 256 x 256 with 8 waves (128 KiB of LDS, one workgroup per CU)
@@ -1000,7 +1018,7 @@ int gemm_ring(const void *A, const void *B, const void *SA, const void *SB, int6
 // 128 x 128 with 4 waves (64 KiB).
 template <int MBA, int MBB>
 int launch_gemm(const uint8_t *ac, const uint8_t *as, const uint8_t *am, const uint8_t *bc,
-                const uint8_t *bs, const uint8_t *bm, int M, int N, int K, float *C, int64_t ldc,
+                const uint8_t *bs, const uint8_t *bm, int M, int N, int K, void *C, int64_t ldc, int c_bf16,
                 hipStream_t s)
 {
     constexpr size_t kBigLds = 2 * (256 + 256) * (size_t)kPitch;
@@ -1012,27 +1030,27 @@ int launch_gemm(const uint8_t *ac, const uint8_t *as, const uint8_t *am, const u
     if (big_ok) {
         const unsigned grid = (unsigned)((M / 256) * (N / 256));
         hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 4, 4, 2>), dim3(grid), dim3(512), kBigLds, s,
-                           ac, as, am, bc, bs, bm, M, N, K, C, ldc);
+                           ac, as, am, bc, bs, bm, M, N, K, C, ldc, c_bf16);
     } else {
         const unsigned grid = (unsigned)(((M + 127) / 128) * ((N + 127) / 128));
         hipLaunchKernelGGL((mx_gemm_kernel<MBA, MBB, 2, 2, 2, 2>), dim3(grid), dim3(256), kSmallLds,
-                           s, ac, as, am, bc, bs, bm, M, N, K, C, ldc);
+                           s, ac, as, am, bc, bs, bm, M, N, K, C, ldc, c_bf16);
     }
     return launch_status();
 }
 
 template <int MBA>
 int pick_b(int mb, const uint8_t *ac, const uint8_t *as, const uint8_t *am, const uint8_t *bc,
-           const uint8_t *bs, const uint8_t *bm, int M, int N, int K, float *C, int64_t ldc,
+           const uint8_t *bs, const uint8_t *bm, int M, int N, int K, void *C, int64_t ldc, int c_bf16,
            hipStream_t s)
 {
-    if (mb == 7) return launch_gemm<MBA, 7>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
-    if (mb == 4) return launch_gemm<MBA, 4>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
-    return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, s);
+    if (mb == 7) return launch_gemm<MBA, 7>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, c_bf16, s);
+    if (mb == 4) return launch_gemm<MBA, 4>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, c_bf16, s);
+    return launch_gemm<MBA, 2>(ac, as, am, bc, bs, bm, M, N, K, C, ldc, c_bf16, s);
 }
 
 template <int WM, int WN, int TM, int TN>
-int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *C, int64_t ldc, bool dry,
+int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, void *C, int64_t ldc, int c_bf16, bool dry,
               hipStream_t s)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -1043,53 +1061,58 @@ int launch_dl(const uint16_t *A, const uint16_t *B, int M, int N, int K, float *
         return BDR_ERR_LAUNCH;
     if (dry) return BDR_OK;
     hipLaunchKernelGGL((gemm_dl_kernel<WM, WN, TM, TN>), dim3((unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN))),
-                       dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc);
+                       dim3(64 * WM * WN), kLds, s, A, B, M, N, K, C, ldc, c_bf16);
     return launch_status();
 }
 
 // K = 0: one workgroup per row of C (rows on grid.x, which takes up to 2^31 - 1 workgroups;
 // grid.y stops at 65535 and M may be 2^20).
-__global__ void gemm_zero_kernel(float *C, int64_t ldc, int N)
+__global__ void gemm_zero_kernel(void *C, int64_t ldc, int c_bf16, int N)
 {
     const int64_t row = blockIdx.x;
-    for (int c = threadIdx.x; c < N; c += blockDim.x) C[row * ldc + c] = 0.f;
+    for (int c = threadIdx.x; c < N; c += blockDim.x) {
+        if (c_bf16)
+            static_cast<uint16_t *>(C)[row * ldc + c] = 0;
+        else
+            static_cast<float *>(C)[row * ldc + c] = 0.f;
+    }
 }
 
 }  // namespace
 
 int gemm(const bdr_format &fa, const bdr_format &fb, const void *a_codes, const void *a_sexp,
          const void *a_mexp, const void *b_codes, const void *b_sexp, const void *b_mexp,
-         int64_t M, int64_t N, int64_t K, float *C, int64_t ldc, hipStream_t s)
+         int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16, hipStream_t s)
 {
     if (K == 0) {  // empty sum
-        hipLaunchKernelGGL(gemm_zero_kernel, dim3((unsigned)M), dim3(256), 0, s, C, ldc, (int)N);
+        hipLaunchKernelGGL(gemm_zero_kernel, dim3((unsigned)M), dim3(256), 0, s, C, ldc, c_bf16, (int)N);
         return launch_status();
     }
     const uint8_t *ac = (const uint8_t *)a_codes, *as = (const uint8_t *)a_sexp,
                   *am = (const uint8_t *)a_mexp, *bc = (const uint8_t *)b_codes,
                   *bs = (const uint8_t *)b_sexp, *bm = (const uint8_t *)b_mexp;
-    if (fa.m == 7) return pick_b<7>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
-    if (fa.m == 4) return pick_b<4>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
-    return pick_b<2>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, s);
+    if (fa.m == 7) return pick_b<7>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, c_bf16, s);
+    if (fa.m == 4) return pick_b<4>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, c_bf16, s);
+    return pick_b<2>(fb.m, ac, as, am, bc, bs, bm, (int)M, (int)N, (int)K, C, ldc, c_bf16, s);
 }
 
 // C = A * B^T for row-major BF16 A [M x K] and B [N x K] (K > 0, shapes already validated).
-int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+int gemm_bf16(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
               bool dry, hipStream_t s)
 {
     const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
     if (M % 256 == 0 && N % 256 == 0) {
-        const int st = launch_dl<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, dry, s);
+        const int st = launch_dl<2, 4, 4, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, c_bf16, dry, s);
         if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
     }
-    return launch_dl<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, dry, s);
+    return launch_dl<2, 2, 2, 2>(a, b, (int)M, (int)N, (int)K, C, ldc, c_bf16, dry, s);
 }
 
 // C = A * B^T for K-tiled BF16 images (to_bf16_tiled) of A [M x K] and B [N x K]; K % 32 == 0.
-int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
                     bool dry, hipStream_t s)
 {
-    return gemm_ring<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)(K / 32), C, ldc, dry, s);
+    return gemm_ring<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)(K / 32), C, ldc, c_bf16, dry, s);
 }
 
 // Packed Table II planes of a [rows x K] operand (K % 32 == 0) -> BF16, tiled along K.
@@ -1109,10 +1132,10 @@ int to_bf16_tiled(const bdr_format &f, const void *codes, const void *sexp, cons
 }
 
 // C = A * B^T for FP6 block images (to_fp6) of A [M x K] and B [N x K]; K % 64 == 0.
-int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, float *C, int64_t ldc,
+int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
              bool dry, hipStream_t s)
 {
-    return gemm_ring<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 64), C, ldc, dry, s);
+    return gemm_ring<kFmtFp6>(A, B, nullptr, nullptr, M, N, (int)(K / 64), C, ldc, c_bf16, dry, s);
 }
 
 // Packed MX6 or MX4 planes of a [rows x K] operand (K % 64 == 0) -> rows x K / 16 chunks of
@@ -1144,9 +1167,9 @@ size_t fp4_scale_bytes(int64_t rows, int64_t K_out)
 
 // C = A * B^T for FP4 block images (to_fp4) of A [M x K] and B [N x K]; K % 128 == 0.
 int gemm_fp4(const void *A, const void *SA, const void *B, const void *SB, int64_t M, int64_t N, int64_t K,
-             float *C, int64_t ldc, bool dry, hipStream_t s)
+             void *C, int64_t ldc, int c_bf16, bool dry, hipStream_t s)
 {
-    return gemm_ring<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 128), C, ldc, dry, s);
+    return gemm_ring<kFmtFp4>(A, B, SA, SB, M, N, (int)(K / 128), C, ldc, c_bf16, dry, s);
 }
 
 // Packed MX4 planes of a [rows x K] operand (K % 32 == 0) -> rows x K_out / 32 chunks of 16

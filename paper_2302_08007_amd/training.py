@@ -40,12 +40,14 @@ def release_workspaces():
     _workspaces.clear()
 
 
-def _mx_matmul(fa, fb, a, a_axis, b, b_axis, M, N, K):
-    """C[M, N] = Q(a) Q(b)^T with a, b quantized along the K axis of the product."""
+def _mx_matmul(fa, fb, a, a_axis, b, b_axis, M, N, K, out_dtype):
+    """C[M, N] = Q(a) Q(b)^T with a, b quantized along the K axis of the product; C comes out in
+    out_dtype (FP32 sums; a BF16 C is rounded as the product kernel stores it, not in a pass of
+    its own)."""
     pa = bdr_quantize(fa, a, axis=a_axis)
     pb = bdr_quantize(fb, b, axis=b_axis)
     ws = _workspace(a.device, mx_gemm_workspace_bytes(M, N, K))
-    return mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws)
+    return mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws, dtype=out_dtype)
 
 
 class _MXLinear(torch.autograd.Function):
@@ -55,8 +57,7 @@ class _MXLinear(torch.autograd.Function):
         O = w.shape[0]
         ctx.save_for_backward(x, w)
         ctx.fmt_bwd = fmt_bwd
-        y = _mx_matmul(fmt_fwd, fmt_fwd, x, AXIS_ROW, w, AXIS_ROW, T, O, I)
-        return y.to(x.dtype)
+        return _mx_matmul(fmt_fwd, fmt_fwd, x, AXIS_ROW, w, AXIS_ROW, T, O, I, x.dtype)
 
     @staticmethod
     def backward(ctx, g):
@@ -67,9 +68,9 @@ class _MXLinear(torch.autograd.Function):
         g = g.contiguous()
         gx = gw = None
         if ctx.needs_input_grad[0]:
-            gx = _mx_matmul(f, f, g, AXIS_ROW, w, AXIS_COL, T, I, O).to(x.dtype)
+            gx = _mx_matmul(f, f, g, AXIS_ROW, w, AXIS_COL, T, I, O, x.dtype)
         if ctx.needs_input_grad[1]:
-            gw = _mx_matmul(f, f, g, AXIS_COL, x, AXIS_COL, O, I, T).to(w.dtype)
+            gw = _mx_matmul(f, f, g, AXIS_COL, x, AXIS_COL, O, I, T, w.dtype)
         return gx, gw, None, None
 
 

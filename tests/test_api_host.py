@@ -165,6 +165,12 @@ def test_sweep_and_gemm_argument_checks():
     assert gm(C=NULL) == ERR_NULL and gm(a=NULL) == ERR_NULL
     assert gm(C=ctypes.c_void_p(0x10002)) == ERR_ALIGN   # C needs only the alignment of a float
     assert gm(M=0) == OK
+    gt = lambda C=FAKE, cd=1, ldc=128, M=128: L.mx_gemm_to(
+        ctypes.byref(f), ctypes.byref(f), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, M, 128, 64, C, cd, ldc, NULL, 0, NULL)
+    assert gt(cd=2) == ERR_DTYPE and gt(cd=-1) == ERR_DTYPE
+    assert gt(C=ctypes.c_void_p(0x10001)) == ERR_ALIGN      # a BF16 C needs the alignment of two bytes
+    assert gt(C=ctypes.c_void_p(0x10002), cd=0) == ERR_ALIGN and gt(C=NULL) == ERR_NULL
+    assert gt(ldc=64) == ERR_SHAPE and gt(M=0) == OK
     need = L.mx_gemm_workspace_bytes(128, 128, 64)
     assert need == 2 * 128 * 64 * 2 and L.mx_gemm_workspace_bytes(-1, 128, 64) == 0
     assert L.mx_gemm_workspace_bytes(128, 384, 64) == (128 + 384) * 64 * 2
@@ -283,7 +289,7 @@ def test_header_is_plain_c(tmp_path):
         "                   (void *)bdr_tile_packing, (void *)bdr_quantize_dequantize,\n"
         "                   (void *)bdr_qsnr_sweep_workspace_bytes, (void *)bdr_qsnr_sweep,\n"
         "                   (void *)bdr_qsnr_sweep_static, (void *)bdr_qsnr_sweep_static_scratch_bytes,\n"
-        "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm,\n"
+        "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm, (void *)mx_gemm_to,\n"
         "                   (void *)mx_dot_pipeline_workspace_bytes, (void *)mx_dot_pipeline};\n"
         "    (void)fns;\n"
         "    return bdr_packed_sizes(&mx9, 4, 64, BDR_AXIS_ROW, &a, &b, &c) + mx6.m + mx4.m;\n"

@@ -305,6 +305,49 @@ def test_strided_output_and_empty_k():
         B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, workspace=ws[:need - 16])
 
 
+def _bf16_rne(v):
+    """float32 array -> bfloat16 bit patterns, ties to even (written out, no library cast)."""
+    u = np.ascontiguousarray(v, np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("shape", [(128, 128, 64), (256, 256, 512), (130, 70, 128), (257, 129, 64), (512, 384, 1024)])
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX9", "MX9"), ("MX4", "MX4"), ("MX9", "MX6")])
+def test_c_in_bf16(shape, names):
+    """mx_gemm_to with a BF16 C (the dtype of the tensors between tensor operations, Sec. V): every
+    element is the FP32 sum of the same form rounded once more to nearest even, so it equals, bit for
+    bit, the rounding of what the FP32 call returns, in every form, and lies within half a BF16
+    unit (plus the FP32 tolerance) of the oracle's product."""
+    M, N, K = shape
+    fa, fb = getattr(B, names[0]), getattr(B, names[1])
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=3 * M + N + K)
+    pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
+    pan, pbn = _planes_np(pa), _planes_np(pb)
+    Cref = O.mx_gemm(ofmt(fa), ofmt(fb), pan, pbn, M, N, K)
+    Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
+    Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
+    bound = RTOL * (np.abs(Ah) @ np.abs(Bh).T) + np.abs(Cref) * 2.0 ** -8 + 1e-30
+    for ws in (None, _workspace(M, N, K)):
+        C32 = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws)
+        C16 = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws, dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        assert C16.dtype == torch.bfloat16
+        got = to_np(C16)
+        assert np.array_equal(got, _bf16_rne(C32.cpu().numpy())), (shape, names, ws is not None)
+        val = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        assert np.all(np.abs(val - Cref) <= bound), (shape, names, ws is not None)
+    # a pitched BF16 C inside a wider tensor, and the empty sum
+    big = torch.full((M + 2, N + 24), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.mx_gemm(fa, fb, pa, pb, M, N, K, out=big[1:M + 1, 8:8 + N], workspace=_workspace(M, N, K))
+    assert np.array_equal(to_np(big[1:M + 1, 8:8 + N].contiguous()), _bf16_rne(B.mx_gemm(
+        fa, fb, pa, pb, M, N, K, workspace=_workspace(M, N, K)).cpu().numpy()))
+    assert bool((big[0] == 7).all()) and bool((big[-1] == 7).all())
+    assert bool((big[:, :8] == 7).all()) and bool((big[:, 8 + N:] == 7).all())
+    z = torch.full((M, N), 3.0, dtype=torch.bfloat16, device="cuda")
+    B.mx_gemm(fa, fb, pa, pb, M, N, 0, out=z)
+    assert bool((z == 0).all())
+
+
 @pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX9", "MX9"), ("MX4", "MX4"), ("MX6", "MX4")])
 def test_full_size_sampled_entries(names):
     # 8192^3, the bench configuration (MX6 x MX6) and the other instruction paths at that size:
