@@ -510,6 +510,21 @@ def other_legs(B, S, torch, timed):
             leg[name] = {"us": round(t * 1e3, 1), "GBps": round(ab / t / 1e6, 1),
                          "frac": round(ab / t / 1e6 / HBM_PEAK_GBS, 4)}
         out["activation_bf16_8192x12288_MX9"] = leg
+        # the same tensor quantized to MX6 straight into the FP6 product kernel's operand image
+        # (2 bytes read, 1 byte written per element), blocks along rows / down columns
+        leg6 = {}
+        ab6 = r * c * 3
+        for axis, name in ((B.AXIS_ROW, "row"), (B.AXIS_COL, "col")):
+            img = torch.empty(B.mx_operand_bytes(B.MX6, r, c), dtype=torch.uint8, device="cuda")
+            k = [0]
+
+            def runo():
+                B.bdr_quantize_operand(B.MX6, xa[k[0] % 3], axis=axis, out=img)
+                k[0] += 1
+            t = timed(runo, reps=7, inner=6)
+            leg6[name] = {"us": round(t * 1e3, 1), "GBps": round(ab6 / t / 1e6, 1),
+                          "frac": round(ab6 / t / 1e6 / HBM_PEAK_GBS, 4)}
+        out["activation_bf16_8192x12288_MX6_operand_image"] = leg6
         del xa
     except B.BdrError as e:
         out["activation_bf16_8192x12288_MX9"] = {"error": str(e)}

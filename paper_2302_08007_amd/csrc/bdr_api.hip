@@ -428,6 +428,62 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
                       workspace, workspace_bytes, hip_stream);
 }
 
+// ---- operands made by the quantizer itself (block-scaled FP6 images)
+
+static bool fp6_operand_format(const bdr_format *f) { return bdr::is_mx(*f) && f->m <= 4; }
+
+size_t mx_operand_bytes(const bdr_format *fmt, int64_t rows, int64_t K)
+{
+    if (check_format(fmt) != BDR_OK || !fp6_operand_format(fmt)) return 0;
+    if (rows < 0 || K < 0 || K % 64 != 0 || rows > (1 << 20) || K > (1 << 20)) return 0;
+    return (size_t)rows * (size_t)K;  // a 16-byte chunk per block of 16
+}
+
+int bdr_quantize_operand(const bdr_format *fmt, const void *x, int dtype, int64_t rows, int64_t cols,
+                         int64_t ld, int axis, int b_operand, void *image, void *hip_stream)
+{
+    int st = check_format(fmt);
+    if (st) return st;
+    if (!fp6_operand_format(fmt)) return BDR_ERR_FORMAT;
+    if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
+    if (axis != BDR_AXIS_ROW && axis != BDR_AXIS_COL) return BDR_ERR_SHAPE;
+    if (rows < 0 || cols < 0 || ld < cols || rows > (1 << 20) || cols > (1 << 20)) return BDR_ERR_SHAPE;
+    if (axis == BDR_AXIS_ROW ? cols % 64 != 0 : !bdr::quantize_fp6_col_ok(dtype, rows, cols)) return BDR_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return BDR_OK;
+    st = check_tensor_ptr(x, dtype, ld);
+    if (st) return st;
+    if (!image) return BDR_ERR_NULL;
+    if (!aligned16(image)) return BDR_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (axis == BDR_AXIS_ROW) return bdr::quantize_fp6_row(*fmt, x, dtype, rows, cols, ld, image, b_operand != 0, s);
+    return bdr::quantize_fp6_col(*fmt, x, dtype, rows, cols, ld, image, b_operand != 0, s);
+}
+
+int mx_gemm_operands(const bdr_format *fa, const bdr_format *fb, const void *image_a, const void *image_b,
+                     int64_t M, int64_t N, int64_t K, void *C, int c_dtype, int64_t ldc, void *hip_stream)
+{
+    if (c_dtype != BDR_F32 && c_dtype != BDR_BF16) return BDR_ERR_DTYPE;
+    int st = check_format(fa);
+    if (st) return st;
+    st = check_format(fb);
+    if (st) return st;
+    if (!fp6_operand_format(fa) || !fp6_operand_format(fb)) return BDR_ERR_FORMAT;
+    if (M < 0 || N < 0 || K < 0 || ldc < N || K % 64 != 0) return BDR_ERR_SHAPE;
+    if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
+    if (M == 0 || N == 0) return BDR_OK;
+    if (!C) return BDR_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(C) % elem_size(c_dtype) != 0) return BDR_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int c_bf16 = c_dtype == BDR_BF16;
+    if (K == 0)  // the empty sum: mx_gemm's own path for it (no operand is read)
+        return bdr::gemm(*fa, *fb, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, M, N, 0, C, ldc, c_bf16, s);
+    if (!image_a || !image_b) return BDR_ERR_NULL;
+    if (!aligned16(image_a) || !aligned16(image_b)) return BDR_ERR_ALIGN;
+    st = bdr::gemm_fp6(image_a, image_b, M, N, K, C, ldc, c_bf16, true, s);
+    if (st) return st;
+    return bdr::gemm_fp6(image_a, image_b, M, N, K, C, ldc, c_bf16, false, s);
+}
+
 size_t mx_dot_pipeline_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     return mx_gemm_workspace_bytes(M, N, K);

@@ -284,6 +284,55 @@ __global__ __launch_bounds__((col_threads<T, MODE>())) void mx_col_kernel(
     }
 }
 
+// Column blocks quantized straight into the operand image of the block-scaled FP6 product
+// (see mx_quantize_fp6_row_kernel): the operand is the transpose, so its rows are the
+// tensor's columns and its K index the tensor's row.  The same tile, the same lane per block;
+// a tile gives every one of its columns eight chunks, 64 consecutive bytes in each of two K
+// steps, and the columns of a tile follow each other in the image, so a tile writes two runs
+// of 64 bytes x its columns: no partial lines, no neighbours to wait for.
+template <int MB, typename T, bool B_OPERAND>
+__global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_fp6_kernel(
+    const T *x, u32x4 *__restrict__ out, int64_t cols, int64_t ld)
+{
+    constexpr int kTC = TileGeom<T>::kTC;
+    constexpr int THREADS = col_threads<T, 0>();
+    __shared__ __attribute__((aligned(16))) uint8_t tile[kTR * kTC * sizeof(T)];
+    uint32_t tx, ty;
+    tile_of<true>(tx, ty);
+    const int64_t r0 = (int64_t)tx * kTR, c0 = (int64_t)ty * kTC;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = lane & (kBPT - 1), c = kCPW * wave + lane / kBPT;  // one pass: THREADS = kBPT * kTC
+    static_assert(THREADS == kBPT * kTC, "one lane per block of the tile");
+    tile_load<T, THREADS>(x, ld, r0, c0, tile);
+    __syncthreads();
+    uint32_t xb[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) xb[i] = lds_get(tile, lds_off<T>(16 * b + i, c), T());
+    const u32x4 chunk = mx_quant_fp6_block<MB, B_OPERAND>(xb);
+    const int64_t kb = (r0 >> 4) + b;
+    stg<true>(chunk, out + (((kb >> 2) * cols + (c0 + c)) * 4 + (kb & 3)));
+}
+
+template <typename T>
+int quantize_fp6_col_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld, void *out,
+                       bool b_operand, hipStream_t s)
+{
+    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC)), block(col_threads<T, 0>());
+    u32x4 *o = (u32x4 *)out;
+    if (f.m == 4) {
+        if (b_operand)
+            hipLaunchKernelGGL((mx_col_fp6_kernel<4, T, true>), grid, block, 0, s, x, o, cols, ld);
+        else
+            hipLaunchKernelGGL((mx_col_fp6_kernel<4, T, false>), grid, block, 0, s, x, o, cols, ld);
+    } else {
+        if (b_operand)
+            hipLaunchKernelGGL((mx_col_fp6_kernel<2, T, true>), grid, block, 0, s, x, o, cols, ld);
+        else
+            hipLaunchKernelGGL((mx_col_fp6_kernel<2, T, false>), grid, block, 0, s, x, o, cols, ld);
+    }
+    return launch_status();
+}
+
 template <int MB, typename T>
 void launch_col(int mode, const T *x, T *y, uint8_t *codes, uint8_t *sexp, uint8_t *mexp,
                 int64_t rows, int64_t cols, int64_t ld, hipStream_t s)
@@ -557,6 +606,22 @@ int col_any(int mode, const bdr_format &f, const void *x, void *y, int dtype, in
 }
 
 }  // namespace
+
+// x [rows x cols] with blocks down the columns (K = rows): rows a multiple of 128, cols of the
+// tile width (64 FP32 / 128 BF16 columns); f is MX6 or MX4.  false: the shape is not made of
+// whole tiles (the caller reports it).
+bool quantize_fp6_col_ok(int dtype, int64_t rows, int64_t cols)
+{
+    const int tc = dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC;
+    return rows % kTR == 0 && cols % tc == 0 && cols / tc <= 65535;
+}
+
+int quantize_fp6_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                     void *out, bool b_operand, hipStream_t s)
+{
+    if (dtype == BDR_F32) return quantize_fp6_col_t(f, (const float *)x, rows, cols, ld, out, b_operand, s);
+    return quantize_fp6_col_t(f, (const uint16_t *)x, rows, cols, ld, out, b_operand, s);
+}
 
 int quantize_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,
                  int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)

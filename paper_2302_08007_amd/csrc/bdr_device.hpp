@@ -228,13 +228,18 @@ __device__ __forceinline__ void load8(const float *p, uint32_t (&xb)[8])
     xb[4] = b.x; xb[5] = b.y; xb[6] = b.z; xb[7] = b.w;
 }
 
-__device__ __forceinline__ void load8(const uint16_t *p, uint32_t (&xb)[8])
+// 8 BF16 values (16 bytes) as FP32 bit patterns
+__device__ __forceinline__ void widen8(const u32x4 &a, uint32_t (&xb)[8])
 {
-    u32x4 a = ldg<true>(reinterpret_cast<const u32x4 *>(p));
     xb[0] = a.x << 16; xb[1] = a.x & 0xffff0000u;
     xb[2] = a.y << 16; xb[3] = a.y & 0xffff0000u;
     xb[4] = a.z << 16; xb[5] = a.z & 0xffff0000u;
     xb[6] = a.w << 16; xb[7] = a.w & 0xffff0000u;
+}
+
+__device__ __forceinline__ void load8(const uint16_t *p, uint32_t (&xb)[8])
+{
+    widen8(ldg<true>(reinterpret_cast<const u32x4 *>(p)), xb);
 }
 
 // Store 8 consecutive FP32 bit patterns as the output type.  For BF16 the low
@@ -312,6 +317,58 @@ __device__ __forceinline__ void store8(uint16_t *p, const uint32_t (&yb)[8])
     u32x4 a = {(yb[0] >> 16) | (yb[1] & 0xffff0000u), (yb[2] >> 16) | (yb[3] & 0xffff0000u),
                (yb[4] >> 16) | (yb[5] & 0xffff0000u), (yb[6] >> 16) | (yb[7] & 0xffff0000u)};
     __builtin_nontemporal_store(a, reinterpret_cast<u32x4 *>(p));
+}
+
+// One whole MX6 or MX4 block held by one lane, quantized (nearest even) straight into the
+// 16-byte chunk the block-scaled FP6 matrix instruction takes as a lane's operand: the 16
+// elements as E2M3 codes in dwords 0-2 (element j at bits 6 j .. 6 j + 5), the block's scale
+// byte in dword 3 (byte 0 for an A operand, byte 2 for a B operand).  An element +-M 2^(SE - 127
+// - tau - (m - 1)) is the E2M3 value (M << sh6) / 8 times 2^(scale - 127):
+//   MX6: sh6 = 2 - tau - z, scale = SE - 2 + z, z = (SE == 1)     MX4: sh6 = 3 - tau, scale = SE - 1
+// (M 2^-tau has at most 4 significant bits over 5 binades, Sec. III; the top binade of E2M3 is
+// needed for M = 15, tau = 0; a block with SE = 1 moves one binade down instead, still exact).
+// The quantizer is that of mx_quant_lane: same maxima, same shifts, same rounding.
+template <int MB, bool B_OPERAND>
+__device__ __forceinline__ u32x4 mx_quant_fp6_block(const uint32_t (&xb)[16])
+{
+    static_assert(MB == 4 || MB == 2, "MX6 or MX4");
+    constexpr uint32_t MMASK = (1u << MB) - 1u;
+    constexpr float TOP = (float)MMASK;
+    uint32_t p[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        p[j] = umax(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask), kMagLo);
+    uint32_t bm = p[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) bm = umax(bm, p[j]);
+    bm = umin(bm, kMagHi);
+    const uint32_t thr = bm & kExpMask;
+    const int se = (int)(bm >> 23);
+    const int c0 = (MB - 1) + 127 - se, c1 = c0 + 1;
+    const int z = (MB == 4 && se == 1) ? 1 : 0;
+    const int scale = MB == 4 ? se - 2 + z : se - 1;  // se >= 1: never negative
+    uint32_t w[3] = {0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const bool below = p[j] < thr;
+        const int sh = below ? c1 : c0;
+        const int sh6 = (MB == 4 ? 2 : 3) - (below ? 1 : 0) - z;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = 2 * j + e;
+            const float y = __builtin_fminf(__builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh), TOP);
+            const uint32_t mag = as_u(y + kMagic) & MMASK;  // nearest-even integer
+            const uint32_t u = mag << sh6;                  // element = u / 8, u <= 60
+            // u >= 8: FP32 of u has exponent field 127 + p (p = 3 .. 5) and u's next three bits
+            // on top of its fraction; E2M3 wants exponent field p - 2 and those bits
+            const uint32_t em = u < 8u ? u : (as_u((float)u) >> 20) - ((127u + 2u) << 3);
+            const uint32_t c6 = ((xb[i] >> 31) << 5) | em;
+            const int bit = 6 * i;
+            w[bit >> 5] |= c6 << (bit & 31);
+            if ((bit & 31) + 6 > 32) w[(bit >> 5) + 1] |= c6 >> (32 - (bit & 31));
+        }
+    }
+    return u32x4{w[0], w[1], w[2], (uint32_t)scale << (B_OPERAND ? 16 : 0)};
 }
 
 // A format tuple as the general (run-time-tuple) kernels take it.

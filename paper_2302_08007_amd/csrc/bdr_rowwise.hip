@@ -1085,6 +1085,79 @@ static int generic_view_t(int what, const bdr_format &f, const T *x, T *y, int64
     return launch_status();
 }
 
+// ---- quantize straight into the operand image of the block-scaled FP6 product
+//
+// For a tensor that is quantized only to be multiplied (Sec. V: both inputs of every tensor
+// operation of a training iteration), the three planes are a detour: the product's two-pass
+// form would read them back at once and rewrite them as the image its kernel takes.  Here
+// the quantizer writes that image itself: one lane per block of 16, the block's 16-byte
+// chunk (mx_quant_fp6_block) stored at [K step of 4 blocks][row][4 chunks].
+template <int MB, typename T, bool B_OPERAND>
+__global__ __launch_bounds__(kThreads) void mx_quantize_fp6_row_kernel(
+    const T *__restrict__ x, int64_t n_blocks, int64_t rows, int32_t row_blocks, int64_t ld,
+    u32x4 *__restrict__ out)
+{
+    const int64_t bi = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (bi >= n_blocks) return;
+    const int64_t row = bi / row_blocks;
+    const int32_t kb = (int32_t)(bi - row * row_blocks);
+    const T *src = x + row * ld + 16 * (int64_t)kb;
+    uint32_t xb[16];
+    if constexpr (sizeof(T) == 4) {
+        uint32_t lo[8], hi[8];
+        load8(src, lo);
+        load8(src + 8, hi);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            xb[i] = lo[i];
+            xb[8 + i] = hi[i];
+        }
+    } else {
+        const u32x4 a = ldg<true>(reinterpret_cast<const u32x4 *>(src));
+        const u32x4 b = ldg<true>(reinterpret_cast<const u32x4 *>(src) + 1);
+        uint32_t lo[8], hi[8];
+        widen8(a, lo);
+        widen8(b, hi);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            xb[i] = lo[i];
+            xb[8 + i] = hi[i];
+        }
+    }
+    const u32x4 chunk = mx_quant_fp6_block<MB, B_OPERAND>(xb);
+    stg<true>(chunk, out + (((int64_t)(kb >> 2) * rows + row) * 4 + (kb & 3)));
+}
+
+template <typename T>
+static int quantize_fp6_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
+                              void *out, bool b_operand, hipStream_t s)
+{
+    const int64_t nb = rows * (cols / 16);
+    const dim3 grid(blocks_for(nb)), block(kThreads);
+    u32x4 *o = (u32x4 *)out;
+    const int32_t rb = (int32_t)(cols / 16);
+    if (f.m == 4) {
+        if (b_operand)
+            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<4, T, true>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+        else
+            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<4, T, false>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+    } else {
+        if (b_operand)
+            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<2, T, true>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+        else
+            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<2, T, false>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+    }
+    return launch_status();
+}
+
+// x [rows x cols], blocks along the rows' own direction (K = cols, a multiple of 64); f is MX6 or MX4.
+int quantize_fp6_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                     void *out, bool b_operand, hipStream_t s)
+{
+    if (dtype == BDR_F32) return quantize_fp6_row_t(f, (const float *)x, rows, cols, ld, out, b_operand, s);
+    return quantize_fp6_row_t(f, (const uint16_t *)x, rows, cols, ld, out, b_operand, s);
+}
+
 // Column blocks: the transposed view [cols x rows].
 int generic_col(int what, const bdr_format &f, const void *x, void *y, int dtype, int64_t rows,
                 int64_t cols, int64_t ld, void *codes, void *sexp, void *mexp, hipStream_t s)

@@ -260,6 +260,28 @@ def test_table_image_argument_checks():
     assert tg(n=0) == OK and tg(n=0, idx=NULL, y=NULL, t=NULL) == OK
 
 
+def test_operand_image_argument_checks():
+    L, f = B.lib, B.MX6
+    assert B.mx_operand_bytes(B.MX6, 128, 256) == 128 * 256 == B.mx_operand_bytes(B.MX4, 128, 256)
+    assert B.mx_operand_bytes(B.MX9, 128, 256) == 0                    # BF16 products: not this image
+    assert B.mx_operand_bytes(B.fmt(16, 2, 1, 4, rounding=B.RTZ), 128, 256) == 0
+    assert B.mx_operand_bytes(B.MX6, 128, 100) == 0 and B.mx_operand_bytes(B.MX6, -1, 64) == 0
+    qo = lambda fm=f, x=FAKE, dtype=0, rows=128, cols=128, ld=128, axis=0, img=FAKE: L.bdr_quantize_operand(
+        ctypes.byref(fm), x, dtype, rows, cols, ld, axis, 0, img, NULL)
+    assert qo(fm=B.MX9) == ERR_FORMAT and qo(fm=B.fmt(32, 2, 1, 4)) == ERR_FORMAT and qo(dtype=2) == ERR_DTYPE
+    assert qo(cols=96, ld=96) == ERR_SHAPE and qo(axis=3) == ERR_SHAPE and qo(ld=64) == ERR_SHAPE
+    assert qo(axis=1, rows=64) == ERR_SHAPE and qo(axis=1, cols=32, ld=32) == ERR_SHAPE
+    assert qo(axis=1, dtype=1, cols=64, ld=64) == ERR_SHAPE            # BF16 tiles are 128 columns wide
+    assert qo(x=NULL) == ERR_NULL and qo(img=NULL) == ERR_NULL
+    assert qo(x=FAKE_ODD) == ERR_ALIGN and qo(img=FAKE_ODD) == ERR_ALIGN and qo(rows=0) == OK
+    go = lambda fa=f, fb=f, a=FAKE, b=FAKE, M=128, N=128, K=64, C=FAKE, cd=0, ldc=128: L.mx_gemm_operands(
+        ctypes.byref(fa), ctypes.byref(fb), a, b, M, N, K, C, cd, ldc, NULL)
+    assert go(fa=B.MX9) == ERR_FORMAT and go(fb=B.fmt(16, 16, 0, 4)) == ERR_FORMAT and go(cd=5) == ERR_DTYPE
+    assert go(K=48) == ERR_SHAPE and go(ldc=64) == ERR_SHAPE and go(M=-1) == ERR_SHAPE
+    assert go(C=NULL) == ERR_NULL and go(a=NULL) == ERR_NULL and go(b=NULL) == ERR_NULL
+    assert go(a=FAKE_ODD) == ERR_ALIGN and go(C=ctypes.c_void_p(0x10002)) == ERR_ALIGN and go(M=0) == OK
+
+
 def test_gather_argument_checks():
     L = B.lib
     f = B.MX6
@@ -290,6 +312,7 @@ def test_header_is_plain_c(tmp_path):
         "                   (void *)bdr_qsnr_sweep_workspace_bytes, (void *)bdr_qsnr_sweep,\n"
         "                   (void *)bdr_qsnr_sweep_static, (void *)bdr_qsnr_sweep_static_scratch_bytes,\n"
         "                   (void *)mx_gemm_workspace_bytes, (void *)mx_gemm, (void *)mx_gemm_to,\n"
+        "                   (void *)mx_operand_bytes, (void *)bdr_quantize_operand, (void *)mx_gemm_operands,\n"
         "                   (void *)mx_dot_pipeline_workspace_bytes, (void *)mx_dot_pipeline};\n"
         "    (void)fns;\n"
         "    return bdr_packed_sizes(&mx9, 4, 64, BDR_AXIS_ROW, &a, &b, &c) + mx6.m + mx4.m;\n"

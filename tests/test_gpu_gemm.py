@@ -305,6 +305,89 @@ def test_strided_output_and_empty_k():
         B.mx_gemm(B.MX6, B.MX6, pa, pb, M, N, K, workspace=ws[:need - 16])
 
 
+def _two_step_images(fa, fb, pa, pb, M, N, K):
+    """The operand images mx_gemm's two-pass form writes into its workspace from the (oracle-checked)
+    planes: A's at the start, B's after A's half (an operand's half is rows * K BF16 values,
+    rounded up to 256 bytes)."""
+    ws = _workspace(M, N, K)
+    C = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws)
+    torch.cuda.synchronize()
+    half = (2 * M * K + 255) // 256 * 256
+    return ws[:M * K].clone(), ws[half:half + N * K].clone(), C
+
+
+def _special(t, top=3.0e38):
+    """zeros, -0, subnormals, blocks with the lowest exponent code, large values"""
+    t[0, :16] = 0.0
+    t[0, 5] = -0.0
+    t[1, :32] = 2.0 ** -140
+    t[1, 7] = -3 * 2.0 ** -149
+    t[2, :16] = 2.0 ** -126
+    t[2, 3] = -1.5 * 2.0 ** -126
+    t[3, :16] = top
+    t[3, 1] = -top / 3
+    return t
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX4", "MX6"), ("MX6", "MX4")])
+@pytest.mark.parametrize("shape", [(128, 128, 64), (256, 384, 512), (130, 70, 128), (512, 256, 1024)])
+def test_operands_made_by_the_quantizer(shape, names, dtype):
+    """bdr_quantize_operand writes, byte for byte, the image that mx_gemm's two-pass form makes of
+    the planes bdr_quantize gives (which are the oracle's, bit for bit), for either operand role;
+    mx_gemm_operands on two such images returns the same C as that call, and that C is within
+    the tolerance of the oracle's product."""
+    M, N, K = shape
+    fa, fb = getattr(B, names[0]), getattr(B, names[1])
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=M + 5 * N + K)
+    A, Bm = _special(A, 1.0e15).to(dtype), _special(Bm, 1.0e15).to(dtype)   # (products stay inside FP32)
+    pa, pb = B.bdr_quantize(fa, A), B.bdr_quantize(fb, Bm)
+    for p, w in zip(pa, O.quantize(ofmt(fa), to_np(A))):
+        assert np.array_equal(p.cpu().numpy(), w)
+    ia, ib, C2 = _two_step_images(fa, fb, pa, pb, M, N, K)
+    ga = B.bdr_quantize_operand(fa, A, b_operand=False)
+    gb = B.bdr_quantize_operand(fb, Bm, b_operand=True)
+    torch.cuda.synchronize()
+    assert ga.numel() == M * K == B.mx_operand_bytes(fa, M, K) and gb.numel() == N * K
+    assert torch.equal(ga, ia), "image of A"
+    assert torch.equal(gb, ib), "image of B"
+    for cd in (torch.float32, torch.bfloat16):
+        C = B.mx_gemm_operands(fa, fb, ga, gb, M, N, K, dtype=cd)
+        want = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=_workspace(M, N, K), dtype=cd)
+        assert torch.equal(C.view(torch.int32 if cd == torch.float32 else torch.int16),
+                           want.view(torch.int32 if cd == torch.float32 else torch.int16))
+    pan, pbn = _planes_np(pa), _planes_np(pb)
+    Cref = O.mx_gemm(ofmt(fa), ofmt(fb), pan, pbn, M, N, K)
+    Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
+    Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
+    err = np.abs(B.mx_gemm_operands(fa, fb, ga, gb, M, N, K).cpu().numpy().astype(np.float64) - Cref)
+    assert np.all(err <= RTOL * (np.abs(Ah) @ np.abs(Bh).T) + 1e-30)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("name", ["MX6", "MX4"])
+@pytest.mark.parametrize("shape", [(128, 128), (384, 256), (1024, 640)])
+def test_operands_of_the_transpose(shape, name, dtype):
+    """Blocks down the columns: the image of the transpose of x equals the image made of the planes
+    that column-wise bdr_quantize gives (those of the transposed tensor), in either role, also for
+    a pitched view."""
+    rows, cols = shape
+    f = getattr(B, name)
+    big = _special(S.wide_range(rows, cols + 256, device="cuda", seed=rows + cols, spread=8)).to(dtype)
+    for x in (big[:, :cols].contiguous(), big[:, 128:128 + cols]):
+        planes = B.bdr_quantize(f, x, axis=B.AXIS_COL)          # = row-wise planes of x^T [cols x rows]
+        want = O.quantize(ofmt(f), np.ascontiguousarray(to_np(x.contiguous()).T))
+        for p, w in zip(planes, want):
+            assert np.array_equal(p.cpu().numpy(), w)
+        # as operand A, then as operand B, of a product with an MX6 image of the same tensor (an
+        # MX4 x MX4 pair would take the FP4 form): the writer's images of this operand
+        other = B.bdr_quantize(B.MX6, x, axis=B.AXIS_COL)
+        ia, _, _ = _two_step_images(f, B.MX6, planes, other, cols, cols, rows)
+        _, ib, _ = _two_step_images(B.MX6, f, other, planes, cols, cols, rows)
+        assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=False), ia)
+        assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=True), ib)
+
+
 def _bf16_rne(v):
     """float32 array -> bfloat16 bit patterns, ties to even (written out, no library cast)."""
     u = np.ascontiguousarray(v, np.float32).view(np.uint32).astype(np.uint64)
