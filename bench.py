@@ -326,6 +326,7 @@ def aux_probe(B, S, torch):
     idx = torch.randint(0, rows_t, (n_look,), generator=g, device="cuda", dtype=torch.int64)
     yo = torch.empty(n_look, cols_t, device="cuda")
     tb = B.bdr_table_pack(B.MX6, pt, rows_t, cols_t)
+    img = torch.empty(B.mx_operand_bytes(B.MX6, ra, ca), dtype=torch.uint8, device="cuda")
     xc = x.view(-1)[:8192 * 8192].view(8192, 8192)   # a square slice for the column-wise general kernel
     yc = y.view(-1)[:8192 * 8192].view(8192, 8192)
     pc = B.alloc_planes(fh, 8192, 8192, B.AXIS_COL)
@@ -338,6 +339,8 @@ def aux_probe(B, S, torch):
         B.bdr_dequantize(B.MX9, prow, ra, ca, axis=B.AXIS_ROW, out=ya)
         B.bdr_gather_dequantize(B.MX6, pt, rows_t, cols_t, idx, out=yo)
         B.bdr_table_gather_dequantize(B.MX6, tb, rows_t, cols_t, idx, out=yo)
+        B.bdr_quantize_operand(B.MX6, xa, axis=B.AXIS_ROW, out=img)
+        B.bdr_quantize_operand(B.MX6, xa, axis=B.AXIS_COL, out=img)
         B.bdr_quantize(fh, x, out=ph)
         B.bdr_dequantize(fh, ph, rows, cols, out=y)
         B.bdr_quantize(fr, x, out=pr)
@@ -346,7 +349,8 @@ def aux_probe(B, S, torch):
         B.bdr_dequantize(fh, pc, 8192, 8192, axis=B.AXIS_COL, out=yc)
     torch.cuda.synchronize()
     print(json.dumps({"aux_probe": "3 x (1 GiB copy; MX9 bf16 8192x12288 column quantize, dequantize, fused, "
-                                   "row quantize, dequantize; MX6 gather 2^20 x 128 from planes and from the table image; k1 32 k2 2 d2 1 m 4 and "
+                                   "row quantize, dequantize; MX6 gather 2^20 x 128 from planes and from the table image; the same "
+                                   "bf16 tensor to the MX6 operand image, row and column blocks; k1 32 k2 2 d2 1 m 4 and "
                                    "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32; k1 32 k2 2 d2 1 m 4 "
                                    "column quantize, dequantize on 8192 x 8192 fp32)"}))
 
