@@ -31,6 +31,19 @@ def test_calls_replay_from_a_graph():
     ph = B.alloc_planes(fh, rows, cols)
     yh = torch.empty_like(x)
     Cp = torch.empty(M, N, device="cuda")
+    # the calls added for tables, operand images, BF16 results and ragged shapes
+    idx = torch.randint(0, rows, (300,), device="cuda", dtype=torch.int64,
+                        generator=torch.Generator(device="cuda").manual_seed(3))
+    table = torch.empty(rows * B.bdr_table_row_bytes(f, cols), dtype=torch.uint8, device="cuda")
+    yt = torch.empty(300, cols, device="cuda")
+    ia = torch.empty(B.mx_operand_bytes(f, M, cols), dtype=torch.uint8, device="cuda")
+    ib = torch.empty(B.mx_operand_bytes(f, cols, rows), dtype=torch.uint8, device="cuda")
+    Co = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    Ct = torch.empty(cols, cols, device="cuda")
+    Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    xr = x[:, :1000]                             # rows with a short last block, pitched
+    pr = B.alloc_planes(f, rows, 1000)
+    yr = torch.zeros(rows, 1000, device="cuda")
 
     def work():
         B.bdr_quantize(f, x, out=planes)
@@ -43,6 +56,15 @@ def test_calls_replay_from_a_graph():
         B.bdr_quantize(fh, x, out=ph)
         B.bdr_dequantize(fh, ph, rows, cols, out=yh)
         B.mx_dot_pipeline(f, f, pa, pa, M, N, cols, r=256, out=Cp, workspace=gws)
+        B.bdr_table_pack(f, planes, rows, cols, out=table)
+        B.bdr_table_gather_dequantize(f, table, rows, cols, idx, out=yt)
+        B.bdr_quantize_operand(f, x[:M], out=ia)
+        B.mx_gemm_operands(f, f, ia, ia, M, N, cols, out=Co)
+        B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=True, out=ib)     # image of x^T [cols x rows]
+        B.mx_gemm_operands(f, f, ib, ib, cols, cols, rows, out=Ct)
+        B.mx_gemm(f, f, pa, pa, M, N, cols, out=Cb, workspace=gws)
+        B.bdr_quantize(f, xr, out=pr)
+        B.bdr_dequantize(f, pr, rows, 1000, out=yr)
 
     x.copy_(S.wide_range(rows, cols, device="cuda", seed=0, spread=3))
     work()                      # first use outside the capture (one-time kernel attributes)
@@ -54,7 +76,8 @@ def test_calls_replay_from_a_graph():
         x.copy_(S.wide_range(rows, cols, device="cuda", seed=seed, spread=3))
         graph.replay()
         torch.cuda.synchronize()
-        every = (*planes, y, yf, out[0], out[1], C, out_s[0], out_s[1], *ph, yh, Cp)
+        every = (*planes, y, yf, out[0], out[1], C, out_s[0], out_s[1], *ph, yh, Cp, table, yt, ia, Co, ib, Ct,
+                 Cb, *pr, yr)
         got = [t.clone() for t in every]
         for t in every:
             t.zero_()           # eager work of the program between replays
