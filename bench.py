@@ -519,7 +519,7 @@ def other_legs(B, S, torch, timed):
         leg6 = {}
         ab6 = r * c * 3
         for axis, name in ((B.AXIS_ROW, "row"), (B.AXIS_COL, "col")):
-            img = torch.empty(B.mx_operand_bytes(B.MX6, r, c), dtype=torch.uint8, device="cuda")
+            img = torch.empty(B.mx_operand_bytes(B.MX6, r, c), dtype=torch.uint8, device="cuda")  # FP6 image
             k = [0]
 
             def runo():

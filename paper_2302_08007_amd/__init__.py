@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libbdr_mx.so")
 RNE, RNA, RTZ = 0, 1, 2
 F32, BF16 = 0, 1
 AXIS_ROW, AXIS_COL = 0, 1
+OPERAND_FP6, OPERAND_BF16 = 0, 1
 OK = 0
 
 EXPORTS = (
@@ -85,10 +86,10 @@ def _load():
     L.mx_gemm_workspace_bytes.restype = SZ
     L.mx_gemm.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I64, P, SZ, P]
     L.mx_gemm_to.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, P, I32, I64, P, SZ, P]
-    L.mx_operand_bytes.argtypes = [FP, I64, I64]
+    L.mx_operand_bytes.argtypes = [FP, I64, I64, I32]
     L.mx_operand_bytes.restype = SZ
-    L.bdr_quantize_operand.argtypes = [FP, P, I32, I64, I64, I64, I32, I32, P, P]
-    L.mx_gemm_operands.argtypes = [FP, FP, P, P, I64, I64, I64, P, I32, I64, P]
+    L.bdr_quantize_operand.argtypes = [FP, P, I32, I64, I64, I64, I32, I32, I32, P, P]
+    L.mx_gemm_operands.argtypes = [FP, FP, P, P, I32, I64, I64, I64, P, I32, I64, P]
     L.mx_dot_pipeline_workspace_bytes.argtypes = [I64, I64, I64]
     L.mx_dot_pipeline_workspace_bytes.restype = SZ
     L.mx_dot_pipeline.argtypes = [FP, FP, P, P, P, P, P, P, I64, I64, I64, I64, I32, P, I64, P, SZ, P]
@@ -321,39 +322,36 @@ def mx_gemm(fa, fb, a_planes, b_planes, M, N, K, out=None, workspace=None, dtype
     return C
 
 
-def mx_operand_bytes(fmt, rows, K):
-    return int(lib.mx_operand_bytes(ctypes.byref(fmt), rows, K))
+def mx_operand_bytes(fmt, rows, K, image=OPERAND_FP6):
+    return int(lib.mx_operand_bytes(ctypes.byref(fmt), rows, K, image))
 
 
-def bdr_quantize_operand(fmt, x, axis=AXIS_ROW, b_operand=False, out=None):
-    """Quantize x (MX6 or MX4) straight into the image the FP6 product kernel reads: the image
+def bdr_quantize_operand(fmt, x, axis=AXIS_ROW, image=OPERAND_FP6, b_operand=False, out=None):
+    """Quantize x straight into an image the product kernel reads (OPERAND_FP6: MX6 / MX4 for the
+    block-scaled FP6 product; OPERAND_BF16: any Table II format for the BF16 product): the image
     of x itself (axis ROW, K = columns) or of its transpose (axis COL, K = rows).  Returns a
     uint8 tensor."""
     rows, cols, ld = _dev2d(x)
     op_rows, K = (rows, cols) if axis == AXIS_ROW else (cols, rows)
-    need = mx_operand_bytes(fmt, op_rows, K)
+    need = mx_operand_bytes(fmt, op_rows, K, image)
     img = out if out is not None else torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    if need == 0 and rows * cols != 0:
-        _check(lib.bdr_quantize_operand(ctypes.byref(fmt), _p(x), _dtype_code(x), rows, cols, ld, axis,
-                                        int(b_operand), None, _stream()))   # reports why
-        raise ValueError("this operand is not taken")
     _check_buffer("image", img, torch.uint8, need)
-    _check(lib.bdr_quantize_operand(ctypes.byref(fmt), _p(x), _dtype_code(x), rows, cols, ld, axis,
+    _check(lib.bdr_quantize_operand(ctypes.byref(fmt), _p(x), _dtype_code(x), rows, cols, ld, axis, image,
                                     int(b_operand), _p(img), _stream()))
     return img
 
 
-def mx_gemm_operands(fa, fb, image_a, image_b, M, N, K, out=None, dtype=None):
-    """C[M, N] = A B^T from two operand images made by bdr_quantize_operand."""
+def mx_gemm_operands(fa, fb, image_a, image_b, M, N, K, image=OPERAND_FP6, out=None, dtype=None):
+    """C[M, N] = A B^T from two operand images of the same kind made by bdr_quantize_operand."""
     dtype = out.dtype if out is not None else (dtype or torch.float32)
     C = out if out is not None else torch.empty((M, N), dtype=dtype, device=image_a.device)
     if not (C.is_cuda and C.dtype in (torch.float32, torch.bfloat16) and C.dim() == 2
             and tuple(C.shape) == (M, N) and C.stride(1) == 1):
         raise ValueError("output must be an [M x N] float32 or bfloat16 GPU tensor with unit column stride")
-    _check_buffer("image_a", image_a, torch.uint8, mx_operand_bytes(fa, M, K))
-    _check_buffer("image_b", image_b, torch.uint8, mx_operand_bytes(fb, N, K))
-    _check(lib.mx_gemm_operands(ctypes.byref(fa), ctypes.byref(fb), _p(image_a), _p(image_b), M, N, K, _p(C),
-                                _dtype_code(C), C.stride(0), _stream()))
+    _check_buffer("image_a", image_a, torch.uint8, mx_operand_bytes(fa, M, K, image))
+    _check_buffer("image_b", image_b, torch.uint8, mx_operand_bytes(fb, N, K, image))
+    _check(lib.mx_gemm_operands(ctypes.byref(fa), ctypes.byref(fb), _p(image_a), _p(image_b), image, M, N, K,
+                                _p(C), _dtype_code(C), C.stride(0), _stream()))
     return C
 
 

@@ -428,46 +428,57 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
                       workspace, workspace_bytes, hip_stream);
 }
 
-// ---- operands made by the quantizer itself (block-scaled FP6 images)
+// ---- operands made by the quantizer itself
 
-static bool fp6_operand_format(const bdr_format *f) { return bdr::is_mx(*f) && f->m <= 4; }
-
-size_t mx_operand_bytes(const bdr_format *fmt, int64_t rows, int64_t K)
+// FP6 images hold MX6 and MX4; BF16 images any of Table II's formats.  Nearest even only: that is
+// what the specialised quantizers implement.
+static bool operand_format(const bdr_format *f, int image)
 {
-    if (check_format(fmt) != BDR_OK || !fp6_operand_format(fmt)) return 0;
+    return bdr::is_mx(*f) && (image == BDR_OPERAND_BF16 || f->m <= 4);
+}
+static bool operand_image(int image) { return image == BDR_OPERAND_FP6 || image == BDR_OPERAND_BF16; }
+
+size_t mx_operand_bytes(const bdr_format *fmt, int64_t rows, int64_t K, int image)
+{
+    if (check_format(fmt) != BDR_OK || !operand_image(image) || !operand_format(fmt, image)) return 0;
     if (rows < 0 || K < 0 || K % 64 != 0 || rows > (1 << 20) || K > (1 << 20)) return 0;
-    return (size_t)rows * (size_t)K;  // a 16-byte chunk per block of 16
+    // FP6: a 16-byte chunk per block of 16; BF16: two bytes per element
+    return (size_t)rows * (size_t)K * (image == BDR_OPERAND_BF16 ? 2u : 1u);
 }
 
 int bdr_quantize_operand(const bdr_format *fmt, const void *x, int dtype, int64_t rows, int64_t cols,
-                         int64_t ld, int axis, int b_operand, void *image, void *hip_stream)
+                         int64_t ld, int axis, int image, int b_operand, void *out, void *hip_stream)
 {
     int st = check_format(fmt);
     if (st) return st;
-    if (!fp6_operand_format(fmt)) return BDR_ERR_FORMAT;
+    if (!operand_image(image)) return BDR_ERR_SHAPE;
+    if (!operand_format(fmt, image)) return BDR_ERR_FORMAT;
     if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
     if (axis != BDR_AXIS_ROW && axis != BDR_AXIS_COL) return BDR_ERR_SHAPE;
     if (rows < 0 || cols < 0 || ld < cols || rows > (1 << 20) || cols > (1 << 20)) return BDR_ERR_SHAPE;
-    if (axis == BDR_AXIS_ROW ? cols % 64 != 0 : !bdr::quantize_fp6_col_ok(dtype, rows, cols)) return BDR_ERR_SHAPE;
+    if (axis == BDR_AXIS_ROW ? cols % 64 != 0 : !bdr::quantize_operand_col_ok(dtype, rows, cols)) return BDR_ERR_SHAPE;
     if (rows == 0 || cols == 0) return BDR_OK;
     st = check_tensor_ptr(x, dtype, ld);
     if (st) return st;
-    if (!image) return BDR_ERR_NULL;
-    if (!aligned16(image)) return BDR_ERR_ALIGN;
+    if (!out) return BDR_ERR_NULL;
+    if (!aligned16(out)) return BDR_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (axis == BDR_AXIS_ROW) return bdr::quantize_fp6_row(*fmt, x, dtype, rows, cols, ld, image, b_operand != 0, s);
-    return bdr::quantize_fp6_col(*fmt, x, dtype, rows, cols, ld, image, b_operand != 0, s);
+    const int kind = image == BDR_OPERAND_BF16 ? 2 : (b_operand ? 1 : 0);
+    if (axis == BDR_AXIS_ROW) return bdr::quantize_operand_row(*fmt, x, dtype, rows, cols, ld, out, kind, s);
+    return bdr::quantize_operand_col(*fmt, x, dtype, rows, cols, ld, out, kind, s);
 }
 
 int mx_gemm_operands(const bdr_format *fa, const bdr_format *fb, const void *image_a, const void *image_b,
-                     int64_t M, int64_t N, int64_t K, void *C, int c_dtype, int64_t ldc, void *hip_stream)
+                     int image, int64_t M, int64_t N, int64_t K, void *C, int c_dtype, int64_t ldc,
+                     void *hip_stream)
 {
     if (c_dtype != BDR_F32 && c_dtype != BDR_BF16) return BDR_ERR_DTYPE;
     int st = check_format(fa);
     if (st) return st;
     st = check_format(fb);
     if (st) return st;
-    if (!fp6_operand_format(fa) || !fp6_operand_format(fb)) return BDR_ERR_FORMAT;
+    if (!operand_image(image)) return BDR_ERR_SHAPE;
+    if (!operand_format(fa, image) || !operand_format(fb, image)) return BDR_ERR_FORMAT;
     if (M < 0 || N < 0 || K < 0 || ldc < N || K % 64 != 0) return BDR_ERR_SHAPE;
     if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
     if (M == 0 || N == 0) return BDR_OK;
@@ -479,6 +490,11 @@ int mx_gemm_operands(const bdr_format *fa, const bdr_format *fb, const void *ima
         return bdr::gemm(*fa, *fb, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, M, N, 0, C, ldc, c_bf16, s);
     if (!image_a || !image_b) return BDR_ERR_NULL;
     if (!aligned16(image_a) || !aligned16(image_b)) return BDR_ERR_ALIGN;
+    if (image == BDR_OPERAND_BF16) {
+        st = bdr::gemm_bf16_tiled(image_a, image_b, M, N, K, C, ldc, c_bf16, true, s);
+        if (st) return st;
+        return bdr::gemm_bf16_tiled(image_a, image_b, M, N, K, C, ldc, c_bf16, false, s);
+    }
     st = bdr::gemm_fp6(image_a, image_b, M, N, K, C, ldc, c_bf16, true, s);
     if (st) return st;
     return bdr::gemm_fp6(image_a, image_b, M, N, K, C, ldc, c_bf16, false, s);

@@ -284,14 +284,16 @@ __global__ __launch_bounds__((col_threads<T, MODE>())) void mx_col_kernel(
     }
 }
 
-// Column blocks quantized straight into the operand image of the block-scaled FP6 product
-// (see mx_quantize_fp6_row_kernel): the operand is the transpose, so its rows are the
-// tensor's columns and its K index the tensor's row.  The same tile, the same lane per block;
-// a tile gives every one of its columns eight chunks, 64 consecutive bytes in each of two K
-// steps, and the columns of a tile follow each other in the image, so a tile writes two runs
-// of 64 bytes x its columns: no partial lines, no neighbours to wait for.
-template <int MB, typename T, bool B_OPERAND>
-__global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_fp6_kernel(
+// Column blocks quantized straight into an operand image of the product kernel (see
+// mx_quantize_operand_row_kernel): the operand is the transpose, so its rows are the tensor's
+// columns and its K index the tensor's row.  The same tile, the same lane per block; a tile gives
+// every one of its columns eight blocks, i.e. whole 64-byte pieces in two (FP6) or four (BF16) K
+// steps, and the columns of a tile follow each other in the image, so a tile writes runs of
+// 64 bytes x its columns: no partial lines, no neighbours to wait for.
+constexpr int kOperandFp6B = 1, kOperandBf16 = 2;  // (0: FP6, A operand)
+
+template <int MB, typename T, int KIND>
+__global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
     const T *x, u32x4 *__restrict__ out, int64_t cols, int64_t ld)
 {
     constexpr int kTC = TileGeom<T>::kTC;
@@ -308,28 +310,45 @@ __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_fp6_kernel(
     uint32_t xb[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) xb[i] = lds_get(tile, lds_off<T>(16 * b + i, c), T());
-    const u32x4 chunk = mx_quant_fp6_block<MB, B_OPERAND>(xb);
     const int64_t kb = (r0 >> 4) + b;
-    stg<true>(chunk, out + (((kb >> 2) * cols + (c0 + c)) * 4 + (kb & 3)));
+    if constexpr (KIND == kOperandBf16) {
+        u32x4 lo, hi;
+        mx_quant_bf16_block<MB>(xb, lo, hi);
+        u32x4 *dst = out + (((kb >> 1) * cols + (c0 + c)) * 4 + 2 * (kb & 1));
+        stg<true>(lo, dst);
+        stg<true>(hi, dst + 1);
+    } else {
+        const u32x4 chunk = mx_quant_fp6_block<MB, KIND == kOperandFp6B>(xb);
+        stg<true>(chunk, out + (((kb >> 2) * cols + (c0 + c)) * 4 + (kb & 3)));
+    }
+}
+
+template <int MB, typename T>
+void launch_operand_col(int kind, dim3 grid, hipStream_t s, const T *x, u32x4 *o, int64_t cols, int64_t ld)
+{
+    const dim3 block(col_threads<T, 0>());
+    if (kind == kOperandBf16)
+        hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, kOperandBf16>), grid, block, 0, s, x, o, cols, ld);
+    else if constexpr (MB <= 4) {
+        if (kind == kOperandFp6B)
+            hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, kOperandFp6B>), grid, block, 0, s, x, o, cols, ld);
+        else
+            hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, 0>), grid, block, 0, s, x, o, cols, ld);
+    }
 }
 
 template <typename T>
-int quantize_fp6_col_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld, void *out,
-                       bool b_operand, hipStream_t s)
+int quantize_operand_col_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld, void *out,
+                           int kind, hipStream_t s)
 {
-    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC)), block(col_threads<T, 0>());
+    const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC));
     u32x4 *o = (u32x4 *)out;
-    if (f.m == 4) {
-        if (b_operand)
-            hipLaunchKernelGGL((mx_col_fp6_kernel<4, T, true>), grid, block, 0, s, x, o, cols, ld);
-        else
-            hipLaunchKernelGGL((mx_col_fp6_kernel<4, T, false>), grid, block, 0, s, x, o, cols, ld);
-    } else {
-        if (b_operand)
-            hipLaunchKernelGGL((mx_col_fp6_kernel<2, T, true>), grid, block, 0, s, x, o, cols, ld);
-        else
-            hipLaunchKernelGGL((mx_col_fp6_kernel<2, T, false>), grid, block, 0, s, x, o, cols, ld);
-    }
+    if (f.m == 7)
+        launch_operand_col<7, T>(kind, grid, s, x, o, cols, ld);
+    else if (f.m == 4)
+        launch_operand_col<4, T>(kind, grid, s, x, o, cols, ld);
+    else
+        launch_operand_col<2, T>(kind, grid, s, x, o, cols, ld);
     return launch_status();
 }
 
@@ -608,19 +627,19 @@ int col_any(int mode, const bdr_format &f, const void *x, void *y, int dtype, in
 }  // namespace
 
 // x [rows x cols] with blocks down the columns (K = rows): rows a multiple of 128, cols of the
-// tile width (64 FP32 / 128 BF16 columns); f is MX6 or MX4.  false: the shape is not made of
-// whole tiles (the caller reports it).
-bool quantize_fp6_col_ok(int dtype, int64_t rows, int64_t cols)
+// tile width (64 FP32 / 128 BF16 columns).  false: the shape is not made of whole tiles (the
+// caller reports it).
+bool quantize_operand_col_ok(int dtype, int64_t rows, int64_t cols)
 {
     const int tc = dtype == BDR_F32 ? TileGeom<float>::kTC : TileGeom<uint16_t>::kTC;
     return rows % kTR == 0 && cols % tc == 0 && cols / tc <= 65535;
 }
 
-int quantize_fp6_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
-                     void *out, bool b_operand, hipStream_t s)
+int quantize_operand_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                         void *out, int kind, hipStream_t s)
 {
-    if (dtype == BDR_F32) return quantize_fp6_col_t(f, (const float *)x, rows, cols, ld, out, b_operand, s);
-    return quantize_fp6_col_t(f, (const uint16_t *)x, rows, cols, ld, out, b_operand, s);
+    if (dtype == BDR_F32) return quantize_operand_col_t(f, (const float *)x, rows, cols, ld, out, kind, s);
+    return quantize_operand_col_t(f, (const uint16_t *)x, rows, cols, ld, out, kind, s);
 }
 
 int quantize_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols,

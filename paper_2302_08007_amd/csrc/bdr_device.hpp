@@ -371,6 +371,21 @@ __device__ __forceinline__ u32x4 mx_quant_fp6_block(const uint32_t (&xb)[16])
     return u32x4{w[0], w[1], w[2], (uint32_t)scale << (B_OPERAND ? 16 : 0)};
 }
 
+// One whole Table II block held by one lane, quantized (nearest even) and written out as its 16
+// dequantized values in BF16 (exact: m + 1 <= 8 significant bits), two per dword: the 32 bytes
+// the block takes in the BF16 operand image of the product kernel.
+template <int MB>
+__device__ __forceinline__ void mx_quant_bf16_block(const uint32_t (&xb)[16], u32x4 &lo, u32x4 &hi)
+{
+    uint32_t ww[MxWords<MB, 8>::kN], se, tau8, yb[16];
+    mx_quant_lane<MB, 8, 0, true>(xb, ww, se, tau8, yb);
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[j] = __builtin_amdgcn_perm(yb[2 * j + 1], yb[2 * j], 0x07060302u);
+    lo = u32x4{w[0], w[1], w[2], w[3]};
+    hi = u32x4{w[4], w[5], w[6], w[7]};
+}
+
 // A format tuple as the general (run-time-tuple) kernels take it.
 struct GenFmt {
     int k1, k2, d2, m, rounding;

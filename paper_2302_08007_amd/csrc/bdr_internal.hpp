@@ -107,14 +107,15 @@ int to_fp6(const bdr_format &f, const void *codes, const void *sexp, const void 
            int64_t rows, int64_t K, void *out, bool b_operand, hipStream_t s);
 int gemm_fp6(const void *A, const void *B, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
              bool dry, hipStream_t s);
-// Quantize (MX6 or MX4, nearest even) straight into that FP6 image: blocks along the rows of
-// x [rows x cols] (the operand is x, K = cols), or down its columns (the operand is the
-// transpose, K = rows; whole tiles only: quantize_fp6_col_ok).
-int quantize_fp6_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
-                     void *out, bool b_operand, hipStream_t s);
-bool quantize_fp6_col_ok(int dtype, int64_t rows, int64_t cols);
-int quantize_fp6_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
-                     void *out, bool b_operand, hipStream_t s);
+// Quantize (Table II, nearest even) straight into an operand image: kind 0 / 1 the FP6 image of an
+// A / B operand (MX6, MX4), kind 2 the BF16 image (to_bf16_tiled's).  Blocks along the rows of x
+// [rows x cols] (the operand is x, K = cols), or down its columns (the operand is the transpose,
+// K = rows; whole tiles only: quantize_operand_col_ok).
+int quantize_operand_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                         void *out, int kind, hipStream_t s);
+bool quantize_operand_col_ok(int dtype, int64_t rows, int64_t cols);
+int quantize_operand_col(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                         void *out, int kind, hipStream_t s);
 // The FP4 form of the two-pass product (MX4 x MX4): image writer, size of its scale image,
 // and the product on two such images (K_out % 128 == 0).
 int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, int64_t K, int64_t K_out,

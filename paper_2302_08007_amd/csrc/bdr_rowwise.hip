@@ -1085,15 +1085,20 @@ static int generic_view_t(int what, const bdr_format &f, const T *x, T *y, int64
     return launch_status();
 }
 
-// ---- quantize straight into the operand image of the block-scaled FP6 product
+// ---- quantize straight into an operand image of the product kernel
 //
 // For a tensor that is quantized only to be multiplied (Sec. V: both inputs of every tensor
 // operation of a training iteration), the three planes are a detour: the product's two-pass
 // form would read them back at once and rewrite them as the image its kernel takes.  Here
-// the quantizer writes that image itself: one lane per block of 16, the block's 16-byte
-// chunk (mx_quant_fp6_block) stored at [K step of 4 blocks][row][4 chunks].
-template <int MB, typename T, bool B_OPERAND>
-__global__ __launch_bounds__(kThreads) void mx_quantize_fp6_row_kernel(
+// the quantizer writes that image itself, one lane per block of 16:
+//   KIND 0 / 1: the block's 16-byte FP6 chunk for an A / B operand (mx_quant_fp6_block), stored at
+//               [K step of 4 blocks][row][4 chunks];
+//   KIND 2:     the block's 16 dequantized BF16 values (mx_quant_bf16_block), stored at
+//               [K step of 2 blocks][row][4 chunks of 8 values].
+constexpr int kOperandFp6A = 0, kOperandFp6B = 1, kOperandBf16 = 2;
+
+template <int MB, typename T, int KIND>
+__global__ __launch_bounds__(kThreads) void mx_quantize_operand_row_kernel(
     const T *__restrict__ x, int64_t n_blocks, int64_t rows, int32_t row_blocks, int64_t ld,
     u32x4 *__restrict__ out)
 {
@@ -1102,60 +1107,70 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_fp6_row_kernel(
     const int64_t row = bi / row_blocks;
     const int32_t kb = (int32_t)(bi - row * row_blocks);
     const T *src = x + row * ld + 16 * (int64_t)kb;
-    uint32_t xb[16];
+    uint32_t xb[16], lo[8], hi[8];
     if constexpr (sizeof(T) == 4) {
-        uint32_t lo[8], hi[8];
         load8(src, lo);
         load8(src + 8, hi);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            xb[i] = lo[i];
-            xb[8 + i] = hi[i];
-        }
     } else {
-        const u32x4 a = ldg<true>(reinterpret_cast<const u32x4 *>(src));
-        const u32x4 b = ldg<true>(reinterpret_cast<const u32x4 *>(src) + 1);
-        uint32_t lo[8], hi[8];
-        widen8(a, lo);
-        widen8(b, hi);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            xb[i] = lo[i];
-            xb[8 + i] = hi[i];
-        }
+        widen8(ldg<true>(reinterpret_cast<const u32x4 *>(src)), lo);
+        widen8(ldg<true>(reinterpret_cast<const u32x4 *>(src) + 1), hi);
     }
-    const u32x4 chunk = mx_quant_fp6_block<MB, B_OPERAND>(xb);
-    stg<true>(chunk, out + (((int64_t)(kb >> 2) * rows + row) * 4 + (kb & 3)));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        xb[i] = lo[i];
+        xb[8 + i] = hi[i];
+    }
+    if constexpr (KIND == kOperandBf16) {
+        u32x4 a, b;
+        mx_quant_bf16_block<MB>(xb, a, b);
+        u32x4 *dst = out + (((int64_t)(kb >> 1) * rows + row) * 4 + 2 * (kb & 1));
+        stg<true>(a, dst);
+        stg<true>(b, dst + 1);
+    } else {
+        const u32x4 chunk = mx_quant_fp6_block<MB, KIND == kOperandFp6B>(xb);
+        stg<true>(chunk, out + (((int64_t)(kb >> 2) * rows + row) * 4 + (kb & 3)));
+    }
+}
+
+template <int MB, typename T>
+static void launch_operand_row(int kind, dim3 grid, hipStream_t s, const T *x, int64_t nb, int64_t rows,
+                               int32_t rb, int64_t ld, u32x4 *o)
+{
+    const dim3 block(kThreads);
+    if (kind == kOperandBf16)
+        hipLaunchKernelGGL((mx_quantize_operand_row_kernel<MB, T, kOperandBf16>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+    else if constexpr (MB <= 4) {
+        if (kind == kOperandFp6B)
+            hipLaunchKernelGGL((mx_quantize_operand_row_kernel<MB, T, kOperandFp6B>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+        else
+            hipLaunchKernelGGL((mx_quantize_operand_row_kernel<MB, T, kOperandFp6A>), grid, block, 0, s, x, nb, rows, rb, ld, o);
+    }
 }
 
 template <typename T>
-static int quantize_fp6_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
-                              void *out, bool b_operand, hipStream_t s)
+static int quantize_operand_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
+                                  void *out, int kind, hipStream_t s)
 {
     const int64_t nb = rows * (cols / 16);
-    const dim3 grid(blocks_for(nb)), block(kThreads);
+    const dim3 grid(blocks_for(nb));
     u32x4 *o = (u32x4 *)out;
     const int32_t rb = (int32_t)(cols / 16);
-    if (f.m == 4) {
-        if (b_operand)
-            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<4, T, true>), grid, block, 0, s, x, nb, rows, rb, ld, o);
-        else
-            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<4, T, false>), grid, block, 0, s, x, nb, rows, rb, ld, o);
-    } else {
-        if (b_operand)
-            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<2, T, true>), grid, block, 0, s, x, nb, rows, rb, ld, o);
-        else
-            hipLaunchKernelGGL((mx_quantize_fp6_row_kernel<2, T, false>), grid, block, 0, s, x, nb, rows, rb, ld, o);
-    }
+    if (f.m == 7)
+        launch_operand_row<7, T>(kind, grid, s, x, nb, rows, rb, ld, o);
+    else if (f.m == 4)
+        launch_operand_row<4, T>(kind, grid, s, x, nb, rows, rb, ld, o);
+    else
+        launch_operand_row<2, T>(kind, grid, s, x, nb, rows, rb, ld, o);
     return launch_status();
 }
 
-// x [rows x cols], blocks along the rows' own direction (K = cols, a multiple of 64); f is MX6 or MX4.
-int quantize_fp6_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
-                     void *out, bool b_operand, hipStream_t s)
+// x [rows x cols], blocks along the rows' own direction (K = cols, a multiple of 64); f is one of
+// Table II's formats (the FP6 kinds: MX6 or MX4), kind one of kOperand*.
+int quantize_operand_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                         void *out, int kind, hipStream_t s)
 {
-    if (dtype == BDR_F32) return quantize_fp6_row_t(f, (const float *)x, rows, cols, ld, out, b_operand, s);
-    return quantize_fp6_row_t(f, (const uint16_t *)x, rows, cols, ld, out, b_operand, s);
+    if (dtype == BDR_F32) return quantize_operand_row_t(f, (const float *)x, rows, cols, ld, out, kind, s);
+    return quantize_operand_row_t(f, (const uint16_t *)x, rows, cols, ld, out, kind, s);
 }
 
 // Column blocks: the transposed view [cols x rows].

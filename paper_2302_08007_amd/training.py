@@ -17,8 +17,8 @@ orders the calls and plugs them into autograd.  Element-wise work stays in the c
 """
 import torch
 
-from . import (AXIS_COL, AXIS_ROW, bdr_quantize, bdr_quantize_operand, mx_gemm, mx_gemm_operands,
-               mx_gemm_workspace_bytes, mx_operand_bytes)
+from . import (AXIS_COL, AXIS_ROW, OPERAND_BF16, OPERAND_FP6, bdr_quantize, bdr_quantize_operand, mx_gemm,
+               mx_gemm_operands, mx_gemm_workspace_bytes, mx_operand_bytes)
 
 _workspaces = {}
 
@@ -45,23 +45,25 @@ def _mx_matmul(fa, fb, a, a_axis, b, b_axis, M, N, K, out_dtype):
     """C[M, N] = Q(a) Q(b)^T with a, b quantized along the K axis of the product; C comes out in
     out_dtype (FP32 sums; a BF16 C is rounded as the product kernel stores it, not in a pass of
     its own)."""
-    if _direct(fa, a, a_axis, M, K) and _direct(fb, b, b_axis, N, K):
-        # MX6 / MX4: the quantizer writes the product kernel's operand images itself (no planes, no
-        # rewriting pass); the two images share the stream's scratch buffer
-        na, nb = mx_operand_bytes(fa, M, K), mx_operand_bytes(fb, N, K)
+    image = OPERAND_FP6 if fa.m <= 4 and fb.m <= 4 else OPERAND_BF16
+    if _direct(fa, a, a_axis, M, K, image) and _direct(fb, b, b_axis, N, K, image):
+        # the quantizer writes the product kernel's operand images itself (no planes, no rewriting
+        # pass): FP6 images when both formats have m <= 4, BF16 images when MX9 takes part; the two
+        # images share the stream's scratch buffer
+        na, nb = mx_operand_bytes(fa, M, K, image), mx_operand_bytes(fb, N, K, image)
         ws = _workspace(a.device, na + nb)
-        ia = bdr_quantize_operand(fa, a, axis=a_axis, b_operand=False, out=ws[:na])
-        ib = bdr_quantize_operand(fb, b, axis=b_axis, b_operand=True, out=ws[na:na + nb])
-        return mx_gemm_operands(fa, fb, ia, ib, M, N, K, dtype=out_dtype)
+        ia = bdr_quantize_operand(fa, a, axis=a_axis, image=image, b_operand=False, out=ws[:na])
+        ib = bdr_quantize_operand(fb, b, axis=b_axis, image=image, b_operand=True, out=ws[na:na + nb])
+        return mx_gemm_operands(fa, fb, ia, ib, M, N, K, image=image, dtype=out_dtype)
     pa = bdr_quantize(fa, a, axis=a_axis)
     pb = bdr_quantize(fb, b, axis=b_axis)
     ws = _workspace(a.device, mx_gemm_workspace_bytes(M, N, K))
     return mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws, dtype=out_dtype)
 
 
-def _direct(f, t, axis, op_rows, K):
+def _direct(f, t, axis, op_rows, K, image):
     """Whether bdr_quantize_operand takes this operand (format, and whole tiles for column blocks)."""
-    if mx_operand_bytes(f, op_rows, K) == 0 or t.stride(0) * t.element_size() % 16:
+    if mx_operand_bytes(f, op_rows, K, image) == 0 or t.stride(0) * t.element_size() % 16:
         return False
     if axis == AXIS_ROW:
         return True

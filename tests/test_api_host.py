@@ -262,23 +262,28 @@ def test_table_image_argument_checks():
 
 def test_operand_image_argument_checks():
     L, f = B.lib, B.MX6
-    assert B.mx_operand_bytes(B.MX6, 128, 256) == 128 * 256 == B.mx_operand_bytes(B.MX4, 128, 256)
-    assert B.mx_operand_bytes(B.MX9, 128, 256) == 0                    # BF16 products: not this image
+    FP6, BF = B.OPERAND_FP6, B.OPERAND_BF16
+    assert B.mx_operand_bytes(B.MX6, 128, 256) == 128 * 256 == B.mx_operand_bytes(B.MX4, 128, 256, FP6)
+    assert B.mx_operand_bytes(B.MX9, 128, 256, FP6) == 0               # MX9 does not fit E2M3
+    assert B.mx_operand_bytes(B.MX9, 128, 256, BF) == 2 * 128 * 256 == B.mx_operand_bytes(B.MX4, 128, 256, BF)
     assert B.mx_operand_bytes(B.fmt(16, 2, 1, 4, rounding=B.RTZ), 128, 256) == 0
     assert B.mx_operand_bytes(B.MX6, 128, 100) == 0 and B.mx_operand_bytes(B.MX6, -1, 64) == 0
-    qo = lambda fm=f, x=FAKE, dtype=0, rows=128, cols=128, ld=128, axis=0, img=FAKE: L.bdr_quantize_operand(
-        ctypes.byref(fm), x, dtype, rows, cols, ld, axis, 0, img, NULL)
+    assert B.mx_operand_bytes(B.MX6, 128, 256, 2) == 0
+    qo = lambda fm=f, x=FAKE, dtype=0, rows=128, cols=128, ld=128, axis=0, image=FP6, img=FAKE: \
+        L.bdr_quantize_operand(ctypes.byref(fm), x, dtype, rows, cols, ld, axis, image, 0, img, NULL)
     assert qo(fm=B.MX9) == ERR_FORMAT and qo(fm=B.fmt(32, 2, 1, 4)) == ERR_FORMAT and qo(dtype=2) == ERR_DTYPE
+    assert qo(fm=B.fmt(32, 2, 1, 4), image=BF) == ERR_FORMAT and qo(image=7) == ERR_SHAPE
     assert qo(cols=96, ld=96) == ERR_SHAPE and qo(axis=3) == ERR_SHAPE and qo(ld=64) == ERR_SHAPE
     assert qo(axis=1, rows=64) == ERR_SHAPE and qo(axis=1, cols=32, ld=32) == ERR_SHAPE
     assert qo(axis=1, dtype=1, cols=64, ld=64) == ERR_SHAPE            # BF16 tiles are 128 columns wide
     assert qo(x=NULL) == ERR_NULL and qo(img=NULL) == ERR_NULL
-    assert qo(x=FAKE_ODD) == ERR_ALIGN and qo(img=FAKE_ODD) == ERR_ALIGN and qo(rows=0) == OK
-    go = lambda fa=f, fb=f, a=FAKE, b=FAKE, M=128, N=128, K=64, C=FAKE, cd=0, ldc=128: L.mx_gemm_operands(
-        ctypes.byref(fa), ctypes.byref(fb), a, b, M, N, K, C, cd, ldc, NULL)
+    assert qo(fm=B.MX9, image=BF, x=FAKE_ODD) == ERR_ALIGN and qo(img=FAKE_ODD) == ERR_ALIGN and qo(rows=0) == OK
+    go = lambda fa=f, fb=f, a=FAKE, b=FAKE, image=FP6, M=128, N=128, K=64, C=FAKE, cd=0, ldc=128: \
+        L.mx_gemm_operands(ctypes.byref(fa), ctypes.byref(fb), a, b, image, M, N, K, C, cd, ldc, NULL)
     assert go(fa=B.MX9) == ERR_FORMAT and go(fb=B.fmt(16, 16, 0, 4)) == ERR_FORMAT and go(cd=5) == ERR_DTYPE
+    assert go(fa=B.fmt(16, 16, 0, 4), image=BF) == ERR_FORMAT and go(image=-1) == ERR_SHAPE
     assert go(K=48) == ERR_SHAPE and go(ldc=64) == ERR_SHAPE and go(M=-1) == ERR_SHAPE
-    assert go(C=NULL) == ERR_NULL and go(a=NULL) == ERR_NULL and go(b=NULL) == ERR_NULL
+    assert go(C=NULL) == ERR_NULL and go(a=NULL) == ERR_NULL and go(b=NULL, fa=B.MX9, image=BF) == ERR_NULL
     assert go(a=FAKE_ODD) == ERR_ALIGN and go(C=ctypes.c_void_p(0x10002)) == ERR_ALIGN and go(M=0) == OK
 
 

@@ -308,12 +308,14 @@ def test_strided_output_and_empty_k():
 def _two_step_images(fa, fb, pa, pb, M, N, K):
     """The operand images mx_gemm's two-pass form writes into its workspace from the (oracle-checked)
     planes: A's at the start, B's after A's half (an operand's half is rows * K BF16 values,
-    rounded up to 256 bytes)."""
+    rounded up to 256 bytes).  One byte per element for FP6 images (both formats m <= 4), two
+    for BF16 images (MX9 takes part)."""
     ws = _workspace(M, N, K)
     C = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=ws)
     torch.cuda.synchronize()
     half = (2 * M * K + 255) // 256 * 256
-    return ws[:M * K].clone(), ws[half:half + N * K].clone(), C
+    per = 1 if fa.m <= 4 and fb.m <= 4 else 2
+    return ws[:per * M * K].clone(), ws[half:half + per * N * K].clone(), C
 
 
 def _special(t, top=3.0e38):
@@ -330,7 +332,8 @@ def _special(t, top=3.0e38):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX4", "MX6"), ("MX6", "MX4")])
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX4", "MX6"), ("MX6", "MX4"), ("MX9", "MX9"), ("MX9", "MX4"),
+                                   ("MX6", "MX9")])
 @pytest.mark.parametrize("shape", [(128, 128, 64), (256, 384, 512), (130, 70, 128), (512, 256, 1024)])
 def test_operands_made_by_the_quantizer(shape, names, dtype):
     """bdr_quantize_operand writes, byte for byte, the image that mx_gemm's two-pass form makes of
@@ -345,14 +348,15 @@ def test_operands_made_by_the_quantizer(shape, names, dtype):
     for p, w in zip(pa, O.quantize(ofmt(fa), to_np(A))):
         assert np.array_equal(p.cpu().numpy(), w)
     ia, ib, C2 = _two_step_images(fa, fb, pa, pb, M, N, K)
-    ga = B.bdr_quantize_operand(fa, A, b_operand=False)
-    gb = B.bdr_quantize_operand(fb, Bm, b_operand=True)
+    image = B.OPERAND_FP6 if fa.m <= 4 and fb.m <= 4 else B.OPERAND_BF16     # (with MX9: BF16 images)
+    ga = B.bdr_quantize_operand(fa, A, image=image, b_operand=False)
+    gb = B.bdr_quantize_operand(fb, Bm, image=image, b_operand=True)
     torch.cuda.synchronize()
-    assert ga.numel() == M * K == B.mx_operand_bytes(fa, M, K) and gb.numel() == N * K
+    assert ga.numel() == ia.numel() == B.mx_operand_bytes(fa, M, K, image) and gb.numel() == ib.numel()
     assert torch.equal(ga, ia), "image of A"
     assert torch.equal(gb, ib), "image of B"
     for cd in (torch.float32, torch.bfloat16):
-        C = B.mx_gemm_operands(fa, fb, ga, gb, M, N, K, dtype=cd)
+        C = B.mx_gemm_operands(fa, fb, ga, gb, M, N, K, image=image, dtype=cd)
         want = B.mx_gemm(fa, fb, pa, pb, M, N, K, workspace=_workspace(M, N, K), dtype=cd)
         assert torch.equal(C.view(torch.int32 if cd == torch.float32 else torch.int16),
                            want.view(torch.int32 if cd == torch.float32 else torch.int16))
@@ -360,32 +364,34 @@ def test_operands_made_by_the_quantizer(shape, names, dtype):
     Cref = O.mx_gemm(ofmt(fa), ofmt(fb), pan, pbn, M, N, K)
     Ah = O.dequantize(ofmt(fa), *pan, M, K).astype(np.float64)
     Bh = O.dequantize(ofmt(fb), *pbn, N, K).astype(np.float64)
-    err = np.abs(B.mx_gemm_operands(fa, fb, ga, gb, M, N, K).cpu().numpy().astype(np.float64) - Cref)
+    err = np.abs(B.mx_gemm_operands(fa, fb, ga, gb, M, N, K, image=image).cpu().numpy().astype(np.float64) - Cref)
     assert np.all(err <= RTOL * (np.abs(Ah) @ np.abs(Bh).T) + 1e-30)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("name", ["MX6", "MX4"])
+@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16", "MX6 as BF16", "MX4 as BF16"])
 @pytest.mark.parametrize("shape", [(128, 128), (384, 256), (1024, 640)])
 def test_operands_of_the_transpose(shape, name, dtype):
     """Blocks down the columns: the image of the transpose of x equals the image made of the planes
     that column-wise bdr_quantize gives (those of the transposed tensor), in either role, also for
     a pitched view."""
     rows, cols = shape
-    f = getattr(B, name)
+    f = getattr(B, name[:3])
+    image = B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP6
+    partner = B.MX9 if image == B.OPERAND_BF16 else B.MX6      # makes the two-pass form write that kind
     big = _special(S.wide_range(rows, cols + 256, device="cuda", seed=rows + cols, spread=8)).to(dtype)
     for x in (big[:, :cols].contiguous(), big[:, 128:128 + cols]):
         planes = B.bdr_quantize(f, x, axis=B.AXIS_COL)          # = row-wise planes of x^T [cols x rows]
         want = O.quantize(ofmt(f), np.ascontiguousarray(to_np(x.contiguous()).T))
         for p, w in zip(planes, want):
             assert np.array_equal(p.cpu().numpy(), w)
-        # as operand A, then as operand B, of a product with an MX6 image of the same tensor (an
-        # MX4 x MX4 pair would take the FP4 form): the writer's images of this operand
-        other = B.bdr_quantize(B.MX6, x, axis=B.AXIS_COL)
-        ia, _, _ = _two_step_images(f, B.MX6, planes, other, cols, cols, rows)
-        _, ib, _ = _two_step_images(B.MX6, f, other, planes, cols, cols, rows)
-        assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=False), ia)
-        assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=True), ib)
+        # as operand A, then as operand B, of a product with a partner image of the same tensor (MX6:
+        # FP6 images, an MX4 x MX4 pair would take the FP4 form; MX9: BF16 images): the writer's images
+        other = B.bdr_quantize(partner, x, axis=B.AXIS_COL)
+        ia, _, _ = _two_step_images(f, partner, planes, other, cols, cols, rows)
+        _, ib, _ = _two_step_images(partner, f, other, planes, cols, cols, rows)
+        assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, image=image, b_operand=False), ia)
+        assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, image=image, b_operand=True), ib)
 
 
 def _bf16_rne(v):

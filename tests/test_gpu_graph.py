@@ -39,6 +39,8 @@ def test_calls_replay_from_a_graph():
     ia = torch.empty(B.mx_operand_bytes(f, M, cols), dtype=torch.uint8, device="cuda")
     ib = torch.empty(B.mx_operand_bytes(f, cols, rows), dtype=torch.uint8, device="cuda")
     Co = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    i9 = torch.empty(B.mx_operand_bytes(B.MX9, M, cols, B.OPERAND_BF16), dtype=torch.uint8, device="cuda")
+    C9 = torch.empty(M, N, device="cuda")
     Ct = torch.empty(cols, cols, device="cuda")
     Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
     xr = x[:, :1000]                             # rows with a short last block, pitched
@@ -60,6 +62,8 @@ def test_calls_replay_from_a_graph():
         B.bdr_table_gather_dequantize(f, table, rows, cols, idx, out=yt)
         B.bdr_quantize_operand(f, x[:M], out=ia)
         B.mx_gemm_operands(f, f, ia, ia, M, N, cols, out=Co)
+        B.bdr_quantize_operand(B.MX9, x[:M], image=B.OPERAND_BF16, out=i9)
+        B.mx_gemm_operands(B.MX9, B.MX9, i9, i9, M, N, cols, image=B.OPERAND_BF16, out=C9)
         B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=True, out=ib)     # image of x^T [cols x rows]
         B.mx_gemm_operands(f, f, ib, ib, cols, cols, rows, out=Ct)
         B.mx_gemm(f, f, pa, pa, M, N, cols, out=Cb, workspace=gws)
@@ -76,7 +80,7 @@ def test_calls_replay_from_a_graph():
         x.copy_(S.wide_range(rows, cols, device="cuda", seed=seed, spread=3))
         graph.replay()
         torch.cuda.synchronize()
-        every = (*planes, y, yf, out[0], out[1], C, out_s[0], out_s[1], *ph, yh, Cp, table, yt, ia, Co, ib, Ct,
+        every = (*planes, y, yf, out[0], out[1], C, out_s[0], out_s[1], *ph, yh, Cp, table, yt, ia, Co, ib, Ct, i9, C9,
                  Cb, *pr, yr)
         got = [t.clone() for t in every]
         for t in every:
