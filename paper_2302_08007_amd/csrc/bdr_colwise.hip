@@ -305,6 +305,8 @@ __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = lane & (kBPT - 1), c = kCPW * wave + lane / kBPT;  // one pass: THREADS = kBPT * kTC
     static_assert(THREADS == kBPT * kTC, "one lane per block of the tile");
+    __shared__ uint8_t s_map[KIND == kOperandBf16 ? 1 : 128];
+    if constexpr (KIND != kOperandBf16) fp6_map_fill<MB>(s_map);
     tile_load<T, THREADS>(x, ld, r0, c0, tile);
     __syncthreads();
     uint32_t xb[16];
@@ -318,7 +320,7 @@ __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
         stg<true>(lo, dst);
         stg<true>(hi, dst + 1);
     } else {
-        const u32x4 chunk = mx_quant_fp6_block<MB, KIND == kOperandFp6B>(xb);
+        const u32x4 chunk = mx_quant_fp6_block<MB, KIND == kOperandFp6B>(xb, s_map);
         stg<true>(chunk, out + (((kb >> 2) * cols + (c0 + c)) * 4 + (kb & 3)));
     }
 }

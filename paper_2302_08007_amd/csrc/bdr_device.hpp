@@ -328,8 +328,28 @@ __device__ __forceinline__ void store8(uint16_t *p, const uint32_t (&yb)[8])
 // (M 2^-tau has at most 4 significant bits over 5 binades, Sec. III; the top binade of E2M3 is
 // needed for M = 15, tau = 0; a block with SE = 1 moves one binade down instead, still exact).
 // The quantizer is that of mx_quant_lane: same maxima, same shifts, same rounding.
+// The element map (sign, M, tau, z) -> E2M3 code as a table in LDS: index = M | sign << MB |
+// tau << (MB + 1) | z << (MB + 2), at most 128 bytes = 32 dwords, one per bank, so look-ups never
+// conflict.  Filled by the first threads of a workgroup (a barrier must follow).
+template <int MB>
+__device__ __forceinline__ void fp6_map_fill(uint8_t *map)
+{
+    constexpr int CB = MB + 1;
+    if (threadIdx.x < (4u << CB)) {
+        const uint32_t idx = threadIdx.x;
+        const uint32_t mag = idx & ((1u << MB) - 1u), sign = (idx >> MB) & 1u;
+        const int tau = (int)((idx >> CB) & 1u), z = (int)(idx >> (CB + 1));
+        const int sh = (MB == 4 ? 2 : 3) - tau - z;
+        const uint32_t u = sh >= 0 ? mag << sh : 0u;  // element = u / 8, u <= 60 (MX4 has no z)
+        // u >= 8: FP32 of u has exponent field 127 + p (p = 3 .. 5) and u's next three bits on top
+        // of its fraction; E2M3 wants exponent field p - 2 and those bits
+        const uint32_t em = u < 8u ? u : (as_u((float)u) >> 20) - ((127u + 2u) << 3);
+        map[idx] = (uint8_t)((sign << 5) | em);
+    }
+}
+
 template <int MB, bool B_OPERAND>
-__device__ __forceinline__ u32x4 mx_quant_fp6_block(const uint32_t (&xb)[16])
+__device__ __forceinline__ u32x4 mx_quant_fp6_block(const uint32_t (&xb)[16], const uint8_t *map)
 {
     static_assert(MB == 4 || MB == 2, "MX6 or MX4");
     constexpr uint32_t MMASK = (1u << MB) - 1u;
@@ -352,17 +372,13 @@ __device__ __forceinline__ u32x4 mx_quant_fp6_block(const uint32_t (&xb)[16])
     for (int j = 0; j < 8; ++j) {
         const bool below = p[j] < thr;
         const int sh = below ? c1 : c0;
-        const int sh6 = (MB == 4 ? 2 : 3) - (below ? 1 : 0) - z;
+        const uint32_t tz = ((below ? 1u : 0u) << (MB + 1)) | ((uint32_t)z << (MB + 2));
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int i = 2 * j + e;
             const float y = __builtin_fminf(__builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh), TOP);
             const uint32_t mag = as_u(y + kMagic) & MMASK;  // nearest-even integer
-            const uint32_t u = mag << sh6;                  // element = u / 8, u <= 60
-            // u >= 8: FP32 of u has exponent field 127 + p (p = 3 .. 5) and u's next three bits
-            // on top of its fraction; E2M3 wants exponent field p - 2 and those bits
-            const uint32_t em = u < 8u ? u : (as_u((float)u) >> 20) - ((127u + 2u) << 3);
-            const uint32_t c6 = ((xb[i] >> 31) << 5) | em;
+            const uint32_t c6 = map[mag | ((xb[i] >> 31) << MB) | tz];
             const int bit = 6 * i;
             w[bit >> 5] |= c6 << (bit & 31);
             if ((bit & 31) + 6 > 32) w[(bit >> 5) + 1] |= c6 >> (32 - (bit & 31));
