@@ -312,16 +312,33 @@ __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
     uint32_t xb[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) xb[i] = lds_get(tile, lds_off<T>(16 * b + i, c), T());
-    const int64_t kb = (r0 >> 4) + b;
-    if constexpr (KIND == kOperandBf16) {
-        u32x4 lo, hi;
-        mx_quant_bf16_block<MB>(xb, lo, hi);
-        u32x4 *dst = out + (((kb >> 1) * cols + (c0 + c)) * 4 + 2 * (kb & 1));
-        stg<true>(lo, dst);
-        stg<true>(hi, dst + 1);
-    } else {
+    if constexpr (KIND != kOperandBf16) {
+        // four lanes write one 64-byte piece, a wave 512 contiguous bytes in each of two K steps
+        const int64_t kb = (r0 >> 4) + b;
         const u32x4 chunk = mx_quant_fp6_block<MB, KIND == kOperandFp6B>(xb, s_map);
         stg<true>(chunk, out + (((kb >> 2) * cols + (c0 + c)) * 4 + (kb & 3)));
+    } else {
+        // A lane's two chunks would leave as 16-byte pieces 32 bytes apart (86 us for 8192 x 12288
+        // BF16).  The tile's part of the image (four K steps x kTC columns x 64 bytes, never more
+        // than the tile itself) is put together in the tile's own LDS instead and leaves as whole
+        // runs of kTC x 64 bytes, a wave writing 1 KiB in a row per store (73 us).  For the FP6
+        // image the same detour costs more than it saves (67 -> 71-74 us).
+        constexpr int kSteps = kTR / 32;
+        static_assert(kSteps * kTC * 64 <= (int)sizeof(tile), "the image of a tile fits in the tile");
+        static_assert((kSteps * kTC * 4) % THREADS == 0, "whole passes");
+        u32x4 *img = reinterpret_cast<u32x4 *>(tile);
+        u32x4 v0, v1;
+        mx_quant_bf16_block<MB>(xb, v0, v1);
+        __syncthreads();  // every lane has its block in registers
+        img[((b >> 1) * kTC + c) * 4 + 2 * (b & 1)] = v0;
+        img[((b >> 1) * kTC + c) * 4 + 2 * (b & 1) + 1] = v1;
+        __syncthreads();
+        const int64_t step0 = r0 / 32;
+#pragma unroll
+        for (int i = threadIdx.x; i < kSteps * kTC * 4; i += THREADS) {
+            const int st = i / (kTC * 4), w = i % (kTC * 4);
+            stg<true>(img[i], out + (((step0 + st) * cols + c0) * 4 + w));
+        }
     }
 }
 
