@@ -327,6 +327,7 @@ def aux_probe(B, S, torch):
     yo = torch.empty(n_look, cols_t, device="cuda")
     tb = B.bdr_table_pack(B.MX6, pt, rows_t, cols_t)
     img = torch.empty(B.mx_operand_bytes(B.MX6, ra, ca), dtype=torch.uint8, device="cuda")
+    img9 = torch.empty(B.mx_operand_bytes(B.MX9, ra, ca, B.OPERAND_BF16), dtype=torch.uint8, device="cuda")
     xc = x.view(-1)[:8192 * 8192].view(8192, 8192)   # a square slice for the column-wise general kernel
     yc = y.view(-1)[:8192 * 8192].view(8192, 8192)
     pc = B.alloc_planes(fh, 8192, 8192, B.AXIS_COL)
@@ -341,6 +342,8 @@ def aux_probe(B, S, torch):
         B.bdr_table_gather_dequantize(B.MX6, tb, rows_t, cols_t, idx, out=yo)
         B.bdr_quantize_operand(B.MX6, xa, axis=B.AXIS_ROW, out=img)
         B.bdr_quantize_operand(B.MX6, xa, axis=B.AXIS_COL, out=img)
+        B.bdr_quantize_operand(B.MX9, xa, axis=B.AXIS_ROW, image=B.OPERAND_BF16, out=img9)
+        B.bdr_quantize_operand(B.MX9, xa, axis=B.AXIS_COL, image=B.OPERAND_BF16, out=img9)
         B.bdr_quantize(fh, x, out=ph)
         B.bdr_dequantize(fh, ph, rows, cols, out=y)
         B.bdr_quantize(fr, x, out=pr)
@@ -350,7 +353,7 @@ def aux_probe(B, S, torch):
     torch.cuda.synchronize()
     print(json.dumps({"aux_probe": "3 x (1 GiB copy; MX9 bf16 8192x12288 column quantize, dequantize, fused, "
                                    "row quantize, dequantize; MX6 gather 2^20 x 128 from planes and from the table image; the same "
-                                   "bf16 tensor to the MX6 operand image, row and column blocks; k1 32 k2 2 d2 1 m 4 and "
+                                   "bf16 tensor to the MX6 (FP6) and MX9 (BF16) operand images, row and column blocks; k1 32 k2 2 d2 1 m 4 and "
                                    "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32; k1 32 k2 2 d2 1 m 4 "
                                    "column quantize, dequantize on 8192 x 8192 fp32)"}))
 
@@ -514,21 +517,25 @@ def other_legs(B, S, torch, timed):
             leg[name] = {"us": round(t * 1e3, 1), "GBps": round(ab / t / 1e6, 1),
                          "frac": round(ab / t / 1e6 / HBM_PEAK_GBS, 4)}
         out["activation_bf16_8192x12288_MX9"] = leg
-        # the same tensor quantized to MX6 straight into the FP6 product kernel's operand image
-        # (2 bytes read, 1 byte written per element), blocks along rows / down columns
-        leg6 = {}
-        ab6 = r * c * 3
-        for axis, name in ((B.AXIS_ROW, "row"), (B.AXIS_COL, "col")):
-            img = torch.empty(B.mx_operand_bytes(B.MX6, r, c), dtype=torch.uint8, device="cuda")  # FP6 image
-            k = [0]
+        # the same tensor quantized straight into an operand image of the product kernels: MX6 into
+        # the FP6 image (2 bytes read, 1 written per element), MX9 into the BF16 image (2 and 2),
+        # blocks along rows / down columns
+        for fmt, image, nbytes, key in ((B.MX6, B.OPERAND_FP6, 3, "activation_bf16_8192x12288_MX6_operand_image"),
+                                        (B.MX9, B.OPERAND_BF16, 4, "activation_bf16_8192x12288_MX9_operand_image")):
+            legi = {}
+            abi = r * c * nbytes
+            for axis, name in ((B.AXIS_ROW, "row"), (B.AXIS_COL, "col")):
+                rows_i, k_i = (r, c) if axis == B.AXIS_ROW else (c, r)
+                img = torch.empty(B.mx_operand_bytes(fmt, rows_i, k_i, image), dtype=torch.uint8, device="cuda")
+                k = [0]
 
-            def runo():
-                B.bdr_quantize_operand(B.MX6, xa[k[0] % 3], axis=axis, out=img)
-                k[0] += 1
-            t = timed(runo, reps=7, inner=6)
-            leg6[name] = {"us": round(t * 1e3, 1), "GBps": round(ab6 / t / 1e6, 1),
-                          "frac": round(ab6 / t / 1e6 / HBM_PEAK_GBS, 4)}
-        out["activation_bf16_8192x12288_MX6_operand_image"] = leg6
+                def runo():
+                    B.bdr_quantize_operand(fmt, xa[k[0] % 3], axis=axis, image=image, out=img)
+                    k[0] += 1
+                t = timed(runo, reps=7, inner=6)
+                legi[name] = {"us": round(t * 1e3, 1), "GBps": round(abi / t / 1e6, 1),
+                              "frac": round(abi / t / 1e6 / HBM_PEAK_GBS, 4)}
+            out[key] = legi
         del xa
     except B.BdrError as e:
         out["activation_bf16_8192x12288_MX9"] = {"error": str(e)}
