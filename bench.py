@@ -580,6 +580,14 @@ def other_legs(B, S, torch, timed):
                                                 "mfma_util_pct_rocprofv3": profiled_mfma_util("gemm_ring_kernel<2,4,4,2,BF16>")},
                                    "qsnr_db_vs_fp32_gemm": round(q9, 3)}
         del p9a, p9b
+        # context only, not part of the path: the library's own BF16 product of the same
+        # (unquantized) operands on this machine, C in BF16 -- what the chip grants a BF16 GEMM today
+        Ah, Bh = A.to(torch.bfloat16), Bm.to(torch.bfloat16)
+        Ch = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+        tl = timed(lambda: torch.matmul(Ah, Bh.t(), out=Ch), reps=5, inner=4, warm=40)
+        out["mx_gemm_8192_MX9"]["library_bf16_gemm_for_context"] = {
+            "ms": round(tl, 3), "TFLOPs": round(2.0 * M * N * K / (tl * 1e-3) / 1e12, 1)}
+        del Ah, Bh, Ch
         # MX4 x MX4: the two-pass form uses block-scaled FP4 images (half the operand bytes)
         p4a, p4b = B.bdr_quantize(B.MX4, A), B.bdr_quantize(B.MX4, Bm)
         t = timed(lambda: B.mx_gemm(B.MX4, B.MX4, p4a, p4b, M, N, K, out=C, workspace=ws),

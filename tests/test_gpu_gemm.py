@@ -394,6 +394,29 @@ def test_operands_of_the_transpose(shape, name, dtype):
         assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, image=image, b_operand=True), ib)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16", "MX6 as BF16", "MX4 as BF16"])
+@pytest.mark.parametrize("shape", [(1, 64), (3, 192), (17, 64), (33, 320), (130, 704), (64, 2112)])
+def test_operands_from_few_rows_and_pitched_views(shape, name, dtype):
+    """Row blocks on shapes that leave the row-wise kernels' tiles (16 rows x 4 K steps per
+    workgroup) partly empty in both directions, from a contiguous tensor and from a view whose rows
+    are further apart than their length: the image equals the one made of the oracle-checked planes."""
+    rows, K = shape
+    f = getattr(B, name[:3])
+    image = B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP6
+    partner = B.MX9 if image == B.OPERAND_BF16 else B.MX6
+    big = _special(S.wide_range(max(rows, 4), K + 192, device="cuda", seed=rows + K, spread=8))[:rows].to(dtype)
+    for x in (big[:, :K].contiguous(), big[:, 64:64 + K]):
+        planes = B.bdr_quantize(f, x.contiguous())
+        for p, w in zip(planes, O.quantize(ofmt(f), to_np(x.contiguous()))):
+            assert np.array_equal(p.cpu().numpy(), w)
+        other = B.bdr_quantize(partner, x.contiguous())
+        ia, _, _ = _two_step_images(f, partner, planes, other, rows, rows, K)
+        _, ib, _ = _two_step_images(partner, f, other, planes, rows, rows, K)
+        assert torch.equal(B.bdr_quantize_operand(f, x, image=image, b_operand=False), ia)
+        assert torch.equal(B.bdr_quantize_operand(f, x, image=image, b_operand=True), ib)
+
+
 def _bf16_rne(v):
     """float32 array -> bfloat16 bit patterns, ties to even (written out, no library cast)."""
     u = np.ascontiguousarray(v, np.float32).view(np.uint32).astype(np.uint64)
