@@ -487,3 +487,92 @@ def test_full_size_sampled_entries(names):
     Cfp = A @ Bm.t()
     q = 10 * torch.log10(Cfp.double().square().sum() / (C.double() - Cfp.double()).square().sum())
     assert 10.0 < q.item() < 50.0
+
+
+# ---- operand images read back by a decoder written here, from the documented layout alone
+#
+# FP6 image: [K / 64][row][4 chunks of 16 bytes]; a chunk is one block of 16: its E2M3 codes in
+# dwords 0-2 (element j at bits 6 j .. 6 j + 5), its scale byte in dword 3 (byte 0 for an A
+# operand, byte 2 for a B operand, the other three bytes zero).  E2M3: sign, two exponent bits e,
+# three fraction bits m; m / 8 for e = 0, else (1 + m / 8) 2^(e - 1).  Scale byte b: 2^(b - 127).
+# BF16 image: [K / 32][row][32 BF16 values].
+
+def _decode_fp6_image(img, rows, K, b_operand, sel):
+    """values [len(sel) x K] (float64) of the image rows `sel`"""
+    a = img.cpu().numpy().reshape(K // 64, rows, 4, 16)[:, sel]
+    w = np.ascontiguousarray(a).view(np.uint32).astype(np.uint64)        # [q, s, chunk, 4 dwords]
+    lo, hi = w[..., 0] | (w[..., 1] << np.uint64(32)), w[..., 2]
+    sc = w[..., 3]
+    shift = np.uint64(16 if b_operand else 0)
+    assert np.all(sc & ~(np.uint64(0xff) << shift) == 0), "dword 3 holds the scale byte and nothing else"
+    scale = ((sc >> shift) & np.uint64(0xff)).astype(np.int64)
+    out = np.empty(a.shape[:3] + (16,), np.float64)
+    for j in range(16):
+        bit = 6 * j
+        if bit + 6 <= 64:
+            c = (lo >> np.uint64(bit)) & np.uint64(63)
+        elif bit >= 64:
+            c = (hi >> np.uint64(bit - 64)) & np.uint64(63)
+        else:
+            c = ((lo >> np.uint64(bit)) | (hi << np.uint64(64 - bit))) & np.uint64(63)
+        c = c.astype(np.int64)
+        e, m = (c >> 3) & 3, (c & 7).astype(np.float64)
+        mag = np.where(e == 0, m / 8.0, (1.0 + m / 8.0) * np.exp2((e - 1).astype(np.float64)))
+        out[..., j] = np.where(c >> 5 == 1, -mag, mag) * np.exp2((scale - 127).astype(np.float64))
+    return out.transpose(1, 0, 2, 3).reshape(len(sel), K)
+
+
+def _decode_bf16_image(img, rows, K, sel):
+    a = img.cpu().numpy().view(np.uint16).reshape(K // 32, rows, 32)[:, sel]
+    bits = a.astype(np.uint32) << np.uint32(16)
+    return bits.view(np.float32).astype(np.float64).transpose(1, 0, 2).reshape(len(sel), K)
+
+
+def _oracle_values(f, x_rows):
+    """what the oracle's quantizer and decoder make of the rows x_rows [s x K] (float64)"""
+    x_rows = np.ascontiguousarray(x_rows)
+    s, K = x_rows.shape
+    return O.dequantize(ofmt(f), *O.quantize(ofmt(f), x_rows), s, K).astype(np.float64)
+
+
+def _check_images_against_the_oracle(f, image, x, axis, sel):
+    rows, K = (x.shape[0], x.shape[1]) if axis == B.AXIS_ROW else (x.shape[1], x.shape[0])
+    src = x[torch.as_tensor(sel, device=x.device)] if axis == B.AXIS_ROW else x[:, torch.as_tensor(sel, device=x.device)].t()
+    want = _oracle_values(f, to_np(src.contiguous()))
+    for b_operand in (False, True):
+        img = B.bdr_quantize_operand(f, x, axis=axis, image=image, b_operand=b_operand)
+        torch.cuda.synchronize()
+        assert img.numel() == B.mx_operand_bytes(f, rows, K, image)
+        got = (_decode_fp6_image(img, rows, K, b_operand, sel) if image == B.OPERAND_FP6
+               else _decode_bf16_image(img, rows, K, sel))
+        assert np.array_equal(got, want), (f, image, axis, b_operand)
+        del img
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16", "MX6 as BF16", "MX4 as BF16"])
+@pytest.mark.parametrize("shape", [(16, 64), (130, 192), (256, 1024), (384, 640)])
+def test_operand_images_hold_the_oracles_values(shape, name, dtype):
+    """Every element of an image made by bdr_quantize_operand, decoded here from the documented
+    layout, is the value the oracle's quantize + dequantize give: row blocks on any shape, column
+    blocks on whole tiles (rows a multiple of 128, columns of 128)."""
+    rows, cols = shape
+    f = getattr(B, name[:3])
+    image = B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP6
+    x = _special(S.wide_range(rows, cols, device="cuda", seed=7 * rows + cols, spread=8)).to(dtype)
+    _check_images_against_the_oracle(f, image, x, B.AXIS_ROW, np.arange(rows))
+    if rows % 128 == 0 and cols % 128 == 0:
+        _check_images_against_the_oracle(f, image, x, B.AXIS_COL, np.arange(cols))
+
+
+@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16"])
+def test_operand_images_of_the_activation_tensor_at_full_size(name):
+    """The bench's operand-image legs (8192 x 12288 BF16, channel outliers), both block directions:
+    96 sampled image rows against the oracle, through the decoder above."""
+    f = getattr(B, name[:3])
+    image = B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP6
+    x = S.activation(device="cuda")
+    rng = np.random.default_rng(11)
+    for axis, n in ((B.AXIS_ROW, x.shape[0]), (B.AXIS_COL, x.shape[1])):
+        sel = np.sort(np.concatenate([[0, n - 1], rng.choice(np.arange(1, n - 1), 94, replace=False)]))
+        _check_images_against_the_oracle(f, image, x, axis, sel)
