@@ -520,8 +520,10 @@ def other_legs(B, S, torch, timed):
         # the same tensor quantized straight into an operand image of the product kernels: MX6 into
         # the FP6 image (2 bytes read, 1 written per element), MX9 into the BF16 image (2 and 2),
         # blocks along rows / down columns
+        # MX4 into the FP4 image (2 read, 1/2 + 1/16 written)
         for fmt, image, nbytes, key in ((B.MX6, B.OPERAND_FP6, 3, "activation_bf16_8192x12288_MX6_operand_image"),
-                                        (B.MX9, B.OPERAND_BF16, 4, "activation_bf16_8192x12288_MX9_operand_image")):
+                                        (B.MX9, B.OPERAND_BF16, 4, "activation_bf16_8192x12288_MX9_operand_image"),
+                                        (B.MX4, B.OPERAND_FP4, 2.5625, "activation_bf16_8192x12288_MX4_operand_image_fp4")):
             legi = {}
             abi = r * c * nbytes
             for axis, name in ((B.AXIS_ROW, "row"), (B.AXIS_COL, "col")):
@@ -682,7 +684,8 @@ def other_legs(B, S, torch, timed):
         gy = torch.randn(T, Osz, generator=g, device="cuda").to(torch.bfloat16)
 
         for name, f, peak, key in (("MX9", B.MX9, 2500.0, "frac_of_bf16_mfma_peak_2500"),
-                                   ("MX6", B.MX6, 10100.0, "frac_of_fp6_mfma_peak_10100")):
+                                   ("MX6", B.MX6, 10100.0, "frac_of_fp6_mfma_peak_10100"),
+                                   ("MX4", B.MX4, 10100.0, "frac_of_fp4_mfma_peak_10100")):
             def step_fn():
                 x.grad = None
                 w.grad = None

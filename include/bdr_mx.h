@@ -270,25 +270,29 @@ int mx_gemm_to(const bdr_format *fa, const bdr_format *fb, const void *a_codes, 
  * bdr_quantize_operand quantizes x (Sec. IX, as bdr_quantize does, nearest even) straight
  * into an image the product kernel reads - what mx_gemm's two-pass form would make of the
  * planes in its workspace, byte for byte - and mx_gemm_operands multiplies two such images.
- * Table II's formats with nearest-even rounding only (BDR_ERR_FORMAT otherwise); two kinds
+ * Table II's formats with nearest-even rounding only (BDR_ERR_FORMAT otherwise); three kinds
  * of image, and both operands of a product must be of the same kind:
  *   BDR_OPERAND_FP6  : MX6 and MX4 (m <= 4): 16 E2M3 codes and a scale byte per block, for
  *                      the block-scaled FP6 product (one byte per element)
  *   BDR_OPERAND_BF16 : MX9, MX6, MX4: the dequantized values in BF16 (exact), for the BF16
  *                      product (two bytes per element)
+ *   BDR_OPERAND_FP4  : MX4 only: 16 E2M1 codes per block (half a byte per element), followed
+ *                      by an image of one scale byte per block whose rows are padded to a
+ *                      multiple of 128, for the block-scaled FP4 product
  *   mx_operand_bytes : host only; bytes of the image of an operand of `rows` rows and
- *            reduction length K (a multiple of 64); 0 for what is not taken
+ *            reduction length K (a multiple of 64; of 128 for FP4); 0 for what is not taken
  *   bdr_quantize_operand : x device, [rows x cols] of dtype, pitch ld, aligned as for
  *            bdr_quantize.  BDR_AXIS_ROW: the operand is x, its K is cols (a multiple of
- *            64).  BDR_AXIS_COL: the operand is the transpose of x, [cols x rows], its K is
- *            rows (a multiple of 128; cols a multiple of 64 for FP32, of 128 for BF16).
+ *            64; of 128 for FP4).  BDR_AXIS_COL: the operand is the transpose of x, [cols x
+ *            rows], its K is rows (a multiple of 128; cols a multiple of 64 for FP32, of
+ *            128 for BF16 and for FP4 images).
  *            b_operand: 0 for the image of A, 1 for the image of B (FP6 images differ in
- *            where the block's scale byte sits; BF16 images do not).  out: device, 16-byte
+ *            where the block's scale byte sits; the others do not).  out: device, 16-byte
  *            aligned, mx_operand_bytes(fmt, operand rows, K, image) bytes, fully overwritten
  *   mx_gemm_operands : C [M x N] = A B^T from the image of A [M x K] and the image of B
  *            [N x K]; C, c_dtype, ldc as for mx_gemm_to.  No workspace is needed.
  * Other shapes, or an unknown image kind, are BDR_ERR_SHAPE. */
-enum bdr_operand_image { BDR_OPERAND_FP6 = 0, BDR_OPERAND_BF16 = 1 };
+enum bdr_operand_image { BDR_OPERAND_FP6 = 0, BDR_OPERAND_BF16 = 1, BDR_OPERAND_FP4 = 2 };
 size_t mx_operand_bytes(const bdr_format *fmt, int64_t rows, int64_t K, int image);
 int bdr_quantize_operand(const bdr_format *fmt, const void *x, int dtype, int64_t rows, int64_t cols,
                          int64_t ld, int axis, int image, int b_operand, void *out, void *hip_stream);

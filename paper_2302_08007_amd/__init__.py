@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libbdr_mx.so")
 RNE, RNA, RTZ = 0, 1, 2
 F32, BF16 = 0, 1
 AXIS_ROW, AXIS_COL = 0, 1
-OPERAND_FP6, OPERAND_BF16 = 0, 1
+OPERAND_FP6, OPERAND_BF16, OPERAND_FP4 = 0, 1, 2
 OK = 0
 
 EXPORTS = (
@@ -328,7 +328,8 @@ def mx_operand_bytes(fmt, rows, K, image=OPERAND_FP6):
 
 def bdr_quantize_operand(fmt, x, axis=AXIS_ROW, image=OPERAND_FP6, b_operand=False, out=None):
     """Quantize x straight into an image the product kernel reads (OPERAND_FP6: MX6 / MX4 for the
-    block-scaled FP6 product; OPERAND_BF16: any Table II format for the BF16 product): the image
+    block-scaled FP6 product; OPERAND_BF16: any Table II format for the BF16 product; OPERAND_FP4:
+    MX4 for the block-scaled FP4 product, K a multiple of 128): the image
     of x itself (axis ROW, K = columns) or of its transpose (axis COL, K = rows).  Returns a
     uint8 tensor."""
     rows, cols, ld = _dev2d(x)

@@ -434,15 +434,23 @@ int mx_gemm(const bdr_format *fa, const bdr_format *fb, const void *a_codes, con
 // what the specialised quantizers implement.
 static bool operand_format(const bdr_format *f, int image)
 {
-    return bdr::is_mx(*f) && (image == BDR_OPERAND_BF16 || f->m <= 4);
+    if (!bdr::is_mx(*f)) return false;
+    return image == BDR_OPERAND_BF16 || (image == BDR_OPERAND_FP6 && f->m <= 4) || (image == BDR_OPERAND_FP4 && f->m == 2);
 }
-static bool operand_image(int image) { return image == BDR_OPERAND_FP6 || image == BDR_OPERAND_BF16; }
+static bool operand_image(int image)
+{
+    return image == BDR_OPERAND_FP6 || image == BDR_OPERAND_BF16 || image == BDR_OPERAND_FP4;
+}
+// K of an operand image: whole K steps of the product kernel that takes it
+static int64_t operand_k_multiple(int image) { return image == BDR_OPERAND_FP4 ? 128 : 64; }
 
 size_t mx_operand_bytes(const bdr_format *fmt, int64_t rows, int64_t K, int image)
 {
     if (check_format(fmt) != BDR_OK || !operand_image(image) || !operand_format(fmt, image)) return 0;
-    if (rows < 0 || K < 0 || K % 64 != 0 || rows > (1 << 20) || K > (1 << 20)) return 0;
-    // FP6: a 16-byte chunk per block of 16; BF16: two bytes per element
+    if (rows < 0 || K < 0 || K % operand_k_multiple(image) != 0 || rows > (1 << 20) || K > (1 << 20)) return 0;
+    // FP6: a 16-byte chunk per block of 16; BF16: two bytes per element; FP4: half a byte per
+    // element, then one scale byte per block with the rows padded to a multiple of 128
+    if (image == BDR_OPERAND_FP4) return (size_t)rows * (size_t)(K / 2) + bdr::fp4_scale_bytes(rows, K);
     return (size_t)rows * (size_t)K * (image == BDR_OPERAND_BF16 ? 2u : 1u);
 }
 
@@ -456,14 +464,17 @@ int bdr_quantize_operand(const bdr_format *fmt, const void *x, int dtype, int64_
     if (dtype != BDR_F32 && dtype != BDR_BF16) return BDR_ERR_DTYPE;
     if (axis != BDR_AXIS_ROW && axis != BDR_AXIS_COL) return BDR_ERR_SHAPE;
     if (rows < 0 || cols < 0 || ld < cols || rows > (1 << 20) || cols > (1 << 20)) return BDR_ERR_SHAPE;
-    if (axis == BDR_AXIS_ROW ? cols % 64 != 0 : !bdr::quantize_operand_col_ok(dtype, rows, cols)) return BDR_ERR_SHAPE;
+    if (axis == BDR_AXIS_ROW ? cols % operand_k_multiple(image) != 0 : !bdr::quantize_operand_col_ok(dtype, rows, cols))
+        return BDR_ERR_SHAPE;
+    // (column blocks: the operand's rows are the tensor's columns; the FP4 scale image wants whole groups of 128)
+    if (image == BDR_OPERAND_FP4 && axis == BDR_AXIS_COL && cols % 128 != 0) return BDR_ERR_SHAPE;
     if (rows == 0 || cols == 0) return BDR_OK;
     st = check_tensor_ptr(x, dtype, ld);
     if (st) return st;
     if (!out) return BDR_ERR_NULL;
     if (!aligned16(out)) return BDR_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int kind = image == BDR_OPERAND_BF16 ? 2 : (b_operand ? 1 : 0);
+    const int kind = image == BDR_OPERAND_BF16 ? 2 : image == BDR_OPERAND_FP4 ? 3 : (b_operand ? 1 : 0);
     if (axis == BDR_AXIS_ROW) return bdr::quantize_operand_row(*fmt, x, dtype, rows, cols, ld, out, kind, s);
     return bdr::quantize_operand_col(*fmt, x, dtype, rows, cols, ld, out, kind, s);
 }
@@ -479,7 +490,7 @@ int mx_gemm_operands(const bdr_format *fa, const bdr_format *fb, const void *ima
     if (st) return st;
     if (!operand_image(image)) return BDR_ERR_SHAPE;
     if (!operand_format(fa, image) || !operand_format(fb, image)) return BDR_ERR_FORMAT;
-    if (M < 0 || N < 0 || K < 0 || ldc < N || K % 64 != 0) return BDR_ERR_SHAPE;
+    if (M < 0 || N < 0 || K < 0 || ldc < N || K % operand_k_multiple(image) != 0) return BDR_ERR_SHAPE;
     if (M > (1 << 20) || N > (1 << 20) || K > (1 << 20)) return BDR_ERR_SHAPE;
     if (M == 0 || N == 0) return BDR_OK;
     if (!C) return BDR_ERR_NULL;
@@ -490,6 +501,13 @@ int mx_gemm_operands(const bdr_format *fa, const bdr_format *fb, const void *ima
         return bdr::gemm(*fa, *fb, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, M, N, 0, C, ldc, c_bf16, s);
     if (!image_a || !image_b) return BDR_ERR_NULL;
     if (!aligned16(image_a) || !aligned16(image_b)) return BDR_ERR_ALIGN;
+    if (image == BDR_OPERAND_FP4) {  // chunks, then the scale image
+        const char *sa = static_cast<const char *>(image_a) + (size_t)M * (size_t)(K / 2);
+        const char *sb = static_cast<const char *>(image_b) + (size_t)N * (size_t)(K / 2);
+        st = bdr::gemm_fp4(image_a, sa, image_b, sb, M, N, K, C, ldc, c_bf16, true, s);
+        if (st) return st;
+        return bdr::gemm_fp4(image_a, sa, image_b, sb, M, N, K, C, ldc, c_bf16, false, s);
+    }
     if (image == BDR_OPERAND_BF16) {
         st = bdr::gemm_bf16_tiled(image_a, image_b, M, N, K, C, ldc, c_bf16, true, s);
         if (st) return st;

@@ -290,11 +290,11 @@ __global__ __launch_bounds__((col_threads<T, MODE>())) void mx_col_kernel(
 // every one of its columns eight blocks, i.e. whole 64-byte pieces in two (FP6) or four (BF16) K
 // steps, and the columns of a tile follow each other in the image, so a tile writes runs of
 // 64 bytes x its columns: no partial lines, no neighbours to wait for.
-constexpr int kOperandFp6B = 1, kOperandBf16 = 2;  // (0: FP6, A operand)
+constexpr int kOperandFp6B = 1, kOperandBf16 = 2, kOperandFp4 = 3;  // (0: FP6, A operand)
 
 template <int MB, typename T, int KIND>
 __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
-    const T *x, u32x4 *__restrict__ out, int64_t cols, int64_t ld)
+    const T *x, u32x4 *__restrict__ out, int64_t cols, int64_t ld, uint8_t *__restrict__ scales)
 {
     constexpr int kTC = TileGeom<T>::kTC;
     constexpr int THREADS = col_threads<T, 0>();
@@ -305,14 +305,31 @@ __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = lane & (kBPT - 1), c = kCPW * wave + lane / kBPT;  // one pass: THREADS = kBPT * kTC
     static_assert(THREADS == kBPT * kTC, "one lane per block of the tile");
-    __shared__ uint8_t s_map[KIND == kOperandBf16 ? 1 : 128];
-    if constexpr (KIND != kOperandBf16) fp6_map_fill<MB>(s_map);
+    constexpr bool kFp6 = KIND == 0 || KIND == kOperandFp6B;
+    __shared__ uint8_t s_map[kFp6 ? 128 : 1];
+    if constexpr (kFp6) fp6_map_fill<MB>(s_map);
     tile_load<T, THREADS>(x, ld, r0, c0, tile);
     __syncthreads();
     uint32_t xb[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) xb[i] = lds_get(tile, lds_off<T>(16 * b + i, c), T());
-    if constexpr (KIND != kOperandBf16) {
+    if constexpr (KIND == kOperandFp4) {
+        // The tile's 128 rows are one K step of the FP4 image, a column's eight lanes hold its
+        // eight blocks: 8 bytes of codes each (64 contiguous bytes per column; columns with bit 4
+        // set keep the two blocks of a chunk in swapped order), and the eight scale bytes, gathered
+        // by three DPP steps into the even blocks' word (lane 0) and the odd blocks' (lane 1).
+        static_assert(MB == 2 && kBPT == 8, "MX4, eight blocks per K step");
+        uint32_t w0, w1, scale;
+        mx_quant_fp4_block(xb, w0, w1, scale);
+        const int64_t col = c0 + c, step = tx;
+        const int half = (b & 1) ^ (int)((col >> 4) & 1);
+        stg<true>(u32x2{w0, w1}, reinterpret_cast<u32x2 *>(reinterpret_cast<uint8_t *>(out) +
+                                                           ((step * cols + col) * 4 + (b >> 1)) * 16 + 8 * half));
+        uint32_t sw = scale << (8 * (b >> 1));
+        sw |= dpp<kQuadXor2>(sw);
+        sw |= dpp<kQuadXor1>(dpp<kQuadXor2>(dpp<kRowHalfMirror>(sw)));  // lane b ^ 4
+        if (b < 2) *reinterpret_cast<uint32_t *>(scales + (step * cols + col) * 8 + 4 * b) = sw;
+    } else if constexpr (KIND != kOperandBf16) {
         // four lanes write one 64-byte piece, a wave 512 contiguous bytes in each of two K steps
         const int64_t kb = (r0 >> 4) + b;
         const u32x4 chunk = mx_quant_fp6_block<MB, KIND == kOperandFp6B>(xb, s_map);
@@ -343,16 +360,19 @@ __global__ __launch_bounds__((col_threads<T, 0>())) void mx_col_operand_kernel(
 }
 
 template <int MB, typename T>
-void launch_operand_col(int kind, dim3 grid, hipStream_t s, const T *x, u32x4 *o, int64_t cols, int64_t ld)
+void launch_operand_col(int kind, dim3 grid, hipStream_t s, const T *x, u32x4 *o, int64_t cols, int64_t ld,
+                        uint8_t *scales)
 {
     const dim3 block(col_threads<T, 0>());
     if (kind == kOperandBf16)
-        hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, kOperandBf16>), grid, block, 0, s, x, o, cols, ld);
+        hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, kOperandBf16>), grid, block, 0, s, x, o, cols, ld, scales);
     else if constexpr (MB <= 4) {
         if (kind == kOperandFp6B)
-            hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, kOperandFp6B>), grid, block, 0, s, x, o, cols, ld);
-        else
-            hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, 0>), grid, block, 0, s, x, o, cols, ld);
+            hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, kOperandFp6B>), grid, block, 0, s, x, o, cols, ld, scales);
+        else if (kind == 0)
+            hipLaunchKernelGGL((mx_col_operand_kernel<MB, T, 0>), grid, block, 0, s, x, o, cols, ld, scales);
+        else if constexpr (MB == 2)
+            hipLaunchKernelGGL((mx_col_operand_kernel<2, T, kOperandFp4>), grid, block, 0, s, x, o, cols, ld, scales);
     }
 }
 
@@ -362,12 +382,14 @@ int quantize_operand_col_t(const bdr_format &f, const T *x, int64_t rows, int64_
 {
     const dim3 grid((unsigned)(rows / kTR), (unsigned)(cols / TileGeom<T>::kTC));
     u32x4 *o = (u32x4 *)out;
+    // FP4 kind: the scale image follows the chunks (the operand is [cols x rows]: half a byte per element)
+    uint8_t *scales = kind == kOperandFp4 ? (uint8_t *)out + cols * (rows / 2) : nullptr;
     if (f.m == 7)
-        launch_operand_col<7, T>(kind, grid, s, x, o, cols, ld);
+        launch_operand_col<7, T>(kind, grid, s, x, o, cols, ld, scales);
     else if (f.m == 4)
-        launch_operand_col<4, T>(kind, grid, s, x, o, cols, ld);
+        launch_operand_col<4, T>(kind, grid, s, x, o, cols, ld, scales);
     else
-        launch_operand_col<2, T>(kind, grid, s, x, o, cols, ld);
+        launch_operand_col<2, T>(kind, grid, s, x, o, cols, ld, scales);
     return launch_status();
 }
 

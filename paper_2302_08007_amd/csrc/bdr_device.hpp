@@ -387,6 +387,46 @@ __device__ __forceinline__ u32x4 mx_quant_fp6_block(const uint32_t (&xb)[16], co
     return u32x4{w[0], w[1], w[2], (uint32_t)scale << (B_OPERAND ? 16 : 0)};
 }
 
+// One whole MX4 block held by one lane, quantized (nearest even) into the 8 bytes the block-scaled
+// FP4 matrix instruction takes: 16 E2M1 codes (sign, two exponent bits, one fraction bit: 0, 0.5,
+// 1, 1.5, 2, 3, 4, 6), element j at bits 4 j .. 4 j + 3, and the block's scale byte.  An MX4
+// element is +-M 2^(SE - 127 - tau - 1) with M <= 3 (Sec. III): M 2^-tau is 0, 0.5, 1, 1.5 (tau =
+// 1: code M) or 0, 1, 2, 3 (tau = 0: codes 0, 2, 4, 5), the rest is the scale byte SE - 1.
+__device__ __forceinline__ void mx_quant_fp4_block(const uint32_t (&xb)[16], uint32_t &w0, uint32_t &w1,
+                                                   uint32_t &scale)
+{
+    uint32_t p[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        p[j] = umax(umax(xb[2 * j] & kAbsMask, xb[2 * j + 1] & kAbsMask), kMagLo);
+    uint32_t bm = p[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) bm = umax(bm, p[j]);
+    bm = umin(bm, kMagHi);
+    const uint32_t thr = bm & kExpMask;
+    const int se = (int)(bm >> 23);
+    const int c0 = 1 + 127 - se, c1 = c0 + 1;
+    scale = (uint32_t)(se - 1);  // se >= 1
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const bool below = p[j] < thr;
+        const int sh = below ? c1 : c0;
+        // the code of magnitude M as nibble M (tau = 0) or 4 + M (tau = 1) of one constant
+        const uint32_t lut = below ? 0x3210u : 0x5420u;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = 2 * j + e;
+            const float y = __builtin_fminf(__builtin_ldexpf(__builtin_fabsf(as_f(xb[i])), sh), 3.0f);
+            const uint32_t mag = as_u(y + kMagic) & 3u;  // nearest-even integer
+            const uint32_t c4 = ((lut >> (4u * mag)) & 7u) | ((xb[i] >> 28) & 8u);
+            w[i >> 3] |= c4 << (4 * (i & 7));
+        }
+    }
+    w0 = w[0];
+    w1 = w[1];
+}
+
 // One whole Table II block held by one lane, quantized (nearest even) and written out as its 16
 // dequantized values in BF16 (exact: m + 1 <= 8 significant bits), two per dword: the 32 bytes
 // the block takes in the BF16 operand image of the product kernel.

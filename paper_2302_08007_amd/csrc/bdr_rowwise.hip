@@ -1094,8 +1094,10 @@ static int generic_view_t(int what, const bdr_format &f, const T *x, T *y, int64
 //   KIND 0 / 1: a block's 16-byte FP6 chunk for an A / B operand (mx_quant_fp6_block), stored at
 //               [K step of 4 blocks][row][4 chunks];
 //   KIND 2:     a block's 16 dequantized BF16 values, stored at
-//               [K step of 2 blocks][row][4 chunks of 8 values].
-constexpr int kOperandFp6A = 0, kOperandFp6B = 1, kOperandBf16 = 2;
+//               [K step of 2 blocks][row][4 chunks of 8 values];
+//   KIND 3:     (MX4 only) a block's 8 bytes of FP4 codes, stored at [K step of 8 blocks][row][4
+//               chunks of 2 blocks], and its scale byte in a scale image after the chunks.
+constexpr int kOperandFp6A = 0, kOperandFp6B = 1, kOperandBf16 = 2, kOperandFp4 = 3;
 
 // Both images are [K step][row][four 16-byte chunks], and in both row-wise kernels a lane makes
 // one chunk, so four consecutive lanes write one 64-byte piece.  A wave takes kImgRows rows x
@@ -1104,16 +1106,18 @@ constexpr int kOperandFp6A = 0, kOperandFp6B = 1, kOperandBf16 = 2;
 // bytes of each step; the four waves of a workgroup stack on rows.
 constexpr int kImgSteps = 4, kImgRows = 16 / kImgSteps, kImgTileRows = kThreads / 64 * kImgRows;
 
+// LANES lanes per K step of a row (4: one chunk each; 8: the FP4 image, half a chunk each).
 struct ImgLane { int64_t row; int32_t q, c; bool in; };
+template <int LANES = 4>
 __device__ __forceinline__ ImgLane img_lane(int64_t rows, int32_t row_steps, int32_t step_tiles)
 {
-    const int tid = threadIdx.x, j = tid >> 2;
+    const int tid = threadIdx.x, j = tid / LANES;
     const int64_t tile = blockIdx.x, rt = tile / step_tiles;
     ImgLane l;
-    l.c = tid & 3;
+    l.c = tid % LANES;
     l.q = (int32_t)(tile - rt * step_tiles) * kImgSteps + (j % kImgSteps);
-    l.row = rt * kImgTileRows + j / kImgSteps;
-    l.in = l.row < rows && l.q < row_steps;  // the four lanes of a K step agree
+    l.row = rt * (kThreads / LANES / kImgSteps) + j / kImgSteps;
+    l.in = l.row < rows && l.q < row_steps;  // the lanes of a K step agree
     return l;
 }
 
@@ -1164,6 +1168,49 @@ __global__ __launch_bounds__(kThreads) void mx_quantize_bf16_image_row_kernel(
     stg<true>(v, out + (((int64_t)l.q * rows + l.row) * 4 + l.c));
 }
 
+// The FP4 image (MX4 only): a K step is 128 elements = 8 blocks = 8 lanes with one block each.
+// A lane writes its 8 bytes of E2M1 codes into chunk c / 2 of [K step][row][4 chunks] (rows with
+// bit 4 set keep the two blocks of a chunk in swapped order, as the product kernel reads them);
+// the step's 8 scale bytes go to the scale image [K step][row padded to 128][even blocks' four,
+// odd blocks' four], gathered by three DPP steps and written by lanes 0 and 1.  The rows that only
+// pad the scale image are visited too and get zero scales.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void mx_quantize_fp4_image_row_kernel(
+    const T *__restrict__ x, int64_t rows, int64_t rows_pad, int32_t row_steps, int32_t step_tiles,
+    int64_t ld, uint8_t *__restrict__ out, uint8_t *__restrict__ scales)
+{
+    const ImgLane l = img_lane<8>(rows_pad, row_steps, step_tiles);
+    if (!l.in) return;
+    uint32_t w0 = 0, w1 = 0, scale = 0;
+    const bool real = l.row < rows;  // uniform over the 8 lanes
+    if (real) {
+        const T *src = x + l.row * ld + 128 * (int64_t)l.q + 16 * l.c;
+        uint32_t xb[16], lo[8], hi[8];
+        if constexpr (sizeof(T) == 4) {
+            load8(src, lo);
+            load8(src + 8, hi);
+        } else {
+            widen8(ldg<true>(reinterpret_cast<const u32x4 *>(src)), lo);
+            widen8(ldg<true>(reinterpret_cast<const u32x4 *>(src) + 1), hi);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            xb[i] = lo[i];
+            xb[8 + i] = hi[i];
+        }
+        mx_quant_fp4_block(xb, w0, w1, scale);
+        const int half = (l.c & 1) ^ (int)((l.row >> 4) & 1);
+        stg<true>(u32x2{w0, w1}, reinterpret_cast<u32x2 *>(
+                                     out + (((int64_t)l.q * rows + l.row) * 4 + (l.c >> 1)) * 16 + 8 * half));
+    }
+    // byte c / 2 of the word of this lane's parity, then OR over the four lanes of that parity
+    uint32_t sw = scale << (8 * (l.c >> 1));
+    sw |= dpp<kQuadXor2>(sw);
+    sw |= dpp<kQuadXor1>(dpp<kQuadXor2>(dpp<kRowHalfMirror>(sw)));  // lane c ^ 4 (7 - c, then ^ 3)
+    if (l.c < 2)
+        *reinterpret_cast<uint32_t *>(scales + ((int64_t)l.q * rows_pad + l.row) * 8 + 4 * l.c) = sw;
+}
+
 template <int MB, typename T>
 static void launch_operand_row(int kind, dim3 grid, hipStream_t s, const T *x, int64_t rows, int32_t steps,
                                int32_t st, int64_t ld, u32x4 *o)
@@ -1183,6 +1230,15 @@ template <typename T>
 static int quantize_operand_row_t(const bdr_format &f, const T *x, int64_t rows, int64_t cols, int64_t ld,
                                   void *out, int kind, hipStream_t s)
 {
+    if (kind == kOperandFp4) {  // f is MX4; chunks, then the scale image
+        const int32_t steps = (int32_t)(cols / 128), st = (steps + kImgSteps - 1) / kImgSteps;
+        const int64_t rows_pad = (rows + 127) / 128 * 128;
+        constexpr int kTile = kThreads / 8 / kImgSteps;
+        uint8_t *o = (uint8_t *)out;
+        hipLaunchKernelGGL((mx_quantize_fp4_image_row_kernel<T>), dim3((unsigned)(rows_pad / kTile * st)),
+                           dim3(kThreads), 0, s, x, rows, rows_pad, steps, st, ld, o, o + rows * (cols / 2));
+        return launch_status();
+    }
     const int32_t steps = (int32_t)(cols / (kind == kOperandBf16 ? 32 : 64));
     const int32_t st = (steps + kImgSteps - 1) / kImgSteps;
     const dim3 grid((unsigned)((rows + kImgTileRows - 1) / kImgTileRows * st));
@@ -1196,8 +1252,9 @@ static int quantize_operand_row_t(const bdr_format &f, const T *x, int64_t rows,
     return launch_status();
 }
 
-// x [rows x cols], blocks along the rows' own direction (K = cols, a multiple of 64); f is one of
-// Table II's formats (the FP6 kinds: MX6 or MX4), kind one of kOperand*.
+// x [rows x cols], blocks along the rows' own direction (K = cols, a multiple of 64; of 128 for the
+// FP4 kind); f is one of Table II's formats (the FP6 kinds: MX6 or MX4; the FP4 kind: MX4), kind
+// one of kOperand*.
 int quantize_operand_row(const bdr_format &f, const void *x, int dtype, int64_t rows, int64_t cols, int64_t ld,
                          void *out, int kind, hipStream_t s)
 {

@@ -17,7 +17,7 @@ orders the calls and plugs them into autograd.  Element-wise work stays in the c
 """
 import torch
 
-from . import (AXIS_COL, AXIS_ROW, OPERAND_BF16, OPERAND_FP6, bdr_quantize, bdr_quantize_operand, mx_gemm,
+from . import (AXIS_COL, AXIS_ROW, OPERAND_BF16, OPERAND_FP4, OPERAND_FP6, bdr_quantize, bdr_quantize_operand, mx_gemm,
                mx_gemm_operands, mx_gemm_workspace_bytes, mx_operand_bytes)
 
 _workspaces = {}
@@ -46,10 +46,12 @@ def _mx_matmul(fa, fb, a, a_axis, b, b_axis, M, N, K, out_dtype):
     out_dtype (FP32 sums; a BF16 C is rounded as the product kernel stores it, not in a pass of
     its own)."""
     image = OPERAND_FP6 if fa.m <= 4 and fb.m <= 4 else OPERAND_BF16
+    if fa.m == 2 and fb.m == 2 and _direct(fa, a, a_axis, M, K, OPERAND_FP4) and _direct(fb, b, b_axis, N, K, OPERAND_FP4):
+        image = OPERAND_FP4
     if _direct(fa, a, a_axis, M, K, image) and _direct(fb, b, b_axis, N, K, image):
         # the quantizer writes the product kernel's operand images itself (no planes, no rewriting
-        # pass): FP6 images when both formats have m <= 4, BF16 images when MX9 takes part; the two
-        # images share the stream's scratch buffer
+        # pass): FP4 images for an MX4 pair (K a multiple of 128), FP6 images when both formats have
+        # m <= 4, BF16 images when MX9 takes part; the two images share the stream's scratch buffer
         na, nb = mx_operand_bytes(fa, M, K, image), mx_operand_bytes(fb, N, K, image)
         ws = _workspace(a.device, na + nb)
         ia = bdr_quantize_operand(fa, a, axis=a_axis, image=image, b_operand=False, out=ws[:na])
@@ -68,7 +70,7 @@ def _direct(f, t, axis, op_rows, K, image):
     if axis == AXIS_ROW:
         return True
     rows, cols = t.shape
-    return rows % 128 == 0 and cols % (64 if t.dtype == torch.float32 else 128) == 0
+    return rows % 128 == 0 and cols % (64 if t.dtype == torch.float32 and image != OPERAND_FP4 else 128) == 0
 
 
 class _MXLinear(torch.autograd.Function):

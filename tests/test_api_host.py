@@ -268,7 +268,11 @@ def test_operand_image_argument_checks():
     assert B.mx_operand_bytes(B.MX9, 128, 256, BF) == 2 * 128 * 256 == B.mx_operand_bytes(B.MX4, 128, 256, BF)
     assert B.mx_operand_bytes(B.fmt(16, 2, 1, 4, rounding=B.RTZ), 128, 256) == 0
     assert B.mx_operand_bytes(B.MX6, 128, 100) == 0 and B.mx_operand_bytes(B.MX6, -1, 64) == 0
-    assert B.mx_operand_bytes(B.MX6, 128, 256, 2) == 0
+    F4 = B.OPERAND_FP4
+    assert B.mx_operand_bytes(B.MX6, 128, 256, F4) == 0 and B.mx_operand_bytes(B.MX6, 128, 256, 3) == 0   # FP4: MX4 only
+    assert B.mx_operand_bytes(B.MX4, 128, 256, F4) == 128 * 128 + 128 * 16            # codes + one scale byte per block
+    assert B.mx_operand_bytes(B.MX4, 130, 256, F4) == 130 * 128 + 256 * 16            # scale rows padded to 128
+    assert B.mx_operand_bytes(B.MX4, 128, 192, F4) == 0                               # K in multiples of 128
     qo = lambda fm=f, x=FAKE, dtype=0, rows=128, cols=128, ld=128, axis=0, image=FP6, img=FAKE: \
         L.bdr_quantize_operand(ctypes.byref(fm), x, dtype, rows, cols, ld, axis, image, 0, img, NULL)
     assert qo(fm=B.MX9) == ERR_FORMAT and qo(fm=B.fmt(32, 2, 1, 4)) == ERR_FORMAT and qo(dtype=2) == ERR_DTYPE
@@ -276,6 +280,9 @@ def test_operand_image_argument_checks():
     assert qo(cols=96, ld=96) == ERR_SHAPE and qo(axis=3) == ERR_SHAPE and qo(ld=64) == ERR_SHAPE
     assert qo(axis=1, rows=64) == ERR_SHAPE and qo(axis=1, cols=32, ld=32) == ERR_SHAPE
     assert qo(axis=1, dtype=1, cols=64, ld=64) == ERR_SHAPE            # BF16 tiles are 128 columns wide
+    assert qo(fm=B.MX6, image=F4) == ERR_FORMAT and qo(fm=B.MX4, image=F4, cols=192, ld=192) == ERR_SHAPE
+    assert qo(fm=B.MX4, image=F4, axis=1, cols=64, ld=64) == ERR_SHAPE   # column blocks: operand rows in 128s
+    assert qo(fm=B.MX4, image=F4, x=NULL) == ERR_NULL and qo(fm=B.MX4, image=F4, rows=0) == OK
     assert qo(x=NULL) == ERR_NULL and qo(img=NULL) == ERR_NULL
     assert qo(fm=B.MX9, image=BF, x=FAKE_ODD) == ERR_ALIGN and qo(img=FAKE_ODD) == ERR_ALIGN and qo(rows=0) == OK
     go = lambda fa=f, fb=f, a=FAKE, b=FAKE, image=FP6, M=128, N=128, K=64, C=FAKE, cd=0, ldc=128: \
@@ -283,6 +290,8 @@ def test_operand_image_argument_checks():
     assert go(fa=B.MX9) == ERR_FORMAT and go(fb=B.fmt(16, 16, 0, 4)) == ERR_FORMAT and go(cd=5) == ERR_DTYPE
     assert go(fa=B.fmt(16, 16, 0, 4), image=BF) == ERR_FORMAT and go(image=-1) == ERR_SHAPE
     assert go(K=48) == ERR_SHAPE and go(ldc=64) == ERR_SHAPE and go(M=-1) == ERR_SHAPE
+    assert go(image=F4) == ERR_FORMAT and go(fa=B.MX4, fb=B.MX4, image=F4, K=64) == ERR_SHAPE
+    assert go(fa=B.MX4, fb=B.MX4, image=F4, K=128, a=NULL) == ERR_NULL and go(fa=B.MX4, fb=B.MX6, image=F4, K=128) == ERR_FORMAT
     assert go(C=NULL) == ERR_NULL and go(a=NULL) == ERR_NULL and go(b=NULL, fa=B.MX9, image=BF) == ERR_NULL
     assert go(a=FAKE_ODD) == ERR_ALIGN and go(C=ctypes.c_void_p(0x10002)) == ERR_ALIGN and go(M=0) == OK
 

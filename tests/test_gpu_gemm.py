@@ -528,6 +528,34 @@ def _decode_bf16_image(img, rows, K, sel):
     return bits.view(np.float32).astype(np.float64).transpose(1, 0, 2).reshape(len(sel), K)
 
 
+def _decode_fp4_image(img, rows, K, sel):
+    """FP4 image: [K / 128][row][4 chunks of 16 bytes], a chunk = two blocks of 16 E2M1 codes
+    (element j of a block at bits 4 j .. 4 j + 3 of its 8 bytes; rows with bit 4 set keep the two
+    blocks of a chunk in swapped order), then the scale image [K / 128][row padded to 128][8 bytes]:
+    the scales of the step's blocks 0, 2, 4, 6, then of blocks 1, 3, 5, 7.  E2M1: sign, two exponent
+    bits e, one fraction bit m; m / 2 for e = 0, else (1 + m / 2) 2^(e - 1)."""
+    raw = img.cpu().numpy()
+    rows_pad = (rows + 127) // 128 * 128
+    nchunk = rows * K // 2
+    assert raw.size == nchunk + rows_pad * K // 16
+    a = raw[:nchunk].reshape(K // 128, rows, 4, 2, 8)[:, sel]                 # [q, s, chunk, half, 8 bytes]
+    sc_all = raw[nchunk:].reshape(K // 128, rows_pad, 8)
+    assert not sc_all[:, rows:].any(), "rows that only pad the scale image hold zero scales"
+    sc = sc_all[:, sel].astype(np.int64)                                       # [q, s, 8]
+    out = np.empty((K // 128, len(sel), 8, 16), np.float64)
+    swap = ((np.asarray(sel) >> 4) & 1)[None, :]                               # [1, s]
+    for b in range(8):
+        half = (b & 1) ^ swap                                                  # [1, s]
+        blk = np.where(half[..., None] == 1, a[:, :, b >> 1, 1], a[:, :, b >> 1, 0])   # [q, s, 8 bytes]
+        scale = np.exp2((sc[:, :, 4 * (b & 1) + (b >> 1)] - 127).astype(np.float64))
+        for j in range(16):
+            c = ((blk[..., j >> 1] >> (4 * (j & 1))) & 15).astype(np.int64)
+            e, m = (c >> 1) & 3, (c & 1).astype(np.float64)
+            mag = np.where(e == 0, m / 2.0, (1.0 + m / 2.0) * np.exp2((e - 1).astype(np.float64)))
+            out[:, :, b, j] = np.where(c >> 3 == 1, -mag, mag) * scale
+    return out.transpose(1, 0, 2, 3).reshape(len(sel), K)
+
+
 def _oracle_values(f, x_rows):
     """what the oracle's quantizer and decoder make of the rows x_rows [s x K] (float64)"""
     x_rows = np.ascontiguousarray(x_rows)
@@ -544,35 +572,98 @@ def _check_images_against_the_oracle(f, image, x, axis, sel):
         torch.cuda.synchronize()
         assert img.numel() == B.mx_operand_bytes(f, rows, K, image)
         got = (_decode_fp6_image(img, rows, K, b_operand, sel) if image == B.OPERAND_FP6
+               else _decode_fp4_image(img, rows, K, sel) if image == B.OPERAND_FP4
                else _decode_bf16_image(img, rows, K, sel))
         assert np.array_equal(got, want), (f, image, axis, b_operand)
         del img
 
 
+def _image_kind(name):
+    return B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP4 if name.endswith("FP4") else B.OPERAND_FP6
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16", "MX6 as BF16", "MX4 as BF16"])
-@pytest.mark.parametrize("shape", [(16, 64), (130, 192), (256, 1024), (384, 640)])
+@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16", "MX6 as BF16", "MX4 as BF16", "MX4 as FP4"])
+@pytest.mark.parametrize("shape", [(16, 64), (130, 192), (41, 256), (256, 1024), (384, 640)])
 def test_operand_images_hold_the_oracles_values(shape, name, dtype):
     """Every element of an image made by bdr_quantize_operand, decoded here from the documented
     layout, is the value the oracle's quantize + dequantize give: row blocks on any shape, column
     blocks on whole tiles (rows a multiple of 128, columns of 128)."""
     rows, cols = shape
     f = getattr(B, name[:3])
-    image = B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP6
+    image = _image_kind(name)
+    if image == B.OPERAND_FP4 and cols % 128:
+        pytest.skip("an FP4 image takes K in multiples of 128")
     x = _special(S.wide_range(rows, cols, device="cuda", seed=7 * rows + cols, spread=8)).to(dtype)
     _check_images_against_the_oracle(f, image, x, B.AXIS_ROW, np.arange(rows))
     if rows % 128 == 0 and cols % 128 == 0:
         _check_images_against_the_oracle(f, image, x, B.AXIS_COL, np.arange(cols))
 
 
-@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16"])
+@pytest.mark.parametrize("name", ["MX6", "MX4", "MX9 as BF16", "MX4 as FP4"])
 def test_operand_images_of_the_activation_tensor_at_full_size(name):
     """The bench's operand-image legs (8192 x 12288 BF16, channel outliers), both block directions:
     96 sampled image rows against the oracle, through the decoder above."""
     f = getattr(B, name[:3])
-    image = B.OPERAND_BF16 if name.endswith("BF16") else B.OPERAND_FP6
+    image = _image_kind(name)
     x = S.activation(device="cuda")
     rng = np.random.default_rng(11)
     for axis, n in ((B.AXIS_ROW, x.shape[0]), (B.AXIS_COL, x.shape[1])):
         sel = np.sort(np.concatenate([[0, n - 1], rng.choice(np.arange(1, n - 1), 94, replace=False)]))
         _check_images_against_the_oracle(f, image, x, axis, sel)
+
+
+def _two_step_fp4_images(pa, pb, M, N, K):
+    """What mx_gemm's two-pass form writes into its workspace for an MX4 x MX4 product with M, N,
+    K >= 128 and K a multiple of 128: per operand the FP4 chunks, then the scale image."""
+    ws = _workspace(M, N, K)
+    C = B.mx_gemm(B.MX4, B.MX4, pa, pb, M, N, K, workspace=ws)
+    torch.cuda.synchronize()
+    half = (2 * M * K + 255) // 256 * 256
+    na, nb = B.mx_operand_bytes(B.MX4, M, K, B.OPERAND_FP4), B.mx_operand_bytes(B.MX4, N, K, B.OPERAND_FP4)
+    return ws[:na].clone(), ws[half:half + nb].clone(), C
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(128, 128, 128), (256, 384, 512), (130, 200, 256), (512, 256, 1024)])
+def test_fp4_operands_made_by_the_quantizer(shape, dtype):
+    """MX4 x MX4 on FP4 images: bdr_quantize_operand writes, byte for byte, the chunks and the scale
+    image the two-pass form makes of the planes; mx_gemm_operands returns that form's C, which is
+    within the tolerance of the oracle's product."""
+    M, N, K = shape
+    f = B.MX4
+    A, Bm = S.gemm_operands(M, N, K, device="cuda", seed=2 * M + N + K)
+    A, Bm = _special(A, 1.0e15).to(dtype), _special(Bm, 1.0e15).to(dtype)
+    pa, pb = B.bdr_quantize(f, A), B.bdr_quantize(f, Bm)
+    ia, ib, want = _two_step_fp4_images(pa, pb, M, N, K)
+    ga = B.bdr_quantize_operand(f, A, image=B.OPERAND_FP4, b_operand=False)
+    gb = B.bdr_quantize_operand(f, Bm, image=B.OPERAND_FP4, b_operand=True)
+    torch.cuda.synchronize()
+    assert torch.equal(ga, ia), "image of A"
+    assert torch.equal(gb, ib), "image of B"
+    for cd in (torch.float32, torch.bfloat16):
+        C = B.mx_gemm_operands(f, f, ga, gb, M, N, K, image=B.OPERAND_FP4, dtype=cd)
+        w = B.mx_gemm(f, f, pa, pb, M, N, K, workspace=_workspace(M, N, K), dtype=cd)
+        assert torch.equal(C.view(torch.int32 if cd == torch.float32 else torch.int16),
+                           w.view(torch.int32 if cd == torch.float32 else torch.int16))
+    pan, pbn = _planes_np(pa), _planes_np(pb)
+    Cref = O.mx_gemm(ofmt(f), ofmt(f), pan, pbn, M, N, K)
+    Ah = O.dequantize(ofmt(f), *pan, M, K).astype(np.float64)
+    Bh = O.dequantize(ofmt(f), *pbn, N, K).astype(np.float64)
+    err = np.abs(B.mx_gemm_operands(f, f, ga, gb, M, N, K, image=B.OPERAND_FP4).cpu().numpy().astype(np.float64) - Cref)
+    assert np.all(err <= RTOL * (np.abs(Ah) @ np.abs(Bh).T) + 1e-30)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(128, 128), (384, 256), (1024, 640)])
+def test_fp4_operands_of_the_transpose(shape, dtype):
+    """Column blocks into the FP4 image: the image of the transpose equals the one the two-pass form
+    makes of the column-wise planes, also from a pitched view."""
+    rows, cols = shape
+    f = B.MX4
+    big = _special(S.wide_range(rows, cols + 256, device="cuda", seed=rows + cols, spread=8)).to(dtype)
+    for x in (big[:, :cols].contiguous(), big[:, 128:128 + cols]):
+        planes = B.bdr_quantize(f, x, axis=B.AXIS_COL)
+        ia, _, _ = _two_step_fp4_images(planes, planes, cols, cols, rows)
+        for b_operand in (False, True):
+            assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, image=B.OPERAND_FP4, b_operand=b_operand), ia)

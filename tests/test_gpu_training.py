@@ -33,7 +33,7 @@ def _close(got, want, absdot, what):
     assert np.all(err <= RTOL * absdot + 1e-30), (what, float((err / (absdot + 1e-30)).max()))
 
 
-@pytest.mark.parametrize("names", [("MX9", "MX9"), ("MX6", "MX9"), ("MX4", "MX6")])
+@pytest.mark.parametrize("names", [("MX9", "MX9"), ("MX6", "MX9"), ("MX4", "MX6"), ("MX4", "MX4")])
 @pytest.mark.parametrize("shape", [(128, 128, 128), (256, 384, 128), (192, 64, 320)])
 def test_linear_layer_flow_fp32(names, shape):
     T, I, Osz = shape
