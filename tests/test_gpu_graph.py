@@ -42,6 +42,10 @@ def test_calls_replay_from_a_graph():
     i9 = torch.empty(B.mx_operand_bytes(B.MX9, M, cols, B.OPERAND_BF16), dtype=torch.uint8, device="cuda")
     C9 = torch.empty(M, N, device="cuda")
     Ct = torch.empty(cols, cols, device="cuda")
+    i4 = torch.empty(B.mx_operand_bytes(B.MX4, M, cols, B.OPERAND_FP4), dtype=torch.uint8, device="cuda")
+    i4t = torch.empty(B.mx_operand_bytes(B.MX4, cols, rows, B.OPERAND_FP4), dtype=torch.uint8, device="cuda")
+    C4 = torch.empty(M, N, device="cuda")
+    C4t = torch.empty(cols, cols, dtype=torch.bfloat16, device="cuda")
     Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
     xr = x[:, :1000]                             # rows with a short last block, pitched
     pr = B.alloc_planes(f, rows, 1000)
@@ -67,6 +71,10 @@ def test_calls_replay_from_a_graph():
         B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, b_operand=True, out=ib)     # image of x^T [cols x rows]
         B.mx_gemm_operands(f, f, ib, ib, cols, cols, rows, out=Ct)
         B.mx_gemm(f, f, pa, pa, M, N, cols, out=Cb, workspace=gws)
+        B.bdr_quantize_operand(B.MX4, x[:M], image=B.OPERAND_FP4, out=i4)
+        B.mx_gemm_operands(B.MX4, B.MX4, i4, i4, M, N, cols, image=B.OPERAND_FP4, out=C4)
+        B.bdr_quantize_operand(B.MX4, x, axis=B.AXIS_COL, image=B.OPERAND_FP4, out=i4t)
+        B.mx_gemm_operands(B.MX4, B.MX4, i4t, i4t, cols, cols, rows, image=B.OPERAND_FP4, out=C4t)
         B.bdr_quantize(f, xr, out=pr)
         B.bdr_dequantize(f, pr, rows, 1000, out=yr)
 
@@ -81,7 +89,7 @@ def test_calls_replay_from_a_graph():
         graph.replay()
         torch.cuda.synchronize()
         every = (*planes, y, yf, out[0], out[1], C, out_s[0], out_s[1], *ph, yh, Cp, table, yt, ia, Co, ib, Ct, i9, C9,
-                 Cb, *pr, yr)
+                 Cb, i4, C4, i4t, C4t, *pr, yr)
         got = [t.clone() for t in every]
         for t in every:
             t.zero_()           # eager work of the program between replays
