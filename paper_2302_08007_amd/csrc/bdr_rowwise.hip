@@ -105,34 +105,111 @@ __device__ __forceinline__ void mx_store_group(uint32_t lo, uint32_t hi, uint32_
     }
 }
 
+// The planes of the ITERS x 64 consecutive groups one wave quantized (group gw + 64 it + lane in
+// it-th place), written from LDS of the wave's own.  A quad's 20 or 12 bytes of 5- or 3-bit codes
+// and its 2 + 2 exponent bytes would otherwise leave as 2-, 4- and 8-byte pieces, four store
+// instructions of such pieces per 64 groups.  Here they are put together in LDS (the same quad
+// funnel, the same DPP gather of the exponent bytes as mx_store_group) and leave as 16-byte
+// chunks of consecutive memory: one or two store instructions for the codes (8-bit codes are 8
+// consecutive bytes per lane and go out directly), one for both exponent planes.  All 64 lanes
+// call it; gw is a multiple of 64, the plane pointers are 16-byte aligned.
+template <int MB, int ITERS>
+struct WavePlanes {
+    static constexpr int CB = MB + 1, kGroups = 64 * ITERS;
+    static constexpr int kCodeBytes = CB == 8 ? 0 : kGroups * CB, kExpBytes = kGroups / 2;
+    static constexpr int kBytes = kCodeBytes + 2 * kExpBytes;
+    static_assert(kCodeBytes % 16 == 0 && kExpBytes % 16 == 0 && 2 * kExpBytes / 16 <= 64, "whole chunks");
+};
+
+template <int MB, int ITERS>
+__device__ __forceinline__ void wave_store_planes(const uint32_t (&lo)[ITERS], const uint32_t (&hi)[ITERS],
+                                                  const uint32_t (&se)[ITERS], const uint32_t (&tau4)[ITERS],
+                                                  int64_t gw, uint8_t *sp, uint8_t *__restrict__ codes,
+                                                  uint8_t *__restrict__ sexp, uint8_t *__restrict__ mexp)
+{
+    typedef WavePlanes<MB, ITERS> W;
+    constexpr int CB = W::CB;
+    const int lane = threadIdx.x & 63;
+    const uint32_t i = lane & 3u;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int quad = it * 16 + (lane >> 2);
+        uint32_t *qw = reinterpret_cast<uint32_t *>(sp) + quad * CB;  // the quad's CB dwords
+        const uint32_t nlo = dpp<kQuadNext>(lo[it]);
+        if (CB == 8) {
+            stg<kNtPlanes>(u32x2{lo[it], hi[it]}, reinterpret_cast<u32x2 *>(codes + 8 * (gw + it * 64 + lane)));
+        } else if (CB == 5) {
+            const uint32_t whi = hi[it] | (nlo << 8);
+            if (i == 0) {
+                qw[0] = lo[it];
+                qw[1] = whi;
+            } else {
+                qw[i + 1] = funnel_r(whi, lo[it], 32u - 8u * i);
+            }
+        } else {
+            if (i < 3) qw[i] = (lo[it] >> (8u * i)) | (nlo << (24u - 8u * i));
+        }
+        uint32_t r = (tau4[it] << (4u * i)) | (se[it] << (16u + 8u * (i >> 1)));
+        r |= dpp<kQuadXor1>(r);
+        r |= dpp<kQuadXor2>(r);
+        if ((i & 1u) == 0)
+            *reinterpret_cast<uint16_t *>(sp + W::kCodeBytes + (i == 0 ? 0 : W::kExpBytes) + 2 * quad) =
+                i == 0 ? (uint16_t)(r >> 16) : (uint16_t)(r & 0xffffu);
+    }
+    // LDS operations of one wave complete in order; keep the compiler from moving them
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const u32x4 *sc = reinterpret_cast<const u32x4 *>(sp);
+    if constexpr (CB != 8) {
+        u32x4 *gc = reinterpret_cast<u32x4 *>(codes + gw * CB);
+#pragma unroll
+        for (int k = 0; k < (W::kCodeBytes / 16 + 63) / 64; ++k)
+            if (64 * k + lane < W::kCodeBytes / 16) stg<kNtPlanes>(sc[64 * k + lane], gc + 64 * k + lane);
+    }
+    constexpr int kEC = W::kExpBytes / 16;  // chunks per exponent plane
+    if (lane < 2 * kEC) {
+        uint8_t *dst = (lane < kEC ? sexp : mexp) + gw / 2;
+        *(reinterpret_cast<u32x4 *>(dst) + (lane % kEC)) = sc[W::kCodeBytes / 16 + lane];
+    }
+}
+
 template <int MB, typename T>
 __global__ __launch_bounds__(kQThreads) void mx_quantize_row_kernel(
     const T *__restrict__ x, uint8_t *__restrict__ codes, uint8_t *__restrict__ sexp,
     uint8_t *__restrict__ mexp, int64_t n_groups)
 {
-    // A thread takes kIter groups, kQThreads apart; whole quads of lanes are in or
-    // out of range together (n_groups % 4 == 0).
     constexpr bool kStage = sizeof(T) == 4;  // FP32 rows arrive through LDS
     __shared__ float s_stage[kStage ? kQThreads / 64 : 1][kStage ? kWaveStage : 1];
     constexpr int kIter = q_iter<T>();
-    const int64_t g0 = (int64_t)blockIdx.x * (kQThreads * kIter) + threadIdx.x;
     uint32_t xb[kIter][8];
-    if constexpr (!kStage) {
-        // Every workgroup but the last is whole: no bounds checks, no lane masks, and nothing
-        // for the compiler to initialise on the paths a check would skip (1.8 of the 15 vector
-        // instructions per element of the checked form).
-        if ((int64_t)(blockIdx.x + 1) * (kQThreads * kIter) <= n_groups) {
+    // Every workgroup but the last is whole: no bounds checks, no lane masks, and nothing for the
+    // compiler to initialise on the paths a check would skip (1.8 of the 15 vector instructions per
+    // BF16 element of the checked form).  A wave then takes kIter x 64 consecutive groups.
+    if ((int64_t)(blockIdx.x + 1) * (kQThreads * kIter) <= n_groups) {
+        typedef WavePlanes<MB, kIter> W;
+        __shared__ __attribute__((aligned(16))) uint8_t s_planes[kQThreads / 64][W::kBytes];
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int64_t gw = (int64_t)blockIdx.x * (kQThreads * kIter) + wave * W::kGroups;  // the wave's first group
 #pragma unroll
-            for (int it = 0; it < kIter; ++it) load8(x + 8 * (g0 + it * kQThreads), xb[it]);
-#pragma unroll
-            for (int it = 0; it < kIter; ++it) {
-                uint32_t yb[8], lo, hi, se, tau4;
-                mx_quant8<MB, false>(xb[it], lo, hi, se, tau4, yb);
-                mx_store_group<MB>(lo, hi, se, tau4, g0 + it * kQThreads, codes, sexp, mexp);
-            }
-            return;
+        for (int it = 0; it < kIter; ++it) {
+            if constexpr (kStage)
+                wave_load512(reinterpret_cast<const float *>(x) + 8 * (gw + it * 64), xb[it], 512, s_stage[wave]);
+            else
+                load8(x + 8 * (gw + it * 64 + lane), xb[it]);
         }
+        uint32_t lo[kIter], hi[kIter], se[kIter], tau4[kIter];
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            uint32_t yb[8];
+            mx_quant8<MB, false>(xb[it], lo[it], hi[it], se[it], tau4[it], yb);
+        }
+        wave_store_planes<MB, kIter>(lo, hi, se, tau4, gw, s_planes[wave], codes, sexp, mexp);
+        return;
     }
+    // The last workgroup: a thread takes kIter groups, kQThreads apart; whole quads of lanes are in
+    // or out of range together (n_groups % 4 == 0).
+    const int64_t g0 = (int64_t)blockIdx.x * (kQThreads * kIter) + threadIdx.x;
 #pragma unroll
     for (int it = 0; it < kIter; ++it) {
         const int64_t g = g0 + it * kQThreads;
