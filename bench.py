@@ -698,6 +698,18 @@ def other_legs(B, S, torch, timed):
             tf = 3 * 2.0 * T * I * Osz / (t * 1e-3) / 1e12
             out["mx_linear_fwd_bwd_8192x12288x12288_%s_bf16" % name] = {
                 "ms": round(t, 3), "TFLOPs": round(tf, 1), key: round(tf / peak, 4)}
+        # direct-cast inference (Sec. V, "Inferencing"): the weight's operand image is made once,
+        # a call quantizes the 8192 x 12288 BF16 activations into theirs and multiplies
+        from paper_2302_08007_amd.training import MXWeight, mx_linear_inference
+        leg = {}
+        for an, wn in (("MX9", "MX9"), ("MX6", "MX6"), ("MX6", "MX4"), ("MX4", "MX4")):
+            wq = MXWeight(w.detach(), getattr(B, wn))
+            fa = getattr(B, an)
+            with torch.no_grad():
+                t = timed(lambda: mx_linear_inference(x, wq, fa), reps=10, inner=2, warm=12)
+            leg["act_%s_weight_%s" % (an, wn)] = {"ms": round(t, 3), "TFLOPs": round(2.0 * T * I * Osz / (t * 1e-3) / 1e12, 1)}
+            del wq
+        out["mx_linear_inference_8192x12288x12288_bf16"] = leg
     except B.BdrError as e:
         out["mx_linear_fwd_bwd_8192x12288x12288_MX9_bf16"] = {"error": str(e)}
     return out

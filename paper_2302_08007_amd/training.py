@@ -90,6 +90,15 @@ class _MXLinear(torch.autograd.Function):
         O = w.shape[0]
         g = g.contiguous()
         gx = gw = None
+        if f is FP32_BACKWARD:
+            # quantization-aware fine-tuning (Sec. VI, "Inferencing with the MX data format"): the
+            # forward pass is the MX one, the backward pass is not quantized at all, so it is the
+            # framework's own matrix product on the unquantized tensors
+            if ctx.needs_input_grad[0]:
+                gx = (g.float() @ w.float()).to(x.dtype)
+            if ctx.needs_input_grad[1]:
+                gw = (g.float().t() @ x.float()).to(w.dtype)
+            return gx, gw, None, None
         if ctx.needs_input_grad[0]:
             gx = _mx_matmul(f, f, g, AXIS_ROW, w, AXIS_COL, T, I, O, x.dtype)
         if ctx.needs_input_grad[1]:
@@ -97,9 +106,75 @@ class _MXLinear(torch.autograd.Function):
         return gx, gw, None, None
 
 
+FP32_BACKWARD = object()   # as fmt_bwd: leave the backward pass unquantized
+
+
 def mx_linear(x, w, fmt_fwd, fmt_bwd=None):
     """y = x w^T with the forward, backward-data and backward-weight products all computed on
     MX-quantized operands (formats of Table II: MX9, MX6 or MX4).  x [T, I] and w [O, I] are
     contiguous FP32 or BF16 CUDA tensors with T, I and O multiples of 64 (each is the reduction
-    length of one of the three products)."""
+    length of one of the three products).  fmt_bwd = FP32_BACKWARD keeps the MX forward pass
+    and computes both gradients in FP32 on the unquantized tensors (the paper's
+    quantization-aware fine-tuning setting)."""
     return _MXLinear.apply(x, w, fmt_fwd, fmt_bwd if fmt_bwd is not None else fmt_fwd)
+
+
+# ---- inference: direct cast (Sec. V, "Inferencing")
+#
+# A trained weight matrix is cast to its MX format once; every call then quantizes only the
+# activations and multiplies.  Weights and activations may have different formats (the paper's
+# generative-inference table pairs them freely); the pair decides the kind of operand image.
+
+def _image_kind(fa, fb):
+    if fa.m == 2 and fb.m == 2:
+        return OPERAND_FP4
+    return OPERAND_FP6 if fa.m <= 4 and fb.m <= 4 else OPERAND_BF16
+
+
+class MXWeight:
+    """w [O, I] cast to `fmt` (a Table II format), blocks along I: the B operand of y = x w^T.
+    The operand image is made on first use for each image kind an activation format asks for
+    and kept; the weight itself is not referenced again."""
+
+    def __init__(self, w, fmt):
+        if w.dim() != 2 or not w.is_cuda or w.dtype not in (torch.float32, torch.bfloat16):
+            raise ValueError("w must be a 2-D float32 or bfloat16 CUDA tensor")
+        self.fmt, self.shape, self.dtype = fmt, tuple(w.shape), w.dtype
+        self._w = w.detach().contiguous()
+        self._images = {}
+
+    def image(self, kind):
+        img = self._images.get(kind)
+        if img is None:
+            O, I = self.shape
+            if mx_operand_bytes(self.fmt, O, I, kind) == 0:
+                raise ValueError("weight of shape %s in this format has no operand image of kind %d "
+                                 "(I must be a multiple of 64; of 128 for an MX4 x MX4 product)" % (self.shape, kind))
+            img = bdr_quantize_operand(self.fmt, self._w, axis=AXIS_ROW, image=kind, b_operand=True)
+            self._images[kind] = img
+        return img
+
+    def drop_source(self):
+        """Forget the unquantized weight (images made so far stay)."""
+        self._w = None
+
+
+def mx_linear_inference(x, weight, act_fmt, out_dtype=None):
+    """y [T, O] = Q_act(x) Q_w(w)^T for x [T, I] (contiguous FP32 or BF16 CUDA tensor, I as the
+    weight's) and an MXWeight: the activations are quantized straight into the operand image,
+    the weight's image is reused.  FP4 images and products when both formats are MX4 and I is a
+    multiple of 128, FP6 when both have m <= 4, BF16 otherwise."""
+    T, I = x.shape
+    O, I2 = weight.shape
+    if I != I2:
+        raise ValueError("x [T, %d] against w [O, %d]" % (I, I2))
+    kind = _image_kind(act_fmt, weight.fmt)
+    if kind == OPERAND_FP4 and I % 128:
+        kind = OPERAND_FP6
+    na = mx_operand_bytes(act_fmt, T, I, kind)
+    if na == 0 or not _direct(act_fmt, x, AXIS_ROW, T, I, kind):
+        raise ValueError("activations of shape %s cannot be quantized into an operand image (I a multiple "
+                         "of 64, rows 16-byte aligned)" % (tuple(x.shape),))
+    ib = weight.image(kind)
+    ia = bdr_quantize_operand(act_fmt, x, axis=AXIS_ROW, image=kind, b_operand=False, out=_workspace(x.device, na)[:na])
+    return mx_gemm_operands(act_fmt, weight.fmt, ia, ib, T, O, I, image=kind, dtype=out_dtype or x.dtype)

@@ -7,7 +7,7 @@ import torch
 
 import oracle as O
 import paper_2302_08007_amd as B
-from paper_2302_08007_amd.training import mx_linear
+from paper_2302_08007_amd.training import FP32_BACKWARD, MXWeight, mx_linear, mx_linear_inference
 from gpu_util import ofmt, to_np
 
 pytestmark = pytest.mark.gpu
@@ -107,3 +107,49 @@ def test_two_streams_do_not_share_a_workspace():
         assert torch.equal(got[k], want[k])
     training.release_workspaces()
     assert not training._workspaces
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("names", [("MX9", "MX9"), ("MX6", "MX6"), ("MX9", "MX6"), ("MX6", "MX4"), ("MX4", "MX4")])
+@pytest.mark.parametrize("shape", [(128, 256, 128), (100, 192, 72), (257, 1024, 384)])
+def test_direct_cast_inference(shape, names, dtype):
+    """Sec. V, "Inferencing": the weight is cast once, the activations at every call; the result is
+    the product of what the oracle's quantize + dequantize make of both, and calling again with
+    other activations reuses the weight's image."""
+    T, I, Osz = shape
+    fa, fw = getattr(B, names[0]), getattr(B, names[1])      # (activations, weights)
+    g = torch.Generator(device="cuda").manual_seed(T + 3 * I + Osz)
+    w = (torch.randn(Osz, I, generator=g, device="cuda") / I ** 0.5).to(dtype)
+    wq = MXWeight(w, fw)
+    wn = to_np(w)
+    wa = _qdq(fw, wn, O.AXIS_ROW)
+    for rep in range(2):
+        x = torch.randn(T, I, generator=g, device="cuda").to(dtype)
+        y = mx_linear_inference(x, wq, fa, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        xa = _qdq(fa, to_np(x), O.AXIS_ROW)
+        _close(to_np(y), xa @ wa.T, np.abs(xa) @ np.abs(wa).T, "inference %d" % rep)
+        if rep == 0:
+            wq.drop_source()
+    assert len(wq._images) == 1
+    with pytest.raises(ValueError):
+        mx_linear_inference(torch.zeros(T, I + 64, device="cuda", dtype=dtype), wq, fa)
+
+
+def test_fine_tuning_flow_keeps_the_backward_pass_unquantized():
+    """Quantization-aware fine-tuning as the paper runs it: MX6 forward (checked against the oracle
+    flow), gradients in FP32 on the unquantized tensors."""
+    T, I, Osz = 192, 256, 128
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.randn(T, I, generator=g, device="cuda", requires_grad=True)
+    w = (torch.randn(Osz, I, generator=g, device="cuda") / 16).requires_grad_()
+    gy = torch.randn(T, Osz, generator=g, device="cuda")
+    y = mx_linear(x, w, B.MX6, FP32_BACKWARD)
+    y.backward(gy)
+    torch.cuda.synchronize()
+    xn, wn, gn = to_np(x), to_np(w), to_np(gy)
+    xa, wa = _qdq(B.MX6, xn, O.AXIS_ROW), _qdq(B.MX6, wn, O.AXIS_ROW)
+    _close(to_np(y), xa @ wa.T, np.abs(xa) @ np.abs(wa).T, "forward")
+    gx, gw = gn.astype(np.float64) @ wn.astype(np.float64), gn.astype(np.float64).T @ xn.astype(np.float64)
+    _close(to_np(x.grad), gx, np.abs(gn).astype(np.float64) @ np.abs(wn).astype(np.float64), "backward-data")
+    _close(to_np(w.grad), gw, np.abs(gn).astype(np.float64).T @ np.abs(xn).astype(np.float64), "backward-weight")
