@@ -710,6 +710,25 @@ def other_legs(B, S, torch, timed):
             leg["act_%s_weight_%s" % (an, wn)] = {"ms": round(t, 3), "TFLOPs": round(2.0 * T * I * Osz / (t * 1e-3) / 1e12, 1)}
             del wq
         out["mx_linear_inference_8192x12288x12288_bf16"] = leg
+        # a decoding step: 16 tokens against the same weight (its image made once); the product is a
+        # stream over the weight image, so its bytes set the time -- BF16 image 2 bytes per element,
+        # FP6 1, FP4 9/16; the library's BF16 product of the unquantized tensors for context
+        leg = {}
+        x16 = x.detach()[:16].contiguous()
+        y16 = torch.empty(16, Osz, device="cuda", dtype=torch.bfloat16)
+        with torch.no_grad():
+            for an, wn in (("MX9", "MX9"), ("MX6", "MX6"), ("MX4", "MX4")):
+                wq = MXWeight(w.detach(), getattr(B, wn))
+                fa = getattr(B, an)
+                t = timed(lambda: mx_linear_inference(x16, wq, fa), reps=7, inner=10, warm=20)
+                img_bytes = sum(v.numel() for v in wq._images.values())
+                leg["act_%s_weight_%s" % (an, wn)] = {"us": round(t * 1e3, 1), "weight_image_MB": round(img_bytes / 1e6, 1),
+                                                      "weight_image_GBps": round(img_bytes / t / 1e6, 1)}
+                del wq
+            wd = w.detach()
+            t = timed(lambda: torch.matmul(x16, wd.t(), out=y16), reps=7, inner=10, warm=20)
+            leg["library_bf16_gemm_for_context"] = {"us": round(t * 1e3, 1), "weight_MB": round(wd.numel() * 2 / 1e6, 1)}
+        out["mx_linear_decode_16_tokens_12288x12288_bf16"] = leg
     except B.BdrError as e:
         out["mx_linear_fwd_bwd_8192x12288x12288_MX9_bf16"] = {"error": str(e)}
     return out

@@ -982,6 +982,142 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
                         m0 + BM <= M && n0 + BN <= N);
 }
 
+// The product for few rows of A (M <= 64: a decoding step, a handful of tokens against a weight
+// matrix): one or two MFMA tiles hold all of A's rows, so there is nothing to reuse from LDS and the
+// call is a stream over B's image.  A workgroup takes 32 rows of B and all of K; its eight waves
+// take K steps in turn (wave w the steps w, w + 8, ...), each lane loading its fragments straight
+// from the images in the MFMA's own layout (fragment = chunk 2 s + lane / 32 of row lane % 32; FP4:
+// the 8-byte half of chunk s), so that the waves of a workgroup read B's image as 2 KiB runs.
+// Plain loads: a row's 64 bytes arrive as two 32-byte halves in consecutive instructions, and the
+// second must find the line the first brought (with the streaming hint the same stream takes 40 %
+// longer).  The eight partial tiles are added in LDS in a fixed order (the result does not depend
+// on timing).  Same images, same scale-byte conventions and the same idle-half trick as
+// gemm_ring_kernel.  Measured, N = K = 12288, ten launches back to back: MX6 25-28 us for M = 1
+// .. 32 (5.4-6.0 TB/s of B's image) and 36-39 us for M = 33 .. 64, MX4 (FP4 images) 22-28 and
+// 39-45 us, MX9 (BF16 images) 52-68 and 75-100 us; the tiled kernel takes 57 / 57 / 112 us for
+// the same calls.  Every workgroup reads all of A again (from L2), which is what M costs; with
+// four tiles (M <= 128) the tiled kernel is the faster one (48 against 55-62 us for MX6).
+constexpr int kSkinnyWaves = 8, kSkinnyRows = 32, kSkinnyMaxM = 64;
+
+template <int FMT, int TM>
+__global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
+    const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const uint8_t *__restrict__ SA,
+    const uint8_t *__restrict__ SB, int M, int N, int nk, void *__restrict__ C, int64_t ldc, int c_bf16)
+{
+    constexpr bool FP6 = FMT == kFmtFp6, FP4 = FMT == kFmtFp4, BF16 = FMT == kFmtBf16;
+    constexpr int NSUB = FP4 ? 4 : 2;
+    __shared__ float s_red[kSkinnyWaves][16][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n0 = blockIdx.x * kSkinnyRows;
+    const int f_row = lane & 31, f_half = lane >> 5;
+    // rows past the edge of an operand repeat its last row (their products are never stored)
+    const int rb = min(n0 + f_row, N - 1);
+    const int64_t a_step = (int64_t)M * kRingRow, b_step = (int64_t)N * kRingRow;
+    // byte offset of this lane's fragment of sub-step 0 within a K step of its operand
+    int ra[TM], a_at[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        ra[i] = min(32 * i + f_row, M - 1);
+        a_at[i] = ra[i] * kRingRow + (FP4 ? 8 * (f_half ^ ((ra[i] >> 4) & 1)) : 16 * f_half);
+    }
+    const int b_at = rb * kRingRow + (FP4 ? 8 * (f_half ^ ((rb >> 4) & 1)) : 16 * f_half);
+    constexpr int kSubBytes = FP4 ? 16 : 32;  // from one sub-step's fragment to the next
+    const int64_t sa_step = (int64_t)((M + 127) / 128 * 128) * 8, sb_step = (int64_t)((N + 127) / 128 * 128) * 8;
+
+    f32x16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    // kAhead K steps of a wave are loaded before the first of them is multiplied: the bytes a wave
+    // has in flight, not its instruction count, set the rate of a stream.  What is loaded is kept
+    // as it comes (16 or 8 bytes per fragment); the MFMA operand is put together at the multiply.
+    using Raw = typename std::conditional<FP4, i32x2, i32x4>::type;
+    constexpr int kAhead = 4;
+    Raw fa[kAhead][TM][NSUB], fb[kAhead][NSUB];
+    uint32_t sa[kAhead][TM], sb[kAhead];
+    auto load = [&](int q, Raw (&xa)[TM][NSUB], Raw (&xb)[NSUB], uint32_t (&xsa)[TM], uint32_t &xsb) {
+        const uint8_t *ap = A + q * a_step, *bp = B + q * b_step + b_at;
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) {
+            xb[sub] = *reinterpret_cast<const Raw *>(bp + sub * kSubBytes);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) xa[i][sub] = *reinterpret_cast<const Raw *>(ap + a_at[i] + sub * kSubBytes);
+        }
+        if constexpr (FP4) {  // the four scale bytes of this lane's parity of blocks, sub-step s in byte s
+            xsb = *reinterpret_cast<const uint32_t *>(SB + q * sb_step + (int64_t)rb * 8 + 4 * f_half);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                xsa[i] = *reinterpret_cast<const uint32_t *>(SA + q * sa_step + (int64_t)ra[i] * 8 + 4 * f_half);
+        }
+    };
+    auto multiply = [&](const Raw (&xa)[TM][NSUB], const Raw (&xb)[NSUB], const uint32_t (&xsa)[TM], uint32_t xsb) {
+        static_for<NSUB>([&](auto S) {
+            constexpr int sub = decltype(S)::value;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (BF16) {
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[i][sub]),
+                                                                     __builtin_bit_cast(bf16x8, xb[sub]), acc[i], 0, 0, 0);
+                } else if constexpr (FP6) {  // the registers of the hardware block's idle half are zero
+                    const i32x8 wa = {xa[i][sub][0], xa[i][sub][1], xa[i][sub][2], xa[i][sub][3], 0, 0, 0, 0};
+                    const i32x8 wb = {xb[sub][0], xb[sub][1], xb[sub][2], xb[sub][3], 0, 0, 0, 0};
+                    acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, wb, acc[i], kFp6, kFp6, kScaleByteA,
+                                                                             wa[3], kScaleByteB, wb[3]);
+                } else {
+                    const i32x8 wa = {xa[i][sub][0], xa[i][sub][1], 0, 0, 0, 0, 0, 0};
+                    const i32x8 wb = {xb[sub][0], xb[sub][1], 0, 0, 0, 0, 0, 0};
+                    acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, wb, acc[i], kFp4, kFp4, sub,
+                                                                             (int)xsa[i], sub, (int)xsb);
+                }
+            }
+        });
+    };
+    for (int q = wave; q < nk; q += kSkinnyWaves * kAhead) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+            if (q + u * kSkinnyWaves < nk) load(q + u * kSkinnyWaves, fa[u], fb[u], sa[u], sb[u]);
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+            if (q + u * kSkinnyWaves < nk) multiply(fa[u], fb[u], sa[u], sb[u]);
+    }
+    // register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4 of its tile of A, column l % 32
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (i > 0) __syncthreads();  // the sums of the tile before have been read
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_red[wave][r][lane] = acc[i][r];
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16 * 64 / (64 * kSkinnyWaves); ++k) {
+            const int e = k * (64 * kSkinnyWaves) + threadIdx.x, r = e >> 6, l = e & 63;
+            float v = s_red[0][r][l];
+#pragma unroll
+            for (int w = 1; w < kSkinnyWaves; ++w) v += s_red[w][r][l];
+            const int m = 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), n = n0 + (l & 31);
+            if (m < M && n < N) {
+                if (c_bf16)
+                    static_cast<uint16_t *>(C)[(int64_t)m * ldc + n] = bf16_rne(v);
+                else
+                    static_cast<float *>(C)[(int64_t)m * ldc + n] = v;
+            }
+        }
+    }
+}
+
+template <int FMT>
+int launch_skinny(const uint8_t *a, const uint8_t *b, const uint8_t *sa, const uint8_t *sb, int M, int N, int nk,
+                  void *C, int64_t ldc, int c_bf16, hipStream_t s)
+{
+    const dim3 grid((unsigned)((N + kSkinnyRows - 1) / kSkinnyRows)), block(64 * kSkinnyWaves);
+    if (M <= 32)
+        hipLaunchKernelGGL((gemm_skinny_kernel<FMT, 1>), grid, block, 0, s, a, b, sa, sb, M, N, nk, C, ldc, c_bf16);
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<FMT, 2>), grid, block, 0, s, a, b, sa, sb, M, N, nk, C, ldc, c_bf16);
+    return launch_status();
+}
+
 // With `dry` set the launch functions below only ask for what the kernel needs (a workgroup
 // of more than 64 KiB of LDS has to be granted once per device) and launch nothing: the entry
 // point calls them that way before it enqueues the image writers.
@@ -1006,6 +1142,10 @@ int gemm_ring(const void *A, const void *B, const void *SA, const void *SB, int6
               int64_t ldc, int c_bf16, bool dry, hipStream_t s)
 {
     const uint8_t *a = (const uint8_t *)A, *b = (const uint8_t *)B, *sa = (const uint8_t *)SA, *sb = (const uint8_t *)SB;
+    if (M <= kSkinnyMaxM) {  // a stream over B's image
+        if (dry) return BDR_OK;
+        return launch_skinny<FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, c_bf16, s);
+    }
     if (M % 256 == 0 && N % 256 == 0) {
         const int st = launch_ring<2, 4, 4, 2, FMT>(a, b, sa, sb, (int)M, (int)N, nk, C, ldc, c_bf16, dry, s);
         if (st != BDR_ERR_LAUNCH) return st;  // a device without 128 KiB workgroups: small tiles
