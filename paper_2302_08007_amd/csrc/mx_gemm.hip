@@ -987,14 +987,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
 // call is a stream over B's image.  A workgroup takes 32 rows of B and all of K; its eight waves
 // take K steps in turn (wave w the steps w, w + 8, ...), each lane loading its fragments straight
 // from the images in the MFMA's own layout (fragment = chunk 2 s + lane / 32 of row lane % 32; FP4:
-// the 8-byte half of chunk s), so that the waves of a workgroup read B's image as 2 KiB runs.
+// see below), so that the waves of a workgroup read B's image as 2 KiB runs.
 // Plain loads: a row's 64 bytes arrive as two 32-byte halves in consecutive instructions, and the
 // second must find the line the first brought (with the streaming hint the same stream takes 40 %
 // longer).  The eight partial tiles are added in LDS in a fixed order (the result does not depend
 // on timing).  Same images, same scale-byte conventions and the same idle-half trick as
 // gemm_ring_kernel.  Measured, N = K = 12288, ten launches back to back: MX6 25-28 us for M = 1
-// .. 32 (5.4-6.0 TB/s of B's image) and 36-39 us for M = 33 .. 64, MX4 (FP4 images) 22-28 and
-// 39-45 us, MX9 (BF16 images) 52-68 and 75-100 us; the tiled kernel takes 57 / 57 / 112 us for
+// .. 32 (5.4-6.0 TB/s of B's image) and 36-39 us for M = 33 .. 64, MX4 (FP4 images) 18-20 and
+// 27-30 us, MX9 (BF16 images) 52-68 and 75-100 us; the tiled kernel takes 57 / 57 / 112 us for
 // the same calls.  Every workgroup reads all of A again (from L2), which is what M costs; with
 // four tiles (M <= 128) the tiled kernel is the faster one (48 against 55-62 us for MX6).
 constexpr int kSkinnyWaves = 8, kSkinnyRows = 32, kSkinnyMaxM = 64;
@@ -1014,16 +1014,22 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
     // rows past the edge of an operand repeat its last row (their products are never stored)
     const int rb = min(n0 + f_row, N - 1);
     const int64_t a_step = (int64_t)M * kRingRow, b_step = (int64_t)N * kRingRow;
-    // byte offset of this lane's fragment of sub-step 0 within a K step of its operand
+    // A lane loads two 16-byte pieces per K step and operand.  FP6 / BF16: the fragments of the
+    // two sub-steps (chunks f_half and 2 + f_half).  FP4: which of a K step's eight blocks meet in
+    // which of the four MFMAs is free as long as both operands agree, so the lower half wave takes
+    // blocks 0-3 (chunks 0, 1) and the upper one blocks 4-7 (chunks 2, 3): 32 consecutive bytes
+    // instead of four 8-byte pieces.
+    constexpr int kPiece = FP4 ? 16 : 32;  // from a lane's first piece to its second
     int ra[TM], a_at[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         ra[i] = min(32 * i + f_row, M - 1);
-        a_at[i] = ra[i] * kRingRow + (FP4 ? 8 * (f_half ^ ((ra[i] >> 4) & 1)) : 16 * f_half);
+        a_at[i] = ra[i] * kRingRow + (FP4 ? 32 : 16) * f_half;
     }
-    const int b_at = rb * kRingRow + (FP4 ? 8 * (f_half ^ ((rb >> 4) & 1)) : 16 * f_half);
-    constexpr int kSubBytes = FP4 ? 16 : 32;  // from one sub-step's fragment to the next
+    const int b_at = rb * kRingRow + (FP4 ? 32 : 16) * f_half;
     const int64_t sa_step = (int64_t)((M + 127) / 128 * 128) * 8, sb_step = (int64_t)((N + 127) / 128 * 128) * 8;
+    // FP4: the scale bytes of blocks 4 h + s, s = 0 .. 3, out of the even blocks' and the odd blocks' words
+    const uint32_t scale_sel = f_half ? 0x07030602u : 0x05010400u;
 
     f32x16 acc[TM];
 #pragma unroll
@@ -1032,27 +1038,33 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
     // kAhead K steps of a wave are loaded before the first of them is multiplied: the bytes a wave
     // has in flight, not its instruction count, set the rate of a stream.  What is loaded is kept
-    // as it comes (16 or 8 bytes per fragment); the MFMA operand is put together at the multiply.
-    using Raw = typename std::conditional<FP4, i32x2, i32x4>::type;
+    // as it comes; the MFMA operand is put together at the multiply.
     constexpr int kAhead = 4;
-    Raw fa[kAhead][TM][NSUB], fb[kAhead][NSUB];
-    uint32_t sa[kAhead][TM], sb[kAhead];
-    auto load = [&](int q, Raw (&xa)[TM][NSUB], Raw (&xb)[NSUB], uint32_t (&xsa)[TM], uint32_t &xsb) {
+    i32x4 fa[kAhead][TM][2], fb[kAhead][2];
+    i32x2 sa[kAhead][TM], sb[kAhead];
+    auto load = [&](int q, i32x4 (&xa)[TM][2], i32x4 (&xb)[2], i32x2 (&xsa)[TM], i32x2 &xsb) {
         const uint8_t *ap = A + q * a_step, *bp = B + q * b_step + b_at;
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) {
-            xb[sub] = *reinterpret_cast<const Raw *>(bp + sub * kSubBytes);
+        for (int k = 0; k < 2; ++k) {
+            xb[k] = *reinterpret_cast<const i32x4 *>(bp + k * kPiece);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) xa[i][sub] = *reinterpret_cast<const Raw *>(ap + a_at[i] + sub * kSubBytes);
+            for (int i = 0; i < TM; ++i) xa[i][k] = *reinterpret_cast<const i32x4 *>(ap + a_at[i] + k * kPiece);
         }
-        if constexpr (FP4) {  // the four scale bytes of this lane's parity of blocks, sub-step s in byte s
-            xsb = *reinterpret_cast<const uint32_t *>(SB + q * sb_step + (int64_t)rb * 8 + 4 * f_half);
+        if constexpr (FP4) {  // a row's eight scale bytes of the step: even blocks' four, odd blocks' four
+            xsb = *reinterpret_cast<const i32x2 *>(SB + q * sb_step + (int64_t)rb * 8);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                xsa[i] = *reinterpret_cast<const uint32_t *>(SA + q * sa_step + (int64_t)ra[i] * 8 + 4 * f_half);
+            for (int i = 0; i < TM; ++i) xsa[i] = *reinterpret_cast<const i32x2 *>(SA + q * sa_step + (int64_t)ra[i] * 8);
         }
     };
-    auto multiply = [&](const Raw (&xa)[TM][NSUB], const Raw (&xb)[NSUB], const uint32_t (&xsa)[TM], uint32_t xsb) {
+    // FP4: block j (0 .. 3) of the lane's four out of its two chunks; rows with bit 4 set keep the
+    // two blocks of a chunk in swapped order
+    auto fp4_block = [&](const i32x4 (&x)[2], int j, bool swapped) {
+        const i32x4 c = x[j >> 1];
+        const bool second = ((j & 1) != 0) != swapped;
+        return i32x8{second ? c[2] : c[0], second ? c[3] : c[1], 0, 0, 0, 0, 0, 0};
+    };
+    const bool b_swapped = (rb >> 4) & 1;
+    auto multiply = [&](const i32x4 (&xa)[TM][2], const i32x4 (&xb)[2], const i32x2 (&xsa)[TM], i32x2 xsb) {
         static_for<NSUB>([&](auto S) {
             constexpr int sub = decltype(S)::value;
 #pragma unroll
@@ -1066,10 +1078,11 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
                     acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, wb, acc[i], kFp6, kFp6, kScaleByteA,
                                                                              wa[3], kScaleByteB, wb[3]);
                 } else {
-                    const i32x8 wa = {xa[i][sub][0], xa[i][sub][1], 0, 0, 0, 0, 0, 0};
-                    const i32x8 wb = {xb[sub][0], xb[sub][1], 0, 0, 0, 0, 0, 0};
-                    acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, wb, acc[i], kFp4, kFp4, sub,
-                                                                             (int)xsa[i], sub, (int)xsb);
+                    const i32x8 wa = fp4_block(xa[i], sub, (ra[i] >> 4) & 1), wb = fp4_block(xb, sub, b_swapped);
+                    const uint32_t ka = __builtin_amdgcn_perm((uint32_t)xsa[i][1], (uint32_t)xsa[i][0], scale_sel);
+                    const uint32_t kb = __builtin_amdgcn_perm((uint32_t)xsb[1], (uint32_t)xsb[0], scale_sel);
+                    acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa, wb, acc[i], kFp4, kFp4, sub, (int)ka,
+                                                                             sub, (int)kb);
                 }
             }
         });
