@@ -330,6 +330,16 @@ def aux_probe(B, S, torch):
     img9 = torch.empty(B.mx_operand_bytes(B.MX9, ra, ca, B.OPERAND_BF16), dtype=torch.uint8, device="cuda")
     img4 = torch.empty(B.mx_operand_bytes(B.MX4, ra, ca, B.OPERAND_FP4), dtype=torch.uint8, device="cuda")
     img4t = torch.empty(B.mx_operand_bytes(B.MX4, ca, ra, B.OPERAND_FP4), dtype=torch.uint8, device="cuda")
+    # a decoding step's product: 16 rows against the image of an [8192 x 8192] weight (a slice of the
+    # activation tensor: any values do)
+    wsrc = xa[:, :8192].float()                            # [8192 x 8192] as a weight [N x K] (FP32 source:
+    #                                                        these set-up launches are not the probed kernels)
+    wimg6 = B.bdr_quantize_operand(B.MX6, wsrc, image=B.OPERAND_FP6, b_operand=True)
+    wimg4 = B.bdr_quantize_operand(B.MX4, wsrc, image=B.OPERAND_FP4, b_operand=True)
+    a16 = wsrc[:16].contiguous()
+    aimg6 = B.bdr_quantize_operand(B.MX6, a16, image=B.OPERAND_FP6)
+    aimg4 = B.bdr_quantize_operand(B.MX4, a16, image=B.OPERAND_FP4)
+    c16 = torch.empty(16, 8192, device="cuda")
     xc = x.view(-1)[:8192 * 8192].view(8192, 8192)   # a square slice for the column-wise general kernel
     yc = y.view(-1)[:8192 * 8192].view(8192, 8192)
     pc = B.alloc_planes(fh, 8192, 8192, B.AXIS_COL)
@@ -348,6 +358,8 @@ def aux_probe(B, S, torch):
         B.bdr_quantize_operand(B.MX9, xa, axis=B.AXIS_COL, image=B.OPERAND_BF16, out=img9)
         B.bdr_quantize_operand(B.MX4, xa, axis=B.AXIS_ROW, image=B.OPERAND_FP4, out=img4)
         B.bdr_quantize_operand(B.MX4, xa, axis=B.AXIS_COL, image=B.OPERAND_FP4, out=img4t)
+        B.mx_gemm_operands(B.MX6, B.MX6, aimg6, wimg6, 16, 8192, 8192, image=B.OPERAND_FP6, out=c16)
+        B.mx_gemm_operands(B.MX4, B.MX4, aimg4, wimg4, 16, 8192, 8192, image=B.OPERAND_FP4, out=c16)
         B.bdr_quantize(fh, x, out=ph)
         B.bdr_dequantize(fh, ph, rows, cols, out=y)
         B.bdr_quantize(fr, x, out=pr)
@@ -357,7 +369,7 @@ def aux_probe(B, S, torch):
     torch.cuda.synchronize()
     print(json.dumps({"aux_probe": "3 x (1 GiB copy; MX9 bf16 8192x12288 column quantize, dequantize, fused, "
                                    "row quantize, dequantize; MX6 gather 2^20 x 128 from planes and from the table image; the same "
-                                   "bf16 tensor to the MX6 (FP6), MX9 (BF16) and MX4 (FP4) operand images, row and column blocks; k1 32 k2 2 d2 1 m 4 and "
+                                   "bf16 tensor to the MX6 (FP6), MX9 (BF16) and MX4 (FP4) operand images, row and column blocks; the product of 16 rows with an 8192 x 8192 MX6 (FP6) and MX4 (FP4) image; k1 32 k2 2 d2 1 m 4 and "
                                    "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32; k1 32 k2 2 d2 1 m 4 "
                                    "column quantize, dequantize on 8192 x 8192 fp32)"}))
 
