@@ -1,8 +1,8 @@
 /* A plain C caller of libbdr_mx.so: no Python, no PyTorch, only the HIP runtime for device
  * memory.  It runs the hot path of the library through its C ABI (packed sizes, quantize,
- * dequantize, the fused round trip, the QSNR sweep) on a seeded tensor and checks every byte of
- * the three planes and every dequantized value against the CPU oracle, which it also calls
- * through its C interface.  Test infrastructure: built and run by tests/test_gpu_c_abi.py. */
+ * dequantize, the fused round trip, the QSNR sweep, operand images and their products) on a seeded
+ * tensor and checks every byte of the three planes, every dequantized value and every product
+ * against the CPU oracle, which it also calls through its C interface.  Test infrastructure: built and run by tests/test_gpu_c_abi.py. */
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -136,7 +136,52 @@ int main(void)
             fprintf(stderr, "QSNR of format %d: %.9g dB against %.9g\n", k, q[k], wq[k]);
             return 6;
         }
-    printf("ok: %d formats, both axes, a ragged shape, the sweep (MX9 %.3f dB, MX6 %.3f dB, MX4 %.3f dB)\n", nf, q[0],
-           q[1], q[2]);
+    /* Products on operand images the quantizer writes itself (Sec. V: both inputs of a tensor
+     * operation quantized along the reduction axis): A = the first M rows of x, B = its first N
+     * rows, K = cols; few rows of A (the streaming kernel) and many (the tiled ones), each image kind.
+     * Expected: the oracle's product of the oracle's planes, within 1e-4 of sum |a b|. */
+    {
+        const int64_t N = 256, K = cols, Ms[2] = {16, 192};
+        const int kinds[3] = {BDR_OPERAND_BF16, BDR_OPERAND_FP6, BDR_OPERAND_FP4}; /* for MX9, MX6, MX4 */
+        float *c = malloc(sizeof(float) * 192 * N), *want = malloc(sizeof(float) * 192 * N);
+        double *absdot = malloc(sizeof(double) * 192 * N);
+        int64_t *ii = malloc(sizeof(int64_t) * 192 * N), *jj = malloc(sizeof(int64_t) * 192 * N);
+        void *dc, *ia, *ib;
+        CHECK_HIP(hipMalloc(&dc, sizeof(float) * 192 * N));
+        CHECK_HIP(hipMalloc(&ia, (size_t)192 * K * 2));
+        CHECK_HIP(hipMalloc(&ib, (size_t)N * K * 2));
+        for (int k = 0; k < 3; ++k) {
+            size_t cb, sb, mb;
+            if (bdr_ref_packed_sizes(&rf[k], rows, K, 0, &cb, &sb, &mb) != 0) return 4;
+            uint8_t *pc = malloc(cb), *ps = malloc(sb), *pm = malloc(mb);
+            if (bdr_ref_quantize(&rf[k], x, 0, rows, K, K, 0, pc, ps, pm) != 0) return 4;
+            for (int t = 0; t < 2; ++t) {
+                const int64_t M = Ms[t];
+                if (mx_operand_bytes(&fm[k], M, K, kinds[k]) == 0 || mx_operand_bytes(&fm[k], M, K, kinds[k]) > (size_t)192 * K * 2)
+                    return 7;
+                CHECK_BDR(bdr_quantize_operand(&fm[k], dx, BDR_F32, M, K, K, BDR_AXIS_ROW, kinds[k], 0, ia, NULL));
+                CHECK_BDR(bdr_quantize_operand(&fm[k], dx, BDR_F32, N, K, K, BDR_AXIS_ROW, kinds[k], 1, ib, NULL));
+                CHECK_BDR(mx_gemm_operands(&fm[k], &fm[k], ia, ib, kinds[k], M, N, K, dc, BDR_F32, N, NULL));
+                CHECK_HIP(hipDeviceSynchronize());
+                CHECK_HIP(hipMemcpy(c, dc, sizeof(float) * M * N, hipMemcpyDeviceToHost));
+                for (int64_t e = 0; e < M * N; ++e) {
+                    ii[e] = e / N;
+                    jj[e] = e % N;
+                }
+                /* rows of A and of B are rows of the same planes (blocks along K) */
+                if (bdr_ref_mx_gemm_sampled(&rf[k], &rf[k], pc, ps, pm, pc, ps, pm, rows, rows, K, M * N, ii, jj, want, absdot) != 0)
+                    return 4;
+                for (int64_t e = 0; e < M * N; ++e)
+                    if (!(fabs((double)c[e] - (double)want[e]) <= 1e-4 * absdot[e] + 1e-30)) {
+                        fprintf(stderr, "product, format %d, M %ld, entry %ld: %.9g against %.9g\n", k, (long)M, (long)e,
+                                (double)c[e], (double)want[e]);
+                        return 8;
+                    }
+            }
+            free(pc); free(ps); free(pm);
+        }
+    }
+    printf("ok: %d formats, both axes, a ragged shape, the sweep (MX9 %.3f dB, MX6 %.3f dB, MX4 %.3f dB), products on "
+           "operand images of every kind\n", nf, q[0], q[1], q[2]);
     return 0;
 }
