@@ -242,8 +242,9 @@ size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
  *            is touched.  Every product is exact in all forms; the forms differ only
  *            in where the FP32 sum over K is rounded (for M > 64 the BF16 forms give
  *            the same bits as each other).  With M <= 64 the two-pass form does not
- *            tile: it streams once over B's rewritten image, so such a call (a
- *            decoding step) costs about the time the bytes of that image take; the
+ *            tile: it streams once over B's rewritten image (over B's planes
+ *            themselves, expanded in registers, when the product is the BF16 one), so
+ *            such a call (a decoding step) costs about the time those bytes take; the
  *            sum over K is then added in another, equally fixed, order.
  * K must be a multiple of 64 and M, N, K at most 2^20 each, else BDR_ERR_SHAPE; M and N
  * are free (tiles that hang over the edge of C cost as much as full ones: multiples of 256,

@@ -396,6 +396,13 @@ int mx_gemm_to(const bdr_format *fa, const bdr_format *fb, const void *a_codes, 
             if (st) return st;
             return bdr::gemm_fp6(wa, wb, M, N, K, C, ldc, c_bf16, false, s);
         }
+        if (both_mx && bdr::gemm_bf16_planes_ok(M, K)) {
+            // few rows of A (a decoding step): only A is expanded; B is streamed once as it is
+            // stored and expanded in registers
+            st = bdr::to_bf16_tiled(*fa, a_codes, a_sexp, a_mexp, M, K, wa, s);
+            if (st) return st;
+            return bdr::gemm_bf16_planes(wa, *fb, b_codes, b_sexp, b_mexp, M, N, K, C, ldc, c_bf16, s);
+        }
         if (both_mx) {
             // MX9 has 8 significant bits with the sign: each operand is expanded to BF16 (exact),
             // in the K-tiled layout of the ring kernel

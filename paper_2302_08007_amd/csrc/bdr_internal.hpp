@@ -118,6 +118,10 @@ int quantize_operand_col(const bdr_format &f, const void *x, int dtype, int64_t 
                          void *out, int kind, hipStream_t s);
 // The FP4 form of the two-pass product (MX4 x MX4): image writer, size of its scale image,
 // and the product on two such images (K_out % 128 == 0).
+bool gemm_bf16_planes_ok(int64_t M, int64_t K);
+int gemm_bf16_planes(const void *A, const bdr_format &fb, const void *b_codes, const void *b_sexp,
+                     const void *b_mexp, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
+                     hipStream_t s);
 int to_fp4(const void *codes, const void *sexp, const void *mexp, int64_t rows, int64_t K, int64_t K_out,
            void *out, void *scales, hipStream_t s);
 size_t fp4_scale_bytes(int64_t rows, int64_t K_out);

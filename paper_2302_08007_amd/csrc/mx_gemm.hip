@@ -1124,6 +1124,102 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
     }
 }
 
+// The same stream when the BF16 product is the one to take (MX9 takes part) and A has few rows: B is
+// not rewritten as a BF16 image (2 bytes per element) but read as it is stored, in its three
+// planes (9, 6 or 4 bits per element), and expanded to BF16 in registers on the way into the MFMA.
+// A is the K-tiled BF16 image of its few rows.  Within 64 elements of K the lower half wave takes
+// the first 32 and the upper one the last 32 (four sub-steps of 8 each): a lane's share is the two
+// blocks load_packed brings, and one K step of A's image (64 bytes).
+template <int MBB, int TM>
+__global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_planes_kernel(
+    const uint8_t *__restrict__ A, const uint8_t *__restrict__ b_codes, const uint8_t *__restrict__ b_sexp,
+    const uint8_t *__restrict__ b_mexp, int M, int N, int nq, void *__restrict__ C, int64_t ldc, int c_bf16)
+{
+    __shared__ float s_red[kSkinnyWaves][16][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n0 = blockIdx.x * kSkinnyRows;
+    const int f_row = lane & 31, f_half = lane >> 5;
+    // rows past the edge of an operand repeat its last row (their products are never stored)
+    const int rb = min(n0 + f_row, N - 1);
+    const int64_t b_blk0 = (int64_t)rb * (4 * (int64_t)nq) + 2 * f_half;  // first of the lane's block pairs
+    const int64_t a_step = (int64_t)M * kRingRow;                         // one K step (32 elements) of A's image
+    int a_at[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a_at[i] = min(32 * i + f_row, M - 1) * kRingRow;
+    f32x16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    constexpr int kAhead = 4;
+    Packed<MBB> pb[kAhead];
+    i32x4 fa[kAhead][TM][4];
+    for (int q = wave; q < nq; q += kSkinnyWaves * kAhead) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int qq = q + u * kSkinnyWaves;
+            if (qq < nq) {
+                load_packed<MBB>(b_codes, b_sexp, b_mexp, b_blk0 + 4 * (int64_t)qq, pb[u]);
+                const uint8_t *ap = A + (2 * (int64_t)qq + f_half) * a_step;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) fa[u][i][c] = *reinterpret_cast<const i32x4 *>(ap + a_at[i] + 16 * c);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            if (q + u * kSkinnyWaves < nq) {
+                uint32_t w[16];
+                unpack32<MBB>(pb[u], w);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const i32x4 fb = {(int)w[4 * c], (int)w[4 * c + 1], (int)w[4 * c + 2], (int)w[4 * c + 3]};
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[u][i][c]),
+                                                                         __builtin_bit_cast(bf16x8, fb), acc[i], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4 of its tile of A, column l % 32
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        if (i > 0) __syncthreads();  // the sums of the tile before have been read
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_red[wave][r][lane] = acc[i][r];
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16 * 64 / (64 * kSkinnyWaves); ++k) {
+            const int e = k * (64 * kSkinnyWaves) + threadIdx.x, r = e >> 6, l = e & 63;
+            float v = s_red[0][r][l];
+#pragma unroll
+            for (int w = 1; w < kSkinnyWaves; ++w) v += s_red[w][r][l];
+            const int m = 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), n = n0 + (l & 31);
+            if (m < M && n < N) {
+                if (c_bf16)
+                    static_cast<uint16_t *>(C)[(int64_t)m * ldc + n] = bf16_rne(v);
+                else
+                    static_cast<float *>(C)[(int64_t)m * ldc + n] = v;
+            }
+        }
+    }
+}
+
+template <int MBB>
+int launch_skinny_planes(const uint8_t *a, const uint8_t *bc, const uint8_t *bs, const uint8_t *bm, int M, int N,
+                         int nq, void *C, int64_t ldc, int c_bf16, hipStream_t s)
+{
+    const dim3 grid((unsigned)((N + kSkinnyRows - 1) / kSkinnyRows)), block(64 * kSkinnyWaves);
+    if (M <= 32)
+        hipLaunchKernelGGL((gemm_skinny_planes_kernel<MBB, 1>), grid, block, 0, s, a, bc, bs, bm, M, N, nq, C, ldc, c_bf16);
+    else
+        hipLaunchKernelGGL((gemm_skinny_planes_kernel<MBB, 2>), grid, block, 0, s, a, bc, bs, bm, M, N, nq, C, ldc, c_bf16);
+    return launch_status();
+}
+
 template <int FMT>
 int launch_skinny(const uint8_t *a, const uint8_t *b, const uint8_t *sa, const uint8_t *sb, int M, int N, int nk,
                   void *C, int64_t ldc, int c_bf16, hipStream_t s)
@@ -1271,6 +1367,23 @@ int gemm_bf16_tiled(const void *A, const void *B, int64_t M, int64_t N, int64_t 
                     bool dry, hipStream_t s)
 {
     return gemm_ring<kFmtBf16>(A, B, nullptr, nullptr, M, N, (int)(K / 32), C, ldc, c_bf16, dry, s);
+}
+
+// Whether gemm_bf16_planes takes a product of these sizes (few rows of A).
+bool gemm_bf16_planes_ok(int64_t M, int64_t K) { return M >= 1 && M <= kSkinnyMaxM && K % 64 == 0; }
+
+// C = A * B^T for the K-tiled BF16 image of A [M x K] (to_bf16_tiled) and the packed planes of B
+// [N x K] in a Table II format; gemm_bf16_planes_ok(M, K).
+int gemm_bf16_planes(const void *A, const bdr_format &fb, const void *b_codes, const void *b_sexp,
+                     const void *b_mexp, int64_t M, int64_t N, int64_t K, void *C, int64_t ldc, int c_bf16,
+                     hipStream_t s)
+{
+    const uint8_t *a = (const uint8_t *)A, *bc = (const uint8_t *)b_codes, *bs = (const uint8_t *)b_sexp,
+                  *bm = (const uint8_t *)b_mexp;
+    const int nq = (int)(K / 64);
+    if (fb.m == 7) return launch_skinny_planes<7>(a, bc, bs, bm, (int)M, (int)N, nq, C, ldc, c_bf16, s);
+    if (fb.m == 4) return launch_skinny_planes<4>(a, bc, bs, bm, (int)M, (int)N, nq, C, ldc, c_bf16, s);
+    return launch_skinny_planes<2>(a, bc, bs, bm, (int)M, (int)N, nq, C, ldc, c_bf16, s);
 }
 
 // Packed Table II planes of a [rows x K] operand (K % 32 == 0) -> BF16, tiled along K.

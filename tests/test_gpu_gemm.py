@@ -671,7 +671,8 @@ def test_fp4_operands_of_the_transpose(shape, dtype):
             assert torch.equal(B.bdr_quantize_operand(f, x, axis=B.AXIS_COL, image=B.OPERAND_FP4, b_operand=b_operand), ia)
 
 
-@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX4", "MX6"), ("MX9", "MX9"), ("MX9", "MX4"), ("MX4", "MX4")])
+@pytest.mark.parametrize("names", [("MX6", "MX6"), ("MX4", "MX6"), ("MX9", "MX9"), ("MX9", "MX4"), ("MX4", "MX4"),
+                                   ("MX9", "MX6"), ("MX6", "MX9")])
 @pytest.mark.parametrize("shape", [(1, 32, 64), (5, 100, 128), (16, 384, 1024), (32, 257, 2048), (31, 64, 4096 + 128),
                                    (33, 96, 256), (64, 130, 1152), (100, 320, 512), (128, 257, 2048)])
 def test_few_rows_of_a(shape, names):
