@@ -414,7 +414,10 @@ def test_operands_from_few_rows_and_pitched_views(shape, name, dtype):
             assert np.array_equal(p.cpu().numpy(), w)
         other = B.bdr_quantize(partner, x.contiguous())
         ia, _, _ = _two_step_images(f, partner, planes, other, rows, rows, K)
-        _, ib, _ = _two_step_images(partner, f, other, planes, rows, rows, K)
+        # (with few rows in A the two-pass BF16 form reads B from its planes and writes no image of
+        # it: the partner in the A role gets 128 rows)
+        tall = x.contiguous().repeat((127 + rows) // rows, 1)[:128].contiguous()
+        _, ib, _ = _two_step_images(partner, f, B.bdr_quantize(partner, tall), planes, 128, rows, K)
         assert torch.equal(B.bdr_quantize_operand(f, x, image=image, b_operand=False), ia)
         assert torch.equal(B.bdr_quantize_operand(f, x, image=image, b_operand=True), ib)
 
