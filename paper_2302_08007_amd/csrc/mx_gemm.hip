@@ -989,20 +989,22 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_ring_kernel(
 
 // The product for few rows of A (M <= 64: a decoding step, a handful of tokens against a weight
 // matrix): one or two MFMA tiles hold all of A's rows, so there is nothing to reuse from LDS and the
-// call is a stream over B's image.  A workgroup takes 32 rows of B and all of K; its eight waves
-// take K steps in turn (wave w the steps w, w + 8, ...), each lane loading its fragments straight
+// call is a stream over B's image.  A workgroup takes 32 rows of B and all of K; its four waves
+// take K steps in turn (wave w the steps w, w + 4, ...), each lane loading its fragments straight
 // from the images in the MFMA's own layout (fragment = chunk 2 s + lane / 32 of row lane % 32; FP4:
 // see below), so that the waves of a workgroup read B's image as 2 KiB runs.
 // Plain loads: a row's 64 bytes arrive as two 32-byte halves in consecutive instructions, and the
 // second must find the line the first brought (with the streaming hint the same stream takes 40 %
-// longer).  The eight partial tiles are added in LDS in a fixed order (the result does not depend
+// longer).  The four partial tiles are added in LDS in a fixed order (the result does not depend
 // on timing).  Same images, same scale-byte conventions and the same idle-half trick as
-// gemm_ring_kernel.  Measured, N = K = 12288, ten launches back to back: MX6 25-28 us for M = 1
-// .. 32 (5.4-6.0 TB/s of B's image) and 36-39 us for M = 33 .. 64, MX4 (FP4 images) 18-20 and
-// 27-30 us, MX9 (BF16 images) 52-68 and 75-100 us; the tiled kernel takes 57 / 57 / 112 us for
-// the same calls.  Every workgroup reads all of A again (from L2), which is what M costs; with
+// gemm_ring_kernel.  Measured, N = K = 12288, ten launches back to back: MX6 23-27 us for M = 1
+// .. 32 (5.6-6.5 TB/s of B's image) and 37 us for M = 64, MX4 (FP4 images) 16-18 and 27 us, MX9
+// (BF16 images) 48-66 and 92 us; the tiled kernel takes 57 / 57 / 112 us for the same calls.
+// Waves per workgroup x K steps a wave loads ahead, same order of figures for MX6 M = 1 / MX4 M = 1
+// / MX9 M = 64: 4 x 2 23.1 / 16.2 / 92, 4 x 4 24.5 / 18.3 / 100, 8 x 2 25.7 / 17.3 / 97, 8 x 4 25.5
+// / 17.5 / 100, 16 x 2 25.8 / 18.3 / 99, deeper or wider than that much worse (registers).  Every workgroup reads all of A again (from L2), which is what M costs; with
 // four tiles (M <= 128) the tiled kernel is the faster one (48 against 55-62 us for MX6).
-constexpr int kSkinnyWaves = 8, kSkinnyRows = 32, kSkinnyMaxM = 64;
+constexpr int kSkinnyWaves = 4, kSkinnyRows = 32, kSkinnyMaxM = 64;
 
 template <int FMT, int TM>
 __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
@@ -1041,10 +1043,10 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_kernel(
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    // kAhead K steps of a wave are loaded before the first of them is multiplied: the bytes a wave
-    // has in flight, not its instruction count, set the rate of a stream.  What is loaded is kept
-    // as it comes; the MFMA operand is put together at the multiply.
-    constexpr int kAhead = 4;
+    // kAhead K steps of a wave are loaded before the first of them is multiplied (enough, with the
+    // waves a CU holds, for the bytes in flight a stream needs).  What is loaded is kept as it
+    // comes; the MFMA operand is put together at the multiply.
+    constexpr int kAhead = 2;
     i32x4 fa[kAhead][TM][2], fb[kAhead][2];
     i32x2 sa[kAhead][TM], sb[kAhead];
     auto load = [&](int q, i32x4 (&xa)[TM][2], i32x4 (&xb)[2], i32x2 (&xsa)[TM], i32x2 &xsb) {
@@ -1152,7 +1154,7 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_planes_kernel(
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    constexpr int kAhead = 4;
+    constexpr int kAhead = 2;
     Packed<MBB> pb[kAhead];
     i32x4 fa[kAhead][TM][4];
     for (int q = wave; q < nq; q += kSkinnyWaves * kAhead) {
