@@ -255,6 +255,17 @@ constexpr int deq_iter()
 {
     return MB == 7 && sizeof(T) == 4 ? 1 : 2;
 }
+// A gather takes one group per lane: its loads are scattered rows, not a stream, and more of them
+// per lane gain nothing (2^27 FP32 values from an MX6 / MX9 / MX4 table image of 128-wide rows: one
+// group 106 / 116 / 92 us, two 108 / 118 / 98, four 109 / 119 / 99).
+template <int MB, typename T>
+constexpr int gather_iter() { return 1; }
+template <int MB, typename T>
+static inline dim3 gather_grid(int64_t n_groups)
+{
+    constexpr int64_t per = (int64_t)kDeqThreads * gather_iter<MB, T>();
+    return dim3((unsigned)((n_groups + per - 1) / per));
+}
 template <int MB, typename T>
 static inline dim3 deq_grid(int64_t n_groups)
 {
@@ -295,7 +306,7 @@ __global__ __launch_bounds__(kDeqThreads) void mx_dequantize_row_kernel(
     constexpr bool kStage = sizeof(T) == 4;  // FP32 rows leave through LDS, see wave_store512
     __shared__ float s_stage[kStage ? kDeqThreads / 64 : 1][kStage ? kWaveStage : 1];
     constexpr int kStep = kDeqThreads;  // distance between a lane's groups
-    constexpr int kDeqIter = deq_iter<MB, T>();
+    constexpr int kDeqIter = GATHER ? gather_iter<MB, T>() : deq_iter<MB, T>();
     const int64_t g0 = (int64_t)blockIdx.x * (kDeqThreads * kDeqIter) + threadIdx.x;
     const uint32_t i = threadIdx.x & 3u;
 
@@ -1047,11 +1058,11 @@ static int table_gather_t(const bdr_format &f, const uint8_t *table, int64_t tab
     const int32_t codes_row = (int32_t)(cols / 8 * (f.m + 1)), e_row = (int32_t)(cols / 16);
     const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0, codes_row + 2 * e_row, codes_row, e_row};
     if (f.m == 7)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true, false, 4, 1, 1, true>), (deq_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true, false, 4, 1, 1, true>), (gather_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
     else if (f.m == 4)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true, false, 4, 1, 1, true>), (deq_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true, false, 4, 1, 1, true>), (gather_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
     else
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true, false, 4, 1, 1, true>), (deq_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true, false, 4, 1, 1, true>), (gather_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, table, table, table, y, ng, ga);
     return launch_status();
 }
 
@@ -1071,11 +1082,11 @@ static int gather_row_t(const bdr_format &f, const uint8_t *codes, const uint8_t
     const int64_t ng = n_idx * cols / 8;
     const GatherArgs ga = {idx, table_rows, (int32_t)(cols / 8), 0, 0, 0, 0};
     if (f.m == 7)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), (deq_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<7, T, true>), (gather_grid<7, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     else if (f.m == 4)
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true>), (deq_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<4, T, true>), (gather_grid<4, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     else
-        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true>), (deq_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
+        hipLaunchKernelGGL((mx_dequantize_row_kernel<2, T, true>), (gather_grid<2, T>(ng)), dim3(kDeqThreads), 0, s, codes, sexp, mexp, y, ng, ga);
     return launch_status();
 }
 
