@@ -47,7 +47,9 @@ namespace {
 
 constexpr int kSweepThreads = 256;
 constexpr int kG = 2;  // groups of 8 elements per lane per iteration
-constexpr int kSweepBlocks = 768;  // three resident workgroups per compute unit
+// Three resident workgroups per compute unit (64 formats x 2^24 values: 512 workgroups 0.099 ms, 768
+// 0.086, 1024 0.096, 1536 0.088).
+constexpr int kSweepBlocks = 768;
 
 constexpr int kChunk = 128;  // formats per launch: bounds kernel arguments (< 4 KiB) and LDS
 constexpr int kMaxGroups = kChunk;
