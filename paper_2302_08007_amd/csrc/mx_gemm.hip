@@ -131,6 +131,33 @@ __device__ __forceinline__ void unpack32(const Packed<MB> &p, uint32_t (&out)[16
     }
 }
 
+// The same for MX9 with fewer instructions (its codes are whole bytes): the magnitudes of four
+// codes are converted by the byte-to-float instructions (the compiler's choice for these casts), scaled by a multiplication (exact:
+// a power of two times at most 7 significant bits, subnormal results included), and the signs of a
+// pair are moved from the code bytes into the packed BF16 pair by one byte permute and one and-or.
+__device__ __forceinline__ void unpack32_mx9(const Packed<7> &p, uint32_t (&out)[16])
+{
+    float sc[2][2];  // 2^(se - 127 - 6 - tau) for tau = 0, 1 of each block
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int q = (int)((p.se2 >> (8 * b)) & 0xffu) - (127 + 6);
+        sc[b][0] = __builtin_ldexpf(1.0f, q);
+        sc[b][1] = __builtin_ldexpf(1.0f, q - 1);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {  // dword k: codes of elements 4k .. 4k+3 = pairs 2k, 2k+1
+        const uint32_t c = p.c[k], m = c & 0x7f7f7f7fu;
+        const float s0 = ((p.tau16 >> (2 * k)) & 1u) ? sc[k >> 2][1] : sc[k >> 2][0];
+        const float s1 = ((p.tau16 >> (2 * k + 1)) & 1u) ? sc[k >> 2][1] : sc[k >> 2][0];
+        const uint32_t f0 = as_u((float)(m & 0xffu) * s0), f1 = as_u((float)((m >> 8) & 0xffu) * s0);
+        const uint32_t f2 = as_u((float)((m >> 16) & 0xffu) * s1), f3 = as_u((float)(m >> 24) * s1);
+        // BF16 pair = the two high halves; signs: code byte 0 -> byte 1 of the pair, code byte 1 -> byte 3
+        const uint32_t lo = __builtin_amdgcn_perm(f1, f0, 0x07060302u), hi = __builtin_amdgcn_perm(f3, f2, 0x07060302u);
+        out[2 * k] = (__builtin_amdgcn_perm(c, c, 0x010c000cu) & 0x80008000u) | lo;
+        out[2 * k + 1] = (__builtin_amdgcn_perm(c, c, 0x030c020cu) & 0x80008000u) | hi;
+    }
+}
+
 // ... and store them as chunks 4*half .. 4*half+3 of LDS row `row` of the operand tile at `base`.
 template <int MB>
 __device__ __forceinline__ void unpack_to_lds(const Packed<MB> &p, uint8_t *base, int row, int half)
@@ -1174,7 +1201,10 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_planes_kernel(
         for (int u = 0; u < kAhead; ++u) {
             if (q + u * kSkinnyWaves < nq) {
                 uint32_t w[16];
-                unpack32<MBB>(pb[u], w);
+                if constexpr (MBB == 7)
+                    unpack32_mx9(pb[u], w);
+                else
+                    unpack32<MBB>(pb[u], w);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const i32x4 fb = {(int)w[4 * c], (int)w[4 * c + 1], (int)w[4 * c + 2], (int)w[4 * c + 3]};
@@ -1210,11 +1240,103 @@ __global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_planes_kernel(
     }
 }
 
+// The same with tiles of 16 x 16 (MFMA 16 x 16 x 32): twice as many workgroups, each with half the
+// expansion work -- the kernel is bound by those vector instructions, and 384 workgroups of 32 rows
+// meet 256 CUs as two rounds for half of them, 768 of 16 rows as three even ones.  Lane l holds row
+// l % 16 and the K group l / 16; within 128 elements of K group g takes elements 32 g .. 32 g + 31
+// (again the two blocks load_packed brings, and one K step of A's image), eight per MFMA.  Both
+// operands give the same elements to the same lane group, which is all the instruction asks for.
+template <int MBB, int TM>
+__global__ __launch_bounds__(64 * kSkinnyWaves) void gemm_skinny_planes16_kernel(
+    const uint8_t *__restrict__ A, const uint8_t *__restrict__ b_codes, const uint8_t *__restrict__ b_sexp,
+    const uint8_t *__restrict__ b_mexp, int M, int N, int nq, void *__restrict__ C, int64_t ldc, int c_bf16)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    __shared__ float s_red[kSkinnyWaves][TM][4][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n0 = blockIdx.x * 16;
+    const int f_row = lane & 15, f_grp = lane >> 4;
+    const int rb = min(n0 + f_row, N - 1);
+    const int64_t b_blk0 = (int64_t)rb * (8 * (int64_t)nq) + 2 * f_grp;  // K / 16 = 8 nq blocks per row
+    const int64_t a_step = (int64_t)M * kRingRow;
+    int a_at[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a_at[i] = min(16 * i + f_row, M - 1) * kRingRow;
+    f32x4 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int kAhead = 2;
+    Packed<MBB> pb[kAhead];
+    i32x4 fa[kAhead][TM][4];
+    for (int q = wave; q < nq; q += kSkinnyWaves * kAhead) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int qq = q + u * kSkinnyWaves;
+            if (qq < nq) {
+                load_packed<MBB>(b_codes, b_sexp, b_mexp, b_blk0 + 8 * (int64_t)qq, pb[u]);
+                const uint8_t *ap = A + (4 * (int64_t)qq + f_grp) * a_step;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) fa[u][i][c] = *reinterpret_cast<const i32x4 *>(ap + a_at[i] + 16 * c);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            if (q + u * kSkinnyWaves < nq) {
+                uint32_t w[16];
+                if constexpr (MBB == 7)
+                    unpack32_mx9(pb[u], w);
+                else
+                    unpack32<MBB>(pb[u], w);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const i32x4 fb = {(int)w[4 * c], (int)w[4 * c + 1], (int)w[4 * c + 2], (int)w[4 * c + 3]};
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fa[u][i][c]),
+                                                                         __builtin_bit_cast(bf16x8, fb), acc[i], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // register r of lane l is row 4 (l / 16) + r of its tile of A, column l % 16
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s_red[wave][i][r][lane] = acc[i][r];
+    __syncthreads();
+    for (int e = threadIdx.x; e < TM * 4 * 64; e += 64 * kSkinnyWaves) {
+        const int i = e >> 8, r = (e >> 6) & 3, l = e & 63;
+        float v = s_red[0][i][r][l];
+#pragma unroll
+        for (int w = 1; w < kSkinnyWaves; ++w) v += s_red[w][i][r][l];
+        const int m = 16 * i + 4 * (l >> 4) + r, n = n0 + (l & 15);
+        if (m < M && n < N) {
+            if (c_bf16)
+                static_cast<uint16_t *>(C)[(int64_t)m * ldc + n] = bf16_rne(v);
+            else
+                static_cast<float *>(C)[(int64_t)m * ldc + n] = v;
+        }
+    }
+}
+
 template <int MBB>
 int launch_skinny_planes(const uint8_t *a, const uint8_t *bc, const uint8_t *bs, const uint8_t *bm, int M, int N,
                          int nq, void *C, int64_t ldc, int c_bf16, hipStream_t s)
 {
     const dim3 grid((unsigned)((N + kSkinnyRows - 1) / kSkinnyRows)), block(64 * kSkinnyWaves);
+    // N = K = 12288, MX9 planes, A's expansion included: 16-row tiles 51 / 55 / 73 / 112 us for M = 1 /
+    // 16 / 32 / 64, 32-row tiles 65 / 69 / 75 / 102 us
+    if (nq % 2 == 0 && M <= 32) {  // K a multiple of 128
+        const dim3 g16((unsigned)((N + 15) / 16));
+        if (M <= 16)
+            hipLaunchKernelGGL((gemm_skinny_planes16_kernel<MBB, 1>), g16, block, 0, s, a, bc, bs, bm, M, N, nq / 2, C, ldc, c_bf16);
+        else
+            hipLaunchKernelGGL((gemm_skinny_planes16_kernel<MBB, 2>), g16, block, 0, s, a, bc, bs, bm, M, N, nq / 2, C, ldc, c_bf16);
+        return launch_status();
+    }
     if (M <= 32)
         hipLaunchKernelGGL((gemm_skinny_planes_kernel<MBB, 1>), grid, block, 0, s, a, bc, bs, bm, M, N, nq, C, ldc, c_bf16);
     else
