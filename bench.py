@@ -737,6 +737,19 @@ def other_legs(B, S, torch, timed):
                 leg["act_%s_weight_%s" % (an, wn)] = {"us": round(t * 1e3, 1), "weight_image_MB": round(img_bytes / 1e6, 1),
                                                       "weight_image_GBps": round(img_bytes / t / 1e6, 1)}
                 del wq
+            # MX9 weights kept as they are stored (three planes, 9 bits per element): the step quantizes
+            # the tokens to planes and mx_gemm streams the weight planes, expanding them in registers
+            wp = B.bdr_quantize(B.MX9, w.detach())
+            gws = torch.empty(B.mx_gemm_workspace_bytes(16, Osz, I), dtype=torch.uint8, device="cuda")
+            c16 = torch.empty(16, Osz, device="cuda", dtype=torch.bfloat16)
+
+            def from_planes():
+                B.mx_gemm(B.MX9, B.MX9, B.bdr_quantize(B.MX9, x16), wp, 16, Osz, I, out=c16, workspace=gws)
+            t = timed(from_planes, reps=7, inner=10, warm=20)
+            pbytes = sum(p.numel() for p in wp)
+            leg["act_MX9_weight_MX9_from_planes"] = {"us": round(t * 1e3, 1), "weight_planes_MB": round(pbytes / 1e6, 1),
+                                                     "weight_planes_GBps": round(pbytes / t / 1e6, 1)}
+            del wp, gws, c16
             wd = w.detach()
             t = timed(lambda: torch.matmul(x16, wd.t(), out=y16), reps=7, inner=10, warm=20)
             leg["library_bf16_gemm_for_context"] = {"us": round(t * 1e3, 1), "weight_MB": round(wd.numel() * 2 / 1e6, 1)}
