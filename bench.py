@@ -340,6 +340,9 @@ def aux_probe(B, S, torch):
     aimg6 = B.bdr_quantize_operand(B.MX6, a16, image=B.OPERAND_FP6)
     aimg4 = B.bdr_quantize_operand(B.MX4, a16, image=B.OPERAND_FP4)
     c16 = torch.empty(16, 8192, device="cuda")
+    wpl9 = B.bdr_quantize(B.MX9, wsrc)                     # the same weight as MX9 planes
+    apl9 = B.bdr_quantize(B.MX9, a16)
+    gws9 = torch.empty(B.mx_gemm_workspace_bytes(16, 8192, 8192), dtype=torch.uint8, device="cuda")
     xc = x.view(-1)[:8192 * 8192].view(8192, 8192)   # a square slice for the column-wise general kernel
     yc = y.view(-1)[:8192 * 8192].view(8192, 8192)
     pc = B.alloc_planes(fh, 8192, 8192, B.AXIS_COL)
@@ -360,6 +363,7 @@ def aux_probe(B, S, torch):
         B.bdr_quantize_operand(B.MX4, xa, axis=B.AXIS_COL, image=B.OPERAND_FP4, out=img4t)
         B.mx_gemm_operands(B.MX6, B.MX6, aimg6, wimg6, 16, 8192, 8192, image=B.OPERAND_FP6, out=c16)
         B.mx_gemm_operands(B.MX4, B.MX4, aimg4, wimg4, 16, 8192, 8192, image=B.OPERAND_FP4, out=c16)
+        B.mx_gemm(B.MX9, B.MX9, apl9, wpl9, 16, 8192, 8192, out=c16, workspace=gws9)   # B streamed from its planes
         B.bdr_quantize(fh, x, out=ph)
         B.bdr_dequantize(fh, ph, rows, cols, out=y)
         B.bdr_quantize(fr, x, out=pr)
@@ -369,7 +373,7 @@ def aux_probe(B, S, torch):
     torch.cuda.synchronize()
     print(json.dumps({"aux_probe": "3 x (1 GiB copy; MX9 bf16 8192x12288 column quantize, dequantize, fused, "
                                    "row quantize, dequantize; MX6 gather 2^20 x 128 from planes and from the table image; the same "
-                                   "bf16 tensor to the MX6 (FP6), MX9 (BF16) and MX4 (FP4) operand images, row and column blocks; the product of 16 rows with an 8192 x 8192 MX6 (FP6) and MX4 (FP4) image; k1 32 k2 2 d2 1 m 4 and "
+                                   "bf16 tensor to the MX6 (FP6), MX9 (BF16) and MX4 (FP4) operand images, row and column blocks; the product of 16 rows with an 8192 x 8192 MX6 (FP6) and MX4 (FP4) image and with MX9 planes; k1 32 k2 2 d2 1 m 4 and "
                                    "k1 32 k2 4 d2 2 m 4 quantize, dequantize on 1 GiB fp32; k1 32 k2 2 d2 1 m 4 "
                                    "column quantize, dequantize on 8192 x 8192 fp32)"}))
 
